@@ -1,0 +1,159 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused rotation-convolution hot path on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch of synthetic input that is
+already resident in HBM: rotconv_pool_fwd, rotconv_pool_bwd_data, rotconv_pool_bwd_weight
+(tap tables are built once per plan, outside the step; the filter-bank expansion and the
+weight-gradient reduction kernels run inside it).  Workload: benchmark configuration 2
+(N=8, 64->64 channels, 256x256, 3x3, R=4 exact quarter turns, fp32, orientation max-pool).
+
+Prints ONE JSON line.  `value` is algorithmic TFLOP/s: per pass
+F_alg = 2*P*Cin*Cout*k^2*Q + P*Cout*k^2*R  (Q = distinct first-quadrant angles; the per-tap
+channel contraction is shared by the four symmetric rotations, paper Eq. 8), three passes
+per step.  The dense-equivalent figure (R separate convolutions) is given beside it in
+`config` for context only.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_FP32_TFLOPS = 157.3  # MI355X fp32 matrix (and vector) peak
+PEAK_HBM_GBS = 8000.0
+
+
+def flops_alg(cfg, Q):
+    P = cfg.N * cfg.Ho * cfg.Wo
+    return 2.0 * P * cfg.Cin * cfg.Cout * cfg.k * cfg.k * Q + 1.0 * P * cfg.Cout * cfg.k * cfg.k * cfg.R
+
+
+def flops_dense(cfg):
+    P = cfg.N * cfg.Ho * cfg.Wo
+    return 2.0 * P * cfg.Cin * cfg.Cout * cfg.k * cfg.k * cfg.R
+
+
+def cpu_baseline(cfg, Q):
+    """The oracle as it stands, timed on the host cores on a bounded sample (a batch slice)."""
+    import dataclasses
+    import numpy as np
+    from oracle import rotconv_oracle as orc
+    from paper_2512_08888_amd import synth
+
+    # about 10-30 s of CPU work: keep dense flops of the sample near 2e10 per pass
+    n_s = max(1, min(cfg.N, int(2.0e10 / (flops_dense(cfg) / cfg.N))))
+    h_s = cfg.H
+    if n_s == 1 and flops_dense(cfg) / cfg.N > 4.0e10:
+        h_s = max(cfg.k, int(cfg.H * 4.0e10 / (flops_dense(cfg) / cfg.N)))
+    sc = dataclasses.replace(cfg, N=n_s, H=h_s)
+    x, w, g = synth.make_x(sc), synth.make_w(sc), synth.make_g(sc)
+    ang = None if sc.angles_deg is None else list(sc.angles_deg)
+    t0 = time.perf_counter()
+    _, _, idx, _ = orc.layer_fwd(x, w, sc.R, ang, sc.mode, sc.stride, sc.pad, sc.G)
+    orc.layer_bwd(x, w, g, idx, sc.R, ang, sc.mode, sc.stride, sc.pad, sc.G)
+    dt = time.perf_counter() - t0
+    cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    return {
+        "value": 3.0 * flops_alg(sc, Q) / dt / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+        "sample": f"{sc.name} slice N={sc.N} H={sc.H} W={sc.W} (of N={cfg.N} H={cfg.H}), fwd+bwd_data+bwd_weight, "
+                  f"fp64 dense definition, {dt:.2f} s",
+        "seconds": dt,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (the path shards over the batch; "
+              "see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2512_08888_amd import binding as rc
+    from paper_2512_08888_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    cfg = synth.CONFIGS[args.workload]
+    plan = rc.Plan.from_config(cfg)
+    Q = plan.orientations()[0]
+    x = torch.from_numpy(synth.make_x(cfg)).cuda()
+    w = torch.from_numpy(synth.make_w(cfg)).cuda()
+    g = torch.from_numpy(synth.make_g(cfg)).cuda()
+    yp = torch.empty((cfg.N, plan.Cpooled, plan.Ho, plan.Wo), device="cuda")
+    idx = torch.empty((cfg.N, plan.Cpooled, plan.Ho, plan.Wo), dtype=torch.uint8, device="cuda")
+    dx = torch.empty_like(x)
+    dw = torch.empty_like(w)
+    plan.workspace()
+
+    def step(ev=None):
+        if ev:
+            ev[0].record()
+        rc.rotconv_pool_fwd(plan, x, w, yp, idx)
+        if ev:
+            ev[1].record()
+        rc.rotconv_pool_bwd_data(plan, g, idx, w, dx)
+        if ev:
+            ev[2].record()
+        rc.rotconv_pool_bwd_weight(plan, x, g, idx, dw)
+        if ev:
+            ev[3].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    # library calls are enqueued on torch's current stream, so torch events bracket them
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        step(events[s])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_step = (t1 - t0) * 1e3 / args.steps
+    pass_ms = [sum(events[s][i].elapsed_time(events[s][i + 1]) for s in range(args.steps)) / args.steps
+               for i in range(3)]
+    names = ["rotconv_pool_fwd", "rotconv_pool_bwd_data", "rotconv_pool_bwd_weight"]
+    fa, fd = flops_alg(cfg, Q), flops_dense(cfg)
+    dom = max(range(3), key=lambda i: pass_ms[i])
+    achieved = fa / (pass_ms[dom] * 1e-3) / 1e12
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(f"{args.workload}:{names[dom]}:{plan.kernel_name(dom)}")
+        except Exception:
+            traffic = None
+    out = {
+        "metric": "rotconv_fwd_bwd_tflops", "value": 3.0 * fa / (ms_step * 1e-3) / 1e12, "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {
+            "workload": f"{cfg.name}: N={cfg.N} Cin={cfg.Cin} Cout={cfg.Cout} {cfg.H}x{cfg.W} k={cfg.k} R={cfg.R} "
+                        f"{cfg.mode} G={cfg.G} stride={cfg.stride} pad={cfg.pad}, fused fwd+bwd_data+bwd_weight",
+            "flops_per_pass_algorithmic": fa, "flops_per_pass_dense_equivalent": fd,
+            "dense_equivalent_tflops": 3.0 * fd / (ms_step * 1e-3) / 1e12,
+            "pass_ms": dict(zip(names, pass_ms)),
+            "pass_tflops_algorithmic": {n: fa / (t * 1e-3) / 1e12 for n, t in zip(names, pass_ms)},
+            "kernels": {n: plan.kernel_name(i) for i, n in enumerate(names)},
+        },
+        "roofline": {
+            "bound": "mfma", "kernel": f"{names[dom]} ({plan.kernel_name(dom)})", "achieved": achieved,
+            "peak": PEAK_FP32_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_TFLOPS, "traffic": traffic,
+        },
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, Q)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

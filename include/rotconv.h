@@ -1,0 +1,148 @@
+/*
+ * rotconv.h - C ABI of the MI355X (gfx950) multi-orientation convolution library.
+ *
+ * One base filter bank is expanded to R orientations; every orientation is a
+ * 2-D cross-correlation of the same input (paper Sec. III-B, Eq. 5 and 7), the
+ * R responses of a filter are max-pooled over orientation groups with the
+ * arg-max kept (Eq. 10), and the backward passes route the upstream gradient
+ * through the arg-max (Eq. 12) into the input gradient (Eq. 13, 15) and the
+ * base-weight gradient (Eq. 14, 16).  Orientations whose angles differ by
+ * multiples of 90 degrees share their per-tap channel contractions (Eq. 8);
+ * other angles get one first-quadrant filter each plus its three quarter-turn
+ * copies (Sec. III-D).
+ *
+ * Conventions common to every call
+ *   - Plain C, no C++ types, no exceptions cross this boundary.
+ *   - Pointers marked DEVICE point to memory of the current HIP device, owned by
+ *     the caller; the library never allocates, frees or keeps them.  Pointers
+ *     marked HOST are ordinary host memory.  The plan owns only its small
+ *     tables (host copies, and device copies uploaded on first use).
+ *   - All tensors are dense, contiguous, row-major, fp32 unless said otherwise:
+ *       x      [N][Cin][H][W]
+ *       w      [B][Cout][Cin][k][k]   B = 2 (f_x then f_y, Eq. 17) in STEERABLE mode, else 1
+ *       y, dy  [N][Cout*R][Ho][Wo]    channel = co*R + r
+ *       ypool, gpool [N][Cout*(R/G)][Ho][Wo]  channel = co*(R/G) + g
+ *       idx    same shape as ypool, uint8: the orientation index r (0..R-1) that won
+ *       dw     [B][Cout][Cin][k][k]   fp32
+ *     Ho = (H + 2*pad - k)/stride + 1, likewise Wo.
+ *   - Orientation r has angle theta_r (degrees, counter-clockwise when row 0 is
+ *     drawn on top).  theta_r = 90*s_r + phi_r, phi_r in [0,90): its filter is
+ *     the first-quadrant filter F_phi_r turned by s_r exact quarter turns,
+ *     rot90(A)[i][j] = A[j][k-1-i].
+ *   - Pool group g of a filter holds the orientations r with r mod (R/G) == g
+ *     (for evenly spaced angles and G = 4: the four symmetric rotations of one
+ *     first-quadrant angle, Sec. V-A).  Ties: the smallest r wins.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls
+ *     only enqueue work; nothing synchronises with the host.  Outputs are
+ *     overwritten, never accumulated into.  Same inputs give bitwise the same
+ *     outputs on every run (no floating-point atomics anywhere).
+ *   - `ws` is a DEVICE scratch buffer of at least rotconv_workspace_bytes(plan)
+ *     bytes, 256-byte aligned; its contents are undefined between calls, and
+ *     two calls sharing one ws must not overlap in time.
+ *   - Return value: a rotconv_status.  Argument errors are found on the host
+ *     before anything is launched and leave the outputs untouched.
+ */
+#ifndef ROTCONV_H
+#define ROTCONV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  ROTCONV_OK = 0,
+  ROTCONV_ERR_NULL = -1,        /* a required pointer is NULL                                  */
+  ROTCONV_ERR_SHAPE = -2,       /* a size is < 1, the output would be empty, G does not divide R */
+  ROTCONV_ERR_ANGLES = -3,      /* angles not ascending in [0,360), or not multiples of 90 in EXACT90 */
+  ROTCONV_ERR_UNSUPPORTED = -4, /* valid request this build has no kernel for                  */
+  ROTCONV_ERR_WORKSPACE = -5,   /* ws is NULL or ws_bytes too small                            */
+  ROTCONV_ERR_LAUNCH = -6       /* the HIP runtime reported an error                           */
+} rotconv_status;
+
+typedef enum { ROTCONV_F32 = 0, ROTCONV_BF16 = 1 } rotconv_dtype;
+typedef enum { ROTCONV_EXACT90 = 0, ROTCONV_STEERABLE = 1, ROTCONV_BILINEAR = 2 } rotconv_mode;
+
+/* Problem statement of Sec. III (input C_in x H x W, filters C_out x C_in x K x K),
+ * with a batch dimension, an orientation set, stride and zero padding. */
+typedef struct {
+  int32_t N, Cin, H, W;
+  int32_t Cout, k;          /* square kernels only: quarter turns need them            */
+  int32_t R;                /* number of orientations, 1..255                          */
+  const double* angles_deg; /* HOST, R strictly ascending angles in [0,360); NULL means
+                               r*360/R (evenly spaced, Sec. III-D).  Copied by plan_create. */
+  int32_t mode;             /* rotconv_mode: how first-quadrant filters are built.
+                               EXACT90: angles must be multiples of 90 (Eq. 5).
+                               STEERABLE: F_phi = sin(phi) f_x + cos(phi) f_y (Eq. 17).
+                               BILINEAR: F_phi = base filter resampled bilinearly about the
+                               tap-grid centre, zero outside the k x k support (not the
+                               paper's rule; the benchmark configurations ask for it). */
+  int32_t stride, pad;      /* stride >= 1, pad >= 0                                   */
+  int32_t pool_group;       /* G, must divide R; 0 means R (one pooled map per filter) */
+  int32_t dtype;            /* rotconv_dtype; only ROTCONV_F32 is implemented          */
+} rotconv_desc;
+
+typedef struct rotconv_plan rotconv_plan; /* opaque */
+
+/* Validates the descriptor, builds the orientation tables on the host and
+ * returns a plan.  Touches no GPU.  `*out` is set only on ROTCONV_OK. */
+int rotconv_plan_create(const rotconv_desc* desc, rotconv_plan** out);
+/* Frees the plan and its device tables (if any were uploaded). NULL is allowed. */
+int rotconv_plan_destroy(rotconv_plan* plan);
+
+/* Bytes of scratch the largest call on this plan needs (may be 0). */
+size_t rotconv_workspace_bytes(const rotconv_plan* plan);
+/* Output extents; any pointer may be NULL. Cunpooled = Cout*R, Cpooled = Cout*R/G. */
+int rotconv_out_shape(const rotconv_plan* plan, int32_t* Ho, int32_t* Wo, int32_t* Cunpooled, int32_t* Cpooled);
+
+/* Host-side views of the plan's tables (for inspection and tests; no GPU).
+ * rotconv_plan_orientations: Q = number of distinct first-quadrant angles;
+ *   bank_of_r[r] in 0..Q-1 and quarter_of_r[r] in 0..3 (HOST arrays of R ints, may be NULL).
+ * rotconv_plan_expansion: the linear map base bank(s) -> rotated banks of one
+ *   (co,ci) slice, dense, HOST array E[R][k*k][B][k*k] of floats:
+ *   W^(r)[t] = sum_{b,u} E[r][t][b][u] * w[b][u]   (Eq. 5 / Sec. III-D / Eq. 17). */
+int rotconv_plan_orientations(const rotconv_plan* plan, int32_t* Q, int32_t* bank_of_r, int32_t* quarter_of_r);
+int rotconv_plan_expansion(const rotconv_plan* plan, float* E);
+
+/* ---- the five calls of the unfused chain ------------------------------------- */
+
+/* Eq. 7: y[n,co*R+r] = W^(r) (cross-correlated with) x.  x, w, y DEVICE. */
+int rotconv_fwd(const rotconv_plan* plan, const void* x, const void* w, void* y, void* ws, size_t ws_bytes,
+                void* stream);
+/* Eq. 13 + 15: dx = sum_r (transposed correlation of dy_r with W^(r)).  dy, w, dx DEVICE. */
+int rotconv_bwd_data(const rotconv_plan* plan, const void* dy, const void* w, void* dx, void* ws, size_t ws_bytes,
+                     void* stream);
+/* Eq. 14 + 16: dw = sum_r expansion^T( correlation of x with dy_r ), summed over the batch.
+ * x, dy, dw DEVICE; dw is fp32. */
+int rotconv_bwd_weight(const rotconv_plan* plan, const void* x, const void* dy, float* dw, void* ws, size_t ws_bytes,
+                       void* stream);
+/* Eq. 10 over pool groups, with arg-max.  y, ypool, idx DEVICE. */
+int orient_maxpool_fwd(const rotconv_plan* plan, const void* y, void* ypool, uint8_t* idx, void* stream);
+/* Eq. 12: dy[n,co*R+r] = gpool[n,co*(R/G)+g] if idx == r else 0.  gpool, idx, dy DEVICE.
+ * idx values that are not members of their pool group give zeros. */
+int orient_maxpool_bwd(const rotconv_plan* plan, const void* gpool, const uint8_t* idx, void* dy, void* stream);
+
+/* ---- the fused hot path: the R-fold tensors y / dy are never materialised ------ */
+
+/* Eq. 8 + Eq. 10 in one pass: the input tile is read once and shared by all rotated copies. */
+int rotconv_pool_fwd(const rotconv_plan* plan, const void* x, const void* w, void* ypool, uint8_t* idx, void* ws,
+                     size_t ws_bytes, void* stream);
+/* Eq. 12 + Eq. 13 + Eq. 15. */
+int rotconv_pool_bwd_data(const rotconv_plan* plan, const void* gpool, const uint8_t* idx, const void* w, void* dx,
+                          void* ws, size_t ws_bytes, void* stream);
+/* Eq. 12 + Eq. 14 + Eq. 16. */
+int rotconv_pool_bwd_weight(const rotconv_plan* plan, const void* x, const void* gpool, const uint8_t* idx, float* dw,
+                            void* ws, size_t ws_bytes, void* stream);
+
+/* Static, never NULL. */
+const char* rotconv_status_string(int status);
+/* Name of the kernel family the last successful call of the given kind on this
+ * plan would use ("generic", "mfma_p4", ...).  pass: 0 fwd, 1 bwd_data, 2 bwd_weight. */
+const char* rotconv_plan_kernel_name(const rotconv_plan* plan, int pass);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ROTCONV_H */

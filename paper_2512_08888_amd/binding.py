@@ -1,0 +1,222 @@
+"""Thin ctypes binding of librotconv.so (the C ABI of include/rotconv.h).
+
+Argument marshalling only: every step of the path runs in the library's HIP
+kernels.  PyTorch supplies device memory and the current stream.  There is no
+fallback of any kind: if the library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "librotconv.so")
+
+OK = 0
+ERR_NULL, ERR_SHAPE, ERR_ANGLES, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_LAUNCH = -1, -2, -3, -4, -5, -6
+F32, BF16 = 0, 1
+MODES = {"exact90": 0, "steerable": 1, "bilinear": 2}
+
+EXPORTS = [
+    "rotconv_plan_create", "rotconv_plan_destroy", "rotconv_workspace_bytes", "rotconv_out_shape",
+    "rotconv_plan_orientations", "rotconv_plan_expansion",
+    "rotconv_fwd", "rotconv_bwd_data", "rotconv_bwd_weight", "orient_maxpool_fwd", "orient_maxpool_bwd",
+    "rotconv_pool_fwd", "rotconv_pool_bwd_data", "rotconv_pool_bwd_weight",
+    "rotconv_status_string", "rotconv_plan_kernel_name",
+]
+
+
+class Desc(ctypes.Structure):
+    _fields_ = [
+        ("N", ctypes.c_int32), ("Cin", ctypes.c_int32), ("H", ctypes.c_int32), ("W", ctypes.c_int32),
+        ("Cout", ctypes.c_int32), ("k", ctypes.c_int32), ("R", ctypes.c_int32),
+        ("angles_deg", ctypes.POINTER(ctypes.c_double)),
+        ("mode", ctypes.c_int32), ("stride", ctypes.c_int32), ("pad", ctypes.c_int32),
+        ("pool_group", ctypes.c_int32), ("dtype", ctypes.c_int32),
+    ]
+
+
+class RotconvError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(f"{what}: {status_string(status)} ({status})")
+
+
+_lib = None
+
+
+def lib():
+    """Loads librotconv.so; raises if it has not been built (no fallback)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2512_08888_amd.build` "
+                "(or __graft_entry__.build()); there is no non-HIP fallback")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, sz, i32p = ctypes.c_void_p, ctypes.c_size_t, ctypes.POINTER(ctypes.c_int32)
+        L.rotconv_plan_create.argtypes = [ctypes.POINTER(Desc), ctypes.POINTER(vp)]
+        L.rotconv_plan_destroy.argtypes = [vp]
+        L.rotconv_workspace_bytes.argtypes = [vp]
+        L.rotconv_workspace_bytes.restype = sz
+        L.rotconv_out_shape.argtypes = [vp, i32p, i32p, i32p, i32p]
+        L.rotconv_plan_orientations.argtypes = [vp, i32p, i32p, i32p]
+        L.rotconv_plan_expansion.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
+        L.rotconv_fwd.argtypes = [vp, vp, vp, vp, vp, sz, vp]
+        L.rotconv_bwd_data.argtypes = [vp, vp, vp, vp, vp, sz, vp]
+        L.rotconv_bwd_weight.argtypes = [vp, vp, vp, vp, vp, sz, vp]
+        L.orient_maxpool_fwd.argtypes = [vp, vp, vp, vp, vp]
+        L.orient_maxpool_bwd.argtypes = [vp, vp, vp, vp, vp]
+        L.rotconv_pool_fwd.argtypes = [vp, vp, vp, vp, vp, vp, sz, vp]
+        L.rotconv_pool_bwd_data.argtypes = [vp, vp, vp, vp, vp, vp, sz, vp]
+        L.rotconv_pool_bwd_weight.argtypes = [vp, vp, vp, vp, vp, vp, sz, vp]
+        L.rotconv_status_string.argtypes = [ctypes.c_int]
+        L.rotconv_status_string.restype = ctypes.c_char_p
+        L.rotconv_plan_kernel_name.argtypes = [vp, ctypes.c_int]
+        L.rotconv_plan_kernel_name.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().rotconv_status_string(int(status)).decode()
+
+
+def _check(status: int, what: str):
+    if status != OK:
+        raise RotconvError(status, what)
+
+
+def _ptr(t) -> Optional[int]:
+    """Device (or host) address of a tensor; None stays NULL."""
+    if t is None:
+        return None
+    if not t.is_contiguous():
+        raise ValueError("tensors handed to the library must be contiguous")
+    return t.data_ptr()
+
+
+def _stream() -> Optional[int]:
+    import torch
+
+    return torch.cuda.current_stream().cuda_stream or None
+
+
+class Plan:
+    """Owns a rotconv_plan*.  Mirrors rotconv_plan_create / destroy and the host-side queries."""
+
+    def __init__(self, N, Cin, H, W, Cout, k=3, R=4, angles_deg: Optional[Sequence[float]] = None, mode="exact90",
+                 stride=1, pad=1, pool_group=0, dtype=F32):
+        self._h = ctypes.c_void_p()
+        self._angles = None
+        ang = None
+        if angles_deg is not None:
+            self._angles = (ctypes.c_double * len(angles_deg))(*[float(a) for a in angles_deg])
+            ang = ctypes.cast(self._angles, ctypes.POINTER(ctypes.c_double))
+        m = MODES[mode] if isinstance(mode, str) else int(mode)
+        self.desc = Desc(N, Cin, H, W, Cout, k, R, ang, m, stride, pad, pool_group or 0, dtype)
+        _check(lib().rotconv_plan_create(ctypes.byref(self.desc), ctypes.byref(self._h)), "rotconv_plan_create")
+        ho, wo, cu, cp = (ctypes.c_int32() for _ in range(4))
+        lib().rotconv_out_shape(self._h, ctypes.byref(ho), ctypes.byref(wo), ctypes.byref(cu), ctypes.byref(cp))
+        self.Ho, self.Wo, self.Cunpooled, self.Cpooled = ho.value, wo.value, cu.value, cp.value
+        self.N, self.Cin, self.H, self.W, self.Cout, self.k, self.R = N, Cin, H, W, Cout, k, R
+        self.B = 2 if m == MODES["steerable"] else 1
+        self.workspace_bytes = int(lib().rotconv_workspace_bytes(self._h))
+        self._ws = None
+
+    @classmethod
+    def from_config(cls, cfg, **over):
+        kw = dict(N=cfg.N, Cin=cfg.Cin, H=cfg.H, W=cfg.W, Cout=cfg.Cout, k=cfg.k, R=cfg.R, angles_deg=cfg.angles_deg,
+                  mode=cfg.mode, stride=cfg.stride, pad=cfg.pad, pool_group=cfg.pool_group or 0)
+        kw.update(over)
+        return cls(**kw)
+
+    def close(self):
+        if self._h:
+            lib().rotconv_plan_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @property
+    def handle(self):
+        return self._h
+
+    def orientations(self):
+        q = ctypes.c_int32()
+        bank = (ctypes.c_int32 * self.R)()
+        quarter = (ctypes.c_int32 * self.R)()
+        _check(lib().rotconv_plan_orientations(self._h, ctypes.byref(q), bank, quarter), "rotconv_plan_orientations")
+        return q.value, list(bank), list(quarter)
+
+    def expansion(self):
+        import numpy as np
+
+        kk = self.k * self.k
+        E = np.zeros((self.R, kk, self.B, kk), dtype=np.float32)
+        _check(lib().rotconv_plan_expansion(self._h, E.ctypes.data_as(ctypes.POINTER(ctypes.c_float))),
+               "rotconv_plan_expansion")
+        return E
+
+    def kernel_name(self, which: int) -> str:
+        return lib().rotconv_plan_kernel_name(self._h, which).decode()
+
+    def workspace(self, device="cuda"):
+        """A torch byte tensor of workspace_bytes on the device (allocated once per plan)."""
+        import torch
+
+        if self._ws is None:
+            self._ws = torch.empty(max(self.workspace_bytes, 256), dtype=torch.uint8, device=device)
+        return self._ws
+
+
+def _ws_args(plan: Plan, ws):
+    if ws is None:
+        ws = plan.workspace()
+    return _ptr(ws), ws.numel() * ws.element_size()
+
+
+def rotconv_fwd(plan: Plan, x, w, y, ws=None):
+    p, n = _ws_args(plan, ws)
+    _check(lib().rotconv_fwd(plan.handle, _ptr(x), _ptr(w), _ptr(y), p, n, _stream()), "rotconv_fwd")
+
+
+def rotconv_bwd_data(plan: Plan, dy, w, dx, ws=None):
+    p, n = _ws_args(plan, ws)
+    _check(lib().rotconv_bwd_data(plan.handle, _ptr(dy), _ptr(w), _ptr(dx), p, n, _stream()), "rotconv_bwd_data")
+
+
+def rotconv_bwd_weight(plan: Plan, x, dy, dw, ws=None):
+    p, n = _ws_args(plan, ws)
+    _check(lib().rotconv_bwd_weight(plan.handle, _ptr(x), _ptr(dy), _ptr(dw), p, n, _stream()), "rotconv_bwd_weight")
+
+
+def orient_maxpool_fwd(plan: Plan, y, ypool, idx):
+    _check(lib().orient_maxpool_fwd(plan.handle, _ptr(y), _ptr(ypool), _ptr(idx), _stream()), "orient_maxpool_fwd")
+
+
+def orient_maxpool_bwd(plan: Plan, gpool, idx, dy):
+    _check(lib().orient_maxpool_bwd(plan.handle, _ptr(gpool), _ptr(idx), _ptr(dy), _stream()), "orient_maxpool_bwd")
+
+
+def rotconv_pool_fwd(plan: Plan, x, w, ypool, idx, ws=None):
+    p, n = _ws_args(plan, ws)
+    _check(lib().rotconv_pool_fwd(plan.handle, _ptr(x), _ptr(w), _ptr(ypool), _ptr(idx), p, n, _stream()),
+           "rotconv_pool_fwd")
+
+
+def rotconv_pool_bwd_data(plan: Plan, gpool, idx, w, dx, ws=None):
+    p, n = _ws_args(plan, ws)
+    _check(lib().rotconv_pool_bwd_data(plan.handle, _ptr(gpool), _ptr(idx), _ptr(w), _ptr(dx), p, n, _stream()),
+           "rotconv_pool_bwd_data")
+
+
+def rotconv_pool_bwd_weight(plan: Plan, x, gpool, idx, dw, ws=None):
+    p, n = _ws_args(plan, ws)
+    _check(lib().rotconv_pool_bwd_weight(plan.handle, _ptr(x), _ptr(gpool), _ptr(idx), _ptr(dw), p, n, _stream()),
+           "rotconv_pool_bwd_weight")

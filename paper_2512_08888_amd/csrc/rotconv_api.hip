@@ -1,0 +1,236 @@
+// extern "C" entry points of the rotation-convolution library (see include/rotconv.h).
+// This layer checks arguments, uploads the plan's tables on first use, picks the
+// kernel family and enqueues; it never synchronises with the host.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstring>
+
+#include "rotconv_kernels.h"
+
+namespace rotconv {
+
+namespace {
+
+template <typename T>
+bool upload(const std::vector<T>& h, T** d) {
+  const size_t bytes = std::max<size_t>(h.size(), 1) * sizeof(T);
+  if (hipMalloc(reinterpret_cast<void**>(d), bytes) != hipSuccess) return false;
+  if (!h.empty() && hipMemcpy(*d, h.data(), h.size() * sizeof(T), hipMemcpyHostToDevice) != hipSuccess) return false;
+  return true;
+}
+
+}  // namespace
+
+int ensure_device_tables(rotconv_plan* p) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return ROTCONV_ERR_LAUNCH;
+  if (p->dev.device == dev) return ROTCONV_OK;
+  if (p->dev.device >= 0) return ROTCONV_ERR_UNSUPPORTED;  // a plan is bound to the first device it ran on
+  const HostTables& t = p->host;
+  DeviceTables& d = p->dev;
+  const bool ok = upload(t.exp_src, &d.exp_src) && upload(t.exp_coef, &d.exp_coef) && upload(t.tr_ptr, &d.tr_ptr) &&
+                  upload(t.tr_col, &d.tr_col) && upload(t.tr_coef, &d.tr_coef) && upload(t.fq_src, &d.fq_src) &&
+                  upload(t.fq_coef, &d.fq_coef) && upload(t.fqt_ptr, &d.fqt_ptr) && upload(t.fqt_col, &d.fqt_col) &&
+                  upload(t.fqt_coef, &d.fqt_coef) && upload(p->rot_of, &d.rot_of);
+  if (!ok) {
+    (void)hipGetLastError();
+    free_device_tables(p);
+    return ROTCONV_ERR_LAUNCH;
+  }
+  d.device = dev;
+  return ROTCONV_OK;
+}
+
+void free_device_tables(rotconv_plan* p) {
+  DeviceTables& d = p->dev;
+  void* ptrs[] = {d.exp_src, d.exp_coef, d.tr_ptr, d.tr_col, d.tr_coef, d.fq_src,
+                  d.fq_coef, d.fqt_ptr, d.fqt_col, d.fqt_coef, d.rot_of};
+  for (void* q : ptrs)
+    if (q) (void)hipFree(q);
+  d = DeviceTables();
+}
+
+namespace {
+
+int finish() { return hipGetLastError() == hipSuccess ? ROTCONV_OK : ROTCONV_ERR_LAUNCH; }
+
+int check_ws(const rotconv_plan* p, const void* ws, size_t ws_bytes) {
+  if (p->ws_bytes == 0) return ROTCONV_OK;
+  if (!ws || ws_bytes < p->ws_bytes) return ROTCONV_ERR_WORKSPACE;
+  return ROTCONV_OK;
+}
+
+}  // namespace
+}  // namespace rotconv
+
+using namespace rotconv;
+
+extern "C" {
+
+int rotconv_plan_create(const rotconv_desc* desc, rotconv_plan** out) {
+  if (!desc || !out) return ROTCONV_ERR_NULL;
+  rotconv_plan* p = nullptr;
+  const int rc = validate_and_build(desc, &p);
+  if (rc != ROTCONV_OK) return rc;
+  p->bwdw_splits = generic_bwdw_splits(p);
+  p->ws_bytes = generic_ws_bytes(p);
+  *out = p;
+  return ROTCONV_OK;
+}
+
+int rotconv_plan_destroy(rotconv_plan* plan) {
+  if (!plan) return ROTCONV_OK;
+  free_device_tables(plan);
+  delete plan;
+  return ROTCONV_OK;
+}
+
+size_t rotconv_workspace_bytes(const rotconv_plan* plan) { return plan ? plan->ws_bytes : 0; }
+
+int rotconv_out_shape(const rotconv_plan* plan, int32_t* Ho, int32_t* Wo, int32_t* Cunpooled, int32_t* Cpooled) {
+  if (!plan) return ROTCONV_ERR_NULL;
+  if (Ho) *Ho = plan->Ho;
+  if (Wo) *Wo = plan->Wo;
+  if (Cunpooled) *Cunpooled = plan->d.Cout * plan->d.R;
+  if (Cpooled) *Cpooled = plan->d.Cout * plan->ng;
+  return ROTCONV_OK;
+}
+
+int rotconv_plan_orientations(const rotconv_plan* plan, int32_t* Q, int32_t* bank_of_r, int32_t* quarter_of_r) {
+  if (!plan) return ROTCONV_ERR_NULL;
+  if (Q) *Q = plan->host.Q;
+  for (int r = 0; r < plan->d.R; ++r) {
+    if (bank_of_r) bank_of_r[r] = plan->host.bank_of_r[r];
+    if (quarter_of_r) quarter_of_r[r] = plan->host.quarter_of_r[r];
+  }
+  return ROTCONV_OK;
+}
+
+int rotconv_plan_expansion(const rotconv_plan* plan, float* E) {
+  if (!plan || !E) return ROTCONV_ERR_NULL;
+  const int kk = plan->kk, B = plan->B, R = plan->d.R;
+  std::memset(E, 0, sizeof(float) * R * kk * B * kk);
+  for (int row = 0; row < R * kk; ++row)
+    for (int e = 0; e < kMaxNnz; ++e) {
+      const int s = plan->host.exp_src[row * kMaxNnz + e];
+      if (s >= 0) E[(size_t)row * B * kk + s] += plan->host.exp_coef[row * kMaxNnz + e];
+    }
+  return ROTCONV_OK;
+}
+
+int rotconv_fwd(const rotconv_plan* plan, const void* x, const void* w, void* y, void* ws, size_t ws_bytes,
+                void* stream) {
+  if (!plan || !x || !w || !y) return ROTCONV_ERR_NULL;
+  int rc = check_ws(plan, ws, ws_bytes);
+  if (rc) return rc;
+  rotconv_plan* p = const_cast<rotconv_plan*>(plan);
+  if ((rc = ensure_device_tables(p))) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  float* wexp = static_cast<float*>(ws);
+  launch_expand_bank(p, static_cast<const float*>(w), wexp, st);
+  launch_fwd_generic(p, static_cast<const float*>(x), wexp, static_cast<float*>(y), st);
+  return finish();
+}
+
+int rotconv_bwd_data(const rotconv_plan* plan, const void* dy, const void* w, void* dx, void* ws, size_t ws_bytes,
+                     void* stream) {
+  if (!plan || !dy || !w || !dx) return ROTCONV_ERR_NULL;
+  int rc = check_ws(plan, ws, ws_bytes);
+  if (rc) return rc;
+  rotconv_plan* p = const_cast<rotconv_plan*>(plan);
+  if ((rc = ensure_device_tables(p))) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  float* wexp = static_cast<float*>(ws);
+  launch_expand_bank(p, static_cast<const float*>(w), wexp, st);
+  launch_bwd_data_generic(p, static_cast<const float*>(dy), wexp, static_cast<float*>(dx), st);
+  return finish();
+}
+
+int rotconv_bwd_weight(const rotconv_plan* plan, const void* x, const void* dy, float* dw, void* ws, size_t ws_bytes,
+                       void* stream) {
+  if (!plan || !x || !dy || !dw) return ROTCONV_ERR_NULL;
+  int rc = check_ws(plan, ws, ws_bytes);
+  if (rc) return rc;
+  rotconv_plan* p = const_cast<rotconv_plan*>(plan);
+  if ((rc = ensure_device_tables(p))) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  launch_bwd_weight_generic(p, static_cast<const float*>(x), static_cast<const float*>(dy), nullptr, nullptr,
+                            static_cast<float*>(ws), dw, st);
+  return finish();
+}
+
+int orient_maxpool_fwd(const rotconv_plan* plan, const void* y, void* ypool, uint8_t* idx, void* stream) {
+  if (!plan || !y || !ypool || !idx) return ROTCONV_ERR_NULL;
+  launch_maxpool_fwd(plan, static_cast<const float*>(y), static_cast<float*>(ypool), idx,
+                     static_cast<hipStream_t>(stream));
+  return finish();
+}
+
+int orient_maxpool_bwd(const rotconv_plan* plan, const void* gpool, const uint8_t* idx, void* dy, void* stream) {
+  if (!plan || !gpool || !idx || !dy) return ROTCONV_ERR_NULL;
+  launch_maxpool_bwd(plan, static_cast<const float*>(gpool), idx, static_cast<float*>(dy),
+                     static_cast<hipStream_t>(stream));
+  return finish();
+}
+
+int rotconv_pool_fwd(const rotconv_plan* plan, const void* x, const void* w, void* ypool, uint8_t* idx, void* ws,
+                     size_t ws_bytes, void* stream) {
+  if (!plan || !x || !w || !ypool || !idx) return ROTCONV_ERR_NULL;
+  int rc = check_ws(plan, ws, ws_bytes);
+  if (rc) return rc;
+  rotconv_plan* p = const_cast<rotconv_plan*>(plan);
+  if ((rc = ensure_device_tables(p))) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  float* wexp = static_cast<float*>(ws);
+  launch_expand_bank(p, static_cast<const float*>(w), wexp, st);
+  launch_pool_fwd_generic(p, static_cast<const float*>(x), wexp, static_cast<float*>(ypool), idx, st);
+  return finish();
+}
+
+int rotconv_pool_bwd_data(const rotconv_plan* plan, const void* gpool, const uint8_t* idx, const void* w, void* dx,
+                          void* ws, size_t ws_bytes, void* stream) {
+  if (!plan || !gpool || !idx || !w || !dx) return ROTCONV_ERR_NULL;
+  int rc = check_ws(plan, ws, ws_bytes);
+  if (rc) return rc;
+  rotconv_plan* p = const_cast<rotconv_plan*>(plan);
+  if ((rc = ensure_device_tables(p))) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  float* wexp = static_cast<float*>(ws);
+  launch_expand_bank(p, static_cast<const float*>(w), wexp, st);
+  launch_pool_bwd_data_generic(p, static_cast<const float*>(gpool), idx, wexp, static_cast<float*>(dx), st);
+  return finish();
+}
+
+int rotconv_pool_bwd_weight(const rotconv_plan* plan, const void* x, const void* gpool, const uint8_t* idx, float* dw,
+                            void* ws, size_t ws_bytes, void* stream) {
+  if (!plan || !x || !gpool || !idx || !dw) return ROTCONV_ERR_NULL;
+  int rc = check_ws(plan, ws, ws_bytes);
+  if (rc) return rc;
+  rotconv_plan* p = const_cast<rotconv_plan*>(plan);
+  if ((rc = ensure_device_tables(p))) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  launch_bwd_weight_generic(p, static_cast<const float*>(x), nullptr, static_cast<const float*>(gpool), idx,
+                            static_cast<float*>(ws), dw, st);
+  return finish();
+}
+
+const char* rotconv_status_string(int status) {
+  switch (status) {
+    case ROTCONV_OK: return "ok";
+    case ROTCONV_ERR_NULL: return "null pointer argument";
+    case ROTCONV_ERR_SHAPE: return "invalid shape, stride, padding or pool group";
+    case ROTCONV_ERR_ANGLES: return "invalid angle set for this mode";
+    case ROTCONV_ERR_UNSUPPORTED: return "request not supported by this build";
+    case ROTCONV_ERR_WORKSPACE: return "workspace missing or too small";
+    case ROTCONV_ERR_LAUNCH: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+const char* rotconv_plan_kernel_name(const rotconv_plan* plan, int pass) {
+  if (!plan || pass < 0 || pass > 2) return "none";
+  return plan->fast[pass] ? "mfma_p4" : "generic";
+}
+
+}  // extern "C"

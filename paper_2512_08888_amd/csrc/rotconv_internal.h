@@ -1,0 +1,79 @@
+// Internal declarations shared by the host code and the HIP kernels of the
+// rotation-convolution library.  Not part of the C ABI.
+#pragma once
+
+#include <cstddef>
+#include <cstdint>
+#include <vector>
+
+#include "rotconv.h"
+
+namespace rotconv {
+
+// One non-zero of the expansion map: W^(r)[dst tap] += coef * w[src], src = b*k*k + u.
+constexpr int kMaxNnz = 4;
+
+struct HostTables {
+  // Orientation structure (Sec. III-D): theta_r = 90*quarter[r] + phi[bank[r]].
+  int Q = 0;
+  std::vector<int> bank_of_r, quarter_of_r;
+  std::vector<double> phi_deg;  // per first-quadrant bank
+  // Forward expansion, one row per (r, dst tap): up to kMaxNnz (src, coef) pairs, src = -1 unused.
+  std::vector<int32_t> exp_src;  // [R*kk*kMaxNnz]
+  std::vector<float> exp_coef;   // [R*kk*kMaxNnz]
+  // Transposed expansion in CSR form, one row per base element (b, u):
+  // dw[b][u] = sum over entries e in row: coef[e] * dW^(r_e)[t_e], col = r*kk + t.
+  std::vector<int32_t> tr_ptr;   // [B*kk + 1]
+  std::vector<int32_t> tr_col;
+  std::vector<float> tr_coef;
+  // First-quadrant expansion (base -> Q banks, before any quarter turn), same row format
+  // as exp_*, one row per (q, dst tap); and its transpose in CSR form (col = q*kk + t).
+  std::vector<int32_t> fq_src;
+  std::vector<float> fq_coef;
+  std::vector<int32_t> fqt_ptr, fqt_col;
+  std::vector<float> fqt_coef;
+  // Quarter-turn tap permutation: turn_tap[s*kk + u] = index of the tap where base tap u
+  // sits after s quarter turns (Eq. 8: (m',n') = R_s(m,n)).
+  std::vector<int32_t> turn_tap;  // [4*kk]
+};
+
+struct DeviceTables {
+  int device = -1;
+  int32_t* exp_src = nullptr;
+  float* exp_coef = nullptr;
+  int32_t* tr_ptr = nullptr;
+  int32_t* tr_col = nullptr;
+  float* tr_coef = nullptr;
+  int32_t* fq_src = nullptr;
+  float* fq_coef = nullptr;
+  int32_t* fqt_ptr = nullptr;
+  int32_t* fqt_col = nullptr;
+  float* fqt_coef = nullptr;
+  int32_t* rot_of = nullptr;  // [Q*4] orientation index r of (bank q, quarter s), -1 if absent
+};
+
+}  // namespace rotconv
+
+struct rotconv_plan {
+  rotconv_desc d;               // angles_deg is redirected to `angles`
+  std::vector<double> angles;
+  int B = 1, G = 1, ng = 1, Ho = 0, Wo = 0, kk = 0;
+  rotconv::HostTables host;
+  std::vector<int32_t> rot_of;  // [Q*4]
+  rotconv::DeviceTables dev;    // uploaded on first launch
+  size_t ws_bytes = 0;
+  // kernel selection per pass (0 fwd, 1 bwd_data, 2 bwd_weight)
+  int fast[3] = {0, 0, 0};
+  int bwdw_splits = 1;          // pixel splits of the generic weight-gradient kernel
+};
+
+namespace rotconv {
+
+// Host logic (rotconv_host.cpp).
+int validate_and_build(const rotconv_desc* desc, rotconv_plan** out);
+
+// Kernel launchers (HIP sources).  All return a rotconv_status.
+int ensure_device_tables(rotconv_plan* plan);
+void free_device_tables(rotconv_plan* plan);
+
+}  // namespace rotconv

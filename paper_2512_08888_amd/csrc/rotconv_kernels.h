@@ -1,0 +1,35 @@
+// Launchers of the HIP kernels (defined in the .hip sources).  Every launcher
+// enqueues on `stream` and returns nothing; the API layer checks hipGetLastError.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include "rotconv_internal.h"
+
+namespace rotconv {
+
+// Geometry handed to kernels by value.
+struct Geom {
+  int N, Cin, H, W, Cout, k, kk, R, stride, pad, Ho, Wo, G, ng, B, Q;
+};
+
+Geom make_geom(const rotconv_plan* p);
+
+// ---- generic family (any k, stride, pad, R, mode) ----
+size_t generic_ws_bytes(const rotconv_plan* p);
+int generic_bwdw_splits(const rotconv_plan* p);
+// base bank(s) -> R rotated banks [R][Cout][Cin][kk]
+void launch_expand_bank(const rotconv_plan* p, const float* w, float* wexp, hipStream_t st);
+void launch_fwd_generic(const rotconv_plan* p, const float* x, const float* wexp, float* y, hipStream_t st);
+void launch_pool_fwd_generic(const rotconv_plan* p, const float* x, const float* wexp, float* ypool, uint8_t* idx,
+                             hipStream_t st);
+void launch_bwd_data_generic(const rotconv_plan* p, const float* dy, const float* wexp, float* dx, hipStream_t st);
+void launch_pool_bwd_data_generic(const rotconv_plan* p, const float* gpool, const uint8_t* idx, const float* wexp,
+                                  float* dx, hipStream_t st);
+// partial sums [splits][R][Cout][Cin][kk] into `partial`, then the transposed expansion into dw
+void launch_bwd_weight_generic(const rotconv_plan* p, const float* x, const float* dy, const float* gpool,
+                               const uint8_t* idx, float* partial, float* dw, hipStream_t st);
+void launch_maxpool_fwd(const rotconv_plan* p, const float* y, float* ypool, uint8_t* idx, hipStream_t st);
+void launch_maxpool_bwd(const rotconv_plan* p, const float* gpool, const uint8_t* idx, float* dy, hipStream_t st);
+
+}  // namespace rotconv

@@ -1,0 +1,264 @@
+"""GPU parity tests: the HIP path, called through the C ABI, against the CPU oracle
+element by element on the same seeded inputs.  Run with -m gpu on the MI355X machine."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import rotconv_oracle as orc
+from paper_2512_08888_amd import binding as rc
+from paper_2512_08888_amd import synth
+
+import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+
+LC = synth.LayerConfig
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+# Tiny / odd shapes: H != W, channel counts that are not multiples of any tile, N > 1,
+# pad 0/1/2, k = 1/2/3/5, stride 1/2, R = 1/2/3/4/8/16, all three modes, sub-group pooling.
+TINY = [
+    LC("t_r4", N=2, Cin=3, H=9, W=7, Cout=5, R=4, seed=11),
+    LC("t_r1", N=1, Cin=4, H=8, W=8, Cout=3, R=1, seed=12),
+    LC("t_r2", N=2, Cin=2, H=6, W=10, Cout=4, R=2, angles_deg=(0.0, 180.0), seed=13),
+    LC("t_r2b", N=1, Cin=2, H=6, W=6, Cout=2, R=2, angles_deg=(90.0, 270.0), seed=14),
+    LC("t_k1", N=2, Cin=5, H=5, W=6, Cout=3, k=1, pad=0, R=4, seed=15),
+    LC("t_k5", N=1, Cin=2, H=9, W=8, Cout=3, k=5, pad=2, R=4, seed=16),
+    LC("t_k2", N=1, Cin=2, H=7, W=7, Cout=2, k=2, pad=1, R=4, seed=17),
+    LC("t_pad0", N=2, Cin=3, H=8, W=9, Cout=2, pad=0, R=4, seed=18),
+    LC("t_pad2", N=1, Cin=3, H=6, W=5, Cout=2, pad=2, R=4, seed=19),
+    LC("t_s2", N=2, Cin=3, H=11, W=10, Cout=4, stride=2, R=4, seed=20),
+    LC("t_g2", N=1, Cin=3, H=8, W=8, Cout=3, R=4, pool_group=2, seed=21),
+    LC("t_g1", N=1, Cin=2, H=6, W=6, Cout=2, R=4, pool_group=1, seed=22),
+    LC("t_r8bil", N=2, Cin=3, H=8, W=7, Cout=3, R=8, mode="bilinear", seed=23),
+    LC("t_r16bil", N=1, Cin=4, H=10, W=10, Cout=2, R=16, mode="bilinear", seed=24),
+    LC("t_r16bil_g4", N=1, Cin=4, H=10, W=9, Cout=3, R=16, mode="bilinear", pool_group=4, seed=25),
+    LC("t_r16ste", N=1, Cin=3, H=8, W=8, Cout=2, R=16, mode="steerable", seed=26),
+    LC("t_r8ste_g4", N=2, Cin=2, H=7, W=8, Cout=3, R=8, mode="steerable", pool_group=4, seed=27),
+    LC("t_r3irr", N=1, Cin=2, H=8, W=8, Cout=2, R=3, mode="bilinear", angles_deg=(10.0, 100.0, 300.0), seed=28),
+    LC("t_r5k5", N=1, Cin=2, H=9, W=9, Cout=2, k=5, pad=2, R=5, mode="bilinear",
+       angles_deg=(0.0, 30.0, 120.0, 200.0, 359.0), seed=29),
+    LC("t_big_tail", N=1, Cin=17, H=33, W=35, Cout=19, R=4, seed=30),
+    LC("t_1px", N=1, Cin=1, H=1, W=1, Cout=1, R=4, seed=31),
+]
+
+
+@pytest.mark.parametrize("cfg", TINY, ids=[c.name for c in TINY])
+def test_fused_path_tiny(cfg):
+    say(f"[case] fused tiny {cfg}")
+    pu.run_fused_parity(cfg)
+
+
+@pytest.mark.parametrize("cfg", [c for c in TINY if c.mode == "exact90"], ids=lambda c: c.name)
+def test_fused_path_tiny_dyadic_bit_exact(cfg):
+    say(f"[case] fused tiny dyadic {cfg.name}")
+    pu.run_fused_parity(cfg, dyadic=True)
+
+
+@pytest.mark.parametrize("cfg", TINY[:1] + TINY[9:12] + TINY[12:15] + TINY[16:18], ids=lambda c: c.name)
+def test_unfused_chain_tiny(cfg):
+    """rotconv_fwd -> orient_maxpool_fwd -> orient_maxpool_bwd -> rotconv_bwd_data / bwd_weight."""
+    say(f"[case] unfused tiny {cfg.name}")
+    x, w, g = synth.make_x(cfg), synth.make_w(cfg), synth.make_g(cfg)
+    ref = pu.oracle_layer(cfg, x, w, g)
+    L = pu.GpuLayer(cfg, x, w)
+    y = L.fwd()
+    N, Cout, R = cfg.N, cfg.Cout, cfg.R
+    pu.assert_close(y.cpu().numpy().reshape(ref["y"].shape), ref["y"], f"{cfg.name} y")
+    yp, idx = L.maxpool_fwd(y)
+    pu.assert_close(yp, ref["ypool"], f"{cfg.name} ypool")
+    pu.check_idx(idx, ref["y"], ref["abs_terms"], cfg.G, f"{cfg.name} idx")
+    # pooling of the ORACLE's y on the GPU must reproduce the oracle's idx bit for bit
+    yp2, idx2 = L.maxpool_fwd(pu.dev(ref["y"].reshape(N, Cout * R, cfg.Ho, cfg.Wo), torch.float32))
+    y32 = ref["y"].astype(np.float32).astype(np.float64)
+    yp_ref32, idx_ref32 = orc.orient_maxpool_fwd(y32, cfg.G)
+    assert np.array_equal(idx2, idx_ref32) and np.array_equal(yp2.astype(np.float64), yp_ref32)
+    dy = L.maxpool_bwd(g, ref["idx"])
+    dy_ref = orc.orient_maxpool_bwd(g, ref["idx"], R, cfg.G)
+    assert np.array_equal(dy.cpu().numpy().reshape(dy_ref.shape).astype(np.float64), dy_ref)
+    pu.assert_close(L.bwd_data(dy), ref["dx"], f"{cfg.name} dx (unfused)")
+    pu.assert_close(L.bwd_weight(dy), ref["dw"], f"{cfg.name} dw (unfused)")
+    # dense (not one-hot) upstream gradient through the unfused backward calls
+    dyd = synth.make_dy(cfg)
+    w_rot = ref["w_rot"]
+    ang = None if cfg.angles_deg is None else list(cfg.angles_deg)
+    dyd5 = dyd.reshape(N, Cout, R, cfg.Ho, cfg.Wo)
+    dx_ref = orc.rotconv_bwd_data(dyd5, w_rot, cfg.H, cfg.W, cfg.stride, cfg.pad)
+    dw_ref = orc.reduce_bank_grad(orc.rotconv_bwd_weight(x, dyd5, cfg.k, cfg.stride, cfg.pad), ang, cfg.mode)
+    dyd_d = pu.dev(dyd, torch.float32)
+    pu.assert_close(L.bwd_data(dyd_d), dx_ref, f"{cfg.name} dx (dense dy)")
+    pu.assert_close(L.bwd_weight(dyd_d), dw_ref, f"{cfg.name} dw (dense dy)")
+
+
+def test_config1_fused_and_unfused():
+    """Benchmark configuration 1 (N=1, 3->8, 64x64, R=4): both call chains, continuous and dyadic."""
+    cfg = synth.C1
+    say(f"[case] C1 {cfg}")
+    out = pu.run_fused_parity(cfg)
+    L, ref = out["layer"], out["ref"]
+    y = L.fwd()
+    pu.assert_close(y.cpu().numpy().reshape(ref["y"].shape), ref["y"], "C1 y")
+    yp, idx = L.maxpool_fwd(y)
+    assert np.array_equal(yp, out["yp"]) or np.allclose(yp, out["yp"], rtol=1e-5, atol=1e-6)
+    dy = L.maxpool_bwd(out["g"], ref["idx"])
+    pu.assert_close(L.bwd_data(dy), ref["dx"], "C1 dx (unfused)")
+    pu.assert_close(L.bwd_weight(dy), ref["dw"], "C1 dw (unfused)")
+    pu.run_fused_parity(cfg, dyadic=True, label="C1 dyadic")
+
+
+def test_determinism_and_untouched_neighbours():
+    """Same inputs twice -> bitwise the same outputs; guard bands around outputs stay intact."""
+    cfg = LC("det", N=2, Cin=6, H=20, W=18, Cout=7, R=4, seed=77)
+    say(f"[case] determinism {cfg.name}")
+    x, w, g = synth.make_x(cfg), synth.make_w(cfg), synth.make_g(cfg)
+    L = pu.GpuLayer(cfg, x, w)
+    idx_any = synth.make_idx(cfg)
+    outs = []
+    for rep in range(2):
+        pad = 1024
+        n_p = int(np.prod(L.P))
+        n_x = x.size
+        buf_y = torch.full((n_p + 2 * pad,), 7.25, device="cuda")
+        buf_i = torch.full((n_p + 2 * pad,), 201, dtype=torch.uint8, device="cuda")
+        buf_dx = torch.full((n_x + 2 * pad,), 7.25, device="cuda")
+        buf_dw = torch.full((w.size + 2 * pad,), 7.25, device="cuda")
+        yp, idx = buf_y[pad:pad + n_p], buf_i[pad:pad + n_p]
+        dx, dw = buf_dx[pad:pad + n_x], buf_dw[pad:pad + w.size]
+        rc.rotconv_pool_fwd(L.plan, L.x, L.w, yp, idx)
+        gd, idd = pu.dev(g, torch.float32), pu.dev(idx_any)
+        rc.rotconv_pool_bwd_data(L.plan, gd, idd, L.w, dx)
+        rc.rotconv_pool_bwd_weight(L.plan, L.x, gd, idd, dw)
+        torch.cuda.synchronize()
+        for b, n in ((buf_y, n_p), (buf_dx, n_x), (buf_dw, w.size)):
+            assert bool((b[:pad] == 7.25).all()) and bool((b[pad + n:] == 7.25).all())
+        assert bool((buf_i[:pad] == 201).all()) and bool((buf_i[pad + n_p:] == 201).all())
+        outs.append([t.clone().cpu().numpy() for t in (yp, idx, dx, dw)])
+    for a, b in zip(*outs):
+        assert np.array_equal(a, b)
+
+
+def test_invalid_idx_values_contribute_nothing():
+    cfg = LC("badidx", N=1, Cin=3, H=8, W=8, Cout=2, R=4, pool_group=2, seed=5)
+    say(f"[case] invalid idx {cfg.name}")
+    x, w, g = synth.make_x(cfg), synth.make_w(cfg), synth.make_g(cfg)
+    L = pu.GpuLayer(cfg, x, w)
+    idx = synth.make_idx(cfg)
+    bad = idx.copy()
+    bad[0, 0, :4] = 250          # out of range
+    bad[0, 1, :4] = 0            # wrong group (channel 1 is group 1: members 1 and 3)
+    g0 = g.copy()
+    g0[0, 0, :4] = 0
+    g0[0, 1, :4] = 0
+    dx_bad, dw_bad = L.pool_bwd_data(g, bad), L.pool_bwd_weight(g, bad)
+    dx_ref, dw_ref = L.pool_bwd_data(g0, idx), L.pool_bwd_weight(g0, idx)
+    assert np.array_equal(dx_bad, dx_ref) and np.array_equal(dw_bad, dw_ref)
+
+
+def test_workspace_too_small_is_rejected():
+    cfg = TINY[0]
+    L = pu.GpuLayer(cfg, synth.make_x(cfg), synth.make_w(cfg))
+    small = torch.empty(16, dtype=torch.uint8, device="cuda")
+    yp, idx = L.nan(L.P), L.nan(L.P, torch.uint8)
+    with pytest.raises(rc.RotconvError) as e:
+        rc.rotconv_pool_fwd(L.plan, L.x, L.w, yp, idx, ws=small)
+    assert e.value.status == rc.ERR_WORKSPACE
+    torch.cuda.synchronize()
+    assert bool(torch.isnan(yp).all())  # outputs untouched
+
+
+def _sample_points(seed, n, dims):
+    cols = [synth.randint(seed + i, n, 0, d - 1) for i, d in enumerate(dims)]
+    return np.stack(cols, axis=1).astype(np.int32)
+
+
+def full_size_sampled_parity(cfg, n_samples=4096, n_pairs=24):
+    """Full benchmark-size layer in the launch configuration bench.py times, checked on sampled
+    outputs the oracle computes one by one, plus identities that hold at any size."""
+    say(f"[case] full-size sampled {cfg}")
+    x, w, g = synth.make_x(cfg), synth.make_w(cfg), synth.make_g(cfg)
+    L = pu.GpuLayer(cfg, x, w)
+    say(f"  kernels: {[L.plan.kernel_name(i) for i in range(3)]}")
+    yp, idx = L.pool_fwd()
+    ang = None if cfg.angles_deg is None else list(cfg.angles_deg)
+    w_rot = orc.expand_bank(w, cfg.R, ang, cfg.mode)
+    ng = cfg.R // cfg.G
+    # forward: sampled pooled outputs
+    pts = _sample_points(cfg.seed + 100, n_samples, (cfg.N, cfg.Cout, cfg.Ho, cfg.Wo))
+    yr = orc.rotconv_fwd_at(x, w_rot, pts, cfg.stride, cfg.pad)                   # [T,R]
+    ya = orc.rotconv_fwd_at(np.abs(x), np.abs(w_rot), pts, cfg.stride, cfg.pad)
+    rms = float(np.sqrt(np.mean(yr.reshape(-1, cfg.G, ng).max(axis=1) ** 2)))
+    near = 0
+    for t, (n, co, oy, ox) in enumerate(pts):
+        for grp in range(ng):
+            members = np.arange(grp, cfg.R, ng)
+            vals = yr[t, members]
+            got_v, got_i = float(yp[n, co * ng + grp, oy, ox]), int(idx[n, co * ng + grp, oy, ox])
+            assert abs(got_v - vals.max()) <= pu.RTOL * abs(vals.max()) + pu.RTOL * rms, (t, got_v, vals.max())
+            assert got_i % ng == grp
+            tau = 64.0 * pu.EPS32 * ya[t, members].max()
+            assert yr[t, got_i] >= vals.max() - tau, ("argmax outside near-tie band", t, got_i, vals)
+            near += int(got_i != members[int(vals.argmax())])
+    say(f"  fwd: {n_samples} sampled outputs ok, {near} accepted near-ties")
+    # backward with the GPU's own idx given to both sides (one shared idx)
+    dx = L.pool_bwd_data(g, idx)
+    dw = L.pool_bwd_weight(g, idx)
+    dy = None
+    if cfg.N * cfg.Cout * cfg.R * cfg.Ho * cfg.Wo <= 160_000_000:
+        dy = orc.orient_maxpool_bwd(g, idx, cfg.R, cfg.G)
+        ptsx = _sample_points(cfg.seed + 200, n_samples, (cfg.N, cfg.Cin, cfg.H, cfg.W))
+        dxr = orc.rotconv_bwd_data_at(dy, w_rot, ptsx, cfg.H, cfg.W, cfg.stride, cfg.pad)
+        got = dx[ptsx[:, 0], ptsx[:, 1], ptsx[:, 2], ptsx[:, 3]]
+        pu.assert_close(got, dxr, f"{cfg.name} dx samples")
+        say(f"  bwd_data: {n_samples} sampled inputs ok")
+    pairs = _sample_points(cfg.seed + 300, n_pairs, (cfg.Cout, cfg.Cin))
+    dwr_rot = orc.rotconv_pool_bwd_weight_at(x, g, idx, pairs, cfg.R, cfg.k, cfg.G, cfg.stride, cfg.pad)  # [T,R,k,k]
+    # reduce each sampled (co,ci) slice through Eq. 16 with the oracle
+    got_dw, ref_dw = [], []
+    for t, (co, ci) in enumerate(pairs):
+        full = np.zeros((cfg.R, 1, 1, cfg.k, cfg.k))
+        full[:, 0, 0] = dwr_rot[t]
+        ref_dw.append(orc.reduce_bank_grad(full, ang, cfg.mode)[:, 0, 0])
+        got_dw.append(dw[:, co, ci])
+    pu.assert_close(np.array(got_dw), np.array(ref_dw), f"{cfg.name} dw samples", rtol=pu.RTOL)
+    say(f"  bwd_weight: {n_pairs} sampled (co,ci) slices ok")
+    # Euler identities through the max (the layer is positively homogeneous of degree 1 in w and in x):
+    # <w, dw> = <x, dx> = <ypool, g>, at full size, no oracle needed.
+    a = float((yp.astype(np.float64) * g).sum())
+    b = float((x.astype(np.float64) * dx).sum())
+    c = float((w.astype(np.float64) * dw).sum())
+    scale = float(np.abs(yp.astype(np.float64) * g).sum())
+    assert abs(a - b) <= 1e-5 * scale and abs(a - c) <= 1e-5 * scale, (a, b, c, scale)
+    say(f"  homogeneity identities ok: {a:.6e} {b:.6e} {c:.6e}")
+    return L
+
+
+def test_config2_full_size_sampled():
+    full_size_sampled_parity(synth.C2)
+
+
+def test_config3_full_size_sampled():
+    full_size_sampled_parity(synth.C3, n_samples=2048, n_pairs=12)
+
+
+def test_config3_steerable_and_group4_reduced():
+    """Config-3 structure (R=16, 22.5 degree steps) in steerable mode and with the paper's
+    sub-group pooling (G=4), at a size the oracle finishes in seconds."""
+    for mode, G in (("steerable", None), ("bilinear", 4), ("steerable", 4)):
+        cfg = dataclasses.replace(synth.C3, name=f"C3r_{mode}_{G}", N=1, Cin=32, Cout=32, H=40, W=40, mode=mode,
+                                  pool_group=G)
+        say(f"[case] {cfg.name}")
+        pu.run_fused_parity(cfg)
+
+
+def test_config2_reduced_exact():
+    """Config-2 structure at reduced extent: element-by-element, continuous and dyadic (bit-exact)."""
+    cfg = dataclasses.replace(synth.C2, name="C2r", N=2, H=48, W=80)
+    say(f"[case] {cfg.name}")
+    pu.run_fused_parity(cfg)
+    pu.run_fused_parity(cfg, dyadic=True, label="C2r dyadic")

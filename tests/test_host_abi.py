@@ -1,0 +1,113 @@
+"""CPU-only checks of the C-ABI library: it loads, exports what include/rotconv.h
+declares, rejects bad descriptors with the documented codes, and its host-built
+orientation tables reproduce the oracle's materialised rotated banks."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import rotconv_oracle as orc
+from paper_2512_08888_amd import binding as rc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+RNG = np.random.default_rng(7)
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "rotconv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(rotconv_[a-z_0-9]+|orient_maxpool_[a-z]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = rc.lib()
+    names = declared_functions()
+    assert len(names) >= 16
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(rc.EXPORTS) == names
+
+
+def test_status_strings():
+    for s in (0, -1, -2, -3, -4, -5, -6, 17):
+        assert isinstance(rc.status_string(s), str) and rc.status_string(s)
+
+
+def _create(**kw):
+    base = dict(N=1, Cin=2, H=8, W=8, Cout=3, k=3, R=4, angles_deg=None, mode="exact90", stride=1, pad=1, pool_group=0)
+    base.update(kw)
+    return rc.Plan(**base)
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(N=0), rc.ERR_SHAPE), (dict(Cin=0), rc.ERR_SHAPE), (dict(k=0), rc.ERR_SHAPE), (dict(R=0), rc.ERR_SHAPE),
+    (dict(R=256, mode="bilinear"), rc.ERR_SHAPE), (dict(stride=0), rc.ERR_SHAPE), (dict(pad=-1), rc.ERR_SHAPE),
+    (dict(pool_group=3), rc.ERR_SHAPE), (dict(pool_group=8), rc.ERR_SHAPE), (dict(H=1, pad=0), rc.ERR_SHAPE),
+    (dict(R=8), rc.ERR_ANGLES),                                    # 45 deg in exact90 mode
+    (dict(R=2, angles_deg=[0.0, 360.0]), rc.ERR_ANGLES),           # outside [0,360)
+    (dict(R=2, angles_deg=[90.0, 0.0]), rc.ERR_ANGLES),            # not ascending
+    (dict(R=2, angles_deg=[90.0, 90.0]), rc.ERR_ANGLES),
+    (dict(mode=7), rc.ERR_UNSUPPORTED), (dict(dtype=rc.BF16), rc.ERR_UNSUPPORTED),
+])
+def test_descriptor_errors(kw, code):
+    with pytest.raises(rc.RotconvError) as e:
+        _create(**kw)
+    assert e.value.status == code
+
+
+def test_null_arguments():
+    L = rc.lib()
+    h = ctypes.c_void_p()
+    assert L.rotconv_plan_create(None, ctypes.byref(h)) == rc.ERR_NULL
+    d = rc.Desc(1, 1, 4, 4, 1, 3, 4, None, 0, 1, 1, 0, 0)
+    assert L.rotconv_plan_create(ctypes.byref(d), None) == rc.ERR_NULL
+    assert L.rotconv_plan_destroy(None) == rc.OK
+    assert L.rotconv_workspace_bytes(None) == 0
+    p = _create()
+    # NULL tensors are rejected before anything touches a device
+    assert L.rotconv_pool_fwd(p.handle, None, None, None, None, None, 0, None) == rc.ERR_NULL
+    assert L.rotconv_fwd(p.handle, None, 1, 1, None, 0, None) == rc.ERR_NULL
+    assert L.orient_maxpool_fwd(p.handle, 1, None, 1, None) == rc.ERR_NULL
+    # non-NULL tensors but no workspace
+    assert L.rotconv_pool_fwd(p.handle, 1, 1, 1, 1, None, 0, None) == rc.ERR_WORKSPACE
+    assert L.rotconv_pool_bwd_weight(p.handle, 1, 1, 1, 1, 1, 8, None) == rc.ERR_WORKSPACE
+
+
+def test_out_shape_and_workspace():
+    p = _create(N=2, H=9, W=7, stride=2, pad=1, R=4, pool_group=2)
+    assert (p.Ho, p.Wo, p.Cunpooled, p.Cpooled) == (5, 4, 12, 6)
+    assert p.workspace_bytes >= 4 * 4 * 3 * 2 * 9
+
+
+def test_orientation_structure():
+    p = _create(R=16, mode="bilinear")
+    Q, bank, quarter = p.orientations()
+    assert Q == 4 and bank == [r % 4 for r in range(16)] and quarter == [r // 4 for r in range(16)]
+    p = _create(R=3, mode="steerable", angles_deg=[10.0, 100.0, 300.0])
+    Q, bank, quarter = p.orientations()
+    assert Q == 2 and bank == [0, 0, 1] and quarter == [0, 1, 3]
+    p = _create(R=2, angles_deg=[0.0, 180.0])
+    assert p.orientations() == (1, [0, 0], [0, 2])
+
+
+@pytest.mark.parametrize("R,mode,k,angles", [
+    (4, "exact90", 3, None), (4, "exact90", 5, None), (4, "exact90", 2, None), (1, "exact90", 3, None),
+    (2, "exact90", 3, [90.0, 270.0]), (16, "bilinear", 3, None), (8, "bilinear", 5, None), (16, "steerable", 3, None),
+    (5, "bilinear", 3, [0.0, 30.0, 120.0, 200.0, 359.0]), (6, "steerable", 4, None),
+])
+def test_expansion_table_reproduces_oracle_banks(R, mode, k, angles):
+    """W^(r) = E[r] . w for random base banks: the host-built tap tables against the oracle's
+    explicitly rotated filters (Eq. 5, Sec. III-D, Eq. 17)."""
+    p = _create(R=R, mode=mode, k=k, angles_deg=angles, pad=k // 2)
+    E = p.expansion().astype(np.float64)  # [R, kk, B, kk]
+    B = 2 if mode == "steerable" else 1
+    w = RNG.standard_normal((B, 2, 3, k, k))
+    wr = orc.expand_bank(w, R, angles, mode)
+    got = np.einsum("rtbu,bocu->roct", E, w.reshape(B, 2, 3, k * k)).reshape(R, 2, 3, k, k)
+    np.testing.assert_allclose(got, wr, rtol=0, atol=2e-7 * np.abs(w).max() * 4)
+    if mode == "exact90":
+        # pure permutation: exactly one unit entry per row
+        assert np.array_equal(np.sort(E.reshape(R, k * k, -1), axis=-1)[..., -1], np.ones((R, k * k)))
+        assert np.count_nonzero(E) == R * k * k
