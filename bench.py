@@ -43,11 +43,11 @@ def cpu_baseline(cfg, Q):
     from oracle import rotconv_oracle as orc
     from paper_2512_08888_amd import synth
 
-    # about 10-30 s of CPU work: keep dense flops of the sample near 2e10 per pass
-    n_s = max(1, min(cfg.N, int(2.0e10 / (flops_dense(cfg) / cfg.N))))
+    # about 10-30 s of CPU work on the 16 host cores of the GPU machine: dense flops of the sample near 1.6e11 per pass
+    n_s = max(1, min(cfg.N, int(1.6e11 / (flops_dense(cfg) / cfg.N))))
     h_s = cfg.H
-    if n_s == 1 and flops_dense(cfg) / cfg.N > 4.0e10:
-        h_s = max(cfg.k, int(cfg.H * 4.0e10 / (flops_dense(cfg) / cfg.N)))
+    if n_s == 1 and flops_dense(cfg) / cfg.N > 3.2e11:
+        h_s = max(cfg.k, int(cfg.H * 3.2e11 / (flops_dense(cfg) / cfg.N)))
     sc = dataclasses.replace(cfg, N=n_s, H=h_s)
     x, w, g = synth.make_x(sc), synth.make_w(sc), synth.make_g(sc)
     ang = None if sc.angles_deg is None else list(sc.angles_deg)
