@@ -7,6 +7,7 @@
 #include <cstring>
 
 #include "rotconv_kernels.h"
+#include "rotconv_p4.h"
 
 namespace rotconv {
 
@@ -55,6 +56,22 @@ namespace {
 
 int finish() { return hipGetLastError() == hipSuccess ? ROTCONV_OK : ROTCONV_ERR_LAUNCH; }
 
+size_t align256(size_t v) { return (v + 255) / 256 * 256; }
+
+bool aligned(const void* p, size_t a) { return reinterpret_cast<uintptr_t>(p) % a == 0; }
+
+// Scratch of the fast forward: packed banks, then per-bank candidates or the unpooled map.
+size_t fwd_fast_ws_bytes(const rotconv_plan* p) {
+  const size_t pack = align256(p4_fwd_pack_floats(p) * sizeof(float));
+  const size_t hw = (size_t)p->d.H * p->d.W;
+  const int mode = p4_fwd_pool_mode(p);
+  size_t extra = 0;
+  if (mode == kOutPartial) extra = align256((size_t)p->host.Q * p->d.N * p->d.Cout * hw * 4) +
+                                   align256((size_t)p->host.Q * p->d.N * p->d.Cout * hw);
+  if (mode == kOutUnpooled) extra = align256((size_t)p->d.N * p->d.Cout * p->d.R * hw * 4);
+  return pack + extra;
+}
+
 int check_ws(const rotconv_plan* p, const void* ws, size_t ws_bytes) {
   if (p->ws_bytes == 0) return ROTCONV_OK;
   if (!ws || ws_bytes < p->ws_bytes) return ROTCONV_ERR_WORKSPACE;
@@ -75,6 +92,9 @@ int rotconv_plan_create(const rotconv_desc* desc, rotconv_plan** out) {
   if (rc != ROTCONV_OK) return rc;
   p->bwdw_splits = generic_bwdw_splits(p);
   p->ws_bytes = generic_ws_bytes(p);
+  p->fast[0] = p4_fwd_supported(p) ? 1 : 0;
+  if (p->fast[0]) p->ws_bytes = std::max(p->ws_bytes, fwd_fast_ws_bytes(p));
+  p->ws_bytes = align256(p->ws_bytes);
   *out = p;
   return ROTCONV_OK;
 }
@@ -127,6 +147,12 @@ int rotconv_fwd(const rotconv_plan* plan, const void* x, const void* w, void* y,
   rotconv_plan* p = const_cast<rotconv_plan*>(plan);
   if ((rc = ensure_device_tables(p))) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
+  if (p->fast[0] && aligned(x, 8) && aligned(ws, 16)) {
+    float* wt = static_cast<float*>(ws);
+    launch_p4_pack_fwd(p, static_cast<const float*>(w), wt, st);
+    launch_p4_fwd(p, kOutUnpooled, static_cast<const float*>(x), wt, static_cast<float*>(y), nullptr, st);
+    return finish();
+  }
   float* wexp = static_cast<float*>(ws);
   launch_expand_bank(p, static_cast<const float*>(w), wexp, st);
   launch_fwd_generic(p, static_cast<const float*>(x), wexp, static_cast<float*>(y), st);
@@ -182,6 +208,26 @@ int rotconv_pool_fwd(const rotconv_plan* plan, const void* x, const void* w, voi
   rotconv_plan* p = const_cast<rotconv_plan*>(plan);
   if ((rc = ensure_device_tables(p))) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
+  if (p->fast[0] && aligned(x, 8) && aligned(ws, 256) && aligned(ypool, 16) && aligned(idx, 8)) {
+    float* wt = static_cast<float*>(ws);
+    char* extra = static_cast<char*>(ws) + align256(p4_fwd_pack_floats(p) * sizeof(float));
+    const int mode = p4_fwd_pool_mode(p);
+    const size_t hw = (size_t)p->d.H * p->d.W;
+    launch_p4_pack_fwd(p, static_cast<const float*>(w), wt, st);
+    if (mode == kOutPooled) {
+      launch_p4_fwd(p, mode, static_cast<const float*>(x), wt, static_cast<float*>(ypool), idx, st);
+    } else if (mode == kOutPartial) {
+      float* pv = reinterpret_cast<float*>(extra);
+      uint8_t* pi = reinterpret_cast<uint8_t*>(extra + align256((size_t)p->host.Q * p->d.N * p->d.Cout * hw * 4));
+      launch_p4_fwd(p, mode, static_cast<const float*>(x), wt, pv, pi, st);
+      launch_p4_combine(p, pv, pi, static_cast<float*>(ypool), idx, st);
+    } else {
+      float* yu = reinterpret_cast<float*>(extra);
+      launch_p4_fwd(p, mode, static_cast<const float*>(x), wt, yu, nullptr, st);
+      launch_maxpool_fwd(p, yu, static_cast<float*>(ypool), idx, st);
+    }
+    return finish();
+  }
   float* wexp = static_cast<float*>(ws);
   launch_expand_bank(p, static_cast<const float*>(w), wexp, st);
   launch_pool_fwd_generic(p, static_cast<const float*>(x), wexp, static_cast<float*>(ypool), idx, st);

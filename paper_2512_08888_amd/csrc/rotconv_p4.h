@@ -1,0 +1,32 @@
+// Declarations of the fast (MFMA, 3x3 / stride 1 / pad 1) kernel family.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include "rotconv_internal.h"
+
+namespace rotconv {
+
+enum { kOutPooled = 0, kOutPartial = 1, kOutUnpooled = 2 };
+
+struct P4Geom {
+  int N, Cin, CinPad, H, W, Cout, CB, R, Q, ng;
+  int TY;        // output rows per wave band
+  int nbg;       // band groups per image (a workgroup takes NWY consecutive bands)
+  int units;     // workgroups with work
+  int nwx;       // waves along x
+  int out_mode;  // kOut*
+};
+
+// forward
+bool p4_fwd_supported(const rotconv_plan* p);
+P4Geom p4_fwd_geom(const rotconv_plan* p, int out_mode);
+size_t p4_fwd_pack_floats(const rotconv_plan* p);
+int p4_fwd_pool_mode(const rotconv_plan* p);
+void launch_p4_pack_fwd(const rotconv_plan* p, const float* w, float* wt, hipStream_t st);
+void launch_p4_fwd(const rotconv_plan* p, int out_mode, const float* x, const float* wt, float* out_val,
+                   uint8_t* out_idx, hipStream_t st);
+void launch_p4_combine(const rotconv_plan* p, const float* pv, const uint8_t* pi, float* ypool, uint8_t* idx,
+                       hipStream_t st);
+
+}  // namespace rotconv

@@ -1,0 +1,407 @@
+// Fast forward kernel for 3x3, stride 1, pad 1 (fp32): shared-product rotation
+// convolution on the fp32 matrix cores (paper Eq. 8, re-designed for CDNA4).
+//
+// For one first-quadrant bank the nine per-tap channel contractions
+//     P_u[co, h, x] = sum_ci F[co,ci,u] * X[ci,h,x]           (u = base tap)
+// are formed ONCE with v_mfma_f32_16x16x4_f32 (M = 16 pixels, N = 16 filters,
+// K = 4 input channels) and then placed at the four quarter-turn positions
+//     Y_s[co, y, x] = sum_u P_u[co, y + i_s(u) - 1, x + j_s(u) - 1],  (i_s,j_s) = R_s(u)
+// entirely in registers: a wave owns 16 filters x 32 consecutive pixels of one
+// image row and walks down the rows of its band, so a row of P feeds the output
+// rows above, at and below it through two rolling partial sums per rotation;
+// column shifts are register renames (each lane holds 8 consecutive pixels),
+// with the one neighbouring value per side fetched from the adjacent lane group
+// (ds_bpermute) or the adjacent wave (a few words of LDS per row).  The max over
+// the bank's rotations and its arg-max are taken in registers and stored once.
+// Nothing R-fold ever reaches memory, and the input row is read once per bank.
+//
+// The filter block (16 filters x all input channels x 9 taps) stays resident in
+// LDS for the life of the workgroup; input rows go straight from global memory
+// into the A-operand registers (8-byte loads, 128 B contiguous per 16 lanes),
+// prefetched one 32-channel chunk ahead.
+#include <hip/hip_runtime.h>
+
+#include "rotconv_kernels.h"
+#include "rotconv_p4.h"
+
+namespace rotconv {
+namespace {
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+
+constexpr int KC = 8;  // K-steps (of 4 channels) per prefetch chunk
+
+// Row / column of base tap u inside the filter turned by s quarter turns (Eq. 8).
+__device__ __host__ constexpr int tap_i(int s, int u) {
+  return s == 0 ? u / 3 : s == 1 ? 2 - u % 3 : s == 2 ? 2 - u / 3 : u % 3;
+}
+__device__ __host__ constexpr int tap_j(int s, int u) {
+  return s == 0 ? u % 3 : s == 1 ? u / 3 : s == 2 ? 2 - u % 3 : 2 - u / 3;
+}
+// Index of non-centre tap u in the 8-entry edge exchange arrays.
+__device__ __host__ constexpr int edge_slot(int u) { return u < 4 ? u : u - 1; }
+
+template <int NWX, int NWY>
+__global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restrict__ x, const float* __restrict__ wt,
+                                                           const int32_t* __restrict__ rot_of,
+                                                           float* __restrict__ out_val, uint8_t* __restrict__ out_idx,
+                                                           P4Geom g) {
+  constexpr int NW = NWX * NWY;
+  constexpr int NT = 64 * NW;
+  extern __shared__ float smem[];
+  float* Wl = smem;                      // [CinPad][9][16]
+  float* EL = smem + g.CinPad * 144;     // [2][NW][8][16] left-edge values of every wave
+  float* ER = EL + 2 * NW * 128;         // [2][NW][8][16] right-edge values
+
+  // XCD-aware unit decode: consecutive units (same image rows, different filter
+  // blocks / banks) go to the same XCD so they share its L2 copy of the input.
+  const int per_xcd = (g.units + 7) / 8;
+  int v = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  if (v >= g.units) return;
+  const int cb = v % g.CB; v /= g.CB;
+  const int q = v % g.Q; v /= g.Q;
+  const int bg = v % g.nbg;
+  const int n = v / g.nbg;
+
+  const int tid = threadIdx.x;
+  {
+    const f4* src = reinterpret_cast<const f4*>(wt + ((size_t)(q * g.CB + cb) * g.CinPad) * 144);
+    f4* dst = reinterpret_cast<f4*>(Wl);
+    const int n4 = g.CinPad * 36;
+    for (int i = tid; i < n4; i += NT) dst[i] = src[i];
+  }
+  __syncthreads();
+
+  const int wave = tid / 64, lane = tid % 64;
+  const int wx = wave % NWX, wy = wave / NWX;
+  const int lg = lane / 16, lc = lane % 16;
+  const int x0 = wx * 32;
+  const int y0 = (bg * NWY + wy) * g.TY;
+  const int nchunk = g.CinPad / (4 * KC);
+  const int nsteps = g.TY + 2;
+
+  int rot[4];
+#pragma unroll
+  for (int s = 0; s < 4; ++s) rot[s] = rot_of[q * 4 + s];
+
+  // A-operand loads: lane (lc, lg) reads X[ci = 4*ks + lg][h][x0 + 2*lc .. +1].
+  const int pxa = x0 + 2 * lc;
+  const bool px_ok = pxa < g.W;
+  const float* xn = x + (size_t)n * g.Cin * g.H * g.W + pxa;
+  const size_t chan_stride = (size_t)g.H * g.W;
+
+  auto load_chunk = [&](int t, int c, float2 (&dst)[KC]) {
+    const int h = y0 - 1 + t;
+    const bool ok = px_ok && h >= 0 && h < g.H;
+#pragma unroll
+    for (int ks = 0; ks < KC; ++ks) {
+      const int ci = (c * KC + ks) * 4 + lg;
+      if (ok && ci < g.Cin)
+        dst[ks] = *reinterpret_cast<const float2*>(xn + ci * chan_stride + (size_t)h * g.W);
+      else
+        dst[ks] = make_float2(0.f, 0.f);
+    }
+  };
+
+  float accA[4][8], accB[4][8];
+#pragma unroll
+  for (int s = 0; s < 4; ++s)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { accA[s][j] = 0.f; accB[s][j] = 0.f; }
+
+  float2 a_cur[KC], a_nxt[KC];
+  load_chunk(0, 0, a_cur);
+  const float* wl_lane = Wl + lg * 144 + lc;
+
+  for (int t = 0; t < nsteps; ++t) {
+    const int h = y0 - 1 + t;
+    const bool row_ok = h >= 0 && h < g.H;
+    f4 P[9][2];
+#pragma unroll
+    for (int u = 0; u < 9; ++u) { P[u][0] = f4{0.f, 0.f, 0.f, 0.f}; P[u][1] = f4{0.f, 0.f, 0.f, 0.f}; }
+
+    for (int c = 0; c < nchunk; ++c) {
+      int tn = t, cn = c + 1;
+      if (cn == nchunk) { cn = 0; tn = t + 1; }
+      if (tn < nsteps) load_chunk(tn, cn, a_nxt);
+      if (row_ok) {
+        const float* wc = wl_lane + (size_t)c * KC * 4 * 144;
+        float bw[2][9];
+#pragma unroll
+        for (int u = 0; u < 9; ++u) bw[0][u] = wc[u * 16];
+#pragma unroll
+        for (int ks = 0; ks < KC; ++ks) {
+          if (ks + 1 < KC) {
+#pragma unroll
+            for (int u = 0; u < 9; ++u) bw[(ks + 1) & 1][u] = wc[(ks + 1) * 4 * 144 + u * 16];
+          }
+#pragma unroll
+          for (int u = 0; u < 9; ++u) {
+            P[u][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur[ks].x, bw[ks & 1][u], P[u][0], 0, 0, 0);
+            P[u][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur[ks].y, bw[ks & 1][u], P[u][1], 0, 0, 0);
+          }
+        }
+      }
+#pragma unroll
+      for (int ks = 0; ks < KC; ++ks) a_cur[ks] = a_nxt[ks];
+    }
+
+    // ---- neighbour values across lane groups and waves --------------------------
+    // Lane (lg, lc) holds filter lc, pixels x0 + 8*lg + j, j = 2*i + b for P[u][b][i].
+    float nbL[9], nbR[9];  // P_u at pixel (first - 1) resp. (last + 1) of this lane's 8 pixels
+    const int par = t & 1;
+    float* el = EL + (par * NW + wave) * 128 + lc;
+    float* er = ER + (par * NW + wave) * 128 + lc;
+    if (lg == 0) {
+#pragma unroll
+      for (int u = 0; u < 9; ++u)
+        if (u != 4) el[edge_slot(u) * 16] = P[u][0][0];
+    }
+    if (lg == 3) {
+#pragma unroll
+      for (int u = 0; u < 9; ++u)
+        if (u != 4) er[edge_slot(u) * 16] = P[u][1][3];
+    }
+    const int addr_up = ((lane + 16) & 63) * 4, addr_dn = ((lane + 48) & 63) * 4;
+#pragma unroll
+    for (int u = 0; u < 9; ++u) {
+      if (u == 4) { nbL[u] = 0.f; nbR[u] = 0.f; continue; }
+      // The sources are pinned in VGPRs of their own first: handing an element of the
+      // accumulator vector straight to the cross-lane read picked the wrong element.
+      float first_px = P[u][0][0], last_px = P[u][1][3];
+      asm volatile("" : "+v"(first_px), "+v"(last_px));
+      nbR[u] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(addr_up, __builtin_bit_cast(int, first_px)));
+      nbL[u] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(addr_dn, __builtin_bit_cast(int, last_px)));
+    }
+    __syncthreads();
+    {
+      // all lanes read both neighbour-wave slots (in bounds for every wave), then select
+      const float* eln = EL + (par * NW + wave + 1) * 128 + lc;  // right neighbour's left edge
+      const float* erp = ER + (par * NW + wave - 1) * 128 + lc;  // left neighbour's right edge
+      const float mr = (wx + 1 < NWX) ? 1.f : 0.f, ml = (wx > 0) ? 1.f : 0.f;
+      const bool at_r = lg == 3, at_l = lg == 0;
+#pragma unroll
+      for (int u = 0; u < 9; ++u) {
+        if (u == 4) continue;
+        const float vr = eln[edge_slot(u) * 16] * mr;
+        const float vl = erp[edge_slot(u) * 16] * ml;
+        nbR[u] = at_r ? vr : nbR[u];
+        nbL[u] = at_l ? vl : nbL[u];
+      }
+    }
+
+    // ---- place the row of products at the rotated positions (Eq. 8) --------------
+    const int y = h - 1;                       // output row completed by this step
+    const bool fin = t >= 2 && y < g.H;
+    float best[8];
+    int bidx[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { best[j] = 0.f; bidx[j] = 0; }
+    bool first = true;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      float yfin[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        float t0 = 0.f, t1 = 0.f, t2 = 0.f;
+#pragma unroll
+        for (int u = 0; u < 9; ++u) {
+          const int jj = j + tap_j(s, u) - 1;
+          const float val = jj < 0 ? nbL[u] : jj > 7 ? nbR[u] : P[u][jj & 1][jj >> 1];
+          const int ti = tap_i(s, u);
+          if (ti == 0) t0 += val;
+          else if (ti == 1) t1 += val;
+          else t2 += val;
+        }
+        yfin[j] = accA[s][j] + t2;      // rows h-2, h-1, h are in: output row h-1 done
+        accA[s][j] = accB[s][j] + t1;   // output row h has rows h-1, h
+        accB[s][j] = t0;                // output row h+1 has row h
+      }
+      if (g.out_mode == kOutUnpooled) {
+        if (fin && rot[s] >= 0 && cb * 16 + lc < g.Cout) {
+          float* o = out_val + (((size_t)n * g.Cout + cb * 16 + lc) * g.R + rot[s]) * chan_stride + (size_t)y * g.W +
+                     x0 + 8 * lg;
+#pragma unroll
+          for (int j = 0; j < 8; ++j)
+            if (x0 + 8 * lg + j < g.W) o[j] = yfin[j];
+        }
+      } else if (rot[s] >= 0) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+          if (first || yfin[j] > best[j]) { best[j] = yfin[j]; bidx[j] = rot[s]; }
+        first = false;
+      }
+    }
+    if (g.out_mode != kOutUnpooled && fin && !first && cb * 16 + lc < g.Cout) {
+      const int co = cb * 16 + lc;
+      size_t chan;
+      if (g.out_mode == kOutPooled) {
+        // every rotation of this bank lies in pool group (r mod ng); pooled channel = co*ng + group
+        chan = (size_t)n * g.Cout * g.ng + (size_t)co * g.ng + (bidx[0] % g.ng);
+      } else {  // kOutPartial: per-bank candidates [Q][N][Cout][H][W]
+        chan = ((size_t)q * g.N + n) * g.Cout + co;
+      }
+      const size_t off = chan * chan_stride + (size_t)y * g.W + x0 + 8 * lg;
+      if ((g.W & 7) == 0) {
+        if (x0 + 8 * lg < g.W) {
+          f4* o = reinterpret_cast<f4*>(out_val + off);
+          o[0] = f4{best[0], best[1], best[2], best[3]};
+          o[1] = f4{best[4], best[5], best[6], best[7]};
+          uint2 pk;
+          pk.x = bidx[0] | (bidx[1] << 8) | (bidx[2] << 16) | (bidx[3] << 24);
+          pk.y = bidx[4] | (bidx[5] << 8) | (bidx[6] << 16) | (bidx[7] << 24);
+          *reinterpret_cast<uint2*>(out_idx + off) = pk;
+        }
+      } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+          if (x0 + 8 * lg + j < g.W) {
+            out_val[off + j] = best[j];
+            out_idx[off + j] = (uint8_t)bidx[j];
+          }
+      }
+    }
+  }
+}
+
+// Max over the per-bank candidates of a pool group that spans several banks.
+// Candidates [Q][N][Cout][HW]; group g of filter co collects banks q with (r mod ng) == g.
+__global__ __launch_bounds__(256) void k_p4_combine(const float* __restrict__ pv, const uint8_t* __restrict__ pi,
+                                                    const int32_t* __restrict__ rot_of, float* __restrict__ ypool,
+                                                    uint8_t* __restrict__ idx, int N, int Cout, int HW, int Q, int ng) {
+  const int p = blockIdx.x * 256 + threadIdx.x;
+  if (p >= HW) return;
+  const int chan = blockIdx.y, n = blockIdx.z;  // chan = co*ng + grp
+  const int co = chan / ng, grp = chan % ng;
+  float best = 0.f;
+  int bi = 255;
+  for (int q = 0; q < Q; ++q) {
+    int r0 = -1;
+    for (int s = 0; s < 4; ++s)
+      if (rot_of[q * 4 + s] >= 0) { r0 = rot_of[q * 4 + s]; break; }
+    if (r0 < 0 || r0 % ng != grp) continue;
+    const size_t o = (((size_t)q * N + n) * Cout + co) * HW + p;
+    const float vq = pv[o];
+    const int iq = pi[o];
+    if (bi == 255 || vq > best || (vq == best && iq < bi)) { best = vq; bi = iq; }
+  }
+  const size_t o = ((size_t)n * Cout * ng + chan) * HW + p;
+  ypool[o] = best;
+  idx[o] = (uint8_t)bi;
+}
+
+// base bank(s) -> Q first-quadrant banks in the LDS image layout [Q][CB][CinPad][9][16]
+// (zero for padded filters / channels).
+__global__ __launch_bounds__(256) void k_p4_pack_fwd(const float* __restrict__ w, float* __restrict__ wt,
+                                                     const int32_t* __restrict__ fq_src,
+                                                     const float* __restrict__ fq_coef, int Q, int CB, int CinPad,
+                                                     int Cin, int Cout) {
+  const int total = Q * CB * CinPad * 144;
+  const int e = blockIdx.x * 256 + threadIdx.x;
+  if (e >= total) return;
+  const int c16 = e % 16;
+  const int u = (e / 16) % 9;
+  const int ci = (e / 144) % CinPad;
+  const int cb = (e / (144 * CinPad)) % CB;
+  const int q = e / (144 * CinPad * CB);
+  const int co = cb * 16 + c16;
+  float acc = 0.f;
+  if (co < Cout && ci < Cin) {
+    const int slices = Cout * Cin;
+#pragma unroll
+    for (int z = 0; z < kMaxNnz; ++z) {
+      const int s = fq_src[(q * 9 + u) * kMaxNnz + z];
+      if (s >= 0) acc += fq_coef[(q * 9 + u) * kMaxNnz + z] * w[((s / 9) * slices + co * Cin + ci) * 9 + s % 9];
+    }
+  }
+  wt[e] = acc;
+}
+
+template <int NWX, int NWY>
+void launch_t(const P4Geom& g, const float* x, const float* wt, const int32_t* rot_of, float* ov, uint8_t* oi,
+              hipStream_t st) {
+  const size_t lds = ((size_t)g.CinPad * 144 + 4 * NWX * NWY * 128) * sizeof(float);
+  const int grid = (g.units + 7) / 8 * 8;
+  (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_p4_fwd<NWX, NWY>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                      (int)lds);
+  hipLaunchKernelGGL((k_p4_fwd<NWX, NWY>), dim3(grid), dim3(64 * NWX * NWY), lds, st, x, wt, rot_of, ov, oi, g);
+}
+
+}  // namespace
+
+bool p4_fwd_supported(const rotconv_plan* p) {
+  const rotconv_desc& d = p->d;
+  if (d.k != 3 || d.stride != 1 || d.pad != 1 || d.dtype != ROTCONV_F32) return false;
+  if (d.W > 256 || (d.W & 1)) return false;
+  const int CinPad = (d.Cin + 31) / 32 * 32;
+  if ((size_t)CinPad * 576 + 16384 > 160 * 1024) return false;
+  return true;
+}
+
+P4Geom p4_fwd_geom(const rotconv_plan* p, int out_mode) {
+  const rotconv_desc& d = p->d;
+  P4Geom g{};
+  g.N = d.N; g.Cin = d.Cin; g.CinPad = (d.Cin + 31) / 32 * 32; g.H = d.H; g.W = d.W; g.Cout = d.Cout;
+  g.CB = (d.Cout + 15) / 16; g.R = d.R; g.Q = p->host.Q; g.ng = p->ng; g.out_mode = out_mode;
+  int nwx = 1;
+  while (nwx * 32 < d.W) nwx *= 2;
+  g.nwx = nwx;
+  const int nwy = 8 / nwx;
+  long best_cost = -1;
+  for (int ty : {8, 16, 32, 64}) {
+    const int nbg = (d.H + nwy * ty - 1) / (nwy * ty);
+    const long units = (long)d.N * g.Q * g.CB * nbg;
+    const long cost = ((units + 255) / 256) * (ty + 2);
+    if (best_cost < 0 || cost <= best_cost) { best_cost = cost; g.TY = ty; g.nbg = nbg; g.units = (int)units; }
+  }
+  return g;
+}
+
+size_t p4_fwd_pack_floats(const rotconv_plan* p) {
+  const int CinPad = (p->d.Cin + 31) / 32 * 32;
+  return (size_t)p->host.Q * ((p->d.Cout + 15) / 16) * CinPad * 144;
+}
+
+// How the bank kernel delivers its result for this plan's pooling.
+int p4_fwd_pool_mode(const rotconv_plan* p) {
+  // every bank must fall into a single pool group: all its rotations share r mod ng
+  for (int q = 0; q < p->host.Q; ++q) {
+    int grp = -1;
+    for (int s = 0; s < 4; ++s) {
+      const int r = p->rot_of[q * 4 + s];
+      if (r < 0) continue;
+      if (grp < 0) grp = r % p->ng;
+      else if (grp != r % p->ng) return kOutUnpooled;
+    }
+  }
+  // does a group collect more than one bank?
+  return (p->host.Q > p->ng) ? kOutPartial : kOutPooled;
+}
+
+void launch_p4_pack_fwd(const rotconv_plan* p, const float* w, float* wt, hipStream_t st) {
+  const int CinPad = (p->d.Cin + 31) / 32 * 32, CB = (p->d.Cout + 15) / 16;
+  const int total = p->host.Q * CB * CinPad * 144;
+  hipLaunchKernelGGL(k_p4_pack_fwd, dim3((total + 255) / 256), dim3(256), 0, st, w, wt, p->dev.fq_src, p->dev.fq_coef,
+                     p->host.Q, CB, CinPad, p->d.Cin, p->d.Cout);
+}
+
+void launch_p4_fwd(const rotconv_plan* p, int out_mode, const float* x, const float* wt, float* out_val,
+                   uint8_t* out_idx, hipStream_t st) {
+  const P4Geom g = p4_fwd_geom(p, out_mode);
+  switch (g.nwx) {
+    case 1: launch_t<1, 8>(g, x, wt, p->dev.rot_of, out_val, out_idx, st); break;
+    case 2: launch_t<2, 4>(g, x, wt, p->dev.rot_of, out_val, out_idx, st); break;
+    case 4: launch_t<4, 2>(g, x, wt, p->dev.rot_of, out_val, out_idx, st); break;
+    default: launch_t<8, 1>(g, x, wt, p->dev.rot_of, out_val, out_idx, st); break;
+  }
+}
+
+void launch_p4_combine(const rotconv_plan* p, const float* pv, const uint8_t* pi, float* ypool, uint8_t* idx,
+                       hipStream_t st) {
+  const int HW = p->d.H * p->d.W;
+  dim3 grid((HW + 255) / 256, p->d.Cout * p->ng, p->d.N);
+  hipLaunchKernelGGL(k_p4_combine, grid, dim3(256), 0, st, pv, pi, p->dev.rot_of, ypool, idx, p->d.N, p->d.Cout, HW,
+                     p->host.Q, p->ng);
+}
+
+}  // namespace rotconv
