@@ -94,6 +94,8 @@ int rotconv_plan_create(const rotconv_desc* desc, rotconv_plan** out) {
   p->ws_bytes = generic_ws_bytes(p);
   p->fast[0] = p4_fwd_supported(p) ? 1 : 0;
   if (p->fast[0]) p->ws_bytes = std::max(p->ws_bytes, fwd_fast_ws_bytes(p));
+  p->fast[1] = p4_bwd_data_supported(p) ? 1 : 0;
+  if (p->fast[1]) p->ws_bytes = std::max(p->ws_bytes, p4_bwd_data_pack_floats(p) * sizeof(float));
   p->ws_bytes = align256(p->ws_bytes);
   *out = p;
   return ROTCONV_OK;
@@ -242,6 +244,12 @@ int rotconv_pool_bwd_data(const rotconv_plan* plan, const void* gpool, const uin
   rotconv_plan* p = const_cast<rotconv_plan*>(plan);
   if ((rc = ensure_device_tables(p))) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
+  if (p->fast[1] && aligned(gpool, 8) && aligned(idx, 2) && aligned(dx, 16) && aligned(ws, 16)) {
+    float* wd = static_cast<float*>(ws);
+    launch_p4_pack_bwd(p, static_cast<const float*>(w), wd, st);
+    launch_p4_bwd_data(p, static_cast<const float*>(gpool), idx, wd, static_cast<float*>(dx), st);
+    return finish();
+  }
   float* wexp = static_cast<float*>(ws);
   launch_expand_bank(p, static_cast<const float*>(w), wexp, st);
   launch_pool_bwd_data_generic(p, static_cast<const float*>(gpool), idx, wexp, static_cast<float*>(dx), st);

@@ -29,4 +29,19 @@ void launch_p4_fwd(const rotconv_plan* p, int out_mode, const float* x, const fl
 void launch_p4_combine(const rotconv_plan* p, const float* pv, const uint8_t* pi, float* ypool, uint8_t* idx,
                        hipStream_t st);
 
+// input gradient
+struct P4BwdGeom {
+  int N, Cin, CinPad, H, W, Cout, CoutPad, R, Q, ng;
+  int ncig;    // groups of 64 input channels
+  int nstrip;  // 32-pixel strips per row
+  int nrb;     // blocks of 8 rows
+  int units;
+};
+bool p4_bwd_data_supported(const rotconv_plan* p);
+P4BwdGeom p4_bwd_data_geom(const rotconv_plan* p);
+size_t p4_bwd_data_pack_floats(const rotconv_plan* p);
+void launch_p4_pack_bwd(const rotconv_plan* p, const float* w, float* wd, hipStream_t st);
+void launch_p4_bwd_data(const rotconv_plan* p, const float* gpool, const uint8_t* idx, const float* wd, float* dx,
+                        hipStream_t st);
+
 }  // namespace rotconv

@@ -1,0 +1,283 @@
+// Fast input-gradient kernel for 3x3, stride 1, pad 1 (fp32), fused with the
+// orientation max-pool backward (paper Eq. 12, 13, 15 in shared-product form).
+//
+//   dX[ci,h,x] = sum_q sum_u sum_co F_q[co,ci,u] * D^q_u[co,h,x]
+//   D^q_u[co,h,x] = sum_s Delta_(q,s)[co, h+1-i_s(u), x+1-j_s(u)],   (i_s,j_s) = R_s(u)
+//   Delta_r = G * 1[idx == r]
+//
+// i.e. the routed gradients of the four quarter turns of a bank are first summed
+// at the rotated tap positions (pure selects and adds on the VALU, done on the fly
+// in the MFMA A-operand layout, never stored), then ONE contraction over
+// (filter, tap) runs on the fp32 matrix cores: the multiplications are shared by
+// the four rotations exactly as in the forward pass.
+//
+// A wave owns one image row x 32 pixels x 64 input channels (four 16x16
+// accumulator tiles per 16-pixel block).  Per K-step of 4 filters a lane reads
+// the 3x4 pixel neighbourhood of (G, idx) of its filter straight from global
+// memory (L1/L2 resident: the eight waves of a workgroup take eight consecutive
+// rows), builds its 18 A values and feeds 72 MFMAs.  The weights stream through
+// LDS in chunks of 16 filters, double-buffered, one barrier per chunk.
+#include <hip/hip_runtime.h>
+
+#include "rotconv_kernels.h"
+#include "rotconv_p4.h"
+
+namespace rotconv {
+namespace {
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+
+constexpr int NCB = 4;                 // 16-channel blocks per wave
+constexpr int CIG = 16 * NCB;          // input channels per workgroup
+constexpr int WROW = 9 * CIG + 16;     // LDS floats per filter row (padded: conflict-free B reads)
+constexpr int CHUNK = 16;              // filters per LDS chunk
+constexpr int NWAVE = 8;
+constexpr int NT = 64 * NWAVE;
+
+__device__ __host__ constexpr int tap_i(int s, int u) {
+  return s == 0 ? u / 3 : s == 1 ? 2 - u % 3 : s == 2 ? 2 - u / 3 : u % 3;
+}
+__device__ __host__ constexpr int tap_j(int s, int u) {
+  return s == 0 ? u % 3 : s == 1 ? u / 3 : s == 2 ? 2 - u % 3 : 2 - u / 3;
+}
+
+struct Raw {           // (G, idx) of one filter on a 3 x 4 pixel neighbourhood
+  float g[3][4];
+  uint32_t i[3];       // four idx bytes per row, byte p = pixel p of the neighbourhood
+};
+
+__global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gpool, const uint8_t* __restrict__ idx,
+                                                    const float* __restrict__ wd,
+                                                    const int32_t* __restrict__ rot_of, float* __restrict__ dx,
+                                                    P4BwdGeom g) {
+  extern __shared__ float smem[];      // [2][CHUNK][WROW]
+
+  const int per_xcd = (g.units + 7) / 8;
+  int v = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  if (v >= g.units) return;
+  const int cig = v % g.ncig; v /= g.ncig;
+  const int strip = v % g.nstrip; v /= g.nstrip;
+  const int rb = v % g.nrb;
+  const int n = v / g.nrb;
+
+  const int tid = threadIdx.x;
+  const int wave = tid / 64, lane = tid % 64;
+  const int lg = lane / 16, lc = lane % 16;
+  const int h = rb * NWAVE + wave;
+  const int x0 = strip * 32;
+  const bool active = h < g.H;
+  const int HW = g.H * g.W;
+  const int nkq = g.CoutPad / 4;               // K-steps per bank
+  const int nk = g.Q * nkq;                    // K-steps in total
+  const int nchunks = nk / 4;
+
+  // ---- weight chunk streaming -----------------------------------------------------
+  constexpr int N4 = CHUNK * 9 * (CIG / 4);    // float4 per chunk
+  constexpr int WPT = (N4 + NT - 1) / NT;      // float4 per thread
+  f4 wreg[WPT];
+  auto wload = [&](int cc) {
+#pragma unroll
+    for (int k = 0; k < WPT; ++k) {
+      const int e = tid + k * NT;
+      if (e < N4) {
+        const int c4 = e % (CIG / 4), u = (e / (CIG / 4)) % 9, r = e / (9 * (CIG / 4));
+        wreg[k] = *reinterpret_cast<const f4*>(wd + ((size_t)(cc * CHUNK + r) * 9 + u) * g.CinPad + cig * CIG + c4 * 4);
+      }
+    }
+  };
+  auto wstore = [&](int buf) {
+    float* dst = smem + buf * CHUNK * WROW;
+#pragma unroll
+    for (int k = 0; k < WPT; ++k) {
+      const int e = tid + k * NT;
+      if (e < N4) {
+        const int c4 = e % (CIG / 4), u = (e / (CIG / 4)) % 9, r = e / (9 * (CIG / 4));
+        *reinterpret_cast<f4*>(dst + r * WROW + u * CIG + c4 * 4) = wreg[k];
+      }
+    }
+  };
+
+  // ---- (G, idx) neighbourhood loads -------------------------------------------------
+  const int xa = x0 + 2 * lc;                  // first of this lane's two pixels
+  auto raw_load = [&](int kk, Raw& r) {
+    const int q = kk / nkq;
+    const int co = (kk % nkq) * 4 + lg;
+    int r0 = -1;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const int rs = rot_of[q * 4 + s];
+      if (r0 < 0 && rs >= 0) r0 = rs;
+    }
+    const bool cok = active && co < g.Cout && r0 >= 0;
+    const size_t plane = ((size_t)n * g.Cout * g.ng + (size_t)co * g.ng + (r0 < 0 ? 0 : r0 % g.ng)) * HW;
+#pragma unroll
+    for (int dr = 0; dr < 3; ++dr) {
+      const int row = h - 1 + dr;
+      const bool rok = cok && row >= 0 && row < g.H;
+      const size_t base = plane + (size_t)row * g.W + xa;
+      const bool okc = rok && xa < g.W, okl = rok && xa >= 1 && xa - 1 < g.W, okr = rok && xa + 2 < g.W;
+      float2 gc = make_float2(0.f, 0.f);
+      uint32_t ic = 0xffffu;
+      if (okc) {
+        gc = *reinterpret_cast<const float2*>(gpool + base);
+        ic = *reinterpret_cast<const uint16_t*>(idx + base);
+      }
+      r.g[dr][1] = gc.x;
+      r.g[dr][2] = gc.y;
+      r.g[dr][0] = okl ? gpool[base - 1] : 0.f;
+      r.g[dr][3] = okr ? gpool[base + 2] : 0.f;
+      const uint32_t il = okl ? idx[base - 1] : 0xffu;
+      const uint32_t ir = okr ? idx[base + 2] : 0xffu;
+      r.i[dr] = il | (ic << 8) | (ir << 24);
+    }
+  };
+
+  f4 acc[NCB][2];
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb) { acc[cb][0] = f4{0.f, 0.f, 0.f, 0.f}; acc[cb][1] = f4{0.f, 0.f, 0.f, 0.f}; }
+
+  Raw cur, nxt;
+  raw_load(0, cur);
+  wload(0);
+  wstore(0);
+  __syncthreads();
+
+  for (int cc = 0; cc < nchunks; ++cc) {
+    if (cc + 1 < nchunks) wload(cc + 1);
+    const float* wl = smem + (cc & 1) * CHUNK * WROW + lg * WROW + lc;
+    const int q = (cc * 4) / nkq;
+    int rot[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) rot[s] = rot_of[q * 4 + s];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      const int kk = cc * 4 + ks;
+      if (kk + 1 < nk) raw_load(kk + 1, nxt);
+      // Delta_s on the neighbourhood, then the nine tap sums for the lane's two pixels
+      float a[9][2];
+#pragma unroll
+      for (int u = 0; u < 9; ++u) { a[u][0] = 0.f; a[u][1] = 0.f; }
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        if (rot[s] < 0) continue;
+        float d[3][4];
+#pragma unroll
+        for (int dr = 0; dr < 3; ++dr)
+#pragma unroll
+          for (int p = 0; p < 4; ++p)
+            d[dr][p] = (((cur.i[dr] >> (8 * p)) & 0xffu) == (uint32_t)rot[s]) ? cur.g[dr][p] : 0.f;
+#pragma unroll
+        for (int u = 0; u < 9; ++u) {
+          a[u][0] += d[2 - tap_i(s, u)][2 - tap_j(s, u)];
+          a[u][1] += d[2 - tap_i(s, u)][3 - tap_j(s, u)];
+        }
+      }
+      if (active) {
+#pragma unroll
+        for (int u = 0; u < 9; ++u) {
+          float bw[NCB];
+#pragma unroll
+          for (int cb = 0; cb < NCB; ++cb) bw[cb] = wl[(ks * 4) * WROW + u * CIG + cb * 16];
+#pragma unroll
+          for (int cb = 0; cb < NCB; ++cb) {
+            acc[cb][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u][0], bw[cb], acc[cb][0], 0, 0, 0);
+            acc[cb][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u][1], bw[cb], acc[cb][1], 0, 0, 0);
+          }
+        }
+      }
+      cur = nxt;
+    }
+    if (cc + 1 < nchunks) wstore((cc + 1) & 1);
+    __syncthreads();
+  }
+
+  // ---- store: lane (lg, lc) holds channel cb*16+lc, pixels x0 + 8*lg + j, j = 2*i + b ----
+  if (!active) return;
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb) {
+    const int ci = cig * CIG + cb * 16 + lc;
+    if (ci >= g.Cin) continue;
+    const int px = x0 + 8 * lg;
+    float* o = dx + ((size_t)n * g.Cin + ci) * HW + (size_t)h * g.W + px;
+    float vals[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) vals[j] = acc[cb][j & 1][j >> 1];
+    if ((g.W & 7) == 0) {
+      if (px < g.W) {
+        reinterpret_cast<f4*>(o)[0] = f4{vals[0], vals[1], vals[2], vals[3]};
+        reinterpret_cast<f4*>(o)[1] = f4{vals[4], vals[5], vals[6], vals[7]};
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        if (px + j < g.W) o[j] = vals[j];
+    }
+  }
+}
+
+// base bank(s) -> Q first-quadrant banks laid out [Q][CoutPad][9][CinPad] (zero padded).
+__global__ __launch_bounds__(256) void k_p4_pack_bwd(const float* __restrict__ w, float* __restrict__ wd,
+                                                     const int32_t* __restrict__ fq_src,
+                                                     const float* __restrict__ fq_coef, int Q, int CoutPad,
+                                                     int CinPad, int Cin, int Cout) {
+  const int total = Q * CoutPad * 9 * CinPad;
+  const int e = blockIdx.x * 256 + threadIdx.x;
+  if (e >= total) return;
+  const int ci = e % CinPad;
+  const int u = (e / CinPad) % 9;
+  const int co = (e / (9 * CinPad)) % CoutPad;
+  const int q = e / (9 * CinPad * CoutPad);
+  float acc = 0.f;
+  if (co < Cout && ci < Cin) {
+    const int slices = Cout * Cin;
+#pragma unroll
+    for (int z = 0; z < kMaxNnz; ++z) {
+      const int s = fq_src[(q * 9 + u) * kMaxNnz + z];
+      if (s >= 0) acc += fq_coef[(q * 9 + u) * kMaxNnz + z] * w[((s / 9) * slices + co * Cin + ci) * 9 + s % 9];
+    }
+  }
+  wd[e] = acc;
+}
+
+}  // namespace
+
+bool p4_bwd_data_supported(const rotconv_plan* p) {
+  const rotconv_desc& d = p->d;
+  if (d.k != 3 || d.stride != 1 || d.pad != 1 || d.dtype != ROTCONV_F32) return false;
+  if (d.W & 1) return false;
+  return p4_fwd_pool_mode(p) != kOutUnpooled;  // every bank inside one pool group
+}
+
+P4BwdGeom p4_bwd_data_geom(const rotconv_plan* p) {
+  const rotconv_desc& d = p->d;
+  P4BwdGeom g{};
+  g.N = d.N; g.Cin = d.Cin; g.CinPad = (d.Cin + CIG - 1) / CIG * CIG; g.H = d.H; g.W = d.W; g.Cout = d.Cout;
+  g.CoutPad = (d.Cout + 15) / 16 * 16; g.R = d.R; g.Q = p->host.Q; g.ng = p->ng;
+  g.ncig = g.CinPad / CIG; g.nstrip = (d.W + 31) / 32; g.nrb = (d.H + NWAVE - 1) / NWAVE;
+  g.units = d.N * g.ncig * g.nstrip * g.nrb;
+  return g;
+}
+
+size_t p4_bwd_data_pack_floats(const rotconv_plan* p) {
+  const P4BwdGeom g = p4_bwd_data_geom(p);
+  return (size_t)g.Q * g.CoutPad * 9 * g.CinPad;
+}
+
+void launch_p4_pack_bwd(const rotconv_plan* p, const float* w, float* wd, hipStream_t st) {
+  const P4BwdGeom g = p4_bwd_data_geom(p);
+  const int total = g.Q * g.CoutPad * 9 * g.CinPad;
+  hipLaunchKernelGGL(k_p4_pack_bwd, dim3((total + 255) / 256), dim3(256), 0, st, w, wd, p->dev.fq_src, p->dev.fq_coef,
+                     g.Q, g.CoutPad, g.CinPad, g.Cin, g.Cout);
+}
+
+void launch_p4_bwd_data(const rotconv_plan* p, const float* gpool, const uint8_t* idx, const float* wd, float* dx,
+                        hipStream_t st) {
+  const P4BwdGeom g = p4_bwd_data_geom(p);
+  const size_t lds = (size_t)2 * CHUNK * WROW * sizeof(float);
+  const int grid = (g.units + 7) / 8 * 8;
+  (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_p4_bwd_data), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)lds);
+  hipLaunchKernelGGL(k_p4_bwd_data, dim3(grid), dim3(NT), lds, st, gpool, idx, wd, p->dev.rot_of, dx, g);
+}
+
+}  // namespace rotconv
