@@ -96,6 +96,8 @@ int rotconv_plan_create(const rotconv_desc* desc, rotconv_plan** out) {
   if (p->fast[0]) p->ws_bytes = std::max(p->ws_bytes, fwd_fast_ws_bytes(p));
   p->fast[1] = p4_bwd_data_supported(p) ? 1 : 0;
   if (p->fast[1]) p->ws_bytes = std::max(p->ws_bytes, p4_bwd_data_pack_floats(p) * sizeof(float));
+  p->fast[2] = p4_bwd_weight_supported(p) ? 1 : 0;
+  if (p->fast[2]) p->ws_bytes = std::max(p->ws_bytes, p4_bwd_weight_ws_floats(p) * sizeof(float));
   p->ws_bytes = align256(p->ws_bytes);
   *out = p;
   return ROTCONV_OK;
@@ -264,6 +266,11 @@ int rotconv_pool_bwd_weight(const rotconv_plan* plan, const void* x, const void*
   rotconv_plan* p = const_cast<rotconv_plan*>(plan);
   if ((rc = ensure_device_tables(p))) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
+  if (p->fast[2] && aligned(x, 16) && aligned(gpool, 16) && aligned(idx, 4) && aligned(ws, 16)) {
+    launch_p4_bwd_weight(p, static_cast<const float*>(x), static_cast<const float*>(gpool), idx,
+                         static_cast<float*>(ws), dw, st);
+    return finish();
+  }
   launch_bwd_weight_generic(p, static_cast<const float*>(x), nullptr, static_cast<const float*>(gpool), idx,
                             static_cast<float*>(ws), dw, st);
   return finish();

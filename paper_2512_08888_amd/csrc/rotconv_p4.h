@@ -44,4 +44,17 @@ void launch_p4_pack_bwd(const rotconv_plan* p, const float* w, float* wd, hipStr
 void launch_p4_bwd_data(const rotconv_plan* p, const float* gpool, const uint8_t* idx, const float* wd, float* dx,
                         hipStream_t st);
 
+// weight gradient
+struct P4BwdWGeom {
+  int N, Cin, CinPad, H, W, Cout, CoutPad, Q, ng;
+  int ncig;    // groups of 64 input channels
+  int ncog;    // groups of 64 filters (one workgroup of 4 waves)
+  int splits;  // ranges of image rows, summed afterwards in order
+};
+bool p4_bwd_weight_supported(const rotconv_plan* p);
+P4BwdWGeom p4_bwd_weight_geom(const rotconv_plan* p);
+size_t p4_bwd_weight_ws_floats(const rotconv_plan* p);
+void launch_p4_bwd_weight(const rotconv_plan* p, const float* x, const float* gpool, const uint8_t* idx,
+                          float* partial, float* dw, hipStream_t st);
+
 }  // namespace rotconv
