@@ -76,12 +76,14 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_weight(const float* __restrict__ 
   const int row_begin = split * rows_per;
   const int row_end = min(rows_total, row_begin + rows_per);
   const int w16 = (g.W + 15) / 16;
-  const int niter = max(0, row_end - row_begin) * w16;
+  const int nrows = max(0, row_end - row_begin);
+  const int niter = nrows * w16;
 
   auto load = [&](int it, RawW& r, f4 (&b)[NCB]) {
-    const int row = row_begin + it / w16;
+    // rows run fastest: consecutive iterations re-read two of their three (G, idx) rows from L1
+    const int row = row_begin + it % nrows;
     const int n = row / g.H, h = row % g.H;
-    const int px = (it % w16) * 16 + 4 * lg;
+    const int px = (it / nrows) * 16 + 4 * lg;
     const bool pok = px < g.W;                       // W % 4 == 0: the four pixels are in or out together
 #pragma unroll
     for (int cb = 0; cb < NCB; ++cb) {
@@ -184,14 +186,32 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_weight(const float* __restrict__ 
   }
 }
 
-// Sum the splits in order, then the transposed first-quadrant expansion (Eq. 16 / adjoint of
-// Eq. 17): dw[b][co][ci][ub] = sum_z coef_z * sum_split partial[split][q_z][t_z][co][ci].
-__global__ __launch_bounds__(256) void k_p4_reduce_w(const float* __restrict__ partial, float* __restrict__ dw,
+// Stage 1: sum the splits.  A block covers 32 consecutive elements x 8 interleaved split groups;
+// each thread adds its splits in ascending order, the groups are combined in a fixed tree, so
+// the result does not depend on scheduling.  out[e] = sum_split partial[split][e].
+__global__ __launch_bounds__(256) void k_p4_sum_splits(const float* __restrict__ partial, float* __restrict__ out,
+                                                       int n_elem, int splits) {
+  __shared__ float red[8][32];
+  const int e = blockIdx.x * 32 + (threadIdx.x % 32);
+  const int grp = threadIdx.x / 32;
+  float s = 0.f;
+  if (e < n_elem)
+    for (int sp = grp; sp < splits; sp += 8) s += partial[(size_t)sp * n_elem + e];
+  red[grp][threadIdx.x % 32] = s;
+  __syncthreads();
+  if (grp == 0 && e < n_elem) {
+    const int l = threadIdx.x;
+    out[e] = ((red[0][l] + red[1][l]) + (red[2][l] + red[3][l])) + ((red[4][l] + red[5][l]) + (red[6][l] + red[7][l]));
+  }
+}
+
+// Stage 2: the transposed first-quadrant expansion (Eq. 16 / adjoint of Eq. 17):
+// dw[b][co][ci][ub] = sum_z coef_z * dF[q_z][t_z][co][ci].
+__global__ __launch_bounds__(256) void k_p4_reduce_w(const float* __restrict__ dF, float* __restrict__ dw,
                                                      const int32_t* __restrict__ fqt_ptr,
                                                      const int32_t* __restrict__ fqt_col,
                                                      const float* __restrict__ fqt_coef, int B, int Cout, int Cin,
-                                                     int CoutPad, int CinPad, int Q, int splits) {
-  // thread -> (b, ub, co, ci) with ci fastest so partial reads are coalesced
+                                                     int CoutPad, int CinPad) {
   const int total = B * 9 * Cout * Cin;
   const int e = blockIdx.x * 256 + threadIdx.x;
   if (e >= total) return;
@@ -201,13 +221,8 @@ __global__ __launch_bounds__(256) void k_p4_reduce_w(const float* __restrict__ p
   const int b = e / (Cin * Cout * 9);
   const size_t plane = (size_t)CoutPad * CinPad;
   float acc = 0.f;
-  for (int z = fqt_ptr[b * 9 + ub]; z < fqt_ptr[b * 9 + ub + 1]; ++z) {
-    const int col = fqt_col[z];  // q*9 + t
-    const float* src = partial + (size_t)col * plane + (size_t)co * CinPad + ci;
-    float s = 0.f;
-    for (int sp = 0; sp < splits; ++sp) s += src[(size_t)sp * Q * 9 * plane];
-    acc += fqt_coef[z] * s;
-  }
+  for (int z = fqt_ptr[b * 9 + ub]; z < fqt_ptr[b * 9 + ub + 1]; ++z)
+    acc += fqt_coef[z] * dF[(size_t)fqt_col[z] * plane + (size_t)co * CinPad + ci];
   dw[(((size_t)b * Cout + co) * Cin + ci) * 9 + ub] = acc;
 }
 
@@ -230,7 +245,7 @@ P4BwdWGeom p4_bwd_weight_geom(const rotconv_plan* p) {
   g.ncog = g.CoutPad / (16 * NWAVE);
   const int combos = g.Q * g.ncig * g.ncog;
   const int rows = d.N * d.H;
-  int splits = (512 + combos - 1) / combos;
+  int splits = (256 + combos - 1) / combos;
   splits = std::min(splits, rows);
   // keep the partial sums below 256 MiB
   const double per = 4.0 * g.Q * 9.0 * g.CoutPad * g.CinPad;
@@ -243,7 +258,7 @@ P4BwdWGeom p4_bwd_weight_geom(const rotconv_plan* p) {
 
 size_t p4_bwd_weight_ws_floats(const rotconv_plan* p) {
   const P4BwdWGeom g = p4_bwd_weight_geom(p);
-  return (size_t)g.splits * g.Q * 9 * g.CoutPad * g.CinPad;
+  return (size_t)(g.splits + 1) * g.Q * 9 * g.CoutPad * g.CinPad;  // partial sums + their total
 }
 
 void launch_p4_bwd_weight(const rotconv_plan* p, const float* x, const float* gpool, const uint8_t* idx,
@@ -251,9 +266,12 @@ void launch_p4_bwd_weight(const rotconv_plan* p, const float* x, const float* gp
   const P4BwdWGeom g = p4_bwd_weight_geom(p);
   const int grid = g.splits * g.ncig * g.ncog * g.Q;
   hipLaunchKernelGGL(k_p4_bwd_weight, dim3(grid), dim3(NT), 0, st, x, gpool, idx, p->dev.rot_of, partial, g);
+  const int n_elem = g.Q * 9 * g.CoutPad * g.CinPad;
+  float* dF = partial + (size_t)g.splits * n_elem;
+  hipLaunchKernelGGL(k_p4_sum_splits, dim3((n_elem + 31) / 32), dim3(256), 0, st, partial, dF, n_elem, g.splits);
   const int total = p->B * 9 * g.Cout * g.Cin;
-  hipLaunchKernelGGL(k_p4_reduce_w, dim3((total + 255) / 256), dim3(256), 0, st, partial, dw, p->dev.fqt_ptr,
-                     p->dev.fqt_col, p->dev.fqt_coef, p->B, g.Cout, g.Cin, g.CoutPad, g.CinPad, g.Q, g.splits);
+  hipLaunchKernelGGL(k_p4_reduce_w, dim3((total + 255) / 256), dim3(256), 0, st, dF, dw, p->dev.fqt_ptr,
+                     p->dev.fqt_col, p->dev.fqt_coef, p->B, g.Cout, g.Cin, g.CoutPad, g.CinPad);
 }
 
 }  // namespace rotconv
