@@ -97,38 +97,54 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gp
     }
   };
 
-  // ---- (G, idx) neighbourhood loads -------------------------------------------------
+  // ---- (G, idx) neighbourhood loads: branch-free (out-of-range positions read a safe address and
+  // are masked; an idx byte of 0xff matches no orientation), so a K-step is one basic block --------
   const int xa = x0 + 2 * lc;                  // first of this lane's two pixels
   auto raw_load = [&](int kk, Raw& r) {
+    kk = min(kk, nk - 1);
     const int q = kk / nkq;
     const int co = (kk % nkq) * 4 + lg;
     int r0 = -1;
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
       const int rs = rot_of[q * 4 + s];
-      if (r0 < 0 && rs >= 0) r0 = rs;
+      r0 = (r0 < 0 && rs >= 0) ? rs : r0;
     }
     const bool cok = active && co < g.Cout && r0 >= 0;
-    const size_t plane = ((size_t)n * g.Cout * g.ng + (size_t)co * g.ng + (r0 < 0 ? 0 : r0 % g.ng)) * HW;
+    const size_t plane = ((size_t)n * g.Cout * g.ng + (size_t)(cok ? co : 0) * g.ng + (r0 < 0 ? 0 : r0 % g.ng)) * HW;
 #pragma unroll
     for (int dr = 0; dr < 3; ++dr) {
       const int row = h - 1 + dr;
       const bool rok = cok && row >= 0 && row < g.H;
-      const size_t base = plane + (size_t)row * g.W + xa;
+      const size_t base = plane + (size_t)(rok ? row : 0) * g.W + xa;
       const bool okc = rok && xa < g.W, okl = rok && xa >= 1 && xa - 1 < g.W, okr = rok && xa + 2 < g.W;
-      float2 gc = make_float2(0.f, 0.f);
-      uint32_t ic = 0xffffu;
-      if (okc) {
-        gc = *reinterpret_cast<const float2*>(gpool + base);
-        ic = *reinterpret_cast<const uint16_t*>(idx + base);
-      }
+      const size_t bc = okc ? base : 0, bl = okl ? base - 1 : 0, br = okr ? base + 2 : 0;
+      const float2 gc = *reinterpret_cast<const float2*>(gpool + bc);
+      const uint32_t ic = *reinterpret_cast<const uint16_t*>(idx + bc);
+      const float gl = gpool[bl], gr = gpool[br];
+      const uint32_t il = idx[bl], ir = idx[br];
+      r.g[dr][0] = gl;
       r.g[dr][1] = gc.x;
       r.g[dr][2] = gc.y;
-      r.g[dr][0] = okl ? gpool[base - 1] : 0.f;
-      r.g[dr][3] = okr ? gpool[base + 2] : 0.f;
-      const uint32_t il = okl ? idx[base - 1] : 0xffu;
-      const uint32_t ir = okr ? idx[base + 2] : 0xffu;
-      r.i[dr] = il | (ic << 8) | (ir << 24);
+      r.g[dr][3] = gr;
+      r.i[dr] = (okl ? il : 0xffu) | ((okc ? ic : 0xffffu) << 8) | ((okr ? ir : 0xffu) << 24);
+    }
+  };
+
+  // One quarter turn's share of the nine tap sums for the lane's two pixels (Eq. 12 + the rotated
+  // tap positions of Eq. 8): Delta_s on the neighbourhood, added where R_s puts each base tap.
+  auto build_slice = [&](const Raw& r, int s, int rs, float (&a)[9][2]) {
+    float d[3][4];
+#pragma unroll
+    for (int dr = 0; dr < 3; ++dr)
+#pragma unroll
+      for (int p = 0; p < 4; ++p)
+        d[dr][p] = (((r.i[dr] >> (8 * p)) & 0xffu) == (uint32_t)rs) ? r.g[dr][p] : 0.f;
+#pragma unroll
+    for (int u = 0; u < 9; ++u) {
+      const float t0 = d[2 - tap_i(s, u)][2 - tap_j(s, u)], t1 = d[2 - tap_i(s, u)][3 - tap_j(s, u)];
+      a[u][0] = s == 0 ? t0 : a[u][0] + t0;
+      a[u][1] = s == 0 ? t1 : a[u][1] + t1;
     }
   };
 
@@ -136,8 +152,39 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gp
 #pragma unroll
   for (int cb = 0; cb < NCB; ++cb) { acc[cb][0] = f4{0.f, 0.f, 0.f, 0.f}; acc[cb][1] = f4{0.f, 0.f, 0.f, 0.f}; }
 
-  Raw cur, nxt;
-  raw_load(0, cur);
+  // Three-stage pipeline over K-steps: (G, idx) loads two steps ahead, A build one step ahead and
+  // spread between the MFMAs of the current step, B reads from LDS one tap ahead.
+  Raw rawA, rawB;
+  float aA[9][2], aB[9][2];
+  int rotq[4];
+  auto stage = [&](int kk, int ks, const float* wl, const Raw& raw_use, Raw& raw_ld, const float (&a_cur)[9][2],
+                   float (&a_nxt)[9][2]) {
+    raw_load(kk + 2, raw_ld);
+    const int qn = min(kk + 1, nk - 1) / nkq;      // bank of the step being built
+    float bw[2][NCB];
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) bw[0][cb] = wl[(ks * 4) * WROW + cb * 16];
+#pragma unroll
+    for (int u = 0; u < 9; ++u) {
+      if (u < 8) {
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb) bw[(u + 1) & 1][cb] = wl[(ks * 4) * WROW + (u + 1) * CIG + cb * 16];
+      }
+#pragma unroll
+      for (int cb = 0; cb < NCB; ++cb) {
+        acc[cb][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur[u][0], bw[u & 1][cb], acc[cb][0], 0, 0, 0);
+        acc[cb][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur[u][1], bw[u & 1][cb], acc[cb][1], 0, 0, 0);
+      }
+      if ((u & 1) == 0 && u < 8) build_slice(raw_use, u / 2, rot_of[qn * 4 + u / 2], a_nxt);
+    }
+  };
+
+  raw_load(0, rawB);
+#pragma unroll
+  for (int s = 0; s < 4; ++s) rotq[s] = rot_of[s];
+#pragma unroll
+  for (int s = 0; s < 4; ++s) build_slice(rawB, s, rotq[s], aA);
+  raw_load(1, rawA);
   wload(0);
   wstore(0);
   __syncthreads();
@@ -145,48 +192,10 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gp
   for (int cc = 0; cc < nchunks; ++cc) {
     if (cc + 1 < nchunks) wload(cc + 1);
     const float* wl = smem + (cc & 1) * CHUNK * WROW + lg * WROW + lc;
-    const int q = (cc * 4) / nkq;
-    int rot[4];
-#pragma unroll
-    for (int s = 0; s < 4; ++s) rot[s] = rot_of[q * 4 + s];
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      const int kk = cc * 4 + ks;
-      if (kk + 1 < nk) raw_load(kk + 1, nxt);
-      // Delta_s on the neighbourhood, then the nine tap sums for the lane's two pixels
-      float a[9][2];
-#pragma unroll
-      for (int u = 0; u < 9; ++u) { a[u][0] = 0.f; a[u][1] = 0.f; }
-#pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        if (rot[s] < 0) continue;
-        float d[3][4];
-#pragma unroll
-        for (int dr = 0; dr < 3; ++dr)
-#pragma unroll
-          for (int p = 0; p < 4; ++p)
-            d[dr][p] = (((cur.i[dr] >> (8 * p)) & 0xffu) == (uint32_t)rot[s]) ? cur.g[dr][p] : 0.f;
-#pragma unroll
-        for (int u = 0; u < 9; ++u) {
-          a[u][0] += d[2 - tap_i(s, u)][2 - tap_j(s, u)];
-          a[u][1] += d[2 - tap_i(s, u)][3 - tap_j(s, u)];
-        }
-      }
-      if (active) {
-#pragma unroll
-        for (int u = 0; u < 9; ++u) {
-          float bw[NCB];
-#pragma unroll
-          for (int cb = 0; cb < NCB; ++cb) bw[cb] = wl[(ks * 4) * WROW + u * CIG + cb * 16];
-#pragma unroll
-          for (int cb = 0; cb < NCB; ++cb) {
-            acc[cb][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u][0], bw[cb], acc[cb][0], 0, 0, 0);
-            acc[cb][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u][1], bw[cb], acc[cb][1], 0, 0, 0);
-          }
-        }
-      }
-      cur = nxt;
-    }
+    stage(cc * 4 + 0, 0, wl, rawA, rawB, aA, aB);
+    stage(cc * 4 + 1, 1, wl, rawB, rawA, aB, aA);
+    stage(cc * 4 + 2, 2, wl, rawA, rawB, aA, aB);
+    stage(cc * 4 + 3, 3, wl, rawB, rawA, aB, aA);
     if (cc + 1 < nchunks) wstore((cc + 1) & 1);
     __syncthreads();
   }
