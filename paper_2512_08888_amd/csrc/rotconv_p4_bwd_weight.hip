@@ -79,64 +79,67 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_weight(const float* __restrict__ 
   const int nrows = max(0, row_end - row_begin);
   const int niter = nrows * w16;
 
-  auto load = [&](int it, RawW& r, f4 (&b)[NCB]) {
-    // rows run fastest: consecutive iterations re-read two of their three (G, idx) rows from L1
-    const int row = row_begin + it % nrows;
+  // Branch-free loads (out-of-range positions read a safe address and are masked; an idx byte of
+  // 0xff matches no orientation), so that a pipeline stage is one basic block.
+  auto load_b = [&](int it, f4 (&b)[NCB]) {
+    it = min(it, niter - 1);
+    const int row = row_begin + it % nrows;   // rows run fastest: (G, idx) rows are re-read from L1
     const int n = row / g.H, h = row % g.H;
     const int px = (it / nrows) * 16 + 4 * lg;
-    const bool pok = px < g.W;                       // W % 4 == 0: the four pixels are in or out together
+    const bool pok = px < g.W;                // W % 4 == 0: the four pixels are in or out together
+    const size_t off = (size_t)n * g.Cin * HW + (size_t)h * g.W + (pok ? px : 0);
 #pragma unroll
     for (int cb = 0; cb < NCB; ++cb) {
       const int ci = ci0 + cb * 16;
-      if (pok && ci < g.Cin)
-        b[cb] = *reinterpret_cast<const f4*>(x + ((size_t)n * g.Cin + ci) * HW + (size_t)h * g.W + px);
-      else
-        b[cb] = f4{0.f, 0.f, 0.f, 0.f};
+      const bool ok = pok && ci < g.Cin;
+      const f4 val = *reinterpret_cast<const f4*>(x + off + (size_t)(ci < g.Cin ? ci : 0) * HW);
+      b[cb] = ok ? val : f4{0.f, 0.f, 0.f, 0.f};
     }
+  };
+  auto load_raw = [&](int it, RawW& r) {
+    it = min(it, niter - 1);
+    const int row = row_begin + it % nrows;
+    const int n = row / g.H, h = row % g.H;
+    const int px = (it / nrows) * 16 + 4 * lg;
+    const bool pok = px < g.W;
+    const int pc = pok ? px : 0, pl = max(px - 1, 0), pr = min(px + 4, g.W - 1);
+    const bool lok = px >= 1 && px - 1 < g.W, rok2 = px + 4 < g.W;
 #pragma unroll
     for (int dr = 0; dr < 3; ++dr) {
       const int rr = h - 1 + dr;
       const bool rok = cok && rr >= 0 && rr < g.H;
-      const size_t base = (size_t)n * gimg + gplane0 + (size_t)rr * g.W + px;
-      const bool okc = rok && pok, okl = rok && px >= 1 && px - 1 < g.W, okr = rok && px + 4 < g.W;
-      f4 gc = f4{0.f, 0.f, 0.f, 0.f};
-      uint32_t ic = 0xffffffffu;
-      if (okc) {
-        gc = *reinterpret_cast<const f4*>(gpool + base);
-        ic = *reinterpret_cast<const uint32_t*>(idx + base);
-      }
+      const size_t rowbase = (size_t)n * gimg + gplane0 + (size_t)(rok ? rr : 0) * g.W;
+      const f4 gc = *reinterpret_cast<const f4*>(gpool + rowbase + pc);
+      const uint32_t ic = *reinterpret_cast<const uint32_t*>(idx + rowbase + pc);
+      const float gl = gpool[rowbase + pl], gr = gpool[rowbase + pr];
+      const uint32_t il = idx[rowbase + pl], ir = idx[rowbase + pr];
       r.g[dr][1] = gc[0]; r.g[dr][2] = gc[1]; r.g[dr][3] = gc[2]; r.g[dr][4] = gc[3];
-      r.g[dr][0] = okl ? gpool[base - 1] : 0.f;
-      r.g[dr][5] = okr ? gpool[base + 4] : 0.f;
-      const uint32_t il = okl ? idx[base - 1] : 0xffu;
-      const uint32_t ir = okr ? idx[base + 4] : 0xffu;
-      r.ic[dr] = ic;
-      r.ie[dr] = il | (ir << 8);
+      r.g[dr][0] = gl;
+      r.g[dr][5] = gr;
+      r.ic[dr] = (rok && pok) ? ic : 0xffffffffu;
+      r.ie[dr] = ((rok && lok) ? il : 0xffu) | (((rok && rok2) ? ir : 0xffu) << 8);
     }
   };
 
-  auto build = [&](const RawW& r, float (&a)[9][4]) {
+  // One quarter turn's share of D for the lane's four pixels: Delta_s on the 3x6 neighbourhood,
+  // added where R_s puts each base tap (Eq. 12 with the tap positions of Eq. 8).
+  auto build_slice = [&](const RawW& r, int s, float (&a)[9][4]) {
+    const uint32_t rs = (uint32_t)rot[s];     // -1 (absent) matches no byte
+    float d[3][6];
+#pragma unroll
+    for (int dr = 0; dr < 3; ++dr) {
+      d[dr][0] = ((r.ie[dr] & 0xffu) == rs) ? r.g[dr][0] : 0.f;
+      d[dr][5] = (((r.ie[dr] >> 8) & 0xffu) == rs) ? r.g[dr][5] : 0.f;
+#pragma unroll
+      for (int p = 0; p < 4; ++p) d[dr][1 + p] = (((r.ic[dr] >> (8 * p)) & 0xffu) == rs) ? r.g[dr][1 + p] : 0.f;
+    }
 #pragma unroll
     for (int u = 0; u < 9; ++u)
 #pragma unroll
-      for (int t = 0; t < 4; ++t) a[u][t] = 0.f;
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      if (rot[s] < 0) continue;
-      float d[3][6];
-#pragma unroll
-      for (int dr = 0; dr < 3; ++dr) {
-        d[dr][0] = ((r.ie[dr] & 0xffu) == (uint32_t)rot[s]) ? r.g[dr][0] : 0.f;
-        d[dr][5] = (((r.ie[dr] >> 8) & 0xffu) == (uint32_t)rot[s]) ? r.g[dr][5] : 0.f;
-#pragma unroll
-        for (int p = 0; p < 4; ++p)
-          d[dr][1 + p] = (((r.ic[dr] >> (8 * p)) & 0xffu) == (uint32_t)rot[s]) ? r.g[dr][1 + p] : 0.f;
+      for (int t = 0; t < 4; ++t) {
+        const float term = d[2 - tap_i(s, u)][t + 2 - tap_j(s, u)];
+        a[u][t] = s == 0 ? term : a[u][t] + term;
       }
-#pragma unroll
-      for (int u = 0; u < 9; ++u)
-#pragma unroll
-        for (int t = 0; t < 4; ++t) a[u][t] += d[2 - tap_i(s, u)][t + 2 - tap_j(s, u)];
-    }
   };
 
   f4 acc[9][NCB];
@@ -146,29 +149,34 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_weight(const float* __restrict__ 
     for (int cb = 0; cb < NCB; ++cb) acc[u][cb] = f4{0.f, 0.f, 0.f, 0.f};
 
   if (niter > 0) {
-    RawW raw1, raw2;
-    f4 b0[NCB], b1[NCB], b2[NCB];
-    float a0[9][4], a1[9][4];
-    load(0, raw1, b0);
-    build(raw1, a0);
-    if (niter > 1) load(1, raw1, b1);
-    for (int it = 0; it < niter; ++it) {
-      if (it + 2 < niter) load(it + 2, raw2, b2);
-      if (it + 1 < niter) build(raw1, a1);
+    // Three-stage software pipeline, unrolled twice so that no buffer is copied: loads of (G, idx)
+    // for step it+2 and of X for step it+1; D build for step it+1, one quarter turn after each of
+    // the four K-steps of step it, so that the VALU work sits between the MFMAs.
+    RawW rawA, rawB;
+    f4 bA[NCB], bB[NCB];
+    float aA[9][4], aB[9][4];
+    auto stage = [&](int it, const RawW& raw_use, RawW& raw_ld, const float (&a_cur)[9][4], float (&a_nxt)[9][4],
+                     const f4 (&b_cur)[NCB], f4 (&b_nxt)[NCB]) {
+      load_raw(it + 2, raw_ld);
+      load_b(it + 1, b_nxt);
 #pragma unroll
-      for (int t = 0; t < 4; ++t)
+      for (int t = 0; t < 4; ++t) {
 #pragma unroll
         for (int u = 0; u < 9; ++u)
 #pragma unroll
           for (int cb = 0; cb < NCB; ++cb)
-            acc[u][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0[u][t], b0[cb][t], acc[u][cb], 0, 0, 0);
+            acc[u][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur[u][t], b_cur[cb][t], acc[u][cb], 0, 0, 0);
+        build_slice(raw_use, t, a_nxt);
+      }
+    };
+    load_raw(0, rawB);
+    load_b(0, bA);
 #pragma unroll
-      for (int u = 0; u < 9; ++u)
-#pragma unroll
-        for (int t = 0; t < 4; ++t) a0[u][t] = a1[u][t];
-#pragma unroll
-      for (int cb = 0; cb < NCB; ++cb) { b0[cb] = b1[cb]; b1[cb] = b2[cb]; }
-      raw1 = raw2;
+    for (int s = 0; s < 4; ++s) build_slice(rawB, s, aA);
+    load_raw(1, rawA);
+    for (int it = 0; it < niter; it += 2) {
+      stage(it, rawA, rawB, aA, aB, bA, bB);
+      if (it + 1 < niter) stage(it + 1, rawB, rawA, aB, aA, bB, bA);
     }
   }
 
