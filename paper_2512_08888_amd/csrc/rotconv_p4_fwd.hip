@@ -87,20 +87,17 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restri
   // A-operand loads: lane (lc, lg) reads X[ci = 4*ks + lg][h][x0 + 2*lc .. +1].
   const int pxa = x0 + 2 * lc;
   const bool px_ok = pxa < g.W;
-  const float* xn = x + (size_t)n * g.Cin * g.H * g.W + pxa;
+  const float* xn_safe = x + (size_t)n * g.Cin * g.H * g.W + (px_ok ? pxa : 0);
   const size_t chan_stride = (size_t)g.H * g.W;
 
-  auto load_chunk = [&](int t, int c, float2 (&dst)[KC]) {
+  // One A-operand load: branch-free.  Rows outside the image and pixels beyond W read a safe
+  // address and are zeroed; channels beyond Cin read channel Cin-1 (their filter taps are zero).
+  auto load_a = [&](int t, int kstep) -> float2 {
     const int h = y0 - 1 + t;
-    const bool ok = px_ok && h >= 0 && h < g.H;
-#pragma unroll
-    for (int ks = 0; ks < KC; ++ks) {
-      const int ci = (c * KC + ks) * 4 + lg;
-      if (ok && ci < g.Cin)
-        dst[ks] = *reinterpret_cast<const float2*>(xn + ci * chan_stride + (size_t)h * g.W);
-      else
-        dst[ks] = make_float2(0.f, 0.f);
-    }
+    const bool ok = px_ok && h >= 0 && h < g.H && t < nsteps;
+    const int ci = min(kstep * 4 + lg, g.Cin - 1);
+    const float2 v2 = *reinterpret_cast<const float2*>(xn_safe + ci * chan_stride + (size_t)(ok ? h : 0) * g.W);
+    return ok ? v2 : make_float2(0.f, 0.f);
   };
 
   float accA[4][8], accB[4][8];
@@ -109,8 +106,11 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restri
 #pragma unroll
     for (int j = 0; j < 8; ++j) { accA[s][j] = 0.f; accB[s][j] = 0.f; }
 
-  float2 a_cur[KC], a_nxt[KC];
-  load_chunk(0, 0, a_cur);
+  // A operands of one 32-channel chunk; each slot is refilled for the next chunk (possibly of the
+  // next row) right after its MFMAs have been issued, so the prefetch distance is one chunk.
+  float2 a_cur[KC];
+#pragma unroll
+  for (int ks = 0; ks < KC; ++ks) a_cur[ks] = load_a(0, ks);
   const float* wl_lane = Wl + lg * 144 + lc;
 
   for (int t = 0; t < nsteps; ++t) {
@@ -123,7 +123,6 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restri
     for (int c = 0; c < nchunk; ++c) {
       int tn = t, cn = c + 1;
       if (cn == nchunk) { cn = 0; tn = t + 1; }
-      if (tn < nsteps) load_chunk(tn, cn, a_nxt);
       if (row_ok) {
         const float* wc = wl_lane + (size_t)c * KC * 4 * 144;
         float bw[2][9];
@@ -140,10 +139,12 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restri
             P[u][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur[ks].x, bw[ks & 1][u], P[u][0], 0, 0, 0);
             P[u][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur[ks].y, bw[ks & 1][u], P[u][1], 0, 0, 0);
           }
+          a_cur[ks] = load_a(tn, cn * KC + ks);
         }
-      }
+      } else {
 #pragma unroll
-      for (int ks = 0; ks < KC; ++ks) a_cur[ks] = a_nxt[ks];
+        for (int ks = 0; ks < KC; ++ks) a_cur[ks] = load_a(tn, cn * KC + ks);
+      }
     }
 
     // ---- neighbour values across lane groups and waves --------------------------
