@@ -97,37 +97,51 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gp
     }
   };
 
-  // ---- (G, idx) neighbourhood loads: branch-free (out-of-range positions read a safe address and
-  // are masked; an idx byte of 0xff matches no orientation), so a K-step is one basic block --------
+  // ---- (G, idx) neighbourhood loads -------------------------------------------------------------
+  // Everything that depends on the lane only (row / pixel offsets inside a channel plane, validity)
+  // is computed once; per K-step the address is a wave-uniform plane base plus those 32-bit lane
+  // offsets.  Out-of-range positions read a clamped (valid) address and get the idx byte 0xff,
+  // which matches no orientation (R <= 255), so they contribute nothing.  Filters beyond Cout read
+  // filter Cout-1: their packed weights are zero.
   const int xa = x0 + 2 * lc;                  // first of this lane's two pixels
+  uint32_t offc[3], offl[3], offr[3], inval[3];
+#pragma unroll
+  for (int dr = 0; dr < 3; ++dr) {
+    const int row = h - 1 + dr;
+    const bool rok = active && row >= 0 && row < g.H;
+    const bool okc = rok && xa < g.W, okl = rok && xa >= 1 && xa - 1 < g.W, okr = rok && xa + 2 < g.W;
+    const uint32_t rowoff = (uint32_t)(rok ? row : 0) * (uint32_t)g.W;
+    offc[dr] = rowoff + (uint32_t)(okc ? xa : 0);
+    offl[dr] = rowoff + (uint32_t)(okl ? xa - 1 : 0);
+    offr[dr] = rowoff + (uint32_t)(okr ? xa + 2 : 0);
+    inval[dr] = (okl ? 0u : 0xffu) | (okc ? 0u : 0xffff00u) | (okr ? 0u : 0xff000000u);
+  }
+  const uint32_t lane_plane = (uint32_t)lg * (uint32_t)g.ng * (uint32_t)HW;   // filter lg of the K-step
   auto raw_load = [&](int kk, Raw& r) {
     kk = min(kk, nk - 1);
     const int q = kk / nkq;
-    const int co = (kk % nkq) * 4 + lg;
-    int r0 = -1;
+    const int co4 = (kk % nkq) * 4;            // first filter of the K-step (wave-uniform)
+    int r0 = 0;
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
+    for (int s = 3; s >= 0; --s) {
       const int rs = rot_of[q * 4 + s];
-      r0 = (r0 < 0 && rs >= 0) ? rs : r0;
+      r0 = rs >= 0 ? rs : r0;
     }
-    const bool cok = active && co < g.Cout && r0 >= 0;
-    const size_t plane = ((size_t)n * g.Cout * g.ng + (size_t)(cok ? co : 0) * g.ng + (r0 < 0 ? 0 : r0 % g.ng)) * HW;
+    // wave-uniform base of filter co4's plane in this bank's pool group
+    const size_t ubase = ((size_t)n * g.Cout * g.ng + (size_t)co4 * g.ng + (size_t)(r0 % g.ng)) * HW;
+    // lanes whose filter would be beyond Cout fall back to the K-step's first filter
+    const uint32_t lp = (co4 + lg < g.Cout) ? lane_plane : 0u;
+    const float* gb = gpool + ubase;
+    const uint8_t* ib = idx + ubase;
 #pragma unroll
     for (int dr = 0; dr < 3; ++dr) {
-      const int row = h - 1 + dr;
-      const bool rok = cok && row >= 0 && row < g.H;
-      const size_t base = plane + (size_t)(rok ? row : 0) * g.W + xa;
-      const bool okc = rok && xa < g.W, okl = rok && xa >= 1 && xa - 1 < g.W, okr = rok && xa + 2 < g.W;
-      const size_t bc = okc ? base : 0, bl = okl ? base - 1 : 0, br = okr ? base + 2 : 0;
-      const float2 gc = *reinterpret_cast<const float2*>(gpool + bc);
-      const uint32_t ic = *reinterpret_cast<const uint16_t*>(idx + bc);
-      const float gl = gpool[bl], gr = gpool[br];
-      const uint32_t il = idx[bl], ir = idx[br];
-      r.g[dr][0] = gl;
+      const float2 gc = *reinterpret_cast<const float2*>(gb + (lp + offc[dr]));
+      const uint32_t ic = *reinterpret_cast<const uint16_t*>(ib + (lp + offc[dr]));
+      r.g[dr][0] = gb[lp + offl[dr]];
       r.g[dr][1] = gc.x;
       r.g[dr][2] = gc.y;
-      r.g[dr][3] = gr;
-      r.i[dr] = (okl ? il : 0xffu) | ((okc ? ic : 0xffffu) << 8) | ((okr ? ir : 0xffu) << 24);
+      r.g[dr][3] = gb[lp + offr[dr]];
+      r.i[dr] = ((uint32_t)ib[lp + offl[dr]] | (ic << 8) | ((uint32_t)ib[lp + offr[dr]] << 24)) | inval[dr];
     }
   };
 
