@@ -151,7 +151,7 @@ int rotconv_fwd(const rotconv_plan* plan, const void* x, const void* w, void* y,
   rotconv_plan* p = const_cast<rotconv_plan*>(plan);
   if ((rc = ensure_device_tables(p))) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if (p->fast[0] && aligned(x, 8) && aligned(ws, 16)) {
+  if (p->fast[0] && aligned(x, 8) && aligned(ws, 16) && aligned(y, 16)) {
     float* wt = static_cast<float*>(ws);
     launch_p4_pack_fwd(p, static_cast<const float*>(w), wt, st);
     launch_p4_fwd(p, kOutUnpooled, static_cast<const float*>(x), wt, static_cast<float*>(y), nullptr, st);

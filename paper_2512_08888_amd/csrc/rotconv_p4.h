@@ -16,11 +16,15 @@ struct P4Geom {
   int units;     // workgroups with work
   int nwx;       // waves along x
   int out_mode;  // kOut*
+  int nseg;      // row segments handled by this launch (1 unless W > 256)
+  int inside;    // 1 if no segment's wave chain reaches beyond the row
+  int seg_xorg[4];  // first product column of a segment's wave chain
+  int seg_lo[4], seg_hi[4];  // output pixels [lo, hi) the segment stores (multiples of 8, or W)
 };
 
 // forward
 bool p4_fwd_supported(const rotconv_plan* p);
-P4Geom p4_fwd_geom(const rotconv_plan* p, int out_mode);
+int p4_fwd_geoms(const rotconv_plan* p, int out_mode, P4Geom* out, int max_out);
 size_t p4_fwd_pack_floats(const rotconv_plan* p);
 int p4_fwd_pool_mode(const rotconv_plan* p);
 void launch_p4_pack_fwd(const rotconv_plan* p, const float* w, float* wt, hipStream_t st);

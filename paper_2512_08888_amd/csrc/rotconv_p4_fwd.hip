@@ -16,9 +16,15 @@
 // Nothing R-fold ever reaches memory, and the input row is read once per bank.
 //
 // The filter block (16 filters x all input channels x 9 taps) stays resident in
-// LDS for the life of the workgroup; input rows go straight from global memory
-// into the A-operand registers (8-byte loads, 128 B contiguous per 16 lanes),
-// prefetched one 32-channel chunk ahead.
+// LDS for the life of the workgroup when it fits (Cin <= 224); deeper inputs
+// stream it through two 32-channel LDS buffers, one barrier per chunk.  Input
+// rows go straight from global memory into the A-operand registers (8-byte
+// loads, 128 B contiguous per 16 lanes), each slot refilled one chunk ahead.
+//
+// Rows wider than the 256 pixels a workgroup's eight waves can chain are cut
+// into segments that overlap by 8 pixels (the products of the overlap are
+// recomputed, about 6 % at W = 512); a segment writes only the pixels whose
+// both neighbours it holds.
 #include <hip/hip_runtime.h>
 
 #include "rotconv_kernels.h"
@@ -41,16 +47,20 @@ __device__ __host__ constexpr int tap_j(int s, int u) {
 // Index of non-centre tap u in the 8-entry edge exchange arrays.
 __device__ __host__ constexpr int edge_slot(int u) { return u < 4 ? u : u - 1; }
 
-template <int NWX, int NWY>
+// UNPOOLED: write every orientation (rotconv_fwd); else max + arg-max over the bank's rotations.
+// FASTW:    W % 8 == 0 and no wave chain reaches beyond the row: no load masks, vector stores.
+// STREAM:   the filter block does not fit LDS: stream it in 32-channel chunks.
+template <int NWX, int NWY, bool UNPOOLED, bool FASTW, bool STREAM>
 __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restrict__ x, const float* __restrict__ wt,
                                                            const int32_t* __restrict__ rot_of,
                                                            float* __restrict__ out_val, uint8_t* __restrict__ out_idx,
                                                            P4Geom g) {
   constexpr int NW = NWX * NWY;
   constexpr int NT = 64 * NW;
+  constexpr int CHF = KC * 4 * 144;      // floats of one 32-channel chunk of the filter block
   extern __shared__ float smem[];
-  float* Wl = smem;                      // [CinPad][9][16]
-  float* EL = smem + g.CinPad * 144;     // [2][NW][8][16] left-edge values of every wave
+  float* Wl = smem;                      // resident: [CinPad][9][16]; streamed: [2][32][9][16]
+  float* EL = smem + (STREAM ? 2 * CHF : g.CinPad * 144);  // [2][NW][8][16] left-edge values of every wave
   float* ER = EL + 2 * NW * 128;         // [2][NW][8][16] right-edge values
 
   // XCD-aware unit decode: consecutive units (same image rows, different filter
@@ -60,12 +70,34 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restri
   if (v >= g.units) return;
   const int cb = v % g.CB; v /= g.CB;
   const int q = v % g.Q; v /= g.Q;
+  const int seg = v % g.nseg; v /= g.nseg;
   const int bg = v % g.nbg;
   const int n = v / g.nbg;
 
   const int tid = threadIdx.x;
-  {
-    const f4* src = reinterpret_cast<const f4*>(wt + ((size_t)(q * g.CB + cb) * g.CinPad) * 144);
+  const int nchunk = g.CinPad / (4 * KC);
+  const float* wsrc = wt + ((size_t)(q * g.CB + cb) * g.CinPad) * 144;
+  constexpr int WPT = (CHF / 4 + NT - 1) / NT;   // float4 per thread and chunk when streaming
+  f4 wreg[STREAM ? WPT : 1];
+  auto wload = [&](int c) {
+#pragma unroll
+    for (int k = 0; k < WPT; ++k) {
+      const int e = tid + k * NT;
+      if (e < CHF / 4) wreg[k] = reinterpret_cast<const f4*>(wsrc + (size_t)c * CHF)[e];
+    }
+  };
+  auto wstore = [&](int buf) {
+#pragma unroll
+    for (int k = 0; k < WPT; ++k) {
+      const int e = tid + k * NT;
+      if (e < CHF / 4) reinterpret_cast<f4*>(Wl + buf * CHF)[e] = wreg[k];
+    }
+  };
+  if (STREAM) {
+    wload(0);
+    wstore(0);
+  } else {
+    const f4* src = reinterpret_cast<const f4*>(wsrc);
     f4* dst = reinterpret_cast<f4*>(Wl);
     const int n4 = g.CinPad * 36;
     for (int i = tid; i < n4; i += NT) dst[i] = src[i];
@@ -75,29 +107,34 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restri
   const int wave = tid / 64, lane = tid % 64;
   const int wx = wave % NWX, wy = wave / NWX;
   const int lg = lane / 16, lc = lane % 16;
-  const int x0 = wx * 32;
+  const int x0 = g.seg_xorg[seg] + wx * 32;
+  const int out_lo = g.seg_lo[seg], out_hi = g.seg_hi[seg];
   const int y0 = (bg * NWY + wy) * g.TY;
-  const int nchunk = g.CinPad / (4 * KC);
   const int nsteps = g.TY + 2;
+  const int HW = g.H * g.W;
 
   int rot[4];
 #pragma unroll
   for (int s = 0; s < 4; ++s) rot[s] = rot_of[q * 4 + s];
 
-  // A-operand loads: lane (lc, lg) reads X[ci = 4*ks + lg][h][x0 + 2*lc .. +1].
+  // A-operand loads: lane (lc, lg) reads X[ci = 4*kstep + lg][h][x0 + 2*lc .. +1].  The address is a
+  // per-row lane pointer plus a 32-bit channel offset.  Rows outside the image are never multiplied
+  // (their MFMAs are skipped), channels beyond Cin meet zero filter taps, so both only need a valid
+  // address; pixels beyond W must read as zero (only possible when W % 32 != 0).
   const int pxa = x0 + 2 * lc;
   const bool px_ok = pxa < g.W;
-  const float* xn_safe = x + (size_t)n * g.Cin * g.H * g.W + (px_ok ? pxa : 0);
-  const size_t chan_stride = (size_t)g.H * g.W;
-
-  // One A-operand load: branch-free.  Rows outside the image and pixels beyond W read a safe
-  // address and are zeroed; channels beyond Cin read channel Cin-1 (their filter taps are zero).
-  auto load_a = [&](int t, int kstep) -> float2 {
-    const int h = y0 - 1 + t;
-    const bool ok = px_ok && h >= 0 && h < g.H && t < nsteps;
-    const int ci = min(kstep * 4 + lg, g.Cin - 1);
-    const float2 v2 = *reinterpret_cast<const float2*>(xn_safe + ci * chan_stride + (size_t)(ok ? h : 0) * g.W);
-    return ok ? v2 : make_float2(0.f, 0.f);
+  const float* xn = x + (size_t)n * g.Cin * HW + (px_ok ? pxa : 0);
+  const uint32_t lgoff = (uint32_t)lg * (uint32_t)HW;
+  const uint32_t off_last = (uint32_t)(g.Cin - 1) * (uint32_t)HW;   // channels beyond Cin read channel Cin-1
+  auto row_ptr = [&](int t) -> const float* {
+    const int h = min(max(y0 - 1 + t, 0), g.H - 1);
+    return xn + (size_t)h * g.W;
+  };
+  auto load_a = [&](const float* rp, int kstep) -> float2 {
+    const uint32_t off = min((uint32_t)(kstep * 4) * (uint32_t)HW + lgoff, off_last);
+    const float2 v2 = *reinterpret_cast<const float2*>(rp + off);
+    if (FASTW) return v2;
+    return px_ok ? v2 : make_float2(0.f, 0.f);
   };
 
   float accA[4][8], accB[4][8];
@@ -109,22 +146,30 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restri
   // A operands of one 32-channel chunk; each slot is refilled for the next chunk (possibly of the
   // next row) right after its MFMAs have been issued, so the prefetch distance is one chunk.
   float2 a_cur[KC];
+  {
+    const float* rp = row_ptr(0);
 #pragma unroll
-  for (int ks = 0; ks < KC; ++ks) a_cur[ks] = load_a(0, ks);
+    for (int ks = 0; ks < KC; ++ks) a_cur[ks] = load_a(rp, ks);
+  }
   const float* wl_lane = Wl + lg * 144 + lc;
+  int seq = 0;                           // chunk steps done (streaming: LDS buffer parity)
 
   for (int t = 0; t < nsteps; ++t) {
     const int h = y0 - 1 + t;
     const bool row_ok = h >= 0 && h < g.H;
+    const float* rp_cur = row_ptr(t);
+    const float* rp_nxt = row_ptr(t + 1);
     f4 P[9][2];
 #pragma unroll
     for (int u = 0; u < 9; ++u) { P[u][0] = f4{0.f, 0.f, 0.f, 0.f}; P[u][1] = f4{0.f, 0.f, 0.f, 0.f}; }
 
     for (int c = 0; c < nchunk; ++c) {
-      int tn = t, cn = c + 1;
-      if (cn == nchunk) { cn = 0; tn = t + 1; }
+      const bool last = c + 1 == nchunk;
+      const float* rp = last ? rp_nxt : rp_cur;
+      const int kn = last ? 0 : (c + 1) * KC;
+      if (STREAM) wload(last ? 0 : c + 1);
       if (row_ok) {
-        const float* wc = wl_lane + (size_t)c * KC * 4 * 144;
+        const float* wc = STREAM ? wl_lane + (seq & 1) * CHF : wl_lane + (size_t)c * CHF;
         float bw[2][9];
 #pragma unroll
         for (int u = 0; u < 9; ++u) bw[0][u] = wc[u * 16];
@@ -139,12 +184,17 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restri
             P[u][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur[ks].x, bw[ks & 1][u], P[u][0], 0, 0, 0);
             P[u][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur[ks].y, bw[ks & 1][u], P[u][1], 0, 0, 0);
           }
-          a_cur[ks] = load_a(tn, cn * KC + ks);
+          a_cur[ks] = load_a(rp, kn + ks);
         }
       } else {
 #pragma unroll
-        for (int ks = 0; ks < KC; ++ks) a_cur[ks] = load_a(tn, cn * KC + ks);
+        for (int ks = 0; ks < KC; ++ks) a_cur[ks] = load_a(rp, kn + ks);
       }
+      if (STREAM) {
+        wstore((seq + 1) & 1);
+        __syncthreads();
+      }
+      ++seq;
     }
 
     // ---- neighbour values across lane groups and waves --------------------------
@@ -175,29 +225,36 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restri
       nbL[u] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(addr_dn, __builtin_bit_cast(int, last_px)));
     }
     __syncthreads();
-    {
-      // all lanes read both neighbour-wave slots (in bounds for every wave), then select
+    if (NWX > 1) {
+      // all lanes read both neighbour-wave slots (in bounds for every wave), then select; a chain
+      // end has no neighbour: zero, which is right at an image border (other ends are not stored)
       const float* eln = EL + (par * NW + wave + 1) * 128 + lc;  // right neighbour's left edge
       const float* erp = ER + (par * NW + wave - 1) * 128 + lc;  // left neighbour's right edge
-      const float mr = (wx + 1 < NWX) ? 1.f : 0.f, ml = (wx > 0) ? 1.f : 0.f;
       const bool at_r = lg == 3, at_l = lg == 0;
+      const bool has_r = wx + 1 < NWX, has_l = wx > 0;
 #pragma unroll
       for (int u = 0; u < 9; ++u) {
         if (u == 4) continue;
-        const float vr = eln[edge_slot(u) * 16] * mr;
-        const float vl = erp[edge_slot(u) * 16] * ml;
+        const float vr = has_r ? eln[edge_slot(u) * 16] : 0.f;
+        const float vl = has_l ? erp[edge_slot(u) * 16] : 0.f;
         nbR[u] = at_r ? vr : nbR[u];
         nbL[u] = at_l ? vl : nbL[u];
+      }
+    } else {
+#pragma unroll
+      for (int u = 0; u < 9; ++u) {
+        nbR[u] = lg == 3 ? 0.f : nbR[u];
+        nbL[u] = lg == 0 ? 0.f : nbL[u];
       }
     }
 
     // ---- place the row of products at the rotated positions (Eq. 8) --------------
     const int y = h - 1;                       // output row completed by this step
-    const bool fin = t >= 2 && y < g.H;
+    const int px0 = x0 + 8 * lg;               // first of this lane's 8 pixels
+    const int co = cb * 16 + lc;
+    const bool fin = t >= 2 && y < g.H && co < g.Cout && px0 >= out_lo && px0 < out_hi;
     float best[8];
     int bidx[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) { best[j] = 0.f; bidx[j] = 0; }
     bool first = true;
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
@@ -218,23 +275,34 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restri
         accA[s][j] = accB[s][j] + t1;   // output row h has rows h-1, h
         accB[s][j] = t0;                // output row h+1 has row h
       }
-      if (g.out_mode == kOutUnpooled) {
-        if (fin && rot[s] >= 0 && cb * 16 + lc < g.Cout) {
-          float* o = out_val + (((size_t)n * g.Cout + cb * 16 + lc) * g.R + rot[s]) * chan_stride + (size_t)y * g.W +
-                     x0 + 8 * lg;
+      if (UNPOOLED) {
+        if (fin && rot[s] >= 0) {
+          float* o = out_val + (((size_t)n * g.Cout + co) * g.R + rot[s]) * HW + (size_t)y * g.W + px0;
+          if (FASTW) {
+            reinterpret_cast<f4*>(o)[0] = f4{yfin[0], yfin[1], yfin[2], yfin[3]};
+            reinterpret_cast<f4*>(o)[1] = f4{yfin[4], yfin[5], yfin[6], yfin[7]};
+          } else {
 #pragma unroll
-          for (int j = 0; j < 8; ++j)
-            if (x0 + 8 * lg + j < g.W) o[j] = yfin[j];
+            for (int j = 0; j < 8; ++j)
+              if (px0 + j < min(g.W, out_hi)) o[j] = yfin[j];
+          }
         }
-      } else if (rot[s] >= 0) {
+      } else if (rot[s] >= 0) {     // wave-uniform
+        if (first) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
-          if (first || yfin[j] > best[j]) { best[j] = yfin[j]; bidx[j] = rot[s]; }
+          for (int j = 0; j < 8; ++j) { best[j] = yfin[j]; bidx[j] = rot[s]; }
+        } else {
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            const bool gt = yfin[j] > best[j];
+            best[j] = gt ? yfin[j] : best[j];
+            bidx[j] = gt ? rot[s] : bidx[j];
+          }
+        }
         first = false;
       }
     }
-    if (g.out_mode != kOutUnpooled && fin && !first && cb * 16 + lc < g.Cout) {
-      const int co = cb * 16 + lc;
+    if (!UNPOOLED && fin && !first) {
       size_t chan;
       if (g.out_mode == kOutPooled) {
         // every rotation of this bank lies in pool group (r mod ng); pooled channel = co*ng + group
@@ -242,21 +310,19 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restri
       } else {  // kOutPartial: per-bank candidates [Q][N][Cout][H][W]
         chan = ((size_t)q * g.N + n) * g.Cout + co;
       }
-      const size_t off = chan * chan_stride + (size_t)y * g.W + x0 + 8 * lg;
-      if ((g.W & 7) == 0) {
-        if (x0 + 8 * lg < g.W) {
-          f4* o = reinterpret_cast<f4*>(out_val + off);
-          o[0] = f4{best[0], best[1], best[2], best[3]};
-          o[1] = f4{best[4], best[5], best[6], best[7]};
-          uint2 pk;
-          pk.x = bidx[0] | (bidx[1] << 8) | (bidx[2] << 16) | (bidx[3] << 24);
-          pk.y = bidx[4] | (bidx[5] << 8) | (bidx[6] << 16) | (bidx[7] << 24);
-          *reinterpret_cast<uint2*>(out_idx + off) = pk;
-        }
+      const size_t off = chan * HW + (size_t)y * g.W + px0;
+      if (FASTW) {
+        f4* o = reinterpret_cast<f4*>(out_val + off);
+        o[0] = f4{best[0], best[1], best[2], best[3]};
+        o[1] = f4{best[4], best[5], best[6], best[7]};
+        uint2 pk;
+        pk.x = bidx[0] | (bidx[1] << 8) | (bidx[2] << 16) | (bidx[3] << 24);
+        pk.y = bidx[4] | (bidx[5] << 8) | (bidx[6] << 16) | (bidx[7] << 24);
+        *reinterpret_cast<uint2*>(out_idx + off) = pk;
       } else {
 #pragma unroll
         for (int j = 0; j < 8; ++j)
-          if (x0 + 8 * lg + j < g.W) {
+          if (px0 + j < min(g.W, out_hi)) {
             out_val[off + j] = best[j];
             out_idx[off + j] = (uint8_t)bidx[j];
           }
@@ -318,14 +384,37 @@ __global__ __launch_bounds__(256) void k_p4_pack_fwd(const float* __restrict__ w
   wt[e] = acc;
 }
 
-template <int NWX, int NWY>
-void launch_t(const P4Geom& g, const float* x, const float* wt, const int32_t* rot_of, float* ov, uint8_t* oi,
+template <int NWX, int NWY, bool UNPOOLED, bool FASTW, bool STREAM>
+void launch_i(const P4Geom& g, const float* x, const float* wt, const int32_t* rot_of, float* ov, uint8_t* oi,
               hipStream_t st) {
-  const size_t lds = ((size_t)g.CinPad * 144 + 4 * NWX * NWY * 128) * sizeof(float);
+  const size_t wfl = STREAM ? (size_t)2 * KC * 4 * 144 : (size_t)g.CinPad * 144;
+  const size_t lds = (wfl + 4 * NWX * NWY * 128) * sizeof(float);
   const int grid = (g.units + 7) / 8 * 8;
-  (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_p4_fwd<NWX, NWY>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                      (int)lds);
-  hipLaunchKernelGGL((k_p4_fwd<NWX, NWY>), dim3(grid), dim3(64 * NWX * NWY), lds, st, x, wt, rot_of, ov, oi, g);
+  auto kern = k_p4_fwd<NWX, NWY, UNPOOLED, FASTW, STREAM>;
+  (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * NWX * NWY), lds, st, x, wt, rot_of, ov, oi, g);
+}
+
+template <int NWX, int NWY>
+void launch_t(const P4Geom& g, bool fastw, bool stream, const float* x, const float* wt, const int32_t* rot_of,
+              float* ov, uint8_t* oi, hipStream_t st) {
+  const bool unp = g.out_mode == kOutUnpooled;
+  if (unp) {
+    if (fastw) launch_i<NWX, NWY, true, true, false>(g, x, wt, rot_of, ov, oi, st);
+    else launch_i<NWX, NWY, true, false, false>(g, x, wt, rot_of, ov, oi, st);
+  } else if (stream) {
+    launch_i<NWX, NWY, false, true, true>(g, x, wt, rot_of, ov, oi, st);
+  } else if (fastw) {
+    launch_i<NWX, NWY, false, true, false>(g, x, wt, rot_of, ov, oi, st);
+  } else {
+    launch_i<NWX, NWY, false, false, false>(g, x, wt, rot_of, ov, oi, st);
+  }
+}
+
+// Is the filter block of 16 filters too large to stay in LDS next to the edge arrays?
+bool needs_stream(int Cin) {
+  const int CinPad = (Cin + 31) / 32 * 32;
+  return (size_t)CinPad * 576 + 16384 > 160 * 1024;
 }
 
 }  // namespace
@@ -333,29 +422,66 @@ void launch_t(const P4Geom& g, const float* x, const float* wt, const int32_t* r
 bool p4_fwd_supported(const rotconv_plan* p) {
   const rotconv_desc& d = p->d;
   if (d.k != 3 || d.stride != 1 || d.pad != 1 || d.dtype != ROTCONV_F32) return false;
-  if (d.W > 256 || (d.W & 1)) return false;
-  const int CinPad = (d.Cin + 31) / 32 * 32;
-  if ((size_t)CinPad * 576 + 16384 > 160 * 1024) return false;
+  if (d.W & 1) return false;
+  if (d.W > 256 && (d.W & 31)) return false;          // segmented rows need whole-lane validity
+  if (needs_stream(d.Cin) && (d.W & 31)) return false;  // the streaming variant is built for W % 32 == 0
   return true;
 }
 
-P4Geom p4_fwd_geom(const rotconv_plan* p, int out_mode) {
+// Cut the row into segments of at most 256 product columns; all segments of one launch share nwx.
+// Returns the number of launches (geoms) written.
+int p4_fwd_geoms(const rotconv_plan* p, int out_mode, P4Geom* out, int max_out) {
   const rotconv_desc& d = p->d;
-  P4Geom g{};
-  g.N = d.N; g.Cin = d.Cin; g.CinPad = (d.Cin + 31) / 32 * 32; g.H = d.H; g.W = d.W; g.Cout = d.Cout;
-  g.CB = (d.Cout + 15) / 16; g.R = d.R; g.Q = p->host.Q; g.ng = p->ng; g.out_mode = out_mode;
-  int nwx = 1;
-  while (nwx * 32 < d.W) nwx *= 2;
-  g.nwx = nwx;
-  const int nwy = 8 / nwx;
-  long best_cost = -1;
-  for (int ty : {8, 16, 32, 64}) {
-    const int nbg = (d.H + nwy * ty - 1) / (nwy * ty);
-    const long units = (long)d.N * g.Q * g.CB * nbg;
-    const long cost = ((units + 255) / 256) * (ty + 2);
-    if (best_cost < 0 || cost <= best_cost) { best_cost = cost; g.TY = ty; g.nbg = nbg; g.units = (int)units; }
+  P4Geom base{};
+  base.N = d.N; base.Cin = d.Cin; base.CinPad = (d.Cin + 31) / 32 * 32; base.H = d.H; base.W = d.W;
+  base.Cout = d.Cout; base.CB = (d.Cout + 15) / 16; base.R = d.R; base.Q = p->host.Q; base.ng = p->ng;
+  base.out_mode = out_mode;
+  int ng = 0;
+  int pos = 0;
+  while (pos < d.W) {
+    int xorg, nwx;
+    if (pos == 0) {
+      xorg = 0;
+      nwx = 1;
+      while (nwx * 32 < d.W && nwx < 8) nwx *= 2;
+    } else {
+      const int need = d.W - (pos - 8);      // product columns from the pixel left of `pos` to the border
+      nwx = 1;
+      while (nwx * 32 < need && nwx < 8) nwx *= 2;
+      // the last segment ends exactly at the right border (W % 32 == 0 here), others start 8 px early
+      xorg = nwx * 32 >= need ? d.W - nwx * 32 : pos - 8;
+    }
+    const int chain_end = xorg + nwx * 32;
+    const int hi = chain_end >= d.W ? d.W : chain_end - 8;
+    int gi = -1;
+    for (int i = 0; i < ng; ++i)
+      if (out[i].nwx == nwx && out[i].nseg < 4) gi = i;
+    if (gi < 0) {
+      if (ng >= max_out) return -1;
+      gi = ng++;
+      out[gi] = base;
+      out[gi].nwx = nwx;
+      out[gi].nseg = 0;
+      out[gi].inside = 1;
+    }
+    P4Geom& g = out[gi];
+    g.seg_xorg[g.nseg] = xorg; g.seg_lo[g.nseg] = pos; g.seg_hi[g.nseg] = hi;
+    if (chain_end > d.W) g.inside = 0;
+    g.nseg++;
+    pos = hi;
   }
-  return g;
+  for (int i = 0; i < ng; ++i) {
+    P4Geom& g = out[i];
+    const int nwy = 8 / g.nwx;
+    long best_cost = -1;
+    for (int ty : {8, 16, 32, 64}) {
+      const int nbg = (d.H + nwy * ty - 1) / (nwy * ty);
+      const long units = (long)d.N * g.Q * g.CB * nbg * g.nseg;
+      const long cost = ((units + 255) / 256) * (ty + 2);
+      if (best_cost < 0 || cost <= best_cost) { best_cost = cost; g.TY = ty; g.nbg = nbg; g.units = (int)units; }
+    }
+  }
+  return ng;
 }
 
 size_t p4_fwd_pack_floats(const rotconv_plan* p) {
@@ -388,12 +514,18 @@ void launch_p4_pack_fwd(const rotconv_plan* p, const float* w, float* wt, hipStr
 
 void launch_p4_fwd(const rotconv_plan* p, int out_mode, const float* x, const float* wt, float* out_val,
                    uint8_t* out_idx, hipStream_t st) {
-  const P4Geom g = p4_fwd_geom(p, out_mode);
-  switch (g.nwx) {
-    case 1: launch_t<1, 8>(g, x, wt, p->dev.rot_of, out_val, out_idx, st); break;
-    case 2: launch_t<2, 4>(g, x, wt, p->dev.rot_of, out_val, out_idx, st); break;
-    case 4: launch_t<4, 2>(g, x, wt, p->dev.rot_of, out_val, out_idx, st); break;
-    default: launch_t<8, 1>(g, x, wt, p->dev.rot_of, out_val, out_idx, st); break;
+  P4Geom gs[4];
+  const int ng = p4_fwd_geoms(p, out_mode, gs, 4);
+  const bool stream = needs_stream(p->d.Cin);
+  for (int i = 0; i < ng; ++i) {
+    const P4Geom& g = gs[i];
+    const bool fastw = (p->d.W & 7) == 0 && g.inside;   // no lane reaches beyond the row: no masks, vector stores
+    switch (g.nwx) {
+      case 1: launch_t<1, 8>(g, fastw, stream, x, wt, p->dev.rot_of, out_val, out_idx, st); break;
+      case 2: launch_t<2, 4>(g, fastw, stream, x, wt, p->dev.rot_of, out_val, out_idx, st); break;
+      case 4: launch_t<4, 2>(g, fastw, stream, x, wt, p->dev.rot_of, out_val, out_idx, st); break;
+      default: launch_t<8, 1>(g, fastw, stream, x, wt, p->dev.rot_of, out_val, out_idx, st); break;
+    }
   }
 }
 

@@ -46,6 +46,14 @@ TINY = [
        angles_deg=(0.0, 30.0, 120.0, 200.0, 359.0), seed=29),
     LC("t_big_tail", N=1, Cin=17, H=33, W=35, Cout=19, R=4, seed=30),
     LC("t_1px", N=1, Cin=1, H=1, W=1, Cout=1, R=4, seed=31),
+    # wide rows (segmented wave chains), rows that end inside a wave chain, deep inputs (streamed filter block)
+    LC("t_w512", N=1, Cin=8, H=11, W=512, Cout=20, R=4, seed=32),
+    LC("t_w288", N=1, Cin=4, H=9, W=288, Cout=16, R=4, seed=33),
+    LC("t_w96", N=2, Cin=4, H=9, W=96, Cout=5, R=4, seed=34),
+    LC("t_w72", N=1, Cin=6, H=9, W=72, Cout=3, R=4, seed=35),
+    LC("t_cin256", N=1, Cin=256, H=10, W=32, Cout=18, R=4, seed=36),
+    LC("t_cin288_r16", N=1, Cin=288, H=9, W=64, Cout=16, R=16, mode="bilinear", seed=37),
+    LC("t_w544_cin6", N=1, Cin=6, H=6, W=544, Cout=16, R=8, mode="steerable", pool_group=4, seed=38),
 ]
 
 
