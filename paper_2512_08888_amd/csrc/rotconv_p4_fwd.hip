@@ -254,28 +254,30 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restri
     const int co = cb * 16 + lc;
     const bool fin = t >= 2 && y < g.H && co < g.Cout && px0 >= out_lo && px0 < out_hi;
     float best[8];
-    int bidx[8];
+    uint32_t pk[2] = {0u, 0u};                 // arg-max bytes of the lane's 8 pixels
+    int grp_r = 0;                             // any rotation of the bank (its pool group)
     bool first = true;
+    auto place = [&](int s, int j, float& yfin) {
+      float t0 = 0.f, t1 = 0.f, t2 = 0.f;
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      float yfin[8];
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        float t0 = 0.f, t1 = 0.f, t2 = 0.f;
-#pragma unroll
-        for (int u = 0; u < 9; ++u) {
-          const int jj = j + tap_j(s, u) - 1;
-          const float val = jj < 0 ? nbL[u] : jj > 7 ? nbR[u] : P[u][jj & 1][jj >> 1];
-          const int ti = tap_i(s, u);
-          if (ti == 0) t0 += val;
-          else if (ti == 1) t1 += val;
-          else t2 += val;
-        }
-        yfin[j] = accA[s][j] + t2;      // rows h-2, h-1, h are in: output row h-1 done
-        accA[s][j] = accB[s][j] + t1;   // output row h has rows h-1, h
-        accB[s][j] = t0;                // output row h+1 has row h
+      for (int u = 0; u < 9; ++u) {
+        const int jj = j + tap_j(s, u) - 1;
+        const float val = jj < 0 ? nbL[u] : jj > 7 ? nbR[u] : P[u][jj & 1][jj >> 1];
+        const int ti = tap_i(s, u);
+        if (ti == 0) t0 += val;
+        else if (ti == 1) t1 += val;
+        else t2 += val;
       }
-      if (UNPOOLED) {
+      yfin = accA[s][j] + t2;         // rows h-2, h-1, h are in: output row h-1 done
+      accA[s][j] = accB[s][j] + t1;   // output row h has rows h-1, h
+      accB[s][j] = t0;                // output row h+1 has row h
+    };
+    if (UNPOOLED) {
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        float yfin[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) place(s, j, yfin[j]);
         if (fin && rot[s] >= 0) {
           float* o = out_val + (((size_t)n * g.Cout + co) * g.R + rot[s]) * HW + (size_t)y * g.W + px0;
           if (FASTW) {
@@ -287,26 +289,37 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restri
               if (px0 + j < min(g.W, out_hi)) o[j] = yfin[j];
           }
         }
-      } else if (rot[s] >= 0) {     // wave-uniform
-        if (first) {
+      }
+    } else {
+      // pixel by pixel: the four rotations' values, their max and arg-max (smallest r wins ties)
 #pragma unroll
-          for (int j = 0; j < 8; ++j) { best[j] = yfin[j]; bidx[j] = rot[s]; }
-        } else {
+      for (int s = 0; s < 4; ++s)
+        if (rot[s] >= 0) { grp_r = rot[s]; first = false; }
 #pragma unroll
-          for (int j = 0; j < 8; ++j) {
-            const bool gt = yfin[j] > best[j];
-            best[j] = gt ? yfin[j] : best[j];
-            bidx[j] = gt ? rot[s] : bidx[j];
+      for (int j = 0; j < 8; ++j) {
+        float bv = 0.f;
+        int bi = 0;
+        bool have = false;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          float yv;
+          place(s, j, yv);
+          if (rot[s] >= 0) {          // wave-uniform
+            const bool gt = !have || yv > bv;
+            bv = gt ? yv : bv;
+            bi = gt ? rot[s] : bi;
+            have = true;
           }
         }
-        first = false;
+        best[j] = bv;
+        pk[j >> 2] |= (uint32_t)bi << (8 * (j & 3));
       }
     }
     if (!UNPOOLED && fin && !first) {
       size_t chan;
       if (g.out_mode == kOutPooled) {
         // every rotation of this bank lies in pool group (r mod ng); pooled channel = co*ng + group
-        chan = (size_t)n * g.Cout * g.ng + (size_t)co * g.ng + (bidx[0] % g.ng);
+        chan = (size_t)n * g.Cout * g.ng + (size_t)co * g.ng + (grp_r % g.ng);
       } else {  // kOutPartial: per-bank candidates [Q][N][Cout][H][W]
         chan = ((size_t)q * g.N + n) * g.Cout + co;
       }
@@ -315,16 +328,13 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restri
         f4* o = reinterpret_cast<f4*>(out_val + off);
         o[0] = f4{best[0], best[1], best[2], best[3]};
         o[1] = f4{best[4], best[5], best[6], best[7]};
-        uint2 pk;
-        pk.x = bidx[0] | (bidx[1] << 8) | (bidx[2] << 16) | (bidx[3] << 24);
-        pk.y = bidx[4] | (bidx[5] << 8) | (bidx[6] << 16) | (bidx[7] << 24);
-        *reinterpret_cast<uint2*>(out_idx + off) = pk;
+        *reinterpret_cast<uint2*>(out_idx + off) = make_uint2(pk[0], pk[1]);
       } else {
 #pragma unroll
         for (int j = 0; j < 8; ++j)
           if (px0 + j < min(g.W, out_hi)) {
             out_val[off + j] = best[j];
-            out_idx[off + j] = (uint8_t)bidx[j];
+            out_idx[off + j] = (uint8_t)(pk[j >> 2] >> (8 * (j & 3)));
           }
       }
     }
