@@ -26,6 +26,15 @@ EXPORTS = [
     "rotconv_status_string", "rotconv_plan_kernel_name",
 ]
 
+# include/unetglue.h
+GLUE_EXPORTS = [
+    "glue_relu_fwd", "glue_relu_bwd", "glue_maxpool2_fwd", "glue_maxpool2_bwd",
+    "glue_upconv2_workspace_bytes", "glue_upconv2_fwd", "glue_upconv2_bwd_data", "glue_upconv2_bwd_weight",
+    "glue_concat2", "glue_split2",
+    "glue_conv1x1_workspace_bytes", "glue_conv1x1_fwd", "glue_conv1x1_bwd_data", "glue_conv1x1_bwd_weight",
+    "glue_softmax_ce",
+]
+
 
 class Desc(ctypes.Structure):
     _fields_ = [
@@ -75,6 +84,24 @@ def lib():
         L.rotconv_status_string.restype = ctypes.c_char_p
         L.rotconv_plan_kernel_name.argtypes = [vp, ctypes.c_int]
         L.rotconv_plan_kernel_name.restype = ctypes.c_char_p
+        ci = ctypes.c_int
+        L.glue_relu_fwd.argtypes = [vp, vp, sz, vp]
+        L.glue_relu_bwd.argtypes = [vp, vp, vp, sz, vp]
+        L.glue_maxpool2_fwd.argtypes = [vp, vp, vp, ci, ci, ci, ci, vp]
+        L.glue_maxpool2_bwd.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, vp]
+        L.glue_upconv2_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
+        L.glue_upconv2_workspace_bytes.restype = sz
+        L.glue_upconv2_fwd.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, vp]
+        L.glue_upconv2_bwd_data.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, vp]
+        L.glue_upconv2_bwd_weight.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, vp, sz, vp]
+        L.glue_concat2.argtypes = [vp, vp, vp, ci, ci, ci, sz, vp]
+        L.glue_split2.argtypes = [vp, vp, vp, ci, ci, ci, sz, ci, vp]
+        L.glue_conv1x1_workspace_bytes.argtypes = [ci, ci, ci, sz]
+        L.glue_conv1x1_workspace_bytes.restype = sz
+        L.glue_conv1x1_fwd.argtypes = [vp, vp, vp, ci, ci, ci, sz, vp]
+        L.glue_conv1x1_bwd_data.argtypes = [vp, vp, vp, ci, ci, ci, sz, vp]
+        L.glue_conv1x1_bwd_weight.argtypes = [vp, vp, vp, ci, ci, ci, sz, vp, sz, vp]
+        L.glue_softmax_ce.argtypes = [vp, vp, vp, vp, ci, ci, sz, vp, sz, vp]
         _lib = L
     return _lib
 
@@ -220,3 +247,93 @@ def rotconv_pool_bwd_weight(plan: Plan, x, gpool, idx, dw, ws=None):
     p, n = _ws_args(plan, ws)
     _check(lib().rotconv_pool_bwd_weight(plan.handle, _ptr(x), _ptr(gpool), _ptr(idx), _ptr(dw), p, n, _stream()),
            "rotconv_pool_bwd_weight")
+
+
+# ---- network glue (include/unetglue.h): same names, argument marshalling only -------------------
+
+def _nbytes(t):
+    return 0 if t is None else t.numel() * t.element_size()
+
+
+def glue_relu_fwd(x, y):
+    _check(lib().glue_relu_fwd(_ptr(x), _ptr(y), x.numel(), _stream()), "glue_relu_fwd")
+
+
+def glue_relu_bwd(y, dy, dx):
+    _check(lib().glue_relu_bwd(_ptr(y), _ptr(dy), _ptr(dx), y.numel(), _stream()), "glue_relu_bwd")
+
+
+def glue_maxpool2_fwd(x, y, idx):
+    N, C, H, W = x.shape
+    _check(lib().glue_maxpool2_fwd(_ptr(x), _ptr(y), _ptr(idx), N, C, H, W, _stream()), "glue_maxpool2_fwd")
+
+
+def glue_maxpool2_bwd(dy, idx, dx, accumulate=False):
+    N, C, H, W = dx.shape
+    _check(lib().glue_maxpool2_bwd(_ptr(dy), _ptr(idx), _ptr(dx), N, C, H, W, int(bool(accumulate)), _stream()),
+           "glue_maxpool2_bwd")
+
+
+def glue_upconv2_workspace_bytes(N, Cin, Cout, H, W):
+    return int(lib().glue_upconv2_workspace_bytes(N, Cin, Cout, H, W))
+
+
+def glue_upconv2_fwd(x, w, y):
+    N, Cin, H, W = x.shape
+    _check(lib().glue_upconv2_fwd(_ptr(x), _ptr(w), _ptr(y), N, Cin, w.shape[1], H, W, _stream()), "glue_upconv2_fwd")
+
+
+def glue_upconv2_bwd_data(dy, w, dx):
+    N, Cin, H, W = dx.shape
+    _check(lib().glue_upconv2_bwd_data(_ptr(dy), _ptr(w), _ptr(dx), N, Cin, w.shape[1], H, W, _stream()),
+           "glue_upconv2_bwd_data")
+
+
+def glue_upconv2_bwd_weight(x, dy, dw, ws):
+    N, Cin, H, W = x.shape
+    _check(lib().glue_upconv2_bwd_weight(_ptr(x), _ptr(dy), _ptr(dw), N, Cin, dw.shape[1], H, W, _ptr(ws), _nbytes(ws),
+                                         _stream()), "glue_upconv2_bwd_weight")
+
+
+def glue_concat2(a, b, out):
+    N, Ca = a.shape[0], a.shape[1]
+    P = a.numel() // (N * Ca)
+    _check(lib().glue_concat2(_ptr(a), _ptr(b), _ptr(out), N, Ca, b.shape[1], P, _stream()), "glue_concat2")
+
+
+def glue_split2(dcat, da, db, accumulate_a=False):
+    N, Ca = da.shape[0], da.shape[1]
+    P = da.numel() // (N * Ca)
+    _check(lib().glue_split2(_ptr(dcat), _ptr(da), _ptr(db), N, Ca, db.shape[1], P, int(bool(accumulate_a)), _stream()),
+           "glue_split2")
+
+
+def glue_conv1x1_workspace_bytes(N, Cin, Cout, P):
+    return int(lib().glue_conv1x1_workspace_bytes(N, Cin, Cout, P))
+
+
+def glue_conv1x1_fwd(x, w, y):
+    N, Cin = x.shape[0], x.shape[1]
+    P = x.numel() // (N * Cin)
+    _check(lib().glue_conv1x1_fwd(_ptr(x), _ptr(w), _ptr(y), N, Cin, w.shape[0], P, _stream()), "glue_conv1x1_fwd")
+
+
+def glue_conv1x1_bwd_data(dy, w, dx):
+    N, Cin = dx.shape[0], dx.shape[1]
+    P = dx.numel() // (N * Cin)
+    _check(lib().glue_conv1x1_bwd_data(_ptr(dy), _ptr(w), _ptr(dx), N, Cin, w.shape[0], P, _stream()),
+           "glue_conv1x1_bwd_data")
+
+
+def glue_conv1x1_bwd_weight(x, dy, dw, ws):
+    N, Cin = x.shape[0], x.shape[1]
+    P = x.numel() // (N * Cin)
+    _check(lib().glue_conv1x1_bwd_weight(_ptr(x), _ptr(dy), _ptr(dw), N, Cin, dw.shape[0], P, _ptr(ws), _nbytes(ws),
+                                         _stream()), "glue_conv1x1_bwd_weight")
+
+
+def glue_softmax_ce(logits, labels, loss, dlogits, ws):
+    N, K = logits.shape[0], logits.shape[1]
+    P = logits.numel() // (N * K)
+    _check(lib().glue_softmax_ce(_ptr(logits), _ptr(labels), _ptr(loss), _ptr(dlogits), N, K, P, _ptr(ws), _nbytes(ws),
+                                 _stream()), "glue_softmax_ce")

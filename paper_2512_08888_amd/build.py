@@ -22,6 +22,15 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")) + glob.glob(os.path.join(CSRC, "*.cpp")))
 
 
+def stale_sources():
+    """Sources (and headers) modified after the built library; everything if it is missing."""
+    deps = sources() + glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(ROOT, "include", "*.h"))
+    if not os.path.exists(LIB):
+        return deps
+    t = os.path.getmtime(LIB)
+    return [d for d in deps if os.path.getmtime(d) > t]
+
+
 def build(verbose: bool = False, extra_flags=()) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objs = []

@@ -1,0 +1,243 @@
+"""One training step (forward + backward) of the UNet-shaped stack of rotation-convolution
+layers (paper Sec. V-A, Fig. 9, with both convolutions of a block rotation-invariant), run
+entirely through the C-ABI library: this module only owns the device buffers (torch tensors as
+plain memory), the per-layer plans and the order of the calls.
+
+    Block(a->b) = rotconv_pool(a->b) + ReLU, rotconv_pool(b->b) + ReLU        (3x3, pad 1)
+    encoder: Block, 2x2 max-pool per level; bottleneck Block; decoder per level: 2x2 stride-2
+    transposed convolution, concat [skip, up], Block; 1x1 head; mean soft-max cross-entropy.
+
+No arithmetic happens here and nothing falls back to torch ops.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Dict, Optional, Sequence, Tuple
+
+import numpy as np
+
+from . import binding as rc
+from . import synth
+
+
+@dataclass(frozen=True)
+class UNetConfig:
+    name: str
+    N: int
+    Cin: int
+    H: int
+    W: int
+    widths: Tuple[int, ...]          # encoder widths ..., last = bottleneck
+    classes: int
+    R: int = 4
+    mode: str = "exact90"
+    pool_group: Optional[int] = None  # None = pool over all R orientations
+    seed: int = 2024
+
+    @property
+    def depth(self):
+        return len(self.widths) - 1
+
+    @property
+    def B(self):
+        return 2 if self.mode == "steerable" else 1
+
+
+C4 = UNetConfig("C4", 4, 3, 512, 512, (64, 128, 256, 512, 1024), 6, R=4, mode="exact90", seed=404)
+C5 = UNetConfig("C5", 2, 3, 512, 512, (64, 128, 256, 512, 1024), 6, R=16, mode="bilinear", pool_group=16, seed=505)
+UNET_CONFIGS = {"C4": C4, "C5": C5}
+
+
+def rot_layers(cfg: UNetConfig):
+    """(name, Cin, Cout, H, W) of every rotation-convolution layer in forward order."""
+    out, c, h, w = [], cfg.Cin, cfg.H, cfg.W
+    for lvl in range(cfg.depth):
+        out += [(f"enc{lvl}a", c, cfg.widths[lvl], h, w), (f"enc{lvl}b", cfg.widths[lvl], cfg.widths[lvl], h, w)]
+        c, h, w = cfg.widths[lvl], h // 2, w // 2
+    wb = cfg.widths[-1]
+    out += [("bota", c, wb, h, w), ("botb", wb, wb, h, w)]
+    for lvl in reversed(range(cfg.depth)):
+        h, w = 2 * h, 2 * w
+        wl = cfg.widths[lvl]
+        out += [(f"dec{lvl}a", 2 * wl, wl, h, w), (f"dec{lvl}b", wl, wl, h, w)]
+    return out
+
+
+def param_shapes(cfg: UNetConfig) -> Dict[str, Tuple[int, ...]]:
+    shapes = {n: (cfg.B, co, ci, 3, 3) for n, ci, co, _, _ in rot_layers(cfg)}
+    for lvl in range(cfg.depth):
+        shapes[f"up{lvl}"] = (cfg.widths[lvl + 1], cfg.widths[lvl], 2, 2)
+    shapes["head"] = (cfg.classes, cfg.widths[0])
+    return shapes
+
+
+def make_params(cfg: UNetConfig) -> Dict[str, np.ndarray]:
+    """He-normal parameters sqrt(2 / fan_in) from the counter-based generator (fp32 values)."""
+    out = {}
+    for i, (name, shp) in enumerate(sorted(param_shapes(cfg).items())):
+        fan_in = shp[1] if name == "head" else shp[0] if name.startswith("up") else shp[2] * 9
+        n = int(np.prod(shp))
+        v = synth.normal01(cfg.seed * 1000 + i, n) * np.sqrt(2.0 / fan_in)
+        out[name] = v.astype(np.float32).reshape(shp)
+    return out
+
+
+def make_batch(cfg: UNetConfig):
+    """images uniform [0,1) fp32 [N,Cin,H,W]; labels uniform ints int32 [N,H,W]."""
+    n = cfg.N * cfg.Cin * cfg.H * cfg.W
+    images = synth.uniform01(cfg.seed * 1000 + 900, n).astype(np.float32).reshape(cfg.N, cfg.Cin, cfg.H, cfg.W)
+    labels = synth.randint(cfg.seed * 1000 + 901, cfg.N * cfg.H * cfg.W, 0, cfg.classes - 1).astype(np.int32)
+    return images, labels.reshape(cfg.N, cfg.H, cfg.W)
+
+
+class UNet:
+    """Device state of the stack: plans, parameters, activations, gradients, one shared workspace."""
+
+    def __init__(self, cfg: UNetConfig, params: Optional[Dict[str, np.ndarray]] = None, device="cuda"):
+        import torch
+
+        if not torch.cuda.is_available():
+            raise RuntimeError("the UNet-shaped step runs on the GPU only")
+        rc.lib()  # fails loudly when the library is not built
+        self.cfg, self.dev, self.torch = cfg, device, torch
+        f32, u8 = torch.float32, torch.uint8
+        N = cfg.N
+        if cfg.H % (1 << cfg.depth) or cfg.W % (1 << cfg.depth):
+            raise ValueError("H and W must be divisible by 2**depth")
+
+        def buf(*shape, dtype=f32):
+            return torch.empty(shape, dtype=dtype, device=device)
+
+        self.layers = rot_layers(cfg)
+        self.plans: Dict[str, rc.Plan] = {}
+        self.act: Dict[str, Dict[str, "torch.Tensor"]] = {}
+        ws_bytes = 256
+        for name, ci, co, h, w in self.layers:
+            p = rc.Plan(N, ci, h, w, co, k=3, R=cfg.R, mode=cfg.mode, stride=1, pad=1, pool_group=cfg.pool_group or 0)
+            self.plans[name] = p
+            ws_bytes = max(ws_bytes, p.workspace_bytes)
+            self.act[name] = dict(y=buf(N, p.Cpooled, h, w), idx=buf(N, p.Cpooled, h, w, dtype=u8),
+                                  g=buf(N, p.Cpooled, h, w))
+            if p.Cpooled != co:
+                raise ValueError("the stack needs layers whose pooled channel count equals Cout (pool over all R)")
+        h, w = cfg.H, cfg.W
+        for lvl in range(cfg.depth):
+            c = cfg.widths[lvl]
+            self.act[f"pool{lvl}"] = dict(y=buf(N, c, h // 2, w // 2), idx=buf(N, c, h // 2, w // 2, dtype=u8),
+                                          g=buf(N, c, h // 2, w // 2))
+            cu = cfg.widths[lvl + 1]
+            self.act[f"up{lvl}"] = dict(y=buf(N, c, h, w), cat=buf(N, 2 * c, h, w), gcat=buf(N, 2 * c, h, w),
+                                        g=buf(N, c, h, w))
+            ws_bytes = max(ws_bytes, rc.glue_upconv2_workspace_bytes(N, cu, c, h // 2, w // 2))
+            h, w = h // 2, w // 2
+        P = cfg.H * cfg.W
+        self.act["head"] = dict(y=buf(N, cfg.classes, cfg.H, cfg.W), g=buf(N, cfg.classes, cfg.H, cfg.W))
+        ws_bytes = max(ws_bytes, rc.glue_conv1x1_workspace_bytes(N, cfg.widths[0], cfg.classes, P), N * P * 4)
+        self.ws = torch.empty(ws_bytes, dtype=u8, device=device)
+        self.loss = buf(1)
+        self.images = buf(N, cfg.Cin, cfg.H, cfg.W)
+        self.labels = buf(N, cfg.H, cfg.W, dtype=torch.int32)
+        self.params = {n: buf(*s) for n, s in param_shapes(cfg).items()}
+        self.grads = {n: buf(*s) for n, s in param_shapes(cfg).items()}
+        if params is not None:
+            self.load_params(params)
+
+    def rot_flops(self):
+        """(algorithmic, dense-equivalent) flops of one step's rotation convolutions: three passes per
+        layer (Eq. 8 shared products over Q banks plus one add per tap and orientation), no input
+        gradient for the first layer."""
+        cfg = self.cfg
+        alg = dense = 0.0
+        for i, (name, ci, co, h, w) in enumerate(self.layers):
+            Q = self.plans[name].orientations()[0]
+            P = cfg.N * h * w
+            passes = 2 if i == 0 else 3
+            alg += passes * (2.0 * P * ci * co * 9 * Q * cfg.B + P * co * 9 * cfg.R)
+            dense += passes * 2.0 * P * ci * co * 9 * cfg.R
+        return alg, dense
+
+    # ---- host <-> device plumbing -------------------------------------------------------------
+    def load_params(self, params):
+        for n, t in self.params.items():
+            t.copy_(self.torch.from_numpy(np.ascontiguousarray(params[n], dtype=np.float32)))
+
+    def load_batch(self, images, labels):
+        self.images.copy_(self.torch.from_numpy(np.ascontiguousarray(images, dtype=np.float32)))
+        self.labels.copy_(self.torch.from_numpy(np.ascontiguousarray(labels, dtype=np.int32)))
+
+    # ---- the step -----------------------------------------------------------------------------
+    def _rot_fwd(self, name, x):
+        a = self.act[name]
+        a["x"] = x
+        rc.rotconv_pool_fwd(self.plans[name], x, self.params[name], a["y"], a["idx"], self.ws)
+        rc.glue_relu_fwd(a["y"], a["y"])
+        return a["y"]
+
+    def _rot_bwd(self, name, need_dx=True):
+        """a['g'] holds dL/d(ReLU output); returns nothing: dL/dx lands in the producer's 'g' slot."""
+        a = self.act[name]
+        rc.glue_relu_bwd(a["y"], a["g"], a["g"])
+        rc.rotconv_pool_bwd_weight(self.plans[name], a["x"], a["g"], a["idx"], self.grads[name], self.ws)
+        if need_dx:
+            rc.rotconv_pool_bwd_data(self.plans[name], a["g"], a["idx"], self.params[name], a["gx"], self.ws)
+
+    def forward(self):
+        cfg, act = self.cfg, self.act
+        x = self.images
+        for lvl in range(cfg.depth):
+            x = self._rot_fwd(f"enc{lvl}a", x)
+            x = self._rot_fwd(f"enc{lvl}b", x)
+            p = act[f"pool{lvl}"]
+            rc.glue_maxpool2_fwd(x, p["y"], p["idx"])
+            x = p["y"]
+        x = self._rot_fwd("bota", x)
+        x = self._rot_fwd("botb", x)
+        for lvl in reversed(range(cfg.depth)):
+            u = act[f"up{lvl}"]
+            u["x"] = x
+            rc.glue_upconv2_fwd(x, self.params[f"up{lvl}"], u["y"])
+            rc.glue_concat2(act[f"enc{lvl}b"]["y"], u["y"], u["cat"])
+            x = self._rot_fwd(f"dec{lvl}a", u["cat"])
+            x = self._rot_fwd(f"dec{lvl}b", x)
+        hd = act["head"]
+        hd["x"] = x
+        rc.glue_conv1x1_fwd(x, self.params["head"], hd["y"])
+        rc.glue_softmax_ce(hd["y"], self.labels, self.loss, hd["g"], self.ws)
+        return self.loss
+
+    def backward(self):
+        cfg, act = self.cfg, self.act
+        hd = act["head"]
+        rc.glue_conv1x1_bwd_weight(hd["x"], hd["g"], self.grads["head"], self.ws)
+        rc.glue_conv1x1_bwd_data(hd["g"], self.params["head"], act["dec0b"]["g"])
+        for lvl in range(cfg.depth):
+            u = act[f"up{lvl}"]
+            act[f"dec{lvl}b"]["gx"] = act[f"dec{lvl}a"]["g"]
+            self._rot_bwd(f"dec{lvl}b")
+            act[f"dec{lvl}a"]["gx"] = u["gcat"]
+            self._rot_bwd(f"dec{lvl}a")
+            # gradient of the concatenation: skip half into the encoder output's slot, up half on
+            rc.glue_split2(u["gcat"], act[f"enc{lvl}b"]["g"], u["g"], accumulate_a=False)
+            below = act["botb"] if lvl == cfg.depth - 1 else act[f"dec{lvl + 1}b"]
+            rc.glue_upconv2_bwd_weight(u["x"], u["g"], self.grads[f"up{lvl}"], self.ws)
+            rc.glue_upconv2_bwd_data(u["g"], self.params[f"up{lvl}"], below["g"])
+        act["botb"]["gx"] = act["bota"]["g"]
+        self._rot_bwd("botb")
+        act["bota"]["gx"] = act[f"pool{cfg.depth - 1}"]["g"]
+        self._rot_bwd("bota")
+        for lvl in reversed(range(cfg.depth)):
+            p = act[f"pool{lvl}"]
+            # pooled branch adds to the skip gradient already in the slot
+            rc.glue_maxpool2_bwd(p["g"], p["idx"], act[f"enc{lvl}b"]["g"], accumulate=True)
+            act[f"enc{lvl}b"]["gx"] = act[f"enc{lvl}a"]["g"]
+            self._rot_bwd(f"enc{lvl}b")
+            if lvl > 0:
+                act[f"enc{lvl}a"]["gx"] = act[f"pool{lvl - 1}"]["g"]
+                self._rot_bwd(f"enc{lvl}a")
+            else:
+                self._rot_bwd("enc0a", need_dx=False)
+
+    def step(self):
+        self.forward()
+        self.backward()
+        return self.loss

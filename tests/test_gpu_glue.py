@@ -1,0 +1,255 @@
+"""GPU parity of the network glue (include/unetglue.h) and of the UNet-shaped training step
+against the CPU oracle (oracle/unet_oracle.py), called through the C-ABI binding."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import rotconv_oracle as orc
+from oracle import unet_oracle as uo
+from paper_2512_08888_amd import binding as rc
+from paper_2512_08888_amd import unet as un
+from parity_util import RTOL, assert_close, check_idx, dev
+
+pytestmark = pytest.mark.gpu
+
+
+def nan(*shape, dtype=torch.float32):
+    t = torch.empty(shape, dtype=dtype, device="cuda")
+    t.fill_(float("nan") if dtype.is_floating_point else 255)
+    return t
+
+
+def f32(rng, *shape, scale=1.0):
+    return (rng.standard_normal(shape) * scale).astype(np.float32)
+
+
+def host(t):
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+def test_relu_fwd_bwd():
+    rng = np.random.default_rng(1)
+    x = f32(rng, 3, 5, 7, 11)
+    x.flat[::7] = 0.0
+    dy = f32(rng, 3, 5, 7, 11)
+    y = nan(*x.shape)
+    rc.glue_relu_fwd(dev(x), y)
+    assert np.array_equal(host(y), uo.relu_fwd(x).astype(np.float32))
+    dx = nan(*x.shape)
+    rc.glue_relu_bwd(y, dev(dy), dx)
+    assert np.array_equal(host(dx), uo.relu_bwd(uo.relu_fwd(x), dy).astype(np.float32))
+    # in place
+    t = dev(x)
+    rc.glue_relu_fwd(t, t)
+    assert np.array_equal(host(t), host(y))
+
+
+@pytest.mark.parametrize("shape", [(2, 3, 6, 10), (1, 5, 2, 2), (3, 2, 34, 18)])
+def test_maxpool2(shape):
+    rng = np.random.default_rng(2)
+    x = rng.integers(-4, 5, size=shape).astype(np.float32)      # many ties: the first maximum must win
+    N, C, H, W = shape
+    y, idx = nan(N, C, H // 2, W // 2), nan(N, C, H // 2, W // 2, dtype=torch.uint8)
+    rc.glue_maxpool2_fwd(dev(x), y, idx)
+    yr, ir = uo.maxpool2_fwd(x)
+    assert np.array_equal(host(y), yr.astype(np.float32)) and np.array_equal(host(idx), ir)
+    dy = f32(rng, N, C, H // 2, W // 2)
+    dx = nan(*shape)
+    rc.glue_maxpool2_bwd(dev(dy), idx, dx)
+    ref = uo.maxpool2_bwd(dy, ir, H, W)
+    assert np.array_equal(host(dx), ref.astype(np.float32))
+    base = f32(rng, *shape)
+    acc = dev(base)
+    rc.glue_maxpool2_bwd(dev(dy), idx, acc, accumulate=True)
+    assert np.array_equal(host(acc), (base + ref.astype(np.float32)).astype(np.float32))
+
+
+@pytest.mark.parametrize("N,Cin,Cout,H,W", [(2, 5, 3, 3, 5), (1, 40, 36, 9, 7), (2, 130, 70, 12, 16), (1, 256, 128, 16, 16)])
+def test_upconv2(N, Cin, Cout, H, W):
+    rng = np.random.default_rng(3)
+    x, w = f32(rng, N, Cin, H, W), f32(rng, Cin, Cout, 2, 2, scale=Cin ** -0.5)
+    dy = f32(rng, N, Cout, 2 * H, 2 * W)
+    y = nan(N, Cout, 2 * H, 2 * W)
+    rc.glue_upconv2_fwd(dev(x), dev(w), y)
+    assert_close(host(y), uo.upconv2_fwd(x, w), "upconv2_fwd")
+    dxr, dwr = uo.upconv2_bwd(x, w, dy)
+    dx = nan(N, Cin, H, W)
+    rc.glue_upconv2_bwd_data(dev(dy), dev(w), dx)
+    assert_close(host(dx), dxr, "upconv2_bwd_data")
+    dw = nan(Cin, Cout, 2, 2)
+    ws = torch.empty(max(256, rc.glue_upconv2_workspace_bytes(N, Cin, Cout, H, W)), dtype=torch.uint8, device="cuda")
+    rc.glue_upconv2_bwd_weight(dev(x), dev(dy), dw, ws)
+    assert_close(host(dw), dwr, "upconv2_bwd_weight")
+    first = host(dw).copy()
+    rc.glue_upconv2_bwd_weight(dev(x), dev(dy), dw, ws)
+    assert np.array_equal(first, host(dw))                      # fixed reduction order
+
+
+def test_concat_split():
+    rng = np.random.default_rng(4)
+    a, b = f32(rng, 3, 4, 5, 6), f32(rng, 3, 7, 5, 6)
+    out = nan(3, 11, 5, 6)
+    rc.glue_concat2(dev(a), dev(b), out)
+    cat = np.concatenate([a, b], axis=1)
+    assert np.array_equal(host(out), cat)
+    da, db = nan(*a.shape), nan(*b.shape)
+    rc.glue_split2(out, da, db)
+    assert np.array_equal(host(da), a) and np.array_equal(host(db), b)
+    base = f32(rng, *a.shape)
+    da = dev(base)
+    rc.glue_split2(out, da, db, accumulate_a=True)
+    assert np.array_equal(host(da), base + a)
+
+
+@pytest.mark.parametrize("N,Cin,Cout,H,W", [(2, 7, 3, 5, 9), (1, 64, 6, 48, 40), (2, 150, 130, 6, 22)])
+def test_conv1x1(N, Cin, Cout, H, W):
+    rng = np.random.default_rng(5)
+    x, w, dy = f32(rng, N, Cin, H, W), f32(rng, Cout, Cin, scale=Cin ** -0.5), f32(rng, N, Cout, H, W)
+    y = nan(N, Cout, H, W)
+    rc.glue_conv1x1_fwd(dev(x), dev(w), y)
+    assert_close(host(y), uo.conv1x1_fwd(x, w), "conv1x1_fwd")
+    dxr, dwr = uo.conv1x1_bwd(x, w, dy)
+    dx = nan(N, Cin, H, W)
+    rc.glue_conv1x1_bwd_data(dev(dy), dev(w), dx)
+    assert_close(host(dx), dxr, "conv1x1_bwd_data")
+    dw = nan(Cout, Cin)
+    ws = torch.empty(max(256, rc.glue_conv1x1_workspace_bytes(N, Cin, Cout, H * W)), dtype=torch.uint8, device="cuda")
+    rc.glue_conv1x1_bwd_weight(dev(x), dev(dy), dw, ws)
+    assert_close(host(dw), dwr, "conv1x1_bwd_weight")
+
+
+@pytest.mark.parametrize("N,K,H,W", [(1, 2, 3, 5), (2, 6, 33, 20), (3, 11, 8, 8)])
+def test_softmax_ce(N, K, H, W):
+    rng = np.random.default_rng(6)
+    lg = f32(rng, N, K, H, W, scale=4.0)
+    lab = rng.integers(0, K, size=(N, H, W)).astype(np.int32)
+    loss, dl = nan(1), nan(N, K, H, W)
+    ws = torch.empty(N * H * W * 4, dtype=torch.uint8, device="cuda")
+    rc.glue_softmax_ce(dev(lg), dev(lab), loss, dl, ws)
+    lr, dlr = uo.softmax_ce(lg, lab)
+    assert abs(float(host(loss)[0]) - lr) <= RTOL * abs(lr)
+    assert_close(host(dl), dlr, "softmax_ce dlogits")
+
+
+def test_softmax_ce_ignores_out_of_range_labels():
+    lg = np.zeros((1, 3, 2, 2), np.float32)
+    lab = np.array([[[0, 7], [-1, 2]]], np.int32)
+    loss, dl = nan(1), nan(1, 3, 2, 2)
+    ws = torch.empty(16, dtype=torch.uint8, device="cuda")
+    rc.glue_softmax_ce(dev(lg), dev(lab), loss, dl, ws)
+    assert np.isclose(float(host(loss)[0]), 2 * np.log(3) / 4, rtol=1e-6)
+    d = host(dl)
+    assert np.all(d[0, :, 0, 1] == 0) and np.all(d[0, :, 1, 0] == 0)
+
+
+# ---- the stack ------------------------------------------------------------------------------------
+
+def _run_stack(cfg):
+    params = un.make_params(cfg)
+    images, labels = un.make_batch(cfg)
+    net = un.UNet(cfg, params)
+    net.load_batch(images, labels)
+    for t in list(net.grads.values()) + [net.loss]:
+        t.fill_(float("nan"))
+    net.step()
+    torch.cuda.synchronize()
+    return net, params, images, labels
+
+
+SMALL = [
+    un.UNetConfig("u_r4_d2", 2, 3, 32, 64, (8, 12, 16), 4, R=4, mode="exact90", seed=11),
+    un.UNetConfig("u_r4_d3", 1, 3, 64, 32, (16, 24, 40, 72), 6, R=4, mode="exact90", seed=12),
+    un.UNetConfig("u_r16_d2", 1, 3, 32, 32, (8, 8, 16), 3, R=16, mode="bilinear", pool_group=16, seed=13),
+]
+
+
+@pytest.mark.parametrize("cfg", SMALL, ids=[c.name for c in SMALL])
+def test_unet_step_teacher_forced(cfg):
+    """Every call of the step against the oracle's result for the same call, each fed the tensors the
+    GPU step itself produced (so one near-tie arg-max cannot cascade), plus the loss."""
+    net, params, images, labels = _run_stack(cfg)
+    A = net.act
+    H = lambda t: t.detach().cpu().numpy().astype(np.float64)
+    p64 = {k: v.astype(np.float64) for k, v in params.items()}
+    # forward, layer by layer
+    for name, ci, co, h, w in net.layers:
+        x = H(A[name]["x"])
+        y_ref, yp_ref, idx_ref, w_rot = orc.layer_fwd(x, p64[name], cfg.R, None, cfg.mode, 1, 1, cfg.pool_group)
+        assert_close(H(A[name]["y"]), uo.relu_fwd(yp_ref), f"{name} fwd")
+        abs_terms = orc.rotconv_fwd(np.abs(x), np.abs(w_rot), 1, 1)
+        check_idx(H(A[name]["idx"]).astype(np.uint8), y_ref, abs_terms, cfg.pool_group or cfg.R, f"{name} idx")
+    for lvl in range(cfg.depth):
+        p = A[f"pool{lvl}"]
+        yr, ir = uo.maxpool2_fwd(H(A[f"enc{lvl}b"]["y"]))
+        assert np.array_equal(H(p["y"]), yr) and np.array_equal(H(p["idx"]).astype(np.uint8), ir)
+        u = A[f"up{lvl}"]
+        assert_close(H(u["y"]), uo.upconv2_fwd(H(u["x"]), p64[f"up{lvl}"]), f"up{lvl} fwd")
+        assert np.array_equal(H(u["cat"]), np.concatenate([H(A[f"enc{lvl}b"]["y"]), H(u["y"])], axis=1))
+    hd = A["head"]
+    assert_close(H(hd["y"]), uo.conv1x1_fwd(H(hd["x"]), p64["head"]), "head fwd")
+    loss_ref, dl_ref = uo.softmax_ce(H(hd["y"]), labels)
+    assert abs(float(net.loss.cpu()[0]) - loss_ref) <= RTOL * abs(loss_ref)
+    assert_close(H(hd["g"]), dl_ref, "dlogits")
+    # backward, call by call, on the GPU's own upstream gradients and arg-max indices
+    # (a gradient slot is masked in place by its owner's ReLU backward after it is written, so a
+    # producer's dX is compared where that mask kept it)
+    masked = lambda owner, ref: np.where(H(A[owner]["y"]) > 0, ref, 0.0)
+    dxr, dwr = uo.conv1x1_bwd(H(hd["x"]), p64["head"], H(hd["g"]))
+    assert_close(H(net.grads["head"]), dwr, "head dW")
+    assert_close(H(A["dec0b"]["g"]), masked("dec0b", dxr), "head dX")
+    for i, (name, ci, co, h, w) in enumerate(net.layers):
+        a = A[name]
+        g = H(a["g"])                       # after the in-place ReLU backward: gradient of the pooled map
+        assert np.all(g[H(a["y"]) <= 0] == 0), f"{name}: ReLU backward"
+        dx_ref, dw_ref = orc.layer_bwd(H(a["x"]), p64[name], g, H(a["idx"]).astype(np.uint8), cfg.R, None, cfg.mode,
+                                       1, 1, cfg.pool_group)
+        assert_close(H(net.grads[name]), dw_ref, f"{name} dW")
+        if i == 0:
+            continue
+        if name.endswith("b"):              # lands in the block's first layer's slot
+            assert_close(H(a["gx"]), masked(name[:-1] + "a", dx_ref), f"{name} dX")
+        else:                               # lands in a pool's or a concatenation's slot: not touched again
+            assert_close(H(a["gx"]), dx_ref, f"{name} dX")
+    for lvl in range(cfg.depth):
+        u = A[f"up{lvl}"]
+        C = cfg.widths[lvl]
+        dx_ref, dw_ref = uo.upconv2_bwd(H(u["x"]), p64[f"up{lvl}"], H(u["g"]))
+        assert_close(H(net.grads[f"up{lvl}"]), dw_ref, f"up{lvl} dW")
+        below = "botb" if lvl == cfg.depth - 1 else f"dec{lvl + 1}b"
+        assert_close(H(A[below]["g"]), masked(below, dx_ref), f"up{lvl} dX")
+        assert np.array_equal(H(u["gcat"])[:, C:], H(u["g"]))
+        # skip gradient + the 2x2 max-pool's routed gradient, then the encoder layer's ReLU mask
+        p = A[f"pool{lvl}"]
+        ref = H(u["gcat"])[:, :C] + uo.maxpool2_bwd(H(p["g"]), H(p["idx"]).astype(np.uint8), *A[f"enc{lvl}b"]["y"].shape[2:])
+        assert_close(H(A[f"enc{lvl}b"]["g"]), masked(f"enc{lvl}b", ref), f"enc{lvl}b upstream gradient")
+
+
+def test_unet_step_end_to_end_loss_and_gradients():
+    """The whole step against the oracle's whole step on one small stack: loss to the fp32 bar, the
+    gradients in relative L2 norm (an arg-max that flips on a near-tie moves single elements, not the
+    norm; the teacher-forced test above holds each call to the elementwise bar)."""
+    cfg = SMALL[0]
+    net, params, images, labels = _run_stack(cfg)
+    p64 = {k: v.astype(np.float64) for k, v in params.items()}
+    loss, grads, acts = uo.unet_step(images.astype(np.float64), labels, p64, cfg.R, cfg.mode, cfg.pool_group)
+    assert abs(float(net.loss.cpu()[0]) - loss) <= RTOL * abs(loss)
+    for name, gref in grads.items():
+        got = net.grads[name].cpu().numpy().astype(np.float64)
+        rel = np.linalg.norm(got - gref) / max(np.linalg.norm(gref), 1e-30)
+        assert rel < 5e-3, (name, rel)
+    flips = sum(int((net.act[n]["idx"].cpu().numpy() != acts[n]["idx"]).sum()) for n, *_ in net.layers)
+    total = sum(net.act[n]["idx"].numel() for n, *_ in net.layers)
+    assert flips <= 1e-3 * total, (flips, total)
+
+
+def test_unet_step_is_deterministic():
+    cfg = SMALL[1]
+    net, *_ = _run_stack(cfg)
+    first = {k: v.cpu().numpy().copy() for k, v in net.grads.items()}
+    l0 = float(net.loss.cpu()[0])
+    net.step()
+    torch.cuda.synchronize()
+    assert float(net.loss.cpu()[0]) == l0
+    for k, v in net.grads.items():
+        assert np.array_equal(first[k], v.cpu().numpy()), k

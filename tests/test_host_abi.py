@@ -15,10 +15,10 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 RNG = np.random.default_rng(7)
 
 
-def declared_functions():
-    text = open(os.path.join(ROOT, "include", "rotconv.h")).read()
+def declared_functions(header="rotconv.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(rotconv_[a-z_0-9]+|orient_maxpool_[a-z]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(rotconv_[a-z_0-9]+|orient_maxpool_[a-z]+|glue_[a-z_0-9]+)\s*\(", text)))
 
 
 def test_library_exports_every_declared_symbol():
@@ -28,6 +28,28 @@ def test_library_exports_every_declared_symbol():
     for n in names:
         assert hasattr(L, n), n
     assert sorted(rc.EXPORTS) == names
+    glue = declared_functions("unetglue.h")
+    assert len(glue) == 15 and sorted(rc.GLUE_EXPORTS) == glue
+    for n in glue:
+        assert hasattr(L, n), n
+
+
+def test_library_is_not_older_than_its_sources():
+    from paper_2512_08888_amd import build as b
+
+    assert b.stale_sources() == [], "rebuild the library: python -c 'import __graft_entry__ as g; g.build()'"
+
+
+def test_glue_argument_errors():
+    L = rc.lib()
+    assert L.glue_relu_fwd(None, 1, 4, None) == rc.ERR_NULL
+    assert L.glue_maxpool2_fwd(1, 1, 1, 1, 1, 3, 4, None) == rc.ERR_SHAPE      # odd height
+    assert L.glue_maxpool2_bwd(1, 1, 1, 1, 1, 4, 3, 0, None) == rc.ERR_SHAPE
+    assert L.glue_upconv2_fwd(1, 1, 1, 0, 1, 1, 1, 1, None) == rc.ERR_SHAPE
+    assert L.glue_upconv2_bwd_weight(1, 1, 1, 1, 4, 4, 2, 2, None, 0, None) == rc.ERR_WORKSPACE
+    assert L.glue_conv1x1_bwd_weight(1, 1, 1, 1, 4, 4, 16, 1, 8, None) == rc.ERR_WORKSPACE
+    assert L.glue_softmax_ce(1, 1, 1, 1, 1, 3, 16, None, 0, None) == rc.ERR_WORKSPACE
+    assert L.glue_upconv2_workspace_bytes(2, 8, 4, 4, 4) >= 2 * 8 * 16 * 4
 
 
 def test_status_strings():
