@@ -64,12 +64,105 @@ def cpu_baseline(cfg, Q):
     }
 
 
+def bench_unet(name, steps, warmup):
+    """ms per training step of the UNet-shaped stack (benchmark configurations 4 and 5, fp32), whole
+    step timed between synchronisations; then one more step with an event pair around every library
+    call for the per-call breakdown."""
+    import torch
+    from paper_2512_08888_amd import unet as un
+
+    cfg = un.UNET_CONFIGS[name]
+    net = un.UNet(cfg, un.make_params(cfg))
+    net.load_batch(*un.make_batch(cfg))
+    for _ in range(warmup):
+        net.step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        net.step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    net.trace = []
+    net.step()
+    torch.cuda.synchronize()
+    by_call, by_layer = {}, {}
+    for what, where, e0, e1 in net.trace:
+        t = e0.elapsed_time(e1)
+        by_call[what] = by_call.get(what, 0.0) + t
+        if what.startswith("rotconv"):
+            by_layer.setdefault(where, {})[what.replace("rotconv_pool_", "")] = round(t, 4)
+    net.trace = None
+    alg, dense = net.rot_flops()
+    rot_ms = sum(t for k, t in by_call.items() if k.startswith("rotconv"))
+    loss = float(net.loss.cpu()[0])
+    out = {
+        "workload": f"{cfg.name}: UNet-shaped stack, N={cfg.N} {cfg.H}x{cfg.W} widths={list(cfg.widths)} "
+                    f"classes={cfg.classes} R={cfg.R} {cfg.mode}, one training step (fwd+bwd), fp32",
+        "ms_per_step": ms, "steps": steps, "warmup": warmup, "loss": loss,
+        "rotconv_flops_algorithmic": alg, "rotconv_flops_dense_equivalent": dense,
+        "rotconv_ms": rot_ms, "glue_ms": sum(by_call.values()) - rot_ms,
+        "rotconv_tflops_algorithmic": alg / (rot_ms * 1e-3) / 1e12,
+        "step_tflops_algorithmic": alg / (ms * 1e-3) / 1e12,
+        "frac_of_fp32_peak": alg / (ms * 1e-3) / 1e12 / PEAK_FP32_TFLOPS,
+        "ms_by_call": {k: round(v, 4) for k, v in sorted(by_call.items())},
+        "rotconv_ms_by_layer": by_layer,
+        "kernels": {n: [net.plans[n].kernel_name(i) for i in range(3)] for n, *_ in net.layers},
+    }
+    del net
+    torch.cuda.empty_cache()
+    return out
+
+
+def cpu_baseline_unet(name):
+    """The oracle's whole step on a bounded sample of the stack: one image of 64x64 (R=4) or 32x32
+    (R=16) pixels, the full widths."""
+    import dataclasses
+    import numpy as np
+    from oracle import unet_oracle as uo
+    from paper_2512_08888_amd import unet as un
+
+    cfg = un.UNET_CONFIGS[name]
+    side = 64 if cfg.R <= 4 else 32
+    sc = dataclasses.replace(cfg, N=1, H=side, W=side)
+    params = {k: v.astype(np.float64) for k, v in un.make_params(sc).items()}
+    images, labels = un.make_batch(sc)
+    t0 = time.perf_counter()
+    uo.unet_step(images.astype(np.float64), labels, params, sc.R, sc.mode, sc.pool_group)
+    dt = time.perf_counter() - t0
+    scale = (cfg.N * cfg.H * cfg.W) / (sc.N * sc.H * sc.W)
+    cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    return {"value": dt * scale * 1e3, "unit": "ms/step (extrapolated by pixel count)", "cores": cores, "kind": "oracle",
+            "sample": f"{cfg.name} stack with full widths on N=1, {side}x{side} (1/{scale:.0f} of the pixels), fwd+bwd, fp64, "
+                      f"{dt:.2f} s", "seconds": dt}
+
+
+def main_unet(args):
+    import torch
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    r = bench_unet(args.workload, args.steps, args.warmup)
+    out = {
+        "metric": "unet_train_step_ms", "value": r["ms_per_step"], "unit": "ms", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": r["ms_per_step"], "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic", "config": r,
+        "roofline": {"bound": "mfma",
+                     "kernel": "all rotation-convolution calls of the step (fwd, bwd_data, bwd_weight; 18 layers)",
+                     "achieved": r["rotconv_tflops_algorithmic"], "peak": PEAK_FP32_TFLOPS, "unit": "TFLOP/s",
+                     "frac": r["rotconv_tflops_algorithmic"] / PEAK_FP32_TFLOPS, "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline_unet(args.workload)
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3"])
+    ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4", "C5"])
+    ap.add_argument("--no-unet", action="store_true", help="skip the UNet-shaped steps appended to the default line")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (2 GiB of HBM traffic) so that rocprofv3 "
@@ -79,6 +172,9 @@ def main():
         print("bench.py: this build measures one GPU only (the path shards over the batch; "
               "see DESIGN.md); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
+
+    if args.workload in ("C4", "C5"):
+        return main_unet(args)
 
     import torch
     from paper_2512_08888_amd import binding as rc
@@ -161,6 +257,10 @@ def main():
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, Q)
+    if args.workload == "C2" and not args.no_unet:
+        # the second half of the headline metric: ms per UNet-shaped training step at R=4 and R=16
+        del x, w, g, yp, idx, dx, dw
+        out["unet_train_step"] = {n: bench_unet(n, 5, 2) for n in ("C4", "C5")}
     print(json.dumps(out), flush=True)
 
 

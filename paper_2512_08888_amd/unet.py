@@ -135,6 +135,8 @@ class UNet:
         ws_bytes = max(ws_bytes, rc.glue_conv1x1_workspace_bytes(N, cfg.widths[0], cfg.classes, P), N * P * 4)
         self.ws = torch.empty(ws_bytes, dtype=u8, device=device)
         self.loss = buf(1)
+        self.trace = None         # a list turns on per-call event timing
+        self._where = ""
         self.images = buf(N, cfg.Cin, cfg.H, cfg.W)
         self.labels = buf(N, cfg.H, cfg.W, dtype=torch.int32)
         self.params = {n: buf(*s) for n, s in param_shapes(cfg).items()}
@@ -166,20 +168,38 @@ class UNet:
         self.labels.copy_(self.torch.from_numpy(np.ascontiguousarray(labels, dtype=np.int32)))
 
     # ---- the step -----------------------------------------------------------------------------
+    def _c(self, what, fn, *args, **kw):
+        """Issue one library call; with self.trace a list, bracket it with events on the current stream
+        and record (call name, layer it belongs to, start, end)."""
+        if self.trace is None:
+            fn(*args, **kw)
+            return
+        ev = self.torch.cuda.Event
+        e0, e1 = ev(enable_timing=True), ev(enable_timing=True)
+        e0.record()
+        fn(*args, **kw)
+        e1.record()
+        self.trace.append((what, self._where, e0, e1))
+
     def _rot_fwd(self, name, x):
+        self._where = name
         a = self.act[name]
         a["x"] = x
-        rc.rotconv_pool_fwd(self.plans[name], x, self.params[name], a["y"], a["idx"], self.ws)
-        rc.glue_relu_fwd(a["y"], a["y"])
+        self._c("rotconv_pool_fwd", rc.rotconv_pool_fwd, self.plans[name], x, self.params[name], a["y"], a["idx"],
+                self.ws)
+        self._c("glue_relu_fwd", rc.glue_relu_fwd, a["y"], a["y"])
         return a["y"]
 
     def _rot_bwd(self, name, need_dx=True):
         """a['g'] holds dL/d(ReLU output); returns nothing: dL/dx lands in the producer's 'g' slot."""
+        self._where = name
         a = self.act[name]
-        rc.glue_relu_bwd(a["y"], a["g"], a["g"])
-        rc.rotconv_pool_bwd_weight(self.plans[name], a["x"], a["g"], a["idx"], self.grads[name], self.ws)
+        self._c("glue_relu_bwd", rc.glue_relu_bwd, a["y"], a["g"], a["g"])
+        self._c("rotconv_pool_bwd_weight", rc.rotconv_pool_bwd_weight, self.plans[name], a["x"], a["g"], a["idx"],
+                self.grads[name], self.ws)
         if need_dx:
-            rc.rotconv_pool_bwd_data(self.plans[name], a["g"], a["idx"], self.params[name], a["gx"], self.ws)
+            self._c("rotconv_pool_bwd_data", rc.rotconv_pool_bwd_data, self.plans[name], a["g"], a["idx"],
+                    self.params[name], a["gx"], self.ws)
 
     def forward(self):
         cfg, act = self.cfg, self.act
@@ -188,28 +208,32 @@ class UNet:
             x = self._rot_fwd(f"enc{lvl}a", x)
             x = self._rot_fwd(f"enc{lvl}b", x)
             p = act[f"pool{lvl}"]
-            rc.glue_maxpool2_fwd(x, p["y"], p["idx"])
+            self._where = f"pool{lvl}"
+            self._c("glue_maxpool2_fwd", rc.glue_maxpool2_fwd, x, p["y"], p["idx"])
             x = p["y"]
         x = self._rot_fwd("bota", x)
         x = self._rot_fwd("botb", x)
         for lvl in reversed(range(cfg.depth)):
             u = act[f"up{lvl}"]
             u["x"] = x
-            rc.glue_upconv2_fwd(x, self.params[f"up{lvl}"], u["y"])
-            rc.glue_concat2(act[f"enc{lvl}b"]["y"], u["y"], u["cat"])
+            self._where = f"up{lvl}"
+            self._c("glue_upconv2_fwd", rc.glue_upconv2_fwd, x, self.params[f"up{lvl}"], u["y"])
+            self._c("glue_concat2", rc.glue_concat2, act[f"enc{lvl}b"]["y"], u["y"], u["cat"])
             x = self._rot_fwd(f"dec{lvl}a", u["cat"])
             x = self._rot_fwd(f"dec{lvl}b", x)
         hd = act["head"]
         hd["x"] = x
-        rc.glue_conv1x1_fwd(x, self.params["head"], hd["y"])
-        rc.glue_softmax_ce(hd["y"], self.labels, self.loss, hd["g"], self.ws)
+        self._where = "head"
+        self._c("glue_conv1x1_fwd", rc.glue_conv1x1_fwd, x, self.params["head"], hd["y"])
+        self._c("glue_softmax_ce", rc.glue_softmax_ce, hd["y"], self.labels, self.loss, hd["g"], self.ws)
         return self.loss
 
     def backward(self):
         cfg, act = self.cfg, self.act
         hd = act["head"]
-        rc.glue_conv1x1_bwd_weight(hd["x"], hd["g"], self.grads["head"], self.ws)
-        rc.glue_conv1x1_bwd_data(hd["g"], self.params["head"], act["dec0b"]["g"])
+        self._where = "head"
+        self._c("glue_conv1x1_bwd_weight", rc.glue_conv1x1_bwd_weight, hd["x"], hd["g"], self.grads["head"], self.ws)
+        self._c("glue_conv1x1_bwd_data", rc.glue_conv1x1_bwd_data, hd["g"], self.params["head"], act["dec0b"]["g"])
         for lvl in range(cfg.depth):
             u = act[f"up{lvl}"]
             act[f"dec{lvl}b"]["gx"] = act[f"dec{lvl}a"]["g"]
@@ -217,10 +241,12 @@ class UNet:
             act[f"dec{lvl}a"]["gx"] = u["gcat"]
             self._rot_bwd(f"dec{lvl}a")
             # gradient of the concatenation: skip half into the encoder output's slot, up half on
-            rc.glue_split2(u["gcat"], act[f"enc{lvl}b"]["g"], u["g"], accumulate_a=False)
+            self._where = f"up{lvl}"
+            self._c("glue_split2", rc.glue_split2, u["gcat"], act[f"enc{lvl}b"]["g"], u["g"], accumulate_a=False)
             below = act["botb"] if lvl == cfg.depth - 1 else act[f"dec{lvl + 1}b"]
-            rc.glue_upconv2_bwd_weight(u["x"], u["g"], self.grads[f"up{lvl}"], self.ws)
-            rc.glue_upconv2_bwd_data(u["g"], self.params[f"up{lvl}"], below["g"])
+            self._c("glue_upconv2_bwd_weight", rc.glue_upconv2_bwd_weight, u["x"], u["g"], self.grads[f"up{lvl}"],
+                    self.ws)
+            self._c("glue_upconv2_bwd_data", rc.glue_upconv2_bwd_data, u["g"], self.params[f"up{lvl}"], below["g"])
         act["botb"]["gx"] = act["bota"]["g"]
         self._rot_bwd("botb")
         act["bota"]["gx"] = act[f"pool{cfg.depth - 1}"]["g"]
@@ -228,7 +254,9 @@ class UNet:
         for lvl in reversed(range(cfg.depth)):
             p = act[f"pool{lvl}"]
             # pooled branch adds to the skip gradient already in the slot
-            rc.glue_maxpool2_bwd(p["g"], p["idx"], act[f"enc{lvl}b"]["g"], accumulate=True)
+            self._where = f"pool{lvl}"
+            self._c("glue_maxpool2_bwd", rc.glue_maxpool2_bwd, p["g"], p["idx"], act[f"enc{lvl}b"]["g"],
+                    accumulate=True)
             act[f"enc{lvl}b"]["gx"] = act[f"enc{lvl}a"]["g"]
             self._rot_bwd(f"enc{lvl}b")
             if lvl > 0:

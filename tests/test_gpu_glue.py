@@ -253,3 +253,101 @@ def test_unet_step_is_deterministic():
     assert float(net.loss.cpu()[0]) == l0
     for k, v in net.grads.items():
         assert np.array_equal(first[k], v.cpu().numpy()), k
+
+
+# ---- the benchmark's stacks at full size ------------------------------------------------------------
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _pts(seed, n, dims):
+    from paper_2512_08888_amd import synth
+    return np.stack([synth.randint(seed + i, n, 0, d - 1) for i, d in enumerate(dims)], axis=1).astype(np.int32)
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("cfg", [un.C4, un.C5], ids=["C4", "C5"])
+def test_unet_full_size_sampled(cfg):
+    """The benchmark's stack in the launch configuration bench.py times.  Every rotation-convolution call is
+    checked on sampled outputs the oracle computes one by one from the tensors that call read on the GPU
+    (forward values and arg-max, input gradient, weight gradient), every glue call against its definition,
+    plus the homogeneity identity <w, dW> = <y, g> per layer at full size."""
+    net, params, images, labels = _run_stack(cfg)
+    A, R, G = net.act, cfg.R, cfg.pool_group or cfg.R
+    H = lambda t: t.detach().cpu().numpy()
+    ns, npairs = 384, 4
+    for li, (name, ci, co, h, w) in enumerate(net.layers):
+        a = A[name]
+        x, y, idx, g = H(a["x"]), H(a["y"]), H(a["idx"]), H(a["g"])
+        wb = params[name].astype(np.float64)
+        w_rot = orc.expand_bank(wb, R, None, cfg.mode)
+        pts = _pts(1000 + li, ns, (cfg.N, co, h, w))
+        yr = orc.rotconv_fwd_at(x, w_rot, pts, 1, 1)
+        ya = orc.rotconv_fwd_at(np.abs(x), np.abs(w_rot), pts, 1, 1)
+        best = yr.max(axis=1)
+        got_v = y[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3]].astype(np.float64)
+        got_i = idx[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3]].astype(np.int64)
+        rms = float(np.sqrt(np.mean(best ** 2)))
+        assert np.all(np.abs(got_v - np.maximum(best, 0)) <= RTOL * np.abs(best) + RTOL * rms), f"{name} fwd samples"
+        tau = 64.0 * np.finfo(np.float32).eps * ya.max(axis=1)
+        assert np.all(got_i < R) and np.all(yr[np.arange(ns), got_i] >= best - tau), f"{name} arg-max samples"
+        # weight gradient: sampled (co, ci) slices, reduced through Eq. 16 by the oracle
+        pairs = _pts(2000 + li, npairs, (co, ci))
+        dwr = orc.rotconv_pool_bwd_weight_at(x, g, idx, pairs, R, 3, G, 1, 1)
+        dw = H(net.grads[name])
+        got_dw, ref_dw = [], []
+        for t, (o, c) in enumerate(pairs):
+            full = np.zeros((R, 1, 1, 3, 3))
+            full[:, 0, 0] = dwr[t]
+            ref_dw.append(orc.reduce_bank_grad(full, None, cfg.mode)[:, 0, 0])
+            got_dw.append(dw[:, o, c])
+        assert_close(np.array(got_dw), np.array(ref_dw), f"{name} dW samples")
+        # homogeneity through max-pool and ReLU: <w, dW> = <y, g>
+        lhs = float((params[name].astype(np.float64) * dw).sum())
+        rhs = float((y.astype(np.float64) * g).sum())
+        scale = float(np.abs(y.astype(np.float64) * g).sum())
+        assert abs(lhs - rhs) <= 1e-5 * scale, (name, lhs, rhs, scale)
+        # input gradient at sampled inputs of one image (slots a later in-place ReLU backward masks are
+        # compared where the mask kept them)
+        if li > 0 and co * R * h * w <= 300_000_000:
+            n0 = li % cfg.N
+            dy = orc.orient_maxpool_bwd(g[n0:n0 + 1], idx[n0:n0 + 1], R, G)
+            ptx = _pts(3000 + li, ns, (1, ci, h, w))
+            ref = orc.rotconv_bwd_data_at(dy, w_rot, ptx, h, w, 1, 1)
+            got = H(a["gx"])[n0][ptx[:, 1], ptx[:, 2], ptx[:, 3]].astype(np.float64)
+            if name.endswith("b"):
+                keep = H(A[name[:-1] + "a"]["y"])[n0][ptx[:, 1], ptx[:, 2], ptx[:, 3]] > 0
+                ref = np.where(keep, ref, 0.0)
+            assert_close(got, ref, f"{name} dX samples")
+            del dy
+        _say(f"  {cfg.name} {name}: {ci}->{co} @{h}x{w} ok")
+    # glue at full size
+    for lvl in range(cfg.depth):
+        p, e = A[f"pool{lvl}"], A[f"enc{lvl}b"]
+        yr, ir = uo.maxpool2_fwd(H(e["y"]))
+        assert np.array_equal(H(p["y"]), yr.astype(np.float32)) and np.array_equal(H(p["idx"]), ir)
+        u = A[f"up{lvl}"]
+        C = cfg.widths[lvl]
+        xin, wu, yu = H(u["x"]).astype(np.float64), params[f"up{lvl}"].astype(np.float64), H(u["y"])
+        pts = _pts(4000 + lvl, 512, (cfg.N, C, yu.shape[2], yu.shape[3]))
+        ref = np.array([xin[n, :, oy // 2, ox // 2] @ wu[:, c, oy % 2, ox % 2] for n, c, oy, ox in pts])
+        assert_close(yu[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3]], ref, f"up{lvl} fwd samples")
+        cat = H(u["cat"])
+        assert np.array_equal(cat[:, :C], H(e["y"])) and np.array_equal(cat[:, C:], yu)
+        gu = H(u["g"]).astype(np.float64)
+        # dW of the up-convolution: sampled (ci, co) slices summed over all pixels
+        prs = _pts(5000 + lvl, 4, (xin.shape[1], C))
+        dwu = H(net.grads[f"up{lvl}"])
+        ref = np.array([[[np.sum(xin[:, i] * gu[:, o, aa::2, bb::2]) for bb in range(2)] for aa in range(2)]
+                        for i, o in prs])
+        assert_close(np.array([dwu[i, o] for i, o in prs]), ref, f"up{lvl} dW samples")
+        _say(f"  {cfg.name} pool{lvl}/up{lvl} ok")
+    hd = A["head"]
+    logits = H(hd["y"])
+    assert_close(logits, uo.conv1x1_fwd(H(hd["x"]), params["head"]), "head fwd")
+    loss_ref, dl_ref = uo.softmax_ce(logits, labels)
+    assert abs(float(net.loss.cpu()[0]) - loss_ref) <= RTOL * abs(loss_ref)
+    assert_close(H(hd["g"]), dl_ref, "dlogits")
+    _, dwh = uo.conv1x1_bwd(H(hd["x"]), params["head"], H(hd["g"]))
+    assert_close(H(net.grads["head"]), dwh, "head dW")
