@@ -53,7 +53,11 @@ struct P4BwdWGeom {
   int N, Cin, CinPad, H, W, Cout, CoutPad, Q, ng;
   int ncig;    // groups of 64 input channels
   int ncog;    // groups of 64 filters (one workgroup of 4 waves)
-  int splits;  // ranges of image rows, summed afterwards in order
+  int nstrip;    // 32-pixel strips per row
+  int rows_per;  // rows per range
+  int nrange;    // row ranges per image
+  int units;     // (image, range, strip) work units
+  int splits;    // workgroups per (bank, filter group, channel group); their sums are added in order
 };
 bool p4_bwd_weight_supported(const rotconv_plan* p);
 P4BwdWGeom p4_bwd_weight_geom(const rotconv_plan* p);

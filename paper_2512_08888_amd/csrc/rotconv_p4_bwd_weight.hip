@@ -36,10 +36,10 @@ __device__ __host__ constexpr int tap_j(int s, int u) {
   return s == 0 ? u % 3 : s == 1 ? u / 3 : s == 2 ? 2 - u % 3 : 2 - u / 3;
 }
 
-struct RawW {            // (G, idx) of one filter on a 3 x 6 pixel neighbourhood
-  float g[3][6];
-  uint32_t ic[3];        // idx bytes of the 4 centre pixels
-  uint32_t ie[3];        // byte 0: left neighbour, byte 1: right neighbour
+struct RowW {            // (G, idx) of one filter on one image row: the lane's 8 pixels and one neighbour per side
+  float g[10];           // g[0] = left neighbour, g[1..8] = the 8 pixels, g[9] = right neighbour
+  uint32_t ic0, ic1;     // idx bytes of pixels 0..3 and 4..7
+  uint32_t ie;           // byte 0: left neighbour, byte 1: right neighbour
 };
 
 __global__ __launch_bounds__(NT) void k_p4_bwd_weight(const float* __restrict__ x, const float* __restrict__ gpool,
@@ -69,70 +69,42 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_weight(const float* __restrict__ 
   const bool cok = co < g.Cout && r0 >= 0;
   const size_t gplane0 = ((size_t)(cok ? co : 0) * g.ng + (r0 < 0 ? 0 : r0 % g.ng)) * HW;
   const size_t gimg = (size_t)g.Cout * g.ng * HW;
+  const size_t ximg = (size_t)g.Cin * HW;
 
-  // rows of the flattened (n, h) space handled by this split
-  const int rows_total = g.N * g.H;
-  const int rows_per = (rows_total + g.splits - 1) / g.splits;
-  const int row_begin = split * rows_per;
-  const int row_end = min(rows_total, row_begin + rows_per);
-  const int w16 = (g.W + 15) / 16;
-  const int nrows = max(0, row_end - row_begin);
-  const int niter = nrows * w16;
-
-  // Branch-free loads (out-of-range positions read a safe address and are masked; an idx byte of
-  // 0xff matches no orientation), so that a pipeline stage is one basic block.
-  auto load_b = [&](int it, f4 (&b)[NCB]) {
-    it = min(it, niter - 1);
-    const int row = row_begin + it % nrows;   // rows run fastest: (G, idx) rows are re-read from L1
-    const int n = row / g.H, h = row % g.H;
-    const int px = (it / nrows) * 16 + 4 * lg;
-    const bool pok = px < g.W;                // W % 4 == 0: the four pixels are in or out together
-    const size_t off = (size_t)n * g.Cin * HW + (size_t)h * g.W + (pok ? px : 0);
+  // Channel-plane offsets of the lane's NCB channels (clamped; out-of-range channels are masked).
+  uint32_t xplane[NCB];
+  bool xok[NCB];
 #pragma unroll
-    for (int cb = 0; cb < NCB; ++cb) {
-      const int ci = ci0 + cb * 16;
-      const bool ok = pok && ci < g.Cin;
-      const f4 val = *reinterpret_cast<const f4*>(x + off + (size_t)(ci < g.Cin ? ci : 0) * HW);
-      b[cb] = ok ? val : f4{0.f, 0.f, 0.f, 0.f};
-    }
-  };
-  auto load_raw = [&](int it, RawW& r) {
-    it = min(it, niter - 1);
-    const int row = row_begin + it % nrows;
-    const int n = row / g.H, h = row % g.H;
-    const int px = (it / nrows) * 16 + 4 * lg;
-    const bool pok = px < g.W;
-    const int pc = pok ? px : 0, pl = max(px - 1, 0), pr = min(px + 4, g.W - 1);
-    const bool lok = px >= 1 && px - 1 < g.W, rok2 = px + 4 < g.W;
-#pragma unroll
-    for (int dr = 0; dr < 3; ++dr) {
-      const int rr = h - 1 + dr;
-      const bool rok = cok && rr >= 0 && rr < g.H;
-      const size_t rowbase = (size_t)n * gimg + gplane0 + (size_t)(rok ? rr : 0) * g.W;
-      const f4 gc = *reinterpret_cast<const f4*>(gpool + rowbase + pc);
-      const uint32_t ic = *reinterpret_cast<const uint32_t*>(idx + rowbase + pc);
-      const float gl = gpool[rowbase + pl], gr = gpool[rowbase + pr];
-      const uint32_t il = idx[rowbase + pl], ir = idx[rowbase + pr];
-      r.g[dr][1] = gc[0]; r.g[dr][2] = gc[1]; r.g[dr][3] = gc[2]; r.g[dr][4] = gc[3];
-      r.g[dr][0] = gl;
-      r.g[dr][5] = gr;
-      r.ic[dr] = (rok && pok) ? ic : 0xffffffffu;
-      r.ie[dr] = ((rok && lok) ? il : 0xffu) | (((rok && rok2) ? ir : 0xffu) << 8);
-    }
-  };
+  for (int cb = 0; cb < NCB; ++cb) {
+    const int ci = ci0 + cb * 16;
+    xok[cb] = ci < g.Cin;
+    xplane[cb] = (uint32_t)(xok[cb] ? ci : 0) * (uint32_t)HW;
+  }
 
-  // One quarter turn's share of D for the lane's four pixels: Delta_s on the 3x6 neighbourhood,
-  // added where R_s puts each base tap (Eq. 12 with the tap positions of Eq. 8).
-  auto build_slice = [&](const RawW& r, int s, float (&a)[9][4]) {
+  f4 acc[9][NCB];
+#pragma unroll
+  for (int u = 0; u < 9; ++u)
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) acc[u][cb] = f4{0.f, 0.f, 0.f, 0.f};
+
+  // One quarter turn's share of D for four of the lane's pixels (half j of the 8): Delta_s on the
+  // 3 x 6 neighbourhood, added where R_s puts each base tap (Eq. 12 with the tap positions of Eq. 8).
+  auto build_slice = [&](const RowW& ra, const RowW& rb, const RowW& rc, int j, int s, float (&a)[9][4]) {
     const uint32_t rs = (uint32_t)rot[s];     // -1 (absent) matches no byte
     float d[3][6];
+    auto sel_row = [&](const RowW& r, float (&dd)[6]) {
+      const uint32_t icj = j == 0 ? r.ic0 : r.ic1;
+      // window column w <-> row column 4 j + w;  column 0 of the row is the left neighbour, 9 the right one
+      const uint32_t il = j == 0 ? (r.ie & 0xffu) : (r.ic0 >> 24);
+      const uint32_t ir = j == 0 ? (r.ic1 & 0xffu) : ((r.ie >> 8) & 0xffu);
+      dd[0] = il == rs ? r.g[4 * j] : 0.f;
+      dd[5] = ir == rs ? r.g[4 * j + 5] : 0.f;
 #pragma unroll
-    for (int dr = 0; dr < 3; ++dr) {
-      d[dr][0] = ((r.ie[dr] & 0xffu) == rs) ? r.g[dr][0] : 0.f;
-      d[dr][5] = (((r.ie[dr] >> 8) & 0xffu) == rs) ? r.g[dr][5] : 0.f;
-#pragma unroll
-      for (int p = 0; p < 4; ++p) d[dr][1 + p] = (((r.ic[dr] >> (8 * p)) & 0xffu) == rs) ? r.g[dr][1 + p] : 0.f;
-    }
+      for (int p = 0; p < 4; ++p) dd[1 + p] = (((icj >> (8 * p)) & 0xffu) == rs) ? r.g[4 * j + 1 + p] : 0.f;
+    };
+    sel_row(ra, d[0]);
+    sel_row(rb, d[1]);
+    sel_row(rc, d[2]);
 #pragma unroll
     for (int u = 0; u < 9; ++u)
 #pragma unroll
@@ -142,41 +114,85 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_weight(const float* __restrict__ 
       }
   };
 
-  f4 acc[9][NCB];
-#pragma unroll
-  for (int u = 0; u < 9; ++u)
-#pragma unroll
-    for (int cb = 0; cb < NCB; ++cb) acc[u][cb] = f4{0.f, 0.f, 0.f, 0.f};
+  // Work units: (image, row range, 32-pixel strip).  A lane owns pixels px0 .. px0+7 of the strip; it walks
+  // down the rows of the range keeping the (G, idx) rows h-1, h, h+1 in registers (each row of the range is
+  // loaded once), X comes straight from global memory into the B operand, a full 128-byte line per channel
+  // and row.
+  for (int unit = split; unit < g.units; unit += g.splits) {
+    int uu = unit;
+    const int strip = uu % g.nstrip; uu /= g.nstrip;
+    const int rng = uu % g.nrange;
+    const int n = uu / g.nrange;
+    const int h0 = rng * g.rows_per, h1 = min(g.H, h0 + g.rows_per);
+    const int px0 = strip * 32 + 8 * lg;
+    const bool pok0 = px0 < g.W, pok1 = px0 + 4 < g.W;       // W % 4 == 0: groups of four are in or out together
+    const bool lok = pok0 && px0 >= 1, rok2 = px0 + 8 < g.W;
+    const int pc0 = pok0 ? px0 : 0, pc1 = pok1 ? px0 + 4 : 0, pl = lok ? px0 - 1 : 0, pr = rok2 ? px0 + 8 : 0;
+    const float* gb = gpool + (size_t)n * gimg + gplane0;
+    const uint8_t* ib = idx + (size_t)n * gimg + gplane0;
+    const float* xb = x + (size_t)n * ximg;
 
-  if (niter > 0) {
-    // Three-stage software pipeline, unrolled twice so that no buffer is copied: loads of (G, idx)
-    // for step it+2 and of X for step it+1; D build for step it+1, one quarter turn after each of
-    // the four K-steps of step it, so that the VALU work sits between the MFMAs.
-    RawW rawA, rawB;
-    f4 bA[NCB], bB[NCB];
-    float aA[9][4], aB[9][4];
-    auto stage = [&](int it, const RawW& raw_use, RawW& raw_ld, const float (&a_cur)[9][4], float (&a_nxt)[9][4],
-                     const f4 (&b_cur)[NCB], f4 (&b_nxt)[NCB]) {
-      load_raw(it + 2, raw_ld);
-      load_b(it + 1, b_nxt);
+    // Branch-free loads: out-of-range positions read a safe address and get the idx byte 0xff, which
+    // matches no orientation.
+    auto load_row = [&](int h, RowW& r) {
+      const bool rok = cok && h >= 0 && h < g.H;
+      const uint32_t ro = (uint32_t)(rok ? h : 0) * (uint32_t)g.W;
+      const f4 g0 = *reinterpret_cast<const f4*>(gb + ro + pc0);
+      const f4 g1 = *reinterpret_cast<const f4*>(gb + ro + pc1);
+      const uint32_t i0 = *reinterpret_cast<const uint32_t*>(ib + ro + pc0);
+      const uint32_t i1 = *reinterpret_cast<const uint32_t*>(ib + ro + pc1);
+      r.g[0] = gb[ro + pl];
+      r.g[9] = gb[ro + pr];
+      const uint32_t il = ib[ro + pl], ir = ib[ro + pr];
+      r.g[1] = g0[0]; r.g[2] = g0[1]; r.g[3] = g0[2]; r.g[4] = g0[3];
+      r.g[5] = g1[0]; r.g[6] = g1[1]; r.g[7] = g1[2]; r.g[8] = g1[3];
+      r.ic0 = (rok && pok0) ? i0 : 0xffffffffu;
+      r.ic1 = (rok && pok1) ? i1 : 0xffffffffu;
+      r.ie = ((rok && lok) ? il : 0xffu) | (((rok && rok2) ? ir : 0xffu) << 8);
+    };
+    auto load_x = [&](int h, int j, f4 (&b)[NCB]) {
+      const uint32_t off = (uint32_t)min(h, g.H - 1) * (uint32_t)g.W + (uint32_t)(j == 0 ? pc0 : pc1);
+      const bool pok = j == 0 ? pok0 : pok1;
 #pragma unroll
-      for (int t = 0; t < 4; ++t) {
-#pragma unroll
-        for (int u = 0; u < 9; ++u)
-#pragma unroll
-          for (int cb = 0; cb < NCB; ++cb)
-            acc[u][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur[u][t], b_cur[cb][t], acc[u][cb], 0, 0, 0);
-        build_slice(raw_use, t, a_nxt);
+      for (int cb = 0; cb < NCB; ++cb) {
+        const f4 val = *reinterpret_cast<const f4*>(xb + xplane[cb] + off);
+        b[cb] = (pok && xok[cb]) ? val : f4{0.f, 0.f, 0.f, 0.f};
       }
     };
-    load_raw(0, rawB);
-    load_b(0, bA);
+    auto mfma_half = [&](const float (&a)[9][4], const f4 (&b)[NCB], int t) {
 #pragma unroll
-    for (int s = 0; s < 4; ++s) build_slice(rawB, s, aA);
-    load_raw(1, rawA);
-    for (int it = 0; it < niter; it += 2) {
-      stage(it, rawA, rawB, aA, aB, bA, bB);
-      if (it + 1 < niter) stage(it + 1, rawB, rawA, aB, aA, bB, bA);
+      for (int u = 0; u < 9; ++u)
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb)
+          acc[u][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u][t], b[cb][t], acc[u][cb], 0, 0, 0);
+    };
+
+    RowW ra, rb, rc, rn;                 // rows h-1, h, h+1 and the one being loaded
+    f4 bA[NCB], bB[NCB];
+    float aA[9][4], aB[9][4];
+    load_row(h0 - 1, ra);
+    load_row(h0, rb);
+    load_row(h0 + 1, rc);
+    load_x(h0, 0, bA);
+#pragma unroll
+    for (int s = 0; s < 4; ++s) build_slice(ra, rb, rc, 0, s, aA);
+    for (int h = h0; h < h1; ++h) {
+      // first half of the row: D of the second half is built between its K-steps
+      load_row(h + 2, rn);
+      load_x(h, 1, bB);
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        mfma_half(aA, bA, t);
+        build_slice(ra, rb, rc, 1, t, aB);
+      }
+      ra = rb; rb = rc; rc = rn;
+      // second half: D of the next row's first half
+      load_x(h + 1, 0, bA);
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        mfma_half(aB, bB, t);
+        build_slice(ra, rb, rc, 0, t, aA);
+      }
     }
   }
 
@@ -251,16 +267,17 @@ P4BwdWGeom p4_bwd_weight_geom(const rotconv_plan* p) {
   g.CoutPad = (d.Cout + 16 * NWAVE - 1) / (16 * NWAVE) * (16 * NWAVE);
   g.ncig = g.CinPad / (16 * NCB);
   g.ncog = g.CoutPad / (16 * NWAVE);
+  // work units: (image, row range, 32-pixel strip); a range never crosses an image
   const int combos = g.Q * g.ncig * g.ncog;
-  const int rows = d.N * d.H;
-  int splits = (256 + combos - 1) / combos;
-  splits = std::min(splits, rows);
-  // keep the partial sums below 256 MiB
+  g.nstrip = (d.W + 31) / 32;
+  const int want = (256 + combos - 1) / combos;                       // units wanted to fill the chip
+  int per_image = std::max(1, std::min(d.H, (want + d.N * g.nstrip - 1) / (d.N * g.nstrip)));
+  g.rows_per = (d.H + per_image - 1) / per_image;
+  g.nrange = (d.H + g.rows_per - 1) / g.rows_per;
+  g.units = d.N * g.nrange * g.nstrip;
+  // one partial-sum image per split; keep them below 256 MiB (a workgroup then takes several units)
   const double per = 4.0 * g.Q * 9.0 * g.CoutPad * g.CinPad;
-  splits = std::max(1, std::min(splits, (int)(268435456.0 / per)));
-  // equal row counts per split where possible
-  const int rows_per = (rows + splits - 1) / splits;
-  g.splits = (rows + rows_per - 1) / rows_per;
+  g.splits = std::max(1, std::min(std::min(g.units, want), (int)(268435456.0 / per)));
   return g;
 }
 
