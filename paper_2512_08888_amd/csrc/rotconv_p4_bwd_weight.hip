@@ -36,21 +36,26 @@ __device__ __host__ constexpr int tap_j(int s, int u) {
   return s == 0 ? u % 3 : s == 1 ? u / 3 : s == 2 ? 2 - u % 3 : 2 - u / 3;
 }
 
-struct RowW {            // (G, idx) of one filter on one image row: the lane's 8 pixels and one neighbour per side
-  float g[10];           // g[0] = left neighbour, g[1..8] = the 8 pixels, g[9] = right neighbour
-  uint32_t ic0, ic1;     // idx bytes of pixels 0..3 and 4..7
-  uint32_t ie;           // byte 0: left neighbour, byte 1: right neighbour
+struct RowW {            // (G, idx) of one filter on one image row as loaded: the lane's 8 pixels and one neighbour per side
+  f4 g0, g1;             // pixels 0..3 and 4..7
+  float gl, gr;          // left and right neighbour
+  uint32_t i0, i1;       // idx bytes of pixels 0..3 and 4..7
+  uint32_t il, ir;       // idx of the neighbours
 };
 
 __global__ __launch_bounds__(NT) void k_p4_bwd_weight(const float* __restrict__ x, const float* __restrict__ gpool,
                                                       const uint8_t* __restrict__ idx,
                                                       const int32_t* __restrict__ rot_of,
                                                       float* __restrict__ partial, P4BwdWGeom g) {
-  int v = blockIdx.x;
-  const int split = v % g.splits; v /= g.splits;
+  // Consecutive indices go to one XCD: the (bank, filter group, channel group) combinations of one work
+  // unit share its X and (G, idx) lines in that XCD's L2, and so do the strips of one row range, whose halo
+  // columns lie in their neighbours' lines.
+  const int per_xcd = gridDim.x / 8;
+  int v = gridDim.x % 8 == 0 ? (blockIdx.x % 8) * per_xcd + blockIdx.x / 8 : blockIdx.x;
   const int cig = v % g.ncig; v /= g.ncig;
-  const int cog = v % g.ncog;
-  const int q = v / g.ncog;
+  const int cog = v % g.ncog; v /= g.ncog;
+  const int q = v % g.Q;
+  const int split = v / g.Q;
 
   const int tid = threadIdx.x;
   const int wave = tid / 64, lane = tid % 64;
@@ -73,12 +78,10 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_weight(const float* __restrict__ 
 
   // Channel-plane offsets of the lane's NCB channels (clamped; out-of-range channels are masked).
   uint32_t xplane[NCB];
-  bool xok[NCB];
 #pragma unroll
   for (int cb = 0; cb < NCB; ++cb) {
     const int ci = ci0 + cb * 16;
-    xok[cb] = ci < g.Cin;
-    xplane[cb] = (uint32_t)(xok[cb] ? ci : 0) * (uint32_t)HW;
+    xplane[cb] = (uint32_t)(ci < g.Cin ? ci : 0) * (uint32_t)HW;
   }
 
   f4 acc[9][NCB];
@@ -87,31 +90,38 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_weight(const float* __restrict__ 
 #pragma unroll
     for (int cb = 0; cb < NCB; ++cb) acc[u][cb] = f4{0.f, 0.f, 0.f, 0.f};
 
-  // One quarter turn's share of D for four of the lane's pixels (half j of the 8): Delta_s on the
-  // 3 x 6 neighbourhood, added where R_s puts each base tap (Eq. 12 with the tap positions of Eq. 8).
-  auto build_slice = [&](const RowW& ra, const RowW& rb, const RowW& rc, int j, int s, float (&a)[9][4]) {
-    const uint32_t rs = (uint32_t)rot[s];     // -1 (absent) matches no byte
-    float d[3][6];
-    auto sel_row = [&](const RowW& r, float (&dd)[6]) {
-      const uint32_t icj = j == 0 ? r.ic0 : r.ic1;
-      // window column w <-> row column 4 j + w;  column 0 of the row is the left neighbour, 9 the right one
-      const uint32_t il = j == 0 ? (r.ie & 0xffu) : (r.ic0 >> 24);
-      const uint32_t ir = j == 0 ? (r.ic1 & 0xffu) : ((r.ie >> 8) & 0xffu);
-      dd[0] = il == rs ? r.g[4 * j] : 0.f;
-      dd[5] = ir == rs ? r.g[4 * j + 5] : 0.f;
+  // Routed gradients of one row, per quarter turn: m[s][c] = G where idx == orientation (q, s), else 0
+  // (Eq. 12).  Column 0 is the left neighbour, 1..8 the lane's pixels, 9 the right neighbour.  Computed
+  // once per row and kept in registers while the row serves as h-1, h and h+1.
+  auto select_row = [&](const RowW& r, bool rok, bool pok0, bool pok1, bool lok, bool rok2, float (&m)[4][10]) {
+    // positions outside the image (or filters beyond Cout) get the idx byte 0xff, which matches no orientation
+    const uint32_t ic0 = (rok && pok0) ? r.i0 : 0xffffffffu, ic1 = (rok && pok1) ? r.i1 : 0xffffffffu;
+    const uint32_t il = (rok && lok) ? r.il : 0xffu, ir = (rok && rok2) ? r.ir : 0xffu;
+    const float gc[8] = {r.g0[0], r.g0[1], r.g0[2], r.g0[3], r.g1[0], r.g1[1], r.g1[2], r.g1[3]};
 #pragma unroll
-      for (int p = 0; p < 4; ++p) dd[1 + p] = (((icj >> (8 * p)) & 0xffu) == rs) ? r.g[4 * j + 1 + p] : 0.f;
-    };
-    sel_row(ra, d[0]);
-    sel_row(rb, d[1]);
-    sel_row(rc, d[2]);
+    for (int s = 0; s < 4; ++s) {
+      const uint32_t rs = (uint32_t)rot[s];   // -1 (absent) matches no byte
+      m[s][0] = il == rs ? r.gl : 0.f;
+      m[s][9] = ir == rs ? r.gr : 0.f;
 #pragma unroll
-    for (int u = 0; u < 9; ++u)
-#pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        const float term = d[2 - tap_i(s, u)][t + 2 - tap_j(s, u)];
-        a[u][t] = s == 0 ? term : a[u][t] + term;
+      for (int p = 0; p < 4; ++p) {
+        m[s][1 + p] = ((ic0 >> (8 * p)) & 0xffu) == rs ? gc[p] : 0.f;
+        m[s][5 + p] = ((ic1 >> (8 * p)) & 0xffu) == rs ? gc[4 + p] : 0.f;
       }
+    }
+  };
+  // D of pixel t of half j (column 4 j + t + 1 of the rows), all nine taps: each quarter turn's routed
+  // gradient is taken where R_s puts the base tap (the tap positions of Eq. 8).  Adds only.
+  auto build_pixel = [&](const float (&ma)[4][10], const float (&mb)[4][10], const float (&mc)[4][10], int j, int t,
+                         float (&a)[9][4]) {
+    auto at = [&](int row, int s, int col) -> float { return row == 0 ? ma[s][col] : row == 1 ? mb[s][col] : mc[s][col]; };
+#pragma unroll
+    for (int u = 0; u < 9; ++u) {
+      float v = at(2 - tap_i(0, u), 0, 4 * j + t + 2 - tap_j(0, u));
+#pragma unroll
+      for (int s = 1; s < 4; ++s) v += at(2 - tap_i(s, u), s, 4 * j + t + 2 - tap_j(s, u));
+      a[u][t] = v;
+    }
   };
 
   // Work units: (image, row range, 32-pixel strip).  A lane owns pixels px0 .. px0+7 of the strip; it walks
@@ -132,32 +142,27 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_weight(const float* __restrict__ 
     const uint8_t* ib = idx + (size_t)n * gimg + gplane0;
     const float* xb = x + (size_t)n * ximg;
 
-    // Branch-free loads: out-of-range positions read a safe address and get the idx byte 0xff, which
-    // matches no orientation.
+    // Branch-free loads: out-of-range positions read a safe (clamped) address; what they return is
+    // discarded when the row is routed (select_row).  X needs no mask: where a pixel is out of range D is
+    // zero, and the clamped address stays inside the same channel plane; channels beyond Cin land in padded
+    // columns of the partial sums that nobody reads.
+    auto row_ok = [&](int h) { return cok && h >= 0 && h < g.H; };
     auto load_row = [&](int h, RowW& r) {
-      const bool rok = cok && h >= 0 && h < g.H;
-      const uint32_t ro = (uint32_t)(rok ? h : 0) * (uint32_t)g.W;
-      const f4 g0 = *reinterpret_cast<const f4*>(gb + ro + pc0);
-      const f4 g1 = *reinterpret_cast<const f4*>(gb + ro + pc1);
-      const uint32_t i0 = *reinterpret_cast<const uint32_t*>(ib + ro + pc0);
-      const uint32_t i1 = *reinterpret_cast<const uint32_t*>(ib + ro + pc1);
-      r.g[0] = gb[ro + pl];
-      r.g[9] = gb[ro + pr];
-      const uint32_t il = ib[ro + pl], ir = ib[ro + pr];
-      r.g[1] = g0[0]; r.g[2] = g0[1]; r.g[3] = g0[2]; r.g[4] = g0[3];
-      r.g[5] = g1[0]; r.g[6] = g1[1]; r.g[7] = g1[2]; r.g[8] = g1[3];
-      r.ic0 = (rok && pok0) ? i0 : 0xffffffffu;
-      r.ic1 = (rok && pok1) ? i1 : 0xffffffffu;
-      r.ie = ((rok && lok) ? il : 0xffu) | (((rok && rok2) ? ir : 0xffu) << 8);
+      const uint32_t ro = (uint32_t)min(max(h, 0), g.H - 1) * (uint32_t)g.W;
+      r.g0 = *reinterpret_cast<const f4*>(gb + ro + pc0);
+      r.g1 = *reinterpret_cast<const f4*>(gb + ro + pc1);
+      r.i0 = *reinterpret_cast<const uint32_t*>(ib + ro + pc0);
+      r.i1 = *reinterpret_cast<const uint32_t*>(ib + ro + pc1);
+      r.gl = gb[ro + pl];
+      r.gr = gb[ro + pr];
+      r.il = ib[ro + pl];
+      r.ir = ib[ro + pr];
     };
+    auto route = [&](const RowW& r, int h, float (&m)[4][10]) { select_row(r, row_ok(h), pok0, pok1, lok, rok2, m); };
     auto load_x = [&](int h, int j, f4 (&b)[NCB]) {
       const uint32_t off = (uint32_t)min(h, g.H - 1) * (uint32_t)g.W + (uint32_t)(j == 0 ? pc0 : pc1);
-      const bool pok = j == 0 ? pok0 : pok1;
 #pragma unroll
-      for (int cb = 0; cb < NCB; ++cb) {
-        const f4 val = *reinterpret_cast<const f4*>(xb + xplane[cb] + off);
-        b[cb] = (pok && xok[cb]) ? val : f4{0.f, 0.f, 0.f, 0.f};
-      }
+      for (int cb = 0; cb < NCB; ++cb) b[cb] = *reinterpret_cast<const f4*>(xb + xplane[cb] + off);
     };
     auto mfma_half = [&](const float (&a)[9][4], const f4 (&b)[NCB], int t) {
 #pragma unroll
@@ -167,32 +172,50 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_weight(const float* __restrict__ 
           acc[u][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u][t], b[cb][t], acc[u][cb], 0, 0, 0);
     };
 
-    RowW ra, rb, rc, rn;                 // rows h-1, h, h+1 and the one being loaded
+    RowW rn;                             // the row being loaded (h + 2)
+    float m0[4][10], m1[4][10], m2[4][10];   // routed rows h-1, h, h+1; the roles rotate from row to row
     f4 bA[NCB], bB[NCB];
     float aA[9][4], aB[9][4];
-    load_row(h0 - 1, ra);
-    load_row(h0, rb);
-    load_row(h0 + 1, rc);
-    load_x(h0, 0, bA);
-#pragma unroll
-    for (int s = 0; s < 4; ++s) build_slice(ra, rb, rc, 0, s, aA);
-    for (int h = h0; h < h1; ++h) {
-      // first half of the row: D of the second half is built between its K-steps
+    // One image row: (ma, mb, mc) = rows (h-1, h, h+1).  The D values of the half that comes next are built
+    // pixel by pixel between the K-steps of the current half; between the halves the freshly loaded row h+2
+    // replaces row h-1.
+    auto step = [&](int h, float (&ma)[4][10], float (&mb)[4][10], float (&mc)[4][10]) {
+      // The scheduling fences keep the loads where they are issued: half a row (144 MFMAs) ahead of
+      // their first use.  Left alone, the compiler sinks each load to its use and waits for it there.
       load_row(h + 2, rn);
       load_x(h, 1, bB);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
         mfma_half(aA, bA, t);
-        build_slice(ra, rb, rc, 1, t, aB);
+        build_pixel(ma, mb, mc, 1, t, aB);
       }
-      ra = rb; rb = rc; rc = rn;
-      // second half: D of the next row's first half
+      __builtin_amdgcn_sched_barrier(0);
       load_x(h + 1, 0, bA);
+      route(rn, h + 2, ma);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
         mfma_half(aB, bB, t);
-        build_slice(ra, rb, rc, 0, t, aA);
+        build_pixel(mb, mc, ma, 0, t, aA);
       }
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    load_row(h0 - 1, rn);
+    route(rn, h0 - 1, m0);
+    load_row(h0, rn);
+    route(rn, h0, m1);
+    load_row(h0 + 1, rn);
+    route(rn, h0 + 1, m2);
+    load_x(h0, 0, bA);
+#pragma unroll
+    for (int t = 0; t < 4; ++t) build_pixel(m0, m1, m2, 0, t, aA);
+    for (int h = h0; h < h1; h += 3) {
+      step(h, m0, m1, m2);
+      if (h + 1 >= h1) break;
+      step(h + 1, m1, m2, m0);
+      if (h + 2 >= h1) break;
+      step(h + 2, m2, m0, m1);
     }
   }
 
