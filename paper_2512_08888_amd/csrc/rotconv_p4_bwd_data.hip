@@ -41,9 +41,11 @@ __device__ __host__ constexpr int tap_j(int s, int u) {
   return s == 0 ? u % 3 : s == 1 ? u / 3 : s == 2 ? 2 - u % 3 : 2 - u / 3;
 }
 
-struct Raw {           // (G, idx) of one filter on a 3 x 4 pixel neighbourhood
-  float g[3][4];
-  uint32_t i[3];       // four idx bytes per row, byte p = pixel p of the neighbourhood
+struct Raw {           // (G, idx) of one filter on a 3 x 4 pixel neighbourhood, as loaded
+  float gl[3], gr[3];  // left / right neighbour of the lane's two pixels
+  float2 gc[3];        // the two pixels
+  uint32_t il[3], ic[3], ir[3];   // idx of the same positions (ic: two bytes)
+  uint32_t finv;       // all ones if the lane's filter of this K-step is beyond Cout
 };
 
 __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gpool, const uint8_t* __restrict__ idx,
@@ -99,10 +101,11 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gp
 
   // ---- (G, idx) neighbourhood loads -------------------------------------------------------------
   // Everything that depends on the lane only (row / pixel offsets inside a channel plane, validity)
-  // is computed once; per K-step the address is a wave-uniform plane base plus those 32-bit lane
-  // offsets.  Out-of-range positions read a clamped (valid) address and get the idx byte 0xff,
-  // which matches no orientation (R <= 255), so they contribute nothing.  Filters beyond Cout read
-  // filter Cout-1: their packed weights are zero.
+  // is computed once; per K-step the address is a wave-uniform base plus 32-bit lane offsets.
+  // Out-of-range positions read a clamped (valid) address and get the idx byte 0xff, which matches no
+  // orientation (R <= 255), so they contribute nothing; so do lanes whose filter is beyond Cout (they
+  // read filter 0).  Nothing is computed from a loaded value before the K-step that uses it, so the
+  // loads stay in flight for two K-steps.
   const int xa = x0 + 2 * lc;                  // first of this lane's two pixels
   uint32_t offc[3], offl[3], offr[3], inval[3];
 #pragma unroll
@@ -116,32 +119,49 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gp
     offr[dr] = rowoff + (uint32_t)(okr ? xa + 2 : 0);
     inval[dr] = (okl ? 0u : 0xffu) | (okc ? 0u : 0xffff00u) | (okr ? 0u : 0xff000000u);
   }
-  const uint32_t lane_plane = (uint32_t)lg * (uint32_t)g.ng * (uint32_t)HW;   // filter lg of the K-step
-  auto raw_load = [&](int kk, Raw& r) {
-    kk = min(kk, nk - 1);
-    const int q = kk / nkq;
-    const int co4 = (kk % nkq) * 4;            // first filter of the K-step (wave-uniform)
+  const uint32_t plane = (uint32_t)g.ng * (uint32_t)HW;          // floats between consecutive filters
+  const float* gimg = gpool + (size_t)n * g.Cout * plane;
+  const uint8_t* iimg = idx + (size_t)n * g.Cout * plane;
+  auto bank_rot = [&](int q, int (&rot)[4]) {                     // orientation index of each quarter turn (-1: absent)
+#pragma unroll
+    for (int s = 0; s < 4; ++s) rot[s] = rot_of[q * 4 + s];
+  };
+  auto group_of = [&](const int (&rot)[4]) {                      // pool group the bank's orientations live in
     int r0 = 0;
 #pragma unroll
-    for (int s = 3; s >= 0; --s) {
-      const int rs = rot_of[q * 4 + s];
-      r0 = rs >= 0 ? rs : r0;
-    }
-    // wave-uniform base of filter co4's plane in this bank's pool group
-    const size_t ubase = ((size_t)n * g.Cout * g.ng + (size_t)co4 * g.ng + (size_t)(r0 % g.ng)) * HW;
-    // lanes whose filter would be beyond Cout fall back to the K-step's first filter
-    const uint32_t lp = (co4 + lg < g.Cout) ? lane_plane : 0u;
-    const float* gb = gpool + ubase;
-    const uint8_t* ib = idx + ubase;
+    for (int s = 3; s >= 0; --s) r0 = rot[s] >= 0 ? rot[s] : r0;
+    return r0 % g.ng;
+  };
+  // load cursor: K-step (bank, first filter) that the next raw_load fetches; it stops on the last K-step
+  int ld_q = 0, ld_co = 0, ld_pg;
+  {
+    int r[4];
+    bank_rot(0, r);
+    ld_pg = group_of(r);
+  }
+  auto raw_load = [&](Raw& r) {
+    const bool fok = ld_co + lg < g.Cout;
+    const uint32_t fl = (uint32_t)(fok ? ld_co + lg : 0) * plane;   // lane's filter plane
+    const float* gb = gimg + (size_t)ld_pg * HW;
+    const uint8_t* ib = iimg + (size_t)ld_pg * HW;
+    r.finv = fok ? 0u : 0xffffffffu;
 #pragma unroll
     for (int dr = 0; dr < 3; ++dr) {
-      const float2 gc = *reinterpret_cast<const float2*>(gb + (lp + offc[dr]));
-      const uint32_t ic = *reinterpret_cast<const uint16_t*>(ib + (lp + offc[dr]));
-      r.g[dr][0] = gb[lp + offl[dr]];
-      r.g[dr][1] = gc.x;
-      r.g[dr][2] = gc.y;
-      r.g[dr][3] = gb[lp + offr[dr]];
-      r.i[dr] = ((uint32_t)ib[lp + offl[dr]] | (ic << 8) | ((uint32_t)ib[lp + offr[dr]] << 24)) | inval[dr];
+      r.gc[dr] = *reinterpret_cast<const float2*>(gb + (fl + offc[dr]));
+      r.ic[dr] = *reinterpret_cast<const uint16_t*>(ib + (fl + offc[dr]));
+      r.gl[dr] = gb[fl + offl[dr]];
+      r.gr[dr] = gb[fl + offr[dr]];
+      r.il[dr] = ib[fl + offl[dr]];
+      r.ir[dr] = ib[fl + offr[dr]];
+    }
+    if (ld_co + 4 < g.CoutPad) {
+      ld_co += 4;
+    } else if (ld_q + 1 < g.Q) {
+      ++ld_q;
+      ld_co = 0;
+      int rr[4];
+      bank_rot(ld_q, rr);
+      ld_pg = group_of(rr);
     }
   };
 
@@ -150,10 +170,12 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gp
   auto build_slice = [&](const Raw& r, int s, int rs, float (&a)[9][2]) {
     float d[3][4];
 #pragma unroll
-    for (int dr = 0; dr < 3; ++dr)
+    for (int dr = 0; dr < 3; ++dr) {
+      const uint32_t iw = (r.il[dr] | (r.ic[dr] << 8) | (r.ir[dr] << 24)) | inval[dr] | r.finv;
+      const float gv[4] = {r.gl[dr], r.gc[dr].x, r.gc[dr].y, r.gr[dr]};
 #pragma unroll
-      for (int p = 0; p < 4; ++p)
-        d[dr][p] = (((r.i[dr] >> (8 * p)) & 0xffu) == (uint32_t)rs) ? r.g[dr][p] : 0.f;
+      for (int p = 0; p < 4; ++p) d[dr][p] = (((iw >> (8 * p)) & 0xffu) == (uint32_t)rs) ? gv[p] : 0.f;
+    }
 #pragma unroll
     for (int u = 0; u < 9; ++u) {
       const float t0 = d[2 - tap_i(s, u)][2 - tap_j(s, u)], t1 = d[2 - tap_i(s, u)][3 - tap_j(s, u)];
@@ -167,49 +189,59 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gp
   for (int cb = 0; cb < NCB; ++cb) { acc[cb][0] = f4{0.f, 0.f, 0.f, 0.f}; acc[cb][1] = f4{0.f, 0.f, 0.f, 0.f}; }
 
   // Three-stage pipeline over K-steps: (G, idx) loads two steps ahead, A build one step ahead and
-  // spread between the MFMAs of the current step, B reads from LDS one tap ahead.
+  // spread between the MFMAs of the current step, B reads from LDS one tap ahead.  Scheduling fences
+  // keep the loads at the head of the stage; left alone, the compiler sinks them next to their use.
   Raw rawA, rawB;
   float aA[9][2], aB[9][2];
-  int rotq[4];
-  auto stage = [&](int kk, int ks, const float* wl, const Raw& raw_use, Raw& raw_ld, const float (&a_cur)[9][2],
+  int rotb[4];                      // orientations of the bank of the K-step being built
+  int bd_q = 0, bd_co = 0;          // build cursor
+  bank_rot(0, rotb);
+  auto stage = [&](int ks, const float* wl, const Raw& raw_use, Raw& raw_ld, const float (&a_cur)[9][2],
                    float (&a_nxt)[9][2]) {
-    raw_load(kk + 2, raw_ld);
-    const int qn = min(kk + 1, nk - 1) / nkq;      // bank of the step being built
-    float bw[2][NCB];
-#pragma unroll
-    for (int cb = 0; cb < NCB; ++cb) bw[0][cb] = wl[(ks * 4) * WROW + cb * 16];
+    raw_load(raw_ld);
+    // the K-step being built is the one after the current one
+    if (bd_co + 4 < g.CoutPad) {
+      bd_co += 4;
+    } else if (bd_q + 1 < g.Q) {
+      ++bd_q;
+      bd_co = 0;
+      bank_rot(bd_q, rotb);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // B operand: one 16-byte LDS read per tap (the lane's channel in the four 16-channel blocks), issued
+    // one tap ahead; the fences keep it there.
+    f4 bw[2];
+    bw[0] = *reinterpret_cast<const f4*>(wl + (ks * 4) * WROW);
 #pragma unroll
     for (int u = 0; u < 9; ++u) {
-      if (u < 8) {
-#pragma unroll
-        for (int cb = 0; cb < NCB; ++cb) bw[(u + 1) & 1][cb] = wl[(ks * 4) * WROW + (u + 1) * CIG + cb * 16];
-      }
+      if (u < 8) bw[(u + 1) & 1] = *reinterpret_cast<const f4*>(wl + (ks * 4) * WROW + (u + 1) * CIG);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int cb = 0; cb < NCB; ++cb) {
         acc[cb][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur[u][0], bw[u & 1][cb], acc[cb][0], 0, 0, 0);
         acc[cb][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur[u][1], bw[u & 1][cb], acc[cb][1], 0, 0, 0);
       }
-      if ((u & 1) == 0 && u < 8) build_slice(raw_use, u / 2, rot_of[qn * 4 + u / 2], a_nxt);
+      if ((u & 1) == 0 && u < 8) build_slice(raw_use, u / 2, rotb[u / 2], a_nxt);
+      __builtin_amdgcn_sched_barrier(0);
     }
   };
 
-  raw_load(0, rawB);
+  raw_load(rawB);
 #pragma unroll
-  for (int s = 0; s < 4; ++s) rotq[s] = rot_of[s];
-#pragma unroll
-  for (int s = 0; s < 4; ++s) build_slice(rawB, s, rotq[s], aA);
-  raw_load(1, rawA);
+  for (int s = 0; s < 4; ++s) build_slice(rawB, s, rotb[s], aA);
+  raw_load(rawA);
   wload(0);
   wstore(0);
   __syncthreads();
 
   for (int cc = 0; cc < nchunks; ++cc) {
     if (cc + 1 < nchunks) wload(cc + 1);
-    const float* wl = smem + (cc & 1) * CHUNK * WROW + lg * WROW + lc;
-    stage(cc * 4 + 0, 0, wl, rawA, rawB, aA, aB);
-    stage(cc * 4 + 1, 1, wl, rawB, rawA, aB, aA);
-    stage(cc * 4 + 2, 2, wl, rawA, rawB, aA, aB);
-    stage(cc * 4 + 3, 3, wl, rawB, rawA, aB, aA);
+    __builtin_amdgcn_sched_barrier(0);
+    const float* wl = smem + (cc & 1) * CHUNK * WROW + lg * WROW + lc * 4;
+    stage(0, wl, rawA, rawB, aA, aB);
+    stage(1, wl, rawB, rawA, aB, aA);
+    stage(2, wl, rawA, rawB, aA, aB);
+    stage(3, wl, rawB, rawA, aB, aA);
     if (cc + 1 < nchunks) wstore((cc + 1) & 1);
     __syncthreads();
   }
@@ -246,7 +278,10 @@ __global__ __launch_bounds__(256) void k_p4_pack_bwd(const float* __restrict__ w
   const int total = Q * CoutPad * 9 * CinPad;
   const int e = blockIdx.x * 256 + threadIdx.x;
   if (e >= total) return;
-  const int ci = e % CinPad;
+  // Inside each group of 64 channels position p holds channel (p % 4) * 16 + p / 4, so that the four
+  // 16-channel blocks of a lane's channel sit side by side (one 16-byte LDS read per tap in the kernel).
+  const int pos = e % CinPad;
+  const int ci = (pos / CIG) * CIG + (pos % 4) * 16 + (pos % CIG) / 4;
   const int u = (e / CinPad) % 9;
   const int co = (e / (9 * CinPad)) % CoutPad;
   const int q = e / (9 * CinPad * CoutPad);
