@@ -104,7 +104,9 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restri
   }
   __syncthreads();
 
-  const int wave = tid / 64, lane = tid % 64;
+  // the wave index as a scalar: everything derived from it (band, rows, validity) is wave-uniform and the
+  // compiler can branch on it without masking lanes
+  const int wave = __builtin_amdgcn_readfirstlane(tid / 64), lane = tid % 64;
   const int wx = wave % NWX, wy = wave / NWX;
   const int lg = lane / 16, lc = lane % 16;
   const int x0 = g.seg_xorg[seg] + wx * 32;
@@ -150,6 +152,7 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restri
     const float* rp = row_ptr(0);
 #pragma unroll
     for (int ks = 0; ks < KC; ++ks) a_cur[ks] = load_a(rp, ks);
+    __builtin_amdgcn_s_waitcnt(0x0F70);
   }
   const float* wl_lane = Wl + lg * 144 + lc;
   int seq = 0;                           // chunk steps done (streaming: LDS buffer parity)
@@ -163,12 +166,15 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restri
 #pragma unroll
     for (int u = 0; u < 9; ++u) { P[u][0] = f4{0.f, 0.f, 0.f, 0.f}; P[u][1] = f4{0.f, 0.f, 0.f, 0.f}; }
 
-    for (int c = 0; c < nchunk; ++c) {
+    // One 32-channel chunk: MFMAs of its eight K-steps, each slot of A refilled for the next chunk right
+    // after its MFMAs, B read from LDS one K-step ahead.  The scheduling fences keep loads and LDS reads
+    // where they are issued; left alone the compiler sinks them next to their first use and waits there.
+    auto chunk = [&](int c, bool mul) {
       const bool last = c + 1 == nchunk;
       const float* rp = last ? rp_nxt : rp_cur;
       const int kn = last ? 0 : (c + 1) * KC;
       if (STREAM) wload(last ? 0 : c + 1);
-      if (row_ok) {
+      if (mul) {
         const float* wc = STREAM ? wl_lane + (seq & 1) * CHF : wl_lane + (size_t)c * CHF;
         float bw[2][9];
 #pragma unroll
@@ -179,12 +185,14 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restri
 #pragma unroll
             for (int u = 0; u < 9; ++u) bw[(ks + 1) & 1][u] = wc[(ks + 1) * 4 * 144 + u * 16];
           }
+          __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
           for (int u = 0; u < 9; ++u) {
             P[u][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur[ks].x, bw[ks & 1][u], P[u][0], 0, 0, 0);
             P[u][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur[ks].y, bw[ks & 1][u], P[u][1], 0, 0, 0);
           }
           a_cur[ks] = load_a(rp, kn + ks);
+          __builtin_amdgcn_sched_barrier(0);
         }
       } else {
 #pragma unroll
@@ -195,6 +203,14 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restri
         __syncthreads();
       }
       ++seq;
+    };
+    if (row_ok) {
+      for (int c = 0; c < nchunk; ++c) chunk(c, true);
+    } else {
+      for (int c = 0; c < nchunk; ++c) chunk(c, false);
+      // rare path (rows above / below the image): drain its loads here, so that the hot loop's wait
+      // counters only ever see the refills issued by the hot loop itself (vmcnt(0), other counters open)
+      __builtin_amdgcn_s_waitcnt(0x0F70);
     }
 
     // ---- neighbour values across lane groups and waves --------------------------
