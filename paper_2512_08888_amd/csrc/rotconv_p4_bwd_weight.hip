@@ -143,9 +143,15 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_weight(const float* __restrict__ 
     const float* xb = x + (size_t)n * ximg;
 
     // Branch-free loads: out-of-range positions read a safe (clamped) address; what they return is
-    // discarded when the row is routed (select_row).  X needs no mask: where a pixel is out of range D is
-    // zero, and the clamped address stays inside the same channel plane; channels beyond Cin land in padded
-    // columns of the partial sums that nobody reads.
+    // discarded when the row is routed (select_row).  X of pixels beyond the row must be zeroed (D there
+    // gathers from in-range neighbours): done where the half is used, and only in a strip that hangs over
+    // the row end, so the loads themselves stay unconditional.  Channels beyond Cin land in padded columns
+    // of the partial sums that nobody reads.
+    const bool tail = strip * 32 + 32 > g.W;       // wave-uniform
+    auto mask_x = [&](bool pok, f4 (&b)[NCB]) {
+#pragma unroll
+      for (int cb = 0; cb < NCB; ++cb) b[cb] = pok ? b[cb] : f4{0.f, 0.f, 0.f, 0.f};
+    };
     auto row_ok = [&](int h) { return cok && h >= 0 && h < g.H; };
     auto load_row = [&](int h, RowW& r) {
       const uint32_t ro = (uint32_t)min(max(h, 0), g.H - 1) * (uint32_t)g.W;
@@ -185,6 +191,7 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_weight(const float* __restrict__ 
       load_row(h + 2, rn);
       load_x(h, 1, bB);
       __builtin_amdgcn_sched_barrier(0);
+      if (tail) mask_x(pok0, bA);
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
         mfma_half(aA, bA, t);
@@ -194,6 +201,7 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_weight(const float* __restrict__ 
       load_x(h + 1, 0, bA);
       route(rn, h + 2, ma);
       __builtin_amdgcn_sched_barrier(0);
+      if (tail) mask_x(pok1, bB);
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
         mfma_half(aB, bB, t);

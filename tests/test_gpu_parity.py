@@ -54,6 +54,10 @@ TINY = [
     LC("t_cin256", N=1, Cin=256, H=10, W=32, Cout=18, R=4, seed=36),
     LC("t_cin288_r16", N=1, Cin=288, H=9, W=64, Cout=16, R=16, mode="bilinear", seed=37),
     LC("t_w544_cin6", N=1, Cin=6, H=6, W=544, Cout=16, R=8, mode="steerable", pool_group=4, seed=38),
+    # rows that end half way through a lane's eight pixels (W % 8 == 4), one and several strips, many rows
+    LC("t_w4", N=2, Cin=5, H=10, W=4, Cout=6, R=4, seed=39),
+    LC("t_w44", N=1, Cin=3, H=7, W=44, Cout=4, R=4, seed=40),
+    LC("t_w20_cout72", N=1, Cin=40, H=8, W=20, Cout=72, R=4, seed=41),
 ]
 
 
