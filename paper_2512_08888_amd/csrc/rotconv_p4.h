@@ -37,7 +37,8 @@ void launch_p4_combine(const rotconv_plan* p, const float* pv, const uint8_t* pi
 struct P4BwdGeom {
   int N, Cin, CinPad, H, W, Cout, CoutPad, R, Q, ng;
   int ncig;    // groups of 64 input channels
-  int nstrip;  // 32-pixel strips per row
+  int px;      // pixels per lane (2 or 4)
+  int nstrip;  // strips of 16 * px pixels per row
   int nrb;     // blocks of 8 rows
   int units;
 };

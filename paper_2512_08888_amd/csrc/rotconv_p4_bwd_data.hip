@@ -41,13 +41,17 @@ __device__ __host__ constexpr int tap_j(int s, int u) {
   return s == 0 ? u % 3 : s == 1 ? u / 3 : s == 2 ? 2 - u % 3 : 2 - u / 3;
 }
 
-struct Raw {           // (G, idx) of one filter on a 3 x 4 pixel neighbourhood, as loaded
-  float gl[3], gr[3];  // left / right neighbour of the lane's two pixels
-  float2 gc[3];        // the two pixels
-  uint32_t il[3], ic[3], ir[3];   // idx of the same positions (ic: two bytes)
+template <int PX>
+struct Raw {           // (G, idx) of one filter on a 3 x (PX + 2) pixel neighbourhood, as loaded
+  float gl[3], gr[3];  // left / right neighbour of the lane's PX pixels
+  float gc[3][PX];     // the PX pixels
+  uint32_t il[3], ic[3], ir[3];   // idx of the same positions (ic: PX bytes)
   uint32_t finv;       // all ones if the lane's filter of this K-step is beyond Cout
 };
 
+// PX = pixels per lane (2 or 4): a wave owns one image row x 16 PX pixels x 64 input channels.  More pixels
+// per lane means fewer selects and loads per pixel (the 3 x (PX + 2) neighbourhood is shared by PX pixels).
+template <int PX>
 __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gpool, const uint8_t* __restrict__ idx,
                                                     const float* __restrict__ wd,
                                                     const int32_t* __restrict__ rot_of, float* __restrict__ dx,
@@ -66,7 +70,7 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gp
   const int wave = tid / 64, lane = tid % 64;
   const int lg = lane / 16, lc = lane % 16;
   const int h = rb * NWAVE + wave;
-  const int x0 = strip * 32;
+  const int x0 = strip * 16 * PX;
   const bool active = h < g.H;
   const int HW = g.H * g.W;
   const int nkq = g.CoutPad / 4;               // K-steps per bank
@@ -74,26 +78,28 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gp
   const int nchunks = nk / 4;
 
   // ---- weight chunk streaming -----------------------------------------------------
-  constexpr int N4 = CHUNK * 9 * (CIG / 4);    // float4 per chunk
-  constexpr int WPT = (N4 + NT - 1) / NT;      // float4 per thread
-  f4 wreg[WPT];
-  auto wload = [&](int cc) {
+  // A chunk is 16 filters x 9 taps x 64 channels.  It is copied global -> registers -> LDS a quarter
+  // (four filters) per pipeline stage into the buffer the current chunk does not use, so that only two
+  // staging registers are live at any time.
+  constexpr int Q4 = 4 * 9 * (CIG / 4);        // float4 per quarter chunk (576)
+  f4 wreg[2];
+  auto wload = [&](int cc, int part) {
 #pragma unroll
-    for (int k = 0; k < WPT; ++k) {
+    for (int k = 0; k < 2; ++k) {
       const int e = tid + k * NT;
-      if (e < N4) {
-        const int c4 = e % (CIG / 4), u = (e / (CIG / 4)) % 9, r = e / (9 * (CIG / 4));
+      if (e < Q4) {
+        const int c4 = e % (CIG / 4), u = (e / (CIG / 4)) % 9, r = part * 4 + e / (9 * (CIG / 4));
         wreg[k] = *reinterpret_cast<const f4*>(wd + ((size_t)(cc * CHUNK + r) * 9 + u) * g.CinPad + cig * CIG + c4 * 4);
       }
     }
   };
-  auto wstore = [&](int buf) {
+  auto wstore = [&](int buf, int part) {
     float* dst = smem + buf * CHUNK * WROW;
 #pragma unroll
-    for (int k = 0; k < WPT; ++k) {
+    for (int k = 0; k < 2; ++k) {
       const int e = tid + k * NT;
-      if (e < N4) {
-        const int c4 = e % (CIG / 4), u = (e / (CIG / 4)) % 9, r = e / (9 * (CIG / 4));
+      if (e < Q4) {
+        const int c4 = e % (CIG / 4), u = (e / (CIG / 4)) % 9, r = part * 4 + e / (9 * (CIG / 4));
         *reinterpret_cast<f4*>(dst + r * WROW + u * CIG + c4 * 4) = wreg[k];
       }
     }
@@ -106,18 +112,19 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gp
   // orientation (R <= 255), so they contribute nothing; so do lanes whose filter is beyond Cout (they
   // read filter 0).  Nothing is computed from a loaded value before the K-step that uses it, so the
   // loads stay in flight for two K-steps.
-  const int xa = x0 + 2 * lc;                  // first of this lane's two pixels
-  uint32_t offc[3], offl[3], offr[3], inval[3];
+  const int xa = x0 + PX * lc;                 // first of this lane's PX pixels (W % PX == 0: in or out together)
+  uint32_t offc[3], offl[3], offr[3], invc[3], inve[3];   // invc: centre bytes, inve: byte 0 left, byte 1 right
 #pragma unroll
   for (int dr = 0; dr < 3; ++dr) {
     const int row = h - 1 + dr;
     const bool rok = active && row >= 0 && row < g.H;
-    const bool okc = rok && xa < g.W, okl = rok && xa >= 1 && xa - 1 < g.W, okr = rok && xa + 2 < g.W;
+    const bool okc = rok && xa < g.W, okl = rok && xa >= 1 && xa - 1 < g.W, okr = rok && xa + PX < g.W;
     const uint32_t rowoff = (uint32_t)(rok ? row : 0) * (uint32_t)g.W;
     offc[dr] = rowoff + (uint32_t)(okc ? xa : 0);
     offl[dr] = rowoff + (uint32_t)(okl ? xa - 1 : 0);
-    offr[dr] = rowoff + (uint32_t)(okr ? xa + 2 : 0);
-    inval[dr] = (okl ? 0u : 0xffu) | (okc ? 0u : 0xffff00u) | (okr ? 0u : 0xff000000u);
+    offr[dr] = rowoff + (uint32_t)(okr ? xa + PX : 0);
+    invc[dr] = okc ? 0u : 0xffffffffu;
+    inve[dr] = (okl ? 0u : 0xffu) | (okr ? 0u : 0xff00u);
   }
   const uint32_t plane = (uint32_t)g.ng * (uint32_t)HW;          // floats between consecutive filters
   const float* gimg = gpool + (size_t)n * g.Cout * plane;
@@ -139,7 +146,7 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gp
     bank_rot(0, r);
     ld_pg = group_of(r);
   }
-  auto raw_load = [&](Raw& r) {
+  auto raw_load = [&](Raw<PX>& r) {
     const bool fok = ld_co + lg < g.Cout;
     const uint32_t fl = (uint32_t)(fok ? ld_co + lg : 0) * plane;   // lane's filter plane
     const float* gb = gimg + (size_t)ld_pg * HW;
@@ -147,8 +154,16 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gp
     r.finv = fok ? 0u : 0xffffffffu;
 #pragma unroll
     for (int dr = 0; dr < 3; ++dr) {
-      r.gc[dr] = *reinterpret_cast<const float2*>(gb + (fl + offc[dr]));
-      r.ic[dr] = *reinterpret_cast<const uint16_t*>(ib + (fl + offc[dr]));
+      if (PX == 2) {
+        const float2 v = *reinterpret_cast<const float2*>(gb + (fl + offc[dr]));
+        r.gc[dr][0] = v.x; r.gc[dr][1] = v.y;
+        r.ic[dr] = *reinterpret_cast<const uint16_t*>(ib + (fl + offc[dr]));
+      } else {
+        const f4 v = *reinterpret_cast<const f4*>(gb + (fl + offc[dr]));
+#pragma unroll
+        for (int p = 0; p < PX; ++p) r.gc[dr][p] = v[p];
+        r.ic[dr] = *reinterpret_cast<const uint32_t*>(ib + (fl + offc[dr]));
+      }
       r.gl[dr] = gb[fl + offl[dr]];
       r.gr[dr] = gb[fl + offr[dr]];
       r.il[dr] = ib[fl + offl[dr]];
@@ -167,37 +182,42 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gp
 
   // One quarter turn's share of the nine tap sums for the lane's two pixels (Eq. 12 + the rotated
   // tap positions of Eq. 8): Delta_s on the neighbourhood, added where R_s puts each base tap.
-  auto build_slice = [&](const Raw& r, int s, int rs, float (&a)[9][2]) {
-    float d[3][4];
+  auto build_slice = [&](const Raw<PX>& r, int s, int rs, float (&a)[9][PX]) {
+    float d[3][PX + 2];
 #pragma unroll
     for (int dr = 0; dr < 3; ++dr) {
-      const uint32_t iw = (r.il[dr] | (r.ic[dr] << 8) | (r.ir[dr] << 24)) | inval[dr] | r.finv;
-      const float gv[4] = {r.gl[dr], r.gc[dr].x, r.gc[dr].y, r.gr[dr]};
+      const uint32_t iwc = r.ic[dr] | invc[dr] | r.finv | (PX == 2 ? 0xffff0000u : 0u);
+      const uint32_t iwe = (r.il[dr] | (r.ir[dr] << 8)) | inve[dr] | r.finv;
+      d[dr][0] = ((iwe & 0xffu) == (uint32_t)rs) ? r.gl[dr] : 0.f;
+      d[dr][PX + 1] = (((iwe >> 8) & 0xffu) == (uint32_t)rs) ? r.gr[dr] : 0.f;
 #pragma unroll
-      for (int p = 0; p < 4; ++p) d[dr][p] = (((iw >> (8 * p)) & 0xffu) == (uint32_t)rs) ? gv[p] : 0.f;
+      for (int p = 0; p < PX; ++p) d[dr][1 + p] = (((iwc >> (8 * p)) & 0xffu) == (uint32_t)rs) ? r.gc[dr][p] : 0.f;
     }
 #pragma unroll
-    for (int u = 0; u < 9; ++u) {
-      const float t0 = d[2 - tap_i(s, u)][2 - tap_j(s, u)], t1 = d[2 - tap_i(s, u)][3 - tap_j(s, u)];
-      a[u][0] = s == 0 ? t0 : a[u][0] + t0;
-      a[u][1] = s == 0 ? t1 : a[u][1] + t1;
-    }
+    for (int u = 0; u < 9; ++u)
+#pragma unroll
+      for (int b = 0; b < PX; ++b) {
+        const float t = d[2 - tap_i(s, u)][b + 2 - tap_j(s, u)];
+        a[u][b] = s == 0 ? t : a[u][b] + t;
+      }
   };
 
-  f4 acc[NCB][2];
+  f4 acc[NCB][PX];
 #pragma unroll
-  for (int cb = 0; cb < NCB; ++cb) { acc[cb][0] = f4{0.f, 0.f, 0.f, 0.f}; acc[cb][1] = f4{0.f, 0.f, 0.f, 0.f}; }
+  for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+    for (int b = 0; b < PX; ++b) acc[cb][b] = f4{0.f, 0.f, 0.f, 0.f};
 
   // Three-stage pipeline over K-steps: (G, idx) loads two steps ahead, A build one step ahead and
   // spread between the MFMAs of the current step, B reads from LDS one tap ahead.  Scheduling fences
   // keep the loads at the head of the stage; left alone, the compiler sinks them next to their use.
-  Raw rawA, rawB;
-  float aA[9][2], aB[9][2];
+  Raw<PX> rawA, rawB;
+  float aA[9][PX], aB[9][PX];
   int rotb[4];                      // orientations of the bank of the K-step being built
   int bd_q = 0, bd_co = 0;          // build cursor
   bank_rot(0, rotb);
-  auto stage = [&](int ks, const float* wl, const Raw& raw_use, Raw& raw_ld, const float (&a_cur)[9][2],
-                   float (&a_nxt)[9][2]) {
+  auto stage = [&](int ks, const float* wl, const Raw<PX>& raw_use, Raw<PX>& raw_ld, const float (&a_cur)[9][PX],
+                   float (&a_nxt)[9][PX]) {
     raw_load(raw_ld);
     // the K-step being built is the one after the current one
     if (bd_co + 4 < g.CoutPad) {
@@ -217,10 +237,10 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gp
       if (u < 8) bw[(u + 1) & 1] = *reinterpret_cast<const f4*>(wl + (ks * 4) * WROW + (u + 1) * CIG);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int cb = 0; cb < NCB; ++cb) {
-        acc[cb][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur[u][0], bw[u & 1][cb], acc[cb][0], 0, 0, 0);
-        acc[cb][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur[u][1], bw[u & 1][cb], acc[cb][1], 0, 0, 0);
-      }
+      for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+        for (int b = 0; b < PX; ++b)
+          acc[cb][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur[u][b], bw[u & 1][cb], acc[cb][b], 0, 0, 0);
       if ((u & 1) == 0 && u < 8) build_slice(raw_use, u / 2, rotb[u / 2], a_nxt);
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -230,41 +250,47 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gp
 #pragma unroll
   for (int s = 0; s < 4; ++s) build_slice(rawB, s, rotb[s], aA);
   raw_load(rawA);
-  wload(0);
-  wstore(0);
+#pragma unroll
+  for (int part = 0; part < 4; ++part) {
+    wload(0, part);
+    wstore(0, part);
+  }
   __syncthreads();
 
   for (int cc = 0; cc < nchunks; ++cc) {
-    if (cc + 1 < nchunks) wload(cc + 1);
-    __builtin_amdgcn_sched_barrier(0);
+    const bool more = cc + 1 < nchunks;
     const float* wl = smem + (cc & 1) * CHUNK * WROW + lg * WROW + lc * 4;
+    if (more) wload(cc + 1, 0);
     stage(0, wl, rawA, rawB, aA, aB);
+    if (more) { wstore((cc + 1) & 1, 0); wload(cc + 1, 1); }
     stage(1, wl, rawB, rawA, aB, aA);
+    if (more) { wstore((cc + 1) & 1, 1); wload(cc + 1, 2); }
     stage(2, wl, rawA, rawB, aA, aB);
+    if (more) { wstore((cc + 1) & 1, 2); wload(cc + 1, 3); }
     stage(3, wl, rawB, rawA, aB, aA);
-    if (cc + 1 < nchunks) wstore((cc + 1) & 1);
+    if (more) wstore((cc + 1) & 1, 3);
     __syncthreads();
   }
 
-  // ---- store: lane (lg, lc) holds channel cb*16+lc, pixels x0 + 8*lg + j, j = 2*i + b ----
+  // ---- store: lane (lg, lc) holds channel cb*16+lc, pixels x0 + 4*PX*lg + j, j = PX*i + b ----
   if (!active) return;
 #pragma unroll
   for (int cb = 0; cb < NCB; ++cb) {
     const int ci = cig * CIG + cb * 16 + lc;
     if (ci >= g.Cin) continue;
-    const int px = x0 + 8 * lg;
+    const int px = x0 + 4 * PX * lg;
     float* o = dx + ((size_t)n * g.Cin + ci) * HW + (size_t)h * g.W + px;
-    float vals[8];
+    float vals[4 * PX];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) vals[j] = acc[cb][j & 1][j >> 1];
-    if ((g.W & 7) == 0) {
-      if (px < g.W) {
-        reinterpret_cast<f4*>(o)[0] = f4{vals[0], vals[1], vals[2], vals[3]};
-        reinterpret_cast<f4*>(o)[1] = f4{vals[4], vals[5], vals[6], vals[7]};
-      }
+    for (int j = 0; j < 4 * PX; ++j) vals[j] = acc[cb][j % PX][j / PX];
+    if ((g.W & 3) == 0) {
+#pragma unroll
+      for (int v4 = 0; v4 < PX; ++v4)
+        if (px + 4 * v4 < g.W)
+          reinterpret_cast<f4*>(o)[v4] = f4{vals[4 * v4], vals[4 * v4 + 1], vals[4 * v4 + 2], vals[4 * v4 + 3]};
     } else {
 #pragma unroll
-      for (int j = 0; j < 8; ++j)
+      for (int j = 0; j < 4 * PX; ++j)
         if (px + j < g.W) o[j] = vals[j];
     }
   }
@@ -311,7 +337,8 @@ P4BwdGeom p4_bwd_data_geom(const rotconv_plan* p) {
   P4BwdGeom g{};
   g.N = d.N; g.Cin = d.Cin; g.CinPad = (d.Cin + CIG - 1) / CIG * CIG; g.H = d.H; g.W = d.W; g.Cout = d.Cout;
   g.CoutPad = (d.Cout + 15) / 16 * 16; g.R = d.R; g.Q = p->host.Q; g.ng = p->ng;
-  g.ncig = g.CinPad / CIG; g.nstrip = (d.W + 31) / 32; g.nrb = (d.H + NWAVE - 1) / NWAVE;
+  g.px = ((d.W & 3) == 0 && d.W > 32) ? 4 : 2;   // pixels per lane
+  g.ncig = g.CinPad / CIG; g.nstrip = (d.W + 16 * g.px - 1) / (16 * g.px); g.nrb = (d.H + NWAVE - 1) / NWAVE;
   g.units = d.N * g.ncig * g.nstrip * g.nrb;
   return g;
 }
@@ -333,9 +360,15 @@ void launch_p4_bwd_data(const rotconv_plan* p, const float* gpool, const uint8_t
   const P4BwdGeom g = p4_bwd_data_geom(p);
   const size_t lds = (size_t)2 * CHUNK * WROW * sizeof(float);
   const int grid = (g.units + 7) / 8 * 8;
-  (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_p4_bwd_data), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)lds);
-  hipLaunchKernelGGL(k_p4_bwd_data, dim3(grid), dim3(NT), lds, st, gpool, idx, wd, p->dev.rot_of, dx, g);
+  if (g.px == 4) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_p4_bwd_data<4>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipLaunchKernelGGL(k_p4_bwd_data<4>, dim3(grid), dim3(NT), lds, st, gpool, idx, wd, p->dev.rot_of, dx, g);
+  } else {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_p4_bwd_data<2>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipLaunchKernelGGL(k_p4_bwd_data<2>, dim3(grid), dim3(NT), lds, st, gpool, idx, wd, p->dev.rot_of, dx, g);
+  }
 }
 
 }  // namespace rotconv
