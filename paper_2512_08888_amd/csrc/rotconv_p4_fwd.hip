@@ -126,7 +126,8 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restri
   const int pxa = x0 + 2 * lc;
   const bool px_ok = pxa < g.W;
   const float* xn = x + (size_t)n * g.Cin * HW + (px_ok ? pxa : 0);
-  const uint32_t lgoff = (uint32_t)lg * (uint32_t)HW;
+  uint32_t lgoff = (uint32_t)lg * (uint32_t)HW;
+  asm volatile("" : "+v"(lgoff));   // opaque: keeps the K-step part of the offset scalar (no per-load vector multiply)
   const uint32_t off_last = (uint32_t)(g.Cin - 1) * (uint32_t)HW;   // channels beyond Cin read channel Cin-1
   auto row_ptr = [&](int t) -> const float* {
     const int h = min(max(y0 - 1 + t, 0), g.H - 1);
@@ -162,14 +163,12 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restri
     const bool row_ok = h >= 0 && h < g.H;
     const float* rp_cur = row_ptr(t);
     const float* rp_nxt = row_ptr(t + 1);
-    f4 P[9][2];
-#pragma unroll
-    for (int u = 0; u < 9; ++u) { P[u][0] = f4{0.f, 0.f, 0.f, 0.f}; P[u][1] = f4{0.f, 0.f, 0.f, 0.f}; }
+    f4 P[9][2];   // written by the row's first K-step (accumulator input = constant zero), or zeroed below
 
     // One 32-channel chunk: MFMAs of its eight K-steps, each slot of A refilled for the next chunk right
     // after its MFMAs, B read from LDS one K-step ahead.  The scheduling fences keep loads and LDS reads
     // where they are issued; left alone the compiler sinks them next to their first use and waits there.
-    auto chunk = [&](int c, bool mul) {
+    auto chunk = [&](int c, bool mul, bool first) {
       const bool last = c + 1 == nchunk;
       const float* rp = last ? rp_nxt : rp_cur;
       const int kn = last ? 0 : (c + 1) * KC;
@@ -188,8 +187,9 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restri
           __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
           for (int u = 0; u < 9; ++u) {
-            P[u][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur[ks].x, bw[ks & 1][u], P[u][0], 0, 0, 0);
-            P[u][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur[ks].y, bw[ks & 1][u], P[u][1], 0, 0, 0);
+            const f4 zero = f4{0.f, 0.f, 0.f, 0.f};
+            P[u][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur[ks].x, bw[ks & 1][u], first && ks == 0 ? zero : P[u][0], 0, 0, 0);
+            P[u][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur[ks].y, bw[ks & 1][u], first && ks == 0 ? zero : P[u][1], 0, 0, 0);
           }
           a_cur[ks] = load_a(rp, kn + ks);
           __builtin_amdgcn_sched_barrier(0);
@@ -205,9 +205,12 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restri
       ++seq;
     };
     if (row_ok) {
-      for (int c = 0; c < nchunk; ++c) chunk(c, true);
+      chunk(0, true, true);
+      for (int c = 1; c < nchunk; ++c) chunk(c, true, false);
     } else {
-      for (int c = 0; c < nchunk; ++c) chunk(c, false);
+#pragma unroll
+      for (int u = 0; u < 9; ++u) { P[u][0] = f4{0.f, 0.f, 0.f, 0.f}; P[u][1] = f4{0.f, 0.f, 0.f, 0.f}; }
+      for (int c = 0; c < nchunk; ++c) chunk(c, false, false);
       // rare path (rows above / below the image): drain its loads here, so that the hot loop's wait
       // counters only ever see the refills issued by the hot loop itself (vmcnt(0), other counters open)
       __builtin_amdgcn_s_waitcnt(0x0F70);
