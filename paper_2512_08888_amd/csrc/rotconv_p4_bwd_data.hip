@@ -337,8 +337,10 @@ P4BwdGeom p4_bwd_data_geom(const rotconv_plan* p) {
   P4BwdGeom g{};
   g.N = d.N; g.Cin = d.Cin; g.CinPad = (d.Cin + CIG - 1) / CIG * CIG; g.H = d.H; g.W = d.W; g.Cout = d.Cout;
   g.CoutPad = (d.Cout + 15) / 16 * 16; g.R = d.R; g.Q = p->host.Q; g.ng = p->ng;
-  g.px = ((d.W & 3) == 0 && d.W > 32) ? 4 : 2;   // pixels per lane
-  g.ncig = g.CinPad / CIG; g.nstrip = (d.W + 16 * g.px - 1) / (16 * g.px); g.nrb = (d.H + NWAVE - 1) / NWAVE;
+  g.ncig = g.CinPad / CIG; g.nrb = (d.H + NWAVE - 1) / NWAVE;
+  // pixels per lane: four when the rows are long enough and that still leaves a workgroup per CU
+  g.px = ((d.W & 3) == 0 && d.W > 32 && d.N * g.ncig * g.nrb * ((d.W + 63) / 64) >= 256) ? 4 : 2;
+  g.nstrip = (d.W + 16 * g.px - 1) / (16 * g.px);
   g.units = d.N * g.ncig * g.nstrip * g.nrb;
   return g;
 }
