@@ -11,12 +11,13 @@
 // (filter, tap) runs on the fp32 matrix cores: the multiplications are shared by
 // the four rotations exactly as in the forward pass.
 //
-// A wave owns one image row x 32 pixels x 64 input channels (four 16x16
-// accumulator tiles per 16-pixel block).  Per K-step of 4 filters a lane reads
-// the 3x4 pixel neighbourhood of (G, idx) of its filter straight from global
-// memory (L1/L2 resident: the eight waves of a workgroup take eight consecutive
-// rows), builds its 18 A values and feeds 72 MFMAs.  The weights stream through
-// LDS in chunks of 16 filters, double-buffered, one barrier per chunk.
+// A wave owns one image row x 16 PX pixels x 64 input channels (PX = 2 or 4 pixels
+// per lane, four 16x16 accumulator tiles per 16-pixel block).  Per K-step of 4
+// filters a lane reads the 3 x (PX + 2) pixel neighbourhood of (G, idx) of its
+// filter straight from global memory (L1/L2 resident: the eight waves of a
+// workgroup take eight consecutive rows), builds its 9 PX A values and feeds
+// 36 PX MFMAs.  The weights stream through LDS in chunks of 16 filters,
+// double-buffered, a quarter chunk per pipeline stage, one barrier per chunk.
 #include <hip/hip_runtime.h>
 
 #include "rotconv_kernels.h"

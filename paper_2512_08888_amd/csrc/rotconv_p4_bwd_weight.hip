@@ -8,13 +8,15 @@
 // positions BEFORE the contraction is Eq. 16's inverse-rotate-and-accumulate moved
 // in front of Eq. 14: one contraction over the pixels per bank instead of four.
 // The contraction runs on the fp32 matrix cores with M = 16 filters, N = 16 input
-// channels, K = 4 pixels; D is built on the fly by selects and adds in the A-operand
-// layout (a lane owns 4 consecutive pixels of one filter and reads the 3x6
-// neighbourhood of (G, idx) around them), X goes straight from global memory into
-// the B operand.  A wave keeps the 9 x 4 accumulator tiles of its 16 filters x 64
-// channels (144 registers) over its whole pixel range; ranges ("splits") are
-// summed afterwards in a fixed order by the reduction kernel, which also applies
-// the transposed first-quadrant expansion, so the result is deterministic.
+// channels, K = 4 pixels.  A lane owns 8 consecutive pixels of one filter (A role)
+// and of one channel (B role) in a 32-pixel strip and walks down the rows of its
+// range: every (G, idx) row is loaded and routed per quarter turn once and stays
+// in registers for the three rows it serves; D is then built from adds alone, in
+// the A-operand layout; X goes straight from global memory into the B operand.
+// A wave keeps the 9 x 4 accumulator tiles of its 16 filters x 64 channels (144
+// registers) over all its work units; the workgroups' sums ("splits") are added
+// afterwards in a fixed order by the reduction kernel, which also applies the
+// transposed first-quadrant expansion, so the result is deterministic.
 #include <hip/hip_runtime.h>
 
 #include "rotconv_kernels.h"

@@ -19,7 +19,9 @@
 // LDS for the life of the workgroup when it fits (Cin <= 224); deeper inputs
 // stream it through two 32-channel LDS buffers, one barrier per chunk.  Input
 // rows go straight from global memory into the A-operand registers (8-byte
-// loads, 128 B contiguous per 16 lanes), each slot refilled one chunk ahead.
+// loads, 128 B contiguous per 16 lanes), each slot refilled one chunk ahead;
+// scheduling fences keep those loads and the LDS reads of the B operand where
+// they are issued (the compiler would otherwise sink them to their first use).
 //
 // Rows wider than the 256 pixels a workgroup's eight waves can chain are cut
 // into segments that overlap by 8 pixels (the products of the overlap are
