@@ -65,7 +65,8 @@ def cpu_baseline(cfg, Q):
 
 
 def bench_unet(name, steps, warmup):
-    """ms per training step of the UNet-shaped stack (benchmark configurations 4 and 5, fp32), whole
+    """ms per training step of the UNet-shaped stack (benchmark configurations 4 and 5; P4 / P8 / P16: the
+    paper's own block, rotation convolution then standard convolution, at 4 / 8 / 16 orientations; fp32), whole
     step timed between synchronisations; then one more step with an event pair around every library
     call for the per-call breakdown."""
     import torch
@@ -97,7 +98,7 @@ def bench_unet(name, steps, warmup):
     loss = float(net.loss.cpu()[0])
     out = {
         "workload": f"{cfg.name}: UNet-shaped stack, N={cfg.N} {cfg.H}x{cfg.W} widths={list(cfg.widths)} "
-                    f"classes={cfg.classes} R={cfg.R} {cfg.mode}, one training step (fwd+bwd), fp32",
+                    f"classes={cfg.classes} R={cfg.R} {cfg.mode} block={cfg.block}, one training step (fwd+bwd), fp32",
         "ms_per_step": ms, "steps": steps, "warmup": warmup, "loss": loss,
         "rotconv_flops_algorithmic": alg, "rotconv_flops_dense_equivalent": dense,
         "rotconv_ms": rot_ms, "glue_ms": sum(by_call.values()) - rot_ms,
@@ -127,7 +128,7 @@ def cpu_baseline_unet(name):
     params = {k: v.astype(np.float64) for k, v in un.make_params(sc).items()}
     images, labels = un.make_batch(sc)
     t0 = time.perf_counter()
-    uo.unet_step(images.astype(np.float64), labels, params, sc.R, sc.mode, sc.pool_group)
+    uo.unet_step(images.astype(np.float64), labels, params, sc.R, sc.mode, sc.pool_group, un.oracle_layer_spec(sc))
     dt = time.perf_counter() - t0
     scale = (cfg.N * cfg.H * cfg.W) / (sc.N * sc.H * sc.W)
     cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
@@ -161,7 +162,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4", "C5"])
+    ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4", "C5", "P4", "P8", "P16"])
     ap.add_argument("--no-unet", action="store_true", help="skip the UNet-shaped steps appended to the default line")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -173,7 +174,7 @@ def main():
               "see DESIGN.md); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
-    if args.workload in ("C4", "C5"):
+    if args.workload in ("C4", "C5", "P4", "P8", "P16"):
         return main_unet(args)
 
     import torch

@@ -91,16 +91,21 @@ def rot_layer_names(depth=4):
     return names
 
 
-def unet_step(images, labels, params, R=4, mode="exact90", pool_group=None):
+def unet_step(images, labels, params, R=4, mode="exact90", pool_group=None, layer_spec=None):
     """One training step (forward + backward) of the stack.  params: dict name -> array
-    (rot layers [B,Cout,Cin,3,3], 'up{lvl}' [Cin,Cout,2,2], 'head' [K,C0]).
+    (rot layers [B,Cout,Cin,3,3], 'up{lvl}' [Cin,Cout,2,2], 'head' [K,C0]).  layer_spec: optional
+    dict name -> (R, mode, pool_group) for layers that differ from the common setting (the paper's own
+    block, Sec. V-A: rotation convolution followed by a standard convolution, R = 1).
     Returns (loss, grads dict, acts dict of every layer's forward tensors)."""
+    layer_spec = layer_spec or {}
+    common = (R, mode, pool_group)
     depth = sum(1 for k in params if k.startswith("enc") and k.endswith("a"))
     acts, tape = {}, []
 
     def rot(name, x):
         w = params[name]
-        _, yp, idx, _ = orc.layer_fwd(x, w, R, None, mode, 1, 1, pool_group)
+        Rl, model, Gl = layer_spec.get(name, common)
+        _, yp, idx, _ = orc.layer_fwd(x, w, Rl, None, model, 1, 1, Gl)
         y = relu_fwd(yp)
         acts[name] = dict(x=x, ypool=yp, idx=idx, y=y)
         tape.append(("rot", name))
@@ -135,7 +140,8 @@ def unet_step(images, labels, params, R=4, mode="exact90", pool_group=None):
         if kind == "rot":
             dyp = relu_bwd(a["y"], dx)
             a["dypool"] = dyp
-            dxx, dw = orc.layer_bwd(a["x"], params[name], dyp, a["idx"], R, None, mode, 1, 1, pool_group)
+            Rl, model, Gl = layer_spec.get(name, common)
+            dxx, dw = orc.layer_bwd(a["x"], params[name], dyp, a["idx"], Rl, None, model, 1, 1, Gl)
             grads[name] = dw
             dx = dxx
         elif kind == "up":

@@ -53,7 +53,7 @@ void launch_p4_bwd_data(const rotconv_plan* p, const float* gpool, const uint8_t
 struct P4BwdWGeom {
   int N, Cin, CinPad, H, W, Cout, CoutPad, Q, ng;
   int ncig;    // groups of 64 input channels
-  int ncog;    // groups of 64 filters (one workgroup of 4 waves)
+  int ncog;    // groups of four (bank, 16-filter block) pairs (one workgroup of 4 waves)
   int nstrip;    // 32-pixel strips per row
   int rows_per;  // rows per range
   int nrange;    // row ranges per image

@@ -55,15 +55,21 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_weight(const float* __restrict__ 
   const int per_xcd = gridDim.x / 8;
   int v = gridDim.x % 8 == 0 ? (blockIdx.x % 8) * per_xcd + blockIdx.x / 8 : blockIdx.x;
   const int cig = v % g.ncig; v /= g.ncig;
-  const int cog = v % g.ncog; v /= g.ncog;
-  const int q = v % g.Q;
-  const int split = v / g.Q;
+  const int fbg = v % g.ncog;                 // group of four (bank, 16-filter block) pairs
+  const int split = v / g.ncog;
 
   const int tid = threadIdx.x;
   const int wave = tid / 64, lane = tid % 64;
   const int lg = lane / 16, lc = lane % 16;
   const int HW = g.H * g.W;
-  const int co = (cog * NWAVE + wave) * 16 + lc;     // this lane's filter (A role)
+  // The waves of a workgroup take consecutive (bank, 16-filter block) pairs, banks outermost, so that a bank
+  // with fewer than 64 filters does not leave waves idle.
+  const int nfb = g.CoutPad / 16;                                    // 16-filter blocks per bank
+  const int fb_flat = min(fbg * NWAVE + wave, g.Q * nfb - 1);       // an idle wave redoes the last pair
+  const bool wave_on = fbg * NWAVE + wave < g.Q * nfb;
+  const int q = __builtin_amdgcn_readfirstlane(fb_flat / nfb);   // wave-uniform: keeps the rotation indices scalar
+  const int cobase = (fb_flat % nfb) * 16;
+  const int co = cobase + lc;                        // this lane's filter (A role)
   const int ci0 = cig * 16 * NCB + lc;               // this lane's channel in block 0 (B role)
 
   int rot[4];
@@ -230,8 +236,7 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_weight(const float* __restrict__ 
   }
 
   // partial[split][q][u][CoutPad][CinPad]; lane holds rows (filters) 4*lg+i, column (channel) lc
-  const int cobase = (cog * NWAVE + wave) * 16;
-  if (cobase < g.CoutPad) {
+  if (wave_on) {
     float* out = partial + ((size_t)(split * g.Q + q) * 9) * g.CoutPad * g.CinPad;
 #pragma unroll
     for (int u = 0; u < 9; ++u)
@@ -297,11 +302,11 @@ P4BwdWGeom p4_bwd_weight_geom(const rotconv_plan* p) {
   P4BwdWGeom g{};
   g.N = d.N; g.Cin = d.Cin; g.H = d.H; g.W = d.W; g.Cout = d.Cout; g.Q = p->host.Q; g.ng = p->ng;
   g.CinPad = (d.Cin + 16 * NCB - 1) / (16 * NCB) * (16 * NCB);
-  g.CoutPad = (d.Cout + 16 * NWAVE - 1) / (16 * NWAVE) * (16 * NWAVE);
+  g.CoutPad = (d.Cout + 15) / 16 * 16;
   g.ncig = g.CinPad / (16 * NCB);
-  g.ncog = g.CoutPad / (16 * NWAVE);
+  g.ncog = (g.Q * (g.CoutPad / 16) + NWAVE - 1) / NWAVE;   // workgroups per channel group and split
   // work units: (image, row range, 32-pixel strip); a range never crosses an image
-  const int combos = g.Q * g.ncig * g.ncog;
+  const int combos = g.ncig * g.ncog;
   g.nstrip = (d.W + 31) / 32;
   const int want = (256 + combos - 1) / combos;                       // units wanted to fill the chip
   int per_image = std::max(1, std::min(d.H, (want + d.N * g.nstrip - 1) / (d.N * g.nstrip)));
@@ -322,7 +327,7 @@ size_t p4_bwd_weight_ws_floats(const rotconv_plan* p) {
 void launch_p4_bwd_weight(const rotconv_plan* p, const float* x, const float* gpool, const uint8_t* idx,
                           float* partial, float* dw, hipStream_t st) {
   const P4BwdWGeom g = p4_bwd_weight_geom(p);
-  const int grid = g.splits * g.ncig * g.ncog * g.Q;
+  const int grid = g.splits * g.ncig * g.ncog;
   hipLaunchKernelGGL(k_p4_bwd_weight, dim3(grid), dim3(NT), 0, st, x, gpool, idx, p->dev.rot_of, partial, g);
   const int n_elem = g.Q * 9 * g.CoutPad * g.CinPad;
   float* dF = partial + (size_t)g.splits * n_elem;

@@ -33,6 +33,11 @@ class UNetConfig:
     mode: str = "exact90"
     pool_group: Optional[int] = None  # None = pool over all R orientations
     seed: int = 2024
+    # "rot_rot": both convolutions of a block rotation-invariant, pooled over pool_group (the benchmark's
+    # stack).  "rot_std": the paper's own block (Sec. V-A): the first convolution rotation-invariant with
+    # pooling over the 4 quarter turns of each first-quadrant angle (R/4 features per filter, so
+    # width / (R/4) filters), the second a standard convolution (R = 1 through the same library).
+    block: str = "rot_rot"
 
     @property
     def depth(self):
@@ -45,7 +50,11 @@ class UNetConfig:
 
 C4 = UNetConfig("C4", 4, 3, 512, 512, (64, 128, 256, 512, 1024), 6, R=4, mode="exact90", seed=404)
 C5 = UNetConfig("C5", 2, 3, 512, 512, (64, 128, 256, 512, 1024), 6, R=16, mode="bilinear", pool_group=16, seed=505)
-UNET_CONFIGS = {"C4": C4, "C5": C5}
+# the paper's own block (rotation convolution, then a standard one) at 4, 8 and 16 orientations
+P4 = UNetConfig("P4", 4, 3, 512, 512, (64, 128, 256, 512, 1024), 6, R=4, mode="exact90", block="rot_std", seed=604)
+P8 = UNetConfig("P8", 4, 3, 512, 512, (64, 128, 256, 512, 1024), 6, R=8, mode="bilinear", block="rot_std", seed=608)
+P16 = UNetConfig("P16", 4, 3, 512, 512, (64, 128, 256, 512, 1024), 6, R=16, mode="bilinear", block="rot_std", seed=616)
+UNET_CONFIGS = {"C4": C4, "C5": C5, "P4": P4, "P8": P8, "P16": P16}
 
 
 def rot_layers(cfg: UNetConfig):
@@ -63,8 +72,33 @@ def rot_layers(cfg: UNetConfig):
     return out
 
 
+def layer_specs(cfg: UNetConfig):
+    """Per rotation-convolution layer in forward order: dict(name, Cin, Cout (base filters), H, W, R, mode,
+    pool_group, B (base banks), width (pooled output channels))."""
+    out = []
+    for name, ci, width, h, w in rot_layers(cfg):
+        if cfg.block == "rot_std":
+            if name.endswith("a"):
+                per = max(1, cfg.R // 4)
+                if width % per:
+                    raise ValueError("layer width must be divisible by R/4 in the rot_std block")
+                spec = dict(R=cfg.R, mode=cfg.mode, pool_group=min(4, cfg.R), Cout=width // per)
+            else:
+                spec = dict(R=1, mode="exact90", pool_group=None, Cout=width)
+        else:
+            spec = dict(R=cfg.R, mode=cfg.mode, pool_group=cfg.pool_group, Cout=width)
+        spec.update(name=name, Cin=ci, H=h, W=w, width=width, B=2 if spec["mode"] == "steerable" else 1)
+        out.append(spec)
+    return out
+
+
+def oracle_layer_spec(cfg: UNetConfig):
+    """name -> (R, mode, pool_group) in the form the stack oracle takes."""
+    return {sp["name"]: (sp["R"], sp["mode"], sp["pool_group"]) for sp in layer_specs(cfg)}
+
+
 def param_shapes(cfg: UNetConfig) -> Dict[str, Tuple[int, ...]]:
-    shapes = {n: (cfg.B, co, ci, 3, 3) for n, ci, co, _, _ in rot_layers(cfg)}
+    shapes = {sp["name"]: (sp["B"], sp["Cout"], sp["Cin"], 3, 3) for sp in layer_specs(cfg)}
     for lvl in range(cfg.depth):
         shapes[f"up{lvl}"] = (cfg.widths[lvl + 1], cfg.widths[lvl], 2, 2)
     shapes["head"] = (cfg.classes, cfg.widths[0])
@@ -108,18 +142,21 @@ class UNet:
         def buf(*shape, dtype=f32):
             return torch.empty(shape, dtype=dtype, device=device)
 
-        self.layers = rot_layers(cfg)
+        self.layers = rot_layers(cfg)         # (name, Cin, width, H, W)
+        self.specs = layer_specs(cfg)
         self.plans: Dict[str, rc.Plan] = {}
         self.act: Dict[str, Dict[str, "torch.Tensor"]] = {}
         ws_bytes = 256
-        for name, ci, co, h, w in self.layers:
-            p = rc.Plan(N, ci, h, w, co, k=3, R=cfg.R, mode=cfg.mode, stride=1, pad=1, pool_group=cfg.pool_group or 0)
+        for sp in self.specs:
+            name, h, w = sp["name"], sp["H"], sp["W"]
+            p = rc.Plan(N, sp["Cin"], h, w, sp["Cout"], k=3, R=sp["R"], mode=sp["mode"], stride=1, pad=1,
+                        pool_group=sp["pool_group"] or 0)
             self.plans[name] = p
             ws_bytes = max(ws_bytes, p.workspace_bytes)
             self.act[name] = dict(y=buf(N, p.Cpooled, h, w), idx=buf(N, p.Cpooled, h, w, dtype=u8),
                                   g=buf(N, p.Cpooled, h, w))
-            if p.Cpooled != co:
-                raise ValueError("the stack needs layers whose pooled channel count equals Cout (pool over all R)")
+            if p.Cpooled != sp["width"]:
+                raise ValueError(f"{name}: pooled channel count {p.Cpooled} differs from the layer width {sp['width']}")
         h, w = cfg.H, cfg.W
         for lvl in range(cfg.depth):
             c = cfg.widths[lvl]
@@ -150,12 +187,12 @@ class UNet:
         gradient for the first layer."""
         cfg = self.cfg
         alg = dense = 0.0
-        for i, (name, ci, co, h, w) in enumerate(self.layers):
-            Q = self.plans[name].orientations()[0]
-            P = cfg.N * h * w
+        for i, sp in enumerate(self.specs):
+            Q = self.plans[sp["name"]].orientations()[0]
+            P = cfg.N * sp["H"] * sp["W"]
             passes = 2 if i == 0 else 3
-            alg += passes * (2.0 * P * ci * co * 9 * Q * cfg.B + P * co * 9 * cfg.R)
-            dense += passes * 2.0 * P * ci * co * 9 * cfg.R
+            alg += passes * (2.0 * P * sp["Cin"] * sp["Cout"] * 9 * Q * sp["B"] + P * sp["Cout"] * 9 * sp["R"])
+            dense += passes * 2.0 * P * sp["Cin"] * sp["Cout"] * 9 * sp["R"]
         return alg, dense
 
     # ---- host <-> device plumbing -------------------------------------------------------------

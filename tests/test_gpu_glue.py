@@ -161,6 +161,10 @@ SMALL = [
     un.UNetConfig("u_r4_d2", 2, 3, 32, 64, (8, 12, 16), 4, R=4, mode="exact90", seed=11),
     un.UNetConfig("u_r4_d3", 1, 3, 64, 32, (16, 24, 40, 72), 6, R=4, mode="exact90", seed=12),
     un.UNetConfig("u_r16_d2", 1, 3, 32, 32, (8, 8, 16), 3, R=16, mode="bilinear", pool_group=16, seed=13),
+    # the paper's own block: rotation convolution pooled over quarter turns, then a standard convolution
+    un.UNetConfig("p_r4_d2", 2, 3, 32, 64, (8, 12, 16), 4, R=4, mode="exact90", block="rot_std", seed=14),
+    un.UNetConfig("p_r8_d2", 1, 3, 32, 32, (8, 12, 16), 3, R=8, mode="bilinear", block="rot_std", seed=15),
+    un.UNetConfig("p_r16_d1", 1, 3, 32, 64, (8, 16), 3, R=16, mode="steerable", block="rot_std", seed=16),
 ]
 
 
@@ -173,12 +177,13 @@ def test_unet_step_teacher_forced(cfg):
     H = lambda t: t.detach().cpu().numpy().astype(np.float64)
     p64 = {k: v.astype(np.float64) for k, v in params.items()}
     # forward, layer by layer
-    for name, ci, co, h, w in net.layers:
+    for sp in net.specs:
+        name, R, mode, G = sp["name"], sp["R"], sp["mode"], sp["pool_group"]
         x = H(A[name]["x"])
-        y_ref, yp_ref, idx_ref, w_rot = orc.layer_fwd(x, p64[name], cfg.R, None, cfg.mode, 1, 1, cfg.pool_group)
+        y_ref, yp_ref, idx_ref, w_rot = orc.layer_fwd(x, p64[name], R, None, mode, 1, 1, G)
         assert_close(H(A[name]["y"]), uo.relu_fwd(yp_ref), f"{name} fwd")
         abs_terms = orc.rotconv_fwd(np.abs(x), np.abs(w_rot), 1, 1)
-        check_idx(H(A[name]["idx"]).astype(np.uint8), y_ref, abs_terms, cfg.pool_group or cfg.R, f"{name} idx")
+        check_idx(H(A[name]["idx"]).astype(np.uint8), y_ref, abs_terms, G or R, f"{name} idx")
     for lvl in range(cfg.depth):
         p = A[f"pool{lvl}"]
         yr, ir = uo.maxpool2_fwd(H(A[f"enc{lvl}b"]["y"]))
@@ -198,12 +203,13 @@ def test_unet_step_teacher_forced(cfg):
     dxr, dwr = uo.conv1x1_bwd(H(hd["x"]), p64["head"], H(hd["g"]))
     assert_close(H(net.grads["head"]), dwr, "head dW")
     assert_close(H(A["dec0b"]["g"]), masked("dec0b", dxr), "head dX")
-    for i, (name, ci, co, h, w) in enumerate(net.layers):
+    for i, sp in enumerate(net.specs):
+        name = sp["name"]
         a = A[name]
         g = H(a["g"])                       # after the in-place ReLU backward: gradient of the pooled map
         assert np.all(g[H(a["y"]) <= 0] == 0), f"{name}: ReLU backward"
-        dx_ref, dw_ref = orc.layer_bwd(H(a["x"]), p64[name], g, H(a["idx"]).astype(np.uint8), cfg.R, None, cfg.mode,
-                                       1, 1, cfg.pool_group)
+        dx_ref, dw_ref = orc.layer_bwd(H(a["x"]), p64[name], g, H(a["idx"]).astype(np.uint8), sp["R"], None,
+                                       sp["mode"], 1, 1, sp["pool_group"])
         assert_close(H(net.grads[name]), dw_ref, f"{name} dW")
         if i == 0:
             continue
@@ -225,14 +231,15 @@ def test_unet_step_teacher_forced(cfg):
         assert_close(H(A[f"enc{lvl}b"]["g"]), masked(f"enc{lvl}b", ref), f"enc{lvl}b upstream gradient")
 
 
-def test_unet_step_end_to_end_loss_and_gradients():
+@pytest.mark.parametrize("cfg", [SMALL[0], SMALL[3]], ids=lambda c: c.name)
+def test_unet_step_end_to_end_loss_and_gradients(cfg):
     """The whole step against the oracle's whole step on one small stack: loss to the fp32 bar, the
     gradients in relative L2 norm (an arg-max that flips on a near-tie moves single elements, not the
     norm; the teacher-forced test above holds each call to the elementwise bar)."""
-    cfg = SMALL[0]
     net, params, images, labels = _run_stack(cfg)
     p64 = {k: v.astype(np.float64) for k, v in params.items()}
-    loss, grads, acts = uo.unet_step(images.astype(np.float64), labels, p64, cfg.R, cfg.mode, cfg.pool_group)
+    loss, grads, acts = uo.unet_step(images.astype(np.float64), labels, p64, cfg.R, cfg.mode, cfg.pool_group,
+                                     un.oracle_layer_spec(cfg))
     assert abs(float(net.loss.cpu()[0]) - loss) <= RTOL * abs(loss)
     for name, gref in grads.items():
         got = net.grads[name].cpu().numpy().astype(np.float64)
@@ -267,31 +274,39 @@ def _pts(seed, n, dims):
 
 
 @pytest.mark.timeout(900)
-@pytest.mark.parametrize("cfg", [un.C4, un.C5], ids=["C4", "C5"])
+@pytest.mark.parametrize("cfg", [un.C4, un.C5, un.P8], ids=["C4", "C5", "P8"])
 def test_unet_full_size_sampled(cfg):
-    """The benchmark's stack in the launch configuration bench.py times.  Every rotation-convolution call is
-    checked on sampled outputs the oracle computes one by one from the tensors that call read on the GPU
-    (forward values and arg-max, input gradient, weight gradient), every glue call against its definition,
-    plus the homogeneity identity <w, dW> = <y, g> per layer at full size."""
+    """The benchmark's stacks (and the paper's own block at 8 orientations) in the launch configuration
+    bench.py times.  Every rotation-convolution call is checked on sampled outputs the oracle computes one by
+    one from the tensors that call read on the GPU (forward values and arg-max, input gradient, weight
+    gradient), every glue call against its definition, plus the homogeneity identity <w, dW> = <y, g> per
+    layer at full size."""
     net, params, images, labels = _run_stack(cfg)
-    A, R, G = net.act, cfg.R, cfg.pool_group or cfg.R
+    A = net.act
     H = lambda t: t.detach().cpu().numpy()
     ns, npairs = 384, 4
-    for li, (name, ci, co, h, w) in enumerate(net.layers):
+    for li, sp in enumerate(net.specs):
+        name, ci, co, h, w, R, mode = sp["name"], sp["Cin"], sp["Cout"], sp["H"], sp["W"], sp["R"], sp["mode"]
+        G = sp["pool_group"] or R
+        ng = R // G
         a = A[name]
         x, y, idx, g = H(a["x"]), H(a["y"]), H(a["idx"]), H(a["g"])
         wb = params[name].astype(np.float64)
-        w_rot = orc.expand_bank(wb, R, None, cfg.mode)
+        w_rot = orc.expand_bank(wb, R, None, mode)
         pts = _pts(1000 + li, ns, (cfg.N, co, h, w))
         yr = orc.rotconv_fwd_at(x, w_rot, pts, 1, 1)
         ya = orc.rotconv_fwd_at(np.abs(x), np.abs(w_rot), pts, 1, 1)
-        best = yr.max(axis=1)
-        got_v = y[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3]].astype(np.float64)
-        got_i = idx[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3]].astype(np.int64)
-        rms = float(np.sqrt(np.mean(best ** 2)))
-        assert np.all(np.abs(got_v - np.maximum(best, 0)) <= RTOL * np.abs(best) + RTOL * rms), f"{name} fwd samples"
-        tau = 64.0 * np.finfo(np.float32).eps * ya.max(axis=1)
-        assert np.all(got_i < R) and np.all(yr[np.arange(ns), got_i] >= best - tau), f"{name} arg-max samples"
+        rms = float(np.sqrt(np.mean(yr.reshape(ns, G, ng).max(axis=1) ** 2)))
+        for grp in range(ng):
+            members = np.arange(grp, R, ng)
+            best = yr[:, members].max(axis=1)
+            chan = pts[:, 1] * ng + grp
+            got_v = y[pts[:, 0], chan, pts[:, 2], pts[:, 3]].astype(np.float64)
+            got_i = idx[pts[:, 0], chan, pts[:, 2], pts[:, 3]].astype(np.int64)
+            assert np.all(np.abs(got_v - np.maximum(best, 0)) <= RTOL * np.abs(best) + RTOL * rms), f"{name} fwd samples"
+            tau = 64.0 * np.finfo(np.float32).eps * ya[:, members].max(axis=1)
+            assert np.all(got_i % ng == grp) and np.all(got_i < R), f"{name} arg-max group"
+            assert np.all(yr[np.arange(ns), got_i] >= best - tau), f"{name} arg-max samples"
         # weight gradient: sampled (co, ci) slices, reduced through Eq. 16 by the oracle
         pairs = _pts(2000 + li, npairs, (co, ci))
         dwr = orc.rotconv_pool_bwd_weight_at(x, g, idx, pairs, R, 3, G, 1, 1)
@@ -300,7 +315,7 @@ def test_unet_full_size_sampled(cfg):
         for t, (o, c) in enumerate(pairs):
             full = np.zeros((R, 1, 1, 3, 3))
             full[:, 0, 0] = dwr[t]
-            ref_dw.append(orc.reduce_bank_grad(full, None, cfg.mode)[:, 0, 0])
+            ref_dw.append(orc.reduce_bank_grad(full, None, mode)[:, 0, 0])
             got_dw.append(dw[:, o, c])
         assert_close(np.array(got_dw), np.array(ref_dw), f"{name} dW samples")
         # homogeneity through max-pool and ReLU: <w, dW> = <y, g>
