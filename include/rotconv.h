@@ -81,7 +81,13 @@ typedef struct {
                                paper's rule; the benchmark configurations ask for it). */
   int32_t stride, pad;      /* stride >= 1, pad >= 0                                   */
   int32_t pool_group;       /* G, must divide R; 0 means R (one pooled map per filter) */
-  int32_t dtype;            /* rotconv_dtype; only ROTCONV_F32 is implemented          */
+  int32_t dtype;            /* rotconv_dtype of x, w, y, ypool, gpool, dy, dx.
+                               ROTCONV_BF16: those tensors hold bfloat16; products are
+                               accumulated in fp32, the arg-max is taken on the fp32
+                               values before y / ypool are rounded (nearest even) to
+                               bf16; dw stays fp32; idx stays uint8.  This build widens
+                               the bf16 tensors to fp32 in the workspace and runs the
+                               fp32 kernels on the copies (no bf16 matrix instructions). */
 } rotconv_desc;
 
 typedef struct rotconv_plan rotconv_plan; /* opaque */

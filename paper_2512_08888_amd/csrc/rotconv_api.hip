@@ -7,6 +7,7 @@
 #include <cstring>
 
 #include "rotconv_kernels.h"
+#include "rotconv_bf16.h"
 #include "rotconv_p4.h"
 
 namespace rotconv {
@@ -72,9 +73,10 @@ size_t fwd_fast_ws_bytes(const rotconv_plan* p) {
   return pack + extra;
 }
 
-int check_ws(const rotconv_plan* p, const void* ws, size_t ws_bytes) {
-  if (p->ws_bytes == 0) return ROTCONV_OK;
-  if (!ws || ws_bytes < p->ws_bytes) return ROTCONV_ERR_WORKSPACE;
+// the fp32 path's own need (a bf16 plan adds its staging areas in front, see carve())
+int check_ws_inner(const rotconv_plan* p, const void* ws, size_t ws_bytes) {
+  if (p->ws_inner == 0) return ROTCONV_OK;
+  if (!ws || ws_bytes < p->ws_inner) return ROTCONV_ERR_WORKSPACE;
   return ROTCONV_OK;
 }
 
@@ -98,7 +100,14 @@ int rotconv_plan_create(const rotconv_desc* desc, rotconv_plan** out) {
   if (p->fast[1]) p->ws_bytes = std::max(p->ws_bytes, p4_bwd_data_pack_floats(p) * sizeof(float));
   p->fast[2] = p4_bwd_weight_supported(p) ? 1 : 0;
   if (p->fast[2]) p->ws_bytes = std::max(p->ws_bytes, p4_bwd_weight_ws_floats(p) * sizeof(float));
-  p->ws_bytes = align256(p->ws_bytes);
+  p->ws_inner = p->ws_bytes = align256(p->ws_bytes);
+  const size_t hw_in = (size_t)p->d.H * p->d.W, hw_out = (size_t)p->Ho * p->Wo;
+  p->n_x = (size_t)p->d.N * p->d.Cin * hw_in;
+  p->n_w = (size_t)p->B * p->d.Cout * p->d.Cin * p->kk;
+  p->n_yp = (size_t)p->d.N * p->d.Cout * p->ng * hw_out;
+  p->n_yu = (size_t)p->d.N * p->d.Cout * p->d.R * hw_out;
+  if (p->d.dtype == ROTCONV_BF16)
+    p->ws_bytes = align256(p->n_x * 4) + align256(p->n_w * 4) + align256(p->n_yu * 4) + p->ws_inner;
   *out = p;
   return ROTCONV_OK;
 }
@@ -143,10 +152,12 @@ int rotconv_plan_expansion(const rotconv_plan* plan, float* E) {
   return ROTCONV_OK;
 }
 
-int rotconv_fwd(const rotconv_plan* plan, const void* x, const void* w, void* y, void* ws, size_t ws_bytes,
+}  // extern "C" (the fp32 implementations below have internal linkage)
+
+static int f32_rotconv_fwd(const rotconv_plan* plan, const void* x, const void* w, void* y, void* ws, size_t ws_bytes,
                 void* stream) {
   if (!plan || !x || !w || !y) return ROTCONV_ERR_NULL;
-  int rc = check_ws(plan, ws, ws_bytes);
+  int rc = check_ws_inner(plan, ws, ws_bytes);
   if (rc) return rc;
   rotconv_plan* p = const_cast<rotconv_plan*>(plan);
   if ((rc = ensure_device_tables(p))) return rc;
@@ -163,10 +174,10 @@ int rotconv_fwd(const rotconv_plan* plan, const void* x, const void* w, void* y,
   return finish();
 }
 
-int rotconv_bwd_data(const rotconv_plan* plan, const void* dy, const void* w, void* dx, void* ws, size_t ws_bytes,
+static int f32_rotconv_bwd_data(const rotconv_plan* plan, const void* dy, const void* w, void* dx, void* ws, size_t ws_bytes,
                      void* stream) {
   if (!plan || !dy || !w || !dx) return ROTCONV_ERR_NULL;
-  int rc = check_ws(plan, ws, ws_bytes);
+  int rc = check_ws_inner(plan, ws, ws_bytes);
   if (rc) return rc;
   rotconv_plan* p = const_cast<rotconv_plan*>(plan);
   if ((rc = ensure_device_tables(p))) return rc;
@@ -177,10 +188,10 @@ int rotconv_bwd_data(const rotconv_plan* plan, const void* dy, const void* w, vo
   return finish();
 }
 
-int rotconv_bwd_weight(const rotconv_plan* plan, const void* x, const void* dy, float* dw, void* ws, size_t ws_bytes,
+static int f32_rotconv_bwd_weight(const rotconv_plan* plan, const void* x, const void* dy, float* dw, void* ws, size_t ws_bytes,
                        void* stream) {
   if (!plan || !x || !dy || !dw) return ROTCONV_ERR_NULL;
-  int rc = check_ws(plan, ws, ws_bytes);
+  int rc = check_ws_inner(plan, ws, ws_bytes);
   if (rc) return rc;
   rotconv_plan* p = const_cast<rotconv_plan*>(plan);
   if ((rc = ensure_device_tables(p))) return rc;
@@ -190,24 +201,24 @@ int rotconv_bwd_weight(const rotconv_plan* plan, const void* x, const void* dy, 
   return finish();
 }
 
-int orient_maxpool_fwd(const rotconv_plan* plan, const void* y, void* ypool, uint8_t* idx, void* stream) {
+static int f32_orient_maxpool_fwd(const rotconv_plan* plan, const void* y, void* ypool, uint8_t* idx, void* stream) {
   if (!plan || !y || !ypool || !idx) return ROTCONV_ERR_NULL;
   launch_maxpool_fwd(plan, static_cast<const float*>(y), static_cast<float*>(ypool), idx,
                      static_cast<hipStream_t>(stream));
   return finish();
 }
 
-int orient_maxpool_bwd(const rotconv_plan* plan, const void* gpool, const uint8_t* idx, void* dy, void* stream) {
+static int f32_orient_maxpool_bwd(const rotconv_plan* plan, const void* gpool, const uint8_t* idx, void* dy, void* stream) {
   if (!plan || !gpool || !idx || !dy) return ROTCONV_ERR_NULL;
   launch_maxpool_bwd(plan, static_cast<const float*>(gpool), idx, static_cast<float*>(dy),
                      static_cast<hipStream_t>(stream));
   return finish();
 }
 
-int rotconv_pool_fwd(const rotconv_plan* plan, const void* x, const void* w, void* ypool, uint8_t* idx, void* ws,
+static int f32_rotconv_pool_fwd(const rotconv_plan* plan, const void* x, const void* w, void* ypool, uint8_t* idx, void* ws,
                      size_t ws_bytes, void* stream) {
   if (!plan || !x || !w || !ypool || !idx) return ROTCONV_ERR_NULL;
-  int rc = check_ws(plan, ws, ws_bytes);
+  int rc = check_ws_inner(plan, ws, ws_bytes);
   if (rc) return rc;
   rotconv_plan* p = const_cast<rotconv_plan*>(plan);
   if ((rc = ensure_device_tables(p))) return rc;
@@ -238,10 +249,10 @@ int rotconv_pool_fwd(const rotconv_plan* plan, const void* x, const void* w, voi
   return finish();
 }
 
-int rotconv_pool_bwd_data(const rotconv_plan* plan, const void* gpool, const uint8_t* idx, const void* w, void* dx,
+static int f32_rotconv_pool_bwd_data(const rotconv_plan* plan, const void* gpool, const uint8_t* idx, const void* w, void* dx,
                           void* ws, size_t ws_bytes, void* stream) {
   if (!plan || !gpool || !idx || !w || !dx) return ROTCONV_ERR_NULL;
-  int rc = check_ws(plan, ws, ws_bytes);
+  int rc = check_ws_inner(plan, ws, ws_bytes);
   if (rc) return rc;
   rotconv_plan* p = const_cast<rotconv_plan*>(plan);
   if ((rc = ensure_device_tables(p))) return rc;
@@ -258,10 +269,10 @@ int rotconv_pool_bwd_data(const rotconv_plan* plan, const void* gpool, const uin
   return finish();
 }
 
-int rotconv_pool_bwd_weight(const rotconv_plan* plan, const void* x, const void* gpool, const uint8_t* idx, float* dw,
+static int f32_rotconv_pool_bwd_weight(const rotconv_plan* plan, const void* x, const void* gpool, const uint8_t* idx, float* dw,
                             void* ws, size_t ws_bytes, void* stream) {
   if (!plan || !x || !gpool || !idx || !dw) return ROTCONV_ERR_NULL;
-  int rc = check_ws(plan, ws, ws_bytes);
+  int rc = check_ws_inner(plan, ws, ws_bytes);
   if (rc) return rc;
   rotconv_plan* p = const_cast<rotconv_plan*>(plan);
   if ((rc = ensure_device_tables(p))) return rc;
@@ -274,6 +285,134 @@ int rotconv_pool_bwd_weight(const rotconv_plan* plan, const void* x, const void*
   launch_bwd_weight_generic(p, static_cast<const float*>(x), nullptr, static_cast<const float*>(gpool), idx,
                             static_cast<float*>(ws), dw, st);
   return finish();
+}
+
+extern "C" {
+
+// ---- public entry points: fp32 plans go straight to the kernels; bf16 plans widen the bf16 tensors into
+// fp32 staging areas at the head of the workspace, run the same kernels behind them, and round the results to
+// bf16 once (the arg-max is taken on the fp32 values).  dW is fp32 in both cases. ----
+
+namespace {
+
+struct Stage {               // fp32 staging areas of a bf16 plan inside the caller's workspace
+  float *x, *w, *y;          // input-sized, weight-sized, (unpooled-)output-sized
+  void* inner;               // workspace handed on to the fp32 path
+  size_t inner_bytes;
+};
+
+Stage carve(const rotconv_plan* p, void* ws, size_t ws_bytes) {
+  Stage s;
+  char* c = static_cast<char*>(ws);
+  s.x = reinterpret_cast<float*>(c); c += align256(p->n_x * 4);
+  s.w = reinterpret_cast<float*>(c); c += align256(p->n_w * 4);
+  s.y = reinterpret_cast<float*>(c); c += align256(p->n_yu * 4);
+  s.inner = c;
+  s.inner_bytes = ws_bytes - (size_t)(c - static_cast<char*>(ws));
+  return s;
+}
+
+bool is_bf16(const rotconv_plan* p) { return p->d.dtype == ROTCONV_BF16; }
+const uint16_t* h16(const void* p) { return static_cast<const uint16_t*>(p); }
+
+}  // namespace
+
+int rotconv_fwd(const rotconv_plan* plan, const void* x, const void* w, void* y, void* ws, size_t ws_bytes,
+                void* stream) {
+  if (!plan || !x || !w || !y) return ROTCONV_ERR_NULL;
+  if (!is_bf16(plan)) return f32_rotconv_fwd(plan, x, w, y, ws, ws_bytes, stream);
+  if (!ws || ws_bytes < plan->ws_bytes) return ROTCONV_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const Stage s = carve(plan, ws, ws_bytes);
+  launch_widen(h16(x), s.x, plan->n_x, st);
+  launch_widen(h16(w), s.w, plan->n_w, st);
+  const int rc = f32_rotconv_fwd(plan, s.x, s.w, s.y, s.inner, s.inner_bytes, stream);
+  if (rc) return rc;
+  launch_narrow(s.y, static_cast<uint16_t*>(y), plan->n_yu, st);
+  return finish();
+}
+
+int rotconv_bwd_data(const rotconv_plan* plan, const void* dy, const void* w, void* dx, void* ws, size_t ws_bytes,
+                     void* stream) {
+  if (!plan || !dy || !w || !dx) return ROTCONV_ERR_NULL;
+  if (!is_bf16(plan)) return f32_rotconv_bwd_data(plan, dy, w, dx, ws, ws_bytes, stream);
+  if (!ws || ws_bytes < plan->ws_bytes) return ROTCONV_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const Stage s = carve(plan, ws, ws_bytes);
+  launch_widen(h16(dy), s.y, plan->n_yu, st);
+  launch_widen(h16(w), s.w, plan->n_w, st);
+  const int rc = f32_rotconv_bwd_data(plan, s.y, s.w, s.x, s.inner, s.inner_bytes, stream);
+  if (rc) return rc;
+  launch_narrow(s.x, static_cast<uint16_t*>(dx), plan->n_x, st);
+  return finish();
+}
+
+int rotconv_bwd_weight(const rotconv_plan* plan, const void* x, const void* dy, float* dw, void* ws, size_t ws_bytes,
+                       void* stream) {
+  if (!plan || !x || !dy || !dw) return ROTCONV_ERR_NULL;
+  if (!is_bf16(plan)) return f32_rotconv_bwd_weight(plan, x, dy, dw, ws, ws_bytes, stream);
+  if (!ws || ws_bytes < plan->ws_bytes) return ROTCONV_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const Stage s = carve(plan, ws, ws_bytes);
+  launch_widen(h16(x), s.x, plan->n_x, st);
+  launch_widen(h16(dy), s.y, plan->n_yu, st);
+  return f32_rotconv_bwd_weight(plan, s.x, s.y, dw, s.inner, s.inner_bytes, stream);
+}
+
+int orient_maxpool_fwd(const rotconv_plan* plan, const void* y, void* ypool, uint8_t* idx, void* stream) {
+  if (!plan || !y || !ypool || !idx) return ROTCONV_ERR_NULL;
+  if (!is_bf16(plan)) return f32_orient_maxpool_fwd(plan, y, ypool, idx, stream);
+  launch_maxpool_fwd_bf16(plan, h16(y), static_cast<uint16_t*>(ypool), idx, static_cast<hipStream_t>(stream));
+  return finish();
+}
+
+int orient_maxpool_bwd(const rotconv_plan* plan, const void* gpool, const uint8_t* idx, void* dy, void* stream) {
+  if (!plan || !gpool || !idx || !dy) return ROTCONV_ERR_NULL;
+  if (!is_bf16(plan)) return f32_orient_maxpool_bwd(plan, gpool, idx, dy, stream);
+  launch_maxpool_bwd_bf16(plan, h16(gpool), idx, static_cast<uint16_t*>(dy), static_cast<hipStream_t>(stream));
+  return finish();
+}
+
+int rotconv_pool_fwd(const rotconv_plan* plan, const void* x, const void* w, void* ypool, uint8_t* idx, void* ws,
+                     size_t ws_bytes, void* stream) {
+  if (!plan || !x || !w || !ypool || !idx) return ROTCONV_ERR_NULL;
+  if (!is_bf16(plan)) return f32_rotconv_pool_fwd(plan, x, w, ypool, idx, ws, ws_bytes, stream);
+  if (!ws || ws_bytes < plan->ws_bytes) return ROTCONV_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const Stage s = carve(plan, ws, ws_bytes);
+  launch_widen(h16(x), s.x, plan->n_x, st);
+  launch_widen(h16(w), s.w, plan->n_w, st);
+  const int rc = f32_rotconv_pool_fwd(plan, s.x, s.w, s.y, idx, s.inner, s.inner_bytes, stream);
+  if (rc) return rc;
+  launch_narrow(s.y, static_cast<uint16_t*>(ypool), plan->n_yp, st);
+  return finish();
+}
+
+int rotconv_pool_bwd_data(const rotconv_plan* plan, const void* gpool, const uint8_t* idx, const void* w, void* dx,
+                          void* ws, size_t ws_bytes, void* stream) {
+  if (!plan || !gpool || !idx || !w || !dx) return ROTCONV_ERR_NULL;
+  if (!is_bf16(plan)) return f32_rotconv_pool_bwd_data(plan, gpool, idx, w, dx, ws, ws_bytes, stream);
+  if (!ws || ws_bytes < plan->ws_bytes) return ROTCONV_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const Stage s = carve(plan, ws, ws_bytes);
+  launch_widen(h16(gpool), s.y, plan->n_yp, st);
+  launch_widen(h16(w), s.w, plan->n_w, st);
+  const int rc = f32_rotconv_pool_bwd_data(plan, s.y, idx, s.w, s.x, s.inner, s.inner_bytes, stream);
+  if (rc) return rc;
+  launch_narrow(s.x, static_cast<uint16_t*>(dx), plan->n_x, st);
+  return finish();
+}
+
+int rotconv_pool_bwd_weight(const rotconv_plan* plan, const void* x, const void* gpool, const uint8_t* idx, float* dw,
+                            void* ws, size_t ws_bytes, void* stream) {
+  if (!plan || !x || !gpool || !idx || !dw) return ROTCONV_ERR_NULL;
+  if (!is_bf16(plan)) return f32_rotconv_pool_bwd_weight(plan, x, gpool, idx, dw, ws, ws_bytes, stream);
+  if (!ws || ws_bytes < plan->ws_bytes) return ROTCONV_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const Stage s = carve(plan, ws, ws_bytes);
+  launch_widen(h16(x), s.x, plan->n_x, st);
+  launch_widen(h16(gpool), s.y, plan->n_yp, st);
+  return f32_rotconv_pool_bwd_weight(plan, s.x, s.y, idx, dw, s.inner, s.inner_bytes, stream);
 }
 
 const char* rotconv_status_string(int status) {

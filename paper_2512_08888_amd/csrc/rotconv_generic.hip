@@ -5,6 +5,7 @@
 // is the fallback and the path for tiny / odd shapes.
 #include <hip/hip_runtime.h>
 
+#include "rotconv_bf16.h"
 #include "rotconv_kernels.h"
 
 namespace rotconv {
@@ -106,35 +107,44 @@ __global__ __launch_bounds__(256) void k_fwd_generic(const float* __restrict__ x
 }
 
 // Eq. 10 on a materialised y.
-__global__ __launch_bounds__(256) void k_maxpool_fwd(const float* __restrict__ y, float* __restrict__ ypool,
+// T = float, or uint16_t holding bfloat16 (compared as fp32; the winner's bits are copied unchanged)
+template <typename T> __device__ __forceinline__ float as_f32(T v);
+template <> __device__ __forceinline__ float as_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ float as_f32<uint16_t>(uint16_t v) { return bf16_to_f32(v); }
+
+template <typename T>
+__global__ __launch_bounds__(256) void k_maxpool_fwd(const T* __restrict__ y, T* __restrict__ ypool,
                                                      uint8_t* __restrict__ idx, Geom g) {
   const int P = g.Ho * g.Wo;
   const int p = blockIdx.x * 256 + threadIdx.x;
   if (p >= P) return;
   const int chan = blockIdx.y, n = blockIdx.z;
   const int co = chan / g.ng, grp = chan % g.ng;
-  const float* yb = y + ((size_t)n * g.Cout + co) * g.R * P + p;
-  float best = yb[(size_t)grp * P];
+  const T* yb = y + ((size_t)n * g.Cout + co) * g.R * P + p;
+  T best_raw = yb[(size_t)grp * P];
+  float best = as_f32<T>(best_raw);
   int best_r = grp;
   for (int r = grp + g.ng; r < g.R; r += g.ng) {
-    const float v = yb[(size_t)r * P];
-    if (v > best) { best = v; best_r = r; }
+    const T raw = yb[(size_t)r * P];
+    const float v = as_f32<T>(raw);
+    if (v > best) { best = v; best_raw = raw; best_r = r; }
   }
   const size_t q = ((size_t)n * g.Cout * g.ng + chan) * P + p;
-  ypool[q] = best;
+  ypool[q] = best_raw;
   idx[q] = (uint8_t)best_r;
 }
 
 // Eq. 12.
-__global__ __launch_bounds__(256) void k_maxpool_bwd(const float* __restrict__ gpool, const uint8_t* __restrict__ idx,
-                                                     float* __restrict__ dy, Geom g) {
+template <typename T>
+__global__ __launch_bounds__(256) void k_maxpool_bwd(const T* __restrict__ gpool, const uint8_t* __restrict__ idx,
+                                                     T* __restrict__ dy, Geom g) {
   const int P = g.Ho * g.Wo;
   const int p = blockIdx.x * 256 + threadIdx.x;
   if (p >= P) return;
   const int chan = blockIdx.y, n = blockIdx.z;   // chan = co*R + r
   const int co = chan / g.R, r = chan % g.R;
   const size_t q = (((size_t)n * g.Cout + co) * g.ng + r % g.ng) * P + p;
-  dy[((size_t)n * g.Cout * g.R + chan) * P + p] = (idx[q] == r) ? gpool[q] : 0.f;
+  dy[((size_t)n * g.Cout * g.R + chan) * P + p] = (idx[q] == r) ? gpool[q] : T(0);
 }
 
 // Eq. 13 + 15 (with Eq. 12 folded in when FUSED: only the winning orientation of
@@ -313,13 +323,26 @@ void launch_pool_fwd_generic(const rotconv_plan* p, const float* x, const float*
 void launch_maxpool_fwd(const rotconv_plan* p, const float* y, float* ypool, uint8_t* idx, hipStream_t st) {
   const Geom g = make_geom(p);
   dim3 grid((g.Ho * g.Wo + 255) / 256, g.Cout * g.ng, g.N);
-  hipLaunchKernelGGL(k_maxpool_fwd, grid, dim3(256), 0, st, y, ypool, idx, g);
+  hipLaunchKernelGGL(k_maxpool_fwd<float>, grid, dim3(256), 0, st, y, ypool, idx, g);
+}
+
+void launch_maxpool_fwd_bf16(const rotconv_plan* p, const uint16_t* y, uint16_t* ypool, uint8_t* idx, hipStream_t st) {
+  const Geom g = make_geom(p);
+  dim3 grid((g.Ho * g.Wo + 255) / 256, g.Cout * g.ng, g.N);
+  hipLaunchKernelGGL(k_maxpool_fwd<uint16_t>, grid, dim3(256), 0, st, y, ypool, idx, g);
 }
 
 void launch_maxpool_bwd(const rotconv_plan* p, const float* gpool, const uint8_t* idx, float* dy, hipStream_t st) {
   const Geom g = make_geom(p);
   dim3 grid((g.Ho * g.Wo + 255) / 256, g.Cout * g.R, g.N);
-  hipLaunchKernelGGL(k_maxpool_bwd, grid, dim3(256), 0, st, gpool, idx, dy, g);
+  hipLaunchKernelGGL(k_maxpool_bwd<float>, grid, dim3(256), 0, st, gpool, idx, dy, g);
+}
+
+void launch_maxpool_bwd_bf16(const rotconv_plan* p, const uint16_t* gpool, const uint8_t* idx, uint16_t* dy,
+                             hipStream_t st) {
+  const Geom g = make_geom(p);
+  dim3 grid((g.Ho * g.Wo + 255) / 256, g.Cout * g.R, g.N);
+  hipLaunchKernelGGL(k_maxpool_bwd<uint16_t>, grid, dim3(256), 0, st, gpool, idx, dy, g);
 }
 
 void launch_bwd_data_generic(const rotconv_plan* p, const float* dy, const float* wexp, float* dx, hipStream_t st) {

@@ -61,7 +61,9 @@ struct rotconv_plan {
   rotconv::HostTables host;
   std::vector<int32_t> rot_of;  // [Q*4]
   rotconv::DeviceTables dev;    // uploaded on first launch
-  size_t ws_bytes = 0;
+  size_t ws_bytes = 0;          // what the caller must provide
+  size_t ws_inner = 0;          // what the fp32 kernels need (== ws_bytes for fp32 plans)
+  size_t n_x = 0, n_w = 0, n_yp = 0, n_yu = 0;   // elements of input, base weights, pooled and unpooled output
   // kernel selection per pass (0 fwd, 1 bwd_data, 2 bwd_weight)
   int fast[3] = {0, 0, 0};
   int bwdw_splits = 1;          // pixel splits of the generic weight-gradient kernel

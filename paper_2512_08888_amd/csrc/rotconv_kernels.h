@@ -31,5 +31,8 @@ void launch_bwd_weight_generic(const rotconv_plan* p, const float* x, const floa
                                const uint8_t* idx, float* partial, float* dw, hipStream_t st);
 void launch_maxpool_fwd(const rotconv_plan* p, const float* y, float* ypool, uint8_t* idx, hipStream_t st);
 void launch_maxpool_bwd(const rotconv_plan* p, const float* gpool, const uint8_t* idx, float* dy, hipStream_t st);
+void launch_maxpool_fwd_bf16(const rotconv_plan* p, const uint16_t* y, uint16_t* ypool, uint8_t* idx, hipStream_t st);
+void launch_maxpool_bwd_bf16(const rotconv_plan* p, const uint16_t* gpool, const uint8_t* idx, uint16_t* dy,
+                             hipStream_t st);
 
 }  // namespace rotconv

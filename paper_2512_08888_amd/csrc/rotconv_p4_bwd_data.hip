@@ -328,7 +328,7 @@ __global__ __launch_bounds__(256) void k_p4_pack_bwd(const float* __restrict__ w
 
 bool p4_bwd_data_supported(const rotconv_plan* p) {
   const rotconv_desc& d = p->d;
-  if (d.k != 3 || d.stride != 1 || d.pad != 1 || d.dtype != ROTCONV_F32) return false;
+  if (d.k != 3 || d.stride != 1 || d.pad != 1) return false;   // bf16 plans run these kernels on widened copies
   if (d.W & 1) return false;
   return p4_fwd_pool_mode(p) != kOutUnpooled;  // every bank inside one pool group
 }

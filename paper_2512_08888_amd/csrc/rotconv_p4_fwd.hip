@@ -452,7 +452,7 @@ bool needs_stream(int Cin) {
 
 bool p4_fwd_supported(const rotconv_plan* p) {
   const rotconv_desc& d = p->d;
-  if (d.k != 3 || d.stride != 1 || d.pad != 1 || d.dtype != ROTCONV_F32) return false;
+  if (d.k != 3 || d.stride != 1 || d.pad != 1) return false;   // bf16 plans run these kernels on widened copies
   if (d.W & 1) return false;
   if (d.W > 256 && (d.W & 31)) return false;          // segmented rows need whole-lane validity
   if (needs_stream(d.Cin) && (d.W & 31)) return false;  // the streaming variant is built for W % 32 == 0

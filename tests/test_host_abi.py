@@ -71,7 +71,7 @@ def _create(**kw):
     (dict(R=2, angles_deg=[0.0, 360.0]), rc.ERR_ANGLES),           # outside [0,360)
     (dict(R=2, angles_deg=[90.0, 0.0]), rc.ERR_ANGLES),            # not ascending
     (dict(R=2, angles_deg=[90.0, 90.0]), rc.ERR_ANGLES),
-    (dict(mode=7), rc.ERR_UNSUPPORTED), (dict(dtype=rc.BF16), rc.ERR_UNSUPPORTED),
+    (dict(mode=7), rc.ERR_UNSUPPORTED), (dict(dtype=2), rc.ERR_UNSUPPORTED),
 ])
 def test_descriptor_errors(kw, code):
     with pytest.raises(rc.RotconvError) as e:
@@ -101,6 +101,13 @@ def test_out_shape_and_workspace():
     p = _create(N=2, H=9, W=7, stride=2, pad=1, R=4, pool_group=2)
     assert (p.Ho, p.Wo, p.Cunpooled, p.Cpooled) == (5, 4, 12, 6)
     assert p.workspace_bytes >= 4 * 4 * 3 * 2 * 9
+
+
+def test_bf16_plan_adds_staging_to_the_workspace():
+    a, b = _create(N=2, Cin=5, H=8, W=8, Cout=3), _create(N=2, Cin=5, H=8, W=8, Cout=3, dtype=rc.BF16)
+    staging = 4 * (2 * 5 * 64 + 3 * 5 * 9 + 2 * 3 * 4 * 64)          # x, w, unpooled y in fp32
+    assert b.workspace_bytes >= a.workspace_bytes + staging
+    assert (b.Ho, b.Wo, b.Cpooled) == (a.Ho, a.Wo, a.Cpooled)
 
 
 def test_orientation_structure():
