@@ -64,7 +64,7 @@ def cpu_baseline(cfg, Q):
     }
 
 
-def bench_unet(name, steps, warmup):
+def bench_unet(name, steps, warmup, dtype="f32"):
     """ms per training step of the UNet-shaped stack (benchmark configurations 4 and 5; P4 / P8 / P16: the
     paper's own block, rotation convolution then standard convolution, at 4 / 8 / 16 orientations; fp32), whole
     step timed between synchronisations; then one more step with an event pair around every library
@@ -73,7 +73,7 @@ def bench_unet(name, steps, warmup):
     from paper_2512_08888_amd import unet as un
 
     cfg = un.UNET_CONFIGS[name]
-    net = un.UNet(cfg, un.make_params(cfg))
+    net = un.UNet(cfg, un.make_params(cfg), dtype=dtype)
     net.load_batch(*un.make_batch(cfg))
     for _ in range(warmup):
         net.step()
@@ -98,7 +98,9 @@ def bench_unet(name, steps, warmup):
     loss = float(net.loss.cpu()[0])
     out = {
         "workload": f"{cfg.name}: UNet-shaped stack, N={cfg.N} {cfg.H}x{cfg.W} widths={list(cfg.widths)} "
-                    f"classes={cfg.classes} R={cfg.R} {cfg.mode} block={cfg.block}, one training step (fwd+bwd), fp32",
+                    f"classes={cfg.classes} R={cfg.R} {cfg.mode} block={cfg.block}, one training step (fwd+bwd), "
+                    + ("fp32" if dtype == "f32" else "bf16 parameters / activations, fp32 accumulation, fp32 dW and loss"),
+        "dtype": dtype,
         "ms_per_step": ms, "steps": steps, "warmup": warmup, "loss": loss,
         "rotconv_flops_algorithmic": alg, "rotconv_flops_dense_equivalent": dense,
         "rotconv_ms": rot_ms, "glue_ms": sum(by_call.values()) - rot_ms,
@@ -142,11 +144,11 @@ def main_unet(args):
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    r = bench_unet(args.workload, args.steps, args.warmup)
+    r = bench_unet(args.workload, args.steps, args.warmup, args.dtype)
     out = {
         "metric": "unet_train_step_ms", "value": r["ms_per_step"], "unit": "ms", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": r["ms_per_step"], "higher_is_better": False, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f32", "data": "synthetic", "config": r,
+        "vs_baseline": None, "dtype": args.dtype, "data": "synthetic", "config": r,
         "roofline": {"bound": "mfma",
                      "kernel": "all rotation-convolution calls of the step (fwd, bwd_data, bwd_weight; 18 layers)",
                      "achieved": r["rotconv_tflops_algorithmic"], "peak": PEAK_FP32_TFLOPS, "unit": "TFLOP/s",
@@ -163,6 +165,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4", "C5", "P4", "P8", "P16"])
+    ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"],
+                    help="storage type of activations and weights (accumulation is fp32 either way)")
     ap.add_argument("--no-unet", action="store_true", help="skip the UNet-shaped steps appended to the default line")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -262,6 +266,7 @@ def main():
         # the second half of the headline metric: ms per UNet-shaped training step at R=4 and R=16
         del x, w, g, yp, idx, dx, dw
         out["unet_train_step"] = {n: bench_unet(n, 5, 2) for n in ("C4", "C5")}
+        out["unet_train_step"]["C5_bf16"] = bench_unet("C5", 5, 2, "bf16")
     print(json.dumps(out), flush=True)
 
 

@@ -63,6 +63,37 @@ int glue_conv1x1_bwd_weight(const float* x, const float* dy, float* dw, int N, i
 int glue_softmax_ce(const float* logits, const int32_t* labels, float* loss, float* dlogits, int N, int K, size_t P,
                     void* ws, size_t ws_bytes, void* stream);
 
+/* ---- bfloat16 twins ------------------------------------------------------------------------------
+ * Same operations and argument meanings with activations, their gradients and the weights handed to
+ * the forward / input-gradient calls stored as bfloat16 (uint16_t holding the upper half of the fp32
+ * bit pattern): configuration "bf16 weights / activations, fp32 accumulation".  Every value is widened
+ * exactly, all arithmetic and accumulation is fp32, and each bf16 output element is rounded once, to
+ * nearest-even.  Weight gradients (dw) and the loss stay fp32; workspace sizes are those of the fp32
+ * calls. */
+int glue_relu_fwd_bf16(const uint16_t* x, uint16_t* y, size_t n, void* stream);
+int glue_relu_bwd_bf16(const uint16_t* y, const uint16_t* dy, uint16_t* dx, size_t n, void* stream);
+int glue_maxpool2_fwd_bf16(const uint16_t* x, uint16_t* y, uint8_t* idx, int N, int C, int H, int W, void* stream);
+int glue_maxpool2_bwd_bf16(const uint16_t* dy, const uint8_t* idx, uint16_t* dx, int N, int C, int H, int W,
+                           int accumulate, void* stream);
+int glue_upconv2_fwd_bf16(const uint16_t* x, const uint16_t* w, uint16_t* y, int N, int Cin, int Cout, int H, int W,
+                          void* stream);
+int glue_upconv2_bwd_data_bf16(const uint16_t* dy, const uint16_t* w, uint16_t* dx, int N, int Cin, int Cout, int H,
+                               int W, void* stream);
+int glue_upconv2_bwd_weight_bf16(const uint16_t* x, const uint16_t* dy, float* dw, int N, int Cin, int Cout, int H,
+                                 int W, void* ws, size_t ws_bytes, void* stream);
+int glue_concat2_bf16(const uint16_t* a, const uint16_t* b, uint16_t* out, int N, int Ca, int Cb, size_t P,
+                      void* stream);
+int glue_split2_bf16(const uint16_t* dcat, uint16_t* da, uint16_t* db, int N, int Ca, int Cb, size_t P,
+                     int accumulate_a, void* stream);
+int glue_conv1x1_fwd_bf16(const uint16_t* x, const uint16_t* w, uint16_t* y, int N, int Cin, int Cout, size_t P,
+                          void* stream);
+int glue_conv1x1_bwd_data_bf16(const uint16_t* dy, const uint16_t* w, uint16_t* dx, int N, int Cin, int Cout, size_t P,
+                               void* stream);
+int glue_conv1x1_bwd_weight_bf16(const uint16_t* x, const uint16_t* dy, float* dw, int N, int Cin, int Cout, size_t P,
+                                 void* ws, size_t ws_bytes, void* stream);
+int glue_softmax_ce_bf16(const uint16_t* logits, const int32_t* labels, float* loss, uint16_t* dlogits, int N, int K,
+                         size_t P, void* ws, size_t ws_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

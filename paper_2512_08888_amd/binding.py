@@ -34,6 +34,8 @@ GLUE_EXPORTS = [
     "glue_conv1x1_workspace_bytes", "glue_conv1x1_fwd", "glue_conv1x1_bwd_data", "glue_conv1x1_bwd_weight",
     "glue_softmax_ce",
 ]
+# the bfloat16 twins: every call above except the two workspace-size queries
+GLUE_EXPORTS += [n + "_bf16" for n in GLUE_EXPORTS if not n.endswith("_workspace_bytes")]
 
 
 class Desc(ctypes.Structure):
@@ -102,6 +104,9 @@ def lib():
         L.glue_conv1x1_bwd_data.argtypes = [vp, vp, vp, ci, ci, ci, sz, vp]
         L.glue_conv1x1_bwd_weight.argtypes = [vp, vp, vp, ci, ci, ci, sz, vp, sz, vp]
         L.glue_softmax_ce.argtypes = [vp, vp, vp, vp, ci, ci, sz, vp, sz, vp]
+        for name in GLUE_EXPORTS:
+            if name.endswith("_bf16"):
+                getattr(L, name).argtypes = getattr(L, name[:-5]).argtypes
         _lib = L
     return _lib
 
@@ -255,22 +260,35 @@ def _nbytes(t):
     return 0 if t is None else t.numel() * t.element_size()
 
 
+def _glue(name, *tensors):
+    """The library entry point for the tensors' storage type: `name` for fp32, `name`_bf16 for bfloat16
+    (all activation tensors of one call share the type)."""
+    import torch
+
+    kinds = {t.dtype for t in tensors}
+    if kinds == {torch.bfloat16}:
+        return getattr(lib(), name + "_bf16")
+    if kinds == {torch.float32}:
+        return getattr(lib(), name)
+    raise TypeError(f"{name}: tensors must be all float32 or all bfloat16, got {sorted(map(str, kinds))}")
+
+
 def glue_relu_fwd(x, y):
-    _check(lib().glue_relu_fwd(_ptr(x), _ptr(y), x.numel(), _stream()), "glue_relu_fwd")
+    _check(_glue("glue_relu_fwd", x, y)(_ptr(x), _ptr(y), x.numel(), _stream()), "glue_relu_fwd")
 
 
 def glue_relu_bwd(y, dy, dx):
-    _check(lib().glue_relu_bwd(_ptr(y), _ptr(dy), _ptr(dx), y.numel(), _stream()), "glue_relu_bwd")
+    _check(_glue("glue_relu_bwd", y, dy, dx)(_ptr(y), _ptr(dy), _ptr(dx), y.numel(), _stream()), "glue_relu_bwd")
 
 
 def glue_maxpool2_fwd(x, y, idx):
     N, C, H, W = x.shape
-    _check(lib().glue_maxpool2_fwd(_ptr(x), _ptr(y), _ptr(idx), N, C, H, W, _stream()), "glue_maxpool2_fwd")
+    _check(_glue("glue_maxpool2_fwd", x, y)(_ptr(x), _ptr(y), _ptr(idx), N, C, H, W, _stream()), "glue_maxpool2_fwd")
 
 
 def glue_maxpool2_bwd(dy, idx, dx, accumulate=False):
     N, C, H, W = dx.shape
-    _check(lib().glue_maxpool2_bwd(_ptr(dy), _ptr(idx), _ptr(dx), N, C, H, W, int(bool(accumulate)), _stream()),
+    _check(_glue("glue_maxpool2_bwd", dy, dx)(_ptr(dy), _ptr(idx), _ptr(dx), N, C, H, W, int(bool(accumulate)), _stream()),
            "glue_maxpool2_bwd")
 
 
@@ -280,31 +298,31 @@ def glue_upconv2_workspace_bytes(N, Cin, Cout, H, W):
 
 def glue_upconv2_fwd(x, w, y):
     N, Cin, H, W = x.shape
-    _check(lib().glue_upconv2_fwd(_ptr(x), _ptr(w), _ptr(y), N, Cin, w.shape[1], H, W, _stream()), "glue_upconv2_fwd")
+    _check(_glue("glue_upconv2_fwd", x, w, y)(_ptr(x), _ptr(w), _ptr(y), N, Cin, w.shape[1], H, W, _stream()), "glue_upconv2_fwd")
 
 
 def glue_upconv2_bwd_data(dy, w, dx):
     N, Cin, H, W = dx.shape
-    _check(lib().glue_upconv2_bwd_data(_ptr(dy), _ptr(w), _ptr(dx), N, Cin, w.shape[1], H, W, _stream()),
+    _check(_glue("glue_upconv2_bwd_data", dy, w, dx)(_ptr(dy), _ptr(w), _ptr(dx), N, Cin, w.shape[1], H, W, _stream()),
            "glue_upconv2_bwd_data")
 
 
 def glue_upconv2_bwd_weight(x, dy, dw, ws):
     N, Cin, H, W = x.shape
-    _check(lib().glue_upconv2_bwd_weight(_ptr(x), _ptr(dy), _ptr(dw), N, Cin, dw.shape[1], H, W, _ptr(ws), _nbytes(ws),
+    _check(_glue("glue_upconv2_bwd_weight", x, dy)(_ptr(x), _ptr(dy), _ptr(dw), N, Cin, dw.shape[1], H, W, _ptr(ws), _nbytes(ws),
                                          _stream()), "glue_upconv2_bwd_weight")
 
 
 def glue_concat2(a, b, out):
     N, Ca = a.shape[0], a.shape[1]
     P = a.numel() // (N * Ca)
-    _check(lib().glue_concat2(_ptr(a), _ptr(b), _ptr(out), N, Ca, b.shape[1], P, _stream()), "glue_concat2")
+    _check(_glue("glue_concat2", a, b, out)(_ptr(a), _ptr(b), _ptr(out), N, Ca, b.shape[1], P, _stream()), "glue_concat2")
 
 
 def glue_split2(dcat, da, db, accumulate_a=False):
     N, Ca = da.shape[0], da.shape[1]
     P = da.numel() // (N * Ca)
-    _check(lib().glue_split2(_ptr(dcat), _ptr(da), _ptr(db), N, Ca, db.shape[1], P, int(bool(accumulate_a)), _stream()),
+    _check(_glue("glue_split2", dcat, da, db)(_ptr(dcat), _ptr(da), _ptr(db), N, Ca, db.shape[1], P, int(bool(accumulate_a)), _stream()),
            "glue_split2")
 
 
@@ -315,25 +333,25 @@ def glue_conv1x1_workspace_bytes(N, Cin, Cout, P):
 def glue_conv1x1_fwd(x, w, y):
     N, Cin = x.shape[0], x.shape[1]
     P = x.numel() // (N * Cin)
-    _check(lib().glue_conv1x1_fwd(_ptr(x), _ptr(w), _ptr(y), N, Cin, w.shape[0], P, _stream()), "glue_conv1x1_fwd")
+    _check(_glue("glue_conv1x1_fwd", x, w, y)(_ptr(x), _ptr(w), _ptr(y), N, Cin, w.shape[0], P, _stream()), "glue_conv1x1_fwd")
 
 
 def glue_conv1x1_bwd_data(dy, w, dx):
     N, Cin = dx.shape[0], dx.shape[1]
     P = dx.numel() // (N * Cin)
-    _check(lib().glue_conv1x1_bwd_data(_ptr(dy), _ptr(w), _ptr(dx), N, Cin, w.shape[0], P, _stream()),
+    _check(_glue("glue_conv1x1_bwd_data", dy, w, dx)(_ptr(dy), _ptr(w), _ptr(dx), N, Cin, w.shape[0], P, _stream()),
            "glue_conv1x1_bwd_data")
 
 
 def glue_conv1x1_bwd_weight(x, dy, dw, ws):
     N, Cin = x.shape[0], x.shape[1]
     P = x.numel() // (N * Cin)
-    _check(lib().glue_conv1x1_bwd_weight(_ptr(x), _ptr(dy), _ptr(dw), N, Cin, dw.shape[0], P, _ptr(ws), _nbytes(ws),
+    _check(_glue("glue_conv1x1_bwd_weight", x, dy)(_ptr(x), _ptr(dy), _ptr(dw), N, Cin, dw.shape[0], P, _ptr(ws), _nbytes(ws),
                                          _stream()), "glue_conv1x1_bwd_weight")
 
 
 def glue_softmax_ce(logits, labels, loss, dlogits, ws):
     N, K = logits.shape[0], logits.shape[1]
     P = logits.numel() // (N * K)
-    _check(lib().glue_softmax_ce(_ptr(logits), _ptr(labels), _ptr(loss), _ptr(dlogits), N, K, P, _ptr(ws), _nbytes(ws),
+    _check(_glue("glue_softmax_ce", logits, dlogits)(_ptr(logits), _ptr(labels), _ptr(loss), _ptr(dlogits), N, K, P, _ptr(ws), _nbytes(ws),
                                  _stream()), "glue_softmax_ce")

@@ -7,6 +7,7 @@
 #include <hip/hip_runtime.h>
 
 #include "glue_internal.h"
+#include "rotconv_bf16.h"
 
 namespace rotconv {
 namespace {
@@ -24,8 +25,8 @@ __device__ __forceinline__ size_t shuffled(int r, int p, int H, int W) {
 
 // A element (m, k): transA ? A[k*lda + m] : A[m*lda + k];  B element (k, n): transB ? B[n*ldb + k] : B[k*ldb + n]
 template <bool TA, bool TB>
-__global__ __launch_bounds__(NT) void k_gemm(const float* __restrict__ A, const float* __restrict__ B,
-                                            float* __restrict__ C, GemmArgs p) {
+__global__ __launch_bounds__(NT) void k_gemm(const void* __restrict__ A, const void* __restrict__ B,
+                                            void* __restrict__ C, GemmArgs p) {
   __shared__ float As[2][BK][PITCH];
   __shared__ float Bs[2][BK][PITCH];
   const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64, lg = lane / 16, lc = lane % 16;
@@ -34,9 +35,14 @@ __global__ __launch_bounds__(NT) void k_gemm(const float* __restrict__ A, const 
   const int batch = z / p.splitk, ks = z % p.splitk;
   const int kchunk = ((p.K + p.splitk - 1) / p.splitk + BK - 1) / BK * BK;
   const int kbeg = ks * kchunk, kend = min(p.K, kbeg + kchunk);
-  const float* Ab = A + (size_t)batch * p.strideA;
-  const float* Bb = B + (size_t)batch * p.strideB;
-  float* Cb = C + (size_t)z * p.strideC;
+  const size_t Abase = (size_t)batch * p.strideA, Bbase = (size_t)batch * p.strideB, Cbase = (size_t)z * p.strideC;
+  // element access in the operand's storage type (wave-uniform choice)
+  auto ldA = [&](size_t off) {
+    return p.bf16A ? bf16_to_f32(static_cast<const uint16_t*>(A)[Abase + off]) : static_cast<const float*>(A)[Abase + off];
+  };
+  auto ldB = [&](size_t off) {
+    return p.bf16B ? bf16_to_f32(static_cast<const uint16_t*>(B)[Bbase + off]) : static_cast<const float*>(B)[Bbase + off];
+  };
 
   float ra[8], rb[8];
   auto gload = [&](int k0) {
@@ -47,14 +53,14 @@ __global__ __launch_bounds__(NT) void k_gemm(const float* __restrict__ A, const 
       const int gm = m0 + m, gk = k0 + k;
       const bool ok = gm < p.M && gk < kend;
       const size_t off = TA ? (size_t)gk * p.lda + gm : (size_t)gm * p.lda + gk;
-      ra[i] = ok ? Ab[off] : 0.f;
+      ra[i] = ok ? ldA(off) : 0.f;
       int n, kb;
       if (TB) { kb = tid % 16; n = tid / 16 + 16 * i; } else { n = tid % 128; kb = tid / 128 + 2 * i; }
       const int gn = n0 + n, gkb = k0 + kb;
       const bool okb = gn < p.N && gkb < kend;
       size_t offb = TB ? (size_t)gn * p.ldb + gkb : (size_t)gkb * p.ldb + gn;
       if (p.shufB) offb = shuffled(TB ? gn : gkb, TB ? gkb : gn, p.shufH, p.shufW);
-      rb[i] = okb ? Bb[offb] : 0.f;
+      rb[i] = okb ? ldB(offb) : 0.f;
     }
   };
   auto sstore = [&](int buf) {
@@ -109,8 +115,11 @@ __global__ __launch_bounds__(NT) void k_gemm(const float* __restrict__ A, const 
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const int gm = m0 + wm + 16 * i + 4 * lg + r, gn = n0 + wn + 16 * j + lc;
-        if (gm < p.M && gn < p.N)
-          Cb[p.shufC ? shuffled(gm, gn, p.shufH, p.shufW) : (size_t)gm * p.ldc + gn] = acc[i][j][r];
+        if (gm < p.M && gn < p.N) {
+          const size_t off = Cbase + (p.shufC ? shuffled(gm, gn, p.shufH, p.shufW) : (size_t)gm * p.ldc + gn);
+          if (p.bf16C) static_cast<uint16_t*>(C)[off] = f32_to_bf16(acc[i][j][r]);
+          else static_cast<float*>(C)[off] = acc[i][j][r];
+        }
       }
 }
 
@@ -126,7 +135,7 @@ __global__ __launch_bounds__(256) void k_sum_parts(const float* __restrict__ par
 
 }  // namespace
 
-void launch_gemm(const GemmArgs& a, const float* A, const float* B, float* C, hipStream_t st) {
+void launch_gemm(const GemmArgs& a, const void* A, const void* B, void* C, hipStream_t st) {
   dim3 grid((a.M + BM - 1) / BM, (a.N + BN - 1) / BN, a.batch * a.splitk);
   if (a.transA && a.transB) hipLaunchKernelGGL((k_gemm<true, true>), grid, dim3(NT), 0, st, A, B, C, a);
   else if (a.transA) hipLaunchKernelGGL((k_gemm<true, false>), grid, dim3(NT), 0, st, A, B, C, a);

@@ -17,9 +17,10 @@ struct GemmArgs {
   size_t strideC;           // per (batch, split)
   int shufB, shufC;         // B is read / C is written through the 2x2 pixel-shuffle map
   int shufH, shufW;         // input extent (H, W) of that map
+  int bf16A, bf16B, bf16C;  // the operand holds bfloat16 (widened on load / rounded on store) instead of fp32
 };
 
-void launch_gemm(const GemmArgs& a, const float* A, const float* B, float* C, hipStream_t st);
+void launch_gemm(const GemmArgs& a, const void* A, const void* B, void* C, hipStream_t st);
 void launch_sum_parts(const float* part, float* out, size_t n, int nparts, size_t stride, hipStream_t st);
 
 }  // namespace rotconv

@@ -8,6 +8,7 @@
 
 #include "glue_internal.h"
 #include "rotconv.h"
+#include "rotconv_bf16.h"
 #include "unetglue.h"
 
 namespace rotconv {
@@ -17,82 +18,147 @@ int finish() { return hipGetLastError() == hipSuccess ? ROTCONV_OK : ROTCONV_ERR
 unsigned blocks_for(size_t n) { return (unsigned)std::max<size_t>(1, std::min<size_t>((n + 255) / 256, 1u << 20)); }
 
 typedef float f4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u4 __attribute__((ext_vector_type(4)));
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
-// Streaming kernels: 16 bytes per lane and access when the shapes and pointers allow (V = 4), else scalar (V = 1).
-template <int V>
-__global__ __launch_bounds__(256) void k_relu_fwd(const float* __restrict__ x, float* __restrict__ y, size_t n) {
+// Element access for the two storage types: fp32, and bfloat16 kept in uint16_t (arithmetic is fp32 in
+// both cases; a bf16 result is rounded once, to nearest even).  V = elements of one 16-byte access.
+template <typename T> struct Elt;
+template <> struct Elt<float> {
+  static constexpr int V = 4;
+  static __device__ __forceinline__ float ld(const float* p) { return *p; }
+  static __device__ __forceinline__ void st(float* p, float v) { *p = v; }
+  static __device__ __forceinline__ void ldv(const float* p, float* v) {
+    const f4 a = *reinterpret_cast<const f4*>(p);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) v[k] = a[k];
+  }
+  static __device__ __forceinline__ void stv(float* p, const float* v) {
+    *reinterpret_cast<f4*>(p) = f4{v[0], v[1], v[2], v[3]};
+  }
+  static __device__ __forceinline__ void ldh(const float* p, float* v) {   // half a vector: 8 bytes
+    const float2 a = *reinterpret_cast<const float2*>(p);
+    v[0] = a.x; v[1] = a.y;
+  }
+  static __device__ __forceinline__ void sth(float* p, const float* v) {
+    *reinterpret_cast<float2*>(p) = make_float2(v[0], v[1]);
+  }
+};
+template <> struct Elt<uint16_t> {
+  static constexpr int V = 8;
+  static __device__ __forceinline__ float ld(const uint16_t* p) { return bf16_to_f32(*p); }
+  static __device__ __forceinline__ void st(uint16_t* p, float v) { *p = f32_to_bf16(v); }
+  static __device__ __forceinline__ void ldv(const uint16_t* p, float* v) {
+    const u4 a = *reinterpret_cast<const u4*>(p);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      v[2 * k] = __uint_as_float(a[k] << 16);
+      v[2 * k + 1] = __uint_as_float(a[k] & 0xffff0000u);
+    }
+  }
+  static __device__ __forceinline__ void stv(uint16_t* p, const float* v) {
+    u4 a;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) a[k] = (uint32_t)f32_to_bf16(v[2 * k]) | ((uint32_t)f32_to_bf16(v[2 * k + 1]) << 16);
+    *reinterpret_cast<u4*>(p) = a;
+  }
+  static __device__ __forceinline__ void ldh(const uint16_t* p, float* v) {
+    const uint2 a = *reinterpret_cast<const uint2*>(p);
+    v[0] = __uint_as_float(a.x << 16); v[1] = __uint_as_float(a.x & 0xffff0000u);
+    v[2] = __uint_as_float(a.y << 16); v[3] = __uint_as_float(a.y & 0xffff0000u);
+  }
+  static __device__ __forceinline__ void sth(uint16_t* p, const float* v) {
+    *reinterpret_cast<uint2*>(p) = make_uint2((uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16),
+                                              (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16));
+  }
+};
+
+// Streaming kernels: one 16-byte access per lane when the shapes and pointers allow (VEC), else one element.
+template <typename T, bool VEC>
+__global__ __launch_bounds__(256) void k_relu_fwd(const T* __restrict__ x, T* __restrict__ y, size_t n) {
+  constexpr int V = VEC ? Elt<T>::V : 1;
   const size_t nv = n / V;
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < nv; i += (size_t)gridDim.x * 256) {
-    if (V == 4) {
-      const f4 v = reinterpret_cast<const f4*>(x)[i];
-      reinterpret_cast<f4*>(y)[i] = f4{fmaxf(v[0], 0.f), fmaxf(v[1], 0.f), fmaxf(v[2], 0.f), fmaxf(v[3], 0.f)};
+    if (VEC) {
+      float v[Elt<T>::V];
+      Elt<T>::ldv(x + i * V, v);
+#pragma unroll
+      for (int k = 0; k < V; ++k) v[k] = fmaxf(v[k], 0.f);
+      Elt<T>::stv(y + i * V, v);
     } else {
-      y[i] = fmaxf(x[i], 0.f);
+      Elt<T>::st(y + i, fmaxf(Elt<T>::ld(x + i), 0.f));
     }
   }
   const size_t t = nv * V + (size_t)blockIdx.x * 256 + threadIdx.x;    // the last n % V elements
-  if (V > 1 && t < n) y[t] = fmaxf(x[t], 0.f);
+  if (VEC && t < n) Elt<T>::st(y + t, fmaxf(Elt<T>::ld(x + t), 0.f));
 }
-template <int V>
-__global__ __launch_bounds__(256) void k_relu_bwd(const float* __restrict__ y, const float* __restrict__ dy,
-                                                  float* __restrict__ dx, size_t n) {
+template <typename T, bool VEC>
+__global__ __launch_bounds__(256) void k_relu_bwd(const T* __restrict__ y, const T* __restrict__ dy,
+                                                  T* __restrict__ dx, size_t n) {
+  constexpr int V = VEC ? Elt<T>::V : 1;
   const size_t nv = n / V;
   for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < nv; i += (size_t)gridDim.x * 256) {
-    if (V == 4) {
-      const f4 a = reinterpret_cast<const f4*>(y)[i], d = reinterpret_cast<const f4*>(dy)[i];
-      reinterpret_cast<f4*>(dx)[i] = f4{a[0] > 0.f ? d[0] : 0.f, a[1] > 0.f ? d[1] : 0.f, a[2] > 0.f ? d[2] : 0.f,
-                                        a[3] > 0.f ? d[3] : 0.f};
+    if (VEC) {
+      float a[Elt<T>::V], d[Elt<T>::V];
+      Elt<T>::ldv(y + i * V, a);
+      Elt<T>::ldv(dy + i * V, d);
+#pragma unroll
+      for (int k = 0; k < V; ++k) d[k] = a[k] > 0.f ? d[k] : 0.f;
+      Elt<T>::stv(dx + i * V, d);
     } else {
-      dx[i] = y[i] > 0.f ? dy[i] : 0.f;
+      Elt<T>::st(dx + i, Elt<T>::ld(y + i) > 0.f ? Elt<T>::ld(dy + i) : 0.f);
     }
   }
   const size_t t = nv * V + (size_t)blockIdx.x * 256 + threadIdx.x;
-  if (V > 1 && t < n) dx[t] = y[t] > 0.f ? dy[t] : 0.f;
+  if (VEC && t < n) Elt<T>::st(dx + t, Elt<T>::ld(y + t) > 0.f ? Elt<T>::ld(dy + t) : 0.f);
 }
 
-// One thread per pair of windows when V == 2 (four input columns: 16-byte row reads), else per window.
-template <int V>
-__global__ __launch_bounds__(256) void k_maxpool2_fwd(const float* __restrict__ x, float* __restrict__ y,
+// VEC: one thread per 16 bytes of an input row pair (V columns = V/2 windows); else one thread per window.
+template <typename T, bool VEC>
+__global__ __launch_bounds__(256) void k_maxpool2_fwd(const T* __restrict__ x, T* __restrict__ y,
                                                       uint8_t* __restrict__ idx, size_t planes, int H, int W) {
-  const int Ho = H / 2, Wo = W / 2, Wv = Wo / V;
+  constexpr int NW = VEC ? Elt<T>::V / 2 : 1;   // windows per thread
+  const int Ho = H / 2, Wo = W / 2, Wv = Wo / NW;
   const size_t total = planes * Ho * Wv;
   for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (size_t)gridDim.x * 256) {
-    const int ox = (int)(e % Wv) * V, oy = (int)((e / Wv) % Ho);
+    const int ox = (int)(e % Wv) * NW, oy = (int)((e / Wv) % Ho);
     const size_t pl = e / ((size_t)Wv * Ho);
-    const float* p = x + (pl * H + 2 * oy) * W + 2 * ox;
-    float r0[2 * V], r1[2 * V];
-    if (V == 2) {
-      const f4 a = *reinterpret_cast<const f4*>(p), b = *reinterpret_cast<const f4*>(p + W);
-#pragma unroll
-      for (int k = 0; k < 4; ++k) { r0[k] = a[k]; r1[k] = b[k]; }
+    const T* p = x + (pl * H + 2 * oy) * W + 2 * ox;
+    float r0[2 * NW], r1[2 * NW];
+    if (VEC) {
+      Elt<T>::ldv(p, r0);
+      Elt<T>::ldv(p + W, r1);
     } else {
-      r0[0] = p[0]; r0[1] = p[1]; r1[0] = p[W]; r1[1] = p[W + 1];
+      r0[0] = Elt<T>::ld(p); r0[1] = Elt<T>::ld(p + 1); r1[0] = Elt<T>::ld(p + W); r1[1] = Elt<T>::ld(p + W + 1);
     }
-    float best[V];
-    int bi[V];
+    float best[NW];
+    uint32_t packed = 0;
 #pragma unroll
-    for (int k = 0; k < V; ++k) {
-      best[k] = r0[2 * k]; bi[k] = 0;
-      if (r0[2 * k + 1] > best[k]) { best[k] = r0[2 * k + 1]; bi[k] = 1; }
-      if (r1[2 * k] > best[k]) { best[k] = r1[2 * k]; bi[k] = 2; }
-      if (r1[2 * k + 1] > best[k]) { best[k] = r1[2 * k + 1]; bi[k] = 3; }
+    for (int k = 0; k < NW; ++k) {
+      int bi = 0;
+      best[k] = r0[2 * k];
+      if (r0[2 * k + 1] > best[k]) { best[k] = r0[2 * k + 1]; bi = 1; }
+      if (r1[2 * k] > best[k]) { best[k] = r1[2 * k]; bi = 2; }
+      if (r1[2 * k + 1] > best[k]) { best[k] = r1[2 * k + 1]; bi = 3; }
+      packed |= (uint32_t)bi << (8 * k);
     }
     const size_t o = (pl * Ho + oy) * Wo + ox;
-    if (V == 2) {
-      *reinterpret_cast<float2*>(y + o) = make_float2(best[0], best[V - 1]);
-      *reinterpret_cast<uint16_t*>(idx + o) = (uint16_t)(bi[0] | (bi[V - 1] << 8));
+    if (VEC) {
+      Elt<T>::sth(y + o, best);
+      if (NW == 2) *reinterpret_cast<uint16_t*>(idx + o) = (uint16_t)packed;
+      else *reinterpret_cast<uint32_t*>(idx + o) = packed;
     } else {
-      y[o] = best[0];
-      idx[o] = (uint8_t)bi[0];
+      Elt<T>::st(y + o, best[0]);
+      idx[o] = (uint8_t)packed;
     }
   }
 }
-// One thread per four input columns (two windows) when V == 4, else per input element.
-template <int V>
-__global__ __launch_bounds__(256) void k_maxpool2_bwd(const float* __restrict__ dy, const uint8_t* __restrict__ idx,
-                                                      float* __restrict__ dx, size_t planes, int H, int W, int acc) {
+// VEC: one thread per 16 bytes of an input row (V columns, V/2 windows); else one thread per input element.
+template <typename T, bool VEC>
+__global__ __launch_bounds__(256) void k_maxpool2_bwd(const T* __restrict__ dy, const uint8_t* __restrict__ idx,
+                                                      T* __restrict__ dx, size_t planes, int H, int W, int acc) {
+  constexpr int V = VEC ? Elt<T>::V : 1;
   const int Ho = H / 2, Wo = W / 2, Wv = W / V;
   const size_t total = planes * H * Wv;
   for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (size_t)gridDim.x * 256) {
@@ -100,76 +166,97 @@ __global__ __launch_bounds__(256) void k_maxpool2_bwd(const float* __restrict__ 
     const size_t pl = e / ((size_t)Wv * H);
     const size_t o = (pl * Ho + yy / 2) * Wo + xx / 2;
     const size_t i = (pl * H + yy) * W + xx;
-    if (V == 4) {
-      const float2 d = *reinterpret_cast<const float2*>(dy + o);
-      const uint32_t w = *reinterpret_cast<const uint16_t*>(idx + o);
+    if (VEC) {
+      constexpr int NW = Elt<T>::V / 2;
+      float d[NW], v[Elt<T>::V];
+      Elt<T>::ldh(dy + o, d);
+      const uint32_t w = NW == 2 ? (uint32_t)*reinterpret_cast<const uint16_t*>(idx + o)
+                                 : *reinterpret_cast<const uint32_t*>(idx + o);
       const uint32_t r = 2 * (yy & 1);
-      f4 v = f4{(w & 0xff) == r ? d.x : 0.f, (w & 0xff) == r + 1 ? d.x : 0.f, (w >> 8) == r ? d.y : 0.f,
-                (w >> 8) == r + 1 ? d.y : 0.f};
-      if (acc) v += *reinterpret_cast<const f4*>(dx + i);
-      *reinterpret_cast<f4*>(dx + i) = v;
-    } else {
-      const float v = idx[o] == (uint8_t)(2 * (yy & 1) + (xx & 1)) ? dy[o] : 0.f;
-      dx[i] = acc ? dx[i] + v : v;
-    }
-  }
-}
-
-// na, nb: elements per image of the two parts.  V == 4 needs both divisible by 4.
-template <int V>
-__global__ __launch_bounds__(256) void k_concat2(const float* __restrict__ a, const float* __restrict__ b,
-                                                 float* __restrict__ out, int N, size_t na, size_t nb) {
-  const size_t va = na / V, vb = nb / V, total = (size_t)N * (va + vb);
-  for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (size_t)gridDim.x * 256) {
-    const size_t n = e / (va + vb), r = e % (va + vb);
-    if (V == 4) {
-      reinterpret_cast<f4*>(out)[e] = r < va ? reinterpret_cast<const f4*>(a)[n * va + r]
-                                             : reinterpret_cast<const f4*>(b)[n * vb + (r - va)];
-    } else {
-      out[e] = r < va ? a[n * va + r] : b[n * vb + (r - va)];
-    }
-  }
-}
-template <int V>
-__global__ __launch_bounds__(256) void k_split2(const float* __restrict__ dcat, float* __restrict__ da,
-                                                float* __restrict__ db, int N, size_t na, size_t nb, int acc) {
-  const size_t va = na / V, vb = nb / V, total = (size_t)N * (va + vb);
-  for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (size_t)gridDim.x * 256) {
-    const size_t n = e / (va + vb), r = e % (va + vb);
-    if (V == 4) {
-      const f4 v = reinterpret_cast<const f4*>(dcat)[e];
-      if (r < va) {
-        f4* d = reinterpret_cast<f4*>(da) + (n * va + r);
-        *d = acc ? *d + v : v;
-      } else {
-        reinterpret_cast<f4*>(db)[n * vb + (r - va)] = v;
+#pragma unroll
+      for (int k = 0; k < NW; ++k) {
+        const uint32_t b = (w >> (8 * k)) & 0xff;
+        v[2 * k] = b == r ? d[k] : 0.f;
+        v[2 * k + 1] = b == r + 1 ? d[k] : 0.f;
       }
+      if (acc) {
+        float old[Elt<T>::V];
+        Elt<T>::ldv(dx + i, old);
+#pragma unroll
+        for (int k = 0; k < V; ++k) v[k] += old[k];
+      }
+      Elt<T>::stv(dx + i, v);
     } else {
-      if (r < va) da[n * va + r] = acc ? da[n * va + r] + dcat[e] : dcat[e];
-      else db[n * vb + (r - va)] = dcat[e];
+      const float v = idx[o] == (uint8_t)(2 * (yy & 1) + (xx & 1)) ? Elt<T>::ld(dy + o) : 0.f;
+      Elt<T>::st(dx + i, acc ? Elt<T>::ld(dx + i) + v : v);
     }
   }
 }
 
-// per-pixel loss into `pix`, dlogits = (softmax - onehot) * inv
-__global__ __launch_bounds__(256) void k_softmax_ce(const float* __restrict__ logits, const int32_t* __restrict__ labels,
-                                                    float* __restrict__ pix, float* __restrict__ dl, int N, int K,
+// na, nb: elements per image of the two parts.  VEC needs both divisible by V.
+template <typename T, bool VEC>
+__global__ __launch_bounds__(256) void k_concat2(const T* __restrict__ a, const T* __restrict__ b,
+                                                 T* __restrict__ out, int N, size_t na, size_t nb) {
+  constexpr int V = VEC ? Elt<T>::V : 1;
+  const size_t va = na / V, vb = nb / V, total = (size_t)N * (va + vb);
+  for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (size_t)gridDim.x * 256) {
+    const size_t n = e / (va + vb), r = e % (va + vb);
+    const T* src = r < va ? a + (n * va + r) * V : b + (n * vb + (r - va)) * V;
+    if (VEC) *reinterpret_cast<u4*>(out + e * V) = *reinterpret_cast<const u4*>(src);
+    else out[e] = *src;
+  }
+}
+template <typename T, bool VEC>
+__global__ __launch_bounds__(256) void k_split2(const T* __restrict__ dcat, T* __restrict__ da,
+                                                T* __restrict__ db, int N, size_t na, size_t nb, int acc) {
+  constexpr int V = VEC ? Elt<T>::V : 1;
+  const size_t va = na / V, vb = nb / V, total = (size_t)N * (va + vb);
+  for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (size_t)gridDim.x * 256) {
+    const size_t n = e / (va + vb), r = e % (va + vb);
+    if (r >= va) {
+      T* d = db + (n * vb + (r - va)) * V;
+      if (VEC) *reinterpret_cast<u4*>(d) = *reinterpret_cast<const u4*>(dcat + e * V);
+      else *d = dcat[e];
+    } else if (!acc) {
+      T* d = da + (n * va + r) * V;
+      if (VEC) *reinterpret_cast<u4*>(d) = *reinterpret_cast<const u4*>(dcat + e * V);
+      else *d = dcat[e];
+    } else if (VEC) {
+      float v[Elt<T>::V], old[Elt<T>::V];
+      T* d = da + (n * va + r) * V;
+      Elt<T>::ldv(dcat + e * V, v);
+      Elt<T>::ldv(d, old);
+#pragma unroll
+      for (int k = 0; k < V; ++k) v[k] += old[k];
+      Elt<T>::stv(d, v);
+    } else {
+      T* d = da + n * va + r;
+      Elt<T>::st(d, Elt<T>::ld(d) + Elt<T>::ld(dcat + e));
+    }
+  }
+}
+
+// per-pixel loss into `pix` (fp32), dlogits = (softmax - onehot) * inv
+template <typename T>
+__global__ __launch_bounds__(256) void k_softmax_ce(const T* __restrict__ logits, const int32_t* __restrict__ labels,
+                                                    float* __restrict__ pix, T* __restrict__ dl, int N, int K,
                                                     size_t P, float inv) {
   const size_t total = (size_t)N * P;
   for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (size_t)gridDim.x * 256) {
     const size_t n = e / P, p = e % P;
-    const float* lg = logits + n * K * P + p;
-    float m = lg[0];
-    for (int k = 1; k < K; ++k) m = fmaxf(m, lg[(size_t)k * P]);
+    const T* lg = logits + n * K * P + p;
+    float m = Elt<T>::ld(lg);
+    for (int k = 1; k < K; ++k) m = fmaxf(m, Elt<T>::ld(lg + (size_t)k * P));
     float s = 0.f;
-    for (int k = 0; k < K; ++k) s += expf(lg[(size_t)k * P] - m);
+    for (int k = 0; k < K; ++k) s += expf(Elt<T>::ld(lg + (size_t)k * P) - m);
     const int lab = labels[e];
     const bool valid = lab >= 0 && lab < K;      // a label outside 0..K-1 contributes nothing
     const float lse = m + logf(s);
-    pix[e] = valid ? lse - lg[(size_t)lab * P] : 0.f;
-    float* d = dl + n * K * P + p;
+    pix[e] = valid ? lse - Elt<T>::ld(lg + (size_t)(valid ? lab : 0) * P) : 0.f;
+    T* d = dl + n * K * P + p;
     for (int k = 0; k < K; ++k)
-      d[(size_t)k * P] = valid ? (expf(lg[(size_t)k * P] - lse) - (k == lab ? 1.f : 0.f)) * inv : 0.f;
+      Elt<T>::st(d + (size_t)k * P,
+                 valid ? (expf(Elt<T>::ld(lg + (size_t)k * P) - lse) - (k == lab ? 1.f : 0.f)) * inv : 0.f);
   }
 }
 // deterministic mean: 1024 threads each sum a strided subset in order, then a fixed tree
@@ -194,83 +281,120 @@ int pick_splitk(int tiles, int batch, int K) {
   return std::min(s, 64);
 }
 
-}  // namespace
-}  // namespace rotconv
+hipStream_t S(void* stream) { return static_cast<hipStream_t>(stream); }
 
-using namespace rotconv;
-
-extern "C" {
-
-int glue_relu_fwd(const float* x, float* y, size_t n, void* stream) {
+// ---- typed bodies of the entry points (T = float, or uint16_t holding bfloat16) ----
+template <typename T>
+int relu_fwd_t(const T* x, T* y, size_t n, void* stream) {
   if (!x || !y) return ROTCONV_ERR_NULL;
   if (aligned16(x) && aligned16(y))
-    hipLaunchKernelGGL(k_relu_fwd<4>, dim3(blocks_for(n / 4 + 4)), dim3(256), 0, (hipStream_t)stream, x, y, n);
+    hipLaunchKernelGGL((k_relu_fwd<T, true>), dim3(blocks_for(n / Elt<T>::V + 8)), dim3(256), 0, S(stream), x, y, n);
   else
-    hipLaunchKernelGGL(k_relu_fwd<1>, dim3(blocks_for(n)), dim3(256), 0, (hipStream_t)stream, x, y, n);
+    hipLaunchKernelGGL((k_relu_fwd<T, false>), dim3(blocks_for(n)), dim3(256), 0, S(stream), x, y, n);
   return finish();
 }
-int glue_relu_bwd(const float* y, const float* dy, float* dx, size_t n, void* stream) {
+template <typename T>
+int relu_bwd_t(const T* y, const T* dy, T* dx, size_t n, void* stream) {
   if (!y || !dy || !dx) return ROTCONV_ERR_NULL;
   if (aligned16(y) && aligned16(dy) && aligned16(dx))
-    hipLaunchKernelGGL(k_relu_bwd<4>, dim3(blocks_for(n / 4 + 4)), dim3(256), 0, (hipStream_t)stream, y, dy, dx, n);
+    hipLaunchKernelGGL((k_relu_bwd<T, true>), dim3(blocks_for(n / Elt<T>::V + 8)), dim3(256), 0, S(stream), y, dy, dx, n);
   else
-    hipLaunchKernelGGL(k_relu_bwd<1>, dim3(blocks_for(n)), dim3(256), 0, (hipStream_t)stream, y, dy, dx, n);
+    hipLaunchKernelGGL((k_relu_bwd<T, false>), dim3(blocks_for(n)), dim3(256), 0, S(stream), y, dy, dx, n);
   return finish();
 }
-
-int glue_maxpool2_fwd(const float* x, float* y, uint8_t* idx, int N, int C, int H, int W, void* stream) {
+template <typename T>
+int maxpool2_fwd_t(const T* x, T* y, uint8_t* idx, int N, int C, int H, int W, void* stream) {
   if (!x || !y || !idx) return ROTCONV_ERR_NULL;
   if (N < 1 || C < 1 || H < 2 || W < 2 || (H & 1) || (W & 1)) return ROTCONV_ERR_SHAPE;
   const size_t planes = (size_t)N * C;
-  if ((W & 3) == 0 && aligned16(x) && aligned16(y) && aligned16(idx))
-    hipLaunchKernelGGL(k_maxpool2_fwd<2>, dim3(blocks_for(planes * H * W / 8)), dim3(256), 0, (hipStream_t)stream, x, y,
-                       idx, planes, H, W);
+  if (W % Elt<T>::V == 0 && aligned16(x) && aligned16(y) && aligned16(idx))
+    hipLaunchKernelGGL((k_maxpool2_fwd<T, true>), dim3(blocks_for(planes * H * W / (2 * Elt<T>::V))), dim3(256), 0,
+                       S(stream), x, y, idx, planes, H, W);
   else
-    hipLaunchKernelGGL(k_maxpool2_fwd<1>, dim3(blocks_for(planes * H * W / 4)), dim3(256), 0, (hipStream_t)stream, x, y,
+    hipLaunchKernelGGL((k_maxpool2_fwd<T, false>), dim3(blocks_for(planes * H * W / 4)), dim3(256), 0, S(stream), x, y,
                        idx, planes, H, W);
   return finish();
 }
-int glue_maxpool2_bwd(const float* dy, const uint8_t* idx, float* dx, int N, int C, int H, int W, int accumulate,
-                      void* stream) {
+template <typename T>
+int maxpool2_bwd_t(const T* dy, const uint8_t* idx, T* dx, int N, int C, int H, int W, int accumulate, void* stream) {
   if (!dy || !idx || !dx) return ROTCONV_ERR_NULL;
   if (N < 1 || C < 1 || H < 2 || W < 2 || (H & 1) || (W & 1)) return ROTCONV_ERR_SHAPE;
   const size_t planes = (size_t)N * C;
-  if ((W & 3) == 0 && aligned16(dy) && aligned16(dx) && aligned16(idx))
-    hipLaunchKernelGGL(k_maxpool2_bwd<4>, dim3(blocks_for(planes * H * W / 4)), dim3(256), 0, (hipStream_t)stream, dy,
-                       idx, dx, planes, H, W, accumulate);
+  if (W % Elt<T>::V == 0 && aligned16(dy) && aligned16(dx) && aligned16(idx))
+    hipLaunchKernelGGL((k_maxpool2_bwd<T, true>), dim3(blocks_for(planes * H * W / Elt<T>::V)), dim3(256), 0, S(stream),
+                       dy, idx, dx, planes, H, W, accumulate);
   else
-    hipLaunchKernelGGL(k_maxpool2_bwd<1>, dim3(blocks_for(planes * H * W)), dim3(256), 0, (hipStream_t)stream, dy, idx,
-                       dx, planes, H, W, accumulate);
+    hipLaunchKernelGGL((k_maxpool2_bwd<T, false>), dim3(blocks_for(planes * H * W)), dim3(256), 0, S(stream), dy, idx, dx,
+                       planes, H, W, accumulate);
+  return finish();
+}
+template <typename T>
+int concat2_t(const T* a, const T* b, T* out, int N, int Ca, int Cb, size_t P, void* stream) {
+  if (!a || !b || !out) return ROTCONV_ERR_NULL;
+  if (N < 1 || Ca < 1 || Cb < 1 || P < 1) return ROTCONV_ERR_SHAPE;
+  const size_t na = (size_t)Ca * P, nb = (size_t)Cb * P;
+  constexpr int V = Elt<T>::V;
+  if (na % V == 0 && nb % V == 0 && aligned16(a) && aligned16(b) && aligned16(out))
+    hipLaunchKernelGGL((k_concat2<T, true>), dim3(blocks_for((size_t)N * (na + nb) / V)), dim3(256), 0, S(stream), a, b,
+                       out, N, na, nb);
+  else
+    hipLaunchKernelGGL((k_concat2<T, false>), dim3(blocks_for((size_t)N * (na + nb))), dim3(256), 0, S(stream), a, b, out,
+                       N, na, nb);
+  return finish();
+}
+template <typename T>
+int split2_t(const T* dcat, T* da, T* db, int N, int Ca, int Cb, size_t P, int accumulate_a, void* stream) {
+  if (!dcat || !da || !db) return ROTCONV_ERR_NULL;
+  if (N < 1 || Ca < 1 || Cb < 1 || P < 1) return ROTCONV_ERR_SHAPE;
+  const size_t na = (size_t)Ca * P, nb = (size_t)Cb * P;
+  constexpr int V = Elt<T>::V;
+  if (na % V == 0 && nb % V == 0 && aligned16(dcat) && aligned16(da) && aligned16(db))
+    hipLaunchKernelGGL((k_split2<T, true>), dim3(blocks_for((size_t)N * (na + nb) / V)), dim3(256), 0, S(stream), dcat,
+                       da, db, N, na, nb, accumulate_a);
+  else
+    hipLaunchKernelGGL((k_split2<T, false>), dim3(blocks_for((size_t)N * (na + nb))), dim3(256), 0, S(stream), dcat, da,
+                       db, N, na, nb, accumulate_a);
+  return finish();
+}
+template <typename T>
+int softmax_ce_t(const T* logits, const int32_t* labels, float* loss, T* dlogits, int N, int K, size_t P, void* ws,
+                 size_t ws_bytes, void* stream) {
+  if (!logits || !labels || !loss || !dlogits) return ROTCONV_ERR_NULL;
+  if (N < 1 || K < 1 || P < 1) return ROTCONV_ERR_SHAPE;
+  if (!ws || ws_bytes < (size_t)N * P * sizeof(float)) return ROTCONV_ERR_WORKSPACE;
+  const float inv = 1.0f / (float)((double)N * (double)P);
+  hipLaunchKernelGGL((k_softmax_ce<T>), dim3(blocks_for((size_t)N * P)), dim3(256), 0, S(stream), logits, labels,
+                     (float*)ws, dlogits, N, K, P, inv);
+  hipLaunchKernelGGL(k_mean, dim3(1), dim3(1024), 0, S(stream), (const float*)ws, loss, (size_t)N * P, inv);
   return finish();
 }
 
-size_t glue_upconv2_workspace_bytes(int N, int Cin, int Cout, int H, int W) {
-  const int tiles = ((Cin + 127) / 128) * ((4 * Cout + 127) / 128);
-  return (size_t)N * pick_splitk(tiles, N, H * W) * Cin * 4 * Cout * sizeof(float);
-}
-int glue_upconv2_fwd(const float* x, const float* w, float* y, int N, int Cin, int Cout, int H, int W, void* stream) {
+// The GEMM-shaped layers.  bf = 1: x / y / dy / dx and w are bfloat16; weight gradients stay fp32.
+int upconv2_fwd_g(const void* x, const void* w, void* y, int N, int Cin, int Cout, int H, int W, int bf, void* stream) {
   if (!x || !w || !y) return ROTCONV_ERR_NULL;
   if (N < 1 || Cin < 1 || Cout < 1 || H < 1 || W < 1) return ROTCONV_ERR_SHAPE;
   GemmArgs a{};
   a.M = 4 * Cout; a.N = H * W; a.K = Cin; a.lda = 4 * Cout; a.ldb = H * W; a.ldc = H * W; a.transA = 1; a.transB = 0;
   a.batch = N; a.splitk = 1; a.strideA = 0; a.strideB = (size_t)Cin * H * W; a.strideC = (size_t)Cout * 4 * H * W;
   a.shufB = 0; a.shufC = 1; a.shufH = H; a.shufW = W;
-  launch_gemm(a, w, x, y, (hipStream_t)stream);
+  a.bf16A = a.bf16B = a.bf16C = bf;
+  launch_gemm(a, w, x, y, S(stream));
   return finish();
 }
-int glue_upconv2_bwd_data(const float* dy, const float* w, float* dx, int N, int Cin, int Cout, int H, int W,
-                          void* stream) {
+int upconv2_bwd_data_g(const void* dy, const void* w, void* dx, int N, int Cin, int Cout, int H, int W, int bf,
+                       void* stream) {
   if (!dy || !w || !dx) return ROTCONV_ERR_NULL;
   if (N < 1 || Cin < 1 || Cout < 1 || H < 1 || W < 1) return ROTCONV_ERR_SHAPE;
   GemmArgs a{};
   a.M = Cin; a.N = H * W; a.K = 4 * Cout; a.lda = 4 * Cout; a.ldb = 0; a.ldc = H * W; a.transA = 0; a.transB = 0;
   a.batch = N; a.splitk = 1; a.strideA = 0; a.strideB = (size_t)Cout * 4 * H * W; a.strideC = (size_t)Cin * H * W;
   a.shufB = 1; a.shufC = 0; a.shufH = H; a.shufW = W;
-  launch_gemm(a, w, dy, dx, (hipStream_t)stream);
+  a.bf16A = a.bf16B = a.bf16C = bf;
+  launch_gemm(a, w, dy, dx, S(stream));
   return finish();
 }
-int glue_upconv2_bwd_weight(const float* x, const float* dy, float* dw, int N, int Cin, int Cout, int H, int W,
-                            void* ws, size_t ws_bytes, void* stream) {
+int upconv2_bwd_weight_g(const void* x, const void* dy, float* dw, int N, int Cin, int Cout, int H, int W, void* ws,
+                         size_t ws_bytes, int bf, void* stream) {
   if (!x || !dy || !dw) return ROTCONV_ERR_NULL;
   if (N < 1 || Cin < 1 || Cout < 1 || H < 1 || W < 1) return ROTCONV_ERR_SHAPE;
   if (!ws || ws_bytes < glue_upconv2_workspace_bytes(N, Cin, Cout, H, W)) return ROTCONV_ERR_WORKSPACE;
@@ -280,62 +404,34 @@ int glue_upconv2_bwd_weight(const float* x, const float* dy, float* dw, int N, i
   a.batch = N; a.splitk = pick_splitk(tiles, N, H * W); a.strideA = (size_t)Cin * H * W;
   a.strideB = (size_t)Cout * 4 * H * W; a.strideC = (size_t)Cin * 4 * Cout;
   a.shufB = 1; a.shufC = 0; a.shufH = H; a.shufW = W;
-  launch_gemm(a, x, dy, (float*)ws, (hipStream_t)stream);
-  launch_sum_parts((const float*)ws, dw, a.strideC, N * a.splitk, a.strideC, (hipStream_t)stream);
+  a.bf16A = a.bf16B = bf;
+  launch_gemm(a, x, dy, ws, S(stream));
+  launch_sum_parts((const float*)ws, dw, a.strideC, N * a.splitk, a.strideC, S(stream));
   return finish();
 }
-
-int glue_concat2(const float* a, const float* b, float* out, int N, int Ca, int Cb, size_t P, void* stream) {
-  if (!a || !b || !out) return ROTCONV_ERR_NULL;
-  if (N < 1 || Ca < 1 || Cb < 1 || P < 1) return ROTCONV_ERR_SHAPE;
-  const size_t na = (size_t)Ca * P, nb = (size_t)Cb * P;
-  if (na % 4 == 0 && nb % 4 == 0 && aligned16(a) && aligned16(b) && aligned16(out))
-    hipLaunchKernelGGL(k_concat2<4>, dim3(blocks_for((size_t)N * (na + nb) / 4)), dim3(256), 0, (hipStream_t)stream, a, b,
-                       out, N, na, nb);
-  else
-    hipLaunchKernelGGL(k_concat2<1>, dim3(blocks_for((size_t)N * (na + nb))), dim3(256), 0, (hipStream_t)stream, a, b, out,
-                       N, na, nb);
-  return finish();
-}
-int glue_split2(const float* dcat, float* da, float* db, int N, int Ca, int Cb, size_t P, int accumulate_a,
-                void* stream) {
-  if (!dcat || !da || !db) return ROTCONV_ERR_NULL;
-  if (N < 1 || Ca < 1 || Cb < 1 || P < 1) return ROTCONV_ERR_SHAPE;
-  const size_t na = (size_t)Ca * P, nb = (size_t)Cb * P;
-  if (na % 4 == 0 && nb % 4 == 0 && aligned16(dcat) && aligned16(da) && aligned16(db))
-    hipLaunchKernelGGL(k_split2<4>, dim3(blocks_for((size_t)N * (na + nb) / 4)), dim3(256), 0, (hipStream_t)stream, dcat,
-                       da, db, N, na, nb, accumulate_a);
-  else
-    hipLaunchKernelGGL(k_split2<1>, dim3(blocks_for((size_t)N * (na + nb))), dim3(256), 0, (hipStream_t)stream, dcat, da,
-                       db, N, na, nb, accumulate_a);
-  return finish();
-}
-
-size_t glue_conv1x1_workspace_bytes(int N, int Cin, int Cout, size_t P) {
-  const int tiles = ((Cout + 127) / 128) * ((Cin + 127) / 128);
-  return (size_t)N * pick_splitk(tiles, N, (int)P) * Cout * Cin * sizeof(float);
-}
-int glue_conv1x1_fwd(const float* x, const float* w, float* y, int N, int Cin, int Cout, size_t P, void* stream) {
+int conv1x1_fwd_g(const void* x, const void* w, void* y, int N, int Cin, int Cout, size_t P, int bf, void* stream) {
   if (!x || !w || !y) return ROTCONV_ERR_NULL;
   if (N < 1 || Cin < 1 || Cout < 1 || P < 1 || P > 0x7fffffff) return ROTCONV_ERR_SHAPE;
   GemmArgs a{};
   a.M = Cout; a.N = (int)P; a.K = Cin; a.lda = Cin; a.ldb = (int)P; a.ldc = (int)P; a.batch = N; a.splitk = 1;
   a.strideB = (size_t)Cin * P; a.strideC = (size_t)Cout * P;
-  launch_gemm(a, w, x, y, (hipStream_t)stream);
+  a.bf16A = a.bf16B = a.bf16C = bf;
+  launch_gemm(a, w, x, y, S(stream));
   return finish();
 }
-int glue_conv1x1_bwd_data(const float* dy, const float* w, float* dx, int N, int Cin, int Cout, size_t P,
-                          void* stream) {
+int conv1x1_bwd_data_g(const void* dy, const void* w, void* dx, int N, int Cin, int Cout, size_t P, int bf,
+                       void* stream) {
   if (!dy || !w || !dx) return ROTCONV_ERR_NULL;
   if (N < 1 || Cin < 1 || Cout < 1 || P < 1 || P > 0x7fffffff) return ROTCONV_ERR_SHAPE;
   GemmArgs a{};
   a.M = Cin; a.N = (int)P; a.K = Cout; a.lda = Cin; a.transA = 1; a.ldb = (int)P; a.ldc = (int)P; a.batch = N;
   a.splitk = 1; a.strideB = (size_t)Cout * P; a.strideC = (size_t)Cin * P;
-  launch_gemm(a, w, dy, dx, (hipStream_t)stream);
+  a.bf16A = a.bf16B = a.bf16C = bf;
+  launch_gemm(a, w, dy, dx, S(stream));
   return finish();
 }
-int glue_conv1x1_bwd_weight(const float* x, const float* dy, float* dw, int N, int Cin, int Cout, size_t P, void* ws,
-                            size_t ws_bytes, void* stream) {
+int conv1x1_bwd_weight_g(const void* x, const void* dy, float* dw, int N, int Cin, int Cout, size_t P, void* ws,
+                         size_t ws_bytes, int bf, void* stream) {
   if (!x || !dy || !dw) return ROTCONV_ERR_NULL;
   if (N < 1 || Cin < 1 || Cout < 1 || P < 1 || P > 0x7fffffff) return ROTCONV_ERR_SHAPE;
   if (!ws || ws_bytes < glue_conv1x1_workspace_bytes(N, Cin, Cout, P)) return ROTCONV_ERR_WORKSPACE;
@@ -344,21 +440,121 @@ int glue_conv1x1_bwd_weight(const float* x, const float* dy, float* dw, int N, i
   a.M = Cout; a.N = Cin; a.K = (int)P; a.lda = (int)P; a.ldb = (int)P; a.transB = 1; a.ldc = Cin; a.batch = N;
   a.splitk = pick_splitk(tiles, N, (int)P); a.strideA = (size_t)Cout * P; a.strideB = (size_t)Cin * P;
   a.strideC = (size_t)Cout * Cin;
-  launch_gemm(a, dy, x, (float*)ws, (hipStream_t)stream);
-  launch_sum_parts((const float*)ws, dw, a.strideC, N * a.splitk, a.strideC, (hipStream_t)stream);
+  a.bf16A = a.bf16B = bf;
+  launch_gemm(a, dy, x, ws, S(stream));
+  launch_sum_parts((const float*)ws, dw, a.strideC, N * a.splitk, a.strideC, S(stream));
   return finish();
 }
 
+}  // namespace
+}  // namespace rotconv
+
+using namespace rotconv;
+
+extern "C" {
+
+size_t glue_upconv2_workspace_bytes(int N, int Cin, int Cout, int H, int W) {
+  const int tiles = ((Cin + 127) / 128) * ((4 * Cout + 127) / 128);
+  return (size_t)N * pick_splitk(tiles, N, H * W) * Cin * 4 * Cout * sizeof(float);
+}
+size_t glue_conv1x1_workspace_bytes(int N, int Cin, int Cout, size_t P) {
+  const int tiles = ((Cout + 127) / 128) * ((Cin + 127) / 128);
+  return (size_t)N * pick_splitk(tiles, N, (int)P) * Cout * Cin * sizeof(float);
+}
+
+// ---- fp32 ----
+int glue_relu_fwd(const float* x, float* y, size_t n, void* stream) { return relu_fwd_t(x, y, n, stream); }
+int glue_relu_bwd(const float* y, const float* dy, float* dx, size_t n, void* stream) {
+  return relu_bwd_t(y, dy, dx, n, stream);
+}
+int glue_maxpool2_fwd(const float* x, float* y, uint8_t* idx, int N, int C, int H, int W, void* stream) {
+  return maxpool2_fwd_t(x, y, idx, N, C, H, W, stream);
+}
+int glue_maxpool2_bwd(const float* dy, const uint8_t* idx, float* dx, int N, int C, int H, int W, int accumulate,
+                      void* stream) {
+  return maxpool2_bwd_t(dy, idx, dx, N, C, H, W, accumulate, stream);
+}
+int glue_upconv2_fwd(const float* x, const float* w, float* y, int N, int Cin, int Cout, int H, int W, void* stream) {
+  return upconv2_fwd_g(x, w, y, N, Cin, Cout, H, W, 0, stream);
+}
+int glue_upconv2_bwd_data(const float* dy, const float* w, float* dx, int N, int Cin, int Cout, int H, int W,
+                          void* stream) {
+  return upconv2_bwd_data_g(dy, w, dx, N, Cin, Cout, H, W, 0, stream);
+}
+int glue_upconv2_bwd_weight(const float* x, const float* dy, float* dw, int N, int Cin, int Cout, int H, int W,
+                            void* ws, size_t ws_bytes, void* stream) {
+  return upconv2_bwd_weight_g(x, dy, dw, N, Cin, Cout, H, W, ws, ws_bytes, 0, stream);
+}
+int glue_concat2(const float* a, const float* b, float* out, int N, int Ca, int Cb, size_t P, void* stream) {
+  return concat2_t(a, b, out, N, Ca, Cb, P, stream);
+}
+int glue_split2(const float* dcat, float* da, float* db, int N, int Ca, int Cb, size_t P, int accumulate_a,
+                void* stream) {
+  return split2_t(dcat, da, db, N, Ca, Cb, P, accumulate_a, stream);
+}
+int glue_conv1x1_fwd(const float* x, const float* w, float* y, int N, int Cin, int Cout, size_t P, void* stream) {
+  return conv1x1_fwd_g(x, w, y, N, Cin, Cout, P, 0, stream);
+}
+int glue_conv1x1_bwd_data(const float* dy, const float* w, float* dx, int N, int Cin, int Cout, size_t P,
+                          void* stream) {
+  return conv1x1_bwd_data_g(dy, w, dx, N, Cin, Cout, P, 0, stream);
+}
+int glue_conv1x1_bwd_weight(const float* x, const float* dy, float* dw, int N, int Cin, int Cout, size_t P, void* ws,
+                            size_t ws_bytes, void* stream) {
+  return conv1x1_bwd_weight_g(x, dy, dw, N, Cin, Cout, P, ws, ws_bytes, 0, stream);
+}
 int glue_softmax_ce(const float* logits, const int32_t* labels, float* loss, float* dlogits, int N, int K, size_t P,
                     void* ws, size_t ws_bytes, void* stream) {
-  if (!logits || !labels || !loss || !dlogits) return ROTCONV_ERR_NULL;
-  if (N < 1 || K < 1 || P < 1) return ROTCONV_ERR_SHAPE;
-  if (!ws || ws_bytes < (size_t)N * P * sizeof(float)) return ROTCONV_ERR_WORKSPACE;
-  const float inv = 1.0f / (float)((double)N * (double)P);
-  hipLaunchKernelGGL(k_softmax_ce, dim3(blocks_for((size_t)N * P)), dim3(256), 0, (hipStream_t)stream, logits, labels,
-                     (float*)ws, dlogits, N, K, P, inv);
-  hipLaunchKernelGGL(k_mean, dim3(1), dim3(1024), 0, (hipStream_t)stream, (const float*)ws, loss, (size_t)N * P, inv);
-  return finish();
+  return softmax_ce_t(logits, labels, loss, dlogits, N, K, P, ws, ws_bytes, stream);
+}
+
+// ---- bfloat16 tensors (uint16_t storage); weight gradients and the loss are fp32 ----
+int glue_relu_fwd_bf16(const uint16_t* x, uint16_t* y, size_t n, void* stream) { return relu_fwd_t(x, y, n, stream); }
+int glue_relu_bwd_bf16(const uint16_t* y, const uint16_t* dy, uint16_t* dx, size_t n, void* stream) {
+  return relu_bwd_t(y, dy, dx, n, stream);
+}
+int glue_maxpool2_fwd_bf16(const uint16_t* x, uint16_t* y, uint8_t* idx, int N, int C, int H, int W, void* stream) {
+  return maxpool2_fwd_t(x, y, idx, N, C, H, W, stream);
+}
+int glue_maxpool2_bwd_bf16(const uint16_t* dy, const uint8_t* idx, uint16_t* dx, int N, int C, int H, int W,
+                           int accumulate, void* stream) {
+  return maxpool2_bwd_t(dy, idx, dx, N, C, H, W, accumulate, stream);
+}
+int glue_upconv2_fwd_bf16(const uint16_t* x, const uint16_t* w, uint16_t* y, int N, int Cin, int Cout, int H, int W,
+                          void* stream) {
+  return upconv2_fwd_g(x, w, y, N, Cin, Cout, H, W, 1, stream);
+}
+int glue_upconv2_bwd_data_bf16(const uint16_t* dy, const uint16_t* w, uint16_t* dx, int N, int Cin, int Cout, int H,
+                               int W, void* stream) {
+  return upconv2_bwd_data_g(dy, w, dx, N, Cin, Cout, H, W, 1, stream);
+}
+int glue_upconv2_bwd_weight_bf16(const uint16_t* x, const uint16_t* dy, float* dw, int N, int Cin, int Cout, int H,
+                                 int W, void* ws, size_t ws_bytes, void* stream) {
+  return upconv2_bwd_weight_g(x, dy, dw, N, Cin, Cout, H, W, ws, ws_bytes, 1, stream);
+}
+int glue_concat2_bf16(const uint16_t* a, const uint16_t* b, uint16_t* out, int N, int Ca, int Cb, size_t P,
+                      void* stream) {
+  return concat2_t(a, b, out, N, Ca, Cb, P, stream);
+}
+int glue_split2_bf16(const uint16_t* dcat, uint16_t* da, uint16_t* db, int N, int Ca, int Cb, size_t P,
+                     int accumulate_a, void* stream) {
+  return split2_t(dcat, da, db, N, Ca, Cb, P, accumulate_a, stream);
+}
+int glue_conv1x1_fwd_bf16(const uint16_t* x, const uint16_t* w, uint16_t* y, int N, int Cin, int Cout, size_t P,
+                          void* stream) {
+  return conv1x1_fwd_g(x, w, y, N, Cin, Cout, P, 1, stream);
+}
+int glue_conv1x1_bwd_data_bf16(const uint16_t* dy, const uint16_t* w, uint16_t* dx, int N, int Cin, int Cout, size_t P,
+                               void* stream) {
+  return conv1x1_bwd_data_g(dy, w, dx, N, Cin, Cout, P, 1, stream);
+}
+int glue_conv1x1_bwd_weight_bf16(const uint16_t* x, const uint16_t* dy, float* dw, int N, int Cin, int Cout, size_t P,
+                                 void* ws, size_t ws_bytes, void* stream) {
+  return conv1x1_bwd_weight_g(x, dy, dw, N, Cin, Cout, P, ws, ws_bytes, 1, stream);
+}
+int glue_softmax_ce_bf16(const uint16_t* logits, const int32_t* labels, float* loss, uint16_t* dlogits, int N, int K,
+                         size_t P, void* ws, size_t ws_bytes, void* stream) {
+  return softmax_ce_t(logits, labels, loss, dlogits, N, K, P, ws, ws_bytes, stream);
 }
 
 }  // extern "C"

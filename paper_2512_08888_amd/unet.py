@@ -127,19 +127,28 @@ def make_batch(cfg: UNetConfig):
 class UNet:
     """Device state of the stack: plans, parameters, activations, gradients, one shared workspace."""
 
-    def __init__(self, cfg: UNetConfig, params: Optional[Dict[str, np.ndarray]] = None, device="cuda"):
+    def __init__(self, cfg: UNetConfig, params: Optional[Dict[str, np.ndarray]] = None, device="cuda",
+                 dtype: str = "f32"):
+        """dtype "f32": everything fp32.  "bf16": images, parameters, activations and activation gradients
+        are stored as bfloat16 (parameters rounded once when loaded), every call accumulates in fp32, and the
+        parameter gradients and the loss are fp32."""
         import torch
 
         if not torch.cuda.is_available():
             raise RuntimeError("the UNet-shaped step runs on the GPU only")
         rc.lib()  # fails loudly when the library is not built
         self.cfg, self.dev, self.torch = cfg, device, torch
+        if dtype not in ("f32", "bf16"):
+            raise ValueError("dtype must be 'f32' or 'bf16'")
+        self.dtype = dtype
         f32, u8 = torch.float32, torch.uint8
+        adt = torch.bfloat16 if dtype == "bf16" else f32      # storage type of activations and parameters
+        self.adt = adt
         N = cfg.N
         if cfg.H % (1 << cfg.depth) or cfg.W % (1 << cfg.depth):
             raise ValueError("H and W must be divisible by 2**depth")
 
-        def buf(*shape, dtype=f32):
+        def buf(*shape, dtype=adt):
             return torch.empty(shape, dtype=dtype, device=device)
 
         self.layers = rot_layers(cfg)         # (name, Cin, width, H, W)
@@ -150,7 +159,7 @@ class UNet:
         for sp in self.specs:
             name, h, w = sp["name"], sp["H"], sp["W"]
             p = rc.Plan(N, sp["Cin"], h, w, sp["Cout"], k=3, R=sp["R"], mode=sp["mode"], stride=1, pad=1,
-                        pool_group=sp["pool_group"] or 0)
+                        pool_group=sp["pool_group"] or 0, dtype=rc.BF16 if dtype == "bf16" else rc.F32)
             self.plans[name] = p
             ws_bytes = max(ws_bytes, p.workspace_bytes)
             self.act[name] = dict(y=buf(N, p.Cpooled, h, w), idx=buf(N, p.Cpooled, h, w, dtype=u8),
@@ -171,13 +180,13 @@ class UNet:
         self.act["head"] = dict(y=buf(N, cfg.classes, cfg.H, cfg.W), g=buf(N, cfg.classes, cfg.H, cfg.W))
         ws_bytes = max(ws_bytes, rc.glue_conv1x1_workspace_bytes(N, cfg.widths[0], cfg.classes, P), N * P * 4)
         self.ws = torch.empty(ws_bytes, dtype=u8, device=device)
-        self.loss = buf(1)
+        self.loss = buf(1, dtype=f32)
         self.trace = None         # a list turns on per-call event timing
         self._where = ""
         self.images = buf(N, cfg.Cin, cfg.H, cfg.W)
         self.labels = buf(N, cfg.H, cfg.W, dtype=torch.int32)
         self.params = {n: buf(*s) for n, s in param_shapes(cfg).items()}
-        self.grads = {n: buf(*s) for n, s in param_shapes(cfg).items()}
+        self.grads = {n: buf(*s, dtype=f32) for n, s in param_shapes(cfg).items()}
         if params is not None:
             self.load_params(params)
 
@@ -198,7 +207,7 @@ class UNet:
     # ---- host <-> device plumbing -------------------------------------------------------------
     def load_params(self, params):
         for n, t in self.params.items():
-            t.copy_(self.torch.from_numpy(np.ascontiguousarray(params[n], dtype=np.float32)))
+            t.copy_(self.torch.from_numpy(np.ascontiguousarray(params[n], dtype=np.float32)))   # rounds if bf16
 
     def load_batch(self, images, labels):
         self.images.copy_(self.torch.from_numpy(np.ascontiguousarray(images, dtype=np.float32)))

@@ -11,6 +11,7 @@ from paper_2512_08888_amd import unet as un
 from parity_util import RTOL, assert_close, check_idx, dev
 
 pytestmark = pytest.mark.gpu
+BF_RTOL = 1e-2      # one rounding to bfloat16 is 2^-9; the benchmark's bf16 bar is 2e-2
 
 
 def nan(*shape, dtype=torch.float32):
@@ -143,12 +144,124 @@ def test_softmax_ce_ignores_out_of_range_labels():
     assert np.all(d[0, :, 0, 1] == 0) and np.all(d[0, :, 1, 0] == 0)
 
 
+# ---- bfloat16 twins: same definitions on the bf16 values, one rounding of each bf16 output ----------
+
+def _b16(a):
+    """numpy -> (bf16 cuda tensor, its values as fp64)."""
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(torch.bfloat16)
+    return t.cuda(), t.to(torch.float64).numpy()
+
+
+def _h64(t):
+    torch.cuda.synchronize()
+    return t.to(torch.float64).cpu().numpy()
+
+
+def _rb(a):
+    """fp64 reference rounded to bf16 (nearest even) -> fp64: what an exact bf16 result must equal."""
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float64)).to(torch.float32).to(torch.bfloat16).to(
+        torch.float64).numpy()
+
+
+@pytest.mark.parametrize("shape", [(2, 3, 6, 10), (1, 5, 2, 2), (3, 2, 34, 16), (1, 4, 8, 40)])
+def test_bf16_streaming_ops(shape):
+    rng = np.random.default_rng(21)
+    N, C, H, W = shape
+    bf = torch.bfloat16
+    xd, x = _b16(rng.integers(-4, 5, size=shape))                 # ties: the first maximum must win
+    y = nan(*shape, dtype=bf)
+    rc.glue_relu_fwd(xd, y)
+    assert np.array_equal(_h64(y), uo.relu_fwd(x))
+    dyd, dy = _b16(f32(rng, *shape))
+    dx = nan(*shape, dtype=bf)
+    rc.glue_relu_bwd(y, dyd, dx)
+    assert np.array_equal(_h64(dx), uo.relu_bwd(uo.relu_fwd(x), dy))
+    yp, idx = nan(N, C, H // 2, W // 2, dtype=bf), nan(N, C, H // 2, W // 2, dtype=torch.uint8)
+    rc.glue_maxpool2_fwd(xd, yp, idx)
+    yr, ir = uo.maxpool2_fwd(x)
+    assert np.array_equal(_h64(yp), yr) and np.array_equal(host(idx), ir)
+    gd, g = _b16(f32(rng, N, C, H // 2, W // 2))
+    dxp = nan(*shape, dtype=bf)
+    rc.glue_maxpool2_bwd(gd, idx, dxp)
+    ref = uo.maxpool2_bwd(g, ir, H, W)
+    assert np.array_equal(_h64(dxp), ref)
+    accd, base = _b16(f32(rng, *shape))
+    rc.glue_maxpool2_bwd(gd, idx, accd, accumulate=True)
+    assert np.array_equal(_h64(accd), _rb(base + ref))
+    bd, b = _b16(f32(rng, N, C + 3, H, W))
+    cat = nan(N, 2 * C + 3, H, W, dtype=bf)
+    rc.glue_concat2(xd, bd, cat)
+    assert np.array_equal(_h64(cat), np.concatenate([x, b], axis=1))
+    da, db = nan(*shape, dtype=bf), nan(N, C + 3, H, W, dtype=bf)
+    rc.glue_split2(cat, da, db)
+    assert np.array_equal(_h64(da), x) and np.array_equal(_h64(db), b)
+    rc.glue_split2(cat, accd, db, accumulate_a=True)
+    assert np.array_equal(_h64(accd), _rb(_rb(base + ref) + x))
+
+
+@pytest.mark.parametrize("N,Cin,Cout,H,W", [(2, 5, 3, 3, 5), (2, 130, 70, 12, 16)])
+def test_bf16_gemm_layers(N, Cin, Cout, H, W):
+    rng = np.random.default_rng(22)
+    bf = torch.bfloat16
+    xd, x = _b16(f32(rng, N, Cin, H, W))
+    wd, w = _b16(f32(rng, Cin, Cout, 2, 2, scale=Cin ** -0.5))
+    dyd, dy = _b16(f32(rng, N, Cout, 2 * H, 2 * W))
+    y = nan(N, Cout, 2 * H, 2 * W, dtype=bf)
+    rc.glue_upconv2_fwd(xd, wd, y)
+    assert_close(_h64(y), uo.upconv2_fwd(x, w), "bf16 upconv2_fwd", rtol=BF_RTOL)
+    dxr, dwr = uo.upconv2_bwd(x, w, dy)
+    dx = nan(N, Cin, H, W, dtype=bf)
+    rc.glue_upconv2_bwd_data(dyd, wd, dx)
+    assert_close(_h64(dx), dxr, "bf16 upconv2_bwd_data", rtol=BF_RTOL)
+    dw = nan(Cin, Cout, 2, 2)
+    ws = torch.empty(max(256, rc.glue_upconv2_workspace_bytes(N, Cin, Cout, H, W)), dtype=torch.uint8, device="cuda")
+    rc.glue_upconv2_bwd_weight(xd, dyd, dw, ws)
+    assert_close(host(dw), dwr, "bf16 upconv2_bwd_weight (fp32 result)")
+    # 1x1 head on the same tensors, read as [N, Cin, P]
+    hwd, hw = _b16(f32(rng, Cout, Cin, scale=Cin ** -0.5))
+    gd, g = _b16(f32(rng, N, Cout, H, W))
+    yh = nan(N, Cout, H, W, dtype=bf)
+    rc.glue_conv1x1_fwd(xd, hwd, yh)
+    assert_close(_h64(yh), uo.conv1x1_fwd(x, hw), "bf16 conv1x1_fwd", rtol=BF_RTOL)
+    dxr, dwr = uo.conv1x1_bwd(x, hw, g)
+    rc.glue_conv1x1_bwd_data(gd, hwd, dx)
+    assert_close(_h64(dx), dxr, "bf16 conv1x1_bwd_data", rtol=BF_RTOL)
+    dwh = nan(Cout, Cin)
+    ws = torch.empty(max(256, rc.glue_conv1x1_workspace_bytes(N, Cin, Cout, H * W)), dtype=torch.uint8, device="cuda")
+    rc.glue_conv1x1_bwd_weight(xd, gd, dwh, ws)
+    assert_close(host(dwh), dwr, "bf16 conv1x1_bwd_weight (fp32 result)")
+    # soft-max cross-entropy on bf16 logits: fp32 loss, bf16 gradient
+    K = Cout
+    lab = rng.integers(0, K, size=(N, H, W)).astype(np.int32)
+    loss, dl = nan(1), nan(N, K, H, W, dtype=bf)
+    ws = torch.empty(N * H * W * 4, dtype=torch.uint8, device="cuda")
+    rc.glue_softmax_ce(gd, dev(lab), loss, dl, ws)
+    lr, dlr = uo.softmax_ce(g, lab)
+    assert abs(float(host(loss)[0]) - lr) <= RTOL * abs(lr)
+    assert_close(_h64(dl), dlr, "bf16 softmax_ce dlogits", rtol=BF_RTOL)
+
+
+def test_glue_rejects_mixed_storage_types():
+    a = torch.zeros(8, device="cuda")
+    b = torch.zeros(8, device="cuda", dtype=torch.bfloat16)
+    with pytest.raises(TypeError):
+        rc.glue_relu_fwd(a, b)
+
+
 # ---- the stack ------------------------------------------------------------------------------------
 
-def _run_stack(cfg):
+def _bf16_round(a):
+    """fp32 values rounded to bfloat16 (nearest even), returned as fp32."""
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(torch.bfloat16).to(torch.float32).numpy()
+
+
+def _run_stack(cfg, dtype="f32"):
     params = un.make_params(cfg)
     images, labels = un.make_batch(cfg)
-    net = un.UNet(cfg, params)
+    if dtype == "bf16":     # the values the GPU holds after its one rounding
+        params = {k: _bf16_round(v) for k, v in params.items()}
+        images = _bf16_round(images)
+    net = un.UNet(cfg, params, dtype=dtype)
     net.load_batch(images, labels)
     for t in list(net.grads.values()) + [net.loss]:
         t.fill_(float("nan"))
@@ -168,20 +281,26 @@ SMALL = [
 ]
 
 
-@pytest.mark.parametrize("cfg", SMALL, ids=[c.name for c in SMALL])
-def test_unet_step_teacher_forced(cfg):
+TEACHER = [(c, "f32") for c in SMALL] + [(SMALL[0], "bf16"), (SMALL[2], "bf16"), (SMALL[4], "bf16")]
+
+
+@pytest.mark.parametrize("cfg,dtype", TEACHER, ids=[f"{c.name}-{d}" for c, d in TEACHER])
+def test_unet_step_teacher_forced(cfg, dtype):
     """Every call of the step against the oracle's result for the same call, each fed the tensors the
-    GPU step itself produced (so one near-tie arg-max cannot cascade), plus the loss."""
-    net, params, images, labels = _run_stack(cfg)
+    GPU step itself produced (so one near-tie arg-max cannot cascade), plus the loss.  bf16: the same, with
+    the oracle fed the bf16 values the GPU holds; bf16 outputs to the bf16 bar, fp32 weight gradients and
+    the loss to the fp32 bar."""
+    net, params, images, labels = _run_stack(cfg, dtype)
     A = net.act
-    H = lambda t: t.detach().cpu().numpy().astype(np.float64)
+    H = lambda t: t.detach().to(torch.float64).cpu().numpy()
+    act_close = assert_close if dtype == "f32" else (lambda got, ref, what: assert_close(got, ref, what, rtol=BF_RTOL))
     p64 = {k: v.astype(np.float64) for k, v in params.items()}
     # forward, layer by layer
     for sp in net.specs:
         name, R, mode, G = sp["name"], sp["R"], sp["mode"], sp["pool_group"]
         x = H(A[name]["x"])
         y_ref, yp_ref, idx_ref, w_rot = orc.layer_fwd(x, p64[name], R, None, mode, 1, 1, G)
-        assert_close(H(A[name]["y"]), uo.relu_fwd(yp_ref), f"{name} fwd")
+        act_close(H(A[name]["y"]), uo.relu_fwd(yp_ref), f"{name} fwd")
         abs_terms = orc.rotconv_fwd(np.abs(x), np.abs(w_rot), 1, 1)
         check_idx(H(A[name]["idx"]).astype(np.uint8), y_ref, abs_terms, G or R, f"{name} idx")
     for lvl in range(cfg.depth):
@@ -189,20 +308,20 @@ def test_unet_step_teacher_forced(cfg):
         yr, ir = uo.maxpool2_fwd(H(A[f"enc{lvl}b"]["y"]))
         assert np.array_equal(H(p["y"]), yr) and np.array_equal(H(p["idx"]).astype(np.uint8), ir)
         u = A[f"up{lvl}"]
-        assert_close(H(u["y"]), uo.upconv2_fwd(H(u["x"]), p64[f"up{lvl}"]), f"up{lvl} fwd")
+        act_close(H(u["y"]), uo.upconv2_fwd(H(u["x"]), p64[f"up{lvl}"]), f"up{lvl} fwd")
         assert np.array_equal(H(u["cat"]), np.concatenate([H(A[f"enc{lvl}b"]["y"]), H(u["y"])], axis=1))
     hd = A["head"]
-    assert_close(H(hd["y"]), uo.conv1x1_fwd(H(hd["x"]), p64["head"]), "head fwd")
+    act_close(H(hd["y"]), uo.conv1x1_fwd(H(hd["x"]), p64["head"]), "head fwd")
     loss_ref, dl_ref = uo.softmax_ce(H(hd["y"]), labels)
     assert abs(float(net.loss.cpu()[0]) - loss_ref) <= RTOL * abs(loss_ref)
-    assert_close(H(hd["g"]), dl_ref, "dlogits")
+    act_close(H(hd["g"]), dl_ref, "dlogits")
     # backward, call by call, on the GPU's own upstream gradients and arg-max indices
     # (a gradient slot is masked in place by its owner's ReLU backward after it is written, so a
     # producer's dX is compared where that mask kept it)
     masked = lambda owner, ref: np.where(H(A[owner]["y"]) > 0, ref, 0.0)
     dxr, dwr = uo.conv1x1_bwd(H(hd["x"]), p64["head"], H(hd["g"]))
     assert_close(H(net.grads["head"]), dwr, "head dW")
-    assert_close(H(A["dec0b"]["g"]), masked("dec0b", dxr), "head dX")
+    act_close(H(A["dec0b"]["g"]), masked("dec0b", dxr), "head dX")
     for i, sp in enumerate(net.specs):
         name = sp["name"]
         a = A[name]
@@ -214,21 +333,21 @@ def test_unet_step_teacher_forced(cfg):
         if i == 0:
             continue
         if name.endswith("b"):              # lands in the block's first layer's slot
-            assert_close(H(a["gx"]), masked(name[:-1] + "a", dx_ref), f"{name} dX")
+            act_close(H(a["gx"]), masked(name[:-1] + "a", dx_ref), f"{name} dX")
         else:                               # lands in a pool's or a concatenation's slot: not touched again
-            assert_close(H(a["gx"]), dx_ref, f"{name} dX")
+            act_close(H(a["gx"]), dx_ref, f"{name} dX")
     for lvl in range(cfg.depth):
         u = A[f"up{lvl}"]
         C = cfg.widths[lvl]
         dx_ref, dw_ref = uo.upconv2_bwd(H(u["x"]), p64[f"up{lvl}"], H(u["g"]))
         assert_close(H(net.grads[f"up{lvl}"]), dw_ref, f"up{lvl} dW")
         below = "botb" if lvl == cfg.depth - 1 else f"dec{lvl + 1}b"
-        assert_close(H(A[below]["g"]), masked(below, dx_ref), f"up{lvl} dX")
+        act_close(H(A[below]["g"]), masked(below, dx_ref), f"up{lvl} dX")
         assert np.array_equal(H(u["gcat"])[:, C:], H(u["g"]))
         # skip gradient + the 2x2 max-pool's routed gradient, then the encoder layer's ReLU mask
         p = A[f"pool{lvl}"]
         ref = H(u["gcat"])[:, :C] + uo.maxpool2_bwd(H(p["g"]), H(p["idx"]).astype(np.uint8), *A[f"enc{lvl}b"]["y"].shape[2:])
-        assert_close(H(A[f"enc{lvl}b"]["g"]), masked(f"enc{lvl}b", ref), f"enc{lvl}b upstream gradient")
+        act_close(H(A[f"enc{lvl}b"]["g"]), masked(f"enc{lvl}b", ref), f"enc{lvl}b upstream gradient")
 
 
 @pytest.mark.parametrize("cfg", [SMALL[0], SMALL[3]], ids=lambda c: c.name)
