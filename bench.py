@@ -23,6 +23,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_FP32_TFLOPS = 157.3  # MI355X fp32 matrix (and vector) peak
+PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
 PEAK_HBM_GBS = 8000.0
 
 
@@ -188,15 +189,18 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     cfg = synth.CONFIGS[args.workload]
-    plan = rc.Plan.from_config(cfg)
+    bf = args.dtype == "bf16"
+    adt = torch.bfloat16 if bf else torch.float32      # storage of x, w, g, ypool, dx; dw is fp32 either way
+    plan = rc.Plan.from_config(cfg, dtype=rc.BF16 if bf else rc.F32)
     Q = plan.orientations()[0]
-    x = torch.from_numpy(synth.make_x(cfg)).cuda()
-    w = torch.from_numpy(synth.make_w(cfg)).cuda()
-    g = torch.from_numpy(synth.make_g(cfg)).cuda()
-    yp = torch.empty((cfg.N, plan.Cpooled, plan.Ho, plan.Wo), device="cuda")
+    x = torch.from_numpy(synth.make_x(cfg)).cuda().to(adt)
+    w = torch.from_numpy(synth.make_w(cfg)).cuda().to(adt)
+    g = torch.from_numpy(synth.make_g(cfg)).cuda().to(adt)
+    yp = torch.empty((cfg.N, plan.Cpooled, plan.Ho, plan.Wo), dtype=adt, device="cuda")
     idx = torch.empty((cfg.N, plan.Cpooled, plan.Ho, plan.Wo), dtype=torch.uint8, device="cuda")
     dx = torch.empty_like(x)
-    dw = torch.empty_like(w)
+    dw = torch.empty(w.shape, dtype=torch.float32, device="cuda")
+    peak = PEAK_BF16_TFLOPS if bf else PEAK_FP32_TFLOPS
     plan.workspace()
 
     def step(ev=None):
@@ -239,13 +243,13 @@ def main():
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get(f"{args.workload}:{names[dom]}:{plan.kernel_name(dom)}")
+            traffic = json.load(open(tpath)).get(f"{args.workload}:{names[dom]}:{plan.kernel_name(dom)}")   # fp32 kernels only
         except Exception:
             traffic = None
     out = {
         "metric": "rotconv_fwd_bwd_tflops", "value": 3.0 * fa / (ms_step * 1e-3) / 1e12, "unit": "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
         "config": {
             "workload": f"{cfg.name}: N={cfg.N} Cin={cfg.Cin} Cout={cfg.Cout} {cfg.H}x{cfg.W} k={cfg.k} R={cfg.R} "
                         f"{cfg.mode} G={cfg.G} stride={cfg.stride} pad={cfg.pad}, fused fwd+bwd_data+bwd_weight",
@@ -257,12 +261,12 @@ def main():
         },
         "roofline": {
             "bound": "mfma", "kernel": f"{names[dom]} ({plan.kernel_name(dom)})", "achieved": achieved,
-            "peak": PEAK_FP32_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_TFLOPS, "traffic": traffic,
+            "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak, "traffic": traffic,
         },
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, Q)
-    if args.workload == "C2" and not args.no_unet:
+    if args.workload == "C2" and not args.no_unet and not bf:
         # the second half of the headline metric: ms per UNet-shaped training step at R=4 and R=16
         del x, w, g, yp, idx, dx, dw
         out["unet_train_step"] = {n: bench_unet(n, 5, 2) for n in ("C4", "C5")}

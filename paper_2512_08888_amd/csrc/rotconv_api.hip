@@ -106,8 +106,10 @@ int rotconv_plan_create(const rotconv_desc* desc, rotconv_plan** out) {
   p->n_w = (size_t)p->B * p->d.Cout * p->d.Cin * p->kk;
   p->n_yp = (size_t)p->d.N * p->d.Cout * p->ng * hw_out;
   p->n_yu = (size_t)p->d.N * p->d.Cout * p->d.R * hw_out;
-  if (p->d.dtype == ROTCONV_BF16)
+  if (p->d.dtype == ROTCONV_BF16) {
     p->ws_bytes = align256(p->n_x * 4) + align256(p->n_w * 4) + align256(p->n_yu * 4) + p->ws_inner;
+    p->native16[0] = p->fast[0] && p4_fwd_bf16_supported(p) ? 1 : 0;
+  }
   *out = p;
   return ROTCONV_OK;
 }
@@ -323,6 +325,15 @@ int rotconv_fwd(const rotconv_plan* plan, const void* x, const void* w, void* y,
   if (!is_bf16(plan)) return f32_rotconv_fwd(plan, x, w, y, ws, ws_bytes, stream);
   if (!ws || ws_bytes < plan->ws_bytes) return ROTCONV_ERR_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);
+  if (plan->native16[0] && aligned(x, 4) && aligned(w, 2) && aligned(ws, 256) && aligned(y, 16)) {
+    rotconv_plan* p = const_cast<rotconv_plan*>(plan);
+    const int rc = ensure_device_tables(p);
+    if (rc) return rc;
+    uint16_t* wt = static_cast<uint16_t*>(ws);
+    launch_p4_pack_fwd_bf16(p, h16(w), wt, st);
+    launch_p4_fwd_bf16(p, kOutUnpooled, h16(x), wt, y, nullptr, st);
+    return finish();
+  }
   const Stage s = carve(plan, ws, ws_bytes);
   launch_widen(h16(x), s.x, plan->n_x, st);
   launch_widen(h16(w), s.w, plan->n_w, st);
@@ -379,6 +390,27 @@ int rotconv_pool_fwd(const rotconv_plan* plan, const void* x, const void* w, voi
   if (!is_bf16(plan)) return f32_rotconv_pool_fwd(plan, x, w, ypool, idx, ws, ws_bytes, stream);
   if (!ws || ws_bytes < plan->ws_bytes) return ROTCONV_ERR_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);
+  const int pmode = plan->native16[0] ? p4_fwd_pool_mode(plan) : kOutUnpooled;
+  if (pmode != kOutUnpooled && aligned(x, 4) && aligned(w, 2) && aligned(ws, 256) && aligned(ypool, 16) &&
+      aligned(idx, 8)) {
+    // bf16 tensors straight into the bf16 matrix-core kernel; scratch laid out as in the fp32 path
+    rotconv_plan* p = const_cast<rotconv_plan*>(plan);
+    const int rc = ensure_device_tables(p);
+    if (rc) return rc;
+    uint16_t* wt = static_cast<uint16_t*>(ws);
+    char* extra = static_cast<char*>(ws) + align256(p4_fwd_pack_floats(p) * sizeof(float));
+    const size_t hw = (size_t)p->d.H * p->d.W;
+    launch_p4_pack_fwd_bf16(p, h16(w), wt, st);
+    if (pmode == kOutPooled) {
+      launch_p4_fwd_bf16(p, pmode, h16(x), wt, ypool, idx, st);
+    } else {
+      float* pv = reinterpret_cast<float*>(extra);
+      uint8_t* pi = reinterpret_cast<uint8_t*>(extra + align256((size_t)p->host.Q * p->d.N * p->d.Cout * hw * 4));
+      launch_p4_fwd_bf16(p, pmode, h16(x), wt, pv, pi, st);
+      launch_p4_combine_bf16(p, pv, pi, static_cast<uint16_t*>(ypool), idx, st);
+    }
+    return finish();
+  }
   const Stage s = carve(plan, ws, ws_bytes);
   launch_widen(h16(x), s.x, plan->n_x, st);
   launch_widen(h16(w), s.w, plan->n_w, st);
@@ -430,6 +462,7 @@ const char* rotconv_status_string(int status) {
 
 const char* rotconv_plan_kernel_name(const rotconv_plan* plan, int pass) {
   if (!plan || pass < 0 || pass > 2) return "none";
+  if (plan->d.dtype == ROTCONV_BF16 && plan->native16[pass]) return "mfma_p4_bf16";
   return plan->fast[pass] ? "mfma_p4" : "generic";
 }
 

@@ -66,6 +66,9 @@ struct rotconv_plan {
   size_t n_x = 0, n_w = 0, n_yp = 0, n_yu = 0;   // elements of input, base weights, pooled and unpooled output
   // kernel selection per pass (0 fwd, 1 bwd_data, 2 bwd_weight)
   int fast[3] = {0, 0, 0};
+  // bf16 plans: the pass has a kernel that reads and writes bfloat16 directly (bf16 matrix cores); the
+  // other passes run the fp32 kernels on widened copies
+  int native16[3] = {0, 0, 0};
   int bwdw_splits = 1;          // pixel splits of the generic weight-gradient kernel
 };
 

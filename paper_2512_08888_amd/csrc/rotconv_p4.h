@@ -33,6 +33,16 @@ void launch_p4_fwd(const rotconv_plan* p, int out_mode, const float* x, const fl
 void launch_p4_combine(const rotconv_plan* p, const float* pv, const uint8_t* pi, float* ypool, uint8_t* idx,
                        hipStream_t st);
 
+// forward on bfloat16 tensors (bf16 matrix cores, fp32 accumulation); out_val is bf16 for the pooled and
+// unpooled modes and fp32 for the per-bank candidates
+bool p4_fwd_bf16_supported(const rotconv_plan* p);
+size_t p4_fwd_bf16_pack_bytes(const rotconv_plan* p);
+void launch_p4_pack_fwd_bf16(const rotconv_plan* p, const uint16_t* w, uint16_t* wt, hipStream_t st);
+void launch_p4_fwd_bf16(const rotconv_plan* p, int out_mode, const uint16_t* x, const uint16_t* wt, void* out_val,
+                        uint8_t* out_idx, hipStream_t st);
+void launch_p4_combine_bf16(const rotconv_plan* p, const float* pv, const uint8_t* pi, uint16_t* ypool, uint8_t* idx,
+                            hipStream_t st);
+
 // input gradient
 struct P4BwdGeom {
   int N, Cin, CinPad, H, W, Cout, CoutPad, R, Q, ng;

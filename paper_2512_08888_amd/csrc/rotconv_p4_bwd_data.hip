@@ -20,6 +20,7 @@
 // double-buffered, a quarter chunk per pipeline stage, one barrier per chunk.
 #include <hip/hip_runtime.h>
 
+#include "rotconv_bf16.h"
 #include "rotconv_kernels.h"
 #include "rotconv_p4.h"
 
@@ -301,7 +302,7 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gp
 __global__ __launch_bounds__(256) void k_p4_pack_bwd(const float* __restrict__ w, float* __restrict__ wd,
                                                      const int32_t* __restrict__ fq_src,
                                                      const float* __restrict__ fq_coef, int Q, int CoutPad,
-                                                     int CinPad, int Cin, int Cout) {
+                                                     int CinPad, int Cin, int Cout, int round16) {
   const int total = Q * CoutPad * 9 * CinPad;
   const int e = blockIdx.x * 256 + threadIdx.x;
   if (e >= total) return;
@@ -321,7 +322,7 @@ __global__ __launch_bounds__(256) void k_p4_pack_bwd(const float* __restrict__ w
       if (s >= 0) acc += fq_coef[(q * 9 + u) * kMaxNnz + z] * w[((s / 9) * slices + co * Cin + ci) * 9 + s % 9];
     }
   }
-  wd[e] = acc;
+  wd[e] = round16 ? bf16_to_f32(f32_to_bf16(acc)) : acc;   // bf16 plans keep the expanded banks in bf16 precision
 }
 
 }  // namespace
@@ -355,7 +356,7 @@ void launch_p4_pack_bwd(const rotconv_plan* p, const float* w, float* wd, hipStr
   const P4BwdGeom g = p4_bwd_data_geom(p);
   const int total = g.Q * g.CoutPad * 9 * g.CinPad;
   hipLaunchKernelGGL(k_p4_pack_bwd, dim3((total + 255) / 256), dim3(256), 0, st, w, wd, p->dev.fq_src, p->dev.fq_coef,
-                     g.Q, g.CoutPad, g.CinPad, g.Cin, g.Cout);
+                     g.Q, g.CoutPad, g.CinPad, g.Cin, g.Cout, p->d.dtype == ROTCONV_BF16 ? 1 : 0);
 }
 
 void launch_p4_bwd_data(const rotconv_plan* p, const float* gpool, const uint8_t* idx, const float* wd, float* dx,

@@ -29,8 +29,10 @@
 // both neighbours it holds.
 #include <hip/hip_runtime.h>
 
+#include "rotconv_bf16.h"
 #include "rotconv_kernels.h"
 #include "rotconv_p4.h"
+#include "rotconv_p4_taps.h"
 
 namespace rotconv {
 namespace {
@@ -38,16 +40,6 @@ namespace {
 typedef float f4 __attribute__((ext_vector_type(4)));
 
 constexpr int KC = 8;  // K-steps (of 4 channels) per prefetch chunk
-
-// Row / column of base tap u inside the filter turned by s quarter turns (Eq. 8).
-__device__ __host__ constexpr int tap_i(int s, int u) {
-  return s == 0 ? u / 3 : s == 1 ? 2 - u % 3 : s == 2 ? 2 - u / 3 : u % 3;
-}
-__device__ __host__ constexpr int tap_j(int s, int u) {
-  return s == 0 ? u % 3 : s == 1 ? u / 3 : s == 2 ? 2 - u % 3 : 2 - u / 3;
-}
-// Index of non-centre tap u in the 8-entry edge exchange arrays.
-__device__ __host__ constexpr int edge_slot(int u) { return u < 4 ? u : u - 1; }
 
 // UNPOOLED: write every orientation (rotconv_fwd); else max + arg-max over the bank's rotations.
 // FASTW:    W % 8 == 0 and no wave chain reaches beyond the row: no load masks, vector stores.
@@ -393,7 +385,7 @@ __global__ __launch_bounds__(256) void k_p4_combine(const float* __restrict__ pv
 __global__ __launch_bounds__(256) void k_p4_pack_fwd(const float* __restrict__ w, float* __restrict__ wt,
                                                      const int32_t* __restrict__ fq_src,
                                                      const float* __restrict__ fq_coef, int Q, int CB, int CinPad,
-                                                     int Cin, int Cout) {
+                                                     int Cin, int Cout, int round16) {
   const int total = Q * CB * CinPad * 144;
   const int e = blockIdx.x * 256 + threadIdx.x;
   if (e >= total) return;
@@ -412,7 +404,7 @@ __global__ __launch_bounds__(256) void k_p4_pack_fwd(const float* __restrict__ w
       if (s >= 0) acc += fq_coef[(q * 9 + u) * kMaxNnz + z] * w[((s / 9) * slices + co * Cin + ci) * 9 + s % 9];
     }
   }
-  wt[e] = acc;
+  wt[e] = round16 ? bf16_to_f32(f32_to_bf16(acc)) : acc;   // bf16 plans keep the expanded banks in bf16 precision
 }
 
 template <int NWX, int NWY, bool UNPOOLED, bool FASTW, bool STREAM>
@@ -434,7 +426,8 @@ void launch_t(const P4Geom& g, bool fastw, bool stream, const float* x, const fl
     if (fastw) launch_i<NWX, NWY, true, true, false>(g, x, wt, rot_of, ov, oi, st);
     else launch_i<NWX, NWY, true, false, false>(g, x, wt, rot_of, ov, oi, st);
   } else if (stream) {
-    launch_i<NWX, NWY, false, true, true>(g, x, wt, rot_of, ov, oi, st);
+    if (fastw) launch_i<NWX, NWY, false, true, true>(g, x, wt, rot_of, ov, oi, st);
+    else launch_i<NWX, NWY, false, false, true>(g, x, wt, rot_of, ov, oi, st);   // a wave chain overhangs the row
   } else if (fastw) {
     launch_i<NWX, NWY, false, true, false>(g, x, wt, rot_of, ov, oi, st);
   } else {
@@ -540,7 +533,7 @@ void launch_p4_pack_fwd(const rotconv_plan* p, const float* w, float* wt, hipStr
   const int CinPad = (p->d.Cin + 31) / 32 * 32, CB = (p->d.Cout + 15) / 16;
   const int total = p->host.Q * CB * CinPad * 144;
   hipLaunchKernelGGL(k_p4_pack_fwd, dim3((total + 255) / 256), dim3(256), 0, st, w, wt, p->dev.fq_src, p->dev.fq_coef,
-                     p->host.Q, CB, CinPad, p->d.Cin, p->d.Cout);
+                     p->host.Q, CB, CinPad, p->d.Cin, p->d.Cout, p->d.dtype == ROTCONV_BF16 ? 1 : 0);
 }
 
 void launch_p4_fwd(const rotconv_plan* p, int out_mode, const float* x, const float* wt, float* out_val,

@@ -1,0 +1,528 @@
+// Fast forward kernel for 3x3, stride 1, pad 1 with bfloat16 tensors: shared-product rotation
+// convolution (paper Eq. 8) on the bf16 matrix cores, fp32 accumulation.
+//
+// Same decomposition as the fp32 kernel: per first-quadrant bank the nine per-tap channel
+// contractions P_u[co,h,x] = sum_ci F[co,ci,u] X[ci,h,x] are formed once, here with
+// v_mfma_f32_16x16x32_bf16 (M = 16 pixels, N = 16 filters, K = 32 input channels), and placed at the
+// four quarter-turn positions in registers; max / arg-max over the bank's rotations are taken on the
+// fp32 sums and the winner is rounded to bf16 once.  A wave owns 16 filters x 32 consecutive pixels
+// of one row and walks down its band of rows.
+//
+// What differs from the fp32 kernel is the operand feed.  A lane loads one dword = the pixel pair
+// (2m, 2m+1) of one channel; eight channels give, after eight byte permutes, the lane's K-slice of
+// both pixel tiles.  With 32 channels per matrix instruction the contraction of a 32-channel chunk
+// is only 18 instructions of 16 clocks, far shorter than the memory latency, so the input rows are
+// prefetched ND = 2 chunks (64 channels) ahead through a ring of register slots, across row ends.
+// The filter block [chunk][tap][k-group][filter][8 channels] sits in LDS (one 16-byte read per lane
+// and tap, conflict free); blocks deeper than 480 channels are streamed in stages of ND chunks.
+// With the contraction this cheap the kernel is bound by the placement adds on the vector ALU.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+
+#include "rotconv_bf16.h"
+#include "rotconv_kernels.h"
+#include "rotconv_p4.h"
+#include "rotconv_p4_taps.h"
+
+namespace rotconv {
+namespace {
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf8 __attribute__((ext_vector_type(8)));
+typedef float f2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
+
+constexpr int CHB = 9 * 4 * 16 * 8 * 2;   // bytes of one 32-channel chunk of a 16-filter block (9216)
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f2{lo, hi}, bf2));
+}
+
+// ND:       chunks of 32 channels the input prefetch runs ahead (CinPad is a multiple of 32 * ND).
+// UNPOOLED: write every orientation (rotconv_fwd); else max + arg-max over the bank's rotations.
+// FASTW:    W % 8 == 0 and no wave chain reaches beyond the row: no load masks, vector stores.
+// STREAM:   the filter block does not fit LDS: stream it in stages of ND chunks.
+// CPAD:     CinPad > Cin: channel offsets are clamped to the last real channel (its taps are zero).
+template <int NWX, int NWY, int ND, bool UNPOOLED, bool FASTW, bool STREAM, bool CPAD>
+__global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd_bf16(const uint16_t* __restrict__ x,
+                                                                const uint16_t* __restrict__ wt,
+                                                                const int32_t* __restrict__ rot_of,
+                                                                void* __restrict__ out_val,
+                                                                uint8_t* __restrict__ out_idx, P4Geom g) {
+  constexpr int NW = NWX * NWY;
+  constexpr int NT = 64 * NW;
+  constexpr int STB = ND * CHB;            // bytes of one streaming stage
+  extern __shared__ __attribute__((aligned(16))) char smem_raw[];
+  char* Wl = smem_raw;                     // resident: [nchunk][CHB]; streamed: [2][STB]
+  const int nchunk = g.CinPad / 32;
+  float* EL = reinterpret_cast<float*>(smem_raw + (STREAM ? 2 * STB : nchunk * CHB));  // [2][NW][8][16]
+  float* ER = EL + 2 * NW * 128;
+
+  // XCD-aware unit decode: consecutive units (same image rows, different filter blocks / banks) go to
+  // the same XCD so they share its L2 copy of the input.
+  const int per_xcd = (g.units + 7) / 8;
+  int v = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  if (v >= g.units) return;
+  const int cb = v % g.CB; v /= g.CB;
+  const int q = v % g.Q; v /= g.Q;
+  const int seg = v % g.nseg; v /= g.nseg;
+  const int bg = v % g.nbg;
+  const int n = v / g.nbg;
+
+  const int tid = threadIdx.x;
+  const char* wsrc = reinterpret_cast<const char*>(wt) + (size_t)(q * g.CB + cb) * nchunk * CHB;
+  constexpr int WPT = (STB / 16 + NT - 1) / NT;   // 16-byte units per thread and stage when streaming
+  u4 wreg[STREAM ? WPT : 1];
+  auto wload = [&](int stage) {
+#pragma unroll
+    for (int k = 0; k < WPT; ++k) {
+      const int e = tid + k * NT;
+      if (e < STB / 16) wreg[k] = reinterpret_cast<const u4*>(wsrc + (size_t)stage * STB)[e];
+    }
+  };
+  auto wstore = [&](int buf) {
+#pragma unroll
+    for (int k = 0; k < WPT; ++k) {
+      const int e = tid + k * NT;
+      if (e < STB / 16) reinterpret_cast<u4*>(Wl + buf * STB)[e] = wreg[k];
+    }
+  };
+  if (STREAM) {
+    wload(0);
+    wstore(0);
+  } else {
+    const u4* src = reinterpret_cast<const u4*>(wsrc);
+    u4* dst = reinterpret_cast<u4*>(Wl);
+    const int n16 = nchunk * (CHB / 16);
+    for (int i = tid; i < n16; i += NT) dst[i] = src[i];
+  }
+  __syncthreads();
+
+  const int wave = __builtin_amdgcn_readfirstlane(tid / 64), lane = tid % 64;
+  const int wx = wave % NWX, wy = wave / NWX;
+  const int lg = lane / 16, lc = lane % 16;
+  const int x0 = g.seg_xorg[seg] + wx * 32;
+  const int out_lo = g.seg_lo[seg], out_hi = g.seg_hi[seg];
+  const int y0 = (bg * NWY + wy) * g.TY;
+  const int nsteps = g.TY + 2;
+  const int HW = g.H * g.W;
+
+  int rot[4];
+#pragma unroll
+  for (int s = 0; s < 4; ++s) rot[s] = rot_of[q * 4 + s];
+
+  // A-operand loads: lane (lc, lg) reads the dword X[ci = 32*chunk + 8*lg + j][h][x0 + 2*lc .. +1],
+  // j = 0..7.  Rows outside the image are never multiplied, channels beyond Cin meet zero taps, so both
+  // only need a valid address; pixels beyond W must read as zero (only when W % 32 != 0).
+  const int pxa = x0 + 2 * lc;
+  const bool px_ok = pxa < g.W;
+  const uint16_t* xn = x + (size_t)n * g.Cin * HW + (px_ok ? pxa : 0);
+  uint32_t lgoff = (uint32_t)(8 * lg) * (uint32_t)HW;
+  asm volatile("" : "+v"(lgoff));   // opaque: the chunk / slot part of the offset stays scalar
+  const uint32_t off_last = (uint32_t)(g.Cin - 1) * (uint32_t)HW;
+  auto row_ptr = [&](int t) -> const uint16_t* {
+    const int h = min(max(y0 - 1 + t, 0), g.H - 1);
+    return xn + (size_t)h * g.W;
+  };
+  auto load_a = [&](const uint16_t* rp, int c, int j) -> uint32_t {
+    uint32_t off = (uint32_t)(c * 32 + j) * (uint32_t)HW + lgoff;
+    if (CPAD) off = min(off, off_last);
+    const uint32_t v2 = *reinterpret_cast<const uint32_t*>(rp + off);
+    if (FASTW) return v2;
+    return px_ok ? v2 : 0u;
+  };
+
+  float accA[4][8], accB[4][8];
+#pragma unroll
+  for (int s = 0; s < 4; ++s)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { accA[s][j] = 0.f; accB[s][j] = 0.f; }
+
+  // ring of ND chunk slots: slot i holds chunk (cc + i) of the current group; it is refilled with the
+  // chunk ND further on (of this row, or of the next row's first group) right after it has been packed
+  uint32_t ring[ND][8];
+  {
+    const uint16_t* rp = row_ptr(0);
+#pragma unroll
+    for (int i = 0; i < ND; ++i)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) ring[i][j] = load_a(rp, i, j);
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+  }
+  const char* wl_lane = Wl + lane * 16;
+  int seq = 0;                           // groups done (streaming: LDS buffer parity)
+
+  for (int t = 0; t < nsteps; ++t) {
+    const int h = y0 - 1 + t;
+    const bool row_ok = h >= 0 && h < g.H;
+    const uint16_t* rp_cur = row_ptr(t);
+    const uint16_t* rp_nxt = row_ptr(t + 1);
+    f4 P[9][2];
+
+    // One group of ND chunks.  Per chunk: pack the slot into the two tiles' A operands, refill the
+    // slot, then 9 taps x 2 tiles of matrix instructions with the B operand read from LDS two taps
+    // ahead.  Scheduling fences keep loads and LDS reads where they are issued.
+    auto group = [&](int cc, bool mul, bool first) {
+      const bool last = cc + ND == nchunk;
+      const uint16_t* rp = last ? rp_nxt : rp_cur;
+      const int cn = last ? 0 : cc + ND;
+      if (STREAM) wload(last ? 0 : cc / ND + 1);
+      if (mul) {
+        const char* wc = STREAM ? wl_lane + (seq & 1) * STB : wl_lane + (size_t)cc * CHB;
+        u4 bw[3];
+        bw[0] = *reinterpret_cast<const u4*>(wc);
+        bw[1] = *reinterpret_cast<const u4*>(wc + 1024);
+#pragma unroll
+        for (int i = 0; i < ND; ++i) {
+          u4 a0, a1;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            a0[j] = __builtin_amdgcn_perm(ring[i][2 * j + 1], ring[i][2 * j], 0x05040100u);
+            a1[j] = __builtin_amdgcn_perm(ring[i][2 * j + 1], ring[i][2 * j], 0x07060302u);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int j = 0; j < 8; ++j) ring[i][j] = load_a(rp, cn + i, j);
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int u = 0; u < 9; ++u) {
+            const int e = i * 9 + u;               // tap counter inside the group
+            if (e + 2 < ND * 9) bw[(e + 2) % 3] = *reinterpret_cast<const u4*>(wc + (e + 2) * 1024);
+            __builtin_amdgcn_sched_barrier(0);
+            const f4 zero = f4{0.f, 0.f, 0.f, 0.f};
+            const bf8 b = __builtin_bit_cast(bf8, bw[e % 3]);
+            P[u][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf8, a0), b,
+                                                              first && i == 0 ? zero : P[u][0], 0, 0, 0);
+            P[u][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf8, a1), b,
+                                                              first && i == 0 ? zero : P[u][1], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < ND; ++i)
+#pragma unroll
+          for (int j = 0; j < 8; ++j) ring[i][j] = load_a(rp, cn + i, j);
+      }
+      if (STREAM) {
+        wstore((seq + 1) & 1);
+        __syncthreads();
+      }
+      ++seq;
+    };
+    if (row_ok) {
+      group(0, true, true);
+      for (int cc = ND; cc < nchunk; cc += ND) group(cc, true, false);
+    } else {
+#pragma unroll
+      for (int u = 0; u < 9; ++u) { P[u][0] = f4{0.f, 0.f, 0.f, 0.f}; P[u][1] = f4{0.f, 0.f, 0.f, 0.f}; }
+      for (int cc = 0; cc < nchunk; cc += ND) group(cc, false, false);
+      // rare path (rows above / below the image): drain its loads here so that the hot loop's wait
+      // counters only ever see the refills issued by the hot loop itself
+      __builtin_amdgcn_s_waitcnt(0x0F70);
+    }
+
+    // ---- neighbour values across lane groups and waves --------------------------
+    // Lane (lg, lc) holds filter lc, pixels x0 + 8*lg + j, j = 2*i + b for P[u][b][i].
+    float nbL[9], nbR[9];  // P_u at pixel (first - 1) resp. (last + 1) of this lane's 8 pixels
+    const int par = t & 1;
+    float* el = EL + (par * NW + wave) * 128 + lc;
+    float* er = ER + (par * NW + wave) * 128 + lc;
+    if (lg == 0) {
+#pragma unroll
+      for (int u = 0; u < 9; ++u)
+        if (u != 4) el[edge_slot(u) * 16] = P[u][0][0];
+    }
+    if (lg == 3) {
+#pragma unroll
+      for (int u = 0; u < 9; ++u)
+        if (u != 4) er[edge_slot(u) * 16] = P[u][1][3];
+    }
+    const int addr_up = ((lane + 16) & 63) * 4, addr_dn = ((lane + 48) & 63) * 4;
+#pragma unroll
+    for (int u = 0; u < 9; ++u) {
+      if (u == 4) { nbL[u] = 0.f; nbR[u] = 0.f; continue; }
+      // sources pinned in VGPRs of their own: an accumulator element handed straight to the
+      // cross-lane read selected the wrong element
+      float first_px = P[u][0][0], last_px = P[u][1][3];
+      asm volatile("" : "+v"(first_px), "+v"(last_px));
+      nbR[u] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(addr_up, __builtin_bit_cast(int, first_px)));
+      nbL[u] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(addr_dn, __builtin_bit_cast(int, last_px)));
+    }
+    __syncthreads();
+    if (NWX > 1) {
+      const float* eln = EL + (par * NW + wave + 1) * 128 + lc;  // right neighbour's left edge
+      const float* erp = ER + (par * NW + wave - 1) * 128 + lc;  // left neighbour's right edge
+      const bool at_r = lg == 3, at_l = lg == 0;
+      const bool has_r = wx + 1 < NWX, has_l = wx > 0;
+#pragma unroll
+      for (int u = 0; u < 9; ++u) {
+        if (u == 4) continue;
+        const float vr = has_r ? eln[edge_slot(u) * 16] : 0.f;
+        const float vl = has_l ? erp[edge_slot(u) * 16] : 0.f;
+        nbR[u] = at_r ? vr : nbR[u];
+        nbL[u] = at_l ? vl : nbL[u];
+      }
+    } else {
+#pragma unroll
+      for (int u = 0; u < 9; ++u) {
+        nbR[u] = lg == 3 ? 0.f : nbR[u];
+        nbL[u] = lg == 0 ? 0.f : nbL[u];
+      }
+    }
+
+    // ---- place the row of products at the rotated positions (Eq. 8) --------------
+    const int y = h - 1;                       // output row completed by this step
+    const int px0 = x0 + 8 * lg;               // first of this lane's 8 pixels
+    const int co = cb * 16 + lc;
+    const bool fin = t >= 2 && y < g.H && co < g.Cout && px0 >= out_lo && px0 < out_hi;
+    float best[8];
+    uint32_t pk[2] = {0u, 0u};                 // arg-max bytes of the lane's 8 pixels
+    int grp_r = 0;                             // any rotation of the bank (its pool group)
+    bool none = true;
+    auto place = [&](int s, int j, float& yfin) {
+      float t0 = 0.f, t1 = 0.f, t2 = 0.f;
+#pragma unroll
+      for (int u = 0; u < 9; ++u) {
+        const int jj = j + tap_j(s, u) - 1;
+        const float val = jj < 0 ? nbL[u] : jj > 7 ? nbR[u] : P[u][jj & 1][jj >> 1];
+        const int ti = tap_i(s, u);
+        if (ti == 0) t0 += val;
+        else if (ti == 1) t1 += val;
+        else t2 += val;
+      }
+      yfin = accA[s][j] + t2;         // rows h-2, h-1, h are in: output row h-1 done
+      accA[s][j] = accB[s][j] + t1;   // output row h has rows h-1, h
+      accB[s][j] = t0;                // output row h+1 has row h
+    };
+    auto store8_bf16 = [&](uint16_t* o, const float* v8) {
+      if (FASTW) {
+        *reinterpret_cast<u4*>(o) = u4{pack_bf16(v8[0], v8[1]), pack_bf16(v8[2], v8[3]), pack_bf16(v8[4], v8[5]),
+                                       pack_bf16(v8[6], v8[7])};
+      } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+          if (px0 + j < min(g.W, out_hi)) o[j] = (uint16_t)(pack_bf16(v8[j], 0.f) & 0xffffu);
+      }
+    };
+    if (UNPOOLED) {
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        float yfin[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) place(s, j, yfin[j]);
+        if (fin && rot[s] >= 0)
+          store8_bf16(static_cast<uint16_t*>(out_val) + (((size_t)n * g.Cout + co) * g.R + rot[s]) * HW +
+                          (size_t)y * g.W + px0, yfin);
+      }
+    } else {
+#pragma unroll
+      for (int s = 0; s < 4; ++s)
+        if (rot[s] >= 0) { grp_r = rot[s]; none = false; }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        float bv = 0.f;
+        int bi = 0;
+        bool have = false;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          float yv;
+          place(s, j, yv);
+          if (rot[s] >= 0) {          // wave-uniform
+            const bool gt = !have || yv > bv;
+            bv = gt ? yv : bv;
+            bi = gt ? rot[s] : bi;
+            have = true;
+          }
+        }
+        best[j] = bv;
+        pk[j >> 2] |= (uint32_t)bi << (8 * (j & 3));
+      }
+    }
+    if (!UNPOOLED && fin && !none) {
+      if (g.out_mode == kOutPooled) {
+        // every rotation of this bank lies in pool group (r mod ng); pooled channel = co*ng + group
+        const size_t chan = (size_t)n * g.Cout * g.ng + (size_t)co * g.ng + (grp_r % g.ng);
+        const size_t off = chan * HW + (size_t)y * g.W + px0;
+        store8_bf16(static_cast<uint16_t*>(out_val) + off, best);
+        if (FASTW) {
+          *reinterpret_cast<uint2*>(out_idx + off) = make_uint2(pk[0], pk[1]);
+        } else {
+#pragma unroll
+          for (int j = 0; j < 8; ++j)
+            if (px0 + j < min(g.W, out_hi)) out_idx[off + j] = (uint8_t)(pk[j >> 2] >> (8 * (j & 3)));
+        }
+      } else {  // kOutPartial: per-bank fp32 candidates [Q][N][Cout][H][W] (the max across banks is taken on fp32)
+        const size_t chan = ((size_t)q * g.N + n) * g.Cout + co;
+        const size_t off = chan * HW + (size_t)y * g.W + px0;
+        float* ov = static_cast<float*>(out_val);
+        if (FASTW) {
+          f4* o = reinterpret_cast<f4*>(ov + off);
+          o[0] = f4{best[0], best[1], best[2], best[3]};
+          o[1] = f4{best[4], best[5], best[6], best[7]};
+          *reinterpret_cast<uint2*>(out_idx + off) = make_uint2(pk[0], pk[1]);
+        } else {
+#pragma unroll
+          for (int j = 0; j < 8; ++j)
+            if (px0 + j < min(g.W, out_hi)) {
+              ov[off + j] = best[j];
+              out_idx[off + j] = (uint8_t)(pk[j >> 2] >> (8 * (j & 3)));
+            }
+        }
+      }
+    }
+  }
+}
+
+// Max over the per-bank fp32 candidates of a pool group that spans several banks, rounded to bf16.
+// Candidates [Q][N][Cout][HW]; group g of filter co collects banks q with (r mod ng) == g.
+__global__ __launch_bounds__(256) void k_p4_combine_bf16(const float* __restrict__ pv, const uint8_t* __restrict__ pi,
+                                                         const int32_t* __restrict__ rot_of,
+                                                         uint16_t* __restrict__ ypool, uint8_t* __restrict__ idx, int N,
+                                                         int Cout, int HW, int Q, int ng) {
+  const int p = blockIdx.x * 256 + threadIdx.x;
+  if (p >= HW) return;
+  const int chan = blockIdx.y, n = blockIdx.z;  // chan = co*ng + grp
+  const int co = chan / ng, grp = chan % ng;
+  float best = 0.f;
+  int bi = 255;
+  for (int q = 0; q < Q; ++q) {
+    int r0 = -1;
+    for (int s = 0; s < 4; ++s)
+      if (rot_of[q * 4 + s] >= 0) { r0 = rot_of[q * 4 + s]; break; }
+    if (r0 < 0 || r0 % ng != grp) continue;
+    const size_t o = (((size_t)q * N + n) * Cout + co) * HW + p;
+    const float vq = pv[o];
+    const int iq = pi[o];
+    if (bi == 255 || vq > best || (vq == best && iq < bi)) { best = vq; bi = iq; }
+  }
+  const size_t o = ((size_t)n * Cout * ng + chan) * HW + p;
+  ypool[o] = f32_to_bf16(best);
+  idx[o] = (uint8_t)bi;
+}
+
+// bf16 base bank(s) -> Q first-quadrant banks (Sec. III-D / Eq. 17 combination in fp32, rounded to bf16
+// once) in the LDS image layout [Q][CB][chunk][9 taps][4 k-groups][16 filters][8 channels]; zero for
+// padded filters / channels.
+__global__ __launch_bounds__(256) void k_p4_pack_fwd_bf16(const uint16_t* __restrict__ w, uint16_t* __restrict__ wt,
+                                                          const int32_t* __restrict__ fq_src,
+                                                          const float* __restrict__ fq_coef, int Q, int CB, int CinPad,
+                                                          int Cin, int Cout) {
+  const int total = Q * CB * CinPad * 144;
+  const int e = blockIdx.x * 256 + threadIdx.x;
+  if (e >= total) return;
+  const int c8 = e % 8;
+  const int f16 = (e / 8) % 16;
+  const int kg = (e / 128) % 4;
+  const int u = (e / 512) % 9;
+  const int chunk = (e / 4608) % (CinPad / 32);
+  const int cb = (e / (144 * CinPad)) % CB;
+  const int q = e / (144 * CinPad * CB);
+  const int co = cb * 16 + f16, ci = chunk * 32 + kg * 8 + c8;
+  float acc = 0.f;
+  if (co < Cout && ci < Cin) {
+    const int slices = Cout * Cin;
+#pragma unroll
+    for (int z = 0; z < kMaxNnz; ++z) {
+      const int s = fq_src[(q * 9 + u) * kMaxNnz + z];
+      if (s >= 0)
+        acc += fq_coef[(q * 9 + u) * kMaxNnz + z] * bf16_to_f32(w[((s / 9) * slices + co * Cin + ci) * 9 + s % 9]);
+    }
+  }
+  wt[e] = f32_to_bf16(acc);
+}
+
+// the ring holds two chunks (a deeper one spills registers): channels padded to a multiple of 64 beyond 32
+int cin_pad(int Cin) { return Cin <= 32 ? 32 : (Cin + 63) / 64 * 64; }
+int ring_depth(int Cin) { return std::min(2, cin_pad(Cin) / 32); }
+// Is the filter block of 16 filters too large to stay in LDS next to the edge arrays?
+bool needs_stream(int Cin) { return (size_t)(cin_pad(Cin) / 32) * CHB + 16384 > 160 * 1024; }
+
+template <int NWX, int NWY, int ND, bool UNPOOLED, bool FASTW, bool STREAM, bool CPAD>
+void launch_i(const P4Geom& g, const uint16_t* x, const uint16_t* wt, const int32_t* rot_of, void* ov, uint8_t* oi,
+              hipStream_t st) {
+  const size_t wbytes = STREAM ? (size_t)2 * ND * CHB : (size_t)(g.CinPad / 32) * CHB;
+  const size_t lds = wbytes + (size_t)4 * NWX * NWY * 128 * sizeof(float);
+  const int grid = (g.units + 7) / 8 * 8;
+  auto kern = k_p4_fwd_bf16<NWX, NWY, ND, UNPOOLED, FASTW, STREAM, CPAD>;
+  (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * NWX * NWY), lds, st, x, wt, rot_of, ov, oi, g);
+}
+
+template <int NWX, int NWY, int ND>
+void launch_t(const P4Geom& g, bool fastw, bool stream, bool cpad, const uint16_t* x, const uint16_t* wt,
+              const int32_t* rot_of, void* ov, uint8_t* oi, hipStream_t st) {
+  const bool unp = g.out_mode == kOutUnpooled;
+  // the specialised instances: pooled output, whole lanes inside the row; everything else takes the
+  // general instance (masks, clamped channels)
+  if (unp) launch_i<NWX, NWY, ND, true, false, false, true>(g, x, wt, rot_of, ov, oi, st);
+  else if (stream && fastw) launch_i<NWX, NWY, ND, false, true, true, false>(g, x, wt, rot_of, ov, oi, st);
+  else if (stream) launch_i<NWX, NWY, ND, false, false, true, false>(g, x, wt, rot_of, ov, oi, st);
+  else if (fastw && !cpad) launch_i<NWX, NWY, ND, false, true, false, false>(g, x, wt, rot_of, ov, oi, st);
+  else launch_i<NWX, NWY, ND, false, false, false, true>(g, x, wt, rot_of, ov, oi, st);
+}
+
+template <int NWX, int NWY>
+void launch_d(int nd, const P4Geom& g, bool fastw, bool stream, bool cpad, const uint16_t* x, const uint16_t* wt,
+              const int32_t* rot_of, void* ov, uint8_t* oi, hipStream_t st) {
+  switch (nd) {
+    case 1: launch_t<NWX, NWY, 1>(g, fastw, stream, cpad, x, wt, rot_of, ov, oi, st); break;
+    default: launch_t<NWX, NWY, 2>(g, fastw, stream, cpad, x, wt, rot_of, ov, oi, st); break;
+  }
+}
+
+}  // namespace
+
+// The bf16 kernel covers the fp32 kernel's shapes; the streamed variant (Cin > 480) is built for whole
+// lanes inside the row and unpadded channel counts.
+bool p4_fwd_bf16_supported(const rotconv_plan* p) {
+  if (!p4_fwd_supported(p)) return false;
+  const rotconv_desc& d = p->d;
+  if (needs_stream(d.Cin) && ((d.W & 31) || cin_pad(d.Cin) != d.Cin)) return false;
+  return true;
+}
+
+size_t p4_fwd_bf16_pack_bytes(const rotconv_plan* p) {
+  return (size_t)p->host.Q * ((p->d.Cout + 15) / 16) * cin_pad(p->d.Cin) * 144 * sizeof(uint16_t);
+}
+
+void launch_p4_pack_fwd_bf16(const rotconv_plan* p, const uint16_t* w, uint16_t* wt, hipStream_t st) {
+  const int CinPad = cin_pad(p->d.Cin), CB = (p->d.Cout + 15) / 16;
+  const int total = p->host.Q * CB * CinPad * 144;
+  hipLaunchKernelGGL(k_p4_pack_fwd_bf16, dim3((total + 255) / 256), dim3(256), 0, st, w, wt, p->dev.fq_src,
+                     p->dev.fq_coef, p->host.Q, CB, CinPad, p->d.Cin, p->d.Cout);
+}
+
+// out_val: bf16 [N][C'][H][W] (kOutPooled), bf16 [N][Cout*R][H][W] (kOutUnpooled) or fp32 per-bank
+// candidates (kOutPartial).
+void launch_p4_fwd_bf16(const rotconv_plan* p, int out_mode, const uint16_t* x, const uint16_t* wt, void* out_val,
+                        uint8_t* out_idx, hipStream_t st) {
+  P4Geom gs[4];
+  const int ng = p4_fwd_geoms(p, out_mode, gs, 4);
+  const bool stream = needs_stream(p->d.Cin);
+  const int nd = ring_depth(p->d.Cin);
+  for (int i = 0; i < ng; ++i) {
+    P4Geom& g = gs[i];
+    g.CinPad = cin_pad(p->d.Cin);
+    const bool fastw = (p->d.W & 7) == 0 && g.inside;
+    const bool cpad = g.CinPad != p->d.Cin;
+    switch (g.nwx) {
+      case 1: launch_d<1, 8>(nd, g, fastw, stream, cpad, x, wt, p->dev.rot_of, out_val, out_idx, st); break;
+      case 2: launch_d<2, 4>(nd, g, fastw, stream, cpad, x, wt, p->dev.rot_of, out_val, out_idx, st); break;
+      case 4: launch_d<4, 2>(nd, g, fastw, stream, cpad, x, wt, p->dev.rot_of, out_val, out_idx, st); break;
+      default: launch_d<8, 1>(nd, g, fastw, stream, cpad, x, wt, p->dev.rot_of, out_val, out_idx, st); break;
+    }
+  }
+}
+
+void launch_p4_combine_bf16(const rotconv_plan* p, const float* pv, const uint8_t* pi, uint16_t* ypool, uint8_t* idx,
+                            hipStream_t st) {
+  const int HW = p->d.H * p->d.W;
+  dim3 grid((HW + 255) / 256, p->d.Cout * p->ng, p->d.N);
+  hipLaunchKernelGGL(k_p4_combine_bf16, grid, dim3(256), 0, st, pv, pi, p->dev.rot_of, ypool, idx, p->d.N, p->d.Cout,
+                     HW, p->host.Q, p->ng);
+}
+
+}  // namespace rotconv

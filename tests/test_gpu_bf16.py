@@ -1,6 +1,9 @@
-"""GPU parity of bfloat16 plans (include/rotconv.h, dtype ROTCONV_BF16) against the fp64 oracle fed the same
-bf16-rounded inputs.  Bars: bf16 outputs within rel 1e-2 (tighter than the benchmark's 2e-2; one rounding to
-bf16 is 2^-9), the fp32 weight gradient within 1e-4, arg-max by the near-tie protocol of the fp32 tests."""
+"""GPU parity of bfloat16 plans (include/rotconv.h, dtype ROTCONV_BF16) against the fp64 oracle fed the values
+the GPU holds: the bf16-rounded inputs and base weights, and the rotated banks rounded to bf16 once more (a bf16
+plan keeps its expanded banks in bf16: they are the matrix-core operand; for exact quarter turns that rounding is
+the identity).  Bars: bf16 outputs within rel 1e-2 (tighter than the benchmark's 2e-2; one rounding to bf16 is
+2^-9), the fp32 weight gradient within 1e-4, arg-max by the near-tie protocol of the fp32 tests; on
+exact-arithmetic (dyadic) inputs everything bit for bit."""
 import numpy as np
 import pytest
 import torch
@@ -20,6 +23,15 @@ CASES = [
     LC("b_r16", N=1, Cin=8, H=10, W=64, Cout=6, R=16, mode="bilinear", seed=53),
     LC("b_ste_g4", N=1, Cin=4, H=8, W=16, Cout=4, R=8, mode="steerable", pool_group=4, seed=54),
     LC("b_s2k5", N=1, Cin=3, H=11, W=10, Cout=4, k=5, pad=2, stride=2, R=4, seed=55),
+    # shapes of the bf16 matrix-core kernels: two chunks in flight, padded channels, ragged rows, wave chains
+    # beyond the row, segmented rows, several bands, a streamed filter block
+    LC("b_c64", N=2, Cin=64, H=40, W=64, Cout=32, R=4, x_dist="absnormal", seed=56),
+    LC("b_c96", N=1, Cin=96, H=9, W=40, Cout=20, R=4, x_dist="absnormal", seed=57),
+    LC("b_w14", N=1, Cin=33, H=7, W=14, Cout=16, R=4, seed=58),
+    LC("b_c160_r16", N=1, Cin=160, H=12, W=32, Cout=24, R=16, mode="bilinear", x_dist="absnormal", seed=59),
+    LC("b_w320", N=1, Cin=16, H=6, W=320, Cout=16, R=4, seed=60),
+    LC("b_stream", N=1, Cin=512, H=8, W=32, Cout=16, R=4, x_dist="absnormal", seed=61),
+    LC("b_stream_w96", N=1, Cin=576, H=5, W=96, Cout=8, R=8, mode="bilinear", pool_group=4, x_dist="absnormal", seed=62),
 ]
 
 
@@ -27,6 +39,12 @@ def bf(a):
     """numpy fp32/fp64 -> (torch bf16 cuda tensor, the rounded values as fp64)."""
     t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(torch.bfloat16)
     return t.cuda(), t.to(torch.float64).numpy()
+
+
+def round_bf16(a):
+    """fp64 -> nearest-even bf16 -> fp64."""
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float64)).to(torch.float32).to(torch.bfloat16).to(
+        torch.float64).numpy()
 
 
 def nan16(*shape):
@@ -38,9 +56,25 @@ def f64(t):
     return t.to(torch.float64).cpu().numpy()
 
 
+def reference(cfg, x, w, ang):
+    """Forward of the oracle on the banks a bf16 plan multiplies with."""
+    w_rot = round_bf16(orc.expand_bank(w, cfg.R, ang, cfg.mode))
+    y = orc.rotconv_fwd(x, w_rot, cfg.stride, cfg.pad)
+    yp, idx = orc.orient_maxpool_fwd(y, cfg.G)
+    return w_rot, y, yp, idx
+
+
+def reference_bwd(cfg, x, w_rot, g, idx, ang):
+    dy = orc.orient_maxpool_bwd(g, idx, cfg.R, cfg.G)
+    dx = orc.rotconv_bwd_data(dy, w_rot, cfg.H, cfg.W, cfg.stride, cfg.pad)
+    dw = orc.reduce_bank_grad(orc.rotconv_bwd_weight(x, dy, cfg.k, cfg.stride, cfg.pad), ang, cfg.mode)
+    return dx, dw
+
+
 @pytest.mark.parametrize("cfg", CASES, ids=[c.name for c in CASES])
 def test_bf16_fused_calls(cfg):
     plan = rc.Plan.from_config(cfg, dtype=rc.BF16)
+    print(f"[case] bf16 fused {cfg.name} kernels {[plan.kernel_name(i) for i in range(3)]}", flush=True)
     ang = None if cfg.angles_deg is None else list(cfg.angles_deg)
     xd, x = bf(synth.make_x(cfg))
     wd, w = bf(synth.make_w(cfg))
@@ -48,19 +82,48 @@ def test_bf16_fused_calls(cfg):
     P = (cfg.N, plan.Cpooled, plan.Ho, plan.Wo)
     yp, idx = nan16(*P), torch.full(P, 255, dtype=torch.uint8, device="cuda")
     rc.rotconv_pool_fwd(plan, xd, wd, yp, idx)
-    y_ref, yp_ref, idx_ref, w_rot = orc.layer_fwd(x, w, cfg.R, ang, cfg.mode, cfg.stride, cfg.pad, cfg.G)
+    w_rot, y_ref, yp_ref, idx_ref = reference(cfg, x, w, ang)
     assert_close(f64(yp), yp_ref, f"{cfg.name} ypool", rtol=BF_RTOL)
     abs_terms = orc.rotconv_fwd(np.abs(x), np.abs(w_rot), cfg.stride, cfg.pad)
     idx_h = idx.cpu().numpy()
     check_idx(idx_h, y_ref, abs_terms, cfg.G, f"{cfg.name} idx")
     # backward on the GPU's own idx, both sides
-    dx_ref, dw_ref = orc.layer_bwd(x, w, g, idx_h, cfg.R, ang, cfg.mode, cfg.stride, cfg.pad, cfg.G)
+    dx_ref, dw_ref = reference_bwd(cfg, x, w_rot, g, idx_h, ang)
     dx = nan16(*xd.shape)
     rc.rotconv_pool_bwd_data(plan, gd, idx, wd, dx)
     assert_close(f64(dx), dx_ref, f"{cfg.name} dx", rtol=BF_RTOL)
     dw = torch.full(tuple(wd.shape), float("nan"), dtype=torch.float32, device="cuda")
     rc.rotconv_pool_bwd_weight(plan, xd, gd, idx, dw)
     assert_close(f64(dw), dw_ref, f"{cfg.name} dw (fp32)", rtol=RTOL)
+
+
+DYADIC = [CASES[1], CASES[5], CASES[7], LC("b_dy_stream", N=1, Cin=512, H=6, W=64, Cout=16, R=4, seed=63)]
+
+
+@pytest.mark.parametrize("cfg", DYADIC, ids=[c.name for c in DYADIC])
+def test_bf16_dyadic_bit_exact(cfg):
+    """Inputs on the exact-arithmetic grid (all representable in bf16; every fp32 partial sum exact in any
+    order): pooled output = the oracle's rounded once to bf16, arg-max and dX (rounded once) bit for bit."""
+    plan = rc.Plan.from_config(cfg, dtype=rc.BF16)
+    print(f"[case] bf16 dyadic {cfg.name}", flush=True)
+    xd, x = bf(synth.make_x_dyadic(cfg))
+    wd, w = bf(synth.make_w_dyadic(cfg))
+    gd, g = bf(synth.make_g_dyadic(cfg))
+    assert np.array_equal(x, synth.make_x_dyadic(cfg)) and np.array_equal(w, synth.make_w_dyadic(cfg))
+    P = (cfg.N, plan.Cpooled, plan.Ho, plan.Wo)
+    yp, idx = nan16(*P), torch.full(P, 255, dtype=torch.uint8, device="cuda")
+    rc.rotconv_pool_fwd(plan, xd, wd, yp, idx)
+    w_rot, y_ref, yp_ref, idx_ref = reference(cfg, x, w, None)
+    assert np.array_equal(idx.cpu().numpy(), idx_ref), f"{cfg.name}: arg-max not bit-exact"
+    assert np.array_equal(f64(yp), round_bf16(yp_ref)), f"{cfg.name}: pooled output not bit-exact"
+    dx_ref, dw_ref = reference_bwd(cfg, x, w_rot, g, idx_ref, None)
+    dx = nan16(*xd.shape)
+    rc.rotconv_pool_bwd_data(plan, gd, idx, wd, dx)
+    assert np.array_equal(f64(dx), round_bf16(dx_ref)), f"{cfg.name}: dx not bit-exact"
+    dw = torch.full(tuple(wd.shape), float("nan"), dtype=torch.float32, device="cuda")
+    rc.rotconv_pool_bwd_weight(plan, xd, gd, idx, dw)
+    if cfg.N * cfg.Ho * cfg.Wo <= (1 << 14):
+        assert np.array_equal(f64(dw), dw_ref), f"{cfg.name}: dw not bit-exact"
 
 
 def test_bf16_unfused_chain():

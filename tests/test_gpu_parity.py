@@ -53,6 +53,7 @@ TINY = [
     LC("t_w72", N=1, Cin=6, H=9, W=72, Cout=3, R=4, seed=35),
     LC("t_cin256", N=1, Cin=256, H=10, W=32, Cout=18, R=4, seed=36),
     LC("t_cin288_r16", N=1, Cin=288, H=9, W=64, Cout=16, R=16, mode="bilinear", seed=37),
+    LC("t_cin288_w96", N=1, Cin=288, H=6, W=96, Cout=8, R=4, seed=42),     # streamed block, chain beyond the row
     LC("t_w544_cin6", N=1, Cin=6, H=6, W=544, Cout=16, R=8, mode="steerable", pool_group=4, seed=38),
     # rows that end half way through a lane's eight pixels (W % 8 == 4), one and several strips, many rows
     LC("t_w4", N=2, Cin=5, H=10, W=4, Cout=6, R=4, seed=39),
