@@ -109,6 +109,7 @@ int rotconv_plan_create(const rotconv_desc* desc, rotconv_plan** out) {
   if (p->d.dtype == ROTCONV_BF16) {
     p->ws_bytes = align256(p->n_x * 4) + align256(p->n_w * 4) + align256(p->n_yu * 4) + p->ws_inner;
     p->native16[0] = p->fast[0] && p4_fwd_bf16_supported(p) ? 1 : 0;
+    p->native16[2] = p->fast[2] && p4_bwd_weight_bf16_supported(p) ? 1 : 0;
   }
   *out = p;
   return ROTCONV_OK;
@@ -441,6 +442,13 @@ int rotconv_pool_bwd_weight(const rotconv_plan* plan, const void* x, const void*
   if (!is_bf16(plan)) return f32_rotconv_pool_bwd_weight(plan, x, gpool, idx, dw, ws, ws_bytes, stream);
   if (!ws || ws_bytes < plan->ws_bytes) return ROTCONV_ERR_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);
+  if (plan->native16[2] && aligned(x, 16) && aligned(gpool, 16) && aligned(idx, 8) && aligned(ws, 16)) {
+    rotconv_plan* p = const_cast<rotconv_plan*>(plan);
+    const int rc = ensure_device_tables(p);
+    if (rc) return rc;
+    launch_p4_bwd_weight_bf16(p, h16(x), h16(gpool), idx, static_cast<float*>(ws), dw, st);
+    return finish();
+  }
   const Stage s = carve(plan, ws, ws_bytes);
   launch_widen(h16(x), s.x, plan->n_x, st);
   launch_widen(h16(gpool), s.y, plan->n_yp, st);

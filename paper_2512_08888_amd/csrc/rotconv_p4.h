@@ -75,5 +75,9 @@ P4BwdWGeom p4_bwd_weight_geom(const rotconv_plan* p);
 size_t p4_bwd_weight_ws_floats(const rotconv_plan* p);
 void launch_p4_bwd_weight(const rotconv_plan* p, const float* x, const float* gpool, const uint8_t* idx,
                           float* partial, float* dw, hipStream_t st);
+// bfloat16 x and gpool (bf16 matrix cores, fp32 partial sums and result); same workspace
+bool p4_bwd_weight_bf16_supported(const rotconv_plan* p);
+void launch_p4_bwd_weight_bf16(const rotconv_plan* p, const uint16_t* x, const uint16_t* gpool, const uint8_t* idx,
+                               float* partial, float* dw, hipStream_t st);
 
 }  // namespace rotconv

@@ -248,6 +248,199 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_weight(const float* __restrict__ 
   }
 }
 
+// ---- bfloat16 tensors -------------------------------------------------------------------------------
+// Same work decomposition (units, strips, row ranges, splits, one wave = 16 filters x 64 channels, nine
+// taps x four channel blocks of accumulators) on v_mfma_f32_16x16x32_bf16: M = 16 filters, N = 16
+// channels, K = 32 pixels = the strip, so a lane's 8 consecutive pixels are exactly its K-slice: the X
+// row (8 bf16 = one 16-byte load) IS the B operand.  The matrix instruction being 16 times cheaper per
+// product than the fp32 one while vector instructions cost the same, the rotated pre-sum D (27 adds per
+// pixel on the vector ALU, and a sum that bf16 could not hold exactly) is dropped: each quarter turn's
+// routed gradient row m_s = G * 1[idx == (q,s)] (exact bf16 values, Eq. 12) is multiplied on its own,
+//     dF_q[co,ci,u] += sum_s  m_s[row h+1-i_s(u)][pixels shifted by 1-j_s(u)] . X[ci][row h]
+// four instructions into one accumulator, the shift being a 16-bit funnel shift of the packed row.  The
+// result is the exact "bf16 operands, fp32 accumulation" value.  Quarter turns absent from the angle set
+// are skipped (wave-uniform).
+typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf8 __attribute__((ext_vector_type(8)));
+
+struct RowB {            // (G, idx) of one filter on one image row as loaded
+  u4 g;                  // the lane's 8 pixels (bf16 pairs)
+  uint16_t gl, gr;       // left and right neighbour
+  uint32_t i0, i1;       // idx bytes of pixels 0..3 and 4..7
+  uint8_t il, ir;        // idx of the neighbours
+};
+
+__global__ __launch_bounds__(NT) void k_p4_bwd_weight_bf16(const uint16_t* __restrict__ x,
+                                                           const uint16_t* __restrict__ gpool,
+                                                           const uint8_t* __restrict__ idx,
+                                                           const int32_t* __restrict__ rot_of,
+                                                           float* __restrict__ partial, P4BwdWGeom g) {
+  const int per_xcd = gridDim.x / 8;
+  int v = gridDim.x % 8 == 0 ? (blockIdx.x % 8) * per_xcd + blockIdx.x / 8 : blockIdx.x;
+  const int cig = v % g.ncig; v /= g.ncig;
+  const int fbg = v % g.ncog;
+  const int split = v / g.ncog;
+
+  const int tid = threadIdx.x;
+  const int wave = tid / 64, lane = tid % 64;
+  const int lg = lane / 16, lc = lane % 16;
+  const int HW = g.H * g.W;
+  const int nfb = g.CoutPad / 16;
+  const int fb_flat = min(fbg * NWAVE + wave, g.Q * nfb - 1);       // an idle wave redoes the last pair
+  const bool wave_on = fbg * NWAVE + wave < g.Q * nfb;
+  const int q = __builtin_amdgcn_readfirstlane(fb_flat / nfb);
+  const int cobase = (fb_flat % nfb) * 16;
+  const int co = cobase + lc;                        // this lane's filter (A role)
+  const int ci0 = cig * 16 * NCB + lc;               // this lane's channel in block 0 (B role)
+
+  int rot[4];
+  int r0 = -1;
+#pragma unroll
+  for (int s = 0; s < 4; ++s) {
+    rot[s] = __builtin_amdgcn_readfirstlane(rot_of[q * 4 + s]);
+    if (r0 < 0 && rot[s] >= 0) r0 = rot[s];
+  }
+  const bool cok = co < g.Cout && r0 >= 0;
+  const size_t gplane0 = ((size_t)(cok ? co : 0) * g.ng + (r0 < 0 ? 0 : r0 % g.ng)) * HW;
+  const size_t gimg = (size_t)g.Cout * g.ng * HW;
+  const size_t ximg = (size_t)g.Cin * HW;
+
+  uint32_t xplane[NCB];
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb) {
+    const int ci = ci0 + cb * 16;
+    xplane[cb] = (uint32_t)(ci < g.Cin ? ci : 0) * (uint32_t)HW;
+  }
+
+  f4 acc[9][NCB];
+#pragma unroll
+  for (int u = 0; u < 9; ++u)
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) acc[u][cb] = f4{0.f, 0.f, 0.f, 0.f};
+
+  // Routed row per quarter turn, packed: m[s][0..3] = the lane's 8 pixels (bf16 pairs) with every pixel
+  // whose arg-max is not orientation (q, s) zeroed; m[s][4] = right neighbour (low half) and left
+  // neighbour (high half), routed the same way.
+  auto select_row = [&](const RowB& r, bool rok, bool pok, bool lok, bool rok2, uint32_t (&m)[4][5]) {
+    // positions outside the image (or filters beyond Cout) get the idx byte 0xff, which matches no orientation
+    const uint32_t iw[2] = {(rok && pok) ? r.i0 : 0xffffffffu, (rok && pok) ? r.i1 : 0xffffffffu};
+    const uint32_t il = (rok && lok) ? (uint32_t)r.il : 0xffu, ir = (rok && rok2) ? (uint32_t)r.ir : 0xffu;
+    const uint32_t glr = ((uint32_t)r.gl << 16) | (uint32_t)r.gr;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const uint32_t rs = (uint32_t)rot[s];   // -1 (absent) matches no byte
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const uint32_t b0 = (iw[j >> 1] >> (16 * (j & 1))) & 0xffu, b1 = (iw[j >> 1] >> (16 * (j & 1) + 8)) & 0xffu;
+        m[s][j] = (b0 == rs ? r.g[j] & 0xffffu : 0u) | (b1 == rs ? r.g[j] & 0xffff0000u : 0u);
+      }
+      m[s][4] = (il == rs ? glr & 0xffff0000u : 0u) | (ir == rs ? glr & 0xffffu : 0u);
+    }
+  };
+  // A operand of (quarter turn s, base tap u): the routed row where R_s puts the tap, its pixels shifted.
+  auto operand = [&](const uint32_t (&ma)[4][5], const uint32_t (&mb)[4][5], const uint32_t (&mc)[4][5], int s,
+                     int u) -> u4 {
+    const int row = 2 - tap_i(s, u), shift = 1 - tap_j(s, u);
+    const uint32_t* m = row == 0 ? ma[s] : row == 1 ? mb[s] : mc[s];
+    if (shift == 0) return u4{m[0], m[1], m[2], m[3]};
+    if (shift < 0)    // pixel t takes pixel t-1: the left neighbour enters from the high half of m[4]
+      return u4{__builtin_amdgcn_alignbit(m[0], m[4], 16), __builtin_amdgcn_alignbit(m[1], m[0], 16),
+                __builtin_amdgcn_alignbit(m[2], m[1], 16), __builtin_amdgcn_alignbit(m[3], m[2], 16)};
+    return u4{__builtin_amdgcn_alignbit(m[1], m[0], 16), __builtin_amdgcn_alignbit(m[2], m[1], 16),
+              __builtin_amdgcn_alignbit(m[3], m[2], 16), __builtin_amdgcn_alignbit(m[4], m[3], 16)};
+  };
+
+  for (int unit = split; unit < g.units; unit += g.splits) {
+    int uu = unit;
+    const int strip = uu % g.nstrip; uu /= g.nstrip;
+    const int rng = uu % g.nrange;
+    const int n = uu / g.nrange;
+    const int h0 = rng * g.rows_per, h1 = min(g.H, h0 + g.rows_per);
+    const int px0 = strip * 32 + 8 * lg;
+    const bool pok = px0 < g.W;                              // W % 8 == 0: a lane's 8 pixels are in or out together
+    const bool lok = pok && px0 >= 1, rok2 = px0 + 8 < g.W;
+    const int pc = pok ? px0 : 0, pl = lok ? px0 - 1 : 0, pr = rok2 ? px0 + 8 : 0;
+    const uint16_t* gb = gpool + (size_t)n * gimg + gplane0;
+    const uint8_t* ib = idx + (size_t)n * gimg + gplane0;
+    const uint16_t* xb = x + (size_t)n * ximg;
+    const bool tail = strip * 32 + 32 > g.W;       // wave-uniform
+
+    auto row_ok = [&](int h) { return cok && h >= 0 && h < g.H; };
+    // Branch-free loads: out-of-range positions read a safe (clamped) address; what they return is
+    // discarded when the row is routed.
+    auto load_row = [&](int h, RowB& r) {
+      const uint32_t ro = (uint32_t)min(max(h, 0), g.H - 1) * (uint32_t)g.W;
+      r.g = *reinterpret_cast<const u4*>(gb + ro + pc);
+      const uint2 iv = *reinterpret_cast<const uint2*>(ib + ro + pc);
+      r.i0 = iv.x; r.i1 = iv.y;
+      r.gl = gb[ro + pl];
+      r.gr = gb[ro + pr];
+      r.il = ib[ro + pl];
+      r.ir = ib[ro + pr];
+    };
+    auto route = [&](const RowB& r, int h, uint32_t (&m)[4][5]) { select_row(r, row_ok(h), pok, lok, rok2, m); };
+    auto load_x = [&](int h, u4 (&b)[NCB]) {
+      const uint32_t off = (uint32_t)min(h, g.H - 1) * (uint32_t)g.W + (uint32_t)pc;
+#pragma unroll
+      for (int cb = 0; cb < NCB; ++cb) b[cb] = *reinterpret_cast<const u4*>(xb + xplane[cb] + off);
+    };
+
+    RowB rn;                                          // the row being loaded (h + 2)
+    uint32_t m0[4][5], m1[4][5], m2[4][5];            // routed rows h-1, h, h+1; the roles rotate
+    u4 bX[NCB], bN[NCB];                              // X of row h, and of row h + 1 in flight
+    auto step = [&](int h, uint32_t (&ma)[4][5], uint32_t (&mb)[4][5], uint32_t (&mc)[4][5]) {
+      // loads a whole row (up to 144 matrix instructions) ahead of their use, fenced so they stay here
+      load_row(h + 2, rn);
+      load_x(h + 1, bN);
+      __builtin_amdgcn_sched_barrier(0);
+      if (tail) {    // X of pixels beyond the row end must be zero: the routed rows there gather in-range neighbours
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb) bX[cb] = pok ? bX[cb] : u4{0u, 0u, 0u, 0u};
+      }
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        if (rot[s] < 0) continue;                     // wave-uniform
+#pragma unroll
+        for (int u = 0; u < 9; ++u) {
+          const bf8 a = __builtin_bit_cast(bf8, operand(ma, mb, mc, s, u));
+#pragma unroll
+          for (int cb = 0; cb < NCB; ++cb)
+            acc[u][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf8, bX[cb]), acc[u][cb], 0, 0, 0);
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      route(rn, h + 2, ma);                           // row h+2 replaces row h-1
+#pragma unroll
+      for (int cb = 0; cb < NCB; ++cb) bX[cb] = bN[cb];
+    };
+    load_row(h0 - 1, rn);
+    route(rn, h0 - 1, m0);
+    load_row(h0, rn);
+    route(rn, h0, m1);
+    load_row(h0 + 1, rn);
+    route(rn, h0 + 1, m2);
+    load_x(h0, bX);
+    for (int h = h0; h < h1; h += 3) {
+      step(h, m0, m1, m2);
+      if (h + 1 >= h1) break;
+      step(h + 1, m1, m2, m0);
+      if (h + 2 >= h1) break;
+      step(h + 2, m2, m0, m1);
+    }
+  }
+
+  if (wave_on) {
+    float* out = partial + ((size_t)(split * g.Q + q) * 9) * g.CoutPad * g.CinPad;
+#pragma unroll
+    for (int u = 0; u < 9; ++u)
+#pragma unroll
+      for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          out[((size_t)u * g.CoutPad + cobase + 4 * lg + i) * g.CinPad + cig * 16 * NCB + cb * 16 + lc] = acc[u][cb][i];
+  }
+}
+
 // Stage 1: sum the splits.  A block covers 32 consecutive elements x 8 interleaved split groups;
 // each thread adds its splits in ascending order, the groups are combined in a fixed tree, so
 // the result does not depend on scheduling.  out[e] = sum_split partial[split][e].
@@ -319,6 +512,9 @@ P4BwdWGeom p4_bwd_weight_geom(const rotconv_plan* p) {
   return g;
 }
 
+// The bf16 kernel loads a lane's 8 pixels with one 16-byte access: rows must start 16-byte aligned.
+bool p4_bwd_weight_bf16_supported(const rotconv_plan* p) { return p4_bwd_weight_supported(p) && (p->d.W & 7) == 0; }
+
 size_t p4_bwd_weight_ws_floats(const rotconv_plan* p) {
   const P4BwdWGeom g = p4_bwd_weight_geom(p);
   return (size_t)(g.splits + 1) * g.Q * 9 * g.CoutPad * g.CinPad;  // partial sums + their total
@@ -329,6 +525,19 @@ void launch_p4_bwd_weight(const rotconv_plan* p, const float* x, const float* gp
   const P4BwdWGeom g = p4_bwd_weight_geom(p);
   const int grid = g.splits * g.ncig * g.ncog;
   hipLaunchKernelGGL(k_p4_bwd_weight, dim3(grid), dim3(NT), 0, st, x, gpool, idx, p->dev.rot_of, partial, g);
+  const int n_elem = g.Q * 9 * g.CoutPad * g.CinPad;
+  float* dF = partial + (size_t)g.splits * n_elem;
+  hipLaunchKernelGGL(k_p4_sum_splits, dim3((n_elem + 31) / 32), dim3(256), 0, st, partial, dF, n_elem, g.splits);
+  const int total = p->B * 9 * g.Cout * g.Cin;
+  hipLaunchKernelGGL(k_p4_reduce_w, dim3((total + 255) / 256), dim3(256), 0, st, dF, dw, p->dev.fqt_ptr,
+                     p->dev.fqt_col, p->dev.fqt_coef, p->B, g.Cout, g.Cin, g.CoutPad, g.CinPad);
+}
+
+void launch_p4_bwd_weight_bf16(const rotconv_plan* p, const uint16_t* x, const uint16_t* gpool, const uint8_t* idx,
+                               float* partial, float* dw, hipStream_t st) {
+  const P4BwdWGeom g = p4_bwd_weight_geom(p);
+  const int grid = g.splits * g.ncig * g.ncog;
+  hipLaunchKernelGGL(k_p4_bwd_weight_bf16, dim3(grid), dim3(NT), 0, st, x, gpool, idx, p->dev.rot_of, partial, g);
   const int n_elem = g.Q * 9 * g.CoutPad * g.CinPad;
   float* dF = partial + (size_t)g.splits * n_elem;
   hipLaunchKernelGGL(k_p4_sum_splits, dim3((n_elem + 31) / 32), dim3(256), 0, st, partial, dF, n_elem, g.splits);

@@ -68,6 +68,32 @@ def check_idx(idx_gpu, y_ref, abs_terms, G, what):
     return int((ig != ref_idx).sum())  # accepted near-ties, for reporting
 
 
+def round_bf16(a):
+    """fp64 -> nearest-even bfloat16 -> fp64."""
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float64)).to(torch.float32).to(torch.bfloat16).to(
+        torch.float64).numpy()
+
+
+def layer_fwd_bf16(x, w_base, R, angles_deg=None, mode="exact90", stride=1, pad=0, pool_group=None):
+    """The oracle's layer forward on the banks a bf16 plan multiplies with: the rotated banks are rounded to
+    bf16 once (the identity for exact quarter turns).  Same return values as the oracle's layer_fwd."""
+    w_rot = round_bf16(orc.expand_bank(w_base, R, angles_deg, mode))
+    y = orc.rotconv_fwd(x, w_rot, stride, pad)
+    yp, idx = orc.orient_maxpool_fwd(y, pool_group)
+    return y, yp, idx, w_rot
+
+
+def layer_bwd_bf16(x, w_base, gpool, idx, R, angles_deg=None, mode="exact90", stride=1, pad=0, pool_group=None):
+    """Backward of the same: dX through the bf16-rounded banks, dW (independent of the banks) through Eq. 16."""
+    x = np.asarray(x, dtype=np.float64)
+    w_rot = round_bf16(orc.expand_bank(w_base, R, angles_deg, mode))
+    k = w_rot.shape[-1]
+    dy = orc.orient_maxpool_bwd(gpool, idx, R, pool_group)
+    dx = orc.rotconv_bwd_data(dy, w_rot, x.shape[2], x.shape[3], stride, pad)
+    dw = orc.reduce_bank_grad(orc.rotconv_bwd_weight(x, dy, k, stride, pad), angles_deg, mode)
+    return dx, dw
+
+
 class GpuLayer:
     """Device tensors + plan of one layer configuration."""
 

@@ -11,7 +11,7 @@ import torch
 from oracle import rotconv_oracle as orc
 from paper_2512_08888_amd import binding as rc
 from paper_2512_08888_amd import synth
-from parity_util import RTOL, assert_close, check_idx
+from parity_util import RTOL, assert_close, check_idx, round_bf16
 
 pytestmark = pytest.mark.gpu
 LC = synth.LayerConfig
@@ -39,12 +39,6 @@ def bf(a):
     """numpy fp32/fp64 -> (torch bf16 cuda tensor, the rounded values as fp64)."""
     t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(torch.bfloat16)
     return t.cuda(), t.to(torch.float64).numpy()
-
-
-def round_bf16(a):
-    """fp64 -> nearest-even bf16 -> fp64."""
-    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float64)).to(torch.float32).to(torch.bfloat16).to(
-        torch.float64).numpy()
 
 
 def nan16(*shape):

@@ -8,7 +8,7 @@ from oracle import rotconv_oracle as orc
 from oracle import unet_oracle as uo
 from paper_2512_08888_amd import binding as rc
 from paper_2512_08888_amd import unet as un
-from parity_util import RTOL, assert_close, check_idx, dev
+from parity_util import RTOL, assert_close, check_idx, dev, layer_bwd_bf16, layer_fwd_bf16
 
 pytestmark = pytest.mark.gpu
 BF_RTOL = 1e-2      # one rounding to bfloat16 is 2^-9; the benchmark's bf16 bar is 2e-2
@@ -294,12 +294,14 @@ def test_unet_step_teacher_forced(cfg, dtype):
     A = net.act
     H = lambda t: t.detach().to(torch.float64).cpu().numpy()
     act_close = assert_close if dtype == "f32" else (lambda got, ref, what: assert_close(got, ref, what, rtol=BF_RTOL))
+    layer_fwd = orc.layer_fwd if dtype == "f32" else layer_fwd_bf16    # bf16 plans hold their rotated banks in bf16
+    layer_bwd = orc.layer_bwd if dtype == "f32" else layer_bwd_bf16
     p64 = {k: v.astype(np.float64) for k, v in params.items()}
     # forward, layer by layer
     for sp in net.specs:
         name, R, mode, G = sp["name"], sp["R"], sp["mode"], sp["pool_group"]
         x = H(A[name]["x"])
-        y_ref, yp_ref, idx_ref, w_rot = orc.layer_fwd(x, p64[name], R, None, mode, 1, 1, G)
+        y_ref, yp_ref, idx_ref, w_rot = layer_fwd(x, p64[name], R, None, mode, 1, 1, G)
         act_close(H(A[name]["y"]), uo.relu_fwd(yp_ref), f"{name} fwd")
         abs_terms = orc.rotconv_fwd(np.abs(x), np.abs(w_rot), 1, 1)
         check_idx(H(A[name]["idx"]).astype(np.uint8), y_ref, abs_terms, G or R, f"{name} idx")
@@ -327,7 +329,7 @@ def test_unet_step_teacher_forced(cfg, dtype):
         a = A[name]
         g = H(a["g"])                       # after the in-place ReLU backward: gradient of the pooled map
         assert np.all(g[H(a["y"]) <= 0] == 0), f"{name}: ReLU backward"
-        dx_ref, dw_ref = orc.layer_bwd(H(a["x"]), p64[name], g, H(a["idx"]).astype(np.uint8), sp["R"], None,
+        dx_ref, dw_ref = layer_bwd(H(a["x"]), p64[name], g, H(a["idx"]).astype(np.uint8), sp["R"], None,
                                        sp["mode"], 1, 1, sp["pool_group"])
         assert_close(H(net.grads[name]), dw_ref, f"{name} dW")
         if i == 0:
