@@ -100,6 +100,10 @@ int rotconv_plan_create(const rotconv_desc* desc, rotconv_plan** out) {
   if (p->fast[1]) p->ws_bytes = std::max(p->ws_bytes, p4_bwd_data_pack_floats(p) * sizeof(float));
   p->fast[2] = p4_bwd_weight_supported(p) ? 1 : 0;
   if (p->fast[2]) p->ws_bytes = std::max(p->ws_bytes, p4_bwd_weight_ws_floats(p) * sizeof(float));
+  if (p->d.dtype == ROTCONV_BF16) {     // scratch of the kernels that take bf16 tensors directly
+    if (p->fast[0] && p4_fwd_bf16_supported(p)) p->ws_bytes = std::max(p->ws_bytes, p4_fwd_bf16_pack_bytes(p));
+    if (p->fast[1] && p4_bwd_data_bf16_supported(p)) p->ws_bytes = std::max(p->ws_bytes, p4_bwd_data_bf16_pack_bytes(p));
+  }
   p->ws_inner = p->ws_bytes = align256(p->ws_bytes);
   const size_t hw_in = (size_t)p->d.H * p->d.W, hw_out = (size_t)p->Ho * p->Wo;
   p->n_x = (size_t)p->d.N * p->d.Cin * hw_in;
@@ -109,6 +113,7 @@ int rotconv_plan_create(const rotconv_desc* desc, rotconv_plan** out) {
   if (p->d.dtype == ROTCONV_BF16) {
     p->ws_bytes = align256(p->n_x * 4) + align256(p->n_w * 4) + align256(p->n_yu * 4) + p->ws_inner;
     p->native16[0] = p->fast[0] && p4_fwd_bf16_supported(p) ? 1 : 0;
+    p->native16[1] = p->fast[1] && p4_bwd_data_bf16_supported(p) ? 1 : 0;
     p->native16[2] = p->fast[2] && p4_bwd_weight_bf16_supported(p) ? 1 : 0;
   }
   *out = p;
@@ -427,6 +432,15 @@ int rotconv_pool_bwd_data(const rotconv_plan* plan, const void* gpool, const uin
   if (!is_bf16(plan)) return f32_rotconv_pool_bwd_data(plan, gpool, idx, w, dx, ws, ws_bytes, stream);
   if (!ws || ws_bytes < plan->ws_bytes) return ROTCONV_ERR_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);
+  if (plan->native16[1] && aligned(gpool, 4) && aligned(idx, 2) && aligned(dx, 16) && aligned(ws, 16)) {
+    rotconv_plan* p = const_cast<rotconv_plan*>(plan);
+    const int rc = ensure_device_tables(p);
+    if (rc) return rc;
+    uint16_t* wt = static_cast<uint16_t*>(ws);
+    launch_p4_pack_bwd_bf16(p, h16(w), wt, st);
+    launch_p4_bwd_data_bf16(p, h16(gpool), idx, wt, static_cast<uint16_t*>(dx), st);
+    return finish();
+  }
   const Stage s = carve(plan, ws, ws_bytes);
   launch_widen(h16(gpool), s.y, plan->n_yp, st);
   launch_widen(h16(w), s.w, plan->n_w, st);

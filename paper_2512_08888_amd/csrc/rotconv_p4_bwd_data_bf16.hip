@@ -1,0 +1,462 @@
+// Fast input-gradient kernel for 3x3, stride 1, pad 1 with bfloat16 tensors, fused with the orientation
+// max-pool backward (paper Eq. 12, 13, 15) on the bf16 matrix cores, fp32 accumulation.
+//
+//   dX[ci,h,x] = sum_q sum_s sum_u sum_co F_q[co,ci,u] * Delta_(q,s)[co, h+1-i_s(u), x+1-j_s(u)]
+//   Delta_(q,s) = G * 1[idx == orientation (q,s)],   (i_s,j_s) = R_s(u): where quarter turn s puts base tap u
+//
+// The fp32 kernel sums the four routed gradients at the rotated tap positions on the vector ALU before one
+// contraction.  With the bf16 matrix instruction 16 times cheaper per product and vector instructions no
+// cheaper, that pre-sum (and the 3x3 neighbourhood every lane had to fetch for it) would dominate, and
+// its sums are not bf16 values.  Here the products are formed first, per quarter turn, on UNSHIFTED
+// routed gradients, and the rotation is an index permutation on the accumulator side:
+//     S_d[ci,h',x'] += sum_co F_q[co,ci,u] * Delta_(q,s)[co,h',x']      for every (s,u) with R_s(u) = d
+//     dX[ci,h,x]     = sum_d S_d[ci, h+1-d_i, x+1-d_j]
+// v_mfma_f32_16x16x32_bf16 with M = 16 pixels, N = 16 input channels, K = 32 filters: four quarter
+// turns x nine taps = 36 products per K-step land in the nine tiles S_d (the one LDS-resident filter block
+// serves all four rotations).  A lane loads one dword of G (a pixel pair of one filter) and its two idx
+// bytes; routing is a compare + select per quarter turn (exact bf16 values), eight filters pack into the
+// lane's K-slice of both pixel tiles.  A wave owns 16 channels x 32 pixels of a row and walks down its band
+// like the forward kernel: the row of S_d feeds the output rows above, at and below through two rolling
+// partial sums; column shifts are register renames plus one neighbour value per side (adjacent lane group
+// via ds_bpermute, adjacent wave via LDS).  The (G, idx) rows are prefetched ND K-steps ahead through a
+// register ring; the filter block [K-step][tap][k-group][16 channels][8 filters] is LDS-resident, or
+// streamed in stages of ND K-steps when it exceeds LDS.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+
+#include "rotconv_bf16.h"
+#include "rotconv_kernels.h"
+#include "rotconv_p4.h"
+#include "rotconv_p4_taps.h"
+
+namespace rotconv {
+namespace {
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf8 __attribute__((ext_vector_type(8)));
+typedef float f2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
+
+constexpr int CHB = 9 * 4 * 16 * 8 * 2;   // bytes of one K-step (32 filters) of a 16-channel block (9216)
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f2{lo, hi}, bf2));
+}
+
+// ND:     K-steps the (G, idx) prefetch runs ahead (K-steps per bank are a multiple of ND).
+// FASTW:  W % 8 == 0 and no wave chain reaches beyond the row: no load masks, vector stores.
+// STREAM: the filter block does not fit LDS: stream it in stages of ND K-steps.
+// CPAD:   CoutPad > Cout: filter offsets are clamped to the last real filter (its taps are zero).
+template <int NWX, int NWY, int ND, bool FASTW, bool STREAM, bool CPAD>
+__global__ __launch_bounds__(64 * NWX * NWY) void k_p4_bwd_data_bf16(const uint16_t* __restrict__ gpool,
+                                                                     const uint8_t* __restrict__ idx,
+                                                                     const uint16_t* __restrict__ wt,
+                                                                     const int32_t* __restrict__ rot_of,
+                                                                     uint16_t* __restrict__ dx, P4BwdBfGeom g) {
+  constexpr int NW = NWX * NWY;
+  constexpr int NT = 64 * NW;
+  constexpr int STB = ND * CHB;            // bytes of one streaming stage
+  extern __shared__ __attribute__((aligned(16))) char smem_raw[];
+  char* Wl = smem_raw;                     // resident: [nks][CHB]; streamed: [2][STB]
+  const int nkc = g.CoutPad / 32;          // K-steps per bank
+  const int nks = g.Q * nkc;               // K-steps per row
+  float* EL = reinterpret_cast<float*>(smem_raw + (STREAM ? 2 * STB : nks * CHB));  // [2][NW][3][16] left edges
+  float* ER = EL + 2 * NW * 48;                                                      // right edges
+
+  const int per_xcd = (g.units + 7) / 8;
+  int v = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  if (v >= g.units) return;
+  const int cib = v % g.CIB; v /= g.CIB;
+  const int seg = v % g.nseg; v /= g.nseg;
+  const int bg = v % g.nbg;
+  const int n = v / g.nbg;
+
+  const int tid = threadIdx.x;
+  const char* wsrc = reinterpret_cast<const char*>(wt) + (size_t)cib * nks * CHB;
+  constexpr int WPT = (STB / 16 + NT - 1) / NT;
+  u4 wreg[STREAM ? WPT : 1];
+  auto wload = [&](int stage) {
+#pragma unroll
+    for (int k = 0; k < WPT; ++k) {
+      const int e = tid + k * NT;
+      if (e < STB / 16) wreg[k] = reinterpret_cast<const u4*>(wsrc + (size_t)stage * STB)[e];
+    }
+  };
+  auto wstore = [&](int buf) {
+#pragma unroll
+    for (int k = 0; k < WPT; ++k) {
+      const int e = tid + k * NT;
+      if (e < STB / 16) reinterpret_cast<u4*>(Wl + buf * STB)[e] = wreg[k];
+    }
+  };
+  if (STREAM) {
+    wload(0);
+    wstore(0);
+  } else {
+    const u4* src = reinterpret_cast<const u4*>(wsrc);
+    u4* dst = reinterpret_cast<u4*>(Wl);
+    const int n16 = nks * (CHB / 16);
+    for (int i = tid; i < n16; i += NT) dst[i] = src[i];
+  }
+  __syncthreads();
+
+  const int wave = __builtin_amdgcn_readfirstlane(tid / 64), lane = tid % 64;
+  const int wx = wave % NWX, wy = wave / NWX;
+  const int lg = lane / 16, lc = lane % 16;
+  const int x0 = g.seg_xorg[seg] + wx * 32;
+  const int out_lo = g.seg_lo[seg], out_hi = g.seg_hi[seg];
+  const int y0 = (bg * NWY + wy) * g.TY;
+  const int nsteps = g.TY + 2;
+  const int HW = g.H * g.W;
+
+  // (G, idx) loads: lane (lc, lg) reads the pixel pair x0 + 2*lc .. +1 of filter co = 32*chunk + 8*lg + j,
+  // j = 0..7, in the pooled plane co*ng + (pool group of the bank).  Rows outside the image are never
+  // multiplied, filters beyond Cout meet zero taps, so both only need a valid address; pixels beyond W
+  // must read as zero gradient (only when W % 32 != 0).
+  const int pxa = x0 + 2 * lc;
+  const bool px_ok = pxa < g.W;
+  const size_t img = (size_t)n * g.Cout * g.ng * HW + (px_ok ? pxa : 0);
+  const uint16_t* gn = gpool + img;
+  const uint8_t* in = idx + img;
+  const uint32_t fstride = (uint32_t)g.ng * (uint32_t)HW;        // elements between consecutive filters
+  uint32_t lgoff = (uint32_t)(8 * lg) * fstride;
+  asm volatile("" : "+v"(lgoff));   // opaque: the K-step / slot part of the offset stays scalar
+  const uint32_t off_last = (uint32_t)(g.Cout - 1) * fstride;
+  auto row_off = [&](int t) -> uint32_t {
+    const int h = min(max(y0 - 1 + t, 0), g.H - 1);
+    return (uint32_t)h * (uint32_t)g.W;
+  };
+  // pool group of bank q: all its orientations share r mod ng
+  auto group_of = [&](int q) -> int {
+    int r0 = 0;
+#pragma unroll
+    for (int s = 3; s >= 0; --s) {
+      const int r = rot_of[q * 4 + s];
+      r0 = r >= 0 ? r : r0;
+    }
+    return r0 % g.ng;
+  };
+  auto load_g = [&](uint32_t base, int c, int j) -> uint32_t {   // base: row offset + pool-group plane
+    uint32_t off = (uint32_t)(c * 32 + j) * fstride + lgoff;
+    if (CPAD) off = min(off, off_last);
+    const uint32_t v2 = *reinterpret_cast<const uint32_t*>(gn + (off + base));
+    if (FASTW) return v2;
+    return px_ok ? v2 : 0u;
+  };
+  auto load_i = [&](uint32_t base, int c, int j) -> uint32_t {
+    uint32_t off = (uint32_t)(c * 32 + j) * fstride + lgoff;
+    if (CPAD) off = min(off, off_last);
+    return (uint32_t)*reinterpret_cast<const uint16_t*>(in + (off + base));
+  };
+
+  float accA[8], accB[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) { accA[j] = 0.f; accB[j] = 0.f; }
+
+  // ring of ND K-step slots: slot i holds K-step (ksg + i) of the current group; refilled with the K-step
+  // ND further on (of this row, or of the next row's first group) right after it has been routed
+  uint32_t rg[ND][8], ri[ND][8];
+  {
+    const uint32_t base = row_off(0) + (uint32_t)group_of(0) * (uint32_t)HW;
+#pragma unroll
+    for (int i = 0; i < ND; ++i)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) { rg[i][j] = load_g(base, i, j); ri[i][j] = load_i(base, i, j); }
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+  }
+  const char* wl_lane = Wl + lane * 16;
+  int seq = 0;                           // groups done (streaming: LDS buffer parity)
+
+  for (int t = 0; t < nsteps; ++t) {
+    const int h = y0 - 1 + t;
+    const bool row_ok = h >= 0 && h < g.H;
+    const uint32_t ro_cur = row_off(t), ro_nxt = row_off(t + 1);
+    f4 S[9][2];      // S_d of this row: tile b holds pixels 2m+b
+#pragma unroll
+    for (int d = 0; d < 9; ++d) { S[d][0] = f4{0.f, 0.f, 0.f, 0.f}; S[d][1] = f4{0.f, 0.f, 0.f, 0.f}; }
+
+    auto group = [&](int ksg, bool mul) {
+      const bool last = ksg + ND == nks;
+      const int kn = last ? 0 : ksg + ND;                   // first K-step of the group being prefetched
+      const int qn = kn / nkc, cn = kn % nkc;
+      const uint32_t base_n = (last ? ro_nxt : ro_cur) + (uint32_t)group_of(qn) * (uint32_t)HW;
+      if (STREAM) wload(last ? 0 : ksg / ND + 1);
+      if (mul) {
+        const int q = ksg / nkc;
+        int rot[4];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) rot[s] = rot_of[q * 4 + s];
+        const char* wc = STREAM ? wl_lane + (seq & 1) * STB : wl_lane + (size_t)ksg * CHB;
+        u4 bw[3];
+        bw[0] = *reinterpret_cast<const u4*>(wc);
+        bw[1] = *reinterpret_cast<const u4*>(wc + 1024);
+#pragma unroll
+        for (int i = 0; i < ND; ++i) {
+          // route per quarter turn (Eq. 12) and pack the eight filters into the K-slice of both tiles
+          u4 a0[4], a1[4];
+#pragma unroll
+          for (int s = 0; s < 4; ++s) {
+            const uint32_t rs = (uint32_t)rot[s];       // -1 (absent) matches no byte
+            uint32_t r[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+              r[j] = ((ri[i][j] & 0xffu) == rs ? rg[i][j] & 0xffffu : 0u) |
+                     ((ri[i][j] >> 8) == rs ? rg[i][j] & 0xffff0000u : 0u);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              a0[s][j] = __builtin_amdgcn_perm(r[2 * j + 1], r[2 * j], 0x05040100u);
+              a1[s][j] = __builtin_amdgcn_perm(r[2 * j + 1], r[2 * j], 0x07060302u);
+            }
+          }
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int j = 0; j < 8; ++j) { rg[i][j] = load_g(base_n, cn + i, j); ri[i][j] = load_i(base_n, cn + i, j); }
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int u = 0; u < 9; ++u) {
+            const int e = i * 9 + u;
+            if (e + 2 < ND * 9) bw[(e + 2) % 3] = *reinterpret_cast<const u4*>(wc + (e + 2) * 1024);
+            __builtin_amdgcn_sched_barrier(0);
+            const bf8 b = __builtin_bit_cast(bf8, bw[e % 3]);
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+              if (rot[s] < 0) continue;                 // wave-uniform
+              const int d = tap_i(s, u) * 3 + tap_j(s, u);
+              S[d][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf8, a0[s]), b, S[d][0], 0, 0, 0);
+              S[d][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf8, a1[s]), b, S[d][1], 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < ND; ++i)
+#pragma unroll
+          for (int j = 0; j < 8; ++j) { rg[i][j] = load_g(base_n, cn + i, j); ri[i][j] = load_i(base_n, cn + i, j); }
+      }
+      if (STREAM) {
+        wstore((seq + 1) & 1);
+        __syncthreads();
+      }
+      ++seq;
+    };
+    if (row_ok) {
+      for (int ksg = 0; ksg < nks; ksg += ND) group(ksg, true);
+    } else {
+      for (int ksg = 0; ksg < nks; ksg += ND) group(ksg, false);
+      __builtin_amdgcn_s_waitcnt(0x0F70);   // rare path: drain its loads so the hot loop's wait counts stay exact
+    }
+
+    // ---- neighbour values across lane groups and waves --------------------------
+    // Lane (lg, lc) holds channel lc, pixels x0 + 8*lg + j, j = 2*i + b for S[d][b][i].  Tiles with d_j = 0
+    // are read one pixel to the right (need the right neighbour's first pixel), d_j = 2 one to the left.
+    float nbL[3], nbR[3];  // per d_i: S_(d_i,2) at pixel (first - 1), S_(d_i,0) at pixel (last + 1)
+    const int par = t & 1;
+    float* el = EL + (par * NW + wave) * 48 + lc;
+    float* er = ER + (par * NW + wave) * 48 + lc;
+    if (lg == 0) {
+#pragma unroll
+      for (int di = 0; di < 3; ++di) el[di * 16] = S[di * 3][0][0];        // my first pixel of S_(di,0): for my left neighbour
+    }
+    if (lg == 3) {
+#pragma unroll
+      for (int di = 0; di < 3; ++di) er[di * 16] = S[di * 3 + 2][1][3];    // my last pixel of S_(di,2): for my right neighbour
+    }
+    const int addr_up = ((lane + 16) & 63) * 4, addr_dn = ((lane + 48) & 63) * 4;
+#pragma unroll
+    for (int di = 0; di < 3; ++di) {
+      float first_px = S[di * 3][0][0], last_px = S[di * 3 + 2][1][3];
+      asm volatile("" : "+v"(first_px), "+v"(last_px));    // pinned: see the forward kernel
+      nbR[di] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(addr_up, __builtin_bit_cast(int, first_px)));
+      nbL[di] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(addr_dn, __builtin_bit_cast(int, last_px)));
+    }
+    __syncthreads();
+    if (NWX > 1) {
+      const float* eln = EL + (par * NW + wave + 1) * 48 + lc;  // right neighbour's left edge
+      const float* erp = ER + (par * NW + wave - 1) * 48 + lc;  // left neighbour's right edge
+      const bool has_r = wx + 1 < NWX, has_l = wx > 0;
+#pragma unroll
+      for (int di = 0; di < 3; ++di) {
+        const float vr = has_r ? eln[di * 16] : 0.f;
+        const float vl = has_l ? erp[di * 16] : 0.f;
+        nbR[di] = lg == 3 ? vr : nbR[di];
+        nbL[di] = lg == 0 ? vl : nbL[di];
+      }
+    } else {
+#pragma unroll
+      for (int di = 0; di < 3; ++di) {
+        nbR[di] = lg == 3 ? 0.f : nbR[di];
+        nbL[di] = lg == 0 ? 0.f : nbL[di];
+      }
+    }
+
+    // ---- dX[h-1] = rolling sums + this row's S_(0,.) ; rows h and h+1 keep their partial sums ----
+    const int y = h - 1;                       // output row completed by this step
+    const int px0 = x0 + 8 * lg;
+    const int ci = cib * 16 + lc;
+    const bool fin = t >= 2 && y < g.H && ci < g.Cin && px0 >= out_lo && px0 < out_hi;
+    float yfin[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      float tsum[3];
+#pragma unroll
+      for (int di = 0; di < 3; ++di) {
+        // S_(di,0) at pixel j+1, S_(di,1) at pixel j, S_(di,2) at pixel j-1
+        const float vr = j + 1 > 7 ? nbR[di] : S[di * 3][(j + 1) & 1][(j + 1) >> 1];
+        const float vc = S[di * 3 + 1][j & 1][j >> 1];
+        const float vl = j - 1 < 0 ? nbL[di] : S[di * 3 + 2][(j - 1) & 1][(j - 1) >> 1];
+        tsum[di] = (vr + vc) + vl;
+      }
+      yfin[j] = accA[j] + tsum[0];      // product rows h-2, h-1, h are in: output row h-1 done
+      accA[j] = accB[j] + tsum[1];      // output row h has product rows h-1, h
+      accB[j] = tsum[2];                // output row h+1 has product row h
+    }
+    if (fin) {
+      uint16_t* o = dx + ((size_t)n * g.Cin + ci) * HW + (size_t)y * g.W + px0;
+      if (FASTW) {
+        *reinterpret_cast<u4*>(o) = u4{pack_bf16(yfin[0], yfin[1]), pack_bf16(yfin[2], yfin[3]),
+                                       pack_bf16(yfin[4], yfin[5]), pack_bf16(yfin[6], yfin[7])};
+      } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+          if (px0 + j < min(g.W, out_hi)) o[j] = (uint16_t)(pack_bf16(yfin[j], 0.f) & 0xffffu);
+      }
+    }
+  }
+}
+
+// bf16 base bank(s) -> Q first-quadrant banks (fp32 combination rounded to bf16 once) in the LDS image layout
+// of the input-gradient kernel: [16-channel block][Q][K-step of 32 filters][9 taps][4 k-groups][16 channels][8 filters].
+__global__ __launch_bounds__(256) void k_p4_pack_bwd_bf16(const uint16_t* __restrict__ w, uint16_t* __restrict__ wt,
+                                                          const int32_t* __restrict__ fq_src,
+                                                          const float* __restrict__ fq_coef, int Q, int CIB,
+                                                          int CoutPad, int Cin, int Cout) {
+  const int total = CIB * Q * CoutPad * 144;
+  const int e = blockIdx.x * 256 + threadIdx.x;
+  if (e >= total) return;
+  const int c8 = e % 8;
+  const int n16 = (e / 8) % 16;
+  const int kg = (e / 128) % 4;
+  const int u = (e / 512) % 9;
+  const int chunk = (e / 4608) % (CoutPad / 32);
+  const int q = (e / (144 * CoutPad)) % Q;
+  const int cib = e / (144 * CoutPad * Q);
+  const int co = chunk * 32 + kg * 8 + c8, ci = cib * 16 + n16;
+  float acc = 0.f;
+  if (co < Cout && ci < Cin) {
+    const int slices = Cout * Cin;
+#pragma unroll
+    for (int z = 0; z < kMaxNnz; ++z) {
+      const int s = fq_src[(q * 9 + u) * kMaxNnz + z];
+      if (s >= 0)
+        acc += fq_coef[(q * 9 + u) * kMaxNnz + z] * bf16_to_f32(w[((s / 9) * slices + co * Cin + ci) * 9 + s % 9]);
+    }
+  }
+  wt[e] = f32_to_bf16(acc);
+}
+
+// filters padded to 32, or to a multiple of 64 (two K-steps in flight)
+int cout_pad(int Cout) { return Cout <= 32 ? 32 : (Cout + 63) / 64 * 64; }
+int ring_depth(int Cout) { return std::min(2, cout_pad(Cout) / 32); }
+bool needs_stream(const rotconv_plan* p) {
+  return (size_t)p->host.Q * (cout_pad(p->d.Cout) / 32) * CHB + 8192 > 160 * 1024;
+}
+
+template <int NWX, int NWY, int ND, bool FASTW, bool STREAM, bool CPAD>
+void launch_i(const P4BwdBfGeom& g, const uint16_t* gp, const uint8_t* idx, const uint16_t* wt, const int32_t* rot_of,
+              uint16_t* dx, hipStream_t st) {
+  const size_t wbytes = STREAM ? (size_t)2 * ND * CHB : (size_t)g.Q * (g.CoutPad / 32) * CHB;
+  const size_t lds = wbytes + (size_t)4 * NWX * NWY * 48 * sizeof(float);
+  const int grid = (g.units + 7) / 8 * 8;
+  auto kern = k_p4_bwd_data_bf16<NWX, NWY, ND, FASTW, STREAM, CPAD>;
+  (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * NWX * NWY), lds, st, gp, idx, wt, rot_of, dx, g);
+}
+
+template <int NWX, int NWY, int ND>
+void launch_t(const P4BwdBfGeom& g, bool fastw, bool stream, bool cpad, const uint16_t* gp, const uint8_t* idx,
+              const uint16_t* wt, const int32_t* rot_of, uint16_t* dx, hipStream_t st) {
+  if (stream && fastw) launch_i<NWX, NWY, ND, true, true, false>(g, gp, idx, wt, rot_of, dx, st);
+  else if (stream) launch_i<NWX, NWY, ND, false, true, false>(g, gp, idx, wt, rot_of, dx, st);
+  else if (fastw && !cpad) launch_i<NWX, NWY, ND, true, false, false>(g, gp, idx, wt, rot_of, dx, st);
+  else launch_i<NWX, NWY, ND, false, false, true>(g, gp, idx, wt, rot_of, dx, st);
+}
+
+template <int NWX, int NWY>
+void launch_d(int nd, const P4BwdBfGeom& g, bool fastw, bool stream, bool cpad, const uint16_t* gp, const uint8_t* idx,
+              const uint16_t* wt, const int32_t* rot_of, uint16_t* dx, hipStream_t st) {
+  if (nd == 1) launch_t<NWX, NWY, 1>(g, fastw, stream, cpad, gp, idx, wt, rot_of, dx, st);
+  else launch_t<NWX, NWY, 2>(g, fastw, stream, cpad, gp, idx, wt, rot_of, dx, st);
+}
+
+// Row segments and bands as in the forward kernel (rows cut into chains of at most 256 product columns
+// that overlap by 8 pixels; a workgroup of 8 waves = nwx waves along x times 8 / nwx bands).
+int geoms(const rotconv_plan* p, P4BwdBfGeom* out, int max_out) {
+  P4Geom fg[4];
+  const int ng = p4_fwd_geoms(p, kOutPooled, fg, 4);
+  if (ng < 0 || ng > max_out) return -1;
+  const rotconv_desc& d = p->d;
+  for (int i = 0; i < ng; ++i) {
+    P4BwdBfGeom& g = out[i];
+    g = P4BwdBfGeom{};
+    g.N = d.N; g.Cin = d.Cin; g.CIB = (d.Cin + 15) / 16; g.H = d.H; g.W = d.W; g.Cout = d.Cout;
+    g.CoutPad = cout_pad(d.Cout); g.Q = p->host.Q; g.ng = p->ng;
+    g.nwx = fg[i].nwx; g.nseg = fg[i].nseg; g.inside = fg[i].inside;
+    for (int k = 0; k < 4; ++k) { g.seg_xorg[k] = fg[i].seg_xorg[k]; g.seg_lo[k] = fg[i].seg_lo[k]; g.seg_hi[k] = fg[i].seg_hi[k]; }
+    const int nwy = 8 / g.nwx;
+    long best_cost = -1;
+    for (int ty : {8, 16, 32, 64}) {
+      const int nbg = (d.H + nwy * ty - 1) / (nwy * ty);
+      const long units = (long)d.N * g.CIB * nbg * g.nseg;
+      const long cost = ((units + 255) / 256) * (ty + 2);
+      if (best_cost < 0 || cost <= best_cost) { best_cost = cost; g.TY = ty; g.nbg = nbg; g.units = (int)units; }
+    }
+  }
+  return ng;
+}
+
+}  // namespace
+
+// Shapes of the forward kernel (even W, segmented rows need W % 32 == 0); every bank inside one pool group;
+// the streamed variant is built for whole lanes inside the row and unpadded filter counts.
+bool p4_bwd_data_bf16_supported(const rotconv_plan* p) {
+  if (!p4_fwd_supported(p) || !p4_bwd_data_supported(p)) return false;
+  const rotconv_desc& d = p->d;
+  if (d.W > 256 && (d.W & 31)) return false;
+  if (needs_stream(p) && ((d.W & 31) || cout_pad(d.Cout) != d.Cout)) return false;
+  return true;
+}
+
+size_t p4_bwd_data_bf16_pack_bytes(const rotconv_plan* p) {
+  return (size_t)((p->d.Cin + 15) / 16) * p->host.Q * cout_pad(p->d.Cout) * 144 * sizeof(uint16_t);
+}
+
+void launch_p4_pack_bwd_bf16(const rotconv_plan* p, const uint16_t* w, uint16_t* wt, hipStream_t st) {
+  const int CIB = (p->d.Cin + 15) / 16, CoutPad = cout_pad(p->d.Cout);
+  const int total = CIB * p->host.Q * CoutPad * 144;
+  hipLaunchKernelGGL(k_p4_pack_bwd_bf16, dim3((total + 255) / 256), dim3(256), 0, st, w, wt, p->dev.fq_src,
+                     p->dev.fq_coef, p->host.Q, CIB, CoutPad, p->d.Cin, p->d.Cout);
+}
+
+void launch_p4_bwd_data_bf16(const rotconv_plan* p, const uint16_t* gpool, const uint8_t* idx, const uint16_t* wt,
+                             uint16_t* dx, hipStream_t st) {
+  P4BwdBfGeom gs[4];
+  const int ng = geoms(p, gs, 4);
+  const bool stream = needs_stream(p);
+  const int nd = ring_depth(p->d.Cout);
+  for (int i = 0; i < ng; ++i) {
+    const P4BwdBfGeom& g = gs[i];
+    const bool fastw = (p->d.W & 7) == 0 && g.inside;
+    const bool cpad = g.CoutPad != p->d.Cout;
+    switch (g.nwx) {
+      case 1: launch_d<1, 8>(nd, g, fastw, stream, cpad, gpool, idx, wt, p->dev.rot_of, dx, st); break;
+      case 2: launch_d<2, 4>(nd, g, fastw, stream, cpad, gpool, idx, wt, p->dev.rot_of, dx, st); break;
+      case 4: launch_d<4, 2>(nd, g, fastw, stream, cpad, gpool, idx, wt, p->dev.rot_of, dx, st); break;
+      default: launch_d<8, 1>(nd, g, fastw, stream, cpad, gpool, idx, wt, p->dev.rot_of, dx, st); break;
+    }
+  }
+}
+
+}  // namespace rotconv

@@ -32,6 +32,12 @@ CASES = [
     LC("b_w320", N=1, Cin=16, H=6, W=320, Cout=16, R=4, seed=60),
     LC("b_stream", N=1, Cin=512, H=8, W=32, Cout=16, R=4, x_dist="absnormal", seed=61),
     LC("b_stream_w96", N=1, Cin=576, H=5, W=96, Cout=8, R=8, mode="bilinear", pool_group=4, x_dist="absnormal", seed=62),
+    # filter counts of the input-gradient kernel: two K-steps in flight, padded filters, streamed filter blocks
+    LC("b_co64", N=2, Cin=24, H=10, W=64, Cout=64, R=4, seed=64),
+    LC("b_co96", N=1, Cin=16, H=6, W=40, Cout=96, R=4, seed=65),
+    LC("b_co192_r16", N=1, Cin=16, H=5, W=32, Cout=192, R=16, mode="bilinear", seed=66),
+    LC("b_co576_w96", N=1, Cin=8, H=5, W=96, Cout=576, R=4, seed=67),
+    LC("b_r1", N=1, Cin=24, H=9, W=32, Cout=40, R=1, seed=68),                                 # a standard convolution
 ]
 
 
@@ -91,7 +97,9 @@ def test_bf16_fused_calls(cfg):
     assert_close(f64(dw), dw_ref, f"{cfg.name} dw (fp32)", rtol=RTOL)
 
 
-DYADIC = [CASES[1], CASES[5], CASES[7], LC("b_dy_stream", N=1, Cin=512, H=6, W=64, Cout=16, R=4, seed=63)]
+DYADIC = [CASES[1], CASES[5], CASES[7], LC("b_dy_stream", N=1, Cin=512, H=6, W=64, Cout=16, R=4, seed=63),
+          LC("b_dy_co64", N=1, Cin=40, H=20, W=64, Cout=64, R=4, seed=69),
+          LC("b_dy_co576", N=1, Cin=8, H=5, W=64, Cout=576, R=4, seed=70)]
 
 
 @pytest.mark.parametrize("cfg", DYADIC, ids=[c.name for c in DYADIC])
