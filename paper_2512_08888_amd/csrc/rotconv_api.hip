@@ -102,7 +102,8 @@ int rotconv_plan_create(const rotconv_desc* desc, rotconv_plan** out) {
   if (p->fast[2]) p->ws_bytes = std::max(p->ws_bytes, p4_bwd_weight_ws_floats(p) * sizeof(float));
   if (p->d.dtype == ROTCONV_BF16) {     // scratch of the kernels that take bf16 tensors directly
     if (p->fast[0] && p4_fwd_bf16_supported(p)) p->ws_bytes = std::max(p->ws_bytes, p4_fwd_bf16_pack_bytes(p));
-    if (p->fast[1] && p4_bwd_data_bf16_supported(p)) p->ws_bytes = std::max(p->ws_bytes, p4_bwd_data_bf16_pack_bytes(p));
+    if (p->fast[1] && p4_bwd_data_bf16_supported(p))
+      p->ws_bytes = std::max(p->ws_bytes, align256(p4_bwd_data_bf16_pack_bytes(p)) + p4_bwd_data_bf16_part_bytes(p));
   }
   p->ws_inner = p->ws_bytes = align256(p->ws_bytes);
   const size_t hw_in = (size_t)p->d.H * p->d.W, hw_out = (size_t)p->Ho * p->Wo;
@@ -438,7 +439,8 @@ int rotconv_pool_bwd_data(const rotconv_plan* plan, const void* gpool, const uin
     if (rc) return rc;
     uint16_t* wt = static_cast<uint16_t*>(ws);
     launch_p4_pack_bwd_bf16(p, h16(w), wt, st);
-    launch_p4_bwd_data_bf16(p, h16(gpool), idx, wt, static_cast<uint16_t*>(dx), st);
+    float* part = reinterpret_cast<float*>(static_cast<char*>(ws) + align256(p4_bwd_data_bf16_pack_bytes(p)));
+    launch_p4_bwd_data_bf16(p, h16(gpool), idx, wt, static_cast<uint16_t*>(dx), part, st);
     return finish();
   }
   const Stage s = carve(plan, ws, ws_bytes);

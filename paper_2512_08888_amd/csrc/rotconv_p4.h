@@ -63,14 +63,16 @@ void launch_p4_bwd_data(const rotconv_plan* p, const float* gpool, const uint8_t
 // the roles of filters and channels swapped
 struct P4BwdBfGeom {
   int N, Cin, CIB, H, W, Cout, CoutPad, Q, ng;   // CIB: 16-channel blocks; CoutPad: filters padded to K-steps of 32
-  int TY, nbg, units, nwx, nseg, inside;         // as in P4Geom
+  int TY, nbg, units, nwx, nseg, inside;         // as in P4Geom (units include the K split)
+  int ksplit, kper;                              // workgroups sharing a unit's K-steps; K-steps per workgroup
   int seg_xorg[4], seg_lo[4], seg_hi[4];
 };
 bool p4_bwd_data_bf16_supported(const rotconv_plan* p);
 size_t p4_bwd_data_bf16_pack_bytes(const rotconv_plan* p);
 void launch_p4_pack_bwd_bf16(const rotconv_plan* p, const uint16_t* w, uint16_t* wt, hipStream_t st);
+size_t p4_bwd_data_bf16_part_bytes(const rotconv_plan* p);
 void launch_p4_bwd_data_bf16(const rotconv_plan* p, const uint16_t* gpool, const uint8_t* idx, const uint16_t* wt,
-                             uint16_t* dx, hipStream_t st);
+                             uint16_t* dx, float* part, hipStream_t st);
 
 // weight gradient
 struct P4BwdWGeom {

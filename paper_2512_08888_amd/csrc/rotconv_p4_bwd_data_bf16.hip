@@ -19,8 +19,13 @@
 // like the forward kernel: the row of S_d feeds the output rows above, at and below through two rolling
 // partial sums; column shifts are register renames plus one neighbour value per side (adjacent lane group
 // via ds_bpermute, adjacent wave via LDS).  The (G, idx) rows are prefetched ND K-steps ahead through a
-// register ring; the filter block [K-step][tap][k-group][16 channels][8 filters] is LDS-resident, or
-// streamed in stages of ND K-steps when it exceeds LDS.
+// register ring; a workgroup's share of the filter block [K-step][tap][k-group][16 channels][8 filters]
+// is LDS-resident (at most 16 K-steps = 512 filters of one bank).
+//
+// Deep layers on small maps have few (channel block, band) units but a long contraction (Q * Cout
+// filters): there the K-steps are split over `ksplit` workgroups per unit, each writing an fp32 partial
+// dX; a second kernel adds the partials in a fixed order and rounds to bf16 (deterministic, no atomics).
+// The split is also what keeps each workgroup's share of the filter block within LDS.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -47,57 +52,41 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
 
 // ND:     K-steps the (G, idx) prefetch runs ahead (K-steps per bank are a multiple of ND).
 // FASTW:  W % 8 == 0 and no wave chain reaches beyond the row: no load masks, vector stores.
-// STREAM: the filter block does not fit LDS: stream it in stages of ND K-steps.
 // CPAD:   CoutPad > Cout: filter offsets are clamped to the last real filter (its taps are zero).
-template <int NWX, int NWY, int ND, bool FASTW, bool STREAM, bool CPAD>
+// SPLIT:  the unit's K-steps are shared by g.ksplit workgroups; the result is an fp32 partial in `part`.
+template <int NWX, int NWY, int ND, bool FASTW, bool CPAD, bool SPLIT>
 __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_bwd_data_bf16(const uint16_t* __restrict__ gpool,
                                                                      const uint8_t* __restrict__ idx,
                                                                      const uint16_t* __restrict__ wt,
                                                                      const int32_t* __restrict__ rot_of,
-                                                                     uint16_t* __restrict__ dx, P4BwdBfGeom g) {
+                                                                     uint16_t* __restrict__ dx,
+                                                                     float* __restrict__ part, P4BwdBfGeom g) {
   constexpr int NW = NWX * NWY;
   constexpr int NT = 64 * NW;
-  constexpr int STB = ND * CHB;            // bytes of one streaming stage
   extern __shared__ __attribute__((aligned(16))) char smem_raw[];
-  char* Wl = smem_raw;                     // resident: [nks][CHB]; streamed: [2][STB]
+  char* Wl = smem_raw;                     // [kper][CHB]
   const int nkc = g.CoutPad / 32;          // K-steps per bank
   const int nks = g.Q * nkc;               // K-steps per row
-  float* EL = reinterpret_cast<float*>(smem_raw + (STREAM ? 2 * STB : nks * CHB));  // [2][NW][3][16] left edges
+  float* EL = reinterpret_cast<float*>(smem_raw + g.kper * CHB);  // [2][NW][3][16] left edges
   float* ER = EL + 2 * NW * 48;                                                      // right edges
 
   const int per_xcd = (g.units + 7) / 8;
   int v = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
   if (v >= g.units) return;
+  const int ksp = SPLIT ? v % g.ksplit : 0;     // fastest: the splits of a tile run side by side and share its (G, idx) lines
+  if (SPLIT) v /= g.ksplit;
+  const int kbeg = ksp * g.kper, kend = min(nks, kbeg + g.kper);   // this workgroup's K-steps (multiples of ND)
   const int cib = v % g.CIB; v /= g.CIB;
   const int seg = v % g.nseg; v /= g.nseg;
   const int bg = v % g.nbg;
   const int n = v / g.nbg;
 
   const int tid = threadIdx.x;
-  const char* wsrc = reinterpret_cast<const char*>(wt) + (size_t)cib * nks * CHB;
-  constexpr int WPT = (STB / 16 + NT - 1) / NT;
-  u4 wreg[STREAM ? WPT : 1];
-  auto wload = [&](int stage) {
-#pragma unroll
-    for (int k = 0; k < WPT; ++k) {
-      const int e = tid + k * NT;
-      if (e < STB / 16) wreg[k] = reinterpret_cast<const u4*>(wsrc + (size_t)stage * STB)[e];
-    }
-  };
-  auto wstore = [&](int buf) {
-#pragma unroll
-    for (int k = 0; k < WPT; ++k) {
-      const int e = tid + k * NT;
-      if (e < STB / 16) reinterpret_cast<u4*>(Wl + buf * STB)[e] = wreg[k];
-    }
-  };
-  if (STREAM) {
-    wload(0);
-    wstore(0);
-  } else {
+  const char* wsrc = reinterpret_cast<const char*>(wt) + ((size_t)cib * nks + kbeg) * CHB;
+  {
     const u4* src = reinterpret_cast<const u4*>(wsrc);
     u4* dst = reinterpret_cast<u4*>(Wl);
-    const int n16 = nks * (CHB / 16);
+    const int n16 = (kend - kbeg) * (CHB / 16);
     for (int i = tid; i < n16; i += NT) dst[i] = src[i];
   }
   __syncthreads();
@@ -158,16 +147,16 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_bwd_data_bf16(const uint1
   // ring of ND K-step slots: slot i holds K-step (ksg + i) of the current group; refilled with the K-step
   // ND further on (of this row, or of the next row's first group) right after it has been routed
   uint32_t rg[ND][8], ri[ND][8];
+  const int q_beg = kbeg / nkc, c_beg = kbeg % nkc;
   {
-    const uint32_t base = row_off(0) + (uint32_t)group_of(0) * (uint32_t)HW;
+    const uint32_t base = row_off(0) + (uint32_t)group_of(q_beg) * (uint32_t)HW;
 #pragma unroll
     for (int i = 0; i < ND; ++i)
 #pragma unroll
-      for (int j = 0; j < 8; ++j) { rg[i][j] = load_g(base, i, j); ri[i][j] = load_i(base, i, j); }
+      for (int j = 0; j < 8; ++j) { rg[i][j] = load_g(base, c_beg + i, j); ri[i][j] = load_i(base, c_beg + i, j); }
     __builtin_amdgcn_s_waitcnt(0x0F70);
   }
   const char* wl_lane = Wl + lane * 16;
-  int seq = 0;                           // groups done (streaming: LDS buffer parity)
 
   for (int t = 0; t < nsteps; ++t) {
     const int h = y0 - 1 + t;
@@ -178,17 +167,16 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_bwd_data_bf16(const uint1
     for (int d = 0; d < 9; ++d) { S[d][0] = f4{0.f, 0.f, 0.f, 0.f}; S[d][1] = f4{0.f, 0.f, 0.f, 0.f}; }
 
     auto group = [&](int ksg, bool mul) {
-      const bool last = ksg + ND == nks;
-      const int kn = last ? 0 : ksg + ND;                   // first K-step of the group being prefetched
+      const bool last = ksg + ND == kend;
+      const int kn = last ? kbeg : ksg + ND;                // first K-step of the group being prefetched
       const int qn = kn / nkc, cn = kn % nkc;
       const uint32_t base_n = (last ? ro_nxt : ro_cur) + (uint32_t)group_of(qn) * (uint32_t)HW;
-      if (STREAM) wload(last ? 0 : ksg / ND + 1);
       if (mul) {
         const int q = ksg / nkc;
         int rot[4];
 #pragma unroll
         for (int s = 0; s < 4; ++s) rot[s] = rot_of[q * 4 + s];
-        const char* wc = STREAM ? wl_lane + (seq & 1) * STB : wl_lane + (size_t)ksg * CHB;
+        const char* wc = wl_lane + (size_t)(ksg - kbeg) * CHB;
         u4 bw[3];
         bw[0] = *reinterpret_cast<const u4*>(wc);
         bw[1] = *reinterpret_cast<const u4*>(wc + 1024);
@@ -236,16 +224,11 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_bwd_data_bf16(const uint1
 #pragma unroll
           for (int j = 0; j < 8; ++j) { rg[i][j] = load_g(base_n, cn + i, j); ri[i][j] = load_i(base_n, cn + i, j); }
       }
-      if (STREAM) {
-        wstore((seq + 1) & 1);
-        __syncthreads();
-      }
-      ++seq;
     };
     if (row_ok) {
-      for (int ksg = 0; ksg < nks; ksg += ND) group(ksg, true);
+      for (int ksg = kbeg; ksg < kend; ksg += ND) group(ksg, true);
     } else {
-      for (int ksg = 0; ksg < nks; ksg += ND) group(ksg, false);
+      for (int ksg = kbeg; ksg < kend; ksg += ND) group(ksg, false);
       __builtin_amdgcn_s_waitcnt(0x0F70);   // rare path: drain its loads so the hot loop's wait counts stay exact
     }
 
@@ -313,7 +296,17 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_bwd_data_bf16(const uint1
       accA[j] = accB[j] + tsum[1];      // output row h has product rows h-1, h
       accB[j] = tsum[2];                // output row h+1 has product row h
     }
-    if (fin) {
+    if (fin && SPLIT) {
+      float* o = part + (((size_t)ksp * g.N + n) * g.Cin + ci) * HW + (size_t)y * g.W + px0;
+      if (FASTW) {
+        reinterpret_cast<f4*>(o)[0] = f4{yfin[0], yfin[1], yfin[2], yfin[3]};
+        reinterpret_cast<f4*>(o)[1] = f4{yfin[4], yfin[5], yfin[6], yfin[7]};
+      } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+          if (px0 + j < min(g.W, out_hi)) o[j] = yfin[j];
+      }
+    } else if (fin) {
       uint16_t* o = dx + ((size_t)n * g.Cin + ci) * HW + (size_t)y * g.W + px0;
       if (FASTW) {
         *reinterpret_cast<u4*>(o) = u4{pack_bf16(yfin[0], yfin[1]), pack_bf16(yfin[2], yfin[3]),
@@ -324,6 +317,27 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_bwd_data_bf16(const uint1
           if (px0 + j < min(g.W, out_hi)) o[j] = (uint16_t)(pack_bf16(yfin[j], 0.f) & 0xffffu);
       }
     }
+  }
+}
+
+// dx = bf16(sum over splits, ascending, of the fp32 partials); n8 = elements / 8 (8 elements per thread).
+__global__ __launch_bounds__(256) void k_p4_sum_dx_parts(const float* __restrict__ part, uint16_t* __restrict__ dx,
+                                                         size_t n_elem, int ksplit) {
+  const size_t n8 = n_elem / 8;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += (size_t)gridDim.x * 256) {
+    f4 a = reinterpret_cast<const f4*>(part)[2 * i], b = reinterpret_cast<const f4*>(part)[2 * i + 1];
+    for (int k = 1; k < ksplit; ++k) {
+      const f4* p = reinterpret_cast<const f4*>(part + (size_t)k * n_elem);
+      a += p[2 * i];
+      b += p[2 * i + 1];
+    }
+    reinterpret_cast<u4*>(dx)[i] = u4{pack_bf16(a[0], a[1]), pack_bf16(a[2], a[3]), pack_bf16(b[0], b[1]),
+                                      pack_bf16(b[2], b[3])};
+  }
+  for (size_t e = n8 * 8 + (size_t)blockIdx.x * 256 + threadIdx.x; e < n_elem; e += (size_t)gridDim.x * 256) {
+    float v = part[e];
+    for (int k = 1; k < ksplit; ++k) v += part[(size_t)k * n_elem + e];
+    dx[e] = (uint16_t)(pack_bf16(v, 0.f) & 0xffffu);
   }
 }
 
@@ -360,35 +374,35 @@ __global__ __launch_bounds__(256) void k_p4_pack_bwd_bf16(const uint16_t* __rest
 // filters padded to 32, or to a multiple of 64 (two K-steps in flight)
 int cout_pad(int Cout) { return Cout <= 32 ? 32 : (Cout + 63) / 64 * 64; }
 int ring_depth(int Cout) { return std::min(2, cout_pad(Cout) / 32); }
-bool needs_stream(const rotconv_plan* p) {
-  return (size_t)p->host.Q * (cout_pad(p->d.Cout) / 32) * CHB + 8192 > 160 * 1024;
-}
+constexpr int kResidentSteps = 16;     // K-steps whose filter block fits LDS beside the edge arrays (16 * 9216 + 8192 <= 160 KB)
 
-template <int NWX, int NWY, int ND, bool FASTW, bool STREAM, bool CPAD>
+
+template <int NWX, int NWY, int ND, bool FASTW, bool CPAD, bool SPLIT>
 void launch_i(const P4BwdBfGeom& g, const uint16_t* gp, const uint8_t* idx, const uint16_t* wt, const int32_t* rot_of,
-              uint16_t* dx, hipStream_t st) {
-  const size_t wbytes = STREAM ? (size_t)2 * ND * CHB : (size_t)g.Q * (g.CoutPad / 32) * CHB;
-  const size_t lds = wbytes + (size_t)4 * NWX * NWY * 48 * sizeof(float);
+              uint16_t* dx, float* part, hipStream_t st) {
+  const size_t lds = (size_t)g.kper * CHB + (size_t)4 * NWX * NWY * 48 * sizeof(float);
   const int grid = (g.units + 7) / 8 * 8;
-  auto kern = k_p4_bwd_data_bf16<NWX, NWY, ND, FASTW, STREAM, CPAD>;
+  auto kern = k_p4_bwd_data_bf16<NWX, NWY, ND, FASTW, CPAD, SPLIT>;
   (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * NWX * NWY), lds, st, gp, idx, wt, rot_of, dx, g);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * NWX * NWY), lds, st, gp, idx, wt, rot_of, dx, part, g);
 }
 
-template <int NWX, int NWY, int ND>
-void launch_t(const P4BwdBfGeom& g, bool fastw, bool stream, bool cpad, const uint16_t* gp, const uint8_t* idx,
-              const uint16_t* wt, const int32_t* rot_of, uint16_t* dx, hipStream_t st) {
-  if (stream && fastw) launch_i<NWX, NWY, ND, true, true, false>(g, gp, idx, wt, rot_of, dx, st);
-  else if (stream) launch_i<NWX, NWY, ND, false, true, false>(g, gp, idx, wt, rot_of, dx, st);
-  else if (fastw && !cpad) launch_i<NWX, NWY, ND, true, false, false>(g, gp, idx, wt, rot_of, dx, st);
-  else launch_i<NWX, NWY, ND, false, false, true>(g, gp, idx, wt, rot_of, dx, st);
+template <int NWX, int NWY, int ND, bool SPLIT>
+void launch_t(const P4BwdBfGeom& g, bool fastw, bool cpad, const uint16_t* gp, const uint8_t* idx,
+              const uint16_t* wt, const int32_t* rot_of, uint16_t* dx, float* part, hipStream_t st) {
+  // the specialised instance: whole lanes inside the row, no padded filters; everything else takes the general one
+  if (fastw && !cpad) launch_i<NWX, NWY, ND, true, false, SPLIT>(g, gp, idx, wt, rot_of, dx, part, st);
+  else launch_i<NWX, NWY, ND, false, true, SPLIT>(g, gp, idx, wt, rot_of, dx, part, st);
 }
 
 template <int NWX, int NWY>
-void launch_d(int nd, const P4BwdBfGeom& g, bool fastw, bool stream, bool cpad, const uint16_t* gp, const uint8_t* idx,
-              const uint16_t* wt, const int32_t* rot_of, uint16_t* dx, hipStream_t st) {
-  if (nd == 1) launch_t<NWX, NWY, 1>(g, fastw, stream, cpad, gp, idx, wt, rot_of, dx, st);
-  else launch_t<NWX, NWY, 2>(g, fastw, stream, cpad, gp, idx, wt, rot_of, dx, st);
+void launch_d(int nd, const P4BwdBfGeom& g, bool fastw, bool cpad, const uint16_t* gp, const uint8_t* idx,
+              const uint16_t* wt, const int32_t* rot_of, uint16_t* dx, float* part, hipStream_t st) {
+  const bool split = g.ksplit > 1;
+  if (nd == 1 && split) launch_t<NWX, NWY, 1, true>(g, fastw, cpad, gp, idx, wt, rot_of, dx, part, st);
+  else if (nd == 1) launch_t<NWX, NWY, 1, false>(g, fastw, cpad, gp, idx, wt, rot_of, dx, part, st);
+  else if (split) launch_t<NWX, NWY, 2, true>(g, fastw, cpad, gp, idx, wt, rot_of, dx, part, st);
+  else launch_t<NWX, NWY, 2, false>(g, fastw, cpad, gp, idx, wt, rot_of, dx, part, st);
 }
 
 // Row segments and bands as in the forward kernel (rows cut into chains of at most 256 product columns
@@ -413,6 +427,24 @@ int geoms(const rotconv_plan* p, P4BwdBfGeom* out, int max_out) {
       const long cost = ((units + 255) / 256) * (ty + 2);
       if (best_cost < 0 || cost <= best_cost) { best_cost = cost; g.TY = ty; g.nbg = nbg; g.units = (int)units; }
     }
+    // Split of the K-steps over workgroups: enough workgroups to fill the chip twice, each share small enough
+    // to keep its filter block LDS-resident; all segment launches of a plan use the same split (one partial
+    // buffer), at most 16 parts and 256 MiB of partial sums.
+    const int nd = ring_depth(d.Cout);
+    const int groups = g.Q * (g.CoutPad / 32) / nd;            // prefetch groups of nd K-steps
+    int want = std::max((int)((512 + g.units - 1) / g.units), (groups * nd + kResidentSteps - 1) / kResidentSteps);
+    const double dx_bytes = 4.0 * d.N * d.Cin * d.H * d.W;
+    want = std::min({want, groups, 16, std::max(1, (int)(268435456.0 / dx_bytes))});
+    const int gper = (groups + want - 1) / want;               // groups per split
+    g.kper = gper * nd;
+    g.ksplit = (groups + gper - 1) / gper;
+  }
+  // one split for all launches: the coarsest
+  for (int i = 1; i < ng; ++i)
+    if (out[i].ksplit < out[0].ksplit) { out[0].ksplit = out[i].ksplit; out[0].kper = out[i].kper; }
+  for (int i = 0; i < ng; ++i) {
+    out[i].ksplit = out[0].ksplit; out[i].kper = out[0].kper;
+    out[i].units *= out[i].ksplit;
   }
   return ng;
 }
@@ -420,13 +452,21 @@ int geoms(const rotconv_plan* p, P4BwdBfGeom* out, int max_out) {
 }  // namespace
 
 // Shapes of the forward kernel (even W, segmented rows need W % 32 == 0); every bank inside one pool group;
-// the streamed variant is built for whole lanes inside the row and unpadded filter counts.
+// after the K split a workgroup's share of the filter block must fit LDS.
 bool p4_bwd_data_bf16_supported(const rotconv_plan* p) {
   if (!p4_fwd_supported(p) || !p4_bwd_data_supported(p)) return false;
   const rotconv_desc& d = p->d;
   if (d.W > 256 && (d.W & 31)) return false;
-  if (needs_stream(p) && ((d.W & 31) || cout_pad(d.Cout) != d.Cout)) return false;
-  return true;
+  P4BwdBfGeom gs[4];
+  if (geoms(p, gs, 4) < 1) return false;
+  return gs[0].kper <= kResidentSteps;
+}
+
+// fp32 partial sums [ksplit][N][Cin][H][W] behind the packed bank (0 when the K-steps are not split)
+size_t p4_bwd_data_bf16_part_bytes(const rotconv_plan* p) {
+  P4BwdBfGeom gs[4];
+  if (geoms(p, gs, 4) < 1 || gs[0].ksplit <= 1) return 0;
+  return (size_t)gs[0].ksplit * p->d.N * p->d.Cin * p->d.H * p->d.W * sizeof(float);
 }
 
 size_t p4_bwd_data_bf16_pack_bytes(const rotconv_plan* p) {
@@ -440,22 +480,27 @@ void launch_p4_pack_bwd_bf16(const rotconv_plan* p, const uint16_t* w, uint16_t*
                      p->dev.fq_coef, p->host.Q, CIB, CoutPad, p->d.Cin, p->d.Cout);
 }
 
+// part: scratch of p4_bwd_data_bf16_part_bytes() bytes (unused when that is 0)
 void launch_p4_bwd_data_bf16(const rotconv_plan* p, const uint16_t* gpool, const uint8_t* idx, const uint16_t* wt,
-                             uint16_t* dx, hipStream_t st) {
+                             uint16_t* dx, float* part, hipStream_t st) {
   P4BwdBfGeom gs[4];
   const int ng = geoms(p, gs, 4);
-  const bool stream = needs_stream(p);
   const int nd = ring_depth(p->d.Cout);
   for (int i = 0; i < ng; ++i) {
     const P4BwdBfGeom& g = gs[i];
     const bool fastw = (p->d.W & 7) == 0 && g.inside;
     const bool cpad = g.CoutPad != p->d.Cout;
     switch (g.nwx) {
-      case 1: launch_d<1, 8>(nd, g, fastw, stream, cpad, gpool, idx, wt, p->dev.rot_of, dx, st); break;
-      case 2: launch_d<2, 4>(nd, g, fastw, stream, cpad, gpool, idx, wt, p->dev.rot_of, dx, st); break;
-      case 4: launch_d<4, 2>(nd, g, fastw, stream, cpad, gpool, idx, wt, p->dev.rot_of, dx, st); break;
-      default: launch_d<8, 1>(nd, g, fastw, stream, cpad, gpool, idx, wt, p->dev.rot_of, dx, st); break;
+      case 1: launch_d<1, 8>(nd, g, fastw, cpad, gpool, idx, wt, p->dev.rot_of, dx, part, st); break;
+      case 2: launch_d<2, 4>(nd, g, fastw, cpad, gpool, idx, wt, p->dev.rot_of, dx, part, st); break;
+      case 4: launch_d<4, 2>(nd, g, fastw, cpad, gpool, idx, wt, p->dev.rot_of, dx, part, st); break;
+      default: launch_d<8, 1>(nd, g, fastw, cpad, gpool, idx, wt, p->dev.rot_of, dx, part, st); break;
     }
+  }
+  if (ng > 0 && gs[0].ksplit > 1) {
+    const size_t n_elem = (size_t)p->d.N * p->d.Cin * p->d.H * p->d.W;
+    const unsigned blocks = (unsigned)std::max<size_t>(1, std::min<size_t>((n_elem / 8 + 255) / 256, 1u << 16));
+    hipLaunchKernelGGL(k_p4_sum_dx_parts, dim3(blocks), dim3(256), 0, st, part, dx, n_elem, gs[0].ksplit);
   }
 }
 
