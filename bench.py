@@ -168,6 +168,9 @@ def main():
     ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4", "C5", "P4", "P8", "P16"])
     ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"],
                     help="storage type of activations and weights (accumulation is fp32 either way)")
+    ap.add_argument("--pool-op", default="max", choices=["max", "avg"],
+                    help="orientation pooling of the single-layer workloads: max (Eq. 10, the benchmark) or average "
+                         "(Eq. 9: one ordinary convolution with the group-averaged bank)")
     ap.add_argument("--no-unet", action="store_true", help="skip the UNet-shaped steps appended to the default line")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -191,7 +194,8 @@ def main():
     cfg = synth.CONFIGS[args.workload]
     bf = args.dtype == "bf16"
     adt = torch.bfloat16 if bf else torch.float32      # storage of x, w, g, ypool, dx; dw is fp32 either way
-    plan = rc.Plan.from_config(cfg, dtype=rc.BF16 if bf else rc.F32)
+    plan = rc.Plan.from_config(cfg, dtype=rc.BF16 if bf else rc.F32, pool_op=args.pool_op)
+    avg = args.pool_op == "avg"
     Q = plan.orientations()[0]
     x = torch.from_numpy(synth.make_x(cfg)).cuda().to(adt)
     w = torch.from_numpy(synth.make_w(cfg)).cuda().to(adt)
@@ -237,6 +241,8 @@ def main():
                for i in range(3)]
     names = ["rotconv_pool_fwd", "rotconv_pool_bwd_data", "rotconv_pool_bwd_weight"]
     fa, fd = flops_alg(cfg, Q), flops_dense(cfg)
+    if avg:     # the mean commutes with the convolution: one conv-equivalent per pooled channel, no placement adds
+        fa = 2.0 * cfg.N * cfg.Ho * cfg.Wo * cfg.Cin * plan.Cpooled * cfg.k * cfg.k
     dom = max(range(3), key=lambda i: pass_ms[i])
     achieved = fa / (pass_ms[dom] * 1e-3) / 1e12
     traffic = None
@@ -252,7 +258,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
         "config": {
             "workload": f"{cfg.name}: N={cfg.N} Cin={cfg.Cin} Cout={cfg.Cout} {cfg.H}x{cfg.W} k={cfg.k} R={cfg.R} "
-                        f"{cfg.mode} G={cfg.G} stride={cfg.stride} pad={cfg.pad}, fused fwd+bwd_data+bwd_weight",
+                        f"{cfg.mode} G={cfg.G} stride={cfg.stride} pad={cfg.pad} pool={args.pool_op}, "
+                        f"fused fwd+bwd_data+bwd_weight",
             "flops_per_pass_algorithmic": fa, "flops_per_pass_dense_equivalent": fd,
             "dense_equivalent_tflops": 3.0 * fd / (ms_step * 1e-3) / 1e12,
             "pass_ms": dict(zip(names, pass_ms)),
@@ -264,9 +271,9 @@ def main():
             "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak, "traffic": traffic,
         },
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not avg:
         out["cpu_baseline"] = cpu_baseline(cfg, Q)
-    if args.workload == "C2" and not args.no_unet and not bf:
+    if args.workload == "C2" and not args.no_unet and not bf and not avg:
         # the second half of the headline metric: ms per UNet-shaped training step at R=4 and R=16
         del x, w, g, yp, idx, dx, dw
         out["unet_train_step"] = {n: bench_unet(n, 5, 2) for n in ("C4", "C5")}

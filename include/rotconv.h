@@ -6,7 +6,9 @@
  * R responses of a filter are max-pooled over orientation groups with the
  * arg-max kept (Eq. 10), and the backward passes route the upstream gradient
  * through the arg-max (Eq. 12) into the input gradient (Eq. 13, 15) and the
- * base-weight gradient (Eq. 14, 16).  Orientations whose angles differ by
+ * base-weight gradient (Eq. 14, 16).  Point-wise average pooling over the
+ * orientation groups (Eq. 9, gradient shared equally: Eq. 11) is the other
+ * pooling the paper names; a plan selects it with pool_op.  Orientations whose angles differ by
  * multiples of 90 degrees share their per-tap channel contractions (Eq. 8);
  * other angles get one first-quadrant filter each plus its three quarter-turn
  * copies (Sec. III-D).
@@ -64,6 +66,7 @@ typedef enum {
 
 typedef enum { ROTCONV_F32 = 0, ROTCONV_BF16 = 1 } rotconv_dtype;
 typedef enum { ROTCONV_EXACT90 = 0, ROTCONV_STEERABLE = 1, ROTCONV_BILINEAR = 2 } rotconv_mode;
+typedef enum { ROTCONV_POOL_MAX = 0, ROTCONV_POOL_AVG = 1 } rotconv_pool_op;
 
 /* Problem statement of Sec. III (input C_in x H x W, filters C_out x C_in x K x K),
  * with a batch dimension, an orientation set, stride and zero padding. */
@@ -85,9 +88,16 @@ typedef struct {
                                ROTCONV_BF16: those tensors hold bfloat16; products are
                                accumulated in fp32, the arg-max is taken on the fp32
                                values before y / ypool are rounded (nearest even) to
-                               bf16; dw stays fp32; idx stays uint8.  This build widens
-                               the bf16 tensors to fp32 in the workspace and runs the
-                               fp32 kernels on the copies (no bf16 matrix instructions). */
+                               bf16; dw stays fp32; idx stays uint8.  The rotated banks a
+                               bf16 plan multiplies with are bf16 too (the first-quadrant
+                               combination is formed in fp32 and rounded once).  3x3 /
+                               stride 1 / pad 1 layers run on the bf16 matrix cores; other
+                               shapes are widened to fp32 in the workspace and run the
+                               fp32 kernels. */
+  int32_t pool_op;          /* rotconv_pool_op.  ROTCONV_POOL_MAX (0): Eq. 10 / Eq. 12.
+                               ROTCONV_POOL_AVG: ypool = mean over the pool group (Eq. 9),
+                               every member receives gpool / G (Eq. 11); `idx` arguments are
+                               ignored and may be NULL.  fp32 plans only. */
 } rotconv_desc;
 
 typedef struct rotconv_plan rotconv_plan; /* opaque */
@@ -124,15 +134,19 @@ int rotconv_bwd_data(const rotconv_plan* plan, const void* dy, const void* w, vo
  * x, dy, dw DEVICE; dw is fp32. */
 int rotconv_bwd_weight(const rotconv_plan* plan, const void* x, const void* dy, float* dw, void* ws, size_t ws_bytes,
                        void* stream);
-/* Eq. 10 over pool groups, with arg-max.  y, ypool, idx DEVICE. */
+/* Eq. 10 over pool groups, with arg-max (ROTCONV_POOL_AVG plans: Eq. 9, the mean; idx untouched).
+ * y, ypool, idx DEVICE. */
 int orient_maxpool_fwd(const rotconv_plan* plan, const void* y, void* ypool, uint8_t* idx, void* stream);
 /* Eq. 12: dy[n,co*R+r] = gpool[n,co*(R/G)+g] if idx == r else 0.  gpool, idx, dy DEVICE.
- * idx values that are not members of their pool group give zeros. */
+ * idx values that are not members of their pool group give zeros.
+ * ROTCONV_POOL_AVG plans: Eq. 11, dy[n,co*R+r] = gpool[n,co*(R/G)+g] / G. */
 int orient_maxpool_bwd(const rotconv_plan* plan, const void* gpool, const uint8_t* idx, void* dy, void* stream);
 
 /* ---- the fused hot path: the R-fold tensors y / dy are never materialised ------ */
 
-/* Eq. 8 + Eq. 10 in one pass: the input tile is read once and shared by all rotated copies. */
+/* Eq. 8 + Eq. 10 in one pass: the input tile is read once and shared by all rotated copies.
+ * ROTCONV_POOL_AVG plans: the mean over a pool group is linear in the bank, so the three fused calls
+ * run ONE ordinary convolution with the group-averaged bank (1/G) sum_r W^(r) (and its adjoints). */
 int rotconv_pool_fwd(const rotconv_plan* plan, const void* x, const void* w, void* ypool, uint8_t* idx, void* ws,
                      size_t ws_bytes, void* stream);
 /* Eq. 12 + Eq. 13 + Eq. 15. */

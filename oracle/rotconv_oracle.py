@@ -161,6 +161,34 @@ def orient_maxpool_bwd(gpool, idx, R: int, pool_group: Optional[int] = None) -> 
     return dy
 
 
+def orient_avgpool_fwd(y, pool_group: Optional[int] = None) -> np.ndarray:
+    """Eq. 9 over pool groups: the point-wise mean of the group's orientations.
+    y [N,Cout,R,Ho,Wo] -> ypool [N,Cout*(R/G),Ho,Wo]; group g holds the orientations r with r mod (R/G) == g."""
+    y = _f64(y)
+    N, Cout, R, Ho, Wo = y.shape
+    G = R if pool_group is None else pool_group
+    assert R % G == 0
+    ng = R // G
+    yp = np.zeros((N, Cout, ng, Ho, Wo), dtype=np.float64)
+    for r in range(R):                      # plain loop over orientations, in order
+        yp[:, :, r % ng] += y[:, :, r]
+    return (yp / G).reshape(N, Cout * ng, Ho, Wo)
+
+
+def orient_avgpool_bwd(gpool, R: int, pool_group: Optional[int] = None) -> np.ndarray:
+    """Eq. 11: the upstream gradient is shared equally by the group's members.  -> Delta [N,Cout,R,Ho,Wo]."""
+    g = _f64(gpool)
+    G = R if pool_group is None else pool_group
+    ng = R // G
+    N, Cp, Ho, Wo = g.shape
+    Cout = Cp // ng
+    g = g.reshape(N, Cout, ng, Ho, Wo)
+    dy = np.empty((N, Cout, R, Ho, Wo), dtype=np.float64)
+    for r in range(R):
+        dy[:, :, r] = g[:, :, r % ng] / G
+    return dy
+
+
 def rotconv_bwd_data(dy, w_rot, H: int, W: int, stride: int = 1, pad: int = 0) -> np.ndarray:
     """Eq. 13 + 15.  dy [N,Cout,R,Ho,Wo] -> dx [N,Cin,H,W]."""
     dy = _f64(dy)
@@ -231,4 +259,22 @@ def layer_bwd(x, w_base, gpool, idx, R, angles_deg=None, mode="exact90", stride=
     dx = rotconv_bwd_data(dy, w_rot, x.shape[2], x.shape[3], stride, pad)
     dw_rot = rotconv_bwd_weight(x, dy, k, stride, pad)
     dw = reduce_bank_grad(dw_rot, angles_deg, mode)
+    return dx, dw
+
+
+def layer_fwd_avg(x, w_base, R, angles_deg=None, mode="exact90", stride=1, pad=0, pool_group=None):
+    """Rotated banks -> Eq. 7 -> Eq. 9.  Returns (y, ypool, w_rot)."""
+    w_rot = expand_bank(w_base, R, angles_deg, mode)
+    y = rotconv_fwd(x, w_rot, stride, pad)
+    return y, orient_avgpool_fwd(y, pool_group), w_rot
+
+
+def layer_bwd_avg(x, w_base, gpool, R, angles_deg=None, mode="exact90", stride=1, pad=0, pool_group=None):
+    """Eq. 11 -> Eq. 13/15 and Eq. 14/16.  Returns (dx, dw_base [B,Cout,Cin,k,k])."""
+    x = _f64(x)
+    w_rot = expand_bank(w_base, R, angles_deg, mode)
+    k = w_rot.shape[-1]
+    dy = orient_avgpool_bwd(gpool, R, pool_group)
+    dx = rotconv_bwd_data(dy, w_rot, x.shape[2], x.shape[3], stride, pad)
+    dw = reduce_bank_grad(rotconv_bwd_weight(x, dy, k, stride, pad), angles_deg, mode)
     return dx, dw

@@ -17,6 +17,7 @@ OK = 0
 ERR_NULL, ERR_SHAPE, ERR_ANGLES, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_LAUNCH = -1, -2, -3, -4, -5, -6
 F32, BF16 = 0, 1
 MODES = {"exact90": 0, "steerable": 1, "bilinear": 2}
+POOL_OPS = {"max": 0, "avg": 1}
 
 EXPORTS = [
     "rotconv_plan_create", "rotconv_plan_destroy", "rotconv_workspace_bytes", "rotconv_out_shape",
@@ -44,7 +45,7 @@ class Desc(ctypes.Structure):
         ("Cout", ctypes.c_int32), ("k", ctypes.c_int32), ("R", ctypes.c_int32),
         ("angles_deg", ctypes.POINTER(ctypes.c_double)),
         ("mode", ctypes.c_int32), ("stride", ctypes.c_int32), ("pad", ctypes.c_int32),
-        ("pool_group", ctypes.c_int32), ("dtype", ctypes.c_int32),
+        ("pool_group", ctypes.c_int32), ("dtype", ctypes.c_int32), ("pool_op", ctypes.c_int32),
     ]
 
 
@@ -139,7 +140,7 @@ class Plan:
     """Owns a rotconv_plan*.  Mirrors rotconv_plan_create / destroy and the host-side queries."""
 
     def __init__(self, N, Cin, H, W, Cout, k=3, R=4, angles_deg: Optional[Sequence[float]] = None, mode="exact90",
-                 stride=1, pad=1, pool_group=0, dtype=F32):
+                 stride=1, pad=1, pool_group=0, dtype=F32, pool_op="max"):
         self._h = ctypes.c_void_p()
         self._angles = None
         ang = None
@@ -147,7 +148,8 @@ class Plan:
             self._angles = (ctypes.c_double * len(angles_deg))(*[float(a) for a in angles_deg])
             ang = ctypes.cast(self._angles, ctypes.POINTER(ctypes.c_double))
         m = MODES[mode] if isinstance(mode, str) else int(mode)
-        self.desc = Desc(N, Cin, H, W, Cout, k, R, ang, m, stride, pad, pool_group or 0, dtype)
+        po = POOL_OPS[pool_op] if isinstance(pool_op, str) else int(pool_op)
+        self.desc = Desc(N, Cin, H, W, Cout, k, R, ang, m, stride, pad, pool_group or 0, dtype, po)
         _check(lib().rotconv_plan_create(ctypes.byref(self.desc), ctypes.byref(self._h)), "rotconv_plan_create")
         ho, wo, cu, cp = (ctypes.c_int32() for _ in range(4))
         lib().rotconv_out_shape(self._h, ctypes.byref(ho), ctypes.byref(wo), ctypes.byref(cu), ctypes.byref(cp))

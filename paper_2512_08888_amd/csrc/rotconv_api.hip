@@ -80,6 +80,20 @@ int check_ws_inner(const rotconv_plan* p, const void* ws, size_t ws_bytes) {
   return ROTCONV_OK;
 }
 
+// Scratch of an average-pooling plan: rotated banks, the group-averaged bank (or its gradient), an all-zero idx
+// map for the R = 1 plan's fused gradient calls, then that plan's own scratch.
+struct AvgLayout { size_t wexp, wavg, idx0, child, total; };
+AvgLayout avg_layout(const rotconv_plan* p) {
+  AvgLayout L;
+  const size_t bank = (size_t)p->d.Cout * p->d.Cin * p->kk * sizeof(float);
+  L.wexp = 0;
+  L.wavg = align256((size_t)p->d.R * bank);
+  L.idx0 = L.wavg + align256((size_t)p->ng * bank);
+  L.child = L.idx0 + align256(p->n_yp);
+  L.total = L.child + align256(p->avg_child ? p->avg_child->ws_bytes : 0);
+  return L;
+}
+
 }  // namespace
 }  // namespace rotconv
 
@@ -117,12 +131,26 @@ int rotconv_plan_create(const rotconv_desc* desc, rotconv_plan** out) {
     p->native16[1] = p->fast[1] && p4_bwd_data_bf16_supported(p) ? 1 : 0;
     p->native16[2] = p->fast[2] && p4_bwd_weight_bf16_supported(p) ? 1 : 0;
   }
+  if (p->d.pool_op == ROTCONV_POOL_AVG) {
+    // the fused calls of an average-pooling plan run an ordinary convolution (R = 1) with Cout * R/G filters
+    rotconv_desc cd = p->d;
+    cd.Cout = p->d.Cout * p->ng; cd.R = 1; cd.angles_deg = nullptr; cd.mode = ROTCONV_EXACT90; cd.pool_group = 0;
+    cd.pool_op = ROTCONV_POOL_MAX;
+    const int crc = rotconv_plan_create(&cd, &p->avg_child);
+    if (crc != ROTCONV_OK) {
+      delete p;
+      return crc;
+    }
+    const AvgLayout L = avg_layout(p);
+    p->ws_inner = p->ws_bytes = std::max(p->ws_bytes, L.total);
+  }
   *out = p;
   return ROTCONV_OK;
 }
 
 int rotconv_plan_destroy(rotconv_plan* plan) {
   if (!plan) return ROTCONV_OK;
+  if (plan->avg_child) rotconv_plan_destroy(plan->avg_child);
   free_device_tables(plan);
   delete plan;
   return ROTCONV_OK;
@@ -211,6 +239,11 @@ static int f32_rotconv_bwd_weight(const rotconv_plan* plan, const void* x, const
 }
 
 static int f32_orient_maxpool_fwd(const rotconv_plan* plan, const void* y, void* ypool, uint8_t* idx, void* stream) {
+  if (plan && plan->avg_child) {
+    if (!y || !ypool) return ROTCONV_ERR_NULL;
+    launch_avgpool_fwd(plan, static_cast<const float*>(y), static_cast<float*>(ypool), static_cast<hipStream_t>(stream));
+    return finish();
+  }
   if (!plan || !y || !ypool || !idx) return ROTCONV_ERR_NULL;
   launch_maxpool_fwd(plan, static_cast<const float*>(y), static_cast<float*>(ypool), idx,
                      static_cast<hipStream_t>(stream));
@@ -218,6 +251,11 @@ static int f32_orient_maxpool_fwd(const rotconv_plan* plan, const void* y, void*
 }
 
 static int f32_orient_maxpool_bwd(const rotconv_plan* plan, const void* gpool, const uint8_t* idx, void* dy, void* stream) {
+  if (plan && plan->avg_child) {
+    if (!gpool || !dy) return ROTCONV_ERR_NULL;
+    launch_avgpool_bwd(plan, static_cast<const float*>(gpool), static_cast<float*>(dy), static_cast<hipStream_t>(stream));
+    return finish();
+  }
   if (!plan || !gpool || !idx || !dy) return ROTCONV_ERR_NULL;
   launch_maxpool_bwd(plan, static_cast<const float*>(gpool), idx, static_cast<float*>(dy),
                      static_cast<hipStream_t>(stream));
@@ -226,12 +264,21 @@ static int f32_orient_maxpool_bwd(const rotconv_plan* plan, const void* gpool, c
 
 static int f32_rotconv_pool_fwd(const rotconv_plan* plan, const void* x, const void* w, void* ypool, uint8_t* idx, void* ws,
                      size_t ws_bytes, void* stream) {
-  if (!plan || !x || !w || !ypool || !idx) return ROTCONV_ERR_NULL;
+  if (!plan || !x || !w || !ypool || (!idx && !plan->avg_child)) return ROTCONV_ERR_NULL;
   int rc = check_ws_inner(plan, ws, ws_bytes);
   if (rc) return rc;
   rotconv_plan* p = const_cast<rotconv_plan*>(plan);
   if ((rc = ensure_device_tables(p))) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
+  if (p->avg_child) {     // Eq. 9: the mean over a group = one convolution with the group-averaged bank
+    const AvgLayout L = avg_layout(p);
+    char* c = static_cast<char*>(ws);
+    float* wexp = reinterpret_cast<float*>(c + L.wexp);
+    float* wavg = reinterpret_cast<float*>(c + L.wavg);
+    launch_expand_bank(p, static_cast<const float*>(w), wexp, st);
+    launch_avg_bank(p, wexp, wavg, st);
+    return f32_rotconv_fwd(p->avg_child, x, wavg, ypool, c + L.child, p->avg_child->ws_bytes, stream);
+  }
   if (p->fast[0] && aligned(x, 8) && aligned(ws, 256) && aligned(ypool, 16) && aligned(idx, 8)) {
     float* wt = static_cast<float*>(ws);
     char* extra = static_cast<char*>(ws) + align256(p4_fwd_pack_floats(p) * sizeof(float));
@@ -260,12 +307,23 @@ static int f32_rotconv_pool_fwd(const rotconv_plan* plan, const void* x, const v
 
 static int f32_rotconv_pool_bwd_data(const rotconv_plan* plan, const void* gpool, const uint8_t* idx, const void* w, void* dx,
                           void* ws, size_t ws_bytes, void* stream) {
-  if (!plan || !gpool || !idx || !w || !dx) return ROTCONV_ERR_NULL;
+  if (!plan || !gpool || (!idx && !plan->avg_child) || !w || !dx) return ROTCONV_ERR_NULL;
   int rc = check_ws_inner(plan, ws, ws_bytes);
   if (rc) return rc;
   rotconv_plan* p = const_cast<rotconv_plan*>(plan);
   if ((rc = ensure_device_tables(p))) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
+  if (p->avg_child) {     // Eq. 11 + 13 + 15: the input gradient of that one convolution (its only orientation is 0)
+    const AvgLayout L = avg_layout(p);
+    char* c = static_cast<char*>(ws);
+    float* wexp = reinterpret_cast<float*>(c + L.wexp);
+    float* wavg = reinterpret_cast<float*>(c + L.wavg);
+    uint8_t* idx0 = reinterpret_cast<uint8_t*>(c + L.idx0);
+    launch_expand_bank(p, static_cast<const float*>(w), wexp, st);
+    launch_avg_bank(p, wexp, wavg, st);
+    launch_fill_u8(idx0, p->n_yp, 0, st);
+    return f32_rotconv_pool_bwd_data(p->avg_child, gpool, idx0, wavg, dx, c + L.child, p->avg_child->ws_bytes, stream);
+  }
   if (p->fast[1] && aligned(gpool, 8) && aligned(idx, 2) && aligned(dx, 16) && aligned(ws, 16)) {
     float* wd = static_cast<float*>(ws);
     launch_p4_pack_bwd(p, static_cast<const float*>(w), wd, st);
@@ -280,12 +338,24 @@ static int f32_rotconv_pool_bwd_data(const rotconv_plan* plan, const void* gpool
 
 static int f32_rotconv_pool_bwd_weight(const rotconv_plan* plan, const void* x, const void* gpool, const uint8_t* idx, float* dw,
                             void* ws, size_t ws_bytes, void* stream) {
-  if (!plan || !x || !gpool || !idx || !dw) return ROTCONV_ERR_NULL;
+  if (!plan || !x || !gpool || (!idx && !plan->avg_child) || !dw) return ROTCONV_ERR_NULL;
   int rc = check_ws_inner(plan, ws, ws_bytes);
   if (rc) return rc;
   rotconv_plan* p = const_cast<rotconv_plan*>(plan);
   if ((rc = ensure_device_tables(p))) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
+  if (p->avg_child) {     // Eq. 11 + 14 + 16: that convolution's weight gradient, shared out to the R banks, reduced
+    const AvgLayout L = avg_layout(p);
+    char* c = static_cast<char*>(ws);
+    float* rep = reinterpret_cast<float*>(c + L.wexp);
+    float* dwavg = reinterpret_cast<float*>(c + L.wavg);
+    uint8_t* idx0 = reinterpret_cast<uint8_t*>(c + L.idx0);
+    launch_fill_u8(idx0, p->n_yp, 0, st);
+    rc = f32_rotconv_pool_bwd_weight(p->avg_child, x, gpool, idx0, dwavg, c + L.child, p->avg_child->ws_bytes, stream);
+    if (rc) return rc;
+    launch_avg_bank_bwd(p, dwavg, rep, dw, st);
+    return finish();
+  }
   if (p->fast[2] && aligned(x, 16) && aligned(gpool, 16) && aligned(idx, 4) && aligned(ws, 16)) {
     launch_p4_bwd_weight(p, static_cast<const float*>(x), static_cast<const float*>(gpool), idx,
                          static_cast<float*>(ws), dw, st);
@@ -378,14 +448,14 @@ int rotconv_bwd_weight(const rotconv_plan* plan, const void* x, const void* dy, 
 }
 
 int orient_maxpool_fwd(const rotconv_plan* plan, const void* y, void* ypool, uint8_t* idx, void* stream) {
-  if (!plan || !y || !ypool || !idx) return ROTCONV_ERR_NULL;
+  if (!plan || !y || !ypool || (!idx && !plan->avg_child)) return ROTCONV_ERR_NULL;
   if (!is_bf16(plan)) return f32_orient_maxpool_fwd(plan, y, ypool, idx, stream);
   launch_maxpool_fwd_bf16(plan, h16(y), static_cast<uint16_t*>(ypool), idx, static_cast<hipStream_t>(stream));
   return finish();
 }
 
 int orient_maxpool_bwd(const rotconv_plan* plan, const void* gpool, const uint8_t* idx, void* dy, void* stream) {
-  if (!plan || !gpool || !idx || !dy) return ROTCONV_ERR_NULL;
+  if (!plan || !gpool || (!idx && !plan->avg_child) || !dy) return ROTCONV_ERR_NULL;
   if (!is_bf16(plan)) return f32_orient_maxpool_bwd(plan, gpool, idx, dy, stream);
   launch_maxpool_bwd_bf16(plan, h16(gpool), idx, static_cast<uint16_t*>(dy), static_cast<hipStream_t>(stream));
   return finish();
@@ -393,7 +463,7 @@ int orient_maxpool_bwd(const rotconv_plan* plan, const void* gpool, const uint8_
 
 int rotconv_pool_fwd(const rotconv_plan* plan, const void* x, const void* w, void* ypool, uint8_t* idx, void* ws,
                      size_t ws_bytes, void* stream) {
-  if (!plan || !x || !w || !ypool || !idx) return ROTCONV_ERR_NULL;
+  if (!plan || !x || !w || !ypool || (!idx && !plan->avg_child)) return ROTCONV_ERR_NULL;
   if (!is_bf16(plan)) return f32_rotconv_pool_fwd(plan, x, w, ypool, idx, ws, ws_bytes, stream);
   if (!ws || ws_bytes < plan->ws_bytes) return ROTCONV_ERR_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -429,7 +499,7 @@ int rotconv_pool_fwd(const rotconv_plan* plan, const void* x, const void* w, voi
 
 int rotconv_pool_bwd_data(const rotconv_plan* plan, const void* gpool, const uint8_t* idx, const void* w, void* dx,
                           void* ws, size_t ws_bytes, void* stream) {
-  if (!plan || !gpool || !idx || !w || !dx) return ROTCONV_ERR_NULL;
+  if (!plan || !gpool || (!idx && !plan->avg_child) || !w || !dx) return ROTCONV_ERR_NULL;
   if (!is_bf16(plan)) return f32_rotconv_pool_bwd_data(plan, gpool, idx, w, dx, ws, ws_bytes, stream);
   if (!ws || ws_bytes < plan->ws_bytes) return ROTCONV_ERR_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -454,7 +524,7 @@ int rotconv_pool_bwd_data(const rotconv_plan* plan, const void* gpool, const uin
 
 int rotconv_pool_bwd_weight(const rotconv_plan* plan, const void* x, const void* gpool, const uint8_t* idx, float* dw,
                             void* ws, size_t ws_bytes, void* stream) {
-  if (!plan || !x || !gpool || !idx || !dw) return ROTCONV_ERR_NULL;
+  if (!plan || !x || !gpool || (!idx && !plan->avg_child) || !dw) return ROTCONV_ERR_NULL;
   if (!is_bf16(plan)) return f32_rotconv_pool_bwd_weight(plan, x, gpool, idx, dw, ws, ws_bytes, stream);
   if (!ws || ws_bytes < plan->ws_bytes) return ROTCONV_ERR_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);

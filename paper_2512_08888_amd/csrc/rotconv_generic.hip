@@ -147,6 +147,55 @@ __global__ __launch_bounds__(256) void k_maxpool_bwd(const T* __restrict__ gpool
   dy[((size_t)n * g.Cout * g.R + chan) * P + p] = (idx[q] == r) ? gpool[q] : T(0);
 }
 
+// Eq. 9: mean over each pool group.
+__global__ __launch_bounds__(256) void k_avgpool_fwd(const float* __restrict__ y, float* __restrict__ ypool, Geom g) {
+  const int P = g.Ho * g.Wo;
+  const int p = blockIdx.x * 256 + threadIdx.x;
+  if (p >= P) return;
+  const int chan = blockIdx.y, n = blockIdx.z;
+  const int co = chan / g.ng, grp = chan % g.ng;
+  const float* yb = y + ((size_t)n * g.Cout + co) * g.R * P + p;
+  float s = 0.f;
+  for (int r = grp; r < g.R; r += g.ng) s += yb[(size_t)r * P];
+  ypool[((size_t)n * g.Cout * g.ng + chan) * P + p] = s * (1.0f / (float)g.G);
+}
+
+// Eq. 11: every member of the group receives gpool / G.
+__global__ __launch_bounds__(256) void k_avgpool_bwd(const float* __restrict__ gpool, float* __restrict__ dy, Geom g) {
+  const int P = g.Ho * g.Wo;
+  const int p = blockIdx.x * 256 + threadIdx.x;
+  if (p >= P) return;
+  const int chan = blockIdx.y, n = blockIdx.z;   // chan = co*R + r
+  const int co = chan / g.R, r = chan % g.R;
+  const size_t q = (((size_t)n * g.Cout + co) * g.ng + r % g.ng) * P + p;
+  dy[((size_t)n * g.Cout * g.R + chan) * P + p] = gpool[q] * (1.0f / (float)g.G);
+}
+
+// Group-averaged bank: wavg[(co*ng+grp)][ci][t] = (1/G) sum_{r mod ng == grp} wexp[r][co][ci][t].
+__global__ __launch_bounds__(256) void k_avg_bank(const float* __restrict__ wexp, float* __restrict__ wavg, int R,
+                                                  int ng, int Cout, int per /* Cin*kk */) {
+  const int total = Cout * ng * per;
+  const int e = blockIdx.x * 256 + threadIdx.x;
+  if (e >= total) return;
+  const int t = e % per, chan = e / per;
+  const int co = chan / ng, grp = chan % ng;
+  float s = 0.f;
+  for (int r = grp; r < R; r += ng) s += wexp[((size_t)r * Cout + co) * per + t];
+  wavg[e] = s * (1.0f / (float)(R / ng));
+}
+// Adjoint of k_avg_bank: rep[r][co][ci][t] = dwavg[(co*ng + r mod ng)][ci][t] / G.
+__global__ __launch_bounds__(256) void k_avg_bank_bwd(const float* __restrict__ dwavg, float* __restrict__ rep, int R,
+                                                      int ng, int Cout, int per) {
+  const int total = R * Cout * per;
+  const int e = blockIdx.x * 256 + threadIdx.x;
+  if (e >= total) return;
+  const int t = e % per, co = (e / per) % Cout, r = e / (per * Cout);
+  rep[e] = dwavg[((size_t)co * ng + r % ng) * per + t] * (1.0f / (float)(R / ng));
+}
+__global__ __launch_bounds__(256) void k_fill_u8(uint8_t* __restrict__ p, size_t n, uint8_t v) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) p[i] = v;
+}
+
 // Eq. 13 + 15 (with Eq. 12 folded in when FUSED: only the winning orientation of
 // each pooled element contributes, so the loop runs over pooled channels and the
 // weight is looked up by the stored orientation index).
@@ -324,6 +373,33 @@ void launch_maxpool_fwd(const rotconv_plan* p, const float* y, float* ypool, uin
   const Geom g = make_geom(p);
   dim3 grid((g.Ho * g.Wo + 255) / 256, g.Cout * g.ng, g.N);
   hipLaunchKernelGGL(k_maxpool_fwd<float>, grid, dim3(256), 0, st, y, ypool, idx, g);
+}
+
+void launch_avgpool_fwd(const rotconv_plan* p, const float* y, float* ypool, hipStream_t st) {
+  const Geom g = make_geom(p);
+  dim3 grid((g.Ho * g.Wo + 255) / 256, g.Cout * g.ng, g.N);
+  hipLaunchKernelGGL(k_avgpool_fwd, grid, dim3(256), 0, st, y, ypool, g);
+}
+void launch_avgpool_bwd(const rotconv_plan* p, const float* gpool, float* dy, hipStream_t st) {
+  const Geom g = make_geom(p);
+  dim3 grid((g.Ho * g.Wo + 255) / 256, g.Cout * g.R, g.N);
+  hipLaunchKernelGGL(k_avgpool_bwd, grid, dim3(256), 0, st, gpool, dy, g);
+}
+void launch_avg_bank(const rotconv_plan* p, const float* wexp, float* wavg, hipStream_t st) {
+  const int per = p->d.Cin * p->kk, total = p->d.Cout * p->ng * per;
+  hipLaunchKernelGGL(k_avg_bank, dim3((total + 255) / 256), dim3(256), 0, st, wexp, wavg, p->d.R, p->ng, p->d.Cout, per);
+}
+void launch_avg_bank_bwd(const rotconv_plan* p, const float* dwavg, float* rep, float* dw, hipStream_t st) {
+  const int per = p->d.Cin * p->kk, total = p->d.R * p->d.Cout * per;
+  hipLaunchKernelGGL(k_avg_bank_bwd, dim3((total + 255) / 256), dim3(256), 0, st, dwavg, rep, p->d.R, p->ng, p->d.Cout,
+                     per);
+  const int slices = p->d.Cout * p->d.Cin, tot = p->B * slices * p->kk;
+  hipLaunchKernelGGL(k_reduce_bank, dim3((tot + 255) / 256), dim3(256), 0, st, rep, dw, p->dev.tr_ptr, p->dev.tr_col,
+                     p->dev.tr_coef, p->B, slices, p->kk, 1, (size_t)p->d.R * slices * p->kk);
+}
+void launch_fill_u8(uint8_t* p, size_t n, uint8_t v, hipStream_t st) {
+  const unsigned blocks = (unsigned)std::max<size_t>(1, std::min<size_t>((n + 255) / 256, 4096));
+  hipLaunchKernelGGL(k_fill_u8, dim3(blocks), dim3(256), 0, st, p, n, v);
 }
 
 void launch_maxpool_fwd_bf16(const rotconv_plan* p, const uint16_t* y, uint16_t* ypool, uint8_t* idx, hipStream_t st) {

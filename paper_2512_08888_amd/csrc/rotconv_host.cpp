@@ -102,6 +102,8 @@ int validate_and_build(const rotconv_desc* desc, rotconv_plan** out) {
   if (d.mode != ROTCONV_EXACT90 && d.mode != ROTCONV_STEERABLE && d.mode != ROTCONV_BILINEAR)
     return ROTCONV_ERR_UNSUPPORTED;
   if (d.dtype != ROTCONV_F32 && d.dtype != ROTCONV_BF16) return ROTCONV_ERR_UNSUPPORTED;
+  if (d.pool_op != ROTCONV_POOL_MAX && d.pool_op != ROTCONV_POOL_AVG) return ROTCONV_ERR_UNSUPPORTED;
+  if (d.pool_op == ROTCONV_POOL_AVG && d.dtype != ROTCONV_F32) return ROTCONV_ERR_UNSUPPORTED;
   if (d.k > 15) return ROTCONV_ERR_UNSUPPORTED;
   const int Ho = (d.H + 2 * d.pad - d.k) / d.stride + 1, Wo = (d.W + 2 * d.pad - d.k) / d.stride + 1;
   const int kk = d.k * d.k, B = d.mode == ROTCONV_STEERABLE ? 2 : 1;

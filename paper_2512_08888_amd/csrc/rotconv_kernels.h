@@ -31,6 +31,14 @@ void launch_bwd_weight_generic(const rotconv_plan* p, const float* x, const floa
                                const uint8_t* idx, float* partial, float* dw, hipStream_t st);
 void launch_maxpool_fwd(const rotconv_plan* p, const float* y, float* ypool, uint8_t* idx, hipStream_t st);
 void launch_maxpool_bwd(const rotconv_plan* p, const float* gpool, const uint8_t* idx, float* dy, hipStream_t st);
+// average pooling (Eq. 9 / Eq. 11) and the pieces of its fused path
+void launch_avgpool_fwd(const rotconv_plan* p, const float* y, float* ypool, hipStream_t st);
+void launch_avgpool_bwd(const rotconv_plan* p, const float* gpool, float* dy, hipStream_t st);
+// wavg[(co*ng+g)][ci][t] = (1/G) sum_{r mod ng == g} wexp[r][co][ci][t]
+void launch_avg_bank(const rotconv_plan* p, const float* wexp, float* wavg, hipStream_t st);
+// its adjoint: rep[r][co][ci][t] = dwavg[(co*ng + r mod ng)][ci][t] / G, then the transposed expansion into dw
+void launch_avg_bank_bwd(const rotconv_plan* p, const float* dwavg, float* rep, float* dw, hipStream_t st);
+void launch_fill_u8(uint8_t* p, size_t n, uint8_t v, hipStream_t st);
 void launch_maxpool_fwd_bf16(const rotconv_plan* p, const uint16_t* y, uint16_t* ypool, uint8_t* idx, hipStream_t st);
 void launch_maxpool_bwd_bf16(const rotconv_plan* p, const uint16_t* gpool, const uint8_t* idx, uint16_t* dy,
                              hipStream_t st);

@@ -1,0 +1,69 @@
+"""GPU parity of average orientation pooling (plans with pool_op = average; paper Eq. 9 and Eq. 11) against the
+fp64 oracle, through the C ABI: the fused calls (one ordinary convolution with the group-averaged bank and its
+adjoints) and the unfused pooling pair.  fp32 bars of the max-pooling tests; there is no arg-max."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import rotconv_oracle as orc
+from paper_2512_08888_amd import binding as rc
+from paper_2512_08888_amd import synth
+from parity_util import assert_close, dev
+
+pytestmark = pytest.mark.gpu
+LC = synth.LayerConfig
+
+CASES = [
+    LC("a_r4", N=2, Cin=3, H=9, W=7, Cout=5, R=4, seed=81),                                        # generic kernels
+    LC("a_fast", N=2, Cin=20, H=12, W=32, Cout=18, R=4, seed=82),                                  # MFMA kernels
+    LC("a_r16", N=1, Cin=8, H=10, W=64, Cout=6, R=16, mode="bilinear", seed=83),
+    LC("a_ste_g4", N=1, Cin=4, H=8, W=16, Cout=4, R=8, mode="steerable", pool_group=4, seed=84),
+    LC("a_g2_s2", N=1, Cin=3, H=11, W=10, Cout=4, k=5, pad=2, stride=2, R=4, pool_group=2, seed=85),
+    LC("a_c64", N=1, Cin=64, H=24, W=64, Cout=32, R=4, x_dist="absnormal", seed=86),
+]
+
+
+def nan(*shape):
+    return torch.full(shape, float("nan"), dtype=torch.float32, device="cuda")
+
+
+def host(t):
+    torch.cuda.synchronize()
+    return t.cpu().numpy().astype(np.float64)
+
+
+@pytest.mark.parametrize("cfg", CASES, ids=[c.name for c in CASES])
+def test_avg_fused_calls(cfg):
+    plan = rc.Plan.from_config(cfg, pool_op="avg")
+    print(f"[case] average pooling {cfg.name}", flush=True)
+    ang = None if cfg.angles_deg is None else list(cfg.angles_deg)
+    x, w, g = synth.make_x(cfg), synth.make_w(cfg), synth.make_g(cfg)
+    xd, wd, gd = dev(x), dev(w), dev(g)
+    P = (cfg.N, plan.Cpooled, plan.Ho, plan.Wo)
+    yp = nan(*P)
+    rc.rotconv_pool_fwd(plan, xd, wd, yp, None)
+    y_ref, yp_ref, _ = orc.layer_fwd_avg(x, w, cfg.R, ang, cfg.mode, cfg.stride, cfg.pad, cfg.G)
+    assert_close(host(yp), yp_ref, f"{cfg.name} ypool (mean)")
+    dx_ref, dw_ref = orc.layer_bwd_avg(x, w, g, cfg.R, ang, cfg.mode, cfg.stride, cfg.pad, cfg.G)
+    dx = nan(*x.shape)
+    rc.rotconv_pool_bwd_data(plan, gd, None, wd, dx)
+    assert_close(host(dx), dx_ref, f"{cfg.name} dx")
+    dw = nan(*w.shape)
+    rc.rotconv_pool_bwd_weight(plan, xd, gd, None, dw)
+    assert_close(host(dw), dw_ref, f"{cfg.name} dw")
+    # the unfused pooling pair of the same plan
+    U = (cfg.N, plan.Cunpooled, plan.Ho, plan.Wo)
+    y = nan(*U)
+    rc.rotconv_fwd(plan, xd, wd, y)
+    yp2 = nan(*P)
+    rc.orient_maxpool_fwd(plan, y, yp2, None)
+    assert_close(host(yp2), orc.orient_avgpool_fwd(host(y).reshape(y_ref.shape), cfg.G), f"{cfg.name} unfused mean")
+    dy = nan(*U)
+    rc.orient_maxpool_bwd(plan, gd, None, dy)
+    assert_close(host(dy).reshape(y_ref.shape), orc.orient_avgpool_bwd(g, cfg.R, cfg.G), f"{cfg.name} unfused Eq. 11")
+
+
+def test_avg_plan_rejects_bf16():
+    with pytest.raises(rc.RotconvError) as e:
+        rc.Plan(1, 4, 8, 8, 4, dtype=rc.BF16, pool_op="avg")
+    assert e.value.status == rc.ERR_UNSUPPORTED

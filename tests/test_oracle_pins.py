@@ -393,3 +393,47 @@ def test_sampled_backward_helpers_match_full():
     got = orc.rotconv_pool_bwd_weight_at(x, g, idx, pairs, R, 3, G, 1, 1)
     for t, (co, ci) in enumerate(pairs):
         np.testing.assert_allclose(got[t], dwr[:, co, ci], rtol=1e-13, atol=1e-13)
+
+
+# ---------------------------------------------------------------- average orientation pooling (Eq. 9, Eq. 11)
+
+@pytest.mark.parametrize("R,mode,G,stride,pad,k", [
+    (4, "exact90", 4, 1, 1, 3), (8, "bilinear", 4, 1, 1, 3), (16, "steerable", 16, 1, 1, 3), (4, "exact90", 2, 2, 2, 5),
+])
+def test_average_pooling_against_numpy_torch_and_linearity(R, mode, G, stride, pad, k):
+    B = 2 if mode == "steerable" else 1
+    x = rnd(2, 3, 7, 6)
+    w = rnd(B, 2, 3, k, k)
+    y, yp, w_rot = orc.layer_fwd_avg(x, w, R, None, mode, stride, pad, G)
+    N, Cout, _, Ho, Wo = y.shape
+    ng = R // G
+    # the library definition: numpy mean over the members of each group (r = j*ng + g)
+    np.testing.assert_allclose(yp, y.reshape(N, Cout, G, ng, Ho, Wo).mean(axis=2).reshape(yp.shape), rtol=1e-13, atol=1e-13)
+    # linearity (Sec. IV-B: every product is divided by the number of rotations before it is added): the mean over
+    # a group is ONE plain convolution with the group-averaged bank
+    wavg = w_rot.reshape(G, ng, Cout, 3, k, k).mean(axis=0).transpose(1, 0, 2, 3, 4).reshape(Cout * ng, 3, k, k)
+    ref = F.conv2d(torch.from_numpy(x), torch.from_numpy(np.ascontiguousarray(wavg)), stride=stride, padding=pad).numpy()
+    np.testing.assert_allclose(yp, ref, rtol=1e-11, atol=1e-11)
+    # gradients: torch autograd through conv2d -> view -> mean
+    g = rnd(*yp.shape)
+    dx, dw = orc.layer_bwd_avg(x, w, g, R, None, mode, stride, pad, G)
+    dy = orc.orient_avgpool_bwd(g, R, G)
+    np.testing.assert_allclose(dy.reshape(N, Cout, G, ng, Ho, Wo).sum(axis=2).reshape(g.shape), g, rtol=1e-13, atol=1e-13)
+    xt = torch.from_numpy(x).requires_grad_(True)
+    wt = torch.from_numpy(w_rot).requires_grad_(True)
+    bank = wt.permute(1, 0, 2, 3, 4).reshape(Cout * R, 3, k, k)
+    out = F.conv2d(xt, bank, stride=stride, padding=pad).view(N, Cout, G, ng, Ho, Wo).mean(dim=2).reshape(yp.shape)
+    out.backward(torch.from_numpy(g))
+    np.testing.assert_allclose(dx, xt.grad.numpy(), rtol=1e-10, atol=1e-10)
+    np.testing.assert_allclose(orc.rotconv_bwd_weight(x, dy, k, stride, pad), wt.grad.numpy(), rtol=1e-10, atol=1e-10)
+    np.testing.assert_allclose(dw, orc.reduce_bank_grad(wt.grad.numpy(), None, mode), rtol=1e-10, atol=1e-10)
+
+
+def test_average_equals_max_for_a_fourfold_symmetric_filter():
+    """W = rot90(W): all orientations respond alike, so mean and max coincide, and so do the gradients' sums."""
+    a = rnd(1, 2, 3, 3, 3)
+    w = sum(np.rot90(a, s, axes=(-2, -1)) for s in range(4))
+    x = rnd(1, 3, 6, 6)
+    _, yp_max, _, _ = orc.layer_fwd(x, w, 4, None, "exact90", 1, 1, 4)
+    _, yp_avg, _ = orc.layer_fwd_avg(x, w, 4, None, "exact90", 1, 1, 4)
+    np.testing.assert_allclose(yp_avg, yp_max, rtol=1e-12, atol=1e-12)
