@@ -156,6 +156,19 @@ int rotconv_pool_bwd_data(const rotconv_plan* plan, const void* gpool, const uin
 int rotconv_pool_bwd_weight(const rotconv_plan* plan, const void* x, const void* gpool, const uint8_t* idx, float* dw,
                             void* ws, size_t ws_bytes, void* stream);
 
+/* ---- regularisers of the steerable pair (Sec. III-D, Eq. 18-20) ------------------------------------
+ * w DEVICE fp32 [2][Cout][per]: the two base banks f_x then f_y of a STEERABLE layer, per = Cin*k*k; "filter b"
+ * of Eq. 19 / Eq. 20 is output filter b flattened over (Cin, k, k) (B = Cout).
+ *   L_mag  = 1/B sum_b (||wx_b|| - ||wy_b||)^2                               (Eq. 19)
+ *   L_orth = 1/B sum_b ( <wx_b, wy_b> / (||wx_b|| ||wy_b|| + eps) )^2       (Eq. 20)
+ * losses DEVICE fp32 [2] receives (L_mag, L_orth).  dw DEVICE fp32 [2][Cout][per] (may be NULL) receives
+ * lambda_mag dL_mag/dw + lambda_orth dL_orth/dw, the regularisers' share of Eq. 18's gradient; accumulate != 0
+ * adds it to what dw holds (the layer's dw from rotconv_pool_bwd_weight) instead of overwriting.  A filter of
+ * zero norm gets a zero gradient for the terms that divide by that norm.  ws: Cout * 2 floats.  Fixed
+ * reduction order: bitwise reproducible. */
+int rotconv_steerable_reg(const float* w, int32_t Cout, int32_t per, float lambda_mag, float lambda_orth, float eps,
+                          float* losses, float* dw, int32_t accumulate, void* ws, size_t ws_bytes, void* stream);
+
 /* Static, never NULL. */
 const char* rotconv_status_string(int status);
 /* Name of the kernel family the last successful call of the given kind on this

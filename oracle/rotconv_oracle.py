@@ -278,3 +278,30 @@ def layer_bwd_avg(x, w_base, gpool, R, angles_deg=None, mode="exact90", stride=1
     dx = rotconv_bwd_data(dy, w_rot, x.shape[2], x.shape[3], stride, pad)
     dw = reduce_bank_grad(rotconv_bwd_weight(x, dy, k, stride, pad), angles_deg, mode)
     return dx, dw
+
+
+def steerable_reg(w, eps: float = 1e-8):
+    """Regularisers of the steerable pair (Sec. III-D, Eq. 19 and Eq. 20) and their gradients.
+    w [2,Cout,Cin,k,k] (f_x then f_y); filter b = output filter b flattened over (Cin,k,k), B = Cout.
+    Returns (L_mag, L_orth, dL_mag/dw, dL_orth/dw).  A zero-norm filter gets a zero gradient for the terms that
+    divide by that norm."""
+    w = _f64(w)
+    B = w.shape[1]
+    wx, wy = w[0].reshape(B, -1), w[1].reshape(B, -1)
+    l_mag = l_orth = 0.0
+    g_mag, g_orth = np.zeros((2,) + wx.shape), np.zeros((2,) + wx.shape)
+    for b in range(B):
+        nx, ny = np.sqrt(np.sum(wx[b] ** 2)), np.sqrt(np.sum(wy[b] ** 2))
+        dot = float(np.sum(wx[b] * wy[b]))
+        diff = nx - ny
+        l_mag += diff ** 2 / B
+        ux = wx[b] / nx if nx > 0 else 0.0 * wx[b]
+        uy = wy[b] / ny if ny > 0 else 0.0 * wy[b]
+        g_mag[0, b] = 2.0 * diff * ux / B
+        g_mag[1, b] = -2.0 * diff * uy / B
+        den = nx * ny + eps
+        c = dot / den
+        l_orth += c ** 2 / B
+        g_orth[0, b] = 2.0 * c * (wy[b] / den - dot * ny * ux / den ** 2) / B
+        g_orth[1, b] = 2.0 * c * (wx[b] / den - dot * nx * uy / den ** 2) / B
+    return l_mag, l_orth, g_mag.reshape(w.shape), g_orth.reshape(w.shape)

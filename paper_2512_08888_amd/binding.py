@@ -24,7 +24,7 @@ EXPORTS = [
     "rotconv_plan_orientations", "rotconv_plan_expansion",
     "rotconv_fwd", "rotconv_bwd_data", "rotconv_bwd_weight", "orient_maxpool_fwd", "orient_maxpool_bwd",
     "rotconv_pool_fwd", "rotconv_pool_bwd_data", "rotconv_pool_bwd_weight",
-    "rotconv_status_string", "rotconv_plan_kernel_name",
+    "rotconv_status_string", "rotconv_plan_kernel_name", "rotconv_steerable_reg",
 ]
 
 # include/unetglue.h
@@ -87,6 +87,8 @@ def lib():
         L.rotconv_status_string.restype = ctypes.c_char_p
         L.rotconv_plan_kernel_name.argtypes = [vp, ctypes.c_int]
         L.rotconv_plan_kernel_name.restype = ctypes.c_char_p
+        L.rotconv_steerable_reg.argtypes = [vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_float, ctypes.c_float,
+                                            ctypes.c_float, vp, vp, ctypes.c_int32, vp, sz, vp]
         ci = ctypes.c_int
         L.glue_relu_fwd.argtypes = [vp, vp, sz, vp]
         L.glue_relu_bwd.argtypes = [vp, vp, vp, sz, vp]
@@ -254,6 +256,19 @@ def rotconv_pool_bwd_weight(plan: Plan, x, gpool, idx, dw, ws=None):
     p, n = _ws_args(plan, ws)
     _check(lib().rotconv_pool_bwd_weight(plan.handle, _ptr(x), _ptr(gpool), _ptr(idx), _ptr(dw), p, n, _stream()),
            "rotconv_pool_bwd_weight")
+
+
+def rotconv_steerable_reg(w, lambda_mag, lambda_orth, eps, losses, dw=None, accumulate=False, ws=None):
+    """w [2,Cout,Cin,k,k] fp32; losses [2] fp32; dw like w or None; ws: at least Cout*2 floats (allocated if None)."""
+    import torch
+
+    Cout = w.shape[1]
+    per = w.numel() // (2 * Cout)
+    if ws is None:
+        ws = torch.empty(max(256, Cout * 8), dtype=torch.uint8, device=w.device)
+    _check(lib().rotconv_steerable_reg(_ptr(w), Cout, per, float(lambda_mag), float(lambda_orth), float(eps),
+                                       _ptr(losses), _ptr(dw), int(bool(accumulate)), _ptr(ws),
+                                       ws.numel() * ws.element_size(), _stream()), "rotconv_steerable_reg")
 
 
 # ---- network glue (include/unetglue.h): same names, argument marshalling only -------------------

@@ -437,3 +437,49 @@ def test_average_equals_max_for_a_fourfold_symmetric_filter():
     _, yp_max, _, _ = orc.layer_fwd(x, w, 4, None, "exact90", 1, 1, 4)
     _, yp_avg, _ = orc.layer_fwd_avg(x, w, 4, None, "exact90", 1, 1, 4)
     np.testing.assert_allclose(yp_avg, yp_max, rtol=1e-12, atol=1e-12)
+
+
+# ---------------------------------------------------------------- steerable regularisers (Eq. 19, Eq. 20)
+
+def test_steerable_regularisers_closed_forms():
+    v = rnd(5, 3, 3)
+    u = rnd(5, 3, 3)
+    u -= (u * v).sum() / (v * v).sum() * v                      # u orthogonal to v
+    # filter 0: parallel bases of norms 2|v| and 3|v|; filter 1: orthogonal bases of equal norm
+    un = u * np.sqrt((v * v).sum() / (u * u).sum())
+    w = np.stack([np.stack([2 * v, v]), np.stack([3 * v, un])])  # [2 (x,y), B = 2, 5, 3, 3]
+    nv = np.sqrt((v * v).sum())
+    l_mag, l_orth, _, _ = orc.steerable_reg(w, eps=0.0)
+    assert np.isclose(l_mag, 0.5 * (nv ** 2 + 0.0), rtol=1e-12)  # (2|v| - 3|v|)^2 / 2 + 0
+    assert np.isclose(l_orth, 0.5 * (1.0 + 0.0), rtol=1e-12)     # cos^2 = 1 for the parallel pair, 0 for the other
+    # homogeneity: L_mag is of degree 2, L_orth (eps = 0) of degree 0 in w
+    w2 = rnd(2, 4, 3, 3, 3)
+    a = orc.steerable_reg(w2, 0.0)
+    b = orc.steerable_reg(3.0 * w2, 0.0)
+    assert np.isclose(b[0], 9.0 * a[0], rtol=1e-12) and np.isclose(b[1], a[1], rtol=1e-12)
+    # Euler: <w, dL_mag> = 2 L_mag, <w, dL_orth> = 0
+    assert np.isclose((w2 * a[2]).sum(), 2.0 * a[0], rtol=1e-11) and abs((w2 * a[3]).sum()) < 1e-12
+
+
+def test_steerable_regulariser_gradients_autograd_and_finite_differences():
+    w = rnd(2, 3, 2, 3, 3)
+    eps = 1e-3
+    l_mag, l_orth, g_mag, g_orth = orc.steerable_reg(w, eps)
+    wt = torch.from_numpy(w).requires_grad_(True)
+    wx, wy = wt[0].reshape(3, -1), wt[1].reshape(3, -1)
+    nx, ny = torch.linalg.vector_norm(wx, dim=1), torch.linalg.vector_norm(wy, dim=1)
+    tm = ((nx - ny) ** 2).mean()
+    to = (((wx * wy).sum(dim=1) / (nx * ny + eps)) ** 2).mean()
+    assert np.isclose(l_mag, tm.item(), rtol=1e-12) and np.isclose(l_orth, to.item(), rtol=1e-12)
+    gm, = torch.autograd.grad(tm, wt, retain_graph=True)
+    go, = torch.autograd.grad(to, wt)
+    np.testing.assert_allclose(g_mag, gm.numpy(), rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(g_orth, go.numpy(), rtol=1e-10, atol=1e-12)
+    h = 1e-6
+    for _ in range(6):
+        i = tuple(RNG.integers(0, s) for s in w.shape)
+        wp, wm = w.copy(), w.copy()
+        wp[i] += h; wm[i] -= h
+        fp, fm = orc.steerable_reg(wp, eps), orc.steerable_reg(wm, eps)
+        assert np.isclose((fp[0] - fm[0]) / (2 * h), g_mag[i], rtol=1e-5, atol=1e-8)
+        assert np.isclose((fp[1] - fm[1]) / (2 * h), g_orth[i], rtol=1e-5, atol=1e-8)
