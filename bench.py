@@ -140,6 +140,49 @@ def cpu_baseline_unet(name):
                       f"{dt:.2f} s", "seconds": dt}
 
 
+def main_sweep(args):
+    """Single-orientation forward (R = 1: the rotation convolution reduces to a standard convolution) over the
+    shapes of the paper's appendix: square maps of 4 .. 256 pixels, 256 / 512 / 1024 input channels, 4 .. 256
+    filters, batch 1, 3x3, pad 1, fp32.  One JSON line: ms per call and dense TFLOP/s of every point; `value` is
+    the geometric mean of the ms over all points (a small-map / launch-latency characterisation, not the
+    headline metric)."""
+    import math
+    import torch
+    from paper_2512_08888_amd import binding as rc
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    pts = []
+    for side in (4, 8, 16, 32, 64, 128, 256):
+        for cin in (256, 512, 1024):
+            for cout in (4, 8, 16, 32, 64, 128, 256):
+                plan = rc.Plan(1, cin, side, side, cout, k=3, R=1, mode="exact90", stride=1, pad=1)
+                x = torch.rand((1, cin, side, side), device="cuda")
+                w = torch.randn((1, cout, cin, 3, 3), device="cuda") * (2.0 / (cin * 9)) ** 0.5
+                y = torch.empty((1, cout, side, side), device="cuda")
+                plan.workspace()
+                for _ in range(args.warmup):
+                    rc.rotconv_fwd(plan, x, w, y)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(args.steps):
+                    rc.rotconv_fwd(plan, x, w, y)
+                e1.record()
+                torch.cuda.synchronize()
+                ms = e0.elapsed_time(e1) / args.steps
+                fl = 2.0 * side * side * cin * cout * 9
+                pts.append({"map": side, "Cin": cin, "Cout": cout, "ms": round(ms, 5), "tflops": round(fl / ms / 1e9, 3),
+                            "kernel": plan.kernel_name(0)})
+                del plan, x, w, y
+    gm = math.exp(sum(math.log(p["ms"]) for p in pts) / len(pts))
+    print(json.dumps({
+        "metric": "single_orientation_fwd_sweep_geomean_ms", "value": gm, "unit": "ms", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": gm, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "sweep: rotconv_fwd with R=1 (standard convolution), N=1, 3x3 pad 1, maps 4..256, "
+                               "Cin 256/512/1024, Cout 4..256 (the paper's appendix shapes)", "points": pts}}), flush=True)
+
+
 def main_unet(args):
     import torch
 
@@ -165,7 +208,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4", "C5", "P4", "P8", "P16"])
+    ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4", "C5", "P4", "P8", "P16", "sweep"])
     ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"],
                     help="storage type of activations and weights (accumulation is fp32 either way)")
     ap.add_argument("--pool-op", default="max", choices=["max", "avg"],
@@ -184,6 +227,8 @@ def main():
 
     if args.workload in ("C4", "C5", "P4", "P8", "P16"):
         return main_unet(args)
+    if args.workload == "sweep":
+        return main_sweep(args)
 
     import torch
     from paper_2512_08888_amd import binding as rc

@@ -421,10 +421,12 @@ int geoms(const rotconv_plan* p, P4BwdBfGeom* out, int max_out) {
     for (int k = 0; k < 4; ++k) { g.seg_xorg[k] = fg[i].seg_xorg[k]; g.seg_lo[k] = fg[i].seg_lo[k]; g.seg_hi[k] = fg[i].seg_hi[k]; }
     const int nwy = 8 / g.nwx;
     long best_cost = -1;
+    // bands of at least 8 rows: parallelism for small maps comes from the K split below, which costs no halo rows
     for (int ty : {8, 16, 32, 64}) {
       const int nbg = (d.H + nwy * ty - 1) / (nwy * ty);
       const long units = (long)d.N * g.CIB * nbg * g.nseg;
-      const long cost = ((units + 255) / 256) * (ty + 2);
+      const int bands = nbg > 1 ? nwy : std::min(nwy, (d.H + ty - 1) / ty);
+      const long cost = ((units + 255) / 256) * (ty + 2) * std::max(4, g.nwx * bands);
       if (best_cost < 0 || cost <= best_cost) { best_cost = cost; g.TY = ty; g.nbg = nbg; g.units = (int)units; }
     }
     // Split of the K-steps over workgroups: enough workgroups to fill the chip twice, each share small enough

@@ -29,6 +29,8 @@
 // both neighbours it holds.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+
 #include "rotconv_bf16.h"
 #include "rotconv_kernels.h"
 #include "rotconv_p4.h"
@@ -423,7 +425,8 @@ void launch_t(const P4Geom& g, bool fastw, bool stream, const float* x, const fl
               float* ov, uint8_t* oi, hipStream_t st) {
   const bool unp = g.out_mode == kOutUnpooled;
   if (unp) {
-    if (fastw) launch_i<NWX, NWY, true, true, false>(g, x, wt, rot_of, ov, oi, st);
+    if (stream) launch_i<NWX, NWY, true, false, true>(g, x, wt, rot_of, ov, oi, st);   // deep inputs: streamed block
+    else if (fastw) launch_i<NWX, NWY, true, true, false>(g, x, wt, rot_of, ov, oi, st);
     else launch_i<NWX, NWY, true, false, false>(g, x, wt, rot_of, ov, oi, st);
   } else if (stream) {
     if (fastw) launch_i<NWX, NWY, false, true, true>(g, x, wt, rot_of, ov, oi, st);
@@ -498,10 +501,14 @@ int p4_fwd_geoms(const rotconv_plan* p, int out_mode, P4Geom* out, int max_out) 
     P4Geom& g = out[i];
     const int nwy = 8 / g.nwx;
     long best_cost = -1;
-    for (int ty : {8, 16, 32, 64}) {
+    // Rows per band: short bands cost halo rows (a band of ty rows computes ty + 2 rows of products) but give
+    // more workgroups when the problem is small.  Cost of a choice = rounds of workgroups over the 256 CUs x row
+    // steps per wave x how many waves share a SIMD (a workgroup whose bands reach beyond the image leaves waves idle).
+    for (int ty : {1, 2, 4, 8, 16, 32, 64}) {
       const int nbg = (d.H + nwy * ty - 1) / (nwy * ty);
       const long units = (long)d.N * g.Q * g.CB * nbg * g.nseg;
-      const long cost = ((units + 255) / 256) * (ty + 2);
+      const int bands = nbg > 1 ? nwy : std::min(nwy, (d.H + ty - 1) / ty);
+      const long cost = ((units + 255) / 256) * (ty + 2) * std::max(4, g.nwx * bands);
       if (best_cost < 0 || cost <= best_cost) { best_cost = cost; g.TY = ty; g.nbg = nbg; g.units = (int)units; }
     }
   }

@@ -457,7 +457,8 @@ void launch_t(const P4Geom& g, bool fastw, bool stream, bool cpad, const uint16_
   const bool unp = g.out_mode == kOutUnpooled;
   // the specialised instances: pooled output, whole lanes inside the row; everything else takes the
   // general instance (masks, clamped channels)
-  if (unp) launch_i<NWX, NWY, ND, true, false, false, true>(g, x, wt, rot_of, ov, oi, st);
+  if (unp && stream) launch_i<NWX, NWY, ND, true, false, true, true>(g, x, wt, rot_of, ov, oi, st);
+  else if (unp) launch_i<NWX, NWY, ND, true, false, false, true>(g, x, wt, rot_of, ov, oi, st);
   else if (stream && fastw) launch_i<NWX, NWY, ND, false, true, true, false>(g, x, wt, rot_of, ov, oi, st);
   else if (stream) launch_i<NWX, NWY, ND, false, false, true, false>(g, x, wt, rot_of, ov, oi, st);
   else if (fastw && !cpad) launch_i<NWX, NWY, ND, false, true, false, false>(g, x, wt, rot_of, ov, oi, st);

@@ -275,3 +275,25 @@ def test_config2_reduced_exact():
     say(f"[case] {cfg.name}")
     pu.run_fused_parity(cfg)
     pu.run_fused_parity(cfg, dyadic=True, label="C2r dyadic")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_unfused_forward_deep_input(dtype):
+    """rotconv_fwd (every orientation written) on an input too deep for an LDS-resident filter block."""
+    cfg = LC("u_deep", N=1, Cin=512, H=6, W=32, Cout=8, R=4, x_dist="absnormal", seed=43)
+    say(f"[case] unfused forward, deep input, {dtype}")
+    x, w = synth.make_x(cfg), synth.make_w(cfg)
+    if dtype == "bf16":
+        xd, wd = pu.dev(x, torch.bfloat16), pu.dev(w, torch.bfloat16)
+        x, w = xd.to(torch.float64).cpu().numpy(), wd.to(torch.float64).cpu().numpy()
+        plan = rc.Plan.from_config(cfg, dtype=rc.BF16)
+        y = torch.full((cfg.N, plan.Cunpooled, plan.Ho, plan.Wo), float("nan"), dtype=torch.bfloat16, device="cuda")
+    else:
+        xd, wd = pu.dev(x), pu.dev(w)
+        plan = rc.Plan.from_config(cfg)
+        y = torch.full((cfg.N, plan.Cunpooled, plan.Ho, plan.Wo), float("nan"), device="cuda")
+    rc.rotconv_fwd(plan, xd, wd, y)
+    torch.cuda.synchronize()
+    ref = orc.rotconv_fwd(x, orc.expand_bank(w, cfg.R, None, cfg.mode), cfg.stride, cfg.pad)
+    pu.assert_close(y.to(torch.float64).cpu().numpy().reshape(ref.shape), ref, f"deep unfused y {dtype}",
+                    rtol=1e-2 if dtype == "bf16" else pu.RTOL)
