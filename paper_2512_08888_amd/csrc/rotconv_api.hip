@@ -111,7 +111,9 @@ int rotconv_plan_create(const rotconv_desc* desc, rotconv_plan** out) {
   p->fast[0] = p4_fwd_supported(p) ? 1 : 0;
   if (p->fast[0]) p->ws_bytes = std::max(p->ws_bytes, fwd_fast_ws_bytes(p));
   p->fast[1] = p4_bwd_data_supported(p) ? 1 : 0;
-  if (p->fast[1]) p->ws_bytes = std::max(p->ws_bytes, p4_bwd_data_pack_floats(p) * sizeof(float));
+  if (p->fast[1])
+    p->ws_bytes = std::max(p->ws_bytes, align256(p4_bwd_data_pack_floats(p) * sizeof(float)) +
+                                            p4_bwd_data_part_floats(p) * sizeof(float));
   p->fast[2] = p4_bwd_weight_supported(p) ? 1 : 0;
   if (p->fast[2]) p->ws_bytes = std::max(p->ws_bytes, p4_bwd_weight_ws_floats(p) * sizeof(float));
   if (p->d.dtype == ROTCONV_BF16) {     // scratch of the kernels that take bf16 tensors directly
@@ -327,7 +329,8 @@ static int f32_rotconv_pool_bwd_data(const rotconv_plan* plan, const void* gpool
   if (p->fast[1] && aligned(gpool, 8) && aligned(idx, 2) && aligned(dx, 16) && aligned(ws, 16)) {
     float* wd = static_cast<float*>(ws);
     launch_p4_pack_bwd(p, static_cast<const float*>(w), wd, st);
-    launch_p4_bwd_data(p, static_cast<const float*>(gpool), idx, wd, static_cast<float*>(dx), st);
+    float* part = reinterpret_cast<float*>(static_cast<char*>(ws) + align256(p4_bwd_data_pack_floats(p) * sizeof(float)));
+    launch_p4_bwd_data(p, static_cast<const float*>(gpool), idx, wd, static_cast<float*>(dx), part, st);
     return finish();
   }
   float* wexp = static_cast<float*>(ws);

@@ -50,14 +50,18 @@ struct P4BwdGeom {
   int px;      // pixels per lane (2 or 4)
   int nstrip;  // strips of 16 * px pixels per row
   int nrb;     // blocks of 8 rows
-  int units;
+  int qsplit;  // workgroups that share a unit's banks (each writes an fp32 partial dX); 1 = no split
+  int qper;    // banks per such workgroup
+  int units;   // workgroups with work (includes the bank split)
 };
 bool p4_bwd_data_supported(const rotconv_plan* p);
 P4BwdGeom p4_bwd_data_geom(const rotconv_plan* p);
 size_t p4_bwd_data_pack_floats(const rotconv_plan* p);
 void launch_p4_pack_bwd(const rotconv_plan* p, const float* w, float* wd, hipStream_t st);
+// scratch behind the packed bank: the fp32 partial dX of a bank split (0 floats without one)
+size_t p4_bwd_data_part_floats(const rotconv_plan* p);
 void launch_p4_bwd_data(const rotconv_plan* p, const float* gpool, const uint8_t* idx, const float* wd, float* dx,
-                        hipStream_t st);
+                        float* part, hipStream_t st);
 
 // input gradient on bfloat16 tensors (bf16 matrix cores): the forward kernel's row segments and bands with
 // the roles of filters and channels swapped

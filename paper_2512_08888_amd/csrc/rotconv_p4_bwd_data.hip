@@ -20,6 +20,8 @@
 // double-buffered, a quarter chunk per pipeline stage, one barrier per chunk.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+
 #include "rotconv_bf16.h"
 #include "rotconv_kernels.h"
 #include "rotconv_p4.h"
@@ -63,6 +65,10 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gp
   const int per_xcd = (g.units + 7) / 8;
   int v = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
   if (v >= g.units) return;
+  // Banks [q0, q1) of this workgroup: layers with few (row block, strip, channel group) units share their banks
+  // out over qsplit workgroups, each writing an fp32 partial dX that k_p4_sum_dx adds in order.
+  const int qs = v % g.qsplit; v /= g.qsplit;
+  const int q0 = qs * g.qper, q1 = min(g.Q, q0 + g.qper);
   const int cig = v % g.ncig; v /= g.ncig;
   const int strip = v % g.nstrip; v /= g.nstrip;
   const int rb = v % g.nrb;
@@ -76,7 +82,8 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gp
   const bool active = h < g.H;
   const int HW = g.H * g.W;
   const int nkq = g.CoutPad / 4;               // K-steps per bank
-  const int nk = g.Q * nkq;                    // K-steps in total
+  const int nk = (q1 - q0) * nkq;              // K-steps of this workgroup
+  const int cbase = q0 * (g.CoutPad / CHUNK);  // its first weight chunk
   const int nchunks = nk / 4;
 
   // ---- weight chunk streaming -----------------------------------------------------
@@ -91,7 +98,7 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gp
       const int e = tid + k * NT;
       if (e < Q4) {
         const int c4 = e % (CIG / 4), u = (e / (CIG / 4)) % 9, r = part * 4 + e / (9 * (CIG / 4));
-        wreg[k] = *reinterpret_cast<const f4*>(wd + ((size_t)(cc * CHUNK + r) * 9 + u) * g.CinPad + cig * CIG + c4 * 4);
+        wreg[k] = *reinterpret_cast<const f4*>(wd + ((size_t)((cbase + cc) * CHUNK + r) * 9 + u) * g.CinPad + cig * CIG + c4 * 4);
       }
     }
   };
@@ -142,10 +149,10 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gp
     return r0 % g.ng;
   };
   // load cursor: K-step (bank, first filter) that the next raw_load fetches; it stops on the last K-step
-  int ld_q = 0, ld_co = 0, ld_pg;
+  int ld_q = q0, ld_co = 0, ld_pg;
   {
     int r[4];
-    bank_rot(0, r);
+    bank_rot(q0, r);
     ld_pg = group_of(r);
   }
   auto raw_load = [&](Raw<PX>& r) {
@@ -173,7 +180,7 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gp
     }
     if (ld_co + 4 < g.CoutPad) {
       ld_co += 4;
-    } else if (ld_q + 1 < g.Q) {
+    } else if (ld_q + 1 < q1) {
       ++ld_q;
       ld_co = 0;
       int rr[4];
@@ -216,15 +223,15 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gp
   Raw<PX> rawA, rawB;
   float aA[9][PX], aB[9][PX];
   int rotb[4];                      // orientations of the bank of the K-step being built
-  int bd_q = 0, bd_co = 0;          // build cursor
-  bank_rot(0, rotb);
+  int bd_q = q0, bd_co = 0;         // build cursor
+  bank_rot(q0, rotb);
   auto stage = [&](int ks, const float* wl, const Raw<PX>& raw_use, Raw<PX>& raw_ld, const float (&a_cur)[9][PX],
                    float (&a_nxt)[9][PX]) {
     raw_load(raw_ld);
     // the K-step being built is the one after the current one
     if (bd_co + 4 < g.CoutPad) {
       bd_co += 4;
-    } else if (bd_q + 1 < g.Q) {
+    } else if (bd_q + 1 < q1) {
       ++bd_q;
       bd_co = 0;
       bank_rot(bd_q, rotb);
@@ -281,7 +288,7 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gp
     const int ci = cig * CIG + cb * 16 + lc;
     if (ci >= g.Cin) continue;
     const int px = x0 + 4 * PX * lg;
-    float* o = dx + ((size_t)n * g.Cin + ci) * HW + (size_t)h * g.W + px;
+    float* o = dx + (((size_t)qs * g.N + n) * g.Cin + ci) * HW + (size_t)h * g.W + px;   // qs > 0 only in the partial buffer
     float vals[4 * PX];
 #pragma unroll
     for (int j = 0; j < 4 * PX; ++j) vals[j] = acc[cb][j % PX][j / PX];
@@ -295,6 +302,22 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gp
       for (int j = 0; j < 4 * PX; ++j)
         if (px + j < g.W) o[j] = vals[j];
     }
+  }
+}
+
+// dx[e] = sum over the bank splits, ascending, of part[s][e] (four elements per thread, scalar tail).
+__global__ __launch_bounds__(256) void k_p4_sum_dx(const float* __restrict__ part, float* __restrict__ dx, size_t n_elem,
+                                                   int nparts) {
+  const size_t n4 = n_elem / 4;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (size_t)gridDim.x * 256) {
+    f4 a = reinterpret_cast<const f4*>(part)[i];
+    for (int k = 1; k < nparts; ++k) a += reinterpret_cast<const f4*>(part + (size_t)k * n_elem)[i];
+    reinterpret_cast<f4*>(dx)[i] = a;
+  }
+  for (size_t e = n4 * 4 + (size_t)blockIdx.x * 256 + threadIdx.x; e < n_elem; e += (size_t)gridDim.x * 256) {
+    float v = part[e];
+    for (int k = 1; k < nparts; ++k) v += part[(size_t)k * n_elem + e];
+    dx[e] = v;
   }
 }
 
@@ -344,7 +367,23 @@ P4BwdGeom p4_bwd_data_geom(const rotconv_plan* p) {
   g.px = ((d.W & 3) == 0 && d.W > 32 && d.N * g.ncig * g.nrb * ((d.W + 63) / 64) >= 256) ? 4 : 2;
   g.nstrip = (d.W + 16 * g.px - 1) / (16 * g.px);
   g.units = d.N * g.ncig * g.nstrip * g.nrb;
+  // Few units and several banks: share the banks out so that the chip is filled about twice (at most 256 MiB of
+  // partial sums).
+  g.qsplit = 1;
+  if (g.units < 256 && g.Q > 1) {
+    const double dx_bytes = 4.0 * d.N * d.Cin * d.H * d.W;
+    const int want = std::min({g.Q, (512 + g.units - 1) / g.units, std::max(1, (int)(268435456.0 / dx_bytes))});
+    g.qper = (g.Q + want - 1) / want;
+    g.qsplit = (g.Q + g.qper - 1) / g.qper;
+  }
+  if (g.qsplit == 1) g.qper = g.Q;
+  g.units *= g.qsplit;
   return g;
+}
+
+size_t p4_bwd_data_part_floats(const rotconv_plan* p) {
+  const P4BwdGeom g = p4_bwd_data_geom(p);
+  return g.qsplit > 1 ? (size_t)g.qsplit * p->d.N * p->d.Cin * p->d.H * p->d.W : 0;
 }
 
 size_t p4_bwd_data_pack_floats(const rotconv_plan* p) {
@@ -359,9 +398,10 @@ void launch_p4_pack_bwd(const rotconv_plan* p, const float* w, float* wd, hipStr
                      g.Q, g.CoutPad, g.CinPad, g.Cin, g.Cout, p->d.dtype == ROTCONV_BF16 ? 1 : 0);
 }
 
-void launch_p4_bwd_data(const rotconv_plan* p, const float* gpool, const uint8_t* idx, const float* wd, float* dx,
-                        hipStream_t st) {
+void launch_p4_bwd_data(const rotconv_plan* p, const float* gpool, const uint8_t* idx, const float* wd, float* dx_out,
+                        float* part, hipStream_t st) {
   const P4BwdGeom g = p4_bwd_data_geom(p);
+  float* dx = g.qsplit > 1 ? part : dx_out;
   const size_t lds = (size_t)2 * CHUNK * WROW * sizeof(float);
   const int grid = (g.units + 7) / 8 * 8;
   if (g.px == 4) {
@@ -372,6 +412,11 @@ void launch_p4_bwd_data(const rotconv_plan* p, const float* gpool, const uint8_t
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_p4_bwd_data<2>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     hipLaunchKernelGGL(k_p4_bwd_data<2>, dim3(grid), dim3(NT), lds, st, gpool, idx, wd, p->dev.rot_of, dx, g);
+  }
+  if (g.qsplit > 1) {
+    const size_t n_elem = (size_t)p->d.N * p->d.Cin * p->d.H * p->d.W;
+    const unsigned blocks = (unsigned)std::max<size_t>(1, std::min<size_t>((n_elem / 4 + 255) / 256, 1u << 16));
+    hipLaunchKernelGGL(k_p4_sum_dx, dim3(blocks), dim3(256), 0, st, part, dx_out, n_elem, g.qsplit);
   }
 }
 
