@@ -16,15 +16,23 @@ typedef float f4 __attribute__((ext_vector_type(4)));
 
 constexpr int BM = 128, BN = 128, BK = 16, PITCH = 144, NT = 256;
 
-// Address of element (r, p) of the virtual matrix T[(co,a,b)][(h,w)] = y[co][2h+a][2w+b] that a 2x2
-// stride-2 transposed convolution reads / writes (r = 4 co + 2 a + b, p = h W + w, y is [Cout][2H][2W]).
-__device__ __forceinline__ size_t shuffled(int r, int p, int H, int W) {
-  const int co = r >> 2, a = (r >> 1) & 1, b = r & 1, h = p / W, w = p - h * W;
-  return ((size_t)co * 2 * H + 2 * h + a) * (2 * W) + 2 * w + b;
+// The virtual matrix T[(co,a,b)][(h,w)] = y[co][2h+a][2w+b] that a 2x2 stride-2 transposed convolution reads /
+// writes (r = 4 co + 2 a + b, p = h W + w, y is [Cout][2H][2W]): address = row part (r) + pixel part (p).
+__device__ __forceinline__ size_t shuf_row(int r, int H, int W) {
+  const int co = r >> 2, a = (r >> 1) & 1, b = r & 1;
+  return ((size_t)co * 2 * H + a) * (2 * W) + b;
+}
+__device__ __forceinline__ size_t shuf_pix(int p, int W) {
+  const int h = p / W, w = p - h * W;
+  return (size_t)(2 * h) * (2 * W) + 2 * w;
 }
 
-// A element (m, k): transA ? A[k*lda + m] : A[m*lda + k];  B element (k, n): transB ? B[n*ldb + k] : B[k*ldb + n]
-template <bool TA, bool TB>
+// A element (m, k): transA ? A[k*lda + m] : A[m*lda + k];  B element (k, n): transB ? B[n*ldb + k] : B[k*ldb + n].
+// Every thread fetches eight A and eight B elements per 16-deep tile; the parts of their addresses that do not
+// depend on the tile (row / column, pixel-shuffle terms, bounds) are computed once, so a tile costs additions only.
+// BF: 0 = fp32 operands and result; 1 = bfloat16 A and B, fp32 result (weight gradients); 2 = all three bfloat16.
+// (compile-time, so that a tile's sixteen loads are issued back to back instead of one per branch)
+template <bool TA, bool TB, int BF>
 __global__ __launch_bounds__(NT) void k_gemm(const void* __restrict__ A, const void* __restrict__ B,
                                             void* __restrict__ C, GemmArgs p) {
   __shared__ float As[2][BK][PITCH];
@@ -36,31 +44,48 @@ __global__ __launch_bounds__(NT) void k_gemm(const void* __restrict__ A, const v
   const int kchunk = ((p.K + p.splitk - 1) / p.splitk + BK - 1) / BK * BK;
   const int kbeg = ks * kchunk, kend = min(p.K, kbeg + kchunk);
   const size_t Abase = (size_t)batch * p.strideA, Bbase = (size_t)batch * p.strideB, Cbase = (size_t)z * p.strideC;
-  // element access in the operand's storage type (wave-uniform choice)
-  auto ldA = [&](size_t off) {
-    return p.bf16A ? bf16_to_f32(static_cast<const uint16_t*>(A)[Abase + off]) : static_cast<const float*>(A)[Abase + off];
+  auto ldA = [&](size_t off) -> float {
+    if (BF) return bf16_to_f32(static_cast<const uint16_t*>(A)[Abase + off]);
+    return static_cast<const float*>(A)[Abase + off];
   };
-  auto ldB = [&](size_t off) {
-    return p.bf16B ? bf16_to_f32(static_cast<const uint16_t*>(B)[Bbase + off]) : static_cast<const float*>(B)[Bbase + off];
+  auto ldB = [&](size_t off) -> float {
+    if (BF) return bf16_to_f32(static_cast<const uint16_t*>(B)[Bbase + off]);
+    return static_cast<const float*>(B)[Bbase + off];
   };
+
+  // tile-independent parts.  A: element i is (m, k) = TA ? (tid % 128, tid / 128 + 2 i) : (tid / 16 + 16 i, tid % 16);
+  // B: element i is (n, k) = TB ? (tid / 16 + 16 i, tid % 16) : (tid % 128, tid / 128 + 2 i).
+  size_t aoff[8], boff[8];
+  bool aok[8], bok[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int m = TA ? tid % 128 : tid / 16 + 16 * i, k = TA ? tid / 128 + 2 * i : tid % 16;
+    const int gm = m0 + m;
+    aok[i] = gm < p.M;
+    aoff[i] = aok[i] ? (TA ? (size_t)k * p.lda + gm : (size_t)gm * p.lda + k) : 0;
+    const int n = TB ? tid / 16 + 16 * i : tid % 128, kb = TB ? tid % 16 : tid / 128 + 2 * i;
+    const int gn = n0 + n;
+    bok[i] = gn < p.N;
+    if (!bok[i]) boff[i] = 0;
+    else if (p.shufB) boff[i] = TB ? shuf_row(gn, p.shufH, p.shufW)                       // + pixel part of k, per tile
+                                   : shuf_pix(gn, p.shufW) + shuf_row(kb, p.shufH, p.shufW);  // + row part of k0, per tile
+    else boff[i] = TB ? (size_t)gn * p.ldb + kb : (size_t)kb * p.ldb + gn;
+  }
 
   float ra[8], rb[8];
   auto gload = [&](int k0) {
+    // what the tile adds to the offsets (k0 is a multiple of 16, so with shufB and !TB the row part of k0 + kb
+    // is the sum of the two row parts: k0's low bits are zero)
+    const size_t astep = TA ? (size_t)k0 * p.lda : (size_t)k0;
+    size_t bstep;
+    if (p.shufB) bstep = TB ? shuf_pix(k0 + tid % 16 < kend ? k0 + tid % 16 : kbeg, p.shufW) : shuf_row(k0, p.shufH, p.shufW);
+    else bstep = TB ? (size_t)k0 : (size_t)k0 * p.ldb;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      int m, k;
-      if (TA) { m = tid % 128; k = tid / 128 + 2 * i; } else { k = tid % 16; m = tid / 16 + 16 * i; }
-      const int gm = m0 + m, gk = k0 + k;
-      const bool ok = gm < p.M && gk < kend;
-      const size_t off = TA ? (size_t)gk * p.lda + gm : (size_t)gm * p.lda + gk;
-      ra[i] = ok ? ldA(off) : 0.f;
-      int n, kb;
-      if (TB) { kb = tid % 16; n = tid / 16 + 16 * i; } else { n = tid % 128; kb = tid / 128 + 2 * i; }
-      const int gn = n0 + n, gkb = k0 + kb;
-      const bool okb = gn < p.N && gkb < kend;
-      size_t offb = TB ? (size_t)gn * p.ldb + gkb : (size_t)gkb * p.ldb + gn;
-      if (p.shufB) offb = shuffled(TB ? gn : gkb, TB ? gkb : gn, p.shufH, p.shufW);
-      rb[i] = okb ? ldB(offb) : 0.f;
+      const int k = TA ? tid / 128 + 2 * i : tid % 16;
+      ra[i] = (aok[i] && k0 + k < kend) ? ldA(aoff[i] + astep) : 0.f;
+      const int kb = TB ? tid % 16 : tid / 128 + 2 * i;
+      rb[i] = (bok[i] && k0 + kb < kend) ? ldB(boff[i] + bstep) : 0.f;
     }
   };
   auto sstore = [&](int buf) {
@@ -109,18 +134,22 @@ __global__ __launch_bounds__(NT) void k_gemm(const void* __restrict__ A, const v
   }
   // accumulator tile (i, j): rows m = wm + 16 i + 4 lg + r, column n = wn + 16 j + lc
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int j = 0; j < 4; ++j) {
+    const int gn = n0 + wn + 16 * j + lc;
+    if (gn >= p.N) continue;
+    const size_t coff = Cbase + (p.shufC ? shuf_pix(gn, p.shufW) : (size_t)gn);
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int i = 0; i < 4; ++i)
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        const int gm = m0 + wm + 16 * i + 4 * lg + r, gn = n0 + wn + 16 * j + lc;
-        if (gm < p.M && gn < p.N) {
-          const size_t off = Cbase + (p.shufC ? shuffled(gm, gn, p.shufH, p.shufW) : (size_t)gm * p.ldc + gn);
-          if (p.bf16C) static_cast<uint16_t*>(C)[off] = f32_to_bf16(acc[i][j][r]);
+        const int gm = m0 + wm + 16 * i + 4 * lg + r;
+        if (gm < p.M) {
+          const size_t off = coff + (p.shufC ? shuf_row(gm, p.shufH, p.shufW) : (size_t)gm * p.ldc);
+          if (BF == 2) static_cast<uint16_t*>(C)[off] = f32_to_bf16(acc[i][j][r]);
           else static_cast<float*>(C)[off] = acc[i][j][r];
         }
       }
+  }
 }
 
 // out[e] = sum_z part[z][e], z ascending (fixed order).
@@ -135,12 +164,19 @@ __global__ __launch_bounds__(256) void k_sum_parts(const float* __restrict__ par
 
 }  // namespace
 
-void launch_gemm(const GemmArgs& a, const void* A, const void* B, void* C, hipStream_t st) {
+template <int BF>
+void launch_gemm_t(const GemmArgs& a, const void* A, const void* B, void* C, hipStream_t st) {
   dim3 grid((a.M + BM - 1) / BM, (a.N + BN - 1) / BN, a.batch * a.splitk);
-  if (a.transA && a.transB) hipLaunchKernelGGL((k_gemm<true, true>), grid, dim3(NT), 0, st, A, B, C, a);
-  else if (a.transA) hipLaunchKernelGGL((k_gemm<true, false>), grid, dim3(NT), 0, st, A, B, C, a);
-  else if (a.transB) hipLaunchKernelGGL((k_gemm<false, true>), grid, dim3(NT), 0, st, A, B, C, a);
-  else hipLaunchKernelGGL((k_gemm<false, false>), grid, dim3(NT), 0, st, A, B, C, a);
+  if (a.transA && a.transB) hipLaunchKernelGGL((k_gemm<true, true, BF>), grid, dim3(NT), 0, st, A, B, C, a);
+  else if (a.transA) hipLaunchKernelGGL((k_gemm<true, false, BF>), grid, dim3(NT), 0, st, A, B, C, a);
+  else if (a.transB) hipLaunchKernelGGL((k_gemm<false, true, BF>), grid, dim3(NT), 0, st, A, B, C, a);
+  else hipLaunchKernelGGL((k_gemm<false, false, BF>), grid, dim3(NT), 0, st, A, B, C, a);
+}
+void launch_gemm(const GemmArgs& a, const void* A, const void* B, void* C, hipStream_t st) {
+  // the glue uses three storage combinations: all fp32, bf16 operands with an fp32 or a bf16 result
+  if (a.bf16A && a.bf16B && a.bf16C) launch_gemm_t<2>(a, A, B, C, st);
+  else if (a.bf16A && a.bf16B) launch_gemm_t<1>(a, A, B, C, st);
+  else launch_gemm_t<0>(a, A, B, C, st);
 }
 
 void launch_sum_parts(const float* part, float* out, size_t n, int nparts, size_t stride, hipStream_t st) {
