@@ -65,7 +65,7 @@ typedef enum {
 } rotconv_status;
 
 typedef enum { ROTCONV_F32 = 0, ROTCONV_BF16 = 1 } rotconv_dtype;
-typedef enum { ROTCONV_EXACT90 = 0, ROTCONV_STEERABLE = 1, ROTCONV_BILINEAR = 2 } rotconv_mode;
+typedef enum { ROTCONV_EXACT90 = 0, ROTCONV_STEERABLE = 1, ROTCONV_BILINEAR = 2, ROTCONV_P4M = 3 } rotconv_mode;
 typedef enum { ROTCONV_POOL_MAX = 0, ROTCONV_POOL_AVG = 1 } rotconv_pool_op;
 
 /* Problem statement of Sec. III (input C_in x H x W, filters C_out x C_in x K x K),
@@ -81,7 +81,13 @@ typedef struct {
                                STEERABLE: F_phi = sin(phi) f_x + cos(phi) f_y (Eq. 17).
                                BILINEAR: F_phi = base filter resampled bilinearly about the
                                tap-grid centre, zero outside the k x k support (not the
-                               paper's rule; the benchmark configurations ask for it). */
+                               paper's rule; the benchmark configurations ask for it).
+                               P4M: rotations and reflection (the p4m group of Sec. II /
+                               Sec. III-B): R is even, angles_deg must be NULL; orientation
+                               r < R/2 is the base filter turned by r*360/(R/2) degrees
+                               (multiples of 90, so R is 2, 4 or 8), orientation R/2 + a is
+                               the left-right mirrored base filter, M[i][j] = W[i][k-1-j],
+                               turned by the same angle a*360/(R/2). */
   int32_t stride, pad;      /* stride >= 1, pad >= 0                                   */
   int32_t pool_group;       /* G, must divide R; 0 means R (one pooled map per filter) */
   int32_t dtype;            /* rotconv_dtype of x, w, y, ypool, gpool, dy, dx.

@@ -70,6 +70,13 @@ def expand_bank(w_base, R: int, angles_deg: Optional[Sequence[float]] = None, mo
     w = _f64(w_base)
     if w.ndim == 4:
         w = w[None]
+    if mode == "p4m":
+        # the p4m group (Sec. II, Sec. III-B): R/2 quarter-turn rotations of the filter, then the same rotations
+        # of its left-right mirror image M[i][j] = W[i][k-1-j]
+        assert R % 2 == 0 and angles_deg is None
+        plain = expand_bank(w, R // 2, None, "exact90")
+        mirrored = expand_bank(np.flip(w, axis=-1), R // 2, None, "exact90")
+        return np.concatenate([plain, mirrored], axis=0)
     B, Cout, Cin, k, k2 = w.shape
     assert k == k2 and B == (2 if mode == "steerable" else 1)
     ang = default_angles(R) if angles_deg is None else _f64(angles_deg)
@@ -85,6 +92,9 @@ def reduce_bank_grad(dw_rot, angles_deg: Optional[Sequence[float]] = None, mode:
     """[R,Cout,Cin,k,k] -> [B,Cout,Cin,k,k]: inverse-rotate and accumulate (Eq. 16)."""
     d = _f64(dw_rot)
     R, Cout, Cin, k, _ = d.shape
+    if mode == "p4m":   # adjoint of the expansion above: rotate back both halves, mirror the second back, add
+        assert R % 2 == 0 and angles_deg is None
+        return reduce_bank_grad(d[:R // 2], None, "exact90") + np.flip(reduce_bank_grad(d[R // 2:], None, "exact90"), axis=-1)
     ang = default_angles(R) if angles_deg is None else _f64(angles_deg)
     B = 2 if mode == "steerable" else 1
     out = np.empty((B, Cout, Cin, k, k), dtype=np.float64)

@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(HERE, "librotconv.so")
 OK = 0
 ERR_NULL, ERR_SHAPE, ERR_ANGLES, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_LAUNCH = -1, -2, -3, -4, -5, -6
 F32, BF16 = 0, 1
-MODES = {"exact90": 0, "steerable": 1, "bilinear": 2}
+MODES = {"exact90": 0, "steerable": 1, "bilinear": 2, "p4m": 3}
 POOL_OPS = {"max": 0, "avg": 1}
 
 EXPORTS = [

@@ -30,8 +30,13 @@ int turned_tap(int k, int s, int u) {
 }
 
 // Non-zeros of row (dst tap t) of the first-quadrant map base -> F_phi.
-int first_quadrant_row(int mode, int k, double phi_deg, int t, Nz out[kMaxNnz]) {
+// mirrored: the bank is built from the left-right mirrored base filter (P4M mode: a tap permutation).
+int first_quadrant_row(int mode, int k, double phi_deg, bool mirrored, int t, Nz out[kMaxNnz]) {
   const int kk = k * k;
+  if (mode == ROTCONV_P4M) {
+    out[0] = {mirrored ? (t / k) * k + (k - 1 - t % k) : t, 1.0};
+    return 1;
+  }
   if (mode == ROTCONV_EXACT90 || (mode == ROTCONV_BILINEAR && phi_deg == 0.0)) {
     out[0] = {t, 1.0};
     return 1;
@@ -99,8 +104,10 @@ int validate_and_build(const rotconv_desc* desc, rotconv_plan** out) {
   const int G = d.pool_group == 0 ? d.R : d.pool_group;
   if (G > d.R || d.R % G != 0) return ROTCONV_ERR_SHAPE;
   if (d.H + 2 * d.pad < d.k || d.W + 2 * d.pad < d.k) return ROTCONV_ERR_SHAPE;
-  if (d.mode != ROTCONV_EXACT90 && d.mode != ROTCONV_STEERABLE && d.mode != ROTCONV_BILINEAR)
+  if (d.mode != ROTCONV_EXACT90 && d.mode != ROTCONV_STEERABLE && d.mode != ROTCONV_BILINEAR && d.mode != ROTCONV_P4M)
     return ROTCONV_ERR_UNSUPPORTED;
+  const bool p4m = d.mode == ROTCONV_P4M;
+  if (p4m && (d.angles_deg || (d.R != 2 && d.R != 4 && d.R != 8))) return ROTCONV_ERR_ANGLES;
   if (d.dtype != ROTCONV_F32 && d.dtype != ROTCONV_BF16) return ROTCONV_ERR_UNSUPPORTED;
   if (d.pool_op != ROTCONV_POOL_MAX && d.pool_op != ROTCONV_POOL_AVG) return ROTCONV_ERR_UNSUPPORTED;
   if (d.pool_op == ROTCONV_POOL_AVG && d.dtype != ROTCONV_F32) return ROTCONV_ERR_UNSUPPORTED;
@@ -112,12 +119,14 @@ int validate_and_build(const rotconv_desc* desc, rotconv_plan** out) {
       !fits_i32(double(d.R) * d.Cout * d.Cin * kk))
     return ROTCONV_ERR_UNSUPPORTED;
 
+  // P4M: the second half of the orientations repeats the angles of the first on the mirrored filter
+  const int nrot = p4m ? d.R / 2 : d.R;
   std::vector<double> ang(d.R);
-  for (int r = 0; r < d.R; ++r) ang[r] = d.angles_deg ? d.angles_deg[r] : r * (360.0 / d.R);
+  for (int r = 0; r < d.R; ++r) ang[r] = d.angles_deg ? d.angles_deg[r] : (r % nrot) * (360.0 / nrot);
   for (int r = 0; r < d.R; ++r) {
     if (!(ang[r] >= 0.0 && ang[r] < 360.0)) return ROTCONV_ERR_ANGLES;
-    if (r && !(ang[r] > ang[r - 1])) return ROTCONV_ERR_ANGLES;
-    if (d.mode == ROTCONV_EXACT90 && std::fmod(ang[r], 90.0) != 0.0) return ROTCONV_ERR_ANGLES;
+    if (r % nrot && !(ang[r] > ang[r - 1])) return ROTCONV_ERR_ANGLES;
+    if ((d.mode == ROTCONV_EXACT90 || p4m) && std::fmod(ang[r], 90.0) != 0.0) return ROTCONV_ERR_ANGLES;
   }
 
   rotconv_plan* p = new (std::nothrow) rotconv_plan();
@@ -139,12 +148,14 @@ int validate_and_build(const rotconv_desc* desc, rotconv_plan** out) {
   for (int r = 0; r < d.R; ++r) {
     const int s = static_cast<int>(std::floor(ang[r] / 90.0));
     const double phi = ang[r] - 90.0 * s;
+    const int mir = p4m && r >= nrot ? 1 : 0;
     int q = -1;
     for (size_t i = 0; i < t.phi_deg.size(); ++i)
-      if (t.phi_deg[i] == phi) q = static_cast<int>(i);
+      if (t.phi_deg[i] == phi && t.mirrored[i] == mir) q = static_cast<int>(i);
     if (q < 0) {
       q = static_cast<int>(t.phi_deg.size());
       t.phi_deg.push_back(phi);
+      t.mirrored.push_back(mir);
     }
     t.bank_of_r[r] = q;
     t.quarter_of_r[r] = s & 3;
@@ -162,7 +173,7 @@ int validate_and_build(const rotconv_desc* desc, rotconv_plan** out) {
   for (int q = 0; q < t.Q; ++q)
     for (int u = 0; u < kk; ++u) {
       Nz nz[kMaxNnz];
-      const int n = first_quadrant_row(d.mode, d.k, t.phi_deg[q], u, nz);
+      const int n = first_quadrant_row(d.mode, d.k, t.phi_deg[q], t.mirrored[q] != 0, u, nz);
       for (int e = 0; e < n; ++e) {
         t.fq_src[(q * kk + u) * kMaxNnz + e] = nz[e].src;
         t.fq_coef[(q * kk + u) * kMaxNnz + e] = static_cast<float>(nz[e].coef);

@@ -18,6 +18,7 @@ struct HostTables {
   int Q = 0;
   std::vector<int> bank_of_r, quarter_of_r;
   std::vector<double> phi_deg;  // per first-quadrant bank
+  std::vector<int> mirrored;    // per bank: built from the left-right mirrored base filter (P4M mode)
   // Forward expansion, one row per (r, dst tap): up to kMaxNnz (src, coef) pairs, src = -1 unused.
   std::vector<int32_t> exp_src;  // [R*kk*kMaxNnz]
   std::vector<float> exp_coef;   // [R*kk*kMaxNnz]

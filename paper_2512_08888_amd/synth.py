@@ -82,7 +82,7 @@ class LayerConfig:
     Cout: int
     k: int = 3
     R: int = 4
-    mode: str = "exact90"          # "exact90" | "steerable" | "bilinear"
+    mode: str = "exact90"          # "exact90" | "steerable" | "bilinear" | "p4m"
     stride: int = 1
     pad: int = 1
     pool_group: Optional[int] = None  # None -> R (one pooled map per filter)

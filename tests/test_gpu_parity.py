@@ -55,6 +55,11 @@ TINY = [
     LC("t_cin288_r16", N=1, Cin=288, H=9, W=64, Cout=16, R=16, mode="bilinear", seed=37),
     LC("t_cin288_w96", N=1, Cin=288, H=6, W=96, Cout=8, R=4, seed=42),     # streamed block, chain beyond the row
     LC("t_w544_cin6", N=1, Cin=6, H=6, W=544, Cout=16, R=8, mode="steerable", pool_group=4, seed=38),
+    # the p4m group (rotations and reflection): the mirrored filter is a second bank of the same kernels
+    LC("t_p4m", N=2, Cin=5, H=10, W=12, Cout=6, R=8, mode="p4m", seed=44),
+    LC("t_p4m_r4", N=1, Cin=3, H=9, W=7, Cout=4, R=4, mode="p4m", seed=45),
+    LC("t_p4m_k5_g1", N=1, Cin=2, H=8, W=8, Cout=3, k=5, pad=2, R=8, mode="p4m", pool_group=1, seed=46),
+    LC("t_p4m_c40", N=1, Cin=40, H=12, W=64, Cout=24, R=8, mode="p4m", x_dist="absnormal", seed=47),
     # rows that end half way through a lane's eight pixels (W % 8 == 4), one and several strips, many rows
     LC("t_w4", N=2, Cin=5, H=10, W=4, Cout=6, R=4, seed=39),
     LC("t_w44", N=1, Cin=3, H=7, W=44, Cout=4, R=4, seed=40),

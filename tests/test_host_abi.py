@@ -140,3 +140,21 @@ def test_expansion_table_reproduces_oracle_banks(R, mode, k, angles):
         # pure permutation: exactly one unit entry per row
         assert np.array_equal(np.sort(E.reshape(R, k * k, -1), axis=-1)[..., -1], np.ones((R, k * k)))
         assert np.count_nonzero(E) == R * k * k
+
+
+def test_p4m_tables_reproduce_the_oracle_banks():
+    """Host-built expansion of the p4m mode (two banks: the filter and its mirror image, four quarter turns each)
+    against the oracle's materialised filters; and the descriptor checks of that mode."""
+    for R in (2, 4, 8):
+        plan = rc.Plan(1, 2, 8, 8, 3, k=3, R=R, mode="p4m")
+        E = plan.expansion()                       # [R][kk][B][kk]
+        w = RNG.standard_normal((1, 3, 2, 3, 3))
+        ref = orc.expand_bank(w, R, None, "p4m")
+        got = np.einsum("rtbu,bocu->roct", E.astype(np.float64), w.reshape(1, 3, 2, 9)).reshape(ref.shape)
+        assert np.array_equal(got, ref)
+        Q, bank, quarter = plan.orientations()
+        assert Q == 2 and bank == [0] * (R // 2) + [1] * (R // 2)
+    for bad in (dict(R=6), dict(R=8, angles_deg=[0, 45, 90, 135, 180, 225, 270, 315])):
+        with pytest.raises(rc.RotconvError) as e:
+            rc.Plan(1, 2, 8, 8, 3, k=3, mode="p4m", **bad)
+        assert e.value.status == rc.ERR_ANGLES

@@ -483,3 +483,40 @@ def test_steerable_regulariser_gradients_autograd_and_finite_differences():
         fp, fm = orc.steerable_reg(wp, eps), orc.steerable_reg(wm, eps)
         assert np.isclose((fp[0] - fm[0]) / (2 * h), g_mag[i], rtol=1e-5, atol=1e-8)
         assert np.isclose((fp[1] - fm[1]) / (2 * h), g_orth[i], rtol=1e-5, atol=1e-8)
+
+
+# ---------------------------------------------------------------- p4m: rotations and reflection (Sec. II, Sec. III-B)
+
+def test_p4m_bank_is_numpy_rot90_of_the_filter_and_of_its_mirror_image():
+    for k in (2, 3, 5):
+        w = rnd(1, 2, 3, k, k)
+        for R in (2, 4, 8):
+            half = R // 2
+            wr = orc.expand_bank(w, R, None, "p4m")
+            for a in range(half):
+                s = a * (4 // half)
+                assert np.array_equal(wr[a], np.rot90(w[0], s, axes=(-2, -1)))
+                assert np.array_equal(wr[half + a], np.rot90(np.flip(w[0], axis=-1), s, axes=(-2, -1)))
+    # the eight filters are closed under mirroring: flip(rot^s W) = rot^-s(flip W)
+    wr = orc.expand_bank(rnd(1, 1, 1, 3, 3), 8, None, "p4m")
+    for s in range(4):
+        assert np.array_equal(np.flip(wr[s], axis=-1), wr[4 + (4 - s) % 4])
+
+
+def test_p4m_pooled_output_is_invariant_to_mirroring_and_quarter_turns():
+    x = rnd(1, 2, 6, 6)
+    w = rnd(1, 3, 2, 3, 3)
+    y, yp, idx, _ = orc.layer_fwd(x, w, 8, None, "p4m", 1, 1, 8)
+    ym, ypm, _, _ = orc.layer_fwd(np.flip(x, axis=-1), w, 8, None, "p4m", 1, 1, 8)
+    np.testing.assert_allclose(ypm, np.flip(yp, axis=-1), rtol=1e-12, atol=1e-12)
+    for s in range(4):      # Y_s(flip X) = flip(Y_{4 + (-s mod 4)}(X))
+        np.testing.assert_allclose(ym[:, :, s], np.flip(y[:, :, 4 + (4 - s) % 4], axis=-1), rtol=1e-12, atol=1e-12)
+    _, ypr, _, _ = orc.layer_fwd(np.rot90(x, 1, axes=(-2, -1)), w, 8, None, "p4m", 1, 1, 8)
+    np.testing.assert_allclose(ypr, np.rot90(yp, 1, axes=(-2, -1)), rtol=1e-12, atol=1e-12)
+
+
+def test_p4m_gradient_reduction_is_the_adjoint_of_the_expansion():
+    w, d = rnd(1, 2, 3, 3, 3), rnd(8, 2, 3, 3, 3)
+    lhs = (orc.expand_bank(w, 8, None, "p4m") * d).sum()
+    rhs = (w * orc.reduce_bank_grad(d, None, "p4m")).sum()
+    assert np.isclose(lhs, rhs, rtol=1e-12)
