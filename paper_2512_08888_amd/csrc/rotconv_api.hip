@@ -410,8 +410,8 @@ int rotconv_fwd(const rotconv_plan* plan, const void* x, const void* w, void* y,
     const int rc = ensure_device_tables(p);
     if (rc) return rc;
     uint16_t* wt = static_cast<uint16_t*>(ws);
-    launch_p4_pack_fwd_bf16(p, h16(w), wt, st);
-    launch_p4_fwd_bf16(p, kOutUnpooled, h16(x), wt, y, nullptr, st);
+    launch_p4_pack_fwd_bf16(p, 1, h16(w), wt, st);
+    launch_p4_fwd_bf16(p, kOutUnpooled, 1, h16(x), wt, y, nullptr, st);
     return finish();
   }
   const Stage s = carve(plan, ws, ws_bytes);
@@ -480,13 +480,16 @@ int rotconv_pool_fwd(const rotconv_plan* plan, const void* x, const void* w, voi
     uint16_t* wt = static_cast<uint16_t*>(ws);
     char* extra = static_cast<char*>(ws) + align256(p4_fwd_pack_floats(p) * sizeof(float));
     const size_t hw = (size_t)p->d.H * p->d.W;
-    launch_p4_pack_fwd_bf16(p, h16(w), wt, st);
+    const int nq = pmode == kOutPartial ? p4_fwd_bf16_fold(p) : 1;
+    launch_p4_pack_fwd_bf16(p, nq, h16(w), wt, st);
     if (pmode == kOutPooled) {
-      launch_p4_fwd_bf16(p, pmode, h16(x), wt, ypool, idx, st);
+      launch_p4_fwd_bf16(p, pmode, 1, h16(x), wt, ypool, idx, st);
+    } else if (nq > 1) {     // the pool group spans all banks: pooled across them inside the kernel
+      launch_p4_fwd_bf16(p, kOutPooled, nq, h16(x), wt, ypool, idx, st);
     } else {
       float* pv = reinterpret_cast<float*>(extra);
       uint8_t* pi = reinterpret_cast<uint8_t*>(extra + align256((size_t)p->host.Q * p->d.N * p->d.Cout * hw * 4));
-      launch_p4_fwd_bf16(p, pmode, h16(x), wt, pv, pi, st);
+      launch_p4_fwd_bf16(p, pmode, 1, h16(x), wt, pv, pi, st);
       launch_p4_combine_bf16(p, pv, pi, static_cast<uint16_t*>(ypool), idx, st);
     }
     return finish();

@@ -18,6 +18,7 @@ struct P4Geom {
   int out_mode;  // kOut*
   int nseg;      // row segments handled by this launch (1 unless W > 256)
   int inside;    // 1 if no segment's wave chain reaches beyond the row
+  int nq;        // bf16 forward: banks folded into a wave's 16 filter columns (0 / 1: none)
   int seg_xorg[4];  // first product column of a segment's wave chain
   int seg_lo[4], seg_hi[4];  // output pixels [lo, hi) the segment stores (multiples of 8, or W)
 };
@@ -37,8 +38,9 @@ void launch_p4_combine(const rotconv_plan* p, const float* pv, const uint8_t* pi
 // unpooled modes and fp32 for the per-bank candidates
 bool p4_fwd_bf16_supported(const rotconv_plan* p);
 size_t p4_fwd_bf16_pack_bytes(const rotconv_plan* p);
-void launch_p4_pack_fwd_bf16(const rotconv_plan* p, const uint16_t* w, uint16_t* wt, hipStream_t st);
-void launch_p4_fwd_bf16(const rotconv_plan* p, int out_mode, const uint16_t* x, const uint16_t* wt, void* out_val,
+int p4_fwd_bf16_fold(const rotconv_plan* p);   // banks a wave can fold into its columns for the pooled forward (1: none)
+void launch_p4_pack_fwd_bf16(const rotconv_plan* p, int nq, const uint16_t* w, uint16_t* wt, hipStream_t st);
+void launch_p4_fwd_bf16(const rotconv_plan* p, int out_mode, int nq, const uint16_t* x, const uint16_t* wt, void* out_val,
                         uint8_t* out_idx, hipStream_t st);
 void launch_p4_combine_bf16(const rotconv_plan* p, const float* pv, const uint8_t* pi, uint16_t* ypool, uint8_t* idx,
                             hipStream_t st);

@@ -45,7 +45,12 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
 // FASTW:    W % 8 == 0 and no wave chain reaches beyond the row: no load masks, vector stores.
 // STREAM:   the filter block does not fit LDS: stream it in stages of ND chunks.
 // CPAD:     CinPad > Cin: channel offsets are clamped to the last real channel (its taps are zero).
-template <int NWX, int NWY, int ND, bool UNPOOLED, bool FASTW, bool STREAM, bool CPAD>
+// NQ:       banks folded into the 16 filter columns of a wave (1, 2 or 4).  NQ > 1 is for a pool group that spans
+//           all NQ banks of the plan (R = 4 NQ orientations pooled together): column n holds bank n / (16/NQ),
+//           filter n % (16/NQ), every lane places and maximises its own bank's four rotations, and the maximum
+//           across the banks is a rotate-and-compare inside the 16-lane row (DPP) - the per-bank candidates
+//           never go through memory.  Pooled output only; every bank has all four quarter turns.
+template <int NWX, int NWY, int ND, bool UNPOOLED, bool FASTW, bool STREAM, bool CPAD, int NQ>
 __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd_bf16(const uint16_t* __restrict__ x,
                                                                 const uint16_t* __restrict__ wt,
                                                                 const int32_t* __restrict__ rot_of,
@@ -109,9 +114,11 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd_bf16(const uint16_t* 
   const int nsteps = g.TY + 2;
   const int HW = g.H * g.W;
 
+  constexpr int FPB = 16 / NQ;               // filters per wave
+  const int qi = NQ > 1 ? lc / FPB : q;       // this lane's bank
   int rot[4];
 #pragma unroll
-  for (int s = 0; s < 4; ++s) rot[s] = rot_of[q * 4 + s];
+  for (int s = 0; s < 4; ++s) rot[s] = rot_of[qi * 4 + s];
 
   // A-operand loads: lane (lc, lg) reads the dword X[ci = 32*chunk + 8*lg + j][h][x0 + 2*lc .. +1],
   // j = 0..7.  Rows outside the image are never multiplied, channels beyond Cin meet zero taps, so both
@@ -276,8 +283,8 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd_bf16(const uint16_t* 
     // ---- place the row of products at the rotated positions (Eq. 8) --------------
     const int y = h - 1;                       // output row completed by this step
     const int px0 = x0 + 8 * lg;               // first of this lane's 8 pixels
-    const int co = cb * 16 + lc;
-    const bool fin = t >= 2 && y < g.H && co < g.Cout && px0 >= out_lo && px0 < out_hi;
+    const int co = NQ > 1 ? cb * FPB + lc % FPB : cb * 16 + lc;
+    const bool fin = t >= 2 && y < g.H && co < g.Cout && px0 >= out_lo && px0 < out_hi && (NQ == 1 || lc < FPB);
     float best[8];
     uint32_t pk[2] = {0u, 0u};                 // arg-max bytes of the lane's 8 pixels
     int grp_r = 0;                             // any rotation of the bank (its pool group)
@@ -318,9 +325,13 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd_bf16(const uint16_t* 
                           (size_t)y * g.W + px0, yfin);
       }
     } else {
+      if (NQ == 1) {
 #pragma unroll
-      for (int s = 0; s < 4; ++s)
-        if (rot[s] >= 0) { grp_r = rot[s]; none = false; }
+        for (int s = 0; s < 4; ++s)
+          if (rot[s] >= 0) { grp_r = rot[s]; none = false; }
+      } else {
+        none = false;       // all rotations present, one pool group (channel = co)
+      }
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
         float bv = 0.f;
@@ -330,12 +341,26 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd_bf16(const uint16_t* 
         for (int s = 0; s < 4; ++s) {
           float yv;
           place(s, j, yv);
-          if (rot[s] >= 0) {          // wave-uniform
+          if (NQ > 1 || rot[s] >= 0) {          // NQ == 1: wave-uniform
             const bool gt = !have || yv > bv;
             bv = gt ? yv : bv;
             bi = gt ? rot[s] : bi;
             have = true;
           }
+        }
+        if (NQ > 1) {
+          // maximum across the banks: the lanes of one filter sit FPB apart inside the 16-lane row
+          auto other = [&](int ctrl_v, int ctrl_i) {
+            const float ov = __builtin_bit_cast(float, ctrl_v);
+            const bool take = ov > bv || (ov == bv && ctrl_i < bi);     // ties: the smallest orientation index
+            bv = take ? ov : bv;
+            bi = take ? ctrl_i : bi;
+          };
+          other(__builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, bv), 0x128, 0xf, 0xf, false),
+                __builtin_amdgcn_update_dpp(0, bi, 0x128, 0xf, 0xf, false));                       // row_ror:8
+          if (NQ == 4)
+            other(__builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, bv), 0x124, 0xf, 0xf, false),
+                  __builtin_amdgcn_update_dpp(0, bi, 0x124, 0xf, 0xf, false));                     // row_ror:4
         }
         best[j] = bv;
         pk[j >> 2] |= (uint32_t)bi << (8 * (j & 3));
@@ -406,11 +431,12 @@ __global__ __launch_bounds__(256) void k_p4_combine_bf16(const float* __restrict
 // bf16 base bank(s) -> Q first-quadrant banks (Sec. III-D / Eq. 17 combination in fp32, rounded to bf16
 // once) in the LDS image layout [Q][CB][chunk][9 taps][4 k-groups][16 filters][8 channels]; zero for
 // padded filters / channels.
+// nq > 1: the banks are folded into the 16 columns (column n = bank n / (16/nq), filter n % (16/nq)): [CB'][chunk]...
 __global__ __launch_bounds__(256) void k_p4_pack_fwd_bf16(const uint16_t* __restrict__ w, uint16_t* __restrict__ wt,
                                                           const int32_t* __restrict__ fq_src,
                                                           const float* __restrict__ fq_coef, int Q, int CB, int CinPad,
-                                                          int Cin, int Cout) {
-  const int total = Q * CB * CinPad * 144;
+                                                          int Cin, int Cout, int nq) {
+  const int total = (nq > 1 ? 1 : Q) * CB * CinPad * 144;
   const int e = blockIdx.x * 256 + threadIdx.x;
   if (e >= total) return;
   const int c8 = e % 8;
@@ -419,8 +445,9 @@ __global__ __launch_bounds__(256) void k_p4_pack_fwd_bf16(const uint16_t* __rest
   const int u = (e / 512) % 9;
   const int chunk = (e / 4608) % (CinPad / 32);
   const int cb = (e / (144 * CinPad)) % CB;
-  const int q = e / (144 * CinPad * CB);
-  const int co = cb * 16 + f16, ci = chunk * 32 + kg * 8 + c8;
+  const int fpb = 16 / nq;
+  const int q = nq > 1 ? f16 / fpb : e / (144 * CinPad * CB);
+  const int co = nq > 1 ? cb * fpb + f16 % fpb : cb * 16 + f16, ci = chunk * 32 + kg * 8 + c8;
   float acc = 0.f;
   if (co < Cout && ci < Cin) {
     const int slices = Cout * Cin;
@@ -440,13 +467,13 @@ int ring_depth(int Cin) { return std::min(2, cin_pad(Cin) / 32); }
 // Is the filter block of 16 filters too large to stay in LDS next to the edge arrays?
 bool needs_stream(int Cin) { return (size_t)(cin_pad(Cin) / 32) * CHB + 16384 > 160 * 1024; }
 
-template <int NWX, int NWY, int ND, bool UNPOOLED, bool FASTW, bool STREAM, bool CPAD>
+template <int NWX, int NWY, int ND, bool UNPOOLED, bool FASTW, bool STREAM, bool CPAD, int NQ = 1>
 void launch_i(const P4Geom& g, const uint16_t* x, const uint16_t* wt, const int32_t* rot_of, void* ov, uint8_t* oi,
               hipStream_t st) {
   const size_t wbytes = STREAM ? (size_t)2 * ND * CHB : (size_t)(g.CinPad / 32) * CHB;
   const size_t lds = wbytes + (size_t)4 * NWX * NWY * 128 * sizeof(float);
   const int grid = (g.units + 7) / 8 * 8;
-  auto kern = k_p4_fwd_bf16<NWX, NWY, ND, UNPOOLED, FASTW, STREAM, CPAD>;
+  auto kern = k_p4_fwd_bf16<NWX, NWY, ND, UNPOOLED, FASTW, STREAM, CPAD, NQ>;
   (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * NWX * NWY), lds, st, x, wt, rot_of, ov, oi, g);
 }
@@ -455,6 +482,16 @@ template <int NWX, int NWY, int ND>
 void launch_t(const P4Geom& g, bool fastw, bool stream, bool cpad, const uint16_t* x, const uint16_t* wt,
               const int32_t* rot_of, void* ov, uint8_t* oi, hipStream_t st) {
   const bool unp = g.out_mode == kOutUnpooled;
+  if (g.nq > 1) {       // banks folded into the columns: resident filter block, pooled output
+    if (g.nq == 4) {
+      if (fastw && !cpad) launch_i<NWX, NWY, ND, false, true, false, false, 4>(g, x, wt, rot_of, ov, oi, st);
+      else launch_i<NWX, NWY, ND, false, false, false, true, 4>(g, x, wt, rot_of, ov, oi, st);
+    } else {
+      if (fastw && !cpad) launch_i<NWX, NWY, ND, false, true, false, false, 2>(g, x, wt, rot_of, ov, oi, st);
+      else launch_i<NWX, NWY, ND, false, false, false, true, 2>(g, x, wt, rot_of, ov, oi, st);
+    }
+    return;
+  }
   // the specialised instances: pooled output, whole lanes inside the row; everything else takes the
   // general instance (masks, clamped channels)
   if (unp && stream) launch_i<NWX, NWY, ND, true, false, true, true>(g, x, wt, rot_of, ov, oi, st);
@@ -476,6 +513,17 @@ void launch_d(int nd, const P4Geom& g, bool fastw, bool stream, bool cpad, const
 
 }  // namespace
 
+// Banks folded into a wave's 16 columns: the plan pools all R = 4 Q orientations of a filter together, Q is 2 or
+// 4, every bank has its four quarter turns, and the filter block stays LDS-resident.  Then the pooled forward
+// needs no per-bank candidates.
+int p4_fwd_bf16_fold(const rotconv_plan* p) {
+  const int Q = p->host.Q;
+  if ((Q != 2 && Q != 4) || p->ng != 1 || needs_stream(p->d.Cin)) return 1;
+  for (int i = 0; i < Q * 4; ++i)
+    if (p->rot_of[i] < 0) return 1;
+  return Q;
+}
+
 // The bf16 kernel covers the fp32 kernel's shapes; the streamed variant (Cin > 480) is built for whole
 // lanes inside the row and unpadded channel counts.
 bool p4_fwd_bf16_supported(const rotconv_plan* p) {
@@ -489,16 +537,18 @@ size_t p4_fwd_bf16_pack_bytes(const rotconv_plan* p) {
   return (size_t)p->host.Q * ((p->d.Cout + 15) / 16) * cin_pad(p->d.Cin) * 144 * sizeof(uint16_t);
 }
 
-void launch_p4_pack_fwd_bf16(const rotconv_plan* p, const uint16_t* w, uint16_t* wt, hipStream_t st) {
-  const int CinPad = cin_pad(p->d.Cin), CB = (p->d.Cout + 15) / 16;
-  const int total = p->host.Q * CB * CinPad * 144;
+// nq: 1 = one bank per wave ([Q][CB] blocks); p4_fwd_bf16_fold(p) = banks folded into the columns ([CB'] blocks)
+void launch_p4_pack_fwd_bf16(const rotconv_plan* p, int nq, const uint16_t* w, uint16_t* wt, hipStream_t st) {
+  const int CinPad = cin_pad(p->d.Cin), CB = nq > 1 ? (p->d.Cout * nq + 15) / 16 : (p->d.Cout + 15) / 16;
+  const int total = (nq > 1 ? 1 : p->host.Q) * CB * CinPad * 144;
   hipLaunchKernelGGL(k_p4_pack_fwd_bf16, dim3((total + 255) / 256), dim3(256), 0, st, w, wt, p->dev.fq_src,
-                     p->dev.fq_coef, p->host.Q, CB, CinPad, p->d.Cin, p->d.Cout);
+                     p->dev.fq_coef, p->host.Q, CB, CinPad, p->d.Cin, p->d.Cout, nq);
 }
 
 // out_val: bf16 [N][C'][H][W] (kOutPooled), bf16 [N][Cout*R][H][W] (kOutUnpooled) or fp32 per-bank
 // candidates (kOutPartial).
-void launch_p4_fwd_bf16(const rotconv_plan* p, int out_mode, const uint16_t* x, const uint16_t* wt, void* out_val,
+// nq > 1 (only with kOutPooled): wt holds the folded blocks and the kernel pools across the banks itself.
+void launch_p4_fwd_bf16(const rotconv_plan* p, int out_mode, int nq, const uint16_t* x, const uint16_t* wt, void* out_val,
                         uint8_t* out_idx, hipStream_t st) {
   P4Geom gs[4];
   const int ng = p4_fwd_geoms(p, out_mode, gs, 4);
@@ -507,6 +557,13 @@ void launch_p4_fwd_bf16(const rotconv_plan* p, int out_mode, const uint16_t* x, 
   for (int i = 0; i < ng; ++i) {
     P4Geom& g = gs[i];
     g.CinPad = cin_pad(p->d.Cin);
+    g.nq = nq;
+    if (nq > 1) {         // one unit covers all banks of 16 / nq filters
+      const int CBf = (p->d.Cout * nq + 15) / 16;
+      g.units = g.units / (g.Q * g.CB) * CBf;
+      g.CB = CBf;
+      g.Q = 1;
+    }
     const bool fastw = (p->d.W & 7) == 0 && g.inside;
     const bool cpad = g.CinPad != p->d.Cin;
     switch (g.nwx) {

@@ -37,6 +37,8 @@ CASES = [
     LC("b_co96", N=1, Cin=16, H=6, W=40, Cout=96, R=4, seed=65),
     LC("b_co192_r16", N=1, Cin=16, H=5, W=32, Cout=192, R=16, mode="bilinear", seed=66),
     LC("b_co576_w96", N=1, Cin=8, H=5, W=96, Cout=576, R=4, seed=67),
+    LC("b_r8_fold2", N=1, Cin=40, H=9, W=64, Cout=20, R=8, mode="bilinear", seed=71),          # two banks in one wave
+    LC("b_r16_fold4_w40", N=2, Cin=64, H=7, W=40, Cout=10, R=16, mode="steerable", x_dist="absnormal", seed=72),
     LC("b_r1", N=1, Cin=24, H=9, W=32, Cout=40, R=1, seed=68),                                 # a standard convolution
 ]
 
