@@ -20,6 +20,17 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float f) {
   return (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
 }
 
+// Packed routing of two bf16 values by their arg-max indices (max-pool backward, Eq. 12): x16 holds the two
+// idx bytes as halfwords, rs2 the wanted orientation in both halfwords; returns 0xffff in each halfword whose idx
+// matches, else 0 (halfword-wise min(x ^ r, 1) - 1).
+__device__ __forceinline__ uint32_t match_mask2(uint32_t x16, uint32_t rs2) {
+  const uint32_t y = x16 ^ rs2, one2 = 0x00010001u;
+  uint32_t t, m;
+  asm("v_pk_min_u16 %0, %1, %2" : "=v"(t) : "v"(y), "s"(one2));
+  asm("v_pk_sub_u16 %0, %1, %2" : "=v"(m) : "v"(t), "s"(one2));
+  return m;
+}
+
 void launch_widen(const uint16_t* in, float* out, size_t n, hipStream_t st);
 void launch_narrow(const float* in, uint16_t* out, size_t n, hipStream_t st);
 

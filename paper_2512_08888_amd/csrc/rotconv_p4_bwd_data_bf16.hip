@@ -182,20 +182,26 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_bwd_data_bf16(const uint1
         bw[1] = *reinterpret_cast<const u4*>(wc + 1024);
 #pragma unroll
         for (int i = 0; i < ND; ++i) {
-          // route per quarter turn (Eq. 12) and pack the eight filters into the K-slice of both tiles
+          // pack the eight filters' pixel pairs into the K-slices of both tiles (G and, as halfwords, idx), then
+          // route per quarter turn (Eq. 12): four packed instructions per operand dword
           u4 a0[4], a1[4];
-#pragma unroll
-          for (int s = 0; s < 4; ++s) {
-            const uint32_t rs = (uint32_t)rot[s];       // -1 (absent) matches no byte
-            uint32_t r[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j)
-              r[j] = ((ri[i][j] & 0xffu) == rs ? rg[i][j] & 0xffffu : 0u) |
-                     ((ri[i][j] >> 8) == rs ? rg[i][j] & 0xffff0000u : 0u);
+          {
+            uint32_t g0[4], g1[4], x0[4], x1[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-              a0[s][j] = __builtin_amdgcn_perm(r[2 * j + 1], r[2 * j], 0x05040100u);
-              a1[s][j] = __builtin_amdgcn_perm(r[2 * j + 1], r[2 * j], 0x07060302u);
+              g0[j] = __builtin_amdgcn_perm(rg[i][2 * j + 1], rg[i][2 * j], 0x05040100u);
+              g1[j] = __builtin_amdgcn_perm(rg[i][2 * j + 1], rg[i][2 * j], 0x07060302u);
+              x0[j] = __builtin_amdgcn_perm(ri[i][2 * j + 1], ri[i][2 * j], 0x0c040c00u);
+              x1[j] = __builtin_amdgcn_perm(ri[i][2 * j + 1], ri[i][2 * j], 0x0c050c01u);
+            }
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+              const uint32_t rs2 = (uint32_t)rot[s] * 0x00010001u;   // -1 (absent) matches no halfword
+#pragma unroll
+              for (int j = 0; j < 4; ++j) {
+                a0[s][j] = g0[j] & match_mask2(x0[j], rs2);
+                a1[s][j] = g1[j] & match_mask2(x1[j], rs2);
+              }
             }
           }
           __builtin_amdgcn_sched_barrier(0);

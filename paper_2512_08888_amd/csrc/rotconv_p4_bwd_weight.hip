@@ -19,6 +19,7 @@
 // transposed first-quadrant expansion, so the result is deterministic.
 #include <hip/hip_runtime.h>
 
+#include "rotconv_bf16.h"
 #include "rotconv_kernels.h"
 #include "rotconv_p4.h"
 
@@ -323,18 +324,19 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_weight_bf16(const uint16_t* __res
   // neighbour (high half), routed the same way.
   auto select_row = [&](const RowB& r, bool rok, bool pok, bool lok, bool rok2, uint32_t (&m)[4][5]) {
     // positions outside the image (or filters beyond Cout) get the idx byte 0xff, which matches no orientation
-    const uint32_t iw[2] = {(rok && pok) ? r.i0 : 0xffffffffu, (rok && pok) ? r.i1 : 0xffffffffu};
+    const uint32_t iw0 = (rok && pok) ? r.i0 : 0xffffffffu, iw1 = (rok && pok) ? r.i1 : 0xffffffffu;
     const uint32_t il = (rok && lok) ? (uint32_t)r.il : 0xffu, ir = (rok && rok2) ? (uint32_t)r.ir : 0xffu;
     const uint32_t glr = ((uint32_t)r.gl << 16) | (uint32_t)r.gr;
+    // the idx bytes of each pixel pair spread to halfwords, then four packed instructions per pair and quarter turn
+    const uint32_t x[5] = {__builtin_amdgcn_perm(0u, iw0, 0x0c010c00u), __builtin_amdgcn_perm(0u, iw0, 0x0c030c02u),
+                           __builtin_amdgcn_perm(0u, iw1, 0x0c010c00u), __builtin_amdgcn_perm(0u, iw1, 0x0c030c02u),
+                           ir | (il << 16)};
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
-      const uint32_t rs = (uint32_t)rot[s];   // -1 (absent) matches no byte
+      const uint32_t rs2 = (uint32_t)rot[s] * 0x00010001u;   // -1 (absent) matches no halfword
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const uint32_t b0 = (iw[j >> 1] >> (16 * (j & 1))) & 0xffu, b1 = (iw[j >> 1] >> (16 * (j & 1) + 8)) & 0xffu;
-        m[s][j] = (b0 == rs ? r.g[j] & 0xffffu : 0u) | (b1 == rs ? r.g[j] & 0xffff0000u : 0u);
-      }
-      m[s][4] = (il == rs ? glr & 0xffff0000u : 0u) | (ir == rs ? glr & 0xffffu : 0u);
+      for (int j = 0; j < 4; ++j) m[s][j] = r.g[j] & match_mask2(x[j], rs2);
+      m[s][4] = glr & match_mask2(x[4], rs2);
     }
   };
   // A operand of (quarter turn s, base tap u): the routed row where R_s puts the tap, its pixels shifted.
