@@ -172,3 +172,63 @@ def test_bf16_workspace_too_small_is_rejected():
     with pytest.raises(rc.RotconvError) as e:
         rc.rotconv_pool_fwd(plan, xd, wd, nan16(*P), torch.empty(P, dtype=torch.uint8, device="cuda"), small)
     assert e.value.status == rc.ERR_WORKSPACE
+
+
+def _pts(seed, n, dims):
+    return np.stack([synth.randint(seed + i, n, 0, d - 1) for i, d in enumerate(dims)], axis=1).astype(np.int32)
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("cfg,ns,npairs", [(synth.C2, 4096, 24), (synth.C3, 2048, 12)], ids=["C2", "C3"])
+def test_bf16_config_full_size_sampled(cfg, ns, npairs):
+    """Benchmark configurations 2 and 3 with bf16 tensors at full size, in the launch configuration bench.py --dtype bf16
+    times: sampled pooled outputs with arg-max, sampled dX and sampled (co,ci) dW slices computed one by one by the
+    oracle on the bf16 values, plus the homogeneity identities at full size."""
+    plan = rc.Plan.from_config(cfg, dtype=rc.BF16)
+    print(f"[case] bf16 full size {cfg.name} kernels {[plan.kernel_name(i) for i in range(3)]}", flush=True)
+    ang = None if cfg.angles_deg is None else list(cfg.angles_deg)
+    xd, x = bf(synth.make_x(cfg))
+    wd, w = bf(synth.make_w(cfg))
+    gd, g = bf(synth.make_g(cfg))
+    P = (cfg.N, plan.Cpooled, plan.Ho, plan.Wo)
+    ypd, idxd = nan16(*P), torch.full(P, 255, dtype=torch.uint8, device="cuda")
+    rc.rotconv_pool_fwd(plan, xd, wd, ypd, idxd)
+    yp, idx = f64(ypd), idxd.cpu().numpy()
+    w_rot = round_bf16(orc.expand_bank(w, cfg.R, ang, cfg.mode))
+    ng = cfg.R // cfg.G
+    pts = _pts(cfg.seed + 100, ns, (cfg.N, cfg.Cout, cfg.Ho, cfg.Wo))
+    yr = orc.rotconv_fwd_at(x, w_rot, pts, cfg.stride, cfg.pad)
+    ya = orc.rotconv_fwd_at(np.abs(x), np.abs(w_rot), pts, cfg.stride, cfg.pad)
+    rms = float(np.sqrt(np.mean(yr.reshape(-1, cfg.G, ng).max(axis=1) ** 2)))
+    for grp in range(ng):
+        members = np.arange(grp, cfg.R, ng)
+        best = yr[:, members].max(axis=1)
+        chan = pts[:, 1] * ng + grp
+        got_v = yp[pts[:, 0], chan, pts[:, 2], pts[:, 3]]
+        got_i = idx[pts[:, 0], chan, pts[:, 2], pts[:, 3]].astype(np.int64)
+        assert np.all(np.abs(got_v - best) <= BF_RTOL * np.abs(best) + BF_RTOL * rms), f"{cfg.name} fwd samples"
+        tau = 64.0 * np.finfo(np.float32).eps * ya[:, members].max(axis=1)
+        assert np.all(got_i % ng == grp) and np.all(yr[np.arange(ns), got_i] >= best - tau), f"{cfg.name} arg-max samples"
+    dxd = nan16(*xd.shape)
+    rc.rotconv_pool_bwd_data(plan, gd, idxd, wd, dxd)
+    dwd = torch.full(tuple(wd.shape), float("nan"), dtype=torch.float32, device="cuda")
+    rc.rotconv_pool_bwd_weight(plan, xd, gd, idxd, dwd)
+    dx, dw = f64(dxd), f64(dwd)
+    if cfg.N * cfg.Cout * cfg.R * cfg.Ho * cfg.Wo <= 160_000_000:
+        dy = orc.orient_maxpool_bwd(g, idx, cfg.R, cfg.G)
+        ptsx = _pts(cfg.seed + 200, ns, (cfg.N, cfg.Cin, cfg.H, cfg.W))
+        ref = orc.rotconv_bwd_data_at(dy, w_rot, ptsx, cfg.H, cfg.W, cfg.stride, cfg.pad)
+        assert_close(dx[ptsx[:, 0], ptsx[:, 1], ptsx[:, 2], ptsx[:, 3]], ref, f"{cfg.name} dx samples", rtol=BF_RTOL)
+    pairs = _pts(cfg.seed + 300, npairs, (cfg.Cout, cfg.Cin))
+    dwr = orc.rotconv_pool_bwd_weight_at(x, g, idx, pairs, cfg.R, cfg.k, cfg.G, cfg.stride, cfg.pad)
+    got_dw, ref_dw = [], []
+    for t, (co, ci) in enumerate(pairs):
+        full = np.zeros((cfg.R, 1, 1, cfg.k, cfg.k))
+        full[:, 0, 0] = dwr[t]
+        ref_dw.append(orc.reduce_bank_grad(full, ang, cfg.mode)[:, 0, 0])
+        got_dw.append(dw[:, co, ci])
+    assert_close(np.array(got_dw), np.array(ref_dw), f"{cfg.name} dw samples (fp32)", rtol=RTOL)
+    # homogeneity through the max: <w, dW> = <x, dX> = <ypool, g>; ypool and dX carry one bf16 rounding each
+    a, b, c = float((yp * g).sum()), float((x * dx).sum()), float((w * dw).sum())
+    scale = float(np.abs(yp * g).sum())
+    assert abs(a - b) <= 1e-4 * scale and abs(a - c) <= 1e-4 * scale, (a, b, c, scale)
