@@ -67,6 +67,7 @@ typedef enum {
 typedef enum { ROTCONV_F32 = 0, ROTCONV_BF16 = 1 } rotconv_dtype;
 typedef enum { ROTCONV_EXACT90 = 0, ROTCONV_STEERABLE = 1, ROTCONV_BILINEAR = 2, ROTCONV_P4M = 3 } rotconv_mode;
 typedef enum { ROTCONV_POOL_MAX = 0, ROTCONV_POOL_AVG = 1 } rotconv_pool_op;
+typedef enum { ROTCONV_ACT_NONE = 0, ROTCONV_ACT_RELU = 1 } rotconv_activation;
 
 /* Problem statement of Sec. III (input C_in x H x W, filters C_out x C_in x K x K),
  * with a batch dimension, an orientation set, stride and zero padding. */
@@ -104,6 +105,13 @@ typedef struct {
                                ROTCONV_POOL_AVG: ypool = mean over the pool group (Eq. 9),
                                every member receives gpool / G (Eq. 11); `idx` arguments are
                                ignored and may be NULL.  fp32 plans only. */
+  int32_t activation;       /* rotconv_activation, applied by rotconv_pool_fwd only (max-pooling plans).
+                               ROTCONV_ACT_RELU: ypool = max(pooled value, 0), and idx = 255 (no
+                               orientation) wherever the pooled value is not positive.  Because an idx
+                               outside its pool group routes nothing (Eq. 12), rotconv_pool_bwd_data and
+                               rotconv_pool_bwd_weight fed that idx and the gradient of the ReLU OUTPUT
+                               return the gradients through ReLU, pooling and convolution: the block
+                               "rotation convolution + ReLU" of Sec. V-A without a pass of its own. */
 } rotconv_desc;
 
 typedef struct rotconv_plan rotconv_plan; /* opaque */

@@ -424,6 +424,7 @@ void orc_rotconv_pool_bwd_weight_at(const double* x, const double* gpool, const 
           for (int ox = 0; ox < Wo; ++ox) {
             const size_t q = ((((size_t)n * Cout + co) * ng + g) * Ho + oy) * Wo + ox;
             const int r = idx[q];
+            if (r >= R || r % ng != g) continue;   /* Eq. 12: an index that names no member of the group routes nothing */
             const double d = gpool[q];
             for (int i = 0; i < k; ++i) {
               const int h = oy * stride + i - pad;

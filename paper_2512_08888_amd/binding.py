@@ -46,6 +46,7 @@ class Desc(ctypes.Structure):
         ("angles_deg", ctypes.POINTER(ctypes.c_double)),
         ("mode", ctypes.c_int32), ("stride", ctypes.c_int32), ("pad", ctypes.c_int32),
         ("pool_group", ctypes.c_int32), ("dtype", ctypes.c_int32), ("pool_op", ctypes.c_int32),
+        ("activation", ctypes.c_int32),
     ]
 
 
@@ -142,7 +143,7 @@ class Plan:
     """Owns a rotconv_plan*.  Mirrors rotconv_plan_create / destroy and the host-side queries."""
 
     def __init__(self, N, Cin, H, W, Cout, k=3, R=4, angles_deg: Optional[Sequence[float]] = None, mode="exact90",
-                 stride=1, pad=1, pool_group=0, dtype=F32, pool_op="max"):
+                 stride=1, pad=1, pool_group=0, dtype=F32, pool_op="max", relu=False):
         self._h = ctypes.c_void_p()
         self._angles = None
         ang = None
@@ -151,7 +152,7 @@ class Plan:
             ang = ctypes.cast(self._angles, ctypes.POINTER(ctypes.c_double))
         m = MODES[mode] if isinstance(mode, str) else int(mode)
         po = POOL_OPS[pool_op] if isinstance(pool_op, str) else int(pool_op)
-        self.desc = Desc(N, Cin, H, W, Cout, k, R, ang, m, stride, pad, pool_group or 0, dtype, po)
+        self.desc = Desc(N, Cin, H, W, Cout, k, R, ang, m, stride, pad, pool_group or 0, dtype, po, 1 if relu else 0)
         _check(lib().rotconv_plan_create(ctypes.byref(self.desc), ctypes.byref(self._h)), "rotconv_plan_create")
         ho, wo, cu, cp = (ctypes.c_int32() for _ in range(4))
         lib().rotconv_out_shape(self._h, ctypes.byref(ho), ctypes.byref(wo), ctypes.byref(cu), ctypes.byref(cp))

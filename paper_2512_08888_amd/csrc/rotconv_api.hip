@@ -297,7 +297,7 @@ static int f32_rotconv_pool_fwd(const rotconv_plan* plan, const void* x, const v
     } else {
       float* yu = reinterpret_cast<float*>(extra);
       launch_p4_fwd(p, mode, static_cast<const float*>(x), wt, yu, nullptr, st);
-      launch_maxpool_fwd(p, yu, static_cast<float*>(ypool), idx, st);
+      launch_maxpool_fwd(p, yu, static_cast<float*>(ypool), idx, st, true);
     }
     return finish();
   }

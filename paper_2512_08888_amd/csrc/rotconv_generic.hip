@@ -15,6 +15,7 @@ Geom make_geom(const rotconv_plan* p) {
   g.N = p->d.N; g.Cin = p->d.Cin; g.H = p->d.H; g.W = p->d.W; g.Cout = p->d.Cout; g.k = p->d.k; g.kk = p->kk;
   g.R = p->d.R; g.stride = p->d.stride; g.pad = p->d.pad; g.Ho = p->Ho; g.Wo = p->Wo; g.G = p->G; g.ng = p->ng;
   g.B = p->B; g.Q = p->host.Q;
+  g.relu = 0;
   return g;
 }
 
@@ -101,8 +102,9 @@ __global__ __launch_bounds__(256) void k_fwd_generic(const float* __restrict__ x
   }
   if (FUSED && live) {
     const size_t q = ((size_t)n * g.Cout * g.ng + chan) * P + p;
-    yout[q] = best;
-    idx[q] = (uint8_t)best_r;
+    const bool dead = g.relu && !(best > 0.f);        // fused ReLU: nothing flows back through this element
+    yout[q] = dead ? 0.f : best;
+    idx[q] = dead ? (uint8_t)255 : (uint8_t)best_r;
   }
 }
 
@@ -130,8 +132,9 @@ __global__ __launch_bounds__(256) void k_maxpool_fwd(const T* __restrict__ y, T*
     if (v > best) { best = v; best_raw = raw; best_r = r; }
   }
   const size_t q = ((size_t)n * g.Cout * g.ng + chan) * P + p;
-  ypool[q] = best_raw;
-  idx[q] = (uint8_t)best_r;
+  const bool dead = g.relu && !(best > 0.f);
+  ypool[q] = dead ? T(0) : best_raw;
+  idx[q] = dead ? (uint8_t)255 : (uint8_t)best_r;
 }
 
 // Eq. 12.
@@ -364,13 +367,15 @@ void launch_fwd_generic(const rotconv_plan* p, const float* x, const float* wexp
 
 void launch_pool_fwd_generic(const rotconv_plan* p, const float* x, const float* wexp, float* ypool, uint8_t* idx,
                              hipStream_t st) {
-  const Geom g = make_geom(p);
+  Geom g = make_geom(p);
+  g.relu = p->d.activation == ROTCONV_ACT_RELU;
   dim3 grid((g.Ho * g.Wo + 255) / 256, g.Cout * g.ng, g.N);
   hipLaunchKernelGGL(k_fwd_generic<true>, grid, dim3(256), 0, st, x, wexp, ypool, idx, g);
 }
 
-void launch_maxpool_fwd(const rotconv_plan* p, const float* y, float* ypool, uint8_t* idx, hipStream_t st) {
-  const Geom g = make_geom(p);
+void launch_maxpool_fwd(const rotconv_plan* p, const float* y, float* ypool, uint8_t* idx, hipStream_t st, bool relu) {
+  Geom g = make_geom(p);
+  g.relu = relu && p->d.activation == ROTCONV_ACT_RELU;
   dim3 grid((g.Ho * g.Wo + 255) / 256, g.Cout * g.ng, g.N);
   hipLaunchKernelGGL(k_maxpool_fwd<float>, grid, dim3(256), 0, st, y, ypool, idx, g);
 }

@@ -111,6 +111,8 @@ int validate_and_build(const rotconv_desc* desc, rotconv_plan** out) {
   if (d.dtype != ROTCONV_F32 && d.dtype != ROTCONV_BF16) return ROTCONV_ERR_UNSUPPORTED;
   if (d.pool_op != ROTCONV_POOL_MAX && d.pool_op != ROTCONV_POOL_AVG) return ROTCONV_ERR_UNSUPPORTED;
   if (d.pool_op == ROTCONV_POOL_AVG && d.dtype != ROTCONV_F32) return ROTCONV_ERR_UNSUPPORTED;
+  if (d.activation != ROTCONV_ACT_NONE && d.activation != ROTCONV_ACT_RELU) return ROTCONV_ERR_UNSUPPORTED;
+  if (d.activation == ROTCONV_ACT_RELU && d.pool_op != ROTCONV_POOL_MAX) return ROTCONV_ERR_UNSUPPORTED;
   if (d.k > 15) return ROTCONV_ERR_UNSUPPORTED;
   const int Ho = (d.H + 2 * d.pad - d.k) / d.stride + 1, Wo = (d.W + 2 * d.pad - d.k) / d.stride + 1;
   const int kk = d.k * d.k, B = d.mode == ROTCONV_STEERABLE ? 2 : 1;

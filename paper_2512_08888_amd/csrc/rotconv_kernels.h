@@ -11,6 +11,7 @@ namespace rotconv {
 // Geometry handed to kernels by value.
 struct Geom {
   int N, Cin, H, W, Cout, k, kk, R, stride, pad, Ho, Wo, G, ng, B, Q;
+  int relu;   // fused pooled forward only: clamp the pooled value at 0 and store idx 255 where it is not positive
 };
 
 Geom make_geom(const rotconv_plan* p);
@@ -29,7 +30,10 @@ void launch_pool_bwd_data_generic(const rotconv_plan* p, const float* gpool, con
 // partial sums [splits][R][Cout][Cin][kk] into `partial`, then the transposed expansion into dw
 void launch_bwd_weight_generic(const rotconv_plan* p, const float* x, const float* dy, const float* gpool,
                                const uint8_t* idx, float* partial, float* dw, hipStream_t st);
-void launch_maxpool_fwd(const rotconv_plan* p, const float* y, float* ypool, uint8_t* idx, hipStream_t st);
+// relu: apply the plan's fused activation (the fused forward's fallback through a materialised y); the public
+// orient_maxpool_fwd never does
+void launch_maxpool_fwd(const rotconv_plan* p, const float* y, float* ypool, uint8_t* idx, hipStream_t st,
+                        bool relu = false);
 void launch_maxpool_bwd(const rotconv_plan* p, const float* gpool, const uint8_t* idx, float* dy, hipStream_t st);
 // average pooling (Eq. 9 / Eq. 11) and the pieces of its fused path
 void launch_avgpool_fwd(const rotconv_plan* p, const float* y, float* ypool, hipStream_t st);

@@ -18,6 +18,7 @@ struct P4Geom {
   int out_mode;  // kOut*
   int nseg;      // row segments handled by this launch (1 unless W > 256)
   int inside;    // 1 if no segment's wave chain reaches beyond the row
+  int relu;      // pooled output: clamp at 0, idx 255 where the pooled value is not positive
   int nq;        // bf16 forward: banks folded into a wave's 16 filter columns (0 / 1: none)
   int seg_xorg[4];  // first product column of a segment's wave chain
   int seg_lo[4], seg_hi[4];  // output pixels [lo, hi) the segment stores (multiples of 8, or W)
@@ -32,7 +33,7 @@ void launch_p4_pack_fwd(const rotconv_plan* p, const float* w, float* wt, hipStr
 void launch_p4_fwd(const rotconv_plan* p, int out_mode, const float* x, const float* wt, float* out_val,
                    uint8_t* out_idx, hipStream_t st);
 void launch_p4_combine(const rotconv_plan* p, const float* pv, const uint8_t* pi, float* ypool, uint8_t* idx,
-                       hipStream_t st);
+                       hipStream_t st);   // applies the plan's fused activation
 
 // forward on bfloat16 tensors (bf16 matrix cores, fp32 accumulation); out_val is bf16 for the pooled and
 // unpooled modes and fp32 for the per-bank candidates

@@ -330,6 +330,14 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restri
         pk[j >> 2] |= (uint32_t)bi << (8 * (j & 3));
       }
     }
+    if (!UNPOOLED && g.relu) {      // fused ReLU (pooled output only): dead elements get idx 255
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const bool dead = !(best[j] > 0.f);
+        best[j] = dead ? 0.f : best[j];
+        pk[j >> 2] |= dead ? 0xffu << (8 * (j & 3)) : 0u;
+      }
+    }
     if (!UNPOOLED && fin && !first) {
       size_t chan;
       if (g.out_mode == kOutPooled) {
@@ -360,7 +368,8 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restri
 // Candidates [Q][N][Cout][HW]; group g of filter co collects banks q with (r mod ng) == g.
 __global__ __launch_bounds__(256) void k_p4_combine(const float* __restrict__ pv, const uint8_t* __restrict__ pi,
                                                     const int32_t* __restrict__ rot_of, float* __restrict__ ypool,
-                                                    uint8_t* __restrict__ idx, int N, int Cout, int HW, int Q, int ng) {
+                                                    uint8_t* __restrict__ idx, int N, int Cout, int HW, int Q, int ng,
+                                                    int relu) {
   const int p = blockIdx.x * 256 + threadIdx.x;
   if (p >= HW) return;
   const int chan = blockIdx.y, n = blockIdx.z;  // chan = co*ng + grp
@@ -378,8 +387,9 @@ __global__ __launch_bounds__(256) void k_p4_combine(const float* __restrict__ pv
     if (bi == 255 || vq > best || (vq == best && iq < bi)) { best = vq; bi = iq; }
   }
   const size_t o = ((size_t)n * Cout * ng + chan) * HW + p;
-  ypool[o] = best;
-  idx[o] = (uint8_t)bi;
+  const bool dead = relu && !(best > 0.f);
+  ypool[o] = dead ? 0.f : best;
+  idx[o] = dead ? (uint8_t)255 : (uint8_t)bi;
 }
 
 // base bank(s) -> Q first-quadrant banks in the LDS image layout [Q][CB][CinPad][9][16]
@@ -463,6 +473,7 @@ int p4_fwd_geoms(const rotconv_plan* p, int out_mode, P4Geom* out, int max_out) 
   base.N = d.N; base.Cin = d.Cin; base.CinPad = (d.Cin + 31) / 32 * 32; base.H = d.H; base.W = d.W;
   base.Cout = d.Cout; base.CB = (d.Cout + 15) / 16; base.R = d.R; base.Q = p->host.Q; base.ng = p->ng;
   base.out_mode = out_mode;
+  base.relu = out_mode == kOutPooled && d.activation == ROTCONV_ACT_RELU;
   int ng = 0;
   int pos = 0;
   while (pos < d.W) {
@@ -565,7 +576,7 @@ void launch_p4_combine(const rotconv_plan* p, const float* pv, const uint8_t* pi
   const int HW = p->d.H * p->d.W;
   dim3 grid((HW + 255) / 256, p->d.Cout * p->ng, p->d.N);
   hipLaunchKernelGGL(k_p4_combine, grid, dim3(256), 0, st, pv, pi, p->dev.rot_of, ypool, idx, p->d.N, p->d.Cout, HW,
-                     p->host.Q, p->ng);
+                     p->host.Q, p->ng, p->d.activation == ROTCONV_ACT_RELU ? 1 : 0);
 }
 
 }  // namespace rotconv

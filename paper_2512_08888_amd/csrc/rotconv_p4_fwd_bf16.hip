@@ -366,6 +366,14 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd_bf16(const uint16_t* 
         pk[j >> 2] |= (uint32_t)bi << (8 * (j & 3));
       }
     }
+    if (!UNPOOLED && g.relu) {      // fused ReLU (pooled output only): dead elements get idx 255
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const bool dead = !(best[j] > 0.f);
+        best[j] = dead ? 0.f : best[j];
+        pk[j >> 2] |= dead ? 0xffu << (8 * (j & 3)) : 0u;
+      }
+    }
     if (!UNPOOLED && fin && !none) {
       if (g.out_mode == kOutPooled) {
         // every rotation of this bank lies in pool group (r mod ng); pooled channel = co*ng + group
@@ -406,7 +414,7 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd_bf16(const uint16_t* 
 __global__ __launch_bounds__(256) void k_p4_combine_bf16(const float* __restrict__ pv, const uint8_t* __restrict__ pi,
                                                          const int32_t* __restrict__ rot_of,
                                                          uint16_t* __restrict__ ypool, uint8_t* __restrict__ idx, int N,
-                                                         int Cout, int HW, int Q, int ng) {
+                                                         int Cout, int HW, int Q, int ng, int relu) {
   const int p = blockIdx.x * 256 + threadIdx.x;
   if (p >= HW) return;
   const int chan = blockIdx.y, n = blockIdx.z;  // chan = co*ng + grp
@@ -424,8 +432,9 @@ __global__ __launch_bounds__(256) void k_p4_combine_bf16(const float* __restrict
     if (bi == 255 || vq > best || (vq == best && iq < bi)) { best = vq; bi = iq; }
   }
   const size_t o = ((size_t)n * Cout * ng + chan) * HW + p;
-  ypool[o] = f32_to_bf16(best);
-  idx[o] = (uint8_t)bi;
+  const bool dead = relu && !(best > 0.f);
+  ypool[o] = dead ? (uint16_t)0 : f32_to_bf16(best);
+  idx[o] = dead ? (uint8_t)255 : (uint8_t)bi;
 }
 
 // bf16 base bank(s) -> Q first-quadrant banks (Sec. III-D / Eq. 17 combination in fp32, rounded to bf16
@@ -580,7 +589,7 @@ void launch_p4_combine_bf16(const rotconv_plan* p, const float* pv, const uint8_
   const int HW = p->d.H * p->d.W;
   dim3 grid((HW + 255) / 256, p->d.Cout * p->ng, p->d.N);
   hipLaunchKernelGGL(k_p4_combine_bf16, grid, dim3(256), 0, st, pv, pi, p->dev.rot_of, ypool, idx, p->d.N, p->d.Cout,
-                     HW, p->host.Q, p->ng);
+                     HW, p->host.Q, p->ng, p->d.activation == ROTCONV_ACT_RELU ? 1 : 0);
 }
 
 }  // namespace rotconv

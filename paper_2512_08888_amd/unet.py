@@ -128,10 +128,13 @@ class UNet:
     """Device state of the stack: plans, parameters, activations, gradients, one shared workspace."""
 
     def __init__(self, cfg: UNetConfig, params: Optional[Dict[str, np.ndarray]] = None, device="cuda",
-                 dtype: str = "f32"):
+                 dtype: str = "f32", fuse_relu: bool = True):
         """dtype "f32": everything fp32.  "bf16": images, parameters, activations and activation gradients
         are stored as bfloat16 (parameters rounded once when loaded), every call accumulates in fp32, and the
-        parameter gradients and the loss are fp32."""
+        parameter gradients and the loss are fp32.
+        fuse_relu: the ReLU after every rotation convolution is the plan's fused activation (the forward writes
+        max(pooled, 0) and marks dead elements in idx, so the gradient calls need no ReLU pass); False runs the
+        separate glue_relu_fwd / glue_relu_bwd calls instead (same values)."""
         import torch
 
         if not torch.cuda.is_available():
@@ -141,6 +144,7 @@ class UNet:
         if dtype not in ("f32", "bf16"):
             raise ValueError("dtype must be 'f32' or 'bf16'")
         self.dtype = dtype
+        self.fuse_relu = bool(fuse_relu)
         f32, u8 = torch.float32, torch.uint8
         adt = torch.bfloat16 if dtype == "bf16" else f32      # storage type of activations and parameters
         self.adt = adt
@@ -159,7 +163,8 @@ class UNet:
         for sp in self.specs:
             name, h, w = sp["name"], sp["H"], sp["W"]
             p = rc.Plan(N, sp["Cin"], h, w, sp["Cout"], k=3, R=sp["R"], mode=sp["mode"], stride=1, pad=1,
-                        pool_group=sp["pool_group"] or 0, dtype=rc.BF16 if dtype == "bf16" else rc.F32)
+                        pool_group=sp["pool_group"] or 0, dtype=rc.BF16 if dtype == "bf16" else rc.F32,
+                        relu=self.fuse_relu)
             self.plans[name] = p
             ws_bytes = max(ws_bytes, p.workspace_bytes)
             self.act[name] = dict(y=buf(N, p.Cpooled, h, w), idx=buf(N, p.Cpooled, h, w, dtype=u8),
@@ -233,14 +238,16 @@ class UNet:
         a["x"] = x
         self._c("rotconv_pool_fwd", rc.rotconv_pool_fwd, self.plans[name], x, self.params[name], a["y"], a["idx"],
                 self.ws)
-        self._c("glue_relu_fwd", rc.glue_relu_fwd, a["y"], a["y"])
+        if not self.fuse_relu:
+            self._c("glue_relu_fwd", rc.glue_relu_fwd, a["y"], a["y"])
         return a["y"]
 
     def _rot_bwd(self, name, need_dx=True):
         """a['g'] holds dL/d(ReLU output); returns nothing: dL/dx lands in the producer's 'g' slot."""
         self._where = name
         a = self.act[name]
-        self._c("glue_relu_bwd", rc.glue_relu_bwd, a["y"], a["g"], a["g"])
+        if not self.fuse_relu:      # fused: idx = 255 at dead elements already keeps their gradient out
+            self._c("glue_relu_bwd", rc.glue_relu_bwd, a["y"], a["g"], a["g"])
         self._c("rotconv_pool_bwd_weight", rc.rotconv_pool_bwd_weight, self.plans[name], a["x"], a["g"], a["idx"],
                 self.grads[name], self.ws)
         if need_dx:

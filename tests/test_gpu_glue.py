@@ -255,13 +255,13 @@ def _bf16_round(a):
     return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(torch.bfloat16).to(torch.float32).numpy()
 
 
-def _run_stack(cfg, dtype="f32"):
+def _run_stack(cfg, dtype="f32", fuse_relu=False):
     params = un.make_params(cfg)
     images, labels = un.make_batch(cfg)
     if dtype == "bf16":     # the values the GPU holds after its one rounding
         params = {k: _bf16_round(v) for k, v in params.items()}
         images = _bf16_round(images)
-    net = un.UNet(cfg, params, dtype=dtype)
+    net = un.UNet(cfg, params, dtype=dtype, fuse_relu=fuse_relu)
     net.load_batch(images, labels)
     for t in list(net.grads.values()) + [net.loss]:
         t.fill_(float("nan"))
@@ -371,6 +371,24 @@ def test_unet_step_end_to_end_loss_and_gradients(cfg):
     assert flips <= 1e-3 * total, (flips, total)
 
 
+@pytest.mark.parametrize("cfg,dtype", [(SMALL[0], "f32"), (SMALL[2], "f32"), (SMALL[5], "f32"), (SMALL[2], "bf16")],
+                         ids=lambda v: v if isinstance(v, str) else v.name)
+def test_unet_step_fused_relu_equals_separate_relu(cfg, dtype):
+    """The plan's fused ReLU (forward clamps the pooled value and stores idx 255 at dead elements, the gradient calls
+    then skip them) against the separate ReLU passes checked call by call above: same activations, same loss, same
+    parameter gradients (a dead element contributes an exact zero either way)."""
+    a, *_ = _run_stack(cfg, dtype, fuse_relu=False)
+    b, *_ = _run_stack(cfg, dtype, fuse_relu=True)
+    assert float(a.loss.cpu()[0]) == float(b.loss.cpu()[0])
+    for n, *_ in a.layers:
+        ya, yb = a.act[n]["y"].float().cpu().numpy(), b.act[n]["y"].float().cpu().numpy()
+        assert np.array_equal(ya, yb), n
+        ia, ib = a.act[n]["idx"].cpu().numpy(), b.act[n]["idx"].cpu().numpy()
+        assert np.array_equal(ib, np.where(yb > 0, ia, 255)), n
+    for k in a.grads:
+        assert np.array_equal(a.grads[k].cpu().numpy(), b.grads[k].cpu().numpy()), k
+
+
 def test_unet_step_is_deterministic():
     cfg = SMALL[1]
     net, *_ = _run_stack(cfg)
@@ -405,7 +423,7 @@ def test_unet_full_size_sampled(cfg, dtype):
     layer at full size.  bf16: the oracle reads the bf16 values the GPU holds (rotated banks rounded to bf16),
     bf16 outputs are held to the bf16 bar, fp32 weight gradients and the loss to the fp32 bar."""
     from parity_util import round_bf16
-    net, params, images, labels = _run_stack(cfg, dtype)
+    net, params, images, labels = _run_stack(cfg, dtype, fuse_relu=True)     # as bench.py runs it
     A = net.act
     bf = dtype == "bf16"
     AT = BF_RTOL if bf else RTOL                    # bar of activation-typed outputs
@@ -434,8 +452,12 @@ def test_unet_full_size_sampled(cfg, dtype):
             got_i = idx[pts[:, 0], chan, pts[:, 2], pts[:, 3]].astype(np.int64)
             assert np.all(np.abs(got_v - np.maximum(best, 0)) <= AT * np.abs(best) + AT * rms), f"{name} fwd samples"
             tau = 64.0 * np.finfo(np.float32).eps * ya[:, members].max(axis=1)
-            assert np.all(got_i % ng == grp) and np.all(got_i < R), f"{name} arg-max group"
-            assert np.all(yr[np.arange(ns), got_i] >= best - tau), f"{name} arg-max samples"
+            # fused ReLU: a dead element (pooled value not positive) carries idx 255; alive ones the arg-max
+            dead = got_i == 255
+            assert np.all(got_v[dead] == 0) and np.all(best[dead] <= tau[dead]), f"{name} dead elements"
+            gi = np.where(dead, grp, got_i)
+            assert np.all(gi % ng == grp) and np.all(gi < R), f"{name} arg-max group"
+            assert np.all((yr[np.arange(ns), gi] >= best - tau) | dead), f"{name} arg-max samples"
         # weight gradient: sampled (co, ci) slices, reduced through Eq. 16 by the oracle
         pairs = _pts(2000 + li, npairs, (co, ci))
         dwr = orc.rotconv_pool_bwd_weight_at(x, g, idx, pairs, R, 3, G, 1, 1)
@@ -461,10 +483,7 @@ def test_unet_full_size_sampled(cfg, dtype):
             ptx = _pts(3000 + li, ns, (1, ci, h, w))
             ref = orc.rotconv_bwd_data_at(dy, w_rot, ptx, h, w, 1, 1)
             got = H(a["gx"])[n0][ptx[:, 1], ptx[:, 2], ptx[:, 3]].astype(np.float64)
-            if name.endswith("b"):
-                keep = H(A[name[:-1] + "a"]["y"])[n0][ptx[:, 1], ptx[:, 2], ptx[:, 3]] > 0
-                ref = np.where(keep, ref, 0.0)
-            act_close(got, ref, f"{name} dX samples")
+            act_close(got, ref, f"{name} dX samples")     # (fused ReLU: the slot is not masked in place afterwards)
             del dy
         _say(f"  {cfg.name} {name}: {ci}->{co} @{h}x{w} ok")
     # glue at full size

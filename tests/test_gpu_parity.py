@@ -302,3 +302,41 @@ def test_unfused_forward_deep_input(dtype):
     ref = orc.rotconv_fwd(x, orc.expand_bank(w, cfg.R, None, cfg.mode), cfg.stride, cfg.pad)
     pu.assert_close(y.to(torch.float64).cpu().numpy().reshape(ref.shape), ref, f"deep unfused y {dtype}",
                     rtol=1e-2 if dtype == "bf16" else pu.RTOL)
+
+
+RELU_CASES = [TINY[0], TINY[10], TINY[13], TINY[18],
+              LC("r_fast", N=2, Cin=20, H=12, W=32, Cout=18, R=4, x_dist="normal", seed=48),
+              LC("r_r16", N=1, Cin=24, H=10, W=64, Cout=12, R=16, mode="bilinear", x_dist="normal", seed=49)]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("cfg", RELU_CASES, ids=lambda c: c.name)
+def test_fused_relu_marks_dead_elements(cfg, dtype):
+    """Plans with the fused ReLU: the pooled forward equals max(unfused result, 0) with idx 255 exactly where that
+    result is not positive, and the two gradient calls fed that idx equal the gradient calls of the plain plan fed
+    the ReLU-masked upstream gradient (every kernel family: generic, fp32 MFMA, bf16 MFMA, per-bank candidates)."""
+    say(f"[case] fused ReLU {cfg.name} {dtype}")
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    dt = rc.BF16 if dtype == "bf16" else rc.F32
+    plain, fused = rc.Plan.from_config(cfg, dtype=dt), rc.Plan.from_config(cfg, dtype=dt, relu=True)
+    x, w, g = (pu.dev(a, tdt) for a in (synth.make_x(cfg), synth.make_w(cfg), synth.make_g(cfg)))
+    P = (cfg.N, plain.Cpooled, plain.Ho, plain.Wo)
+    mk = lambda: (torch.full(P, float("nan"), dtype=tdt, device="cuda"), torch.full(P, 77, dtype=torch.uint8, device="cuda"))
+    (y0, i0), (y1, i1) = mk(), mk()
+    rc.rotconv_pool_fwd(plain, x, w, y0, i0)
+    rc.rotconv_pool_fwd(fused, x, w, y1, i1)
+    torch.cuda.synchronize()
+    alive = y0 > 0
+    assert 0.02 < float(alive.float().mean()) < 0.98        # the case exercises both branches
+    assert torch.equal(y1, torch.where(alive, y0, torch.zeros_like(y0)))
+    assert torch.equal(i1, torch.where(alive, i0, torch.full_like(i0, 255)))
+    gm = torch.where(alive, g, torch.zeros_like(g))
+    dx0, dx1 = torch.full_like(x, float("nan")), torch.full_like(x, float("nan"))
+    rc.rotconv_pool_bwd_data(plain, gm, i0, w, dx0)
+    rc.rotconv_pool_bwd_data(fused, g, i1, w, dx1)
+    dw0 = torch.full(w.shape, float("nan"), device="cuda")
+    dw1 = torch.full(w.shape, float("nan"), device="cuda")
+    rc.rotconv_pool_bwd_weight(plain, x, gm, i0, dw0)
+    rc.rotconv_pool_bwd_weight(fused, x, g, i1, dw1)
+    torch.cuda.synchronize()
+    assert torch.equal(dx0, dx1) and torch.equal(dw0, dw1)
