@@ -61,9 +61,16 @@ size_t align256(size_t v) { return (v + 255) / 256 * 256; }
 
 bool aligned(const void* p, size_t a) { return reinterpret_cast<uintptr_t>(p) % a == 0; }
 
+// Bytes reserved for the packed banks of the fast forward (the larger of the fp32 and, for bf16 plans, the bf16 image).
+size_t fwd_pack_region(const rotconv_plan* p) {
+  size_t b = p4_fwd_pack_floats(p) * sizeof(float);
+  if (p->d.dtype == ROTCONV_BF16) b = std::max(b, p4_fwd_bf16_pack_bytes(p));
+  return align256(b);
+}
+
 // Scratch of the fast forward: packed banks, then per-bank candidates or the unpooled map.
 size_t fwd_fast_ws_bytes(const rotconv_plan* p) {
-  const size_t pack = align256(p4_fwd_pack_floats(p) * sizeof(float));
+  const size_t pack = fwd_pack_region(p);
   const size_t hw = (size_t)p->d.H * p->d.W;
   const int mode = p4_fwd_pool_mode(p);
   size_t extra = 0;
@@ -283,7 +290,7 @@ static int f32_rotconv_pool_fwd(const rotconv_plan* plan, const void* x, const v
   }
   if (p->fast[0] && aligned(x, 8) && aligned(ws, 256) && aligned(ypool, 16) && aligned(idx, 8)) {
     float* wt = static_cast<float*>(ws);
-    char* extra = static_cast<char*>(ws) + align256(p4_fwd_pack_floats(p) * sizeof(float));
+    char* extra = static_cast<char*>(ws) + fwd_pack_region(p);
     const int mode = p4_fwd_pool_mode(p);
     const size_t hw = (size_t)p->d.H * p->d.W;
     launch_p4_pack_fwd(p, static_cast<const float*>(w), wt, st);
@@ -478,7 +485,7 @@ int rotconv_pool_fwd(const rotconv_plan* plan, const void* x, const void* w, voi
     const int rc = ensure_device_tables(p);
     if (rc) return rc;
     uint16_t* wt = static_cast<uint16_t*>(ws);
-    char* extra = static_cast<char*>(ws) + align256(p4_fwd_pack_floats(p) * sizeof(float));
+    char* extra = static_cast<char*>(ws) + fwd_pack_region(p);
     const size_t hw = (size_t)p->d.H * p->d.W;
     const int nq = pmode == kOutPartial ? p4_fwd_bf16_fold(p) : 1;
     launch_p4_pack_fwd_bf16(p, nq, h16(w), wt, st);

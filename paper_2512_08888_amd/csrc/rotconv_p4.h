@@ -84,7 +84,8 @@ void launch_p4_bwd_data_bf16(const rotconv_plan* p, const uint16_t* gpool, const
 // weight gradient
 struct P4BwdWGeom {
   int N, Cin, CinPad, H, W, Cout, CoutPad, Q, ng;
-  int ncig;    // groups of 64 input channels
+  int ncb;     // 16-channel blocks per wave: 4, or 1 for at most 16 input channels
+  int ncig;    // groups of 16 * ncb input channels
   int ncog;    // groups of four (bank, 16-filter block) pairs (one workgroup of 4 waves)
   int nstrip;    // 32-pixel strips per row
   int rows_per;  // rows per range

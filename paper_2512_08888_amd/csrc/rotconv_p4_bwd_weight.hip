@@ -28,7 +28,8 @@ namespace {
 
 typedef float f4 __attribute__((ext_vector_type(4)));
 
-constexpr int NCB = 4;         // 16-channel blocks per wave (64 input channels)
+// NCB (template parameter of both kernels): 16-channel blocks per wave: 4 (64 input channels), or 1 for layers
+// with at most 16 input channels (a network's first layer), which would otherwise multiply 48+ padded channels
 constexpr int NWAVE = 4;       // waves per workgroup = 16-filter blocks per workgroup
 constexpr int NT = 64 * NWAVE;
 
@@ -46,6 +47,7 @@ struct RowW {            // (G, idx) of one filter on one image row as loaded: t
   uint32_t il, ir;       // idx of the neighbours
 };
 
+template <int NCB>
 __global__ __launch_bounds__(NT) void k_p4_bwd_weight(const float* __restrict__ x, const float* __restrict__ gpool,
                                                       const uint8_t* __restrict__ idx,
                                                       const int32_t* __restrict__ rot_of,
@@ -271,6 +273,7 @@ struct RowB {            // (G, idx) of one filter on one image row as loaded
   uint8_t il, ir;        // idx of the neighbours
 };
 
+template <int NCB>
 __global__ __launch_bounds__(NT) void k_p4_bwd_weight_bf16(const uint16_t* __restrict__ x,
                                                            const uint16_t* __restrict__ gpool,
                                                            const uint8_t* __restrict__ idx,
@@ -496,6 +499,8 @@ P4BwdWGeom p4_bwd_weight_geom(const rotconv_plan* p) {
   const rotconv_desc& d = p->d;
   P4BwdWGeom g{};
   g.N = d.N; g.Cin = d.Cin; g.H = d.H; g.W = d.W; g.Cout = d.Cout; g.Q = p->host.Q; g.ng = p->ng;
+  g.ncb = d.Cin <= 16 ? 1 : 4;
+  const int NCB = g.ncb;
   g.CinPad = (d.Cin + 16 * NCB - 1) / (16 * NCB) * (16 * NCB);
   g.CoutPad = (d.Cout + 15) / 16 * 16;
   g.ncig = g.CinPad / (16 * NCB);
@@ -526,7 +531,8 @@ void launch_p4_bwd_weight(const rotconv_plan* p, const float* x, const float* gp
                           float* partial, float* dw, hipStream_t st) {
   const P4BwdWGeom g = p4_bwd_weight_geom(p);
   const int grid = g.splits * g.ncig * g.ncog;
-  hipLaunchKernelGGL(k_p4_bwd_weight, dim3(grid), dim3(NT), 0, st, x, gpool, idx, p->dev.rot_of, partial, g);
+  if (g.ncb == 1) hipLaunchKernelGGL(k_p4_bwd_weight<1>, dim3(grid), dim3(NT), 0, st, x, gpool, idx, p->dev.rot_of, partial, g);
+  else hipLaunchKernelGGL(k_p4_bwd_weight<4>, dim3(grid), dim3(NT), 0, st, x, gpool, idx, p->dev.rot_of, partial, g);
   const int n_elem = g.Q * 9 * g.CoutPad * g.CinPad;
   float* dF = partial + (size_t)g.splits * n_elem;
   hipLaunchKernelGGL(k_p4_sum_splits, dim3((n_elem + 31) / 32), dim3(256), 0, st, partial, dF, n_elem, g.splits);
@@ -539,7 +545,8 @@ void launch_p4_bwd_weight_bf16(const rotconv_plan* p, const uint16_t* x, const u
                                float* partial, float* dw, hipStream_t st) {
   const P4BwdWGeom g = p4_bwd_weight_geom(p);
   const int grid = g.splits * g.ncig * g.ncog;
-  hipLaunchKernelGGL(k_p4_bwd_weight_bf16, dim3(grid), dim3(NT), 0, st, x, gpool, idx, p->dev.rot_of, partial, g);
+  if (g.ncb == 1) hipLaunchKernelGGL(k_p4_bwd_weight_bf16<1>, dim3(grid), dim3(NT), 0, st, x, gpool, idx, p->dev.rot_of, partial, g);
+  else hipLaunchKernelGGL(k_p4_bwd_weight_bf16<4>, dim3(grid), dim3(NT), 0, st, x, gpool, idx, p->dev.rot_of, partial, g);
   const int n_elem = g.Q * 9 * g.CoutPad * g.CinPad;
   float* dF = partial + (size_t)g.splits * n_elem;
   hipLaunchKernelGGL(k_p4_sum_splits, dim3((n_elem + 31) / 32), dim3(256), 0, st, partial, dF, n_elem, g.splits);

@@ -41,12 +41,14 @@ namespace {
 
 typedef float f4 __attribute__((ext_vector_type(4)));
 
-constexpr int KC = 8;  // K-steps (of 4 channels) per prefetch chunk
+// KC (template parameter): K-steps (of 4 channels) per prefetch chunk: 8 (channels padded to 32), or 1 for layers
+// with at most 4 input channels (a network's first layer: channels padded to 4, an eighth of the matrix work)
+int cin_pad_f32(int Cin) { return Cin <= 4 ? 4 : (Cin + 31) / 32 * 32; }
 
 // UNPOOLED: write every orientation (rotconv_fwd); else max + arg-max over the bank's rotations.
 // FASTW:    W % 8 == 0 and no wave chain reaches beyond the row: no load masks, vector stores.
 // STREAM:   the filter block does not fit LDS: stream it in 32-channel chunks.
-template <int NWX, int NWY, bool UNPOOLED, bool FASTW, bool STREAM>
+template <int NWX, int NWY, bool UNPOOLED, bool FASTW, bool STREAM, int KC>
 __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restrict__ x, const float* __restrict__ wt,
                                                            const int32_t* __restrict__ rot_of,
                                                            float* __restrict__ out_val, uint8_t* __restrict__ out_idx,
@@ -419,13 +421,13 @@ __global__ __launch_bounds__(256) void k_p4_pack_fwd(const float* __restrict__ w
   wt[e] = round16 ? bf16_to_f32(f32_to_bf16(acc)) : acc;   // bf16 plans keep the expanded banks in bf16 precision
 }
 
-template <int NWX, int NWY, bool UNPOOLED, bool FASTW, bool STREAM>
+template <int NWX, int NWY, bool UNPOOLED, bool FASTW, bool STREAM, int KC = 8>
 void launch_i(const P4Geom& g, const float* x, const float* wt, const int32_t* rot_of, float* ov, uint8_t* oi,
               hipStream_t st) {
   const size_t wfl = STREAM ? (size_t)2 * KC * 4 * 144 : (size_t)g.CinPad * 144;
   const size_t lds = (wfl + 4 * NWX * NWY * 128) * sizeof(float);
   const int grid = (g.units + 7) / 8 * 8;
-  auto kern = k_p4_fwd<NWX, NWY, UNPOOLED, FASTW, STREAM>;
+  auto kern = k_p4_fwd<NWX, NWY, UNPOOLED, FASTW, STREAM, KC>;
   (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * NWX * NWY), lds, st, x, wt, rot_of, ov, oi, g);
 }
@@ -434,6 +436,13 @@ template <int NWX, int NWY>
 void launch_t(const P4Geom& g, bool fastw, bool stream, const float* x, const float* wt, const int32_t* rot_of,
               float* ov, uint8_t* oi, hipStream_t st) {
   const bool unp = g.out_mode == kOutUnpooled;
+  if (g.CinPad == 4) {      // at most 4 input channels: one K-step per row
+    if (unp && fastw) launch_i<NWX, NWY, true, true, false, 1>(g, x, wt, rot_of, ov, oi, st);
+    else if (unp) launch_i<NWX, NWY, true, false, false, 1>(g, x, wt, rot_of, ov, oi, st);
+    else if (fastw) launch_i<NWX, NWY, false, true, false, 1>(g, x, wt, rot_of, ov, oi, st);
+    else launch_i<NWX, NWY, false, false, false, 1>(g, x, wt, rot_of, ov, oi, st);
+    return;
+  }
   if (unp) {
     if (stream) launch_i<NWX, NWY, true, false, true>(g, x, wt, rot_of, ov, oi, st);   // deep inputs: streamed block
     else if (fastw) launch_i<NWX, NWY, true, true, false>(g, x, wt, rot_of, ov, oi, st);
@@ -450,8 +459,7 @@ void launch_t(const P4Geom& g, bool fastw, bool stream, const float* x, const fl
 
 // Is the filter block of 16 filters too large to stay in LDS next to the edge arrays?
 bool needs_stream(int Cin) {
-  const int CinPad = (Cin + 31) / 32 * 32;
-  return (size_t)CinPad * 576 + 16384 > 160 * 1024;
+  return (size_t)cin_pad_f32(Cin) * 576 + 16384 > 160 * 1024;
 }
 
 }  // namespace
@@ -470,7 +478,7 @@ bool p4_fwd_supported(const rotconv_plan* p) {
 int p4_fwd_geoms(const rotconv_plan* p, int out_mode, P4Geom* out, int max_out) {
   const rotconv_desc& d = p->d;
   P4Geom base{};
-  base.N = d.N; base.Cin = d.Cin; base.CinPad = (d.Cin + 31) / 32 * 32; base.H = d.H; base.W = d.W;
+  base.N = d.N; base.Cin = d.Cin; base.CinPad = cin_pad_f32(d.Cin); base.H = d.H; base.W = d.W;
   base.Cout = d.Cout; base.CB = (d.Cout + 15) / 16; base.R = d.R; base.Q = p->host.Q; base.ng = p->ng;
   base.out_mode = out_mode;
   base.relu = out_mode == kOutPooled && d.activation == ROTCONV_ACT_RELU;
@@ -527,8 +535,7 @@ int p4_fwd_geoms(const rotconv_plan* p, int out_mode, P4Geom* out, int max_out) 
 }
 
 size_t p4_fwd_pack_floats(const rotconv_plan* p) {
-  const int CinPad = (p->d.Cin + 31) / 32 * 32;
-  return (size_t)p->host.Q * ((p->d.Cout + 15) / 16) * CinPad * 144;
+  return (size_t)p->host.Q * ((p->d.Cout + 15) / 16) * cin_pad_f32(p->d.Cin) * 144;
 }
 
 // How the bank kernel delivers its result for this plan's pooling.
@@ -548,7 +555,7 @@ int p4_fwd_pool_mode(const rotconv_plan* p) {
 }
 
 void launch_p4_pack_fwd(const rotconv_plan* p, const float* w, float* wt, hipStream_t st) {
-  const int CinPad = (p->d.Cin + 31) / 32 * 32, CB = (p->d.Cout + 15) / 16;
+  const int CinPad = cin_pad_f32(p->d.Cin), CB = (p->d.Cout + 15) / 16;
   const int total = p->host.Q * CB * CinPad * 144;
   hipLaunchKernelGGL(k_p4_pack_fwd, dim3((total + 255) / 256), dim3(256), 0, st, w, wt, p->dev.fq_src, p->dev.fq_coef,
                      p->host.Q, CB, CinPad, p->d.Cin, p->d.Cout, p->d.dtype == ROTCONV_BF16 ? 1 : 0);
