@@ -293,9 +293,12 @@ static int f32_rotconv_pool_fwd(const rotconv_plan* plan, const void* x, const v
     char* extra = static_cast<char*>(ws) + fwd_pack_region(p);
     const int mode = p4_fwd_pool_mode(p);
     const size_t hw = (size_t)p->d.H * p->d.W;
-    launch_p4_pack_fwd(p, static_cast<const float*>(w), wt, st);
+    const int nq = mode == kOutPartial ? p4_fwd_fold(p) : 1;
+    launch_p4_pack_fwd(p, static_cast<const float*>(w), wt, st, nq);
     if (mode == kOutPooled) {
       launch_p4_fwd(p, mode, static_cast<const float*>(x), wt, static_cast<float*>(ypool), idx, st);
+    } else if (nq > 1) {     // the pool group spans all banks: pooled across them inside the kernel
+      launch_p4_fwd(p, kOutPooled, static_cast<const float*>(x), wt, static_cast<float*>(ypool), idx, st, nq);
     } else if (mode == kOutPartial) {
       float* pv = reinterpret_cast<float*>(extra);
       uint8_t* pi = reinterpret_cast<uint8_t*>(extra + align256((size_t)p->host.Q * p->d.N * p->d.Cout * hw * 4));

@@ -19,7 +19,7 @@ struct P4Geom {
   int nseg;      // row segments handled by this launch (1 unless W > 256)
   int inside;    // 1 if no segment's wave chain reaches beyond the row
   int relu;      // pooled output: clamp at 0, idx 255 where the pooled value is not positive
-  int nq;        // bf16 forward: banks folded into a wave's 16 filter columns (0 / 1: none)
+  int nq;        // banks folded into a wave's 16 filter columns (0 / 1: none)
   int seg_xorg[4];  // first product column of a segment's wave chain
   int seg_lo[4], seg_hi[4];  // output pixels [lo, hi) the segment stores (multiples of 8, or W)
 };
@@ -29,9 +29,11 @@ bool p4_fwd_supported(const rotconv_plan* p);
 int p4_fwd_geoms(const rotconv_plan* p, int out_mode, P4Geom* out, int max_out);
 size_t p4_fwd_pack_floats(const rotconv_plan* p);
 int p4_fwd_pool_mode(const rotconv_plan* p);
-void launch_p4_pack_fwd(const rotconv_plan* p, const float* w, float* wt, hipStream_t st);
+int p4_fwd_fold(const rotconv_plan* p);   // banks a wave can fold into its columns for the pooled forward (1: none)
+// nq = 1: one bank per wave; nq = p4_fwd_fold(p) > 1 (with kOutPooled): folded blocks, pooled across banks in-kernel
+void launch_p4_pack_fwd(const rotconv_plan* p, const float* w, float* wt, hipStream_t st, int nq = 1);
 void launch_p4_fwd(const rotconv_plan* p, int out_mode, const float* x, const float* wt, float* out_val,
-                   uint8_t* out_idx, hipStream_t st);
+                   uint8_t* out_idx, hipStream_t st, int nq = 1);
 void launch_p4_combine(const rotconv_plan* p, const float* pv, const uint8_t* pi, float* ypool, uint8_t* idx,
                        hipStream_t st);   // applies the plan's fused activation
 

@@ -48,7 +48,11 @@ int cin_pad_f32(int Cin) { return Cin <= 4 ? 4 : (Cin + 31) / 32 * 32; }
 // UNPOOLED: write every orientation (rotconv_fwd); else max + arg-max over the bank's rotations.
 // FASTW:    W % 8 == 0 and no wave chain reaches beyond the row: no load masks, vector stores.
 // STREAM:   the filter block does not fit LDS: stream it in 32-channel chunks.
-template <int NWX, int NWY, bool UNPOOLED, bool FASTW, bool STREAM, int KC>
+// NQ: banks folded into the 16 filter columns of a wave (1, 2 or 4).  NQ > 1 serves a pool group that spans all NQ
+//     banks of the plan (R = 4 NQ orientations pooled together): column n holds bank n / (16/NQ), filter n % (16/NQ);
+//     every lane places and maximises its own bank's four rotations and the maximum across the banks is a
+//     rotate-and-compare inside the 16-lane row (DPP), so no per-bank candidates go through memory.
+template <int NWX, int NWY, bool UNPOOLED, bool FASTW, bool STREAM, int KC, int NQ>
 __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restrict__ x, const float* __restrict__ wt,
                                                            const int32_t* __restrict__ rot_of,
                                                            float* __restrict__ out_val, uint8_t* __restrict__ out_idx,
@@ -113,9 +117,11 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restri
   const int nsteps = g.TY + 2;
   const int HW = g.H * g.W;
 
+  constexpr int FPB = 16 / NQ;               // filters per wave
+  const int qi = NQ > 1 ? lc / FPB : q;       // this lane's bank
   int rot[4];
 #pragma unroll
-  for (int s = 0; s < 4; ++s) rot[s] = rot_of[q * 4 + s];
+  for (int s = 0; s < 4; ++s) rot[s] = rot_of[qi * 4 + s];
 
   // A-operand loads: lane (lc, lg) reads X[ci = 4*kstep + lg][h][x0 + 2*lc .. +1].  The address is a
   // per-row lane pointer plus a 32-bit channel offset.  Rows outside the image are never multiplied
@@ -268,8 +274,8 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restri
     // ---- place the row of products at the rotated positions (Eq. 8) --------------
     const int y = h - 1;                       // output row completed by this step
     const int px0 = x0 + 8 * lg;               // first of this lane's 8 pixels
-    const int co = cb * 16 + lc;
-    const bool fin = t >= 2 && y < g.H && co < g.Cout && px0 >= out_lo && px0 < out_hi;
+    const int co = NQ > 1 ? cb * FPB + lc % FPB : cb * 16 + lc;
+    const bool fin = t >= 2 && y < g.H && co < g.Cout && px0 >= out_lo && px0 < out_hi && (NQ == 1 || lc < FPB);
     float best[8];
     uint32_t pk[2] = {0u, 0u};                 // arg-max bytes of the lane's 8 pixels
     int grp_r = 0;                             // any rotation of the bank (its pool group)
@@ -309,9 +315,13 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restri
       }
     } else {
       // pixel by pixel: the four rotations' values, their max and arg-max (smallest r wins ties)
+      if (NQ == 1) {
 #pragma unroll
-      for (int s = 0; s < 4; ++s)
-        if (rot[s] >= 0) { grp_r = rot[s]; first = false; }
+        for (int s = 0; s < 4; ++s)
+          if (rot[s] >= 0) { grp_r = rot[s]; first = false; }
+      } else {
+        first = false;      // all rotations present, one pool group (channel = co)
+      }
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
         float bv = 0.f;
@@ -321,12 +331,26 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restri
         for (int s = 0; s < 4; ++s) {
           float yv;
           place(s, j, yv);
-          if (rot[s] >= 0) {          // wave-uniform
+          if (NQ > 1 || rot[s] >= 0) {          // NQ == 1: wave-uniform
             const bool gt = !have || yv > bv;
             bv = gt ? yv : bv;
             bi = gt ? rot[s] : bi;
             have = true;
           }
+        }
+        if (NQ > 1) {
+          // maximum across the banks: the lanes of one filter sit FPB apart inside the 16-lane row
+          auto other = [&](int ov_bits, int oi) {
+            const float ov = __builtin_bit_cast(float, ov_bits);
+            const bool take = ov > bv || (ov == bv && oi < bi);     // ties: the smallest orientation index
+            bv = take ? ov : bv;
+            bi = take ? oi : bi;
+          };
+          other(__builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, bv), 0x128, 0xf, 0xf, false),
+                __builtin_amdgcn_update_dpp(0, bi, 0x128, 0xf, 0xf, false));                       // row_ror:8
+          if (NQ == 4)
+            other(__builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, bv), 0x124, 0xf, 0xf, false),
+                  __builtin_amdgcn_update_dpp(0, bi, 0x124, 0xf, 0xf, false));                     // row_ror:4
         }
         best[j] = bv;
         pk[j >> 2] |= (uint32_t)bi << (8 * (j & 3));
@@ -399,16 +423,18 @@ __global__ __launch_bounds__(256) void k_p4_combine(const float* __restrict__ pv
 __global__ __launch_bounds__(256) void k_p4_pack_fwd(const float* __restrict__ w, float* __restrict__ wt,
                                                      const int32_t* __restrict__ fq_src,
                                                      const float* __restrict__ fq_coef, int Q, int CB, int CinPad,
-                                                     int Cin, int Cout, int round16) {
-  const int total = Q * CB * CinPad * 144;
+                                                     int Cin, int Cout, int round16, int nq) {
+  // nq > 1: the banks are folded into the 16 columns (column n = bank n / (16/nq), filter n % (16/nq)): [CB'][CinPad]...
+  const int total = (nq > 1 ? 1 : Q) * CB * CinPad * 144;
   const int e = blockIdx.x * 256 + threadIdx.x;
   if (e >= total) return;
   const int c16 = e % 16;
   const int u = (e / 16) % 9;
   const int ci = (e / 144) % CinPad;
   const int cb = (e / (144 * CinPad)) % CB;
-  const int q = e / (144 * CinPad * CB);
-  const int co = cb * 16 + c16;
+  const int fpb = 16 / nq;
+  const int q = nq > 1 ? c16 / fpb : e / (144 * CinPad * CB);
+  const int co = nq > 1 ? cb * fpb + c16 % fpb : cb * 16 + c16;
   float acc = 0.f;
   if (co < Cout && ci < Cin) {
     const int slices = Cout * Cin;
@@ -421,13 +447,13 @@ __global__ __launch_bounds__(256) void k_p4_pack_fwd(const float* __restrict__ w
   wt[e] = round16 ? bf16_to_f32(f32_to_bf16(acc)) : acc;   // bf16 plans keep the expanded banks in bf16 precision
 }
 
-template <int NWX, int NWY, bool UNPOOLED, bool FASTW, bool STREAM, int KC = 8>
+template <int NWX, int NWY, bool UNPOOLED, bool FASTW, bool STREAM, int KC = 8, int NQ = 1>
 void launch_i(const P4Geom& g, const float* x, const float* wt, const int32_t* rot_of, float* ov, uint8_t* oi,
               hipStream_t st) {
   const size_t wfl = STREAM ? (size_t)2 * KC * 4 * 144 : (size_t)g.CinPad * 144;
   const size_t lds = (wfl + 4 * NWX * NWY * 128) * sizeof(float);
   const int grid = (g.units + 7) / 8 * 8;
-  auto kern = k_p4_fwd<NWX, NWY, UNPOOLED, FASTW, STREAM, KC>;
+  auto kern = k_p4_fwd<NWX, NWY, UNPOOLED, FASTW, STREAM, KC, NQ>;
   (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * NWX * NWY), lds, st, x, wt, rot_of, ov, oi, g);
 }
@@ -436,6 +462,16 @@ template <int NWX, int NWY>
 void launch_t(const P4Geom& g, bool fastw, bool stream, const float* x, const float* wt, const int32_t* rot_of,
               float* ov, uint8_t* oi, hipStream_t st) {
   const bool unp = g.out_mode == kOutUnpooled;
+  if (g.nq > 1) {           // banks folded into the columns: resident filter block, pooled output, whole K chunks
+    if (g.nq == 4) {
+      if (fastw) launch_i<NWX, NWY, false, true, false, 8, 4>(g, x, wt, rot_of, ov, oi, st);
+      else launch_i<NWX, NWY, false, false, false, 8, 4>(g, x, wt, rot_of, ov, oi, st);
+    } else {
+      if (fastw) launch_i<NWX, NWY, false, true, false, 8, 2>(g, x, wt, rot_of, ov, oi, st);
+      else launch_i<NWX, NWY, false, false, false, 8, 2>(g, x, wt, rot_of, ov, oi, st);
+    }
+    return;
+  }
   if (g.CinPad == 4) {      // at most 4 input channels: one K-step per row
     if (unp && fastw) launch_i<NWX, NWY, true, true, false, 1>(g, x, wt, rot_of, ov, oi, st);
     else if (unp) launch_i<NWX, NWY, true, false, false, 1>(g, x, wt, rot_of, ov, oi, st);
@@ -534,6 +570,17 @@ int p4_fwd_geoms(const rotconv_plan* p, int out_mode, P4Geom* out, int max_out) 
   return ng;
 }
 
+// Banks folded into a wave's 16 columns for the pooled forward: the plan pools all R = 4 Q orientations of a filter
+// together, Q is 2 or 4, every bank has its four quarter turns, the filter block stays LDS-resident and the channels
+// fill whole 32-channel chunks (1: no folding).
+int p4_fwd_fold(const rotconv_plan* p) {
+  const int Q = p->host.Q;
+  if ((Q != 2 && Q != 4) || p->ng != 1 || needs_stream(p->d.Cin) || cin_pad_f32(p->d.Cin) == 4) return 1;
+  for (int i = 0; i < Q * 4; ++i)
+    if (p->rot_of[i] < 0) return 1;
+  return Q;
+}
+
 size_t p4_fwd_pack_floats(const rotconv_plan* p) {
   return (size_t)p->host.Q * ((p->d.Cout + 15) / 16) * cin_pad_f32(p->d.Cin) * 144;
 }
@@ -554,20 +601,27 @@ int p4_fwd_pool_mode(const rotconv_plan* p) {
   return (p->host.Q > p->ng) ? kOutPartial : kOutPooled;
 }
 
-void launch_p4_pack_fwd(const rotconv_plan* p, const float* w, float* wt, hipStream_t st) {
-  const int CinPad = cin_pad_f32(p->d.Cin), CB = (p->d.Cout + 15) / 16;
-  const int total = p->host.Q * CB * CinPad * 144;
+void launch_p4_pack_fwd(const rotconv_plan* p, const float* w, float* wt, hipStream_t st, int nq) {
+  const int CinPad = cin_pad_f32(p->d.Cin), CB = nq > 1 ? (p->d.Cout * nq + 15) / 16 : (p->d.Cout + 15) / 16;
+  const int total = (nq > 1 ? 1 : p->host.Q) * CB * CinPad * 144;
   hipLaunchKernelGGL(k_p4_pack_fwd, dim3((total + 255) / 256), dim3(256), 0, st, w, wt, p->dev.fq_src, p->dev.fq_coef,
-                     p->host.Q, CB, CinPad, p->d.Cin, p->d.Cout, p->d.dtype == ROTCONV_BF16 ? 1 : 0);
+                     p->host.Q, CB, CinPad, p->d.Cin, p->d.Cout, p->d.dtype == ROTCONV_BF16 ? 1 : 0, nq);
 }
 
 void launch_p4_fwd(const rotconv_plan* p, int out_mode, const float* x, const float* wt, float* out_val,
-                   uint8_t* out_idx, hipStream_t st) {
+                   uint8_t* out_idx, hipStream_t st, int nq) {
   P4Geom gs[4];
   const int ng = p4_fwd_geoms(p, out_mode, gs, 4);
   const bool stream = needs_stream(p->d.Cin);
   for (int i = 0; i < ng; ++i) {
-    const P4Geom& g = gs[i];
+    P4Geom& g = gs[i];
+    g.nq = nq;
+    if (nq > 1) {         // one unit covers all banks of 16 / nq filters
+      const int CBf = (p->d.Cout * nq + 15) / 16;
+      g.units = g.units / (g.Q * g.CB) * CBf;
+      g.CB = CBf;
+      g.Q = 1;
+    }
     const bool fastw = (p->d.W & 7) == 0 && g.inside;   // no lane reaches beyond the row: no masks, vector stores
     switch (g.nwx) {
       case 1: launch_t<1, 8>(g, fastw, stream, x, wt, p->dev.rot_of, out_val, out_idx, st); break;
