@@ -6,6 +6,8 @@
 // next tile prefetched into registers while the current one is multiplied.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "glue_internal.h"
 #include "rotconv_bf16.h"
 
@@ -44,13 +46,14 @@ __global__ __launch_bounds__(NT) void k_gemm(const void* __restrict__ A, const v
   const int kchunk = ((p.K + p.splitk - 1) / p.splitk + BK - 1) / BK * BK;
   const int kbeg = ks * kchunk, kend = min(p.K, kbeg + kchunk);
   const size_t Abase = (size_t)batch * p.strideA, Bbase = (size_t)batch * p.strideB, Cbase = (size_t)z * p.strideC;
-  auto ldA = [&](size_t off) -> float {
-    if (BF) return bf16_to_f32(static_cast<const uint16_t*>(A)[Abase + off]);
-    return static_cast<const float*>(A)[Abase + off];
-  };
-  auto ldB = [&](size_t off) -> float {
-    if (BF) return bf16_to_f32(static_cast<const uint16_t*>(B)[Bbase + off]);
-    return static_cast<const float*>(B)[Bbase + off];
+  // a fetched element as it sits in memory; widened (and zeroed outside the matrix) only when it is written to
+  // LDS, after the current tile's multiplications: nothing between a load and that point waits for it
+  using Raw = typename std::conditional<BF != 0, uint16_t, float>::type;
+  const Raw* Ap = static_cast<const Raw*>(A) + Abase;
+  const Raw* Bp = static_cast<const Raw*>(B) + Bbase;
+  auto widen = [](Raw v) -> float {
+    if constexpr (BF != 0) return bf16_to_f32(v);
+    else return v;
   };
 
   // tile-independent parts.  A: element i is (m, k) = TA ? (tid % 128, tid / 128 + 2 i) : (tid / 16 + 16 i, tid % 16);
@@ -72,7 +75,7 @@ __global__ __launch_bounds__(NT) void k_gemm(const void* __restrict__ A, const v
     else boff[i] = TB ? (size_t)gn * p.ldb + kb : (size_t)kb * p.ldb + gn;
   }
 
-  float ra[8], rb[8];
+  Raw ra[8], rb[8];
   auto gload = [&](int k0) {
     // what the tile adds to the offsets (k0 is a multiple of 16, so with shufB and !TB the row part of k0 + kb
     // is the sum of the two row parts: k0's low bits are zero)
@@ -82,21 +85,23 @@ __global__ __launch_bounds__(NT) void k_gemm(const void* __restrict__ A, const v
     else bstep = TB ? (size_t)k0 : (size_t)k0 * p.ldb;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
+      // every load is issued (from element 0 of the operand where the element lies outside the matrix): a load
+      // under a branch would be waited for before the next one is issued
       const int k = TA ? tid / 128 + 2 * i : tid % 16;
-      ra[i] = (aok[i] && k0 + k < kend) ? ldA(aoff[i] + astep) : 0.f;
+      ra[i] = Ap[(aok[i] && k0 + k < kend) ? aoff[i] + astep : 0];
       const int kb = TB ? tid % 16 : tid / 128 + 2 * i;
-      rb[i] = (bok[i] && k0 + kb < kend) ? ldB(boff[i] + bstep) : 0.f;
+      rb[i] = Bp[(bok[i] && k0 + kb < kend) ? boff[i] + bstep : 0];
     }
   };
-  auto sstore = [&](int buf) {
+  auto sstore = [&](int buf, int k0) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       int m, k;
       if (TA) { m = tid % 128; k = tid / 128 + 2 * i; } else { k = tid % 16; m = tid / 16 + 16 * i; }
-      As[buf][k][m] = ra[i];
+      As[buf][k][m] = (aok[i] && k0 + k < kend) ? widen(ra[i]) : 0.f;
       int n, kb;
       if (TB) { kb = tid % 16; n = tid / 16 + 16 * i; } else { n = tid % 128; kb = tid / 128 + 2 * i; }
-      Bs[buf][kb][n] = rb[i];
+      Bs[buf][kb][n] = (bok[i] && k0 + kb < kend) ? widen(rb[i]) : 0.f;
     }
   };
 
@@ -109,12 +114,13 @@ __global__ __launch_bounds__(NT) void k_gemm(const void* __restrict__ A, const v
 
   if (kbeg < kend) {
     gload(kbeg);
-    sstore(0);
+    sstore(0, kbeg);
     __syncthreads();
     int buf = 0;
     for (int k0 = kbeg; k0 < kend; k0 += BK) {
       const bool more = k0 + BK < kend;
       if (more) gload(k0 + BK);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int kk = 0; kk < BK; kk += 4) {
         float a[4], b[4];
@@ -127,7 +133,8 @@ __global__ __launch_bounds__(NT) void k_gemm(const void* __restrict__ A, const v
 #pragma unroll
           for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[i], b[j], acc[i][j], 0, 0, 0);
       }
-      if (more) sstore(buf ^ 1);
+      __builtin_amdgcn_sched_barrier(0);
+      if (more) sstore(buf ^ 1, k0 + BK);
       __syncthreads();
       buf ^= 1;
     }
