@@ -273,6 +273,158 @@ __global__ __launch_bounds__(1024) void k_mean(const float* __restrict__ v, floa
   if (threadIdx.x == 0) out[0] = red[0] * inv;
 }
 
+// ---- 1x1 head with few output channels (the class scores): streaming kernels on the vector ALU ----
+// A 128-row matrix-core tile would be nine tenths padding for six classes; the layer is HBM-bound (it reads
+// or writes the Cin-channel map once), so a lane owns one 16-byte vector of consecutive pixels and walks the
+// channels.  w sits in LDS as fp32 [ci][HEAD_CO] (zero beyond Cout).  Sums run in a fixed order.
+constexpr int HEAD_CO = 8;         // at most this many output channels
+constexpr int HEAD_CIN = 1024;     // at most this many input channels (LDS copy of w)
+constexpr int HEAD_PARTS = 256;    // workgroups (= partial sums) of the weight gradient, at most
+
+template <typename T>
+__device__ __forceinline__ void head_load_w(const T* __restrict__ w, float* wl, int Cin, int Cout) {
+  for (int i = threadIdx.x; i < Cin * HEAD_CO; i += 256) {
+    const int ci = i / HEAD_CO, co = i % HEAD_CO;
+    wl[i] = co < Cout ? Elt<T>::ld(w + (size_t)co * Cin + ci) : 0.f;
+  }
+  __syncthreads();
+}
+
+// y[n][co][p] = sum_ci w[co][ci] x[n][ci][p]
+template <typename T>
+__global__ __launch_bounds__(256) void k_head_fwd(const T* __restrict__ x, const T* __restrict__ w, T* __restrict__ y,
+                                                  int Cin, int Cout, size_t P, size_t nvec) {
+  constexpr int V = Elt<T>::V;
+  extern __shared__ float wl[];
+  head_load_w(w, wl, Cin, Cout);
+  const size_t pv = P / V;
+  for (size_t v = (size_t)blockIdx.x * 256 + threadIdx.x; v < nvec; v += (size_t)gridDim.x * 256) {
+    const size_t n = v / pv, p = (v - n * pv) * V;
+    const T* xp = x + n * Cin * P + p;
+    float acc[HEAD_CO][V];
+#pragma unroll
+    for (int co = 0; co < HEAD_CO; ++co)
+#pragma unroll
+      for (int k = 0; k < V; ++k) acc[co][k] = 0.f;
+    for (int ci = 0; ci < Cin; ++ci) {
+      float xv[V];
+      Elt<T>::ldv(xp + (size_t)ci * P, xv);
+#pragma unroll
+      for (int co = 0; co < HEAD_CO; ++co) {
+        const float wv = wl[ci * HEAD_CO + co];
+#pragma unroll
+        for (int k = 0; k < V; ++k) acc[co][k] = fmaf(wv, xv[k], acc[co][k]);
+      }
+    }
+#pragma unroll
+    for (int co = 0; co < HEAD_CO; ++co)
+      if (co < Cout) Elt<T>::stv(y + (n * Cout + co) * P + p, acc[co]);
+  }
+}
+
+// dx[n][ci][p] = sum_co w[co][ci] dy[n][co][p]
+template <typename T>
+__global__ __launch_bounds__(256) void k_head_bwd_data(const T* __restrict__ dy, const T* __restrict__ w,
+                                                       T* __restrict__ dx, int Cin, int Cout, size_t P, size_t nvec) {
+  constexpr int V = Elt<T>::V;
+  extern __shared__ float wl[];
+  head_load_w(w, wl, Cin, Cout);
+  const size_t pv = P / V;
+  for (size_t v = (size_t)blockIdx.x * 256 + threadIdx.x; v < nvec; v += (size_t)gridDim.x * 256) {
+    const size_t n = v / pv, p = (v - n * pv) * V;
+    float g[HEAD_CO][V];
+#pragma unroll
+    for (int co = 0; co < HEAD_CO; ++co) {
+      if (co < Cout) {
+        Elt<T>::ldv(dy + (n * Cout + co) * P + p, g[co]);
+      } else {
+#pragma unroll
+        for (int k = 0; k < V; ++k) g[co][k] = 0.f;
+      }
+    }
+    T* dp = dx + n * Cin * P + p;
+    for (int ci = 0; ci < Cin; ++ci) {
+      float o[V];
+#pragma unroll
+      for (int k = 0; k < V; ++k) o[k] = 0.f;
+#pragma unroll
+      for (int co = 0; co < HEAD_CO; ++co) {
+        const float wv = wl[ci * HEAD_CO + co];
+#pragma unroll
+        for (int k = 0; k < V; ++k) o[k] = fmaf(wv, g[co][k], o[k]);
+      }
+      Elt<T>::stv(dp + (size_t)ci * P, o);
+    }
+  }
+}
+
+// part[blockIdx.x][co][ci] = sum over the workgroup's pixel vectors of dy[n][co][p] x[n][ci][p].  blockIdx.y picks
+// a group of 64 input channels, wave j of the workgroup's four takes sixteen of them; every wave walks all of the
+// workgroup's pixel vectors (64 per step), then adds its lanes' sums in a butterfly and lane 0 stores them.
+template <typename T>
+__global__ __launch_bounds__(256) void k_head_bwd_weight(const T* __restrict__ x, const T* __restrict__ dy,
+                                                         float* __restrict__ part, int Cin, int Cout, size_t P,
+                                                         size_t nvec, size_t per_block) {
+  constexpr int V = Elt<T>::V;
+  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+  const int ci0 = blockIdx.y * 64 + wave * 16;
+  const size_t pv = P / V;
+  const size_t vbeg = (size_t)blockIdx.x * per_block, vend = vbeg + per_block < nvec ? vbeg + per_block : nvec;
+  float acc[16][HEAD_CO];
+#pragma unroll
+  for (int c = 0; c < 16; ++c)
+#pragma unroll
+    for (int co = 0; co < HEAD_CO; ++co) acc[c][co] = 0.f;
+  for (size_t v = vbeg + lane; v < vend; v += 64) {
+    const size_t n = v / pv, p = (v - n * pv) * V;
+    float g[HEAD_CO][V];
+#pragma unroll
+    for (int co = 0; co < HEAD_CO; ++co) {
+      if (co < Cout) {
+        Elt<T>::ldv(dy + (n * Cout + co) * P + p, g[co]);
+      } else {
+#pragma unroll
+        for (int k = 0; k < V; ++k) g[co][k] = 0.f;
+      }
+    }
+    const T* xp = x + n * Cin * P + p;
+#pragma unroll
+    for (int c = 0; c < 16; ++c) {
+      float xv[V];
+      if (ci0 + c < Cin) {
+        Elt<T>::ldv(xp + (size_t)(ci0 + c) * P, xv);
+      } else {
+#pragma unroll
+        for (int k = 0; k < V; ++k) xv[k] = 0.f;
+      }
+#pragma unroll
+      for (int co = 0; co < HEAD_CO; ++co)
+#pragma unroll
+        for (int k = 0; k < V; ++k) acc[c][co] = fmaf(g[co][k], xv[k], acc[c][co]);
+    }
+  }
+  float* out = part + (size_t)blockIdx.x * Cout * Cin;
+#pragma unroll
+  for (int c = 0; c < 16; ++c)
+#pragma unroll
+    for (int co = 0; co < HEAD_CO; ++co) {
+      float s = acc[c][co];
+#pragma unroll
+      for (int m = 32; m >= 1; m >>= 1) s += __shfl_xor(s, m);
+      if (lane == 0 && co < Cout && ci0 + c < Cin) out[(size_t)co * Cin + ci0 + c] = s;
+    }
+}
+
+// The streaming head kernels apply when the vectors line up: P a multiple of the 16-byte vector, aligned tensors.
+bool head_fast(int Cin, int Cout, size_t P, int bf, const void* a, const void* b) {
+  return Cout <= HEAD_CO && Cin <= HEAD_CIN && P % (bf ? 8 : 4) == 0 && aligned16(a) && aligned16(b);
+}
+// Workgroups of the head's weight gradient: at least eight pixel vectors per lane, at most HEAD_PARTS.
+int head_parts(int N, size_t P) {
+  const size_t nvec = (size_t)N * P / 4;
+  return (int)std::max<size_t>(1, std::min<size_t>(HEAD_PARTS, nvec / 512));
+}
+
 // Splits of the contraction for the weight gradients (K = pixels of one image): about 1024 workgroups,
 // chunks of at least 64 pixels, at most 64 partial sums per image.
 int pick_splitk(int tiles, int batch, int K) {
@@ -412,6 +564,15 @@ int upconv2_bwd_weight_g(const void* x, const void* dy, float* dw, int N, int Ci
 int conv1x1_fwd_g(const void* x, const void* w, void* y, int N, int Cin, int Cout, size_t P, int bf, void* stream) {
   if (!x || !w || !y) return ROTCONV_ERR_NULL;
   if (N < 1 || Cin < 1 || Cout < 1 || P < 1 || P > 0x7fffffff) return ROTCONV_ERR_SHAPE;
+  if (head_fast(Cin, Cout, P, bf, x, y)) {
+    const size_t nvec = (size_t)N * P / (bf ? 8 : 4);
+    const size_t lds = (size_t)Cin * HEAD_CO * sizeof(float);
+    if (bf) hipLaunchKernelGGL(k_head_fwd<uint16_t>, dim3(blocks_for(nvec)), dim3(256), lds, S(stream), (const uint16_t*)x,
+                               (const uint16_t*)w, (uint16_t*)y, Cin, Cout, P, nvec);
+    else hipLaunchKernelGGL(k_head_fwd<float>, dim3(blocks_for(nvec)), dim3(256), lds, S(stream), (const float*)x,
+                            (const float*)w, (float*)y, Cin, Cout, P, nvec);
+    return finish();
+  }
   GemmArgs a{};
   a.M = Cout; a.N = (int)P; a.K = Cin; a.lda = Cin; a.ldb = (int)P; a.ldc = (int)P; a.batch = N; a.splitk = 1;
   a.strideB = (size_t)Cin * P; a.strideC = (size_t)Cout * P;
@@ -423,6 +584,15 @@ int conv1x1_bwd_data_g(const void* dy, const void* w, void* dx, int N, int Cin, 
                        void* stream) {
   if (!dy || !w || !dx) return ROTCONV_ERR_NULL;
   if (N < 1 || Cin < 1 || Cout < 1 || P < 1 || P > 0x7fffffff) return ROTCONV_ERR_SHAPE;
+  if (head_fast(Cin, Cout, P, bf, dy, dx)) {
+    const size_t nvec = (size_t)N * P / (bf ? 8 : 4);
+    const size_t lds = (size_t)Cin * HEAD_CO * sizeof(float);
+    if (bf) hipLaunchKernelGGL(k_head_bwd_data<uint16_t>, dim3(blocks_for(nvec)), dim3(256), lds, S(stream),
+                               (const uint16_t*)dy, (const uint16_t*)w, (uint16_t*)dx, Cin, Cout, P, nvec);
+    else hipLaunchKernelGGL(k_head_bwd_data<float>, dim3(blocks_for(nvec)), dim3(256), lds, S(stream), (const float*)dy,
+                            (const float*)w, (float*)dx, Cin, Cout, P, nvec);
+    return finish();
+  }
   GemmArgs a{};
   a.M = Cin; a.N = (int)P; a.K = Cout; a.lda = Cin; a.transA = 1; a.ldb = (int)P; a.ldc = (int)P; a.batch = N;
   a.splitk = 1; a.strideB = (size_t)Cout * P; a.strideC = (size_t)Cin * P;
@@ -435,6 +605,18 @@ int conv1x1_bwd_weight_g(const void* x, const void* dy, float* dw, int N, int Ci
   if (!x || !dy || !dw) return ROTCONV_ERR_NULL;
   if (N < 1 || Cin < 1 || Cout < 1 || P < 1 || P > 0x7fffffff) return ROTCONV_ERR_SHAPE;
   if (!ws || ws_bytes < glue_conv1x1_workspace_bytes(N, Cin, Cout, P)) return ROTCONV_ERR_WORKSPACE;
+  if (head_fast(Cin, Cout, P, bf, x, dy)) {
+    const size_t nvec = (size_t)N * P / (bf ? 8 : 4);
+    const int parts = head_parts(N, P);
+    const size_t per_block = ((nvec + parts - 1) / parts + 63) / 64 * 64;
+    const dim3 grid(parts, (Cin + 63) / 64);
+    if (bf) hipLaunchKernelGGL(k_head_bwd_weight<uint16_t>, grid, dim3(256), 0, S(stream), (const uint16_t*)x,
+                               (const uint16_t*)dy, (float*)ws, Cin, Cout, P, nvec, per_block);
+    else hipLaunchKernelGGL(k_head_bwd_weight<float>, grid, dim3(256), 0, S(stream), (const float*)x, (const float*)dy,
+                            (float*)ws, Cin, Cout, P, nvec, per_block);
+    launch_sum_parts((const float*)ws, dw, (size_t)Cout * Cin, parts, (size_t)Cout * Cin, S(stream));
+    return finish();
+  }
   const int tiles = ((Cout + 127) / 128) * ((Cin + 127) / 128);
   GemmArgs a{};
   a.M = Cout; a.N = Cin; a.K = (int)P; a.lda = (int)P; a.ldb = (int)P; a.transB = 1; a.ldc = Cin; a.batch = N;
@@ -459,7 +641,8 @@ size_t glue_upconv2_workspace_bytes(int N, int Cin, int Cout, int H, int W) {
 }
 size_t glue_conv1x1_workspace_bytes(int N, int Cin, int Cout, size_t P) {
   const int tiles = ((Cout + 127) / 128) * ((Cin + 127) / 128);
-  return (size_t)N * pick_splitk(tiles, N, (int)P) * Cout * Cin * sizeof(float);
+  const int parts = std::max(N * pick_splitk(tiles, N, (int)P), head_parts(N, P));   // either kernel family
+  return (size_t)parts * Cout * Cin * sizeof(float);
 }
 
 // ---- fp32 ----

@@ -199,7 +199,8 @@ def test_bf16_streaming_ops(shape):
     assert np.array_equal(_h64(accd), _rb(_rb(base + ref) + x))
 
 
-@pytest.mark.parametrize("N,Cin,Cout,H,W", [(2, 5, 3, 3, 5), (2, 130, 70, 12, 16)])
+@pytest.mark.parametrize("N,Cin,Cout,H,W", [(2, 5, 3, 3, 5), (1, 40, 36, 9, 7), (2, 130, 70, 12, 16), (1, 256, 128, 16, 16),
+                                           (1, 33, 65, 31, 3)])
 def test_bf16_gemm_layers(N, Cin, Cout, H, W):
     rng = np.random.default_rng(22)
     bf = torch.bfloat16
