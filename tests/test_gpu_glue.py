@@ -103,7 +103,9 @@ def test_concat_split():
     assert np.array_equal(host(da), base + a)
 
 
-@pytest.mark.parametrize("N,Cin,Cout,H,W", [(2, 7, 3, 5, 9), (1, 64, 6, 48, 40), (2, 150, 130, 6, 22)])
+@pytest.mark.parametrize("N,Cin,Cout,H,W", [(2, 7, 3, 5, 9), (1, 64, 6, 48, 40), (2, 150, 130, 6, 22),
+                                           # few classes, pixel count a multiple of the vector: the streaming kernels
+                                           (3, 70, 8, 16, 12), (2, 16, 1, 8, 8), (2, 64, 6, 128, 160)])
 def test_conv1x1(N, Cin, Cout, H, W):
     rng = np.random.default_rng(5)
     x, w, dy = f32(rng, N, Cin, H, W), f32(rng, Cout, Cin, scale=Cin ** -0.5), f32(rng, N, Cout, H, W)
@@ -240,6 +242,27 @@ def test_bf16_gemm_layers(N, Cin, Cout, H, W):
     lr, dlr = uo.softmax_ce(g, lab)
     assert abs(float(host(loss)[0]) - lr) <= RTOL * abs(lr)
     assert_close(_h64(dl), dlr, "bf16 softmax_ce dlogits", rtol=BF_RTOL)
+
+
+@pytest.mark.parametrize("N,Cin,Cout,H,W", [(2, 64, 6, 16, 24), (1, 70, 8, 8, 8), (3, 5, 2, 4, 8), (2, 64, 6, 128, 96)])
+def test_bf16_head_streaming(N, Cin, Cout, H, W):
+    """1x1 head with few classes on bf16 tensors whose pixel count is a multiple of the 8-element vector."""
+    rng = np.random.default_rng(23)
+    bf = torch.bfloat16
+    xd, x = _b16(f32(rng, N, Cin, H, W))
+    wd, w = _b16(f32(rng, Cout, Cin, scale=Cin ** -0.5))
+    gd, g = _b16(f32(rng, N, Cout, H, W))
+    y = nan(N, Cout, H, W, dtype=bf)
+    rc.glue_conv1x1_fwd(xd, wd, y)
+    assert_close(_h64(y), uo.conv1x1_fwd(x, w), "bf16 head fwd", rtol=BF_RTOL)
+    dxr, dwr = uo.conv1x1_bwd(x, w, g)
+    dx = nan(N, Cin, H, W, dtype=bf)
+    rc.glue_conv1x1_bwd_data(gd, wd, dx)
+    assert_close(_h64(dx), dxr, "bf16 head bwd_data", rtol=BF_RTOL)
+    dw = nan(Cout, Cin)
+    ws = torch.empty(max(256, rc.glue_conv1x1_workspace_bytes(N, Cin, Cout, H * W)), dtype=torch.uint8, device="cuda")
+    rc.glue_conv1x1_bwd_weight(xd, gd, dw, ws)
+    assert_close(host(dw), dwr, "bf16 head bwd_weight (fp32 result)")
 
 
 def test_glue_rejects_mixed_storage_types():
