@@ -236,12 +236,15 @@ __global__ __launch_bounds__(256) void k_split2(const T* __restrict__ dcat, T* _
   }
 }
 
-// per-pixel loss into `pix` (fp32), dlogits = (softmax - onehot) * inv
+// dlogits = (softmax - onehot) * inv; the workgroup's pixel losses, added in a fixed order (a thread's pixels in
+// sequence, then a tree over the threads), go to part[blockIdx.x]
 template <typename T>
 __global__ __launch_bounds__(256) void k_softmax_ce(const T* __restrict__ logits, const int32_t* __restrict__ labels,
-                                                    float* __restrict__ pix, T* __restrict__ dl, int N, int K,
+                                                    float* __restrict__ part, T* __restrict__ dl, int N, int K,
                                                     size_t P, float inv) {
+  __shared__ float red[256];
   const size_t total = (size_t)N * P;
+  float mine = 0.f;
   for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (size_t)gridDim.x * 256) {
     const size_t n = e / P, p = e % P;
     const T* lg = logits + n * K * P + p;
@@ -252,12 +255,19 @@ __global__ __launch_bounds__(256) void k_softmax_ce(const T* __restrict__ logits
     const int lab = labels[e];
     const bool valid = lab >= 0 && lab < K;      // a label outside 0..K-1 contributes nothing
     const float lse = m + logf(s);
-    pix[e] = valid ? lse - Elt<T>::ld(lg + (size_t)(valid ? lab : 0) * P) : 0.f;
+    mine += valid ? lse - Elt<T>::ld(lg + (size_t)(valid ? lab : 0) * P) : 0.f;
     T* d = dl + n * K * P + p;
     for (int k = 0; k < K; ++k)
       Elt<T>::st(d + (size_t)k * P,
                  valid ? (expf(Elt<T>::ld(lg + (size_t)k * P) - lse) - (k == lab ? 1.f : 0.f)) * inv : 0.f);
   }
+  red[threadIdx.x] = mine;
+  __syncthreads();
+  for (int w = 128; w > 0; w >>= 1) {
+    if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) part[blockIdx.x] = red[0];
 }
 // deterministic mean: 1024 threads each sum a strided subset in order, then a fixed tree
 __global__ __launch_bounds__(1024) void k_mean(const float* __restrict__ v, float* __restrict__ out, size_t n, float inv) {
@@ -515,9 +525,10 @@ int softmax_ce_t(const T* logits, const int32_t* labels, float* loss, T* dlogits
   if (N < 1 || K < 1 || P < 1) return ROTCONV_ERR_SHAPE;
   if (!ws || ws_bytes < (size_t)N * P * sizeof(float)) return ROTCONV_ERR_WORKSPACE;
   const float inv = 1.0f / (float)((double)N * (double)P);
-  hipLaunchKernelGGL((k_softmax_ce<T>), dim3(blocks_for((size_t)N * P)), dim3(256), 0, S(stream), logits, labels,
-                     (float*)ws, dlogits, N, K, P, inv);
-  hipLaunchKernelGGL(k_mean, dim3(1), dim3(1024), 0, S(stream), (const float*)ws, loss, (size_t)N * P, inv);
+  const unsigned blocks = std::min(blocks_for((size_t)N * P), 4096u);    // one partial loss each (4 bytes of ws)
+  hipLaunchKernelGGL((k_softmax_ce<T>), dim3(blocks), dim3(256), 0, S(stream), logits, labels, (float*)ws, dlogits, N,
+                     K, P, inv);
+  hipLaunchKernelGGL(k_mean, dim3(1), dim3(1024), 0, S(stream), (const float*)ws, loss, (size_t)blocks, inv);
   return finish();
 }
 
