@@ -111,6 +111,7 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd_bf16(const uint16_t* 
   const int x0 = g.seg_xorg[seg] + wx * 32;
   const int out_lo = g.seg_lo[seg], out_hi = g.seg_hi[seg];
   const int y0 = (bg * NWY + wy) * g.TY;
+  const bool live = y0 < g.H;                // else: a band below the image
   const int nsteps = g.TY + 2;
   const int HW = g.H * g.W;
 
@@ -121,24 +122,41 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd_bf16(const uint16_t* 
   for (int s = 0; s < 4; ++s) rot[s] = rot_of[qi * 4 + s];
 
   // A-operand loads: lane (lc, lg) reads the dword X[ci = 32*chunk + 8*lg + j][h][x0 + 2*lc .. +1],
-  // j = 0..7.  Rows outside the image are never multiplied, channels beyond Cin meet zero taps, so both
+  // j = 0..7.  Products of rows outside the image are discarded, channels beyond Cin meet zero taps, so both
   // only need a valid address; pixels beyond W must read as zero (only when W % 32 != 0).
   const int pxa = x0 + 2 * lc;
   const bool px_ok = pxa < g.W;
-  const uint16_t* xn = x + (size_t)n * g.Cin * HW + (px_ok ? pxa : 0);
-  uint32_t lgoff = (uint32_t)(8 * lg) * (uint32_t)HW;
-  asm volatile("" : "+v"(lgoff));   // opaque: the chunk / slot part of the offset stays scalar
+  // address = wave-uniform part (image, row, chunk and slot channel: scalar registers) + one per-lane byte offset
+  // that never changes (pixel pair, k-group's channels), so a load costs no vector arithmetic
+  const uint16_t* xn = x + (size_t)n * g.Cin * HW;
+  const uint32_t lgoff = (uint32_t)(8 * lg) * (uint32_t)HW;
+  const uint32_t lane_off = 2u * (lgoff + (uint32_t)(px_ok ? pxa : 0));
   const uint32_t off_last = (uint32_t)(g.Cin - 1) * (uint32_t)HW;
   auto row_ptr = [&](int t) -> const uint16_t* {
     const int h = min(max(y0 - 1 + t, 0), g.H - 1);
     return xn + (size_t)h * g.W;
   };
-  auto load_a = [&](const uint16_t* rp, int c, int j) -> uint32_t {
-    uint32_t off = (uint32_t)(c * 32 + j) * (uint32_t)HW + lgoff;
-    if (CPAD) off = min(off, off_last);
-    const uint32_t v2 = *reinterpret_cast<const uint32_t*>(rp + off);
-    if (FASTW) return v2;
-    return px_ok ? v2 : 0u;
+  const size_t plane_bytes = (size_t)HW * 2;
+  // the eight channels of chunk c that this lane's k-group feeds, into dst[0..7]
+  auto load_chunk = [&](const uint16_t* rp, int c, uint32_t* dst) {
+    if (CPAD) {     // channels beyond Cin read the last one (their taps are zero)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const uint32_t off = min((uint32_t)(c * 32 + j) * (uint32_t)HW + lgoff, off_last) + (uint32_t)(px_ok ? pxa : 0);
+        dst[j] = *reinterpret_cast<const uint32_t*>(rp + off);
+      }
+    } else {
+      const char* base = reinterpret_cast<const char*>(rp) + (size_t)(c * 32) * plane_bytes;   // scalar
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        dst[j] = *reinterpret_cast<const uint32_t*>(base + lane_off);
+        base += plane_bytes;
+      }
+    }
+    if (!FASTW) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) dst[j] = px_ok ? dst[j] : 0u;
+    }
   };
 
   float accA[4][8], accB[4][8];
@@ -153,9 +171,7 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd_bf16(const uint16_t* 
   {
     const uint16_t* rp = row_ptr(0);
 #pragma unroll
-    for (int i = 0; i < ND; ++i)
-#pragma unroll
-      for (int j = 0; j < 8; ++j) ring[i][j] = load_a(rp, i, j);
+    for (int i = 0; i < ND; ++i) load_chunk(rp, i, ring[i]);
     __builtin_amdgcn_s_waitcnt(0x0F70);
   }
   const char* wl_lane = Wl + lane * 16;
@@ -171,47 +187,39 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd_bf16(const uint16_t* 
     // One group of ND chunks.  Per chunk: pack the slot into the two tiles' A operands, refill the
     // slot, then 9 taps x 2 tiles of matrix instructions with the B operand read from LDS two taps
     // ahead.  Scheduling fences keep loads and LDS reads where they are issued.
-    auto group = [&](int cc, bool mul, bool first) {
+    auto group = [&](int cc, bool first) {
       const bool last = cc + ND == nchunk;
       const uint16_t* rp = last ? rp_nxt : rp_cur;
       const int cn = last ? 0 : cc + ND;
       if (STREAM) wload(last ? 0 : cc / ND + 1);
-      if (mul) {
-        const char* wc = STREAM ? wl_lane + (seq & 1) * STB : wl_lane + (size_t)cc * CHB;
-        u4 bw[3];
-        bw[0] = *reinterpret_cast<const u4*>(wc);
-        bw[1] = *reinterpret_cast<const u4*>(wc + 1024);
+      const char* wc = STREAM ? wl_lane + (seq & 1) * STB : wl_lane + (size_t)cc * CHB;
+      u4 bw[3];
+      bw[0] = *reinterpret_cast<const u4*>(wc);
+      bw[1] = *reinterpret_cast<const u4*>(wc + 1024);
 #pragma unroll
-        for (int i = 0; i < ND; ++i) {
-          u4 a0, a1;
+      for (int i = 0; i < ND; ++i) {
+        u4 a0, a1;
 #pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            a0[j] = __builtin_amdgcn_perm(ring[i][2 * j + 1], ring[i][2 * j], 0x05040100u);
-            a1[j] = __builtin_amdgcn_perm(ring[i][2 * j + 1], ring[i][2 * j], 0x07060302u);
-          }
-          __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-          for (int j = 0; j < 8; ++j) ring[i][j] = load_a(rp, cn + i, j);
-          __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-          for (int u = 0; u < 9; ++u) {
-            const int e = i * 9 + u;               // tap counter inside the group
-            if (e + 2 < ND * 9) bw[(e + 2) % 3] = *reinterpret_cast<const u4*>(wc + (e + 2) * 1024);
-            __builtin_amdgcn_sched_barrier(0);
-            const f4 zero = f4{0.f, 0.f, 0.f, 0.f};
-            const bf8 b = __builtin_bit_cast(bf8, bw[e % 3]);
-            P[u][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf8, a0), b,
-                                                              first && i == 0 ? zero : P[u][0], 0, 0, 0);
-            P[u][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf8, a1), b,
-                                                              first && i == 0 ? zero : P[u][1], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-          }
+        for (int j = 0; j < 4; ++j) {
+          a0[j] = __builtin_amdgcn_perm(ring[i][2 * j + 1], ring[i][2 * j], 0x05040100u);
+          a1[j] = __builtin_amdgcn_perm(ring[i][2 * j + 1], ring[i][2 * j], 0x07060302u);
         }
-      } else {
+        __builtin_amdgcn_sched_barrier(0);
+        load_chunk(rp, cn + i, ring[i]);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int i = 0; i < ND; ++i)
-#pragma unroll
-          for (int j = 0; j < 8; ++j) ring[i][j] = load_a(rp, cn + i, j);
+        for (int u = 0; u < 9; ++u) {
+          const int e = i * 9 + u;               // tap counter inside the group
+          if (e + 2 < ND * 9) bw[(e + 2) % 3] = *reinterpret_cast<const u4*>(wc + (e + 2) * 1024);
+          __builtin_amdgcn_sched_barrier(0);
+          const f4 zero = f4{0.f, 0.f, 0.f, 0.f};
+          const bf8 b = __builtin_bit_cast(bf8, bw[e % 3]);
+          P[u][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf8, a0), b,
+                                                            first && i == 0 ? zero : P[u][0], 0, 0, 0);
+          P[u][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf8, a1), b,
+                                                            first && i == 0 ? zero : P[u][1], 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
+        }
       }
       if (STREAM) {
         wstore((seq + 1) & 1);
@@ -219,16 +227,25 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd_bf16(const uint16_t* 
       }
       ++seq;
     };
-    if (row_ok) {
-      group(0, true, true);
-      for (int cc = ND; cc < nchunk; cc += ND) group(cc, true, false);
-    } else {
+    // A row above / below the image (first and last band only) is multiplied like any other, from the clamped
+    // row's values, and its products are then discarded: zeroing them ahead of the branch instead would put
+    // 72 register moves on every row's path.  A wave whose whole band lies below the image (the workgroup's bands
+    // need not divide H) multiplies nothing: it only keeps the workgroup's barriers and filter stages in step.
+    if (live) {
+      group(0, true);
+      for (int cc = ND; cc < nchunk; cc += ND) group(cc, false);
+    } else if (STREAM) {
+      for (int cc = 0; cc < nchunk; cc += ND) {
+        wload(cc + ND == nchunk ? 0 : cc / ND + 1);
+        wstore((seq + 1) & 1);
+        __syncthreads();
+        ++seq;
+      }
+    }
+    if (!row_ok || !live) {
+      asm volatile("" ::: "memory");       // keeps this a branch
 #pragma unroll
       for (int u = 0; u < 9; ++u) { P[u][0] = f4{0.f, 0.f, 0.f, 0.f}; P[u][1] = f4{0.f, 0.f, 0.f, 0.f}; }
-      for (int cc = 0; cc < nchunk; cc += ND) group(cc, false, false);
-      // rare path (rows above / below the image): drain its loads here so that the hot loop's wait
-      // counters only ever see the refills issued by the hot loop itself
-      __builtin_amdgcn_s_waitcnt(0x0F70);
     }
 
     // ---- neighbour values across lane groups and waves --------------------------
@@ -290,16 +307,18 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd_bf16(const uint16_t* 
     int grp_r = 0;                             // any rotation of the bank (its pool group)
     bool none = true;
     auto place = [&](int s, int j, float& yfin) {
-      float t0 = 0.f, t1 = 0.f, t2 = 0.f;
+      // three taps per filter row; a sum starts from its first term (0 + v is an instruction: it is not v for v = -0)
+      float tr[3] = {0.f, 0.f, 0.f};
+      bool begun[3] = {false, false, false};
 #pragma unroll
       for (int u = 0; u < 9; ++u) {
         const int jj = j + tap_j(s, u) - 1;
         const float val = jj < 0 ? nbL[u] : jj > 7 ? nbR[u] : P[u][jj & 1][jj >> 1];
         const int ti = tap_i(s, u);
-        if (ti == 0) t0 += val;
-        else if (ti == 1) t1 += val;
-        else t2 += val;
+        tr[ti] = begun[ti] ? tr[ti] + val : val;
+        begun[ti] = true;
       }
+      const float t0 = tr[0], t1 = tr[1], t2 = tr[2];
       yfin = accA[s][j] + t2;         // rows h-2, h-1, h are in: output row h-1 done
       accA[s][j] = accB[s][j] + t1;   // output row h has rows h-1, h
       accB[s][j] = t0;                // output row h+1 has row h
@@ -332,20 +351,34 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd_bf16(const uint16_t* 
       } else {
         none = false;       // all rotations present, one pool group (channel = co)
       }
+      // all four quarter turns in the orientation set (every closed set; wave-uniform): plain compare chain
+      const bool allrot = NQ > 1 || (rot[0] | rot[1] | rot[2] | rot[3]) >= 0;
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
         float bv = 0.f;
         int bi = 0;
-        bool have = false;
+        float yv[4];
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-          float yv;
-          place(s, j, yv);
-          if (NQ > 1 || rot[s] >= 0) {          // NQ == 1: wave-uniform
-            const bool gt = !have || yv > bv;
-            bv = gt ? yv : bv;
+        for (int s = 0; s < 4; ++s) place(s, j, yv[s]);
+        if (allrot) {
+          bv = yv[0];
+          bi = rot[0];
+#pragma unroll
+          for (int s = 1; s < 4; ++s) {
+            const bool gt = yv[s] > bv;
+            bv = gt ? yv[s] : bv;
             bi = gt ? rot[s] : bi;
-            have = true;
+          }
+        } else {
+          bool have = false;
+#pragma unroll
+          for (int s = 0; s < 4; ++s) {
+            if (rot[s] >= 0) {
+              const bool gt = !have || yv[s] > bv;
+              bv = gt ? yv[s] : bv;
+              bi = gt ? rot[s] : bi;
+              have = true;
+            }
           }
         }
         if (NQ > 1) {
