@@ -114,6 +114,7 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restri
   const int x0 = g.seg_xorg[seg] + wx * 32;
   const int out_lo = g.seg_lo[seg], out_hi = g.seg_hi[seg];
   const int y0 = (bg * NWY + wy) * g.TY;
+  const bool live = y0 < g.H;                // else: a band below the image
   const int nsteps = g.TY + 2;
   const int HW = g.H * g.W;
 
@@ -124,9 +125,9 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restri
   for (int s = 0; s < 4; ++s) rot[s] = rot_of[qi * 4 + s];
 
   // A-operand loads: lane (lc, lg) reads X[ci = 4*kstep + lg][h][x0 + 2*lc .. +1].  The address is a
-  // per-row lane pointer plus a 32-bit channel offset.  Rows outside the image are never multiplied
-  // (their MFMAs are skipped), channels beyond Cin meet zero filter taps, so both only need a valid
-  // address; pixels beyond W must read as zero (only possible when W % 32 != 0).
+  // per-row lane pointer plus a 32-bit channel offset.  Products of rows outside the image are discarded,
+  // channels beyond Cin meet zero filter taps, so both only need a valid address; pixels beyond W must
+  // read as zero (only possible when W % 32 != 0).
   const int pxa = x0 + 2 * lc;
   const bool px_ok = pxa < g.W;
   const float* xn = x + (size_t)n * g.Cin * HW + (px_ok ? pxa : 0);
@@ -172,35 +173,30 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restri
     // One 32-channel chunk: MFMAs of its eight K-steps, each slot of A refilled for the next chunk right
     // after its MFMAs, B read from LDS one K-step ahead.  The scheduling fences keep loads and LDS reads
     // where they are issued; left alone the compiler sinks them next to their first use and waits there.
-    auto chunk = [&](int c, bool mul, bool first) {
+    auto chunk = [&](int c, bool first) {
       const bool last = c + 1 == nchunk;
       const float* rp = last ? rp_nxt : rp_cur;
       const int kn = last ? 0 : (c + 1) * KC;
       if (STREAM) wload(last ? 0 : c + 1);
-      if (mul) {
-        const float* wc = STREAM ? wl_lane + (seq & 1) * CHF : wl_lane + (size_t)c * CHF;
-        float bw[2][9];
+      const float* wc = STREAM ? wl_lane + (seq & 1) * CHF : wl_lane + (size_t)c * CHF;
+      float bw[2][9];
 #pragma unroll
-        for (int u = 0; u < 9; ++u) bw[0][u] = wc[u * 16];
+      for (int u = 0; u < 9; ++u) bw[0][u] = wc[u * 16];
 #pragma unroll
-        for (int ks = 0; ks < KC; ++ks) {
-          if (ks + 1 < KC) {
+      for (int ks = 0; ks < KC; ++ks) {
+        if (ks + 1 < KC) {
 #pragma unroll
-            for (int u = 0; u < 9; ++u) bw[(ks + 1) & 1][u] = wc[(ks + 1) * 4 * 144 + u * 16];
-          }
-          __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-          for (int u = 0; u < 9; ++u) {
-            const f4 zero = f4{0.f, 0.f, 0.f, 0.f};
-            P[u][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur[ks].x, bw[ks & 1][u], first && ks == 0 ? zero : P[u][0], 0, 0, 0);
-            P[u][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur[ks].y, bw[ks & 1][u], first && ks == 0 ? zero : P[u][1], 0, 0, 0);
-          }
-          a_cur[ks] = load_a(rp, kn + ks);
-          __builtin_amdgcn_sched_barrier(0);
+          for (int u = 0; u < 9; ++u) bw[(ks + 1) & 1][u] = wc[(ks + 1) * 4 * 144 + u * 16];
         }
-      } else {
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int ks = 0; ks < KC; ++ks) a_cur[ks] = load_a(rp, kn + ks);
+        for (int u = 0; u < 9; ++u) {
+          const f4 zero = f4{0.f, 0.f, 0.f, 0.f};
+          P[u][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur[ks].x, bw[ks & 1][u], first && ks == 0 ? zero : P[u][0], 0, 0, 0);
+          P[u][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur[ks].y, bw[ks & 1][u], first && ks == 0 ? zero : P[u][1], 0, 0, 0);
+        }
+        a_cur[ks] = load_a(rp, kn + ks);
+        __builtin_amdgcn_sched_barrier(0);
       }
       if (STREAM) {
         wstore((seq + 1) & 1);
@@ -208,16 +204,25 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restri
       }
       ++seq;
     };
-    if (row_ok) {
-      chunk(0, true, true);
-      for (int c = 1; c < nchunk; ++c) chunk(c, true, false);
-    } else {
+    // A row above / below the image (first and last band only) is multiplied like any other, from the clamped
+    // row's values, and its products are then discarded: zeroing them ahead of the branch instead would put
+    // 72 register moves on every row's path.  A wave whose whole band lies below the image (the workgroup's bands
+    // need not divide H) multiplies nothing: it only keeps the workgroup's barriers and filter stages in step.
+    if (live) {
+      chunk(0, true);
+      for (int c = 1; c < nchunk; ++c) chunk(c, false);
+    } else if (STREAM) {
+      for (int c = 0; c < nchunk; ++c) {
+        wload(c + 1 == nchunk ? 0 : c + 1);
+        wstore((seq + 1) & 1);
+        __syncthreads();
+        ++seq;
+      }
+    }
+    if (!row_ok || !live) {
+      asm volatile("" ::: "memory");       // keeps this a branch
 #pragma unroll
       for (int u = 0; u < 9; ++u) { P[u][0] = f4{0.f, 0.f, 0.f, 0.f}; P[u][1] = f4{0.f, 0.f, 0.f, 0.f}; }
-      for (int c = 0; c < nchunk; ++c) chunk(c, false, false);
-      // rare path (rows above / below the image): drain its loads here, so that the hot loop's wait
-      // counters only ever see the refills issued by the hot loop itself (vmcnt(0), other counters open)
-      __builtin_amdgcn_s_waitcnt(0x0F70);
     }
 
     // ---- neighbour values across lane groups and waves --------------------------
@@ -281,16 +286,18 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restri
     int grp_r = 0;                             // any rotation of the bank (its pool group)
     bool first = true;
     auto place = [&](int s, int j, float& yfin) {
-      float t0 = 0.f, t1 = 0.f, t2 = 0.f;
+      // three taps per filter row; a sum starts from its first term (0 + v is an instruction: it is not v for v = -0)
+      float tr[3] = {0.f, 0.f, 0.f};
+      bool begun[3] = {false, false, false};
 #pragma unroll
       for (int u = 0; u < 9; ++u) {
         const int jj = j + tap_j(s, u) - 1;
         const float val = jj < 0 ? nbL[u] : jj > 7 ? nbR[u] : P[u][jj & 1][jj >> 1];
         const int ti = tap_i(s, u);
-        if (ti == 0) t0 += val;
-        else if (ti == 1) t1 += val;
-        else t2 += val;
+        tr[ti] = begun[ti] ? tr[ti] + val : val;
+        begun[ti] = true;
       }
+      const float t0 = tr[0], t1 = tr[1], t2 = tr[2];
       yfin = accA[s][j] + t2;         // rows h-2, h-1, h are in: output row h-1 done
       accA[s][j] = accB[s][j] + t1;   // output row h has rows h-1, h
       accB[s][j] = t0;                // output row h+1 has row h
@@ -322,20 +329,34 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restri
       } else {
         first = false;      // all rotations present, one pool group (channel = co)
       }
+      // all four quarter turns in the orientation set (every closed set; wave-uniform): plain compare chain
+      const bool allrot = NQ > 1 || (rot[0] | rot[1] | rot[2] | rot[3]) >= 0;
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
         float bv = 0.f;
         int bi = 0;
-        bool have = false;
+        float yv[4];
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-          float yv;
-          place(s, j, yv);
-          if (NQ > 1 || rot[s] >= 0) {          // NQ == 1: wave-uniform
-            const bool gt = !have || yv > bv;
-            bv = gt ? yv : bv;
+        for (int s = 0; s < 4; ++s) place(s, j, yv[s]);
+        if (allrot) {
+          bv = yv[0];
+          bi = rot[0];
+#pragma unroll
+          for (int s = 1; s < 4; ++s) {
+            const bool gt = yv[s] > bv;
+            bv = gt ? yv[s] : bv;
             bi = gt ? rot[s] : bi;
-            have = true;
+          }
+        } else {
+          bool have = false;
+#pragma unroll
+          for (int s = 0; s < 4; ++s) {
+            if (rot[s] >= 0) {
+              const bool gt = !have || yv[s] > bv;
+              bv = gt ? yv[s] : bv;
+              bi = gt ? rot[s] : bi;
+              have = true;
+            }
           }
         }
         if (NQ > 1) {
