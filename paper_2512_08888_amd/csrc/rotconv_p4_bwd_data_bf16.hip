@@ -26,6 +26,20 @@
 // filters): there the K-steps are split over `ksplit` workgroups per unit, each writing an fp32 partial
 // dX; a second kernel adds the partials in a fixed order and rounds to bf16 (deterministic, no atomics).
 // The split is also what keeps each workgroup's share of the filter block within LDS.
+//
+// SPARSE instances (evenly spaced closed orientation sets, r = s Q + q): after the max-pool every (pixel,
+// filter) has at most ONE non-zero quarter turn, so with the contraction index widened to (filter, quarter
+// turn) the routed gradient is a 1-of-4 structured-sparse A operand and v_smfmac_f32_16x16x64_bf16 (A: 2 kept
+// values of every 4 plus 2-bit positions; same cycles as the dense 16x16x32) does the four rotations' products
+// in one instruction: half the matrix instructions, and routing shrinks to one validity mask per value
+// plus one subtraction per destination tile.  The dense B' of destination tile d would hold F[k, ci, u_s(d)] at
+// (k, s) - nine different operands; but the taps u_s(d) of the four corner destinations are the same four corner
+// taps in rotated order (likewise the edges), so ONE operand per orbit, B''[(k, t)] = F[k, ci, t-th tap of the
+// orbit], serves its four destinations when the position stored with the value is t = (m - s*) mod 4 for
+// destination m of the orbit and winning quarter turn s*.  Operand layout of the instruction as measured on the
+// chip: A lane (row, lgA) holds pairs p = 0..3 (elements 2p, 2p+1; positions in bits 4p..4p+3 of the lane's own
+// index register, low / high half selected by ABID); pair p meets B lane (column, lgB = 2 (lgA % 2) + p / 2),
+// elements 4 jg .. 4 jg + 3 with jg = 2 (lgA / 2) + p % 2.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -45,6 +59,11 @@ typedef float f2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
 
 constexpr int CHB = 9 * 4 * 16 * 8 * 2;   // bytes of one K-step (32 filters) of a 16-channel block (9216)
+constexpr int CHBS = 2 * 3 * 64 * 32;     // the same in the sparse layout [half][orbit][lane][4 filters x 4 taps] (12288)
+typedef __bf16 bf16x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u8x __attribute__((ext_vector_type(8)));
+// destination tile of member m of an orbit (0: corners, 1: edges) = where quarter turn m puts base tap 0 / 1
+__device__ __host__ constexpr int orbit_pos(int o, int m) { return tap_i(m, o) * 3 + tap_j(m, o); }
 
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(f2{lo, hi}, bf2));
@@ -54,7 +73,8 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
 // FASTW:  W % 8 == 0 and no wave chain reaches beyond the row: no load masks, vector stores.
 // CPAD:   CoutPad > Cout: filter offsets are clamped to the last real filter (its taps are zero).
 // SPLIT:  the unit's K-steps are shared by g.ksplit workgroups; the result is an fp32 partial in `part`.
-template <int NWX, int NWY, int ND, bool FASTW, bool CPAD, bool SPLIT>
+// SPARSE: structured-sparse matrix instruction (see the head of the file); `wt` is in the sparse layout.
+template <int NWX, int NWY, int ND, bool FASTW, bool CPAD, bool SPLIT, bool SPARSE>
 __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_bwd_data_bf16(const uint16_t* __restrict__ gpool,
                                                                      const uint8_t* __restrict__ idx,
                                                                      const uint16_t* __restrict__ wt,
@@ -64,10 +84,11 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_bwd_data_bf16(const uint1
   constexpr int NW = NWX * NWY;
   constexpr int NT = 64 * NW;
   extern __shared__ __attribute__((aligned(16))) char smem_raw[];
-  char* Wl = smem_raw;                     // [kper][CHB]
+  constexpr int KB = SPARSE ? CHBS : CHB;  // bytes of one K-step of the filter block
+  char* Wl = smem_raw;                     // [kper][KB]
   const int nkc = g.CoutPad / 32;          // K-steps per bank
   const int nks = g.Q * nkc;               // K-steps per row
-  float* EL = reinterpret_cast<float*>(smem_raw + g.kper * CHB);  // [2][NW][3][16] left edges
+  float* EL = reinterpret_cast<float*>(smem_raw + g.kper * KB);  // [2][NW][3][16] left edges
   float* ER = EL + 2 * NW * 48;                                                      // right edges
 
   const int per_xcd = (g.units + 7) / 8;
@@ -82,11 +103,11 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_bwd_data_bf16(const uint1
   const int n = v / g.nbg;
 
   const int tid = threadIdx.x;
-  const char* wsrc = reinterpret_cast<const char*>(wt) + ((size_t)cib * nks + kbeg) * CHB;
+  const char* wsrc = reinterpret_cast<const char*>(wt) + ((size_t)cib * nks + kbeg) * KB;
   {
     const u4* src = reinterpret_cast<const u4*>(wsrc);
     u4* dst = reinterpret_cast<u4*>(Wl);
-    const int n16 = (kend - kbeg) * (CHB / 16);
+    const int n16 = (kend - kbeg) * (KB / 16);
     for (int i = tid; i < n16; i += NT) dst[i] = src[i];
   }
   __syncthreads();
@@ -156,7 +177,10 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_bwd_data_bf16(const uint1
       for (int j = 0; j < 8; ++j) { rg[i][j] = load_g(base, c_beg + i, j); ri[i][j] = load_i(base, c_beg + i, j); }
     __builtin_amdgcn_s_waitcnt(0x0F70);
   }
-  const char* wl_lane = Wl + lane * 16;
+  const char* wl_lane = Wl + lane * (SPARSE ? 32 : 16);
+  // sparse routing constants: an idx byte b belongs to bank q when b < 4 Q and b % Q == q, its quarter turn is b / Q
+  const int lq = g.Q == 4 ? 2 : g.Q == 2 ? 1 : 0;
+  const uint32_t keep2 = (0xffu ^ (uint32_t)((4 * g.Q - 1) ^ (g.Q - 1))) * 0x00010001u;   // all bits but the quarter turn's
 
   for (int t = 0; t < nsteps; ++t) {
     const int h = y0 - 1 + t;
@@ -171,7 +195,60 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_bwd_data_bf16(const uint1
       const int kn = last ? kbeg : ksg + ND;                // first K-step of the group being prefetched
       const int qn = kn / nkc, cn = kn % nkc;
       const uint32_t base_n = (last ? ro_nxt : ro_cur) + (uint32_t)group_of(qn) * (uint32_t)HW;
-      if (mul) {
+      if (mul && SPARSE) {
+        const int q = ksg / nkc;
+        const uint32_t q2 = (uint32_t)q * 0x00010001u;
+        const char* wc = wl_lane + (size_t)(ksg - kbeg) * CHBS;
+        u8x bw[2];
+        bw[0] = *reinterpret_cast<const u8x*>(wc);
+#pragma unroll
+        for (int i = 0; i < ND; ++i) {
+          // per filter: validity mask on the pixel pair (two instructions + and), the kept value of either tile
+          // (low / high half), the winning quarter turns packed as 2-bit fields (tile 0: bit 4p, tile 1: bit 16 + 4p)
+          uint32_t v0[8], v1[8], sw[2] = {0u, 0u};
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            const uint32_t xx = __builtin_amdgcn_perm(0u, ri[i][j], 0x0c010c00u);     // halfwords: idx of the even, odd pixel
+            const uint32_t gm = rg[i][j] & match_mask2(xx & keep2, q2);
+            v0[j] = gm & 0xffffu;
+            v1[j] = gm >> 16;
+            sw[j / 4] |= ((xx >> lq) & 0x00030003u) << (4 * (j % 4));
+          }
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int j = 0; j < 8; ++j) { rg[i][j] = load_g(base_n, cn + i, j); ri[i][j] = load_i(base_n, cn + i, j); }
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int h = 0; h < 2; ++h) {
+            // position of the kept value for destination m of an orbit: (m - s*) mod 4, all eight fields at once
+            // (4 + m - s* never borrows; the bits above a field's two land in the unused position of the zero value)
+            uint32_t pos[4];
+#pragma unroll
+            for (int m = 0; m < 4; ++m) pos[m] = ((uint32_t)m * 0x11111111u | 0x44444444u) - sw[h];
+            const bf8 a0 = __builtin_bit_cast(bf8, u4{v0[4 * h], v0[4 * h + 1], v0[4 * h + 2], v0[4 * h + 3]});
+            const bf8 a1 = __builtin_bit_cast(bf8, u4{v1[4 * h], v1[4 * h + 1], v1[4 * h + 2], v1[4 * h + 3]});
+#pragma unroll
+            for (int o = 0; o < 3; ++o) {
+              const int e = (i * 2 + h) * 3 + o;               // operand counter inside the group
+              if (e + 1 < ND * 6) bw[(e + 1) & 1] = *reinterpret_cast<const u8x*>(wc + (e + 1) * 2048);
+              __builtin_amdgcn_sched_barrier(0);
+              const bf16x16 b = __builtin_bit_cast(bf16x16, bw[e & 1]);
+              if (o < 2) {
+#pragma unroll
+                for (int m = 0; m < 4; ++m) {
+                  const int d = orbit_pos(o, m);
+                  S[d][0] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(a0, b, S[d][0], (int)pos[m], 0, 0);
+                  S[d][1] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(a1, b, S[d][1], (int)pos[m], 0, 1);
+                }
+              } else {      // centre tap: the same for every quarter turn, any position
+                S[4][0] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(a0, b, S[4][0], 0, 0, 0);
+                S[4][1] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(a1, b, S[4][1], 0, 0, 0);
+              }
+              __builtin_amdgcn_sched_barrier(0);
+            }
+          }
+        }
+      } else if (mul) {
         const int q = ksg / nkc;
         int rot[4];
 #pragma unroll
@@ -377,43 +454,91 @@ __global__ __launch_bounds__(256) void k_p4_pack_bwd_bf16(const uint16_t* __rest
   wt[e] = f32_to_bf16(acc);
 }
 
+// The same banks in the sparse layout: [16-channel block][Q][K-step][half h][orbit o][lgB][16 channels][jg][t];
+// element (jg, t) of lane (lgB, channel) is tap t of orbit o (corners R_t(0), edges R_t(1), centre for every t) of
+// the filter that the A lane (lgA = 2 (jg / 2) + lgB / 2) holds as pair p = 2 (lgB % 2) + jg % 2 of half h.
+__global__ __launch_bounds__(256) void k_p4_pack_bwd_bf16s(const uint16_t* __restrict__ w, uint16_t* __restrict__ wt,
+                                                           const int32_t* __restrict__ fq_src,
+                                                           const float* __restrict__ fq_coef, int Q, int CIB,
+                                                           int CoutPad, int Cin, int Cout) {
+  const int per_step = CHBS / 2;
+  const int total = CIB * Q * (CoutPad / 32) * per_step;
+  const int e = blockIdx.x * 256 + threadIdx.x;
+  if (e >= total) return;
+  const int t = e % 4, jg = (e / 4) % 4, n16 = (e / 16) % 16, lgB = (e / 256) % 4, o = (e / 1024) % 3, h = (e / 3072) % 2;
+  const int chunk = (e / per_step) % (CoutPad / 32);
+  const int q = (e / (per_step * (CoutPad / 32))) % Q;
+  const int cib = e / (per_step * (CoutPad / 32) * Q);
+  const int lgA = 2 * (jg / 2) + lgB / 2, pr = 2 * (lgB % 2) + jg % 2;
+  const int co = chunk * 32 + 8 * lgA + 4 * h + pr, ci = cib * 16 + n16;
+  const int u = o == 2 ? 4 : orbit_pos(o, t);
+  float acc = 0.f;
+  if (co < Cout && ci < Cin) {
+    const int slices = Cout * Cin;
+#pragma unroll
+    for (int z = 0; z < kMaxNnz; ++z) {
+      const int sr = fq_src[(q * 9 + u) * kMaxNnz + z];
+      if (sr >= 0)
+        acc += fq_coef[(q * 9 + u) * kMaxNnz + z] * bf16_to_f32(w[((sr / 9) * slices + co * Cin + ci) * 9 + sr % 9]);
+    }
+  }
+  wt[e] = f32_to_bf16(acc);
+}
+
 // filters padded to 32, or to a multiple of 64 (two K-steps in flight)
 int cout_pad(int Cout) { return Cout <= 32 ? 32 : (Cout + 63) / 64 * 64; }
 int ring_depth(int Cout) { return std::min(2, cout_pad(Cout) / 32); }
 constexpr int kResidentSteps = 16;     // K-steps whose filter block fits LDS beside the edge arrays (16 * 9216 + 8192 <= 160 KB)
+constexpr int kResidentStepsSparse = 12;   // 12 * 12288 + 8192 <= 160 KB
+
+// The structured-sparse instances need r = s Q + q for every (bank q, quarter turn s): an evenly spaced closed set.
+bool sparse_ok(const rotconv_plan* p) {
+  const int Q = p->host.Q;
+  if (Q != 1 && Q != 2 && Q != 4) return false;
+  for (int q = 0; q < Q; ++q)
+    for (int s = 0; s < 4; ++s)
+      if (p->rot_of[q * 4 + s] != s * Q + q) return false;
+  return true;
+}
 
 
-template <int NWX, int NWY, int ND, bool FASTW, bool CPAD, bool SPLIT>
+template <int NWX, int NWY, int ND, bool FASTW, bool CPAD, bool SPLIT, bool SPARSE>
 void launch_i(const P4BwdBfGeom& g, const uint16_t* gp, const uint8_t* idx, const uint16_t* wt, const int32_t* rot_of,
               uint16_t* dx, float* part, hipStream_t st) {
-  const size_t lds = (size_t)g.kper * CHB + (size_t)4 * NWX * NWY * 48 * sizeof(float);
+  const size_t lds = (size_t)g.kper * (SPARSE ? CHBS : CHB) + (size_t)4 * NWX * NWY * 48 * sizeof(float);
   const int grid = (g.units + 7) / 8 * 8;
-  auto kern = k_p4_bwd_data_bf16<NWX, NWY, ND, FASTW, CPAD, SPLIT>;
+  auto kern = k_p4_bwd_data_bf16<NWX, NWY, ND, FASTW, CPAD, SPLIT, SPARSE>;
   (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * NWX * NWY), lds, st, gp, idx, wt, rot_of, dx, part, g);
 }
 
 template <int NWX, int NWY, int ND, bool SPLIT>
-void launch_t(const P4BwdBfGeom& g, bool fastw, bool cpad, const uint16_t* gp, const uint8_t* idx,
+void launch_t(const P4BwdBfGeom& g, bool fastw, bool cpad, bool sparse, const uint16_t* gp, const uint8_t* idx,
               const uint16_t* wt, const int32_t* rot_of, uint16_t* dx, float* part, hipStream_t st) {
   // the specialised instance: whole lanes inside the row, no padded filters; everything else takes the general one
-  if (fastw && !cpad) launch_i<NWX, NWY, ND, true, false, SPLIT>(g, gp, idx, wt, rot_of, dx, part, st);
-  else launch_i<NWX, NWY, ND, false, true, SPLIT>(g, gp, idx, wt, rot_of, dx, part, st);
+  if (sparse) {
+    if (fastw && !cpad) launch_i<NWX, NWY, ND, true, false, SPLIT, true>(g, gp, idx, wt, rot_of, dx, part, st);
+    else launch_i<NWX, NWY, ND, false, true, SPLIT, true>(g, gp, idx, wt, rot_of, dx, part, st);
+  } else {
+    if (fastw && !cpad) launch_i<NWX, NWY, ND, true, false, SPLIT, false>(g, gp, idx, wt, rot_of, dx, part, st);
+    else launch_i<NWX, NWY, ND, false, true, SPLIT, false>(g, gp, idx, wt, rot_of, dx, part, st);
+  }
 }
 
 template <int NWX, int NWY>
-void launch_d(int nd, const P4BwdBfGeom& g, bool fastw, bool cpad, const uint16_t* gp, const uint8_t* idx,
+void launch_d(int nd, const P4BwdBfGeom& g, bool fastw, bool cpad, bool sparse, const uint16_t* gp, const uint8_t* idx,
               const uint16_t* wt, const int32_t* rot_of, uint16_t* dx, float* part, hipStream_t st) {
   const bool split = g.ksplit > 1;
-  if (nd == 1 && split) launch_t<NWX, NWY, 1, true>(g, fastw, cpad, gp, idx, wt, rot_of, dx, part, st);
-  else if (nd == 1) launch_t<NWX, NWY, 1, false>(g, fastw, cpad, gp, idx, wt, rot_of, dx, part, st);
-  else if (split) launch_t<NWX, NWY, 2, true>(g, fastw, cpad, gp, idx, wt, rot_of, dx, part, st);
-  else launch_t<NWX, NWY, 2, false>(g, fastw, cpad, gp, idx, wt, rot_of, dx, part, st);
+  if (nd == 1 && split) launch_t<NWX, NWY, 1, true>(g, fastw, cpad, sparse, gp, idx, wt, rot_of, dx, part, st);
+  else if (nd == 1) launch_t<NWX, NWY, 1, false>(g, fastw, cpad, sparse, gp, idx, wt, rot_of, dx, part, st);
+  else if (split) launch_t<NWX, NWY, 2, true>(g, fastw, cpad, sparse, gp, idx, wt, rot_of, dx, part, st);
+  else launch_t<NWX, NWY, 2, false>(g, fastw, cpad, sparse, gp, idx, wt, rot_of, dx, part, st);
 }
 
 // Row segments and bands as in the forward kernel (rows cut into chains of at most 256 product columns
 // that overlap by 8 pixels; a workgroup of 8 waves = nwx waves along x times 8 / nwx bands).
-int geoms(const rotconv_plan* p, P4BwdBfGeom* out, int max_out) {
+int geoms(const rotconv_plan* p, P4BwdBfGeom* out, int max_out, bool sparse) {
+  const int resident = sparse ? kResidentStepsSparse : kResidentSteps;
   P4Geom fg[4];
   const int ng = p4_fwd_geoms(p, kOutPooled, fg, 4);
   if (ng < 0 || ng > max_out) return -1;
@@ -440,7 +565,7 @@ int geoms(const rotconv_plan* p, P4BwdBfGeom* out, int max_out) {
     // buffer), at most 16 parts and 256 MiB of partial sums.
     const int nd = ring_depth(d.Cout);
     const int groups = g.Q * (g.CoutPad / 32) / nd;            // prefetch groups of nd K-steps
-    int want = std::max((int)((512 + g.units - 1) / g.units), (groups * nd + kResidentSteps - 1) / kResidentSteps);
+    int want = std::max((int)((512 + g.units - 1) / g.units), (groups * nd + resident - 1) / resident);
     const double dx_bytes = 4.0 * d.N * d.Cin * d.H * d.W;
     want = std::min({want, groups, 16, std::max(1, (int)(268435456.0 / dx_bytes))});
     const int gper = (groups + want - 1) / want;               // groups per split
@@ -457,6 +582,13 @@ int geoms(const rotconv_plan* p, P4BwdBfGeom* out, int max_out) {
   return ng;
 }
 
+// The sparse instances when the orientation set allows them and their (larger) filter share fits LDS.
+bool use_sparse(const rotconv_plan* p) {
+  if (!sparse_ok(p)) return false;
+  P4BwdBfGeom gs[4];
+  return geoms(p, gs, 4, true) >= 1 && gs[0].kper <= kResidentStepsSparse;
+}
+
 }  // namespace
 
 // Shapes of the forward kernel (even W, segmented rows need W % 32 == 0); every bank inside one pool group;
@@ -465,24 +597,32 @@ bool p4_bwd_data_bf16_supported(const rotconv_plan* p) {
   if (!p4_fwd_supported(p) || !p4_bwd_data_supported(p)) return false;
   const rotconv_desc& d = p->d;
   if (d.W > 256 && (d.W & 31)) return false;
+  if (use_sparse(p)) return true;
   P4BwdBfGeom gs[4];
-  if (geoms(p, gs, 4) < 1) return false;
+  if (geoms(p, gs, 4, false) < 1) return false;
   return gs[0].kper <= kResidentSteps;
 }
 
 // fp32 partial sums [ksplit][N][Cin][H][W] behind the packed bank (0 when the K-steps are not split)
 size_t p4_bwd_data_bf16_part_bytes(const rotconv_plan* p) {
   P4BwdBfGeom gs[4];
-  if (geoms(p, gs, 4) < 1 || gs[0].ksplit <= 1) return 0;
+  if (geoms(p, gs, 4, use_sparse(p)) < 1 || gs[0].ksplit <= 1) return 0;
   return (size_t)gs[0].ksplit * p->d.N * p->d.Cin * p->d.H * p->d.W * sizeof(float);
 }
 
 size_t p4_bwd_data_bf16_pack_bytes(const rotconv_plan* p) {
-  return (size_t)((p->d.Cin + 15) / 16) * p->host.Q * cout_pad(p->d.Cout) * 144 * sizeof(uint16_t);
+  const size_t per_step = use_sparse(p) ? CHBS : CHB;
+  return (size_t)((p->d.Cin + 15) / 16) * p->host.Q * (cout_pad(p->d.Cout) / 32) * per_step;
 }
 
 void launch_p4_pack_bwd_bf16(const rotconv_plan* p, const uint16_t* w, uint16_t* wt, hipStream_t st) {
   const int CIB = (p->d.Cin + 15) / 16, CoutPad = cout_pad(p->d.Cout);
+  if (use_sparse(p)) {
+    const int total = CIB * p->host.Q * (CoutPad / 32) * (CHBS / 2);
+    hipLaunchKernelGGL(k_p4_pack_bwd_bf16s, dim3((total + 255) / 256), dim3(256), 0, st, w, wt, p->dev.fq_src,
+                       p->dev.fq_coef, p->host.Q, CIB, CoutPad, p->d.Cin, p->d.Cout);
+    return;
+  }
   const int total = CIB * p->host.Q * CoutPad * 144;
   hipLaunchKernelGGL(k_p4_pack_bwd_bf16, dim3((total + 255) / 256), dim3(256), 0, st, w, wt, p->dev.fq_src,
                      p->dev.fq_coef, p->host.Q, CIB, CoutPad, p->d.Cin, p->d.Cout);
@@ -492,17 +632,18 @@ void launch_p4_pack_bwd_bf16(const rotconv_plan* p, const uint16_t* w, uint16_t*
 void launch_p4_bwd_data_bf16(const rotconv_plan* p, const uint16_t* gpool, const uint8_t* idx, const uint16_t* wt,
                              uint16_t* dx, float* part, hipStream_t st) {
   P4BwdBfGeom gs[4];
-  const int ng = geoms(p, gs, 4);
+  const bool sparse = use_sparse(p);
+  const int ng = geoms(p, gs, 4, sparse);
   const int nd = ring_depth(p->d.Cout);
   for (int i = 0; i < ng; ++i) {
     const P4BwdBfGeom& g = gs[i];
     const bool fastw = (p->d.W & 7) == 0 && g.inside;
     const bool cpad = g.CoutPad != p->d.Cout;
     switch (g.nwx) {
-      case 1: launch_d<1, 8>(nd, g, fastw, cpad, gpool, idx, wt, p->dev.rot_of, dx, part, st); break;
-      case 2: launch_d<2, 4>(nd, g, fastw, cpad, gpool, idx, wt, p->dev.rot_of, dx, part, st); break;
-      case 4: launch_d<4, 2>(nd, g, fastw, cpad, gpool, idx, wt, p->dev.rot_of, dx, part, st); break;
-      default: launch_d<8, 1>(nd, g, fastw, cpad, gpool, idx, wt, p->dev.rot_of, dx, part, st); break;
+      case 1: launch_d<1, 8>(nd, g, fastw, cpad, sparse, gpool, idx, wt, p->dev.rot_of, dx, part, st); break;
+      case 2: launch_d<2, 4>(nd, g, fastw, cpad, sparse, gpool, idx, wt, p->dev.rot_of, dx, part, st); break;
+      case 4: launch_d<4, 2>(nd, g, fastw, cpad, sparse, gpool, idx, wt, p->dev.rot_of, dx, part, st); break;
+      default: launch_d<8, 1>(nd, g, fastw, cpad, sparse, gpool, idx, wt, p->dev.rot_of, dx, part, st); break;
     }
   }
   if (ng > 0 && gs[0].ksplit > 1) {
