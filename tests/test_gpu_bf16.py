@@ -40,6 +40,9 @@ CASES = [
     LC("b_r8_fold2", N=1, Cin=40, H=9, W=64, Cout=20, R=8, mode="bilinear", seed=71),          # two banks in one wave
     LC("b_r16_fold4_w40", N=2, Cin=64, H=7, W=40, Cout=10, R=16, mode="steerable", x_dist="absnormal", seed=72),
     LC("b_r1", N=1, Cin=24, H=9, W=32, Cout=40, R=1, seed=68),                                 # a standard convolution
+    # orientation sets without all four quarter turns per bank: the dense input-gradient instances
+    LC("b_p4m", N=1, Cin=24, H=9, W=32, Cout=40, R=8, mode="p4m", seed=73),
+    LC("b_r2", N=1, Cin=16, H=8, W=32, Cout=80, R=2, seed=74),
 ]
 
 
