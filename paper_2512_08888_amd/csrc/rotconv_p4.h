@@ -55,9 +55,9 @@ struct P4BwdGeom {
   int px;      // pixels per lane (2 or 4)
   int nstrip;  // strips of 16 * px pixels per row
   int nrb;     // blocks of 8 rows
-  int qsplit;  // workgroups that share a unit's banks (each writes an fp32 partial dX); 1 = no split
-  int qper;    // banks per such workgroup
-  int units;   // workgroups with work (includes the bank split)
+  int ksplit;  // workgroups that share a unit's contraction (each writes an fp32 partial dX); 1 = no split
+  int kper;    // weight chunks (16 filters of a bank) per such workgroup
+  int units;   // workgroups with work (includes the split)
 };
 bool p4_bwd_data_supported(const rotconv_plan* p);
 P4BwdGeom p4_bwd_data_geom(const rotconv_plan* p);

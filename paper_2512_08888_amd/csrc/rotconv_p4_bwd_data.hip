@@ -65,10 +65,14 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gp
   const int per_xcd = (g.units + 7) / 8;
   int v = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
   if (v >= g.units) return;
-  // Banks [q0, q1) of this workgroup: layers with few (row block, strip, channel group) units share their banks
-  // out over qsplit workgroups, each writing an fp32 partial dX that k_p4_sum_dx adds in order.
-  const int qs = v % g.qsplit; v /= g.qsplit;
-  const int q0 = qs * g.qper, q1 = min(g.Q, q0 + g.qper);
+  // Weight chunks (16 filters of a bank) [c0, c1) of this workgroup: layers with few (row block, strip, channel
+  // group) units share their contraction out over ksplit workgroups, each writing an fp32 partial dX that
+  // k_p4_sum_dx adds in order.
+  const int cpb = g.CoutPad / CHUNK;           // chunks per bank
+  const int ksp = v % g.ksplit; v /= g.ksplit;
+  const int c0 = ksp * g.kper, c1 = min(g.Q * cpb, c0 + g.kper);
+  const int q0 = c0 / cpb, co0 = (c0 % cpb) * CHUNK;      // first K-step: bank, filter
+  const int q1 = (c1 - 1) / cpb + 1;                       // banks [q0, q1); the cursors never leave them
   const int cig = v % g.ncig; v /= g.ncig;
   const int strip = v % g.nstrip; v /= g.nstrip;
   const int rb = v % g.nrb;
@@ -81,9 +85,8 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gp
   const int x0 = strip * 16 * PX;
   const bool active = h < g.H;
   const int HW = g.H * g.W;
-  const int nkq = g.CoutPad / 4;               // K-steps per bank
-  const int nk = (q1 - q0) * nkq;              // K-steps of this workgroup
-  const int cbase = q0 * (g.CoutPad / CHUNK);  // its first weight chunk
+  const int nk = (c1 - c0) * (CHUNK / 4);      // K-steps of this workgroup
+  const int cbase = c0;                        // its first weight chunk
   const int nchunks = nk / 4;
 
   // ---- weight chunk streaming -----------------------------------------------------
@@ -149,7 +152,7 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gp
     return r0 % g.ng;
   };
   // load cursor: K-step (bank, first filter) that the next raw_load fetches; it stops on the last K-step
-  int ld_q = q0, ld_co = 0, ld_pg;
+  int ld_q = q0, ld_co = co0, ld_pg;
   {
     int r[4];
     bank_rot(q0, r);
@@ -223,7 +226,7 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gp
   Raw<PX> rawA, rawB;
   float aA[9][PX], aB[9][PX];
   int rotb[4];                      // orientations of the bank of the K-step being built
-  int bd_q = q0, bd_co = 0;         // build cursor
+  int bd_q = q0, bd_co = co0;       // build cursor
   bank_rot(q0, rotb);
   auto stage = [&](int ks, const float* wl, const Raw<PX>& raw_use, Raw<PX>& raw_ld, const float (&a_cur)[9][PX],
                    float (&a_nxt)[9][PX]) {
@@ -288,7 +291,7 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gp
     const int ci = cig * CIG + cb * 16 + lc;
     if (ci >= g.Cin) continue;
     const int px = x0 + 4 * PX * lg;
-    float* o = dx + (((size_t)qs * g.N + n) * g.Cin + ci) * HW + (size_t)h * g.W + px;   // qs > 0 only in the partial buffer
+    float* o = dx + (((size_t)ksp * g.N + n) * g.Cin + ci) * HW + (size_t)h * g.W + px;   // ksp > 0 only in the partial buffer
     float vals[4 * PX];
 #pragma unroll
     for (int j = 0; j < 4 * PX; ++j) vals[j] = acc[cb][j % PX][j / PX];
@@ -367,23 +370,24 @@ P4BwdGeom p4_bwd_data_geom(const rotconv_plan* p) {
   g.px = ((d.W & 3) == 0 && d.W > 32 && d.N * g.ncig * g.nrb * ((d.W + 63) / 64) >= 256) ? 4 : 2;
   g.nstrip = (d.W + 16 * g.px - 1) / (16 * g.px);
   g.units = d.N * g.ncig * g.nstrip * g.nrb;
-  // Few units and several banks: share the banks out so that the chip is filled about twice (at most 256 MiB of
-  // partial sums).
-  g.qsplit = 1;
-  if (g.units < 256 && g.Q > 1) {
+  // Few units and a long contraction: share its weight chunks (16 filters of a bank) out so that the chip is filled
+  // about twice; at least 8 chunks per workgroup, at most 256 MiB of partial sums.
+  const int chunks = g.Q * (g.CoutPad / CHUNK);
+  g.ksplit = 1;
+  if (g.units < 256 && chunks >= 16) {
     const double dx_bytes = 4.0 * d.N * d.Cin * d.H * d.W;
-    const int want = std::min({g.Q, (512 + g.units - 1) / g.units, std::max(1, (int)(268435456.0 / dx_bytes))});
-    g.qper = (g.Q + want - 1) / want;
-    g.qsplit = (g.Q + g.qper - 1) / g.qper;
+    const int want = std::min({chunks / 8, (512 + g.units - 1) / g.units, std::max(1, (int)(268435456.0 / dx_bytes))});
+    g.kper = (chunks + want - 1) / want;
+    g.ksplit = (chunks + g.kper - 1) / g.kper;
   }
-  if (g.qsplit == 1) g.qper = g.Q;
-  g.units *= g.qsplit;
+  if (g.ksplit == 1) g.kper = chunks;
+  g.units *= g.ksplit;
   return g;
 }
 
 size_t p4_bwd_data_part_floats(const rotconv_plan* p) {
   const P4BwdGeom g = p4_bwd_data_geom(p);
-  return g.qsplit > 1 ? (size_t)g.qsplit * p->d.N * p->d.Cin * p->d.H * p->d.W : 0;
+  return g.ksplit > 1 ? (size_t)g.ksplit * p->d.N * p->d.Cin * p->d.H * p->d.W : 0;
 }
 
 size_t p4_bwd_data_pack_floats(const rotconv_plan* p) {
@@ -401,7 +405,7 @@ void launch_p4_pack_bwd(const rotconv_plan* p, const float* w, float* wd, hipStr
 void launch_p4_bwd_data(const rotconv_plan* p, const float* gpool, const uint8_t* idx, const float* wd, float* dx_out,
                         float* part, hipStream_t st) {
   const P4BwdGeom g = p4_bwd_data_geom(p);
-  float* dx = g.qsplit > 1 ? part : dx_out;
+  float* dx = g.ksplit > 1 ? part : dx_out;
   const size_t lds = (size_t)2 * CHUNK * WROW * sizeof(float);
   const int grid = (g.units + 7) / 8 * 8;
   if (g.px == 4) {
@@ -413,10 +417,10 @@ void launch_p4_bwd_data(const rotconv_plan* p, const float* gpool, const uint8_t
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     hipLaunchKernelGGL(k_p4_bwd_data<2>, dim3(grid), dim3(NT), lds, st, gpool, idx, wd, p->dev.rot_of, dx, g);
   }
-  if (g.qsplit > 1) {
+  if (g.ksplit > 1) {
     const size_t n_elem = (size_t)p->d.N * p->d.Cin * p->d.H * p->d.W;
     const unsigned blocks = (unsigned)std::max<size_t>(1, std::min<size_t>((n_elem / 4 + 255) / 256, 1u << 16));
-    hipLaunchKernelGGL(k_p4_sum_dx, dim3(blocks), dim3(256), 0, st, part, dx_out, n_elem, g.qsplit);
+    hipLaunchKernelGGL(k_p4_sum_dx, dim3(blocks), dim3(256), 0, st, part, dx_out, n_elem, g.ksplit);
   }
 }
 

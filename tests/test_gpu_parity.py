@@ -64,6 +64,10 @@ TINY = [
     LC("t_w4", N=2, Cin=5, H=10, W=4, Cout=6, R=4, seed=39),
     LC("t_w44", N=1, Cin=3, H=7, W=44, Cout=4, R=4, seed=40),
     LC("t_w20_cout72", N=1, Cin=40, H=8, W=20, Cout=72, R=4, seed=41),
+    # long contraction on a small map: the input gradient shares its filter chunks out over workgroups, the parts
+    # starting inside a bank (17 chunks of one bank in two parts; 2 x 13 chunks in three)
+    LC("t_ksplit_q1", N=1, Cin=24, H=8, W=32, Cout=272, R=4, seed=48),
+    LC("t_ksplit_q2", N=1, Cin=16, H=6, W=32, Cout=200, R=8, mode="bilinear", seed=49),
 ]
 
 
