@@ -118,12 +118,13 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_bwd_data_bf16(const uint1
   const int x0 = g.seg_xorg[seg] + wx * 32;
   const int out_lo = g.seg_lo[seg], out_hi = g.seg_hi[seg];
   const int y0 = (bg * NWY + wy) * g.TY;
+  const bool live = y0 < g.H;                // else: a band below the image
   const int nsteps = g.TY + 2;
   const int HW = g.H * g.W;
 
   // (G, idx) loads: lane (lc, lg) reads the pixel pair x0 + 2*lc .. +1 of filter co = 32*chunk + 8*lg + j,
-  // j = 0..7, in the pooled plane co*ng + (pool group of the bank).  Rows outside the image are never
-  // multiplied, filters beyond Cout meet zero taps, so both only need a valid address; pixels beyond W
+  // j = 0..7, in the pooled plane co*ng + (pool group of the bank).  Products of rows outside the image are
+  // discarded, filters beyond Cout meet zero taps, so both only need a valid address; pixels beyond W
   // must read as zero gradient (only when W % 32 != 0).
   const int pxa = x0 + 2 * lc;
   const bool px_ok = pxa < g.W;
@@ -186,16 +187,21 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_bwd_data_bf16(const uint1
     const int h = y0 - 1 + t;
     const bool row_ok = h >= 0 && h < g.H;
     const uint32_t ro_cur = row_off(t), ro_nxt = row_off(t + 1);
-    f4 S[9][2];      // S_d of this row: tile b holds pixels 2m+b
+    // S_d of this row: tile b holds pixels 2m+b.  Sparse instances: written by the row's first group (accumulator
+    // input = 0); dense instances (quarter turns may be absent, so no product is known to come first): zeroed here.
+    f4 S[9][2];
+    const f4 zero4 = f4{0.f, 0.f, 0.f, 0.f};
+    if (!SPARSE) {
 #pragma unroll
-    for (int d = 0; d < 9; ++d) { S[d][0] = f4{0.f, 0.f, 0.f, 0.f}; S[d][1] = f4{0.f, 0.f, 0.f, 0.f}; }
+      for (int d = 0; d < 9; ++d) { S[d][0] = zero4; S[d][1] = zero4; }
+    }
 
-    auto group = [&](int ksg, bool mul) {
+    auto group = [&](int ksg, bool first) {
       const bool last = ksg + ND == kend;
       const int kn = last ? kbeg : ksg + ND;                // first K-step of the group being prefetched
       const int qn = kn / nkc, cn = kn % nkc;
       const uint32_t base_n = (last ? ro_nxt : ro_cur) + (uint32_t)group_of(qn) * (uint32_t)HW;
-      if (mul && SPARSE) {
+      if (SPARSE) {
         const int q = ksg / nkc;
         const uint32_t q2 = (uint32_t)q * 0x00010001u;
         const char* wc = wl_lane + (size_t)(ksg - kbeg) * CHBS;
@@ -233,22 +239,23 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_bwd_data_bf16(const uint1
               if (e + 1 < ND * 6) bw[(e + 1) & 1] = *reinterpret_cast<const u8x*>(wc + (e + 1) * 2048);
               __builtin_amdgcn_sched_barrier(0);
               const bf16x16 b = __builtin_bit_cast(bf16x16, bw[e & 1]);
+              const bool init = first && i == 0 && h == 0;     // the row's first product into these tiles
               if (o < 2) {
 #pragma unroll
                 for (int m = 0; m < 4; ++m) {
                   const int d = orbit_pos(o, m);
-                  S[d][0] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(a0, b, S[d][0], (int)pos[m], 0, 0);
-                  S[d][1] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(a1, b, S[d][1], (int)pos[m], 0, 1);
+                  S[d][0] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(a0, b, init ? zero4 : S[d][0], (int)pos[m], 0, 0);
+                  S[d][1] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(a1, b, init ? zero4 : S[d][1], (int)pos[m], 0, 1);
                 }
               } else {      // centre tap: the same for every quarter turn, any position
-                S[4][0] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(a0, b, S[4][0], 0, 0, 0);
-                S[4][1] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(a1, b, S[4][1], 0, 0, 0);
+                S[4][0] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(a0, b, init ? zero4 : S[4][0], 0, 0, 0);
+                S[4][1] = __builtin_amdgcn_smfmac_f32_16x16x64_bf16(a1, b, init ? zero4 : S[4][1], 0, 0, 0);
               }
               __builtin_amdgcn_sched_barrier(0);
             }
           }
         }
-      } else if (mul) {
+      } else {
         const int q = ksg / nkc;
         int rot[4];
 #pragma unroll
@@ -301,18 +308,18 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_bwd_data_bf16(const uint1
             __builtin_amdgcn_sched_barrier(0);
           }
         }
-      } else {
-#pragma unroll
-        for (int i = 0; i < ND; ++i)
-#pragma unroll
-          for (int j = 0; j < 8; ++j) { rg[i][j] = load_g(base_n, cn + i, j); ri[i][j] = load_i(base_n, cn + i, j); }
       }
     };
-    if (row_ok) {
-      for (int ksg = kbeg; ksg < kend; ksg += ND) group(ksg, true);
-    } else {
-      for (int ksg = kbeg; ksg < kend; ksg += ND) group(ksg, false);
-      __builtin_amdgcn_s_waitcnt(0x0F70);   // rare path: drain its loads so the hot loop's wait counts stay exact
+    // A row above / below the image (first and last band only) is multiplied like any other, from the clamped row's
+    // values, and its products are then discarded; a wave whose whole band lies below the image multiplies nothing.
+    if (live) {
+      group(kbeg, true);
+      for (int ksg = kbeg + ND; ksg < kend; ksg += ND) group(ksg, false);
+    }
+    if (!row_ok || !live) {
+      asm volatile("" ::: "memory");       // keeps this a branch
+#pragma unroll
+      for (int d = 0; d < 9; ++d) { S[d][0] = zero4; S[d][1] = zero4; }
     }
 
     // ---- neighbour values across lane groups and waves --------------------------
