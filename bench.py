@@ -195,8 +195,10 @@ def main_unet(args):
         "vs_baseline": None, "dtype": args.dtype, "data": "synthetic", "config": r,
         "roofline": {"bound": "mfma",
                      "kernel": "all rotation-convolution calls of the step (fwd, bwd_data, bwd_weight; 18 layers)",
-                     "achieved": r["rotconv_tflops_algorithmic"], "peak": PEAK_FP32_TFLOPS, "unit": "TFLOP/s",
-                     "frac": r["rotconv_tflops_algorithmic"] / PEAK_FP32_TFLOPS, "traffic": None},
+                     "achieved": r["rotconv_tflops_algorithmic"],
+                     "peak": PEAK_BF16_TFLOPS if args.dtype == "bf16" else PEAK_FP32_TFLOPS, "unit": "TFLOP/s",
+                     "frac": r["rotconv_tflops_algorithmic"] / (PEAK_BF16_TFLOPS if args.dtype == "bf16" else PEAK_FP32_TFLOPS),
+                     "traffic": None},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline_unet(args.workload)
@@ -214,6 +216,9 @@ def main():
     ap.add_argument("--pool-op", default="max", choices=["max", "avg"],
                     help="orientation pooling of the single-layer workloads: max (Eq. 10, the benchmark) or average "
                          "(Eq. 9: one ordinary convolution with the group-averaged bank)")
+    ap.add_argument("--group", default=None, choices=["p4m8"],
+                    help="single-layer workloads: run the layer's shape with another orientation group; p4m8 = four "
+                         "quarter turns of the filter and of its mirror image (R = 8, one pool group)")
     ap.add_argument("--no-unet", action="store_true", help="skip the UNet-shaped steps appended to the default line")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -237,6 +242,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     cfg = synth.CONFIGS[args.workload]
+    if args.group == "p4m8":
+        import dataclasses
+        cfg = dataclasses.replace(cfg, name=cfg.name + "_p4m8", R=8, mode="p4m", angles_deg=None, pool_group=None)
     bf = args.dtype == "bf16"
     adt = torch.bfloat16 if bf else torch.float32      # storage of x, w, g, ypool, dx; dw is fp32 either way
     plan = rc.Plan.from_config(cfg, dtype=rc.BF16 if bf else rc.F32, pool_op=args.pool_op)
@@ -285,14 +293,16 @@ def main():
     pass_ms = [sum(events[s][i].elapsed_time(events[s][i + 1]) for s in range(args.steps)) / args.steps
                for i in range(3)]
     names = ["rotconv_pool_fwd", "rotconv_pool_bwd_data", "rotconv_pool_bwd_weight"]
-    fa, fd = flops_alg(cfg, Q), flops_dense(cfg)
+    # p4m: the paper's count is ONE conv-equivalent for the eight filters (the products of the base filter placed at
+    # eight position maps); the kernels execute two (the mirror image is a second bank)
+    fa, fd = flops_alg(cfg, 1 if args.group == "p4m8" else Q), flops_dense(cfg)
     if avg:     # the mean commutes with the convolution: one conv-equivalent per pooled channel, no placement adds
         fa = 2.0 * cfg.N * cfg.Ho * cfg.Wo * cfg.Cin * plan.Cpooled * cfg.k * cfg.k
     dom = max(range(3), key=lambda i: pass_ms[i])
     achieved = fa / (pass_ms[dom] * 1e-3) / 1e12
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
-    if os.path.exists(tpath):
+    if os.path.exists(tpath) and not args.group:
         try:
             traffic = json.load(open(tpath)).get(f"{args.workload}:{names[dom]}:{plan.kernel_name(dom)}")   # fp32 kernels only
         except Exception:
@@ -318,7 +328,7 @@ def main():
     }
     if not args.no_cpu_baseline and not avg:
         out["cpu_baseline"] = cpu_baseline(cfg, Q)
-    if args.workload == "C2" and not args.no_unet and not bf and not avg:
+    if args.workload == "C2" and not args.no_unet and not bf and not avg and not args.group:
         # the second half of the headline metric: ms per UNet-shaped training step at R=4 and R=16
         del x, w, g, yp, idx, dx, dw
         out["unet_train_step"] = {n: bench_unet(n, 5, 2) for n in ("C4", "C5")}
