@@ -74,6 +74,7 @@ struct P4BwdBfGeom {
   int N, Cin, CIB, H, W, Cout, CoutPad, Q, ng;   // CIB: 16-channel blocks; CoutPad: filters padded to K-steps of 32
   int TY, nbg, units, nwx, nseg, inside;         // as in P4Geom (units include the K split)
   int ksplit, kper;                              // workgroups sharing a unit's K-steps; K-steps per workgroup
+  int bank_major;                                // sparse instances: orientations numbered r = 4 q + s instead of r = s Q + q
   int seg_xorg[4], seg_lo[4], seg_hi[4];
 };
 bool p4_bwd_data_bf16_supported(const rotconv_plan* p);

@@ -27,7 +27,7 @@
 // dX; a second kernel adds the partials in a fixed order and rounds to bf16 (deterministic, no atomics).
 // The split is also what keeps each workgroup's share of the filter block within LDS.
 //
-// SPARSE instances (evenly spaced closed orientation sets, r = s Q + q): after the max-pool every (pixel,
+// SPARSE instances (every bank with its four quarter turns, orientations numbered r = s Q + q or r = 4 q + s): after the max-pool every (pixel,
 // filter) has at most ONE non-zero quarter turn, so with the contraction index widened to (filter, quarter
 // turn) the routed gradient is a 1-of-4 structured-sparse A operand and v_smfmac_f32_16x16x64_bf16 (A: 2 kept
 // values of every 4 plus 2-bit positions; same cycles as the dense 16x16x32) does the four rotations' products
@@ -179,9 +179,11 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_bwd_data_bf16(const uint1
     __builtin_amdgcn_s_waitcnt(0x0F70);
   }
   const char* wl_lane = Wl + lane * (SPARSE ? 32 : 16);
-  // sparse routing constants: an idx byte b belongs to bank q when b < 4 Q and b % Q == q, its quarter turn is b / Q
-  const int lq = g.Q == 4 ? 2 : g.Q == 2 ? 1 : 0;
-  const uint32_t keep2 = (0xffu ^ (uint32_t)((4 * g.Q - 1) ^ (g.Q - 1))) * 0x00010001u;   // all bits but the quarter turn's
+  // sparse routing constants.  Interleaved banks (r = s Q + q): an idx byte b belongs to bank q when b < 4 Q and
+  // b % Q == q, its quarter turn is b / Q.  Bank-major (r = 4 q + s): bank b / 4, quarter turn b % 4.
+  const int lq = g.bank_major ? 0 : g.Q == 4 ? 2 : g.Q == 2 ? 1 : 0;
+  const uint32_t keep2 = (0xffu ^ (3u << lq)) * 0x00010001u;             // all idx bits but the quarter turn's
+  const uint32_t qmul = (g.bank_major ? 4u : 1u) * 0x00010001u;         // what those bits read for bank 1
 
   for (int t = 0; t < nsteps; ++t) {
     const int h = y0 - 1 + t;
@@ -203,7 +205,7 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_bwd_data_bf16(const uint1
       const uint32_t base_n = (last ? ro_nxt : ro_cur) + (uint32_t)group_of(qn) * (uint32_t)HW;
       if (SPARSE) {
         const int q = ksg / nkc;
-        const uint32_t q2 = (uint32_t)q * 0x00010001u;
+        const uint32_t q2 = (uint32_t)q * qmul;
         const char* wc = wl_lane + (size_t)(ksg - kbeg) * CHBS;
         u8x bw[2];
         bw[0] = *reinterpret_cast<const u8x*>(wc);
@@ -498,15 +500,20 @@ int ring_depth(int Cout) { return std::min(2, cout_pad(Cout) / 32); }
 constexpr int kResidentSteps = 16;     // K-steps whose filter block fits LDS beside the edge arrays (16 * 9216 + 8192 <= 160 KB)
 constexpr int kResidentStepsSparse = 12;   // 12 * 12288 + 8192 <= 160 KB
 
-// The structured-sparse instances need r = s Q + q for every (bank q, quarter turn s): an evenly spaced closed set.
-bool sparse_ok(const rotconv_plan* p) {
+// The structured-sparse instances need every bank's four quarter turns and a regular numbering of the orientations:
+// 1 = interleaved, r = s Q + q (an evenly spaced closed set), 2 = bank-major, r = 4 q + s (p4m); 0 = neither.
+int sparse_order(const rotconv_plan* p) {
   const int Q = p->host.Q;
-  if (Q != 1 && Q != 2 && Q != 4) return false;
+  if (Q != 1 && Q != 2 && Q != 4) return 0;
+  bool inter = true, major = true;
   for (int q = 0; q < Q; ++q)
-    for (int s = 0; s < 4; ++s)
-      if (p->rot_of[q * 4 + s] != s * Q + q) return false;
-  return true;
+    for (int s = 0; s < 4; ++s) {
+      inter = inter && p->rot_of[q * 4 + s] == s * Q + q;
+      major = major && p->rot_of[q * 4 + s] == 4 * q + s;
+    }
+  return inter ? 1 : major ? 2 : 0;
 }
+bool sparse_ok(const rotconv_plan* p) { return sparse_order(p) != 0; }
 
 
 template <int NWX, int NWY, int ND, bool FASTW, bool CPAD, bool SPLIT, bool SPARSE>
@@ -554,7 +561,7 @@ int geoms(const rotconv_plan* p, P4BwdBfGeom* out, int max_out, bool sparse) {
     P4BwdBfGeom& g = out[i];
     g = P4BwdBfGeom{};
     g.N = d.N; g.Cin = d.Cin; g.CIB = (d.Cin + 15) / 16; g.H = d.H; g.W = d.W; g.Cout = d.Cout;
-    g.CoutPad = cout_pad(d.Cout); g.Q = p->host.Q; g.ng = p->ng;
+    g.CoutPad = cout_pad(d.Cout); g.Q = p->host.Q; g.ng = p->ng; g.bank_major = sparse_order(p) == 2;
     g.nwx = fg[i].nwx; g.nseg = fg[i].nseg; g.inside = fg[i].inside;
     for (int k = 0; k < 4; ++k) { g.seg_xorg[k] = fg[i].seg_xorg[k]; g.seg_lo[k] = fg[i].seg_lo[k]; g.seg_hi[k] = fg[i].seg_hi[k]; }
     const int nwy = 8 / g.nwx;
