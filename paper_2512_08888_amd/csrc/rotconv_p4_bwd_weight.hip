@@ -465,6 +465,18 @@ __global__ __launch_bounds__(256) void k_p4_sum_splits(const float* __restrict__
   }
 }
 
+// The same sum for large images (many elements, few splits): one thread per four elements adds the splits in
+// ascending order, every access a full 16-byte lane access.
+__global__ __launch_bounds__(256) void k_p4_sum_splits_wide(const float* __restrict__ partial, float* __restrict__ out,
+                                                            int n4, int splits) {
+  const int e = blockIdx.x * 256 + threadIdx.x;
+  if (e >= n4) return;
+  const f4* src = reinterpret_cast<const f4*>(partial);
+  f4 s = src[e];
+  for (int sp = 1; sp < splits; ++sp) s += src[(size_t)sp * n4 + e];
+  reinterpret_cast<f4*>(out)[e] = s;
+}
+
 // Stage 2: the transposed first-quadrant expansion (Eq. 16 / adjoint of Eq. 17):
 // dw[b][co][ci][ub] = sum_z coef_z * dF[q_z][t_z][co][ci].
 __global__ __launch_bounds__(256) void k_p4_reduce_w(const float* __restrict__ dF, float* __restrict__ dw,
@@ -472,18 +484,22 @@ __global__ __launch_bounds__(256) void k_p4_reduce_w(const float* __restrict__ d
                                                      const int32_t* __restrict__ fqt_col,
                                                      const float* __restrict__ fqt_coef, int B, int Cout, int Cin,
                                                      int CoutPad, int CinPad) {
-  const int total = B * 9 * Cout * Cin;
+  // one thread per (bank, filter, channel): its nine taps are nine consecutive floats of dw
+  const int total = B * Cout * Cin;
   const int e = blockIdx.x * 256 + threadIdx.x;
   if (e >= total) return;
   const int ci = e % Cin;
   const int co = (e / Cin) % Cout;
-  const int ub = (e / (Cin * Cout)) % 9;
-  const int b = e / (Cin * Cout * 9);
+  const int b = e / (Cin * Cout);
   const size_t plane = (size_t)CoutPad * CinPad;
-  float acc = 0.f;
-  for (int z = fqt_ptr[b * 9 + ub]; z < fqt_ptr[b * 9 + ub + 1]; ++z)
-    acc += fqt_coef[z] * dF[(size_t)fqt_col[z] * plane + (size_t)co * CinPad + ci];
-  dw[(((size_t)b * Cout + co) * Cin + ci) * 9 + ub] = acc;
+  const float* src = dF + (size_t)co * CinPad + ci;
+  float* dst = dw + (size_t)e * 9;
+#pragma unroll
+  for (int ub = 0; ub < 9; ++ub) {
+    float acc = 0.f;
+    for (int z = fqt_ptr[b * 9 + ub]; z < fqt_ptr[b * 9 + ub + 1]; ++z) acc += fqt_coef[z] * src[(size_t)fqt_col[z] * plane];
+    dst[ub] = acc;
+  }
 }
 
 }  // namespace
@@ -527,18 +543,29 @@ size_t p4_bwd_weight_ws_floats(const rotconv_plan* p) {
   return (size_t)(g.splits + 1) * g.Q * 9 * g.CoutPad * g.CinPad;  // partial sums + their total
 }
 
+// partial sums of the splits -> dF (fixed order) -> dw through the transposed expansion
+static void finish_dw(const rotconv_plan* p, const P4BwdWGeom& g, float* partial, float* dw, hipStream_t st) {
+  const int n_elem = g.Q * 9 * g.CoutPad * g.CinPad;      // a multiple of 16
+  float* dF = partial;                                     // a single split is the sum
+  if (g.splits > 1) {
+    dF = partial + (size_t)g.splits * n_elem;
+    if (n_elem >= (1 << 18))
+      hipLaunchKernelGGL(k_p4_sum_splits_wide, dim3((n_elem / 4 + 255) / 256), dim3(256), 0, st, partial, dF, n_elem / 4, g.splits);
+    else
+      hipLaunchKernelGGL(k_p4_sum_splits, dim3((n_elem + 31) / 32), dim3(256), 0, st, partial, dF, n_elem, g.splits);
+  }
+  const int total = p->B * g.Cout * g.Cin;
+  hipLaunchKernelGGL(k_p4_reduce_w, dim3((total + 255) / 256), dim3(256), 0, st, dF, dw, p->dev.fqt_ptr,
+                     p->dev.fqt_col, p->dev.fqt_coef, p->B, g.Cout, g.Cin, g.CoutPad, g.CinPad);
+}
+
 void launch_p4_bwd_weight(const rotconv_plan* p, const float* x, const float* gpool, const uint8_t* idx,
                           float* partial, float* dw, hipStream_t st) {
   const P4BwdWGeom g = p4_bwd_weight_geom(p);
   const int grid = g.splits * g.ncig * g.ncog;
   if (g.ncb == 1) hipLaunchKernelGGL(k_p4_bwd_weight<1>, dim3(grid), dim3(NT), 0, st, x, gpool, idx, p->dev.rot_of, partial, g);
   else hipLaunchKernelGGL(k_p4_bwd_weight<4>, dim3(grid), dim3(NT), 0, st, x, gpool, idx, p->dev.rot_of, partial, g);
-  const int n_elem = g.Q * 9 * g.CoutPad * g.CinPad;
-  float* dF = partial + (size_t)g.splits * n_elem;
-  hipLaunchKernelGGL(k_p4_sum_splits, dim3((n_elem + 31) / 32), dim3(256), 0, st, partial, dF, n_elem, g.splits);
-  const int total = p->B * 9 * g.Cout * g.Cin;
-  hipLaunchKernelGGL(k_p4_reduce_w, dim3((total + 255) / 256), dim3(256), 0, st, dF, dw, p->dev.fqt_ptr,
-                     p->dev.fqt_col, p->dev.fqt_coef, p->B, g.Cout, g.Cin, g.CoutPad, g.CinPad);
+  finish_dw(p, g, partial, dw, st);
 }
 
 void launch_p4_bwd_weight_bf16(const rotconv_plan* p, const uint16_t* x, const uint16_t* gpool, const uint8_t* idx,
@@ -547,12 +574,7 @@ void launch_p4_bwd_weight_bf16(const rotconv_plan* p, const uint16_t* x, const u
   const int grid = g.splits * g.ncig * g.ncog;
   if (g.ncb == 1) hipLaunchKernelGGL(k_p4_bwd_weight_bf16<1>, dim3(grid), dim3(NT), 0, st, x, gpool, idx, p->dev.rot_of, partial, g);
   else hipLaunchKernelGGL(k_p4_bwd_weight_bf16<4>, dim3(grid), dim3(NT), 0, st, x, gpool, idx, p->dev.rot_of, partial, g);
-  const int n_elem = g.Q * 9 * g.CoutPad * g.CinPad;
-  float* dF = partial + (size_t)g.splits * n_elem;
-  hipLaunchKernelGGL(k_p4_sum_splits, dim3((n_elem + 31) / 32), dim3(256), 0, st, partial, dF, n_elem, g.splits);
-  const int total = p->B * 9 * g.Cout * g.Cin;
-  hipLaunchKernelGGL(k_p4_reduce_w, dim3((total + 255) / 256), dim3(256), 0, st, dF, dw, p->dev.fqt_ptr,
-                     p->dev.fqt_col, p->dev.fqt_coef, p->B, g.Cout, g.Cin, g.CoutPad, g.CinPad);
+  finish_dw(p, g, partial, dw, st);
 }
 
 }  // namespace rotconv
