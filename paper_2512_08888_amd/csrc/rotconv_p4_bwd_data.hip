@@ -329,26 +329,30 @@ __global__ __launch_bounds__(256) void k_p4_pack_bwd(const float* __restrict__ w
                                                      const int32_t* __restrict__ fq_src,
                                                      const float* __restrict__ fq_coef, int Q, int CoutPad,
                                                      int CinPad, int Cin, int Cout, int round16) {
-  const int total = Q * CoutPad * 9 * CinPad;
+  // One thread per (bank, filter, channel position): its nine taps read the same 36 bytes of w.
+  const int total = Q * CoutPad * CinPad;
   const int e = blockIdx.x * 256 + threadIdx.x;
   if (e >= total) return;
   // Inside each group of 64 channels position p holds channel (p % 4) * 16 + p / 4, so that the four
   // 16-channel blocks of a lane's channel sit side by side (one 16-byte LDS read per tap in the kernel).
   const int pos = e % CinPad;
   const int ci = (pos / CIG) * CIG + (pos % 4) * 16 + (pos % CIG) / 4;
-  const int u = (e / CinPad) % 9;
-  const int co = (e / (9 * CinPad)) % CoutPad;
-  const int q = e / (9 * CinPad * CoutPad);
-  float acc = 0.f;
-  if (co < Cout && ci < Cin) {
-    const int slices = Cout * Cin;
+  const int co = (e / CinPad) % CoutPad;
+  const int q = e / (CinPad * CoutPad);
+  const bool in = co < Cout && ci < Cin;
+  const int slices = Cout * Cin;
+  const float* src = w + (size_t)(in ? co * Cin + ci : 0) * 9;
+  float* dst = wd + ((size_t)(q * CoutPad + co) * 9) * CinPad + pos;
+#pragma unroll
+  for (int u = 0; u < 9; ++u) {
+    float acc = 0.f;
 #pragma unroll
     for (int z = 0; z < kMaxNnz; ++z) {
       const int s = fq_src[(q * 9 + u) * kMaxNnz + z];
-      if (s >= 0) acc += fq_coef[(q * 9 + u) * kMaxNnz + z] * w[((s / 9) * slices + co * Cin + ci) * 9 + s % 9];
+      if (in && s >= 0) acc += fq_coef[(q * 9 + u) * kMaxNnz + z] * src[(size_t)(s / 9) * slices * 9 + s % 9];
     }
+    dst[(size_t)u * CinPad] = round16 ? bf16_to_f32(f32_to_bf16(acc)) : acc;   // bf16 plans keep the expanded banks in bf16 precision
   }
-  wd[e] = round16 ? bf16_to_f32(f32_to_bf16(acc)) : acc;   // bf16 plans keep the expanded banks in bf16 precision
 }
 
 }  // namespace
@@ -397,7 +401,7 @@ size_t p4_bwd_data_pack_floats(const rotconv_plan* p) {
 
 void launch_p4_pack_bwd(const rotconv_plan* p, const float* w, float* wd, hipStream_t st) {
   const P4BwdGeom g = p4_bwd_data_geom(p);
-  const int total = g.Q * g.CoutPad * 9 * g.CinPad;
+  const int total = g.Q * g.CoutPad * g.CinPad;
   hipLaunchKernelGGL(k_p4_pack_bwd, dim3((total + 255) / 256), dim3(256), 0, st, w, wd, p->dev.fq_src, p->dev.fq_coef,
                      g.Q, g.CoutPad, g.CinPad, g.Cin, g.Cout, p->d.dtype == ROTCONV_BF16 ? 1 : 0);
 }

@@ -439,28 +439,32 @@ __global__ __launch_bounds__(256) void k_p4_pack_bwd_bf16(const uint16_t* __rest
                                                           const int32_t* __restrict__ fq_src,
                                                           const float* __restrict__ fq_coef, int Q, int CIB,
                                                           int CoutPad, int Cin, int Cout) {
-  const int total = CIB * Q * CoutPad * 144;
+  // One thread per (bank, filter, channel): its nine taps read the same 18 bytes of w.
+  const int total = CIB * Q * CoutPad * 16;
   const int e = blockIdx.x * 256 + threadIdx.x;
   if (e >= total) return;
   const int c8 = e % 8;
   const int n16 = (e / 8) % 16;
   const int kg = (e / 128) % 4;
-  const int u = (e / 512) % 9;
-  const int chunk = (e / 4608) % (CoutPad / 32);
-  const int q = (e / (144 * CoutPad)) % Q;
-  const int cib = e / (144 * CoutPad * Q);
+  const int chunk = (e / 512) % (CoutPad / 32);
+  const int q = (e / (16 * CoutPad)) % Q;
+  const int cib = e / (16 * CoutPad * Q);
   const int co = chunk * 32 + kg * 8 + c8, ci = cib * 16 + n16;
-  float acc = 0.f;
-  if (co < Cout && ci < Cin) {
-    const int slices = Cout * Cin;
+  const bool in = co < Cout && ci < Cin;
+  const int slices = Cout * Cin;
+  const uint16_t* src = w + (size_t)(in ? co * Cin + ci : 0) * 9;
+  uint16_t* dst = wt + (size_t)(e / 512) * 4608 + e % 512;      // + u * 512
+#pragma unroll
+  for (int u = 0; u < 9; ++u) {
+    float acc = 0.f;
 #pragma unroll
     for (int z = 0; z < kMaxNnz; ++z) {
       const int s = fq_src[(q * 9 + u) * kMaxNnz + z];
-      if (s >= 0)
-        acc += fq_coef[(q * 9 + u) * kMaxNnz + z] * bf16_to_f32(w[((s / 9) * slices + co * Cin + ci) * 9 + s % 9]);
+      if (in && s >= 0)
+        acc += fq_coef[(q * 9 + u) * kMaxNnz + z] * bf16_to_f32(src[(size_t)(s / 9) * slices * 9 + s % 9]);
     }
+    dst[u * 512] = f32_to_bf16(acc);
   }
-  wt[e] = f32_to_bf16(acc);
 }
 
 // The same banks in the sparse layout: [16-channel block][Q][K-step][half h][orbit o][lgB][16 channels][jg][t];
@@ -470,28 +474,41 @@ __global__ __launch_bounds__(256) void k_p4_pack_bwd_bf16s(const uint16_t* __res
                                                            const int32_t* __restrict__ fq_src,
                                                            const float* __restrict__ fq_coef, int Q, int CIB,
                                                            int CoutPad, int Cin, int Cout) {
-  const int per_step = CHBS / 2;
-  const int total = CIB * Q * (CoutPad / 32) * per_step;
+  // One thread per (bank, filter, channel): the nine taps go to three orbits x four positions (the centre four times).
+  const int per_step = CHBS / 2;                      // elements of one K-step
+  const int total = CIB * Q * (CoutPad / 32) * 2 * 256;
   const int e = blockIdx.x * 256 + threadIdx.x;
   if (e >= total) return;
-  const int t = e % 4, jg = (e / 4) % 4, n16 = (e / 16) % 16, lgB = (e / 256) % 4, o = (e / 1024) % 3, h = (e / 3072) % 2;
-  const int chunk = (e / per_step) % (CoutPad / 32);
-  const int q = (e / (per_step * (CoutPad / 32))) % Q;
-  const int cib = e / (per_step * (CoutPad / 32) * Q);
+  const int jg = e % 4, n16 = (e / 4) % 16, lgB = (e / 64) % 4, h = (e / 256) % 2;
+  const int step = e / 512;                           // (cib * Q + q) * (CoutPad / 32) + chunk
+  const int chunk = step % (CoutPad / 32);
+  const int q = (step / (CoutPad / 32)) % Q;
+  const int cib = step / ((CoutPad / 32) * Q);
   const int lgA = 2 * (jg / 2) + lgB / 2, pr = 2 * (lgB % 2) + jg % 2;
   const int co = chunk * 32 + 8 * lgA + 4 * h + pr, ci = cib * 16 + n16;
-  const int u = o == 2 ? 4 : orbit_pos(o, t);
-  float acc = 0.f;
-  if (co < Cout && ci < Cin) {
-    const int slices = Cout * Cin;
+  const bool in = co < Cout && ci < Cin;
+  const int slices = Cout * Cin;
+  const uint16_t* src = w + (size_t)(in ? co * Cin + ci : 0) * 9;
+  float val[9];
+#pragma unroll
+  for (int u = 0; u < 9; ++u) {
+    float acc = 0.f;
 #pragma unroll
     for (int z = 0; z < kMaxNnz; ++z) {
-      const int sr = fq_src[(q * 9 + u) * kMaxNnz + z];
-      if (sr >= 0)
-        acc += fq_coef[(q * 9 + u) * kMaxNnz + z] * bf16_to_f32(w[((sr / 9) * slices + co * Cin + ci) * 9 + sr % 9]);
+      const int s = fq_src[(q * 9 + u) * kMaxNnz + z];
+      if (in && s >= 0)
+        acc += fq_coef[(q * 9 + u) * kMaxNnz + z] * bf16_to_f32(src[(size_t)(s / 9) * slices * 9 + s % 9]);
     }
+    val[u] = acc;
   }
-  wt[e] = f32_to_bf16(acc);
+  uint16_t* dst = wt + (size_t)step * per_step + h * 3072 + lgB * 256 + n16 * 16 + jg * 4;    // + o * 1024 + t
+#pragma unroll
+  for (int o = 0; o < 3; ++o) {
+    uint16_t t4[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) t4[t] = f32_to_bf16(val[o == 2 ? 4 : orbit_pos(o, t)]);
+    *reinterpret_cast<uint2*>(dst + o * 1024) = make_uint2((uint32_t)t4[0] | ((uint32_t)t4[1] << 16), (uint32_t)t4[2] | ((uint32_t)t4[3] << 16));
+  }
 }
 
 // filters padded to 32, or to a multiple of 64 (two K-steps in flight)
@@ -632,12 +649,12 @@ size_t p4_bwd_data_bf16_pack_bytes(const rotconv_plan* p) {
 void launch_p4_pack_bwd_bf16(const rotconv_plan* p, const uint16_t* w, uint16_t* wt, hipStream_t st) {
   const int CIB = (p->d.Cin + 15) / 16, CoutPad = cout_pad(p->d.Cout);
   if (use_sparse(p)) {
-    const int total = CIB * p->host.Q * (CoutPad / 32) * (CHBS / 2);
+    const int total = CIB * p->host.Q * (CoutPad / 32) * 512;
     hipLaunchKernelGGL(k_p4_pack_bwd_bf16s, dim3((total + 255) / 256), dim3(256), 0, st, w, wt, p->dev.fq_src,
                        p->dev.fq_coef, p->host.Q, CIB, CoutPad, p->d.Cin, p->d.Cout);
     return;
   }
-  const int total = CIB * p->host.Q * CoutPad * 144;
+  const int total = CIB * p->host.Q * CoutPad * 16;
   hipLaunchKernelGGL(k_p4_pack_bwd_bf16, dim3((total + 255) / 256), dim3(256), 0, st, w, wt, p->dev.fq_src,
                      p->dev.fq_coef, p->host.Q, CIB, CoutPad, p->d.Cin, p->d.Cout);
 }

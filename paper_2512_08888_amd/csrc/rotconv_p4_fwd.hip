@@ -446,26 +446,30 @@ __global__ __launch_bounds__(256) void k_p4_pack_fwd(const float* __restrict__ w
                                                      const float* __restrict__ fq_coef, int Q, int CB, int CinPad,
                                                      int Cin, int Cout, int round16, int nq) {
   // nq > 1: the banks are folded into the 16 columns (column n = bank n / (16/nq), filter n % (16/nq)): [CB'][CinPad]...
-  const int total = (nq > 1 ? 1 : Q) * CB * CinPad * 144;
+  // One thread per (bank, filter, channel): its nine taps read the same 36 bytes of w.
+  const int total = (nq > 1 ? 1 : Q) * CB * CinPad * 16;
   const int e = blockIdx.x * 256 + threadIdx.x;
   if (e >= total) return;
   const int c16 = e % 16;
-  const int u = (e / 16) % 9;
-  const int ci = (e / 144) % CinPad;
-  const int cb = (e / (144 * CinPad)) % CB;
+  const int ci = (e / 16) % CinPad;
+  const int cb = (e / (16 * CinPad)) % CB;
   const int fpb = 16 / nq;
-  const int q = nq > 1 ? c16 / fpb : e / (144 * CinPad * CB);
+  const int q = nq > 1 ? c16 / fpb : e / (16 * CinPad * CB);
   const int co = nq > 1 ? cb * fpb + c16 % fpb : cb * 16 + c16;
-  float acc = 0.f;
-  if (co < Cout && ci < Cin) {
-    const int slices = Cout * Cin;
+  const bool in = co < Cout && ci < Cin;
+  const int slices = Cout * Cin;
+  const float* src = w + (size_t)(in ? co * Cin + ci : 0) * 9;
+  float* dst = wt + (size_t)(e / 16) * 144 + c16;
+#pragma unroll
+  for (int u = 0; u < 9; ++u) {
+    float acc = 0.f;
 #pragma unroll
     for (int z = 0; z < kMaxNnz; ++z) {
       const int s = fq_src[(q * 9 + u) * kMaxNnz + z];
-      if (s >= 0) acc += fq_coef[(q * 9 + u) * kMaxNnz + z] * w[((s / 9) * slices + co * Cin + ci) * 9 + s % 9];
+      if (in && s >= 0) acc += fq_coef[(q * 9 + u) * kMaxNnz + z] * src[(size_t)(s / 9) * slices * 9 + s % 9];
     }
+    dst[u * 16] = round16 ? bf16_to_f32(f32_to_bf16(acc)) : acc;   // bf16 plans keep the expanded banks in bf16 precision
   }
-  wt[e] = round16 ? bf16_to_f32(f32_to_bf16(acc)) : acc;   // bf16 plans keep the expanded banks in bf16 precision
 }
 
 template <int NWX, int NWY, bool UNPOOLED, bool FASTW, bool STREAM, int KC = 8, int NQ = 1>
@@ -624,7 +628,7 @@ int p4_fwd_pool_mode(const rotconv_plan* p) {
 
 void launch_p4_pack_fwd(const rotconv_plan* p, const float* w, float* wt, hipStream_t st, int nq) {
   const int CinPad = cin_pad_f32(p->d.Cin), CB = nq > 1 ? (p->d.Cout * nq + 15) / 16 : (p->d.Cout + 15) / 16;
-  const int total = (nq > 1 ? 1 : p->host.Q) * CB * CinPad * 144;
+  const int total = (nq > 1 ? 1 : p->host.Q) * CB * CinPad * 16;
   hipLaunchKernelGGL(k_p4_pack_fwd, dim3((total + 255) / 256), dim3(256), 0, st, w, wt, p->dev.fq_src, p->dev.fq_coef,
                      p->host.Q, CB, CinPad, p->d.Cin, p->d.Cout, p->d.dtype == ROTCONV_BF16 ? 1 : 0, nq);
 }

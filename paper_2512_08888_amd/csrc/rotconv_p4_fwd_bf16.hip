@@ -478,29 +478,33 @@ __global__ __launch_bounds__(256) void k_p4_pack_fwd_bf16(const uint16_t* __rest
                                                           const int32_t* __restrict__ fq_src,
                                                           const float* __restrict__ fq_coef, int Q, int CB, int CinPad,
                                                           int Cin, int Cout, int nq) {
-  const int total = (nq > 1 ? 1 : Q) * CB * CinPad * 144;
+  // One thread per (bank, filter, channel): its nine taps read the same 18 bytes of w.
+  const int total = (nq > 1 ? 1 : Q) * CB * CinPad * 16;
   const int e = blockIdx.x * 256 + threadIdx.x;
   if (e >= total) return;
   const int c8 = e % 8;
   const int f16 = (e / 8) % 16;
   const int kg = (e / 128) % 4;
-  const int u = (e / 512) % 9;
-  const int chunk = (e / 4608) % (CinPad / 32);
-  const int cb = (e / (144 * CinPad)) % CB;
+  const int chunk = (e / 512) % (CinPad / 32);
+  const int cb = (e / (16 * CinPad)) % CB;
   const int fpb = 16 / nq;
-  const int q = nq > 1 ? f16 / fpb : e / (144 * CinPad * CB);
+  const int q = nq > 1 ? f16 / fpb : e / (16 * CinPad * CB);
   const int co = nq > 1 ? cb * fpb + f16 % fpb : cb * 16 + f16, ci = chunk * 32 + kg * 8 + c8;
-  float acc = 0.f;
-  if (co < Cout && ci < Cin) {
-    const int slices = Cout * Cin;
+  const bool in = co < Cout && ci < Cin;
+  const int slices = Cout * Cin;
+  const uint16_t* src = w + (size_t)(in ? co * Cin + ci : 0) * 9;
+  uint16_t* dst = wt + (size_t)(e / 512) * 4608 + e % 512;      // + u * 512
+#pragma unroll
+  for (int u = 0; u < 9; ++u) {
+    float acc = 0.f;
 #pragma unroll
     for (int z = 0; z < kMaxNnz; ++z) {
       const int s = fq_src[(q * 9 + u) * kMaxNnz + z];
-      if (s >= 0)
-        acc += fq_coef[(q * 9 + u) * kMaxNnz + z] * bf16_to_f32(w[((s / 9) * slices + co * Cin + ci) * 9 + s % 9]);
+      if (in && s >= 0)
+        acc += fq_coef[(q * 9 + u) * kMaxNnz + z] * bf16_to_f32(src[(size_t)(s / 9) * slices * 9 + s % 9]);
     }
+    dst[u * 512] = f32_to_bf16(acc);
   }
-  wt[e] = f32_to_bf16(acc);
 }
 
 // the ring holds two chunks (a deeper one spills registers): channels padded to a multiple of 64 beyond 32
@@ -582,7 +586,7 @@ size_t p4_fwd_bf16_pack_bytes(const rotconv_plan* p) {
 // nq: 1 = one bank per wave ([Q][CB] blocks); p4_fwd_bf16_fold(p) = banks folded into the columns ([CB'] blocks)
 void launch_p4_pack_fwd_bf16(const rotconv_plan* p, int nq, const uint16_t* w, uint16_t* wt, hipStream_t st) {
   const int CinPad = cin_pad(p->d.Cin), CB = nq > 1 ? (p->d.Cout * nq + 15) / 16 : (p->d.Cout + 15) / 16;
-  const int total = (nq > 1 ? 1 : p->host.Q) * CB * CinPad * 144;
+  const int total = (nq > 1 ? 1 : p->host.Q) * CB * CinPad * 16;
   hipLaunchKernelGGL(k_p4_pack_fwd_bf16, dim3((total + 255) / 256), dim3(256), 0, st, w, wt, p->dev.fq_src,
                      p->dev.fq_coef, p->host.Q, CB, CinPad, p->d.Cin, p->d.Cout, nq);
 }
