@@ -77,6 +77,9 @@ size_t fwd_fast_ws_bytes(const rotconv_plan* p) {
   if (mode == kOutPartial) extra = align256((size_t)p->host.Q * p->d.N * p->d.Cout * hw * 4) +
                                    align256((size_t)p->host.Q * p->d.N * p->d.Cout * hw);
   if (mode == kOutUnpooled) extra = align256((size_t)p->d.N * p->d.Cout * p->d.R * hw * 4);
+  // channel split: one unpooled part per split
+  const int cs = std::max(p->fwd_csplit[0], p->fwd_csplit[1]);
+  if (cs > 1) extra = std::max(extra, align256((size_t)cs * p->d.N * p->d.Cout * p->d.R * hw * 4));
   return pack + extra;
 }
 
@@ -116,6 +119,10 @@ int rotconv_plan_create(const rotconv_desc* desc, rotconv_plan** out) {
   p->bwdw_splits = generic_bwdw_splits(p);
   p->ws_bytes = generic_ws_bytes(p);
   p->fast[0] = p4_fwd_supported(p) ? 1 : 0;
+  if (p->fast[0]) {
+    p->fwd_csplit[0] = p4_fwd_csplit(p, false);
+    p->fwd_csplit[1] = p4_fwd_csplit(p, true);
+  }
   if (p->fast[0]) p->ws_bytes = std::max(p->ws_bytes, fwd_fast_ws_bytes(p));
   p->fast[1] = p4_bwd_data_supported(p) ? 1 : 0;
   if (p->fast[1])
@@ -208,9 +215,16 @@ static int f32_rotconv_fwd(const rotconv_plan* plan, const void* x, const void* 
   rotconv_plan* p = const_cast<rotconv_plan*>(plan);
   if ((rc = ensure_device_tables(p))) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if (p->fast[0] && aligned(x, 8) && aligned(ws, 16) && aligned(y, 16)) {
+  const int cs = p->fwd_csplit[0];
+  if (p->fast[0] && aligned(x, 8) && aligned(ws, cs > 1 ? 256 : 16) && aligned(y, 16)) {
     float* wt = static_cast<float*>(ws);
     launch_p4_pack_fwd(p, static_cast<const float*>(w), wt, st);
+    if (cs > 1) {     // small map, deep input: the channels are split over workgroups
+      float* part = reinterpret_cast<float*>(static_cast<char*>(ws) + fwd_pack_region(p));
+      launch_p4_fwd(p, kOutUnpooled, static_cast<const float*>(x), wt, part, nullptr, st, 1, cs);
+      launch_p4_sum_parts(p, part, cs, static_cast<float*>(y), st);
+      return finish();
+    }
     launch_p4_fwd(p, kOutUnpooled, static_cast<const float*>(x), wt, static_cast<float*>(y), nullptr, st);
     return finish();
   }
@@ -293,6 +307,14 @@ static int f32_rotconv_pool_fwd(const rotconv_plan* plan, const void* x, const v
     char* extra = static_cast<char*>(ws) + fwd_pack_region(p);
     const int mode = p4_fwd_pool_mode(p);
     const size_t hw = (size_t)p->d.H * p->d.W;
+    const int cs = p->fwd_csplit[1];
+    if (cs > 1) {     // small map, deep input: the channels are split over workgroups, summed and pooled afterwards
+      float* part = reinterpret_cast<float*>(extra);
+      launch_p4_pack_fwd(p, static_cast<const float*>(w), wt, st);
+      launch_p4_fwd(p, kOutUnpooled, static_cast<const float*>(x), wt, part, nullptr, st, 1, cs);
+      launch_p4_sum_pool(p, part, cs, static_cast<float*>(ypool), idx, st);
+      return finish();
+    }
     const int nq = mode == kOutPartial ? p4_fwd_fold(p) : 1;
     launch_p4_pack_fwd(p, static_cast<const float*>(w), wt, st, nq);
     if (mode == kOutPooled) {

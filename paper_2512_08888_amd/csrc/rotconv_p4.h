@@ -20,20 +20,29 @@ struct P4Geom {
   int inside;    // 1 if no segment's wave chain reaches beyond the row
   int relu;      // pooled output: clamp at 0, idx 255 where the pooled value is not positive
   int nq;        // banks folded into a wave's 16 filter columns (0 / 1: none)
+  int csplit;    // parts the channel contraction is split into (1: none); a part is an unpooled fp32 map
+  int cper;      // 32-channel chunks per part (all of them without a split)
+  int cost;      // modelled cost of the launch (host side only)
   int seg_xorg[4];  // first product column of a segment's wave chain
   int seg_lo[4], seg_hi[4];  // output pixels [lo, hi) the segment stores (multiples of 8, or W)
 };
 
 // forward
 bool p4_fwd_supported(const rotconv_plan* p);
-int p4_fwd_geoms(const rotconv_plan* p, int out_mode, P4Geom* out, int max_out);
+int p4_fwd_geoms(const rotconv_plan* p, int out_mode, P4Geom* out, int max_out, int csplit = 1, int nq = 1);
+// parts the forward splits its channel contraction into for this plan (1: none); with a split the kernel runs in
+// the unpooled mode into `csplit` parts of N * Cout * R * H * W floats, added by one of the two kernels below
+int p4_fwd_csplit(const rotconv_plan* p, bool pooled);
+void launch_p4_sum_parts(const rotconv_plan* p, const float* part, int nparts, float* y, hipStream_t st);
+void launch_p4_sum_pool(const rotconv_plan* p, const float* part, int nparts, float* ypool, uint8_t* idx,
+                        hipStream_t st);   // applies the plan's fused activation
 size_t p4_fwd_pack_floats(const rotconv_plan* p);
 int p4_fwd_pool_mode(const rotconv_plan* p);
 int p4_fwd_fold(const rotconv_plan* p);   // banks a wave can fold into its columns for the pooled forward (1: none)
 // nq = 1: one bank per wave; nq = p4_fwd_fold(p) > 1 (with kOutPooled): folded blocks, pooled across banks in-kernel
 void launch_p4_pack_fwd(const rotconv_plan* p, const float* w, float* wt, hipStream_t st, int nq = 1);
 void launch_p4_fwd(const rotconv_plan* p, int out_mode, const float* x, const float* wt, float* out_val,
-                   uint8_t* out_idx, hipStream_t st, int nq = 1);
+                   uint8_t* out_idx, hipStream_t st, int nq = 1, int csplit = 1);
 void launch_p4_combine(const rotconv_plan* p, const float* pv, const uint8_t* pi, float* ypool, uint8_t* idx,
                        hipStream_t st);   // applies the plan's fused activation
 

@@ -30,6 +30,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cstdlib>
 
 #include "rotconv_bf16.h"
 #include "rotconv_kernels.h"
@@ -62,7 +63,7 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restri
   constexpr int CHF = KC * 4 * 144;      // floats of one 32-channel chunk of the filter block
   extern __shared__ float smem[];
   float* Wl = smem;                      // resident: [CinPad][9][16]; streamed: [2][32][9][16]
-  float* EL = smem + (STREAM ? 2 * CHF : g.CinPad * 144);  // [2][NW][8][16] left-edge values of every wave
+  float* EL = smem + (STREAM ? 2 * CHF : g.cper * CHF);    // [2][NW][8][16] left-edge values of every wave
   float* ER = EL + 2 * NW * 128;         // [2][NW][8][16] right-edge values
 
   // XCD-aware unit decode: consecutive units (same image rows, different filter
@@ -70,6 +71,11 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restri
   const int per_xcd = (g.units + 7) / 8;
   int v = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
   if (v >= g.units) return;
+  // Channel split (small maps with deep inputs): the workgroup contracts the 32-channel chunks [c_lo, c_hi) only and
+  // writes its unpooled sums into part `sp`; the parts are added in order afterwards.  Without a split: all chunks.
+  const int sp = v % g.csplit; v /= g.csplit;
+  const int nchunk = g.CinPad / (4 * KC);
+  const int c_lo = sp * g.cper, c_hi = min(nchunk, c_lo + g.cper);
   const int cb = v % g.CB; v /= g.CB;
   const int q = v % g.Q; v /= g.Q;
   const int seg = v % g.nseg; v /= g.nseg;
@@ -77,7 +83,6 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restri
   const int n = v / g.nbg;
 
   const int tid = threadIdx.x;
-  const int nchunk = g.CinPad / (4 * KC);
   const float* wsrc = wt + ((size_t)(q * g.CB + cb) * g.CinPad) * 144;
   constexpr int WPT = (CHF / 4 + NT - 1) / NT;   // float4 per thread and chunk when streaming
   f4 wreg[STREAM ? WPT : 1];
@@ -99,9 +104,9 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restri
     wload(0);
     wstore(0);
   } else {
-    const f4* src = reinterpret_cast<const f4*>(wsrc);
+    const f4* src = reinterpret_cast<const f4*>(wsrc + (size_t)c_lo * CHF);
     f4* dst = reinterpret_cast<f4*>(Wl);
-    const int n4 = g.CinPad * 36;
+    const int n4 = (c_hi - c_lo) * (CHF / 4);
     for (int i = tid; i < n4; i += NT) dst[i] = src[i];
   }
   __syncthreads();
@@ -157,7 +162,7 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restri
   {
     const float* rp = row_ptr(0);
 #pragma unroll
-    for (int ks = 0; ks < KC; ++ks) a_cur[ks] = load_a(rp, ks);
+    for (int ks = 0; ks < KC; ++ks) a_cur[ks] = load_a(rp, c_lo * KC + ks);
     __builtin_amdgcn_s_waitcnt(0x0F70);
   }
   const float* wl_lane = Wl + lg * 144 + lc;
@@ -174,11 +179,11 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restri
     // after its MFMAs, B read from LDS one K-step ahead.  The scheduling fences keep loads and LDS reads
     // where they are issued; left alone the compiler sinks them next to their first use and waits there.
     auto chunk = [&](int c, bool first) {
-      const bool last = c + 1 == nchunk;
+      const bool last = c + 1 == c_hi;
       const float* rp = last ? rp_nxt : rp_cur;
-      const int kn = last ? 0 : (c + 1) * KC;
-      if (STREAM) wload(last ? 0 : c + 1);
-      const float* wc = STREAM ? wl_lane + (seq & 1) * CHF : wl_lane + (size_t)c * CHF;
+      const int kn = (last ? c_lo : c + 1) * KC;
+      if (STREAM) wload(last ? 0 : c + 1);         // streamed blocks are never split: c_lo = 0
+      const float* wc = STREAM ? wl_lane + (seq & 1) * CHF : wl_lane + (size_t)(c - c_lo) * CHF;
       float bw[2][9];
 #pragma unroll
       for (int u = 0; u < 9; ++u) bw[0][u] = wc[u * 16];
@@ -209,8 +214,8 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restri
     // 72 register moves on every row's path.  A wave whose whole band lies below the image (the workgroup's bands
     // need not divide H) multiplies nothing: it only keeps the workgroup's barriers and filter stages in step.
     if (live) {
-      chunk(0, true);
-      for (int c = 1; c < nchunk; ++c) chunk(c, false);
+      chunk(c_lo, true);
+      for (int c = c_lo + 1; c < c_hi; ++c) chunk(c, false);
     } else if (STREAM) {
       for (int c = 0; c < nchunk; ++c) {
         wload(c + 1 == nchunk ? 0 : c + 1);
@@ -309,7 +314,7 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restri
 #pragma unroll
         for (int j = 0; j < 8; ++j) place(s, j, yfin[j]);
         if (fin && rot[s] >= 0) {
-          float* o = out_val + (((size_t)n * g.Cout + co) * g.R + rot[s]) * HW + (size_t)y * g.W + px0;
+          float* o = out_val + ((((size_t)sp * g.N + n) * g.Cout + co) * g.R + rot[s]) * HW + (size_t)y * g.W + px0;
           if (FASTW) {
             reinterpret_cast<f4*>(o)[0] = f4{yfin[0], yfin[1], yfin[2], yfin[3]};
             reinterpret_cast<f4*>(o)[1] = f4{yfin[4], yfin[5], yfin[6], yfin[7]};
@@ -439,6 +444,46 @@ __global__ __launch_bounds__(256) void k_p4_combine(const float* __restrict__ pv
   idx[o] = dead ? (uint8_t)255 : (uint8_t)bi;
 }
 
+// Channel split: y = sum of the parts, ascending (four elements per thread, scalar tail).
+__global__ __launch_bounds__(256) void k_p4_sum_parts(const float* __restrict__ part, float* __restrict__ y,
+                                                      size_t n_elem, int nparts) {
+  const size_t n4 = n_elem / 4;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (size_t)gridDim.x * 256) {
+    f4 a = reinterpret_cast<const f4*>(part)[i];
+    for (int k = 1; k < nparts; ++k) a += reinterpret_cast<const f4*>(part + (size_t)k * n_elem)[i];
+    reinterpret_cast<f4*>(y)[i] = a;
+  }
+  for (size_t e = n4 * 4 + (size_t)blockIdx.x * 256 + threadIdx.x; e < n_elem; e += (size_t)gridDim.x * 256) {
+    float v = part[e];
+    for (int k = 1; k < nparts; ++k) v += part[(size_t)k * n_elem + e];
+    y[e] = v;
+  }
+}
+
+// Channel split, pooled: every orientation's sum over the parts (ascending), then max / arg-max over the pool
+// group (first maximum wins) and the fused activation.  One thread per pooled element.
+__global__ __launch_bounds__(256) void k_p4_sum_pool(const float* __restrict__ part, float* __restrict__ ypool,
+                                                     uint8_t* __restrict__ idx, size_t n_elem, int nparts, int NC,
+                                                     int R, int ng, int HW, int relu) {
+  const size_t total = (size_t)NC * ng * HW;       // NC = N * Cout
+  const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (e >= total) return;
+  const int px = (int)(e % HW);
+  const int grp = (int)((e / HW) % ng);
+  const size_t nc = e / ((size_t)HW * ng);
+  const float* yb = part + nc * R * HW + px;
+  float best = 0.f;
+  int bi = -1;
+  for (int r = grp; r < R; r += ng) {
+    float v = yb[(size_t)r * HW];
+    for (int k = 1; k < nparts; ++k) v += yb[(size_t)k * n_elem + (size_t)r * HW];
+    if (bi < 0 || v > best) { best = v; bi = r; }
+  }
+  const bool dead = relu && !(best > 0.f);
+  ypool[e] = dead ? 0.f : best;
+  idx[e] = dead ? (uint8_t)255 : (uint8_t)bi;
+}
+
 // base bank(s) -> Q first-quadrant banks in the LDS image layout [Q][CB][CinPad][9][16]
 // (zero for padded filters / channels).
 __global__ __launch_bounds__(256) void k_p4_pack_fwd(const float* __restrict__ w, float* __restrict__ wt,
@@ -475,7 +520,7 @@ __global__ __launch_bounds__(256) void k_p4_pack_fwd(const float* __restrict__ w
 template <int NWX, int NWY, bool UNPOOLED, bool FASTW, bool STREAM, int KC = 8, int NQ = 1>
 void launch_i(const P4Geom& g, const float* x, const float* wt, const int32_t* rot_of, float* ov, uint8_t* oi,
               hipStream_t st) {
-  const size_t wfl = STREAM ? (size_t)2 * KC * 4 * 144 : (size_t)g.CinPad * 144;
+  const size_t wfl = STREAM ? (size_t)2 * KC * 4 * 144 : (size_t)g.cper * KC * 4 * 144;
   const size_t lds = (wfl + 4 * NWX * NWY * 128) * sizeof(float);
   const int grid = (g.units + 7) / 8 * 8;
   auto kern = k_p4_fwd<NWX, NWY, UNPOOLED, FASTW, STREAM, KC, NQ>;
@@ -530,15 +575,74 @@ bool p4_fwd_supported(const rotconv_plan* p) {
   if (d.k != 3 || d.stride != 1 || d.pad != 1) return false;   // bf16 plans run these kernels on widened copies
   if (d.W & 1) return false;
   if (d.W > 256 && (d.W & 31)) return false;          // segmented rows need whole-lane validity
-  if (needs_stream(d.Cin) && (d.W & 31)) return false;  // the streaming variant is built for W % 32 == 0
+  // the streaming variant is built for W % 32 == 0; narrower maps split the channels instead
+  if (needs_stream(d.Cin) && (d.W & 31) && p4_fwd_csplit(p, false) < 2) return false;
   return true;
+}
+
+namespace {
+// Cost of a launch plan in quarter row steps (a wave's 144 matrix instructions of one 32-channel chunk and row,
+// about 2 us, count 4): the sum of its launches' band costs.
+long plan_cost(const rotconv_plan* p, int out_mode, int csplit, int nq) {
+  P4Geom gs[4];
+  const int n = p4_fwd_geoms(p, out_mode, gs, 4, csplit, nq);
+  if (n < 0) return -1;
+  long c = 0;
+  for (int i = 0; i < n; ++i) c += gs[i].cost;
+  return c;
+}
+}  // namespace
+
+// Parts the channel contraction is split into (1: no split).  Small maps with deep inputs give the (filter block,
+// band) decomposition too few workgroups, each with a long serial contraction; splitting the 32-channel chunks over
+// workgroups (at most 7 chunks each, so the filter share stays LDS-resident) costs one unpooled fp32 part per split
+// and an ordered sum.  `pooled`: the caller wants the pooled output (the alternative is the fused pooled kernel,
+// with the banks folded where the plan allows it).
+int p4_fwd_csplit(const rotconv_plan* p, bool pooled) {
+  const rotconv_desc& d = p->d;
+  const int CinPad = cin_pad_f32(d.Cin);
+  if (CinPad == 4 || d.W > 256) return 1;
+  const int nchunk = CinPad / 32;
+  if (nchunk < 2) return 1;
+  const bool must = needs_stream(d.Cin) && (d.W & 31);          // no unsplit instance for this shape
+  // Tuning knob, read when the plan is created: ROTCONV_FWD_CSPLIT=1 keeps the contraction whole where an unsplit
+  // instance exists, n >= 2 asks for n parts (rounded so that a part holds at most 7 chunks); unset or 0: the model.
+  int forced = 0;
+  if (const char* e = std::getenv("ROTCONV_FWD_CSPLIT")) forced = std::atoi(e);
+  if (forced == 1 && !must) return 1;
+  if (forced >= 2) {
+    const int cper = std::max((nchunk + forced - 1) / forced, (nchunk + 31) / 32);
+    if (cper <= 7) return (nchunk + cper - 1) / cper;
+  }
+  const int mode = pooled ? p4_fwd_pool_mode(p) : kOutUnpooled;
+  const int nq = pooled && mode == kOutPartial ? p4_fwd_fold(p) : 1;
+  long best = must ? -1 : plan_cost(p, nq > 1 ? kOutPooled : mode, 1, nq);
+  int best_s = 1;
+  const double part_bytes = (double)d.N * d.Cout * d.R * d.H * d.W * 4.0;
+  for (int s = 2; s <= 32; s *= 2) {
+    const int cper = (nchunk + s - 1) / s;
+    if (cper > 7) continue;
+    const int s_eff = (nchunk + cper - 1) / cper;
+    if (s_eff < 2) break;
+    // parts written and read once at about 4 TB/s, two small launches
+    const long over = 24 + (long)(2.0 * s_eff * part_bytes / 2.0e6);
+    const long c = plan_cost(p, kOutUnpooled, s_eff, 1) + over;
+    if (best < 0 || c < best) { best = c; best_s = s_eff; }
+    if (cper == 1) break;
+  }
+  return best_s;
 }
 
 // Cut the row into segments of at most 256 product columns; all segments of one launch share nwx.
 // Returns the number of launches (geoms) written.
-int p4_fwd_geoms(const rotconv_plan* p, int out_mode, P4Geom* out, int max_out) {
+int p4_fwd_geoms(const rotconv_plan* p, int out_mode, P4Geom* out, int max_out, int csplit, int nq) {
   const rotconv_desc& d = p->d;
   P4Geom base{};
+  {
+    const int CinPad = cin_pad_f32(d.Cin), nchunk = CinPad == 4 ? 1 : CinPad / 32;
+    base.cper = (nchunk + csplit - 1) / csplit;
+    base.csplit = (nchunk + base.cper - 1) / base.cper;
+  }
   base.N = d.N; base.Cin = d.Cin; base.CinPad = cin_pad_f32(d.Cin); base.H = d.H; base.W = d.W;
   base.Cout = d.Cout; base.CB = (d.Cout + 15) / 16; base.R = d.R; base.Q = p->host.Q; base.ng = p->ng;
   base.out_mode = out_mode;
@@ -584,13 +688,21 @@ int p4_fwd_geoms(const rotconv_plan* p, int out_mode, P4Geom* out, int max_out) 
     // Rows per band: short bands cost halo rows (a band of ty rows computes ty + 2 rows of products) but give
     // more workgroups when the problem is small.  Cost of a choice = rounds of workgroups over the 256 CUs x row
     // steps per wave x how many waves share a SIMD (a workgroup whose bands reach beyond the image leaves waves idle).
+    // nq > 1 (banks folded into the columns): one unit covers all banks of 16 / nq filters
+    const int ublk = nq > 1 ? (d.Cout * nq + 15) / 16 : g.Q * g.CB;
     for (int ty : {1, 2, 4, 8, 16, 32, 64}) {
       const int nbg = (d.H + nwy * ty - 1) / (nwy * ty);
-      const long units = (long)d.N * g.Q * g.CB * nbg * g.nseg;
+      const long units = (long)d.N * ublk * nbg * g.nseg * g.csplit;
       const int bands = nbg > 1 ? nwy : std::min(nwy, (d.H + ty - 1) / ty);
       const long cost = ((units + 255) / 256) * (ty + 2) * std::max(4, g.nwx * bands);
       if (best_cost < 0 || cost <= best_cost) { best_cost = cost; g.TY = ty; g.nbg = nbg; g.units = (int)units; }
     }
+    g.cost = (int)std::min<long>(best_cost * g.cper, 1L << 30);
+    if (nq > 1) {
+      g.CB = ublk;
+      g.Q = 1;
+    }
+    g.nq = nq;
   }
   return ng;
 }
@@ -634,19 +746,12 @@ void launch_p4_pack_fwd(const rotconv_plan* p, const float* w, float* wt, hipStr
 }
 
 void launch_p4_fwd(const rotconv_plan* p, int out_mode, const float* x, const float* wt, float* out_val,
-                   uint8_t* out_idx, hipStream_t st, int nq) {
+                   uint8_t* out_idx, hipStream_t st, int nq, int csplit) {
   P4Geom gs[4];
-  const int ng = p4_fwd_geoms(p, out_mode, gs, 4);
-  const bool stream = needs_stream(p->d.Cin);
+  const int ng = p4_fwd_geoms(p, out_mode, gs, 4, csplit, nq);
+  const bool stream = csplit < 2 && needs_stream(p->d.Cin);
   for (int i = 0; i < ng; ++i) {
     P4Geom& g = gs[i];
-    g.nq = nq;
-    if (nq > 1) {         // one unit covers all banks of 16 / nq filters
-      const int CBf = (p->d.Cout * nq + 15) / 16;
-      g.units = g.units / (g.Q * g.CB) * CBf;
-      g.CB = CBf;
-      g.Q = 1;
-    }
     const bool fastw = (p->d.W & 7) == 0 && g.inside;   // no lane reaches beyond the row: no masks, vector stores
     switch (g.nwx) {
       case 1: launch_t<1, 8>(g, fastw, stream, x, wt, p->dev.rot_of, out_val, out_idx, st); break;
@@ -655,6 +760,21 @@ void launch_p4_fwd(const rotconv_plan* p, int out_mode, const float* x, const fl
       default: launch_t<8, 1>(g, fastw, stream, x, wt, p->dev.rot_of, out_val, out_idx, st); break;
     }
   }
+}
+
+void launch_p4_sum_parts(const rotconv_plan* p, const float* part, int nparts, float* y, hipStream_t st) {
+  const size_t n_elem = (size_t)p->d.N * p->d.Cout * p->d.R * p->d.H * p->d.W;
+  const unsigned blocks = (unsigned)std::max<size_t>(1, std::min<size_t>((n_elem / 4 + 255) / 256, 4096));
+  hipLaunchKernelGGL(k_p4_sum_parts, dim3(blocks), dim3(256), 0, st, part, y, n_elem, nparts);
+}
+
+void launch_p4_sum_pool(const rotconv_plan* p, const float* part, int nparts, float* ypool, uint8_t* idx,
+                        hipStream_t st) {
+  const int HW = p->d.H * p->d.W;
+  const size_t n_elem = (size_t)p->d.N * p->d.Cout * p->d.R * HW;
+  const size_t total = (size_t)p->d.N * p->d.Cout * p->ng * HW;
+  hipLaunchKernelGGL(k_p4_sum_pool, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, part, ypool, idx, n_elem,
+                     nparts, p->d.N * p->d.Cout, p->d.R, p->ng, HW, p->d.activation == ROTCONV_ACT_RELU ? 1 : 0);
 }
 
 void launch_p4_combine(const rotconv_plan* p, const float* pv, const uint8_t* pi, float* ypool, uint8_t* idx,

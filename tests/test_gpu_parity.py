@@ -68,6 +68,13 @@ TINY = [
     # starting inside a bank (17 chunks of one bank in two parts; 2 x 13 chunks in three)
     LC("t_ksplit_q1", N=1, Cin=24, H=8, W=32, Cout=272, R=4, seed=48),
     LC("t_ksplit_q2", N=1, Cin=16, H=6, W=32, Cout=200, R=8, mode="bilinear", seed=49),
+    # deep inputs on small maps: the forward splits its channel chunks over workgroups (unpooled parts, ordered sum,
+    # then the pool): 17 chunks on a map narrower than a wave, R = 1; three chunks, R = 4; sub-group pooling over
+    # two banks; a pool group that spans four banks
+    LC("t_csplit_w8", N=1, Cin=520, H=8, W=8, Cout=20, R=1, seed=50),
+    LC("t_csplit_r4", N=2, Cin=96, H=6, W=32, Cout=18, R=4, seed=51),
+    LC("t_csplit_r8_g4", N=1, Cin=72, H=5, W=16, Cout=9, R=8, mode="bilinear", pool_group=4, seed=52),
+    LC("t_csplit_r16", N=1, Cin=160, H=4, W=4, Cout=17, R=16, mode="bilinear", seed=53),
 ]
 
 
@@ -116,6 +123,20 @@ def test_unfused_chain_tiny(cfg):
     dyd_d = pu.dev(dyd, torch.float32)
     pu.assert_close(L.bwd_data(dyd_d), dx_ref, f"{cfg.name} dx (dense dy)")
     pu.assert_close(L.bwd_weight(dyd_d), dw_ref, f"{cfg.name} dw (dense dy)")
+
+
+@pytest.mark.parametrize("parts", ["1", "2", "5"])
+@pytest.mark.parametrize("name", ["t_cin256", "t_cin288_r16", "t_csplit_r4", "t_csplit_r16"])
+def test_forward_channel_split_settings(name, parts, monkeypatch):
+    """The forward with its channel contraction kept whole (where such an instance exists) and split into a given
+    number of parts: fused pooled call and the unpooled call, both against the oracle."""
+    cfg = next(c for c in TINY if c.name == name)
+    monkeypatch.setenv("ROTCONV_FWD_CSPLIT", parts)      # read when the plan is created
+    say(f"[case] forward channel split {name} parts={parts}")
+    out = pu.run_fused_parity(cfg)
+    L, ref = out["layer"], out["ref"]
+    y = L.fwd()
+    pu.assert_close(y.cpu().numpy().reshape(ref["y"].shape), ref["y"], f"{name} y parts={parts}")
 
 
 def test_config1_fused_and_unfused():
