@@ -384,6 +384,17 @@ P4BwdGeom p4_bwd_data_geom(const rotconv_plan* p) {
     g.kper = (chunks + want - 1) / want;
     g.ksplit = (chunks + g.kper - 1) / g.kper;
   }
+  // Still far from filling the chip (small maps): go down to two chunks per workgroup, one when dX is tiny, as long
+  // as the partial sums stay within 64 MB.
+  if (g.units * g.ksplit < 256 && chunks >= 2) {
+    const double dx_bytes = 4.0 * d.N * d.Cin * d.H * d.W;
+    const int want = std::min({chunks / (dx_bytes < 2.0e6 ? 1 : 2), (512 + g.units - 1) / g.units,
+                               std::max(1, (int)(67108864.0 / dx_bytes))});
+    if (want > g.ksplit) {
+      g.kper = (chunks + want - 1) / want;
+      g.ksplit = (chunks + g.kper - 1) / g.kper;
+    }
+  }
   if (g.ksplit == 1) g.kper = chunks;
   g.units *= g.ksplit;
   return g;

@@ -68,6 +68,10 @@ TINY = [
     # starting inside a bank (17 chunks of one bank in two parts; 2 x 13 chunks in three)
     LC("t_ksplit_q1", N=1, Cin=24, H=8, W=32, Cout=272, R=4, seed=48),
     LC("t_ksplit_q2", N=1, Cin=16, H=6, W=32, Cout=200, R=8, mode="bilinear", seed=49),
+    # small maps: one or two chunks per workgroup (three chunks of one bank; 2 x 2 chunks of two banks; six chunks in
+    # threes on a map whose dX is not tiny)
+    LC("t_ksplit_small", N=1, Cin=70, H=4, W=8, Cout=40, R=4, seed=54),
+    LC("t_ksplit_small_q2", N=1, Cin=20, H=5, W=6, Cout=24, R=8, mode="bilinear", seed=55),
     # deep inputs on small maps: the forward splits its channel chunks over workgroups (unpooled parts, ordered sum,
     # then the pool): 17 chunks on a map narrower than a wave, R = 1; three chunks, R = 4; sub-group pooling over
     # two banks; a pool group that spans four banks
