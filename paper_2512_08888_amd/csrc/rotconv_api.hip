@@ -104,6 +104,27 @@ AvgLayout avg_layout(const rotconv_plan* p) {
   return L;
 }
 
+// Staging areas of a plan whose calls run on zero-padded rows (pad_child): an input-sized area, an output-sized area
+// (pooled; unpooled if rotconv_fwd goes that way too), the idx map, then the child's own scratch.
+struct PadLayout { size_t in, out, idx, child, total; };
+PadLayout pad_layout(const rotconv_plan* p) {
+  const rotconv_plan* ch = p->pad_child;
+  const size_t es = p->d.dtype == ROTCONV_BF16 ? 2 : 4;
+  PadLayout L;
+  L.in = 0;
+  L.out = align256(ch->n_x * es);
+  L.idx = L.out + align256((p->pad_use[0] ? ch->n_yu : ch->n_yp) * es);
+  L.child = L.idx + align256(ch->n_yp);
+  L.total = L.child + align256(ch->ws_bytes);
+  return L;
+}
+
+// how a pass runs: 2 bf16 matrix-core kernel, 1 fp32 matrix-core kernel, 0 generic
+int pass_level(const rotconv_plan* p, int pass) {
+  if (p->d.dtype == ROTCONV_BF16 && p->native16[pass]) return 2;
+  return p->fast[pass] ? 1 : 0;
+}
+
 }  // namespace
 }  // namespace rotconv
 
@@ -160,6 +181,32 @@ int rotconv_plan_create(const rotconv_desc* desc, rotconv_plan** out) {
     const AvgLayout L = avg_layout(p);
     p->ws_inner = p->ws_bytes = std::max(p->ws_bytes, L.total);
   }
+  // 3x3 / stride 1 / pad 1 layers whose row width keeps a pass off the matrix-core kernels: the same layer on rows
+  // padded to a multiple of 8 (32 beyond 256 pixels)
+  if (p->d.pool_op != ROTCONV_POOL_AVG && p->d.k == 3 && p->d.stride == 1 && p->d.pad == 1) {
+    const int top = p->d.dtype == ROTCONV_BF16 ? 2 : 1;
+    const int Wp = p->d.W > 256 ? (p->d.W + 31) / 32 * 32 : (p->d.W + 7) / 8 * 8;
+    const bool lacking = pass_level(p, 0) < top || pass_level(p, 1) < top || pass_level(p, 2) < top;
+    if (lacking && Wp != p->d.W) {
+      rotconv_desc cd = p->d;       // angles_deg points at the plan's own list (the defaults where none were given)
+      cd.W = Wp;
+      if (cd.mode == ROTCONV_P4M) cd.angles_deg = nullptr;   // that mode takes no explicit angles
+      rotconv_plan* ch = nullptr;
+      const int crc = rotconv_plan_create(&cd, &ch);
+      if (crc != ROTCONV_OK) {
+        delete p;
+        return crc;
+      }
+      int any = 0;
+      for (int i = 0; i < 3; ++i) any |= p->pad_use[i] = pass_level(ch, i) > pass_level(p, i) ? 1 : 0;
+      if (any) {
+        p->pad_child = ch;
+        p->ws_bytes = std::max(p->ws_bytes, pad_layout(p).total);
+      } else {
+        rotconv_plan_destroy(ch);
+      }
+    }
+  }
   *out = p;
   return ROTCONV_OK;
 }
@@ -167,6 +214,7 @@ int rotconv_plan_create(const rotconv_desc* desc, rotconv_plan** out) {
 int rotconv_plan_destroy(rotconv_plan* plan) {
   if (!plan) return ROTCONV_OK;
   if (plan->avg_child) rotconv_plan_destroy(plan->avg_child);
+  if (plan->pad_child) rotconv_plan_destroy(plan->pad_child);
   free_device_tables(plan);
   delete plan;
   return ROTCONV_OK;
@@ -300,7 +348,7 @@ static int f32_rotconv_pool_fwd(const rotconv_plan* plan, const void* x, const v
     float* wavg = reinterpret_cast<float*>(c + L.wavg);
     launch_expand_bank(p, static_cast<const float*>(w), wexp, st);
     launch_avg_bank(p, wexp, wavg, st);
-    return f32_rotconv_fwd(p->avg_child, x, wavg, ypool, c + L.child, p->avg_child->ws_bytes, stream);
+    return rotconv_fwd(p->avg_child, x, wavg, ypool, c + L.child, p->avg_child->ws_bytes, stream);
   }
   if (p->fast[0] && aligned(x, 8) && aligned(ws, 256) && aligned(ypool, 16) && aligned(idx, 8)) {
     float* wt = static_cast<float*>(ws);
@@ -356,7 +404,7 @@ static int f32_rotconv_pool_bwd_data(const rotconv_plan* plan, const void* gpool
     launch_expand_bank(p, static_cast<const float*>(w), wexp, st);
     launch_avg_bank(p, wexp, wavg, st);
     launch_fill_u8(idx0, p->n_yp, 0, st);
-    return f32_rotconv_pool_bwd_data(p->avg_child, gpool, idx0, wavg, dx, c + L.child, p->avg_child->ws_bytes, stream);
+    return rotconv_pool_bwd_data(p->avg_child, gpool, idx0, wavg, dx, c + L.child, p->avg_child->ws_bytes, stream);
   }
   if (p->fast[1] && aligned(gpool, 8) && aligned(idx, 2) && aligned(dx, 16) && aligned(ws, 16)) {
     float* wd = static_cast<float*>(ws);
@@ -386,7 +434,7 @@ static int f32_rotconv_pool_bwd_weight(const rotconv_plan* plan, const void* x, 
     float* dwavg = reinterpret_cast<float*>(c + L.wavg);
     uint8_t* idx0 = reinterpret_cast<uint8_t*>(c + L.idx0);
     launch_fill_u8(idx0, p->n_yp, 0, st);
-    rc = f32_rotconv_pool_bwd_weight(p->avg_child, x, gpool, idx0, dwavg, c + L.child, p->avg_child->ws_bytes, stream);
+    rc = rotconv_pool_bwd_weight(p->avg_child, x, gpool, idx0, dwavg, c + L.child, p->avg_child->ws_bytes, stream);
     if (rc) return rc;
     launch_avg_bank_bwd(p, dwavg, rep, dw, st);
     return finish();
@@ -429,11 +477,43 @@ Stage carve(const rotconv_plan* p, void* ws, size_t ws_bytes) {
 bool is_bf16(const rotconv_plan* p) { return p->d.dtype == ROTCONV_BF16; }
 const uint16_t* h16(const void* p) { return static_cast<const uint16_t*>(p); }
 
+// The calls of a plan with padded rows: stage the tensors at the child's row width, run the child, crop.
+struct PadCtx {
+  const rotconv_plan* ch;
+  char *in, *out, *idx, *cws;
+  int es, W, Wp;
+  size_t rows_x, rows_p, rows_u;    // rows of the input, the pooled and the unpooled maps
+  hipStream_t st;
+};
+int pad_ctx(const rotconv_plan* p, void* ws, size_t ws_bytes, void* stream, PadCtx* c) {
+  if (!ws || ws_bytes < p->ws_bytes) return ROTCONV_ERR_WORKSPACE;
+  const PadLayout L = pad_layout(p);
+  char* b = static_cast<char*>(ws);
+  c->ch = p->pad_child;
+  c->in = b + L.in; c->out = b + L.out; c->idx = b + L.idx; c->cws = b + L.child;
+  c->es = is_bf16(p) ? 2 : 4;
+  c->W = p->d.W; c->Wp = p->pad_child->d.W;
+  c->rows_x = (size_t)p->d.N * p->d.Cin * p->d.H;
+  c->rows_p = (size_t)p->d.N * p->d.Cout * p->ng * p->d.H;
+  c->rows_u = (size_t)p->d.N * p->d.Cout * p->d.R * p->d.H;
+  c->st = static_cast<hipStream_t>(stream);
+  return ROTCONV_OK;
+}
+
 }  // namespace
 
 int rotconv_fwd(const rotconv_plan* plan, const void* x, const void* w, void* y, void* ws, size_t ws_bytes,
                 void* stream) {
   if (!plan || !x || !w || !y) return ROTCONV_ERR_NULL;
+  if (plan->pad_child && plan->pad_use[0]) {
+    PadCtx c;
+    int rc = pad_ctx(plan, ws, ws_bytes, stream, &c);
+    if (rc) return rc;
+    launch_repitch(x, c.in, c.rows_x, c.W, c.Wp, c.es, 0, c.st);
+    if ((rc = rotconv_fwd(c.ch, c.in, w, c.out, c.cws, c.ch->ws_bytes, stream))) return rc;
+    launch_repitch(c.out, y, c.rows_u, c.Wp, c.W, c.es, 0, c.st);
+    return finish();
+  }
   if (!is_bf16(plan)) return f32_rotconv_fwd(plan, x, w, y, ws, ws_bytes, stream);
   if (!ws || ws_bytes < plan->ws_bytes) return ROTCONV_ERR_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -499,6 +579,17 @@ int orient_maxpool_bwd(const rotconv_plan* plan, const void* gpool, const uint8_
 int rotconv_pool_fwd(const rotconv_plan* plan, const void* x, const void* w, void* ypool, uint8_t* idx, void* ws,
                      size_t ws_bytes, void* stream) {
   if (!plan || !x || !w || !ypool || (!idx && !plan->avg_child)) return ROTCONV_ERR_NULL;
+  if (plan->pad_child && plan->pad_use[0]) {
+    PadCtx c;
+    int rc = pad_ctx(plan, ws, ws_bytes, stream, &c);
+    if (rc) return rc;
+    launch_repitch(x, c.in, c.rows_x, c.W, c.Wp, c.es, 0, c.st);
+    if ((rc = rotconv_pool_fwd(c.ch, c.in, w, c.out, reinterpret_cast<uint8_t*>(c.idx), c.cws, c.ch->ws_bytes, stream)))
+      return rc;
+    launch_repitch(c.out, ypool, c.rows_p, c.Wp, c.W, c.es, 0, c.st);
+    launch_repitch(c.idx, idx, c.rows_p, c.Wp, c.W, 1, 0, c.st);
+    return finish();
+  }
   if (!is_bf16(plan)) return f32_rotconv_pool_fwd(plan, x, w, ypool, idx, ws, ws_bytes, stream);
   if (!ws || ws_bytes < plan->ws_bytes) return ROTCONV_ERR_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -538,6 +629,18 @@ int rotconv_pool_fwd(const rotconv_plan* plan, const void* x, const void* w, voi
 int rotconv_pool_bwd_data(const rotconv_plan* plan, const void* gpool, const uint8_t* idx, const void* w, void* dx,
                           void* ws, size_t ws_bytes, void* stream) {
   if (!plan || !gpool || (!idx && !plan->avg_child) || !w || !dx) return ROTCONV_ERR_NULL;
+  if (plan->pad_child && plan->pad_use[1]) {     // padded columns: zero gradient, idx 255 (matches no orientation)
+    PadCtx c;
+    int rc = pad_ctx(plan, ws, ws_bytes, stream, &c);
+    if (rc) return rc;
+    launch_repitch(gpool, c.out, c.rows_p, c.W, c.Wp, c.es, 0, c.st);
+    launch_repitch(idx, c.idx, c.rows_p, c.W, c.Wp, 1, 0xff, c.st);
+    if ((rc = rotconv_pool_bwd_data(c.ch, c.out, reinterpret_cast<const uint8_t*>(c.idx), w, c.in, c.cws,
+                                    c.ch->ws_bytes, stream)))
+      return rc;
+    launch_repitch(c.in, dx, c.rows_x, c.Wp, c.W, c.es, 0, c.st);
+    return finish();
+  }
   if (!is_bf16(plan)) return f32_rotconv_pool_bwd_data(plan, gpool, idx, w, dx, ws, ws_bytes, stream);
   if (!ws || ws_bytes < plan->ws_bytes) return ROTCONV_ERR_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -563,6 +666,16 @@ int rotconv_pool_bwd_data(const rotconv_plan* plan, const void* gpool, const uin
 int rotconv_pool_bwd_weight(const rotconv_plan* plan, const void* x, const void* gpool, const uint8_t* idx, float* dw,
                             void* ws, size_t ws_bytes, void* stream) {
   if (!plan || !x || !gpool || (!idx && !plan->avg_child) || !dw) return ROTCONV_ERR_NULL;
+  if (plan->pad_child && plan->pad_use[2]) {
+    PadCtx c;
+    const int rc = pad_ctx(plan, ws, ws_bytes, stream, &c);
+    if (rc) return rc;
+    launch_repitch(x, c.in, c.rows_x, c.W, c.Wp, c.es, 0, c.st);
+    launch_repitch(gpool, c.out, c.rows_p, c.W, c.Wp, c.es, 0, c.st);
+    launch_repitch(idx, c.idx, c.rows_p, c.W, c.Wp, 1, 0xff, c.st);
+    return rotconv_pool_bwd_weight(c.ch, c.in, c.out, reinterpret_cast<const uint8_t*>(c.idx), dw, c.cws,
+                                   c.ch->ws_bytes, stream);
+  }
   if (!is_bf16(plan)) return f32_rotconv_pool_bwd_weight(plan, x, gpool, idx, dw, ws, ws_bytes, stream);
   if (!ws || ws_bytes < plan->ws_bytes) return ROTCONV_ERR_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -594,6 +707,7 @@ const char* rotconv_status_string(int status) {
 
 const char* rotconv_plan_kernel_name(const rotconv_plan* plan, int pass) {
   if (!plan || pass < 0 || pass > 2) return "none";
+  if (plan->pad_child && plan->pad_use[pass]) return rotconv_plan_kernel_name(plan->pad_child, pass);
   if (plan->d.dtype == ROTCONV_BF16 && plan->native16[pass]) return "mfma_p4_bf16";
   return plan->fast[pass] ? "mfma_p4" : "generic";
 }

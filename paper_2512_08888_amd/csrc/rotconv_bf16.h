@@ -33,5 +33,8 @@ __device__ __forceinline__ uint32_t match_mask2(uint32_t x16, uint32_t rs2) {
 
 void launch_widen(const uint16_t* in, float* out, size_t n, hipStream_t st);
 void launch_narrow(const float* in, uint16_t* out, size_t n, hipStream_t st);
+// rows of Ws elements (1, 2 or 4 bytes each) -> rows of Wd elements; new columns are filled with `fill`
+void launch_repitch(const void* src, void* dst, size_t rows, int Ws, int Wd, int elem_bytes, uint32_t fill,
+                    hipStream_t st);
 
 }  // namespace rotconv

@@ -1,4 +1,4 @@
-// bf16 <-> fp32 conversion kernels (HBM-bound streaming, 8 elements per lane).
+// Staging kernels: bf16 <-> fp32 conversion (HBM-bound streaming, 8 elements per lane) and row re-pitch.
 #include "rotconv_bf16.h"
 
 #include <algorithm>
@@ -46,6 +46,18 @@ __global__ __launch_bounds__(256) void k_narrow(const float* __restrict__ in, ui
     out[i] = f32_to_bf16(in[i]);
 }
 
+// Row re-pitch: dst rows of Wd elements from src rows of Ws elements; columns beyond Ws get `fill` (Wd < Ws: crop).
+template <typename T>
+__global__ __launch_bounds__(256) void k_repitch(const T* __restrict__ src, T* __restrict__ dst, size_t rows, int Ws,
+                                                 int Wd, T fill) {
+  const size_t total = rows * (size_t)Wd;
+  for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (size_t)gridDim.x * 256) {
+    const size_t r = e / Wd;
+    const int c = (int)(e - r * Wd);
+    dst[e] = c < Ws ? src[r * Ws + c] : fill;
+  }
+}
+
 unsigned blocks_for(size_t n) { return (unsigned)std::max<size_t>(1, std::min<size_t>((n / 8 + 255) / 256, 1u << 16)); }
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
@@ -56,6 +68,21 @@ void launch_widen(const uint16_t* in, float* out, size_t n, hipStream_t st) {
 }
 void launch_narrow(const float* in, uint16_t* out, size_t n, hipStream_t st) {
   hipLaunchKernelGGL(k_narrow, dim3(blocks_for(n)), dim3(256), 0, st, in, out, n, aligned16(in) && aligned16(out) ? 1 : 0);
+}
+
+void launch_repitch(const void* src, void* dst, size_t rows, int Ws, int Wd, int elem_bytes, uint32_t fill,
+                    hipStream_t st) {
+  const size_t total = rows * (size_t)Wd;
+  const unsigned blocks = (unsigned)std::max<size_t>(1, std::min<size_t>((total + 255) / 256, 1u << 16));
+  if (elem_bytes == 1)
+    hipLaunchKernelGGL(k_repitch<uint8_t>, dim3(blocks), dim3(256), 0, st, static_cast<const uint8_t*>(src),
+                       static_cast<uint8_t*>(dst), rows, Ws, Wd, (uint8_t)fill);
+  else if (elem_bytes == 2)
+    hipLaunchKernelGGL(k_repitch<uint16_t>, dim3(blocks), dim3(256), 0, st, static_cast<const uint16_t*>(src),
+                       static_cast<uint16_t*>(dst), rows, Ws, Wd, (uint16_t)fill);
+  else
+    hipLaunchKernelGGL(k_repitch<uint32_t>, dim3(blocks), dim3(256), 0, st, static_cast<const uint32_t*>(src),
+                       static_cast<uint32_t*>(dst), rows, Ws, Wd, fill);
 }
 
 }  // namespace rotconv

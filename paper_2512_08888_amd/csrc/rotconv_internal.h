@@ -75,6 +75,12 @@ struct rotconv_plan {
   // Average pooling (Eq. 9 / Eq. 11): the fused calls run one ordinary convolution (this R = 1 plan with
   // Cout * R/G filters) on the group-averaged bank.  Owned by the parent.
   rotconv_plan* avg_child = nullptr;
+  // Row widths the matrix-core kernels do not take (odd, not a multiple of 4 for the weight gradient, ...): the
+  // fused calls and rotconv_fwd run this plan of the same layer on zero-padded rows (width a multiple of 8) through
+  // staging copies; columns beyond W hold zeros / idx 255, which is what the convolution's own padding supplies.
+  // pad_use[pass]: the pass is faster there.  Owned by the parent.
+  rotconv_plan* pad_child = nullptr;
+  int pad_use[3] = {0, 0, 0};
 };
 
 namespace rotconv {

@@ -68,6 +68,10 @@ TINY = [
     # starting inside a bank (17 chunks of one bank in two parts; 2 x 13 chunks in three)
     LC("t_ksplit_q1", N=1, Cin=24, H=8, W=32, Cout=272, R=4, seed=48),
     LC("t_ksplit_q2", N=1, Cin=16, H=6, W=32, Cout=200, R=8, mode="bilinear", seed=49),
+    # row widths the matrix-core kernels do not take run on rows padded to a multiple of 8 (32 beyond 256 pixels)
+    LC("t_padw_r16", N=1, Cin=40, H=9, W=45, Cout=20, R=16, mode="bilinear", seed=56),
+    LC("t_padw_270", N=1, Cin=4, H=6, W=270, Cout=16, R=4, seed=57),
+    LC("t_padw_g2", N=2, Cin=6, H=7, W=13, Cout=5, R=8, mode="steerable", pool_group=4, seed=58),
     # small maps: one or two chunks per workgroup (three chunks of one bank; 2 x 2 chunks of two banks; six chunks in
     # threes on a map whose dX is not tiny)
     LC("t_ksplit_small", N=1, Cin=70, H=4, W=8, Cout=40, R=4, seed=54),
