@@ -89,7 +89,10 @@ typedef struct {
                                (multiples of 90, so R is 2, 4 or 8), orientation R/2 + a is
                                the left-right mirrored base filter, M[i][j] = W[i][k-1-j],
                                turned by the same angle a*360/(R/2). */
-  int32_t stride, pad;      /* stride >= 1, pad >= 0                                   */
+  int32_t stride, pad;      /* stride >= 1, pad >= 0.  3x3 / stride 1 / pad 1 layers run on the matrix
+                               cores whatever N, Cin, Cout, H, W are (row widths the kernels do not take
+                               directly are staged in the workspace on zero-padded rows, same result);
+                               other k, stride, pad run slower general kernels. */
   int32_t pool_group;       /* G, must divide R; 0 means R (one pooled map per filter) */
   int32_t dtype;            /* rotconv_dtype of x, w, y, ypool, gpool, dy, dx.
                                ROTCONV_BF16: those tensors hold bfloat16; products are
