@@ -219,6 +219,9 @@ def main():
     ap.add_argument("--group", default=None, choices=["p4m8"],
                     help="single-layer workloads: run the layer's shape with another orientation group; p4m8 = four "
                          "quarter turns of the filter and of its mirror image (R = 8, one pool group)")
+    ap.add_argument("--ksize", type=int, default=None,
+                    help="single-layer workloads: run the layer's shape with k x k filters (pad k // 2) instead of 3 x 3")
+    ap.add_argument("--stride", type=int, default=None, help="single-layer workloads: convolution stride")
     ap.add_argument("--no-unet", action="store_true", help="skip the UNet-shaped steps appended to the default line")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -245,6 +248,11 @@ def main():
     if args.group == "p4m8":
         import dataclasses
         cfg = dataclasses.replace(cfg, name=cfg.name + "_p4m8", R=8, mode="p4m", angles_deg=None, pool_group=None)
+    if args.ksize or args.stride:
+        import dataclasses
+        k = args.ksize or cfg.k
+        cfg = dataclasses.replace(cfg, name=f"{cfg.name}_k{k}_s{args.stride or cfg.stride}", k=k, pad=k // 2,
+                                  stride=args.stride or cfg.stride)
     bf = args.dtype == "bf16"
     adt = torch.bfloat16 if bf else torch.float32      # storage of x, w, g, ypool, dx; dw is fp32 either way
     plan = rc.Plan.from_config(cfg, dtype=rc.BF16 if bf else rc.F32, pool_op=args.pool_op)
@@ -328,7 +336,8 @@ def main():
     }
     if not args.no_cpu_baseline and not avg:
         out["cpu_baseline"] = cpu_baseline(cfg, Q)
-    if args.workload == "C2" and not args.no_unet and not bf and not avg and not args.group:
+    if args.workload == "C2" and not args.no_unet and not bf and not avg and not args.group and not args.ksize \
+            and not args.stride:
         # the second half of the headline metric: ms per UNet-shaped training step at R=4 and R=16
         del x, w, g, yp, idx, dx, dw
         out["unet_train_step"] = {n: bench_unet(n, 5, 2) for n in ("C4", "C5")}

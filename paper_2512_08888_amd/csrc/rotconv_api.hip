@@ -9,6 +9,7 @@
 #include "rotconv_kernels.h"
 #include "rotconv_bf16.h"
 #include "rotconv_p4.h"
+#include "rotconv_gs.h"
 
 namespace rotconv {
 
@@ -31,10 +32,13 @@ int ensure_device_tables(rotconv_plan* p) {
   if (p->dev.device >= 0) return ROTCONV_ERR_UNSUPPORTED;  // a plan is bound to the first device it ran on
   const HostTables& t = p->host;
   DeviceTables& d = p->dev;
+  std::vector<int32_t> rq(p->d.R);
+  for (int r = 0; r < p->d.R; ++r) rq[r] = t.bank_of_r[r] * 4 + t.quarter_of_r[r];
   const bool ok = upload(t.exp_src, &d.exp_src) && upload(t.exp_coef, &d.exp_coef) && upload(t.tr_ptr, &d.tr_ptr) &&
                   upload(t.tr_col, &d.tr_col) && upload(t.tr_coef, &d.tr_coef) && upload(t.fq_src, &d.fq_src) &&
                   upload(t.fq_coef, &d.fq_coef) && upload(t.fqt_ptr, &d.fqt_ptr) && upload(t.fqt_col, &d.fqt_col) &&
-                  upload(t.fqt_coef, &d.fqt_coef) && upload(p->rot_of, &d.rot_of);
+                  upload(t.fqt_coef, &d.fqt_coef) && upload(p->rot_of, &d.rot_of) && upload(rq, &d.rq_of_r) &&
+                  upload(t.turn_tap, &d.turn_tap);
   if (!ok) {
     (void)hipGetLastError();
     free_device_tables(p);
@@ -47,7 +51,7 @@ int ensure_device_tables(rotconv_plan* p) {
 void free_device_tables(rotconv_plan* p) {
   DeviceTables& d = p->dev;
   void* ptrs[] = {d.exp_src, d.exp_coef, d.tr_ptr, d.tr_col, d.tr_coef, d.fq_src,
-                  d.fq_coef, d.fqt_ptr, d.fqt_col, d.fqt_coef, d.rot_of};
+                  d.fq_coef, d.fqt_ptr, d.fqt_col, d.fqt_coef, d.rot_of, d.rq_of_r, d.turn_tap};
   for (void* q : ptrs)
     if (q) (void)hipFree(q);
   d = DeviceTables();
@@ -155,6 +159,12 @@ int rotconv_plan_create(const rotconv_desc* desc, rotconv_plan** out) {
     if (p->fast[0] && p4_fwd_bf16_supported(p)) p->ws_bytes = std::max(p->ws_bytes, p4_fwd_bf16_pack_bytes(p));
     if (p->fast[1] && p4_bwd_data_bf16_supported(p))
       p->ws_bytes = std::max(p->ws_bytes, align256(p4_bwd_data_bf16_pack_bytes(p)) + p4_bwd_data_bf16_part_bytes(p));
+  }
+  // other layers (k, stride, pad, or a pool group that cuts through a bank): matrix multiply + scatter
+  const bool is3x3 = p->d.k == 3 && p->d.stride == 1 && p->d.pad == 1;
+  if (!(p->fast[0] && p->fast[1] && p->fast[2]) && !(is3x3 && p4_fwd_pool_mode(p) != kOutUnpooled) && gs_wanted(p)) {
+    p->gs = 1;
+    p->ws_bytes = std::max(p->ws_bytes, gs_ws_bytes(p));
   }
   p->ws_inner = p->ws_bytes = align256(p->ws_bytes);
   const size_t hw_in = (size_t)p->d.H * p->d.W, hw_out = (size_t)p->Ho * p->Wo;
@@ -276,6 +286,10 @@ static int f32_rotconv_fwd(const rotconv_plan* plan, const void* x, const void* 
     launch_p4_fwd(p, kOutUnpooled, static_cast<const float*>(x), wt, static_cast<float*>(y), nullptr, st);
     return finish();
   }
+  if (p->gs) {
+    launch_gs_fwd(p, static_cast<const float*>(x), static_cast<const float*>(w), static_cast<float*>(y), ws, st);
+    return finish();
+  }
   float* wexp = static_cast<float*>(ws);
   launch_expand_bank(p, static_cast<const float*>(w), wexp, st);
   launch_fwd_generic(p, static_cast<const float*>(x), wexp, static_cast<float*>(y), st);
@@ -290,6 +304,10 @@ static int f32_rotconv_bwd_data(const rotconv_plan* plan, const void* dy, const 
   rotconv_plan* p = const_cast<rotconv_plan*>(plan);
   if ((rc = ensure_device_tables(p))) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
+  if (p->gs) {
+    launch_gs_bwd_data(p, static_cast<const float*>(dy), static_cast<const float*>(w), static_cast<float*>(dx), ws, st);
+    return finish();
+  }
   float* wexp = static_cast<float*>(ws);
   launch_expand_bank(p, static_cast<const float*>(w), wexp, st);
   launch_bwd_data_generic(p, static_cast<const float*>(dy), wexp, static_cast<float*>(dx), st);
@@ -304,6 +322,10 @@ static int f32_rotconv_bwd_weight(const rotconv_plan* plan, const void* x, const
   rotconv_plan* p = const_cast<rotconv_plan*>(plan);
   if ((rc = ensure_device_tables(p))) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
+  if (p->gs) {
+    launch_gs_bwd_weight(p, static_cast<const float*>(x), static_cast<const float*>(dy), dw, ws, st);
+    return finish();
+  }
   launch_bwd_weight_generic(p, static_cast<const float*>(x), static_cast<const float*>(dy), nullptr, nullptr,
                             static_cast<float*>(ws), dw, st);
   return finish();
@@ -381,6 +403,11 @@ static int f32_rotconv_pool_fwd(const rotconv_plan* plan, const void* x, const v
     }
     return finish();
   }
+  if (p->gs) {
+    launch_gs_pool_fwd(p, static_cast<const float*>(x), static_cast<const float*>(w), static_cast<float*>(ypool), idx,
+                       ws, st);
+    return finish();
+  }
   float* wexp = static_cast<float*>(ws);
   launch_expand_bank(p, static_cast<const float*>(w), wexp, st);
   launch_pool_fwd_generic(p, static_cast<const float*>(x), wexp, static_cast<float*>(ypool), idx, st);
@@ -413,6 +440,11 @@ static int f32_rotconv_pool_bwd_data(const rotconv_plan* plan, const void* gpool
     launch_p4_bwd_data(p, static_cast<const float*>(gpool), idx, wd, static_cast<float*>(dx), part, st);
     return finish();
   }
+  if (p->gs) {
+    launch_gs_pool_bwd_data(p, static_cast<const float*>(gpool), idx, static_cast<const float*>(w),
+                            static_cast<float*>(dx), ws, st);
+    return finish();
+  }
   float* wexp = static_cast<float*>(ws);
   launch_expand_bank(p, static_cast<const float*>(w), wexp, st);
   launch_pool_bwd_data_generic(p, static_cast<const float*>(gpool), idx, wexp, static_cast<float*>(dx), st);
@@ -442,6 +474,10 @@ static int f32_rotconv_pool_bwd_weight(const rotconv_plan* plan, const void* x, 
   if (p->fast[2] && aligned(x, 16) && aligned(gpool, 16) && aligned(idx, 4) && aligned(ws, 16)) {
     launch_p4_bwd_weight(p, static_cast<const float*>(x), static_cast<const float*>(gpool), idx,
                          static_cast<float*>(ws), dw, st);
+    return finish();
+  }
+  if (p->gs) {
+    launch_gs_pool_bwd_weight(p, static_cast<const float*>(x), static_cast<const float*>(gpool), idx, dw, ws, st);
     return finish();
   }
   launch_bwd_weight_generic(p, static_cast<const float*>(x), nullptr, static_cast<const float*>(gpool), idx,
@@ -709,7 +745,7 @@ const char* rotconv_plan_kernel_name(const rotconv_plan* plan, int pass) {
   if (!plan || pass < 0 || pass > 2) return "none";
   if (plan->pad_child && plan->pad_use[pass]) return rotconv_plan_kernel_name(plan->pad_child, pass);
   if (plan->d.dtype == ROTCONV_BF16 && plan->native16[pass]) return "mfma_p4_bf16";
-  return plan->fast[pass] ? "mfma_p4" : "generic";
+  return plan->fast[pass] ? "mfma_p4" : plan->gs ? "mfma_gemm_scatter" : "generic";
 }
 
 }  // extern "C"

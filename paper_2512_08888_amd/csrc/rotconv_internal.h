@@ -51,6 +51,8 @@ struct DeviceTables {
   int32_t* fqt_col = nullptr;
   float* fqt_coef = nullptr;
   int32_t* rot_of = nullptr;  // [Q*4] orientation index r of (bank q, quarter s), -1 if absent
+  int32_t* rq_of_r = nullptr;   // [R] bank * 4 + quarter turn of orientation r
+  int32_t* turn_tap = nullptr;  // [4*kk] tap position of base tap u after s quarter turns
 };
 
 }  // namespace rotconv
@@ -71,6 +73,7 @@ struct rotconv_plan {
   // other passes run the fp32 kernels on widened copies
   int native16[3] = {0, 0, 0};
   int bwdw_splits = 1;          // pixel splits of the generic weight-gradient kernel
+  int gs = 0;                   // passes without a register-resident kernel run the matrix-multiply + scatter family
   int fwd_csplit[2] = {1, 1};   // fast forward: channel splits for the unpooled / the pooled output (1: none)
   // Average pooling (Eq. 9 / Eq. 11): the fused calls run one ordinary convolution (this R = 1 plan with
   // Cout * R/G filters) on the group-averaged bank.  Owned by the parent.

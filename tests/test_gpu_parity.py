@@ -147,6 +147,44 @@ def test_forward_channel_split_settings(name, parts, monkeypatch):
     pu.assert_close(y.cpu().numpy().reshape(ref["y"].shape), ref["y"], f"{name} y parts={parts}")
 
 
+GS_CASES = [c for c in TINY if c.k != 3 or c.stride != 1 or c.pad != 1 or c.name in ("t_g2", "t_g1")] + [
+    LC("t_gs_k5_r8", N=2, Cin=32, H=24, W=24, Cout=32, k=5, pad=2, R=8, mode="steerable", seed=59),
+    LC("t_gs_s2_k7", N=3, Cin=5, H=21, W=18, Cout=6, k=7, pad=3, stride=2, R=4, seed=60),
+    LC("t_gs_s3_p4m", N=1, Cin=4, H=17, W=16, Cout=5, k=3, pad=0, stride=3, R=8, mode="p4m", pool_group=2, seed=61),
+]
+
+
+@pytest.mark.parametrize("cfg", GS_CASES, ids=lambda c: c.name)
+def test_gemm_scatter_family(cfg, monkeypatch):
+    """Layers outside the register-resident kernels (k, stride, pad, pool groups that cut through a bank) on the
+    matrix-multiply + scatter family, forced on for every size: fused calls, then the unfused chain with a dense dy."""
+    monkeypatch.setenv("ROTCONV_GS", "1")      # read when the plan is created
+    say(f"[case] gemm + scatter {cfg.name}")
+    out = pu.run_fused_parity(cfg)
+    L, ref = out["layer"], out["ref"]
+    names = [L.plan.kernel_name(i) for i in range(3)]
+    assert "mfma_gemm_scatter" in names, names
+    y = L.fwd()
+    pu.assert_close(y.cpu().numpy().reshape(ref["y"].shape), ref["y"], f"{cfg.name} y")
+    x = out["x"]
+    dyd = synth.make_dy(cfg)
+    ang = None if cfg.angles_deg is None else list(cfg.angles_deg)
+    dyd5 = dyd.reshape(cfg.N, cfg.Cout, cfg.R, cfg.Ho, cfg.Wo)
+    dx_ref = orc.rotconv_bwd_data(dyd5, ref["w_rot"], cfg.H, cfg.W, cfg.stride, cfg.pad)
+    dw_ref = orc.reduce_bank_grad(orc.rotconv_bwd_weight(x, dyd5, cfg.k, cfg.stride, cfg.pad), ang, cfg.mode)
+    dyd_d = pu.dev(dyd, torch.float32)
+    pu.assert_close(L.bwd_data(dyd_d), dx_ref, f"{cfg.name} dx (dense dy)")
+    pu.assert_close(L.bwd_weight(dyd_d), dw_ref, f"{cfg.name} dw (dense dy)")
+    if cfg.mode == "exact90":
+        pu.run_fused_parity(cfg, dyadic=True, label=f"{cfg.name} dyadic")
+
+
+def test_gemm_scatter_family_is_the_default_for_larger_layers():
+    cfg = next(c for c in GS_CASES if c.name == "t_gs_k5_r8")
+    L = pu.GpuLayer(cfg, synth.make_x(cfg), synth.make_w(cfg))
+    assert [L.plan.kernel_name(i) for i in range(3)] == ["mfma_gemm_scatter"] * 3
+
+
 def test_config1_fused_and_unfused():
     """Benchmark configuration 1 (N=1, 3->8, 64x64, R=4): both call chains, continuous and dyadic."""
     cfg = synth.C1
