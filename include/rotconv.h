@@ -37,7 +37,14 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls
  *     only enqueue work; nothing synchronises with the host.  Outputs are
  *     overwritten, never accumulated into.  Same inputs give bitwise the same
- *     outputs on every run (no floating-point atomics anywhere).
+ *     outputs on every run (no floating-point atomics anywhere).  A plan's first
+ *     call on a device uploads its tables (the only allocation and host-to-device
+ *     copy the library makes); every later call launches kernels only, so it can
+ *     be recorded into a HIP graph and replayed.
+ *   - Two environment variables are read when a plan is created and tune its
+ *     kernel choice: ROTCONV_FWD_CSPLIT (0 / unset: automatic; 1: never split the
+ *     forward's channel contraction; n: n parts) and ROTCONV_GS (0 / 1: never /
+ *     always run shapes outside the 3x3 kernels on the GEMM + scatter family).
  *   - `ws` is a DEVICE scratch buffer of at least rotconv_workspace_bytes(plan)
  *     bytes, 256-byte aligned; its contents are undefined between calls, and
  *     two calls sharing one ws must not overlap in time.
