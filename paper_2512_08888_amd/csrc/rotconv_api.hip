@@ -164,6 +164,7 @@ int rotconv_plan_create(const rotconv_desc* desc, rotconv_plan** out) {
   const bool is3x3 = p->d.k == 3 && p->d.stride == 1 && p->d.pad == 1;
   if (!(p->fast[0] && p->fast[1] && p->fast[2]) && !(is3x3 && p4_fwd_pool_mode(p) != kOutUnpooled) && gs_wanted(p)) {
     p->gs = 1;
+    p->gs_chunk_bytes = gs_chunk_budget();
     p->ws_bytes = std::max(p->ws_bytes, gs_ws_bytes(p));
   }
   p->ws_inner = p->ws_bytes = align256(p->ws_bytes);

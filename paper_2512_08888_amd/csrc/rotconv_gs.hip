@@ -210,7 +210,7 @@ __global__ __launch_bounds__(256) void k_gs_reduce_w(const float* __restrict__ d
 // images whose products / routed gradients are held at once: at most 512 MiB of them, at least one image
 int chunk_images(const rotconv_plan* p) {
   const double per = 4.0 * p->host.Q * p->d.Cout * p->kk * p->d.H * p->d.W;
-  return (int)std::max(1.0, std::min((double)p->d.N, 536870912.0 / per));
+  return (int)std::max(1.0, std::min((double)p->d.N, (double)p->gs_chunk_bytes / per));
 }
 
 // split of the weight gradient's pixel contraction: enough workgroups to fill the chip, at least 256 pixels each
@@ -338,6 +338,15 @@ bool gs_wanted(const rotconv_plan* p) {
   if (const char* e = std::getenv("ROTCONV_GS")) return std::atoi(e) != 0;
   const double flops = 2.0 * p->d.N * p->d.H * p->d.W * p->d.Cin * p->d.Cout * p->kk * p->host.Q;
   return flops >= 1.0e8;
+}
+
+// ROTCONV_GS_CHUNK_MB (read when the plan is created): the budget for the images held at once, in MiB.
+size_t gs_chunk_budget() {
+  if (const char* e = std::getenv("ROTCONV_GS_CHUNK_MB")) {
+    const long mb = std::atol(e);
+    if (mb >= 0) return (size_t)mb << 20;
+  }
+  return (size_t)512 << 20;
 }
 
 size_t gs_ws_bytes(const rotconv_plan* p) { return gs_layout(p).total; }

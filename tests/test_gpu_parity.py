@@ -179,6 +179,17 @@ def test_gemm_scatter_family(cfg, monkeypatch):
         pu.run_fused_parity(cfg, dyadic=True, label=f"{cfg.name} dyadic")
 
 
+def test_gemm_scatter_family_one_image_at_a_time(monkeypatch):
+    """With no room for more than one image's products the family walks the batch image by image (the weight
+    gradient accumulates its per-image sums in order)."""
+    monkeypatch.setenv("ROTCONV_GS", "1")
+    monkeypatch.setenv("ROTCONV_GS_CHUNK_MB", "0")
+    cfg = next(c for c in GS_CASES if c.name == "t_gs_s2_k7")
+    say(f"[case] gemm + scatter, one image per chunk {cfg.name}")
+    pu.run_fused_parity(cfg)
+    pu.run_fused_parity(cfg, dyadic=True, label=f"{cfg.name} dyadic")
+
+
 def test_gemm_scatter_family_is_the_default_for_larger_layers():
     cfg = next(c for c in GS_CASES if c.name == "t_gs_k5_r8")
     L = pu.GpuLayer(cfg, synth.make_x(cfg), synth.make_w(cfg))
