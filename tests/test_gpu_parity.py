@@ -346,6 +346,28 @@ def test_config3_full_size_sampled():
     full_size_sampled_parity(synth.C3, n_samples=2048, n_pairs=12)
 
 
+def test_odd_width_full_size_sampled():
+    """Configuration 2's channels on 255 x 255 images: the matrix-core kernels on zero-padded rows."""
+    cfg = dataclasses.replace(synth.C2, name="C2_255", N=4, H=255, W=255)
+    L = full_size_sampled_parity(cfg, n_samples=2048, n_pairs=12)
+    assert [L.plan.kernel_name(i) for i in range(3)] == ["mfma_p4"] * 3
+
+
+def test_k5_full_size_sampled():
+    """Configuration 2's shape with 5 x 5 filters: GEMM + scatter, several image chunks."""
+    cfg = dataclasses.replace(synth.C2, name="C2_k5", N=4, k=5, pad=2)
+    L = full_size_sampled_parity(cfg, n_samples=2048, n_pairs=12)
+    assert [L.plan.kernel_name(i) for i in range(3)] == ["mfma_gemm_scatter"] * 3
+
+
+def test_small_map_deep_channels_sampled():
+    """A point of the single-orientation sweep and its R = 4 counterpart: 32 x 32 maps, 1024 -> 256 channels (the
+    forward splits its channel chunks, the input gradient its weight chunks)."""
+    for R in (1, 4):
+        cfg = LC(f"sweep32_R{R}", N=1, Cin=1024, H=32, W=32, Cout=256, R=R, seed=62 + R)
+        full_size_sampled_parity(cfg, n_samples=1024, n_pairs=8)
+
+
 def test_config3_steerable_and_group4_reduced():
     """Config-3 structure (R=16, 22.5 degree steps) in steerable mode and with the paper's
     sub-group pooling (G=4), at a size the oracle finishes in seconds."""
