@@ -38,7 +38,7 @@ int ensure_device_tables(rotconv_plan* p) {
                   upload(t.tr_col, &d.tr_col) && upload(t.tr_coef, &d.tr_coef) && upload(t.fq_src, &d.fq_src) &&
                   upload(t.fq_coef, &d.fq_coef) && upload(t.fqt_ptr, &d.fqt_ptr) && upload(t.fqt_col, &d.fqt_col) &&
                   upload(t.fqt_coef, &d.fqt_coef) && upload(p->rot_of, &d.rot_of) && upload(rq, &d.rq_of_r) &&
-                  upload(t.turn_tap, &d.turn_tap);
+                  upload(t.turn_tap, &d.turn_tap) && upload(t.lut_bwd, &d.lut_bwd);
   if (!ok) {
     (void)hipGetLastError();
     free_device_tables(p);
@@ -51,7 +51,7 @@ int ensure_device_tables(rotconv_plan* p) {
 void free_device_tables(rotconv_plan* p) {
   DeviceTables& d = p->dev;
   void* ptrs[] = {d.exp_src, d.exp_coef, d.tr_ptr, d.tr_col, d.tr_coef, d.fq_src,
-                  d.fq_coef, d.fqt_ptr, d.fqt_col, d.fqt_coef, d.rot_of, d.rq_of_r, d.turn_tap};
+                  d.fq_coef, d.fqt_ptr, d.fqt_col, d.fqt_coef, d.rot_of, d.rq_of_r, d.turn_tap, d.lut_bwd};
   for (void* q : ptrs)
     if (q) (void)hipFree(q);
   d = DeviceTables();

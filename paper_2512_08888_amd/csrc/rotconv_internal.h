@@ -36,6 +36,8 @@ struct HostTables {
   // Quarter-turn tap permutation: turn_tap[s*kk + u] = index of the tap where base tap u
   // sits after s quarter turns (Eq. 8: (m',n') = R_s(m,n)).
   std::vector<int32_t> turn_tap;  // [4*kk]
+  // 3x3 plans with one base bank: [9 neighbour offsets][R + 1][12] routed-gradient coefficients (see rotconv_host.cpp)
+  std::vector<float> lut_bwd;
 };
 
 struct DeviceTables {
@@ -53,6 +55,7 @@ struct DeviceTables {
   int32_t* rot_of = nullptr;  // [Q*4] orientation index r of (bank q, quarter s), -1 if absent
   int32_t* rq_of_r = nullptr;   // [R] bank * 4 + quarter turn of orientation r
   int32_t* turn_tap = nullptr;  // [4*kk] tap position of base tap u after s quarter turns
+  float* lut_bwd = nullptr;     // HostTables::lut_bwd (one element if the plan has none)
 };
 
 }  // namespace rotconv

@@ -67,6 +67,7 @@ struct P4BwdGeom {
   int ksplit;  // workgroups that share a unit's contraction (each writes an fp32 partial dX); 1 = no split
   int kper;    // weight chunks (16 filters of a bank) per such workgroup
   int units;   // workgroups with work (includes the split)
+  int lut;     // routed-gradient table: the contraction runs over the base bank only (Q is 1 then)
 };
 bool p4_bwd_data_supported(const rotconv_plan* p);
 P4BwdGeom p4_bwd_data_geom(const rotconv_plan* p);

@@ -21,6 +21,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cstdlib>
 
 #include "rotconv_bf16.h"
 #include "rotconv_kernels.h"
@@ -55,12 +56,21 @@ struct Raw {           // (G, idx) of one filter on a 3 x (PX + 2) pixel neighbo
 
 // PX = pixels per lane (2 or 4): a wave owns one image row x 16 PX pixels x 64 input channels.  More pixels
 // per lane means fewer selects and loads per pixel (the 3 x (PX + 2) neighbourhood is shared by PX pixels).
-template <int PX>
+// LUT: one pool group holds all R orientations of a filter and there is one base bank.  After the max-pool a (filter,
+// pixel) carries one orientation, so the gradient reaching BASE tap u' through the neighbour at offset (dy, dx) is
+// G * lut[offset][idx][u'] (the rotated banks' coefficients, looked up per value): the routed gradients of all banks
+// are summed into the base taps before the contraction, which then runs over the base bank alone, one
+// conv-equivalent of matrix work instead of Q, and the neighbourhood is loaded once instead of once per bank.
+template <int PX, bool LUT>
 __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gpool, const uint8_t* __restrict__ idx,
                                                     const float* __restrict__ wd,
-                                                    const int32_t* __restrict__ rot_of, float* __restrict__ dx,
-                                                    P4BwdGeom g) {
-  extern __shared__ float smem[];      // [2][CHUNK][WROW]
+                                                    const int32_t* __restrict__ rot_of, const float* __restrict__ lut,
+                                                    float* __restrict__ dx, P4BwdGeom g) {
+  extern __shared__ float smem[];      // [2][CHUNK][WROW], then the table [9][R + 1][12] (LUT)
+  float* Tl = smem + 2 * CHUNK * WROW;
+  const int R1 = g.R + 1;
+  if (LUT)
+    for (int i = threadIdx.x; i < 9 * R1 * 12; i += NT) Tl[i] = lut[i];
 
   const int per_xcd = (g.units + 7) / 8;
   int v = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
@@ -214,6 +224,44 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gp
       }
   };
 
+  // LUT build of the nine base-tap sums (see the kernel's head).  lut_prepare: per neighbourhood value its gradient
+  // (dropped for an idx outside [0, R), which also selects the all-zero table row) and its row offset.  The sums are
+  // then formed in 9 PX blocks, block = (row dr, pixel b, column offset dc - 1): nine multiply-adds of the value with
+  // the table row of (offset, orientation).  lut_read issues a block's row reads ahead of a tap's matrix instructions,
+  // lut_fma consumes them behind those.
+  struct LutVals { float gv[3][PX + 2]; uint32_t off[3][PX + 2]; };
+  struct LutRow { f4 t0, t1; float t8; };
+  auto lut_prepare = [&](const Raw<PX>& r, LutVals& v) {
+#pragma unroll
+    for (int dr = 0; dr < 3; ++dr) {
+      const uint32_t iwc = r.ic[dr] | invc[dr] | r.finv | (PX == 2 ? 0xffff0000u : 0u);
+      const uint32_t iwe = (r.il[dr] | (r.ir[dr] << 8)) | inve[dr] | r.finv;
+#pragma unroll
+      for (int c = 0; c < PX + 2; ++c) {
+        const uint32_t byte = c == 0 ? (iwe & 0xffu) : c == PX + 1 ? ((iwe >> 8) & 0xffu) : ((iwc >> (8 * (c - 1))) & 0xffu);
+        const float gval = c == 0 ? r.gl[dr] : c == PX + 1 ? r.gr[dr] : r.gc[dr][c - 1];
+        v.gv[dr][c] = byte < (uint32_t)g.R ? gval : 0.f;
+        v.off[dr][c] = min(byte, (uint32_t)g.R) * 12u;
+      }
+    }
+  };
+  auto lut_read = [&](const LutVals& v, int blk) -> LutRow {
+    const int dr = blk / (3 * PX), bb = (blk % (3 * PX)) / 3, dc = blk % 3;
+    const float* t = Tl + (dr * 3 + dc) * R1 * 12 + v.off[dr][bb + dc];   // neighbour at column offset dc - 1 of pixel bb
+    LutRow row;
+    row.t0 = *reinterpret_cast<const f4*>(t);
+    row.t1 = *reinterpret_cast<const f4*>(t + 4);
+    row.t8 = t[8];
+    return row;
+  };
+  auto lut_fma = [&](const LutVals& v, int blk, const LutRow& row, float (&a)[9][PX]) {
+    const int dr = blk / (3 * PX), bb = (blk % (3 * PX)) / 3, dc = blk % 3;
+    const float gvc = v.gv[dr][bb + dc];
+    const float tv[9] = {row.t0[0], row.t0[1], row.t0[2], row.t0[3], row.t1[0], row.t1[1], row.t1[2], row.t1[3], row.t8};
+#pragma unroll
+    for (int u = 0; u < 9; ++u) a[u][bb] = (dr == 0 && dc == 0) ? gvc * tv[u] : a[u][bb] + gvc * tv[u];
+  };
+
   f4 acc[NCB][PX];
 #pragma unroll
   for (int cb = 0; cb < NCB; ++cb)
@@ -244,23 +292,53 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gp
     // one tap ahead; the fences keep it there.
     f4 bw[2];
     bw[0] = *reinterpret_cast<const f4*>(wl + (ks * 4) * WROW);
+    // LUT: PX blocks of the next K-step's sums per tap, their table rows read one tap ahead
+    LutVals lv;
+    LutRow lrow[PX];
+    if (LUT) lut_prepare(raw_use, lv);
 #pragma unroll
     for (int u = 0; u < 9; ++u) {
       if (u < 8) bw[(u + 1) & 1] = *reinterpret_cast<const f4*>(wl + (ks * 4) * WROW + (u + 1) * CIG);
+      if (LUT) {      // read ahead of the tap's matrix instructions, used behind them
+#pragma unroll
+        for (int i = 0; i < PX; ++i) lrow[i] = lut_read(lv, u * PX + i);
+      }
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int cb = 0; cb < NCB; ++cb)
 #pragma unroll
         for (int b = 0; b < PX; ++b)
           acc[cb][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur[u][b], bw[u & 1][cb], acc[cb][b], 0, 0, 0);
-      if ((u & 1) == 0 && u < 8) build_slice(raw_use, u / 2, rotb[u / 2], a_nxt);
+      if (LUT) {
+#pragma unroll
+        for (int i = 0; i < PX; ++i) lut_fma(lv, u * PX + i, lrow[i], a_nxt);
+        // the sums are first used in the next stage's block: left alone, the compiler sinks all their multiply-adds
+        // there and keeps every table row live until then
+#pragma unroll
+        for (int i = 0; i < PX; ++i)
+#pragma unroll
+          for (int t = 0; t < 9; ++t) asm volatile("" : "+v"(a_nxt[t][(u * PX + i) % (3 * PX) / 3]));
+      } else if ((u & 1) == 0 && u < 8) {
+        build_slice(raw_use, u / 2, rotb[u / 2], a_nxt);
+      }
       __builtin_amdgcn_sched_barrier(0);
     }
   };
 
   raw_load(rawB);
+  if (LUT) __syncthreads();            // the table is in LDS
+  if (LUT) {
+    LutVals lv;
+    lut_prepare(rawB, lv);
 #pragma unroll
-  for (int s = 0; s < 4; ++s) build_slice(rawB, s, rotb[s], aA);
+    for (int blk = 0; blk < 9 * PX; ++blk) {
+      lut_fma(lv, blk, lut_read(lv, blk), aA);
+      __builtin_amdgcn_sched_barrier(0);      // one block's rows at a time (all at once would spill)
+    }
+  } else {
+#pragma unroll
+    for (int s = 0; s < 4; ++s) build_slice(rawB, s, rotb[s], aA);
+  }
   raw_load(rawA);
 #pragma unroll
   for (int part = 0; part < 4; ++part) {
@@ -328,7 +406,8 @@ __global__ __launch_bounds__(256) void k_p4_sum_dx(const float* __restrict__ par
 __global__ __launch_bounds__(256) void k_p4_pack_bwd(const float* __restrict__ w, float* __restrict__ wd,
                                                      const int32_t* __restrict__ fq_src,
                                                      const float* __restrict__ fq_coef, int Q, int CoutPad,
-                                                     int CinPad, int Cin, int Cout, int round16) {
+                                                     int CinPad, int Cin, int Cout, int round16, int base) {
+  // base: the base bank itself (Q = 1, no expansion)
   // One thread per (bank, filter, channel position): its nine taps read the same 36 bytes of w.
   const int total = Q * CoutPad * CinPad;
   const int e = blockIdx.x * 256 + threadIdx.x;
@@ -346,10 +425,14 @@ __global__ __launch_bounds__(256) void k_p4_pack_bwd(const float* __restrict__ w
 #pragma unroll
   for (int u = 0; u < 9; ++u) {
     float acc = 0.f;
+    if (base) {
+      acc = in ? src[u] : 0.f;
+    } else {
 #pragma unroll
-    for (int z = 0; z < kMaxNnz; ++z) {
-      const int s = fq_src[(q * 9 + u) * kMaxNnz + z];
-      if (in && s >= 0) acc += fq_coef[(q * 9 + u) * kMaxNnz + z] * src[(size_t)(s / 9) * slices * 9 + s % 9];
+      for (int z = 0; z < kMaxNnz; ++z) {
+        const int s = fq_src[(q * 9 + u) * kMaxNnz + z];
+        if (in && s >= 0) acc += fq_coef[(q * 9 + u) * kMaxNnz + z] * src[(size_t)(s / 9) * slices * 9 + s % 9];
+      }
     }
     dst[(size_t)u * CinPad] = round16 ? bf16_to_f32(f32_to_bf16(acc)) : acc;   // bf16 plans keep the expanded banks in bf16 precision
   }
@@ -369,9 +452,16 @@ P4BwdGeom p4_bwd_data_geom(const rotconv_plan* p) {
   P4BwdGeom g{};
   g.N = d.N; g.Cin = d.Cin; g.CinPad = (d.Cin + CIG - 1) / CIG * CIG; g.H = d.H; g.W = d.W; g.Cout = d.Cout;
   g.CoutPad = (d.Cout + 15) / 16 * 16; g.R = d.R; g.Q = p->host.Q; g.ng = p->ng;
+  // routed-gradient table instead of per-bank sums: one pool group per filter, one base bank, several banks to save
+  // (ROTCONV_BWD_LUT=0, read here, keeps the per-bank kernel)
+  g.lut = !p->host.lut_bwd.empty() && p->host.Q >= 2 && p->ng == 1 && d.R <= 32 && d.dtype != ROTCONV_BF16;
+  if (g.lut)
+    if (const char* e = std::getenv("ROTCONV_BWD_LUT")) g.lut = std::atoi(e) != 0;
+  if (g.lut) g.Q = 1;
   g.ncig = g.CinPad / CIG; g.nrb = (d.H + NWAVE - 1) / NWAVE;
   // pixels per lane: four when the rows are long enough and that still leaves a workgroup per CU
   g.px = ((d.W & 3) == 0 && d.W > 32 && d.N * g.ncig * g.nrb * ((d.W + 63) / 64) >= 256) ? 4 : 2;
+  if (g.lut) g.px = 2;      // the table build is made for two pixels per lane (four would spill)
   g.nstrip = (d.W + 16 * g.px - 1) / (16 * g.px);
   g.units = d.N * g.ncig * g.nstrip * g.nrb;
   // Few units and a long contraction: share its weight chunks (16 filters of a bank) out so that the chip is filled
@@ -414,24 +504,22 @@ void launch_p4_pack_bwd(const rotconv_plan* p, const float* w, float* wd, hipStr
   const P4BwdGeom g = p4_bwd_data_geom(p);
   const int total = g.Q * g.CoutPad * g.CinPad;
   hipLaunchKernelGGL(k_p4_pack_bwd, dim3((total + 255) / 256), dim3(256), 0, st, w, wd, p->dev.fq_src, p->dev.fq_coef,
-                     g.Q, g.CoutPad, g.CinPad, g.Cin, g.Cout, p->d.dtype == ROTCONV_BF16 ? 1 : 0);
+                     g.Q, g.CoutPad, g.CinPad, g.Cin, g.Cout, p->d.dtype == ROTCONV_BF16 ? 1 : 0, g.lut);
 }
 
 void launch_p4_bwd_data(const rotconv_plan* p, const float* gpool, const uint8_t* idx, const float* wd, float* dx_out,
                         float* part, hipStream_t st) {
   const P4BwdGeom g = p4_bwd_data_geom(p);
   float* dx = g.ksplit > 1 ? part : dx_out;
-  const size_t lds = (size_t)2 * CHUNK * WROW * sizeof(float);
+  const size_t lds = ((size_t)2 * CHUNK * WROW + (g.lut ? 9 * (g.R + 1) * 12 : 0)) * sizeof(float);
   const int grid = (g.units + 7) / 8 * 8;
-  if (g.px == 4) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_p4_bwd_data<4>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    hipLaunchKernelGGL(k_p4_bwd_data<4>, dim3(grid), dim3(NT), lds, st, gpool, idx, wd, p->dev.rot_of, dx, g);
-  } else {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(k_p4_bwd_data<2>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    hipLaunchKernelGGL(k_p4_bwd_data<2>, dim3(grid), dim3(NT), lds, st, gpool, idx, wd, p->dev.rot_of, dx, g);
-  }
+  auto go = [&](auto kern) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(NT), lds, st, gpool, idx, wd, p->dev.rot_of, p->dev.lut_bwd, dx, g);
+  };
+  if (g.px == 4) go(k_p4_bwd_data<4, false>);
+  else if (g.lut) go(k_p4_bwd_data<2, true>);
+  else go(k_p4_bwd_data<2, false>);
   if (g.ksplit > 1) {
     const size_t n_elem = (size_t)p->d.N * p->d.Cin * p->d.H * p->d.W;
     const unsigned blocks = (unsigned)std::max<size_t>(1, std::min<size_t>((n_elem / 4 + 255) / 256, 1u << 16));
