@@ -69,6 +69,7 @@ struct P4BwdGeom {
   int units;   // workgroups with work (includes the split)
   int lut;     // routed-gradient table: the contraction runs over the base bank only (Q is 1 then)
 };
+bool p4_bwd_lut(const rotconv_plan* p);   // the fp32 gradients use the routed-gradient table (contraction over the base bank)
 bool p4_bwd_data_supported(const rotconv_plan* p);
 P4BwdGeom p4_bwd_data_geom(const rotconv_plan* p);
 size_t p4_bwd_data_pack_floats(const rotconv_plan* p);
@@ -105,9 +106,10 @@ struct P4BwdWGeom {
   int nrange;    // row ranges per image
   int units;     // (image, range, strip) work units
   int splits;    // workgroups per (bank, filter group, channel group); their sums are added in order
+  int lut, R;    // routed-gradient table: the sums are those of the base bank (Q is 1 then); orientations
 };
 bool p4_bwd_weight_supported(const rotconv_plan* p);
-P4BwdWGeom p4_bwd_weight_geom(const rotconv_plan* p);
+P4BwdWGeom p4_bwd_weight_geom(const rotconv_plan* p, bool lut = false);
 size_t p4_bwd_weight_ws_floats(const rotconv_plan* p);
 void launch_p4_bwd_weight(const rotconv_plan* p, const float* x, const float* gpool, const uint8_t* idx,
                           float* partial, float* dw, hipStream_t st);

@@ -440,6 +440,14 @@ __global__ __launch_bounds__(256) void k_p4_pack_bwd(const float* __restrict__ w
 
 }  // namespace
 
+// The fp32 gradients run over the base bank through the routed-gradient table: one pool group per filter, one base
+// bank, several banks to save (ROTCONV_BWD_LUT=0, read at every call, keeps the per-bank kernels).
+bool p4_bwd_lut(const rotconv_plan* p) {
+  if (p->host.lut_bwd.empty() || p->host.Q < 2 || p->ng != 1 || p->d.R > 32 || p->d.dtype == ROTCONV_BF16) return false;
+  if (const char* e = std::getenv("ROTCONV_BWD_LUT")) return std::atoi(e) != 0;
+  return true;
+}
+
 bool p4_bwd_data_supported(const rotconv_plan* p) {
   const rotconv_desc& d = p->d;
   if (d.k != 3 || d.stride != 1 || d.pad != 1) return false;   // bf16 plans run these kernels on widened copies
@@ -452,11 +460,8 @@ P4BwdGeom p4_bwd_data_geom(const rotconv_plan* p) {
   P4BwdGeom g{};
   g.N = d.N; g.Cin = d.Cin; g.CinPad = (d.Cin + CIG - 1) / CIG * CIG; g.H = d.H; g.W = d.W; g.Cout = d.Cout;
   g.CoutPad = (d.Cout + 15) / 16 * 16; g.R = d.R; g.Q = p->host.Q; g.ng = p->ng;
-  // routed-gradient table instead of per-bank sums: one pool group per filter, one base bank, several banks to save
-  // (ROTCONV_BWD_LUT=0, read here, keeps the per-bank kernel)
-  g.lut = !p->host.lut_bwd.empty() && p->host.Q >= 2 && p->ng == 1 && d.R <= 32 && d.dtype != ROTCONV_BF16;
-  if (g.lut)
-    if (const char* e = std::getenv("ROTCONV_BWD_LUT")) g.lut = std::atoi(e) != 0;
+  // routed-gradient table instead of per-bank sums
+  g.lut = p4_bwd_lut(p) ? 1 : 0;
   if (g.lut) g.Q = 1;
   g.ncig = g.CinPad / CIG; g.nrb = (d.H + NWAVE - 1) / NWAVE;
   // pixels per lane: four when the rows are long enough and that still leaves a workgroup per CU

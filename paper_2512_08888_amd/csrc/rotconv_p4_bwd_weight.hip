@@ -47,11 +47,21 @@ struct RowW {            // (G, idx) of one filter on one image row as loaded: t
   uint32_t il, ir;       // idx of the neighbours
 };
 
-template <int NCB>
+// LUT: one pool group holds all R orientations of a filter and there is one base bank: D is formed for the BASE taps,
+// D[u'][pixel] = sum over the 3 x 3 neighbours of G * lut[offset][idx][u'] (idx is one-hot after the max-pool; the
+// table row holds the rotated bank's coefficients of the base taps), so the contraction runs once instead of once
+// per bank and its result is the base-bank gradient itself.
+template <int NCB, bool LUT>
 __global__ __launch_bounds__(NT) void k_p4_bwd_weight(const float* __restrict__ x, const float* __restrict__ gpool,
                                                       const uint8_t* __restrict__ idx,
-                                                      const int32_t* __restrict__ rot_of,
+                                                      const int32_t* __restrict__ rot_of, const float* __restrict__ lut,
                                                       float* __restrict__ partial, P4BwdWGeom g) {
+  __shared__ float Tl[LUT ? 9 * 33 * 12 : 4];
+  const int R1 = g.R + 1;
+  if (LUT) {
+    for (int i = threadIdx.x; i < 9 * R1 * 12; i += NT) Tl[i] = lut[i];
+    __syncthreads();
+  }
   // Consecutive indices go to one XCD: the (bank, filter group, channel group) combinations of one work
   // unit share its X and (G, idx) lines in that XCD's L2, and so do the strips of one row range, whose halo
   // columns lie in their neighbours' lines.
@@ -82,8 +92,8 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_weight(const float* __restrict__ 
     rot[s] = rot_of[q * 4 + s];
     if (r0 < 0 && rot[s] >= 0) r0 = rot[s];
   }
-  const bool cok = co < g.Cout && r0 >= 0;
-  const size_t gplane0 = ((size_t)(cok ? co : 0) * g.ng + (r0 < 0 ? 0 : r0 % g.ng)) * HW;
+  const bool cok = co < g.Cout && (LUT || r0 >= 0);
+  const size_t gplane0 = ((size_t)(cok ? co : 0) * g.ng + (LUT || r0 < 0 ? 0 : r0 % g.ng)) * HW;
   const size_t gimg = (size_t)g.Cout * g.ng * HW;
   const size_t ximg = (size_t)g.Cin * HW;
 
@@ -133,6 +143,39 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_weight(const float* __restrict__ 
       for (int s = 1; s < 4; ++s) v += at(2 - tap_i(s, u), s, 4 * j + t + 2 - tap_j(s, u));
       a[u][t] = v;
     }
+  };
+
+  // LUT: a row as kept for the three rows it serves: per column (0 left neighbour, 1..8 the lane's pixels, 9 right
+  // neighbour) the gradient (zero where the position or its idx is not valid) and the table-row offset of its idx
+  // (an idx outside [0, R) selects the all-zero row).
+  struct LutRowW { float gv[10]; uint32_t off[10]; };
+  auto lut_route = [&](const RowW& r, bool rok, bool pok0, bool pok1, bool lok, bool rok2, LutRowW& m) {
+    const uint32_t ic0 = (rok && pok0) ? r.i0 : 0xffffffffu, ic1 = (rok && pok1) ? r.i1 : 0xffffffffu;
+    const uint32_t il = (rok && lok) ? r.il : 0xffu, ir = (rok && rok2) ? r.ir : 0xffu;
+    const float gc[8] = {r.g0[0], r.g0[1], r.g0[2], r.g0[3], r.g1[0], r.g1[1], r.g1[2], r.g1[3]};
+#pragma unroll
+    for (int c = 0; c < 10; ++c) {
+      const uint32_t byte = c == 0 ? il : c == 9 ? ir : c < 5 ? ((ic0 >> (8 * (c - 1))) & 0xffu) : ((ic1 >> (8 * (c - 5))) & 0xffu);
+      const float gval = c == 0 ? r.gl : c == 9 ? r.gr : gc[c - 1];
+      m.gv[c] = byte < (uint32_t)g.R ? gval : 0.f;
+      m.off[c] = min(byte, (uint32_t)g.R) * 12u;
+    }
+  };
+  struct LutT { f4 t0, t1; float t8; };
+  // block (dr, dc) of pixel column pc (1..8): the neighbour in row dr at column pc + dc - 1
+  auto lut_read = [&](const LutRowW& row, int dr, int dc, int pc) -> LutT {
+    const float* t = Tl + (dr * 3 + dc) * R1 * 12 + row.off[pc + dc - 1];
+    LutT v;
+    v.t0 = *reinterpret_cast<const f4*>(t);
+    v.t1 = *reinterpret_cast<const f4*>(t + 4);
+    v.t8 = t[8];
+    return v;
+  };
+  auto lut_fma = [&](const LutRowW& row, int dr, int dc, int pc, const LutT& v, int t, float (&a)[9][4]) {
+    const float gvc = row.gv[pc + dc - 1];
+    const float tv[9] = {v.t0[0], v.t0[1], v.t0[2], v.t0[3], v.t1[0], v.t1[1], v.t1[2], v.t1[3], v.t8};
+#pragma unroll
+    for (int u = 0; u < 9; ++u) a[u][t] = (dr == 0 && dc == 0) ? gvc * tv[u] : a[u][t] + gvc * tv[u];
   };
 
   // Work units: (image, row range, 32-pixel strip).  A lane owns pixels px0 .. px0+7 of the strip; it walks
@@ -220,21 +263,90 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_weight(const float* __restrict__ 
       }
       __builtin_amdgcn_sched_barrier(0);
     };
-    load_row(h0 - 1, rn);
-    route(rn, h0 - 1, m0);
-    load_row(h0, rn);
-    route(rn, h0, m1);
-    load_row(h0 + 1, rn);
-    route(rn, h0 + 1, m2);
-    load_x(h0, 0, bA);
+    // LUT: the same walk with the rows kept as (gradient, table offset) pairs.  Per pixel t of a half: three groups of
+    // (three table-row reads, the matrix instructions of three taps, 27 multiply-adds into the next half's D); the
+    // fences keep a group's reads ahead of its matrix instructions and the opaque uses keep its multiply-adds behind
+    // them (the sums are first needed in the next half: left alone, the compiler sinks all of them there).
+    auto lut_half = [&](const float (&a)[9][4], const f4 (&b)[NCB], int t, const LutRowW& ra, const LutRowW& rb,
+                        const LutRowW& rc, int j, float (&an)[9][4]) {
+      const int pc = 4 * j + t + 1;
 #pragma unroll
-    for (int t = 0; t < 4; ++t) build_pixel(m0, m1, m2, 0, t, aA);
-    for (int h = h0; h < h1; h += 3) {
-      step(h, m0, m1, m2);
-      if (h + 1 >= h1) break;
-      step(h + 1, m1, m2, m0);
-      if (h + 2 >= h1) break;
-      step(h + 2, m2, m0, m1);
+      for (int dr = 0; dr < 3; ++dr) {
+        const LutRowW& row = dr == 0 ? ra : dr == 1 ? rb : rc;
+        LutT v[3];
+#pragma unroll
+        for (int dc = 0; dc < 3; ++dc) v[dc] = lut_read(row, dr, dc, pc);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int u = 3 * dr; u < 3 * dr + 3; ++u)
+#pragma unroll
+          for (int cb = 0; cb < NCB; ++cb)
+            acc[u][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u][t], b[cb][t], acc[u][cb], 0, 0, 0);
+#pragma unroll
+        for (int dc = 0; dc < 3; ++dc) lut_fma(row, dr, dc, pc, v[dc], t, an);
+#pragma unroll
+        for (int u = 0; u < 9; ++u) asm volatile("" : "+v"(an[u][t]));
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    };
+    LutRowW l0, l1, l2;
+    auto lroute = [&](const RowW& r, int h, LutRowW& m) { lut_route(r, row_ok(h), pok0, pok1, lok, rok2, m); };
+    auto step_lut = [&](int h, LutRowW& ra, LutRowW& rb, LutRowW& rc) {
+      load_row(h + 2, rn);
+      load_x(h, 1, bB);
+      __builtin_amdgcn_sched_barrier(0);
+      if (tail) mask_x(pok0, bA);
+#pragma unroll
+      for (int t = 0; t < 4; ++t) lut_half(aA, bA, t, ra, rb, rc, 1, aB);
+      load_x(h + 1, 0, bA);
+      lroute(rn, h + 2, ra);
+      __builtin_amdgcn_sched_barrier(0);
+      if (tail) mask_x(pok1, bB);
+#pragma unroll
+      for (int t = 0; t < 4; ++t) lut_half(aB, bB, t, rb, rc, ra, 0, aA);
+    };
+    if (LUT) {
+      load_row(h0 - 1, rn);
+      lroute(rn, h0 - 1, l0);
+      load_row(h0, rn);
+      lroute(rn, h0, l1);
+      load_row(h0 + 1, rn);
+      lroute(rn, h0 + 1, l2);
+      load_x(h0, 0, bA);
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int dr = 0; dr < 3; ++dr)
+#pragma unroll
+          for (int dc = 0; dc < 3; ++dc) {
+            const LutRowW& row = dr == 0 ? l0 : dr == 1 ? l1 : l2;
+            lut_fma(row, dr, dc, t + 1, lut_read(row, dr, dc, t + 1), t, aA);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+      for (int h = h0; h < h1; h += 3) {
+        step_lut(h, l0, l1, l2);
+        if (h + 1 >= h1) break;
+        step_lut(h + 1, l1, l2, l0);
+        if (h + 2 >= h1) break;
+        step_lut(h + 2, l2, l0, l1);
+      }
+    } else {
+      load_row(h0 - 1, rn);
+      route(rn, h0 - 1, m0);
+      load_row(h0, rn);
+      route(rn, h0, m1);
+      load_row(h0 + 1, rn);
+      route(rn, h0 + 1, m2);
+      load_x(h0, 0, bA);
+#pragma unroll
+      for (int t = 0; t < 4; ++t) build_pixel(m0, m1, m2, 0, t, aA);
+      for (int h = h0; h < h1; h += 3) {
+        step(h, m0, m1, m2);
+        if (h + 1 >= h1) break;
+        step(h + 1, m1, m2, m0);
+        if (h + 2 >= h1) break;
+        step(h + 2, m2, m0, m1);
+      }
     }
   }
 
@@ -483,7 +595,7 @@ __global__ __launch_bounds__(256) void k_p4_reduce_w(const float* __restrict__ d
                                                      const int32_t* __restrict__ fqt_ptr,
                                                      const int32_t* __restrict__ fqt_col,
                                                      const float* __restrict__ fqt_coef, int B, int Cout, int Cin,
-                                                     int CoutPad, int CinPad) {
+                                                     int CoutPad, int CinPad, int base) {
   // one thread per (bank, filter, channel): its nine taps are nine consecutive floats of dw
   const int total = B * Cout * Cin;
   const int e = blockIdx.x * 256 + threadIdx.x;
@@ -497,7 +609,11 @@ __global__ __launch_bounds__(256) void k_p4_reduce_w(const float* __restrict__ d
 #pragma unroll
   for (int ub = 0; ub < 9; ++ub) {
     float acc = 0.f;
-    for (int z = fqt_ptr[b * 9 + ub]; z < fqt_ptr[b * 9 + ub + 1]; ++z) acc += fqt_coef[z] * src[(size_t)fqt_col[z] * plane];
+    if (base) {       // dF already is the base bank's gradient: only the layout changes
+      acc = src[(size_t)ub * plane];
+    } else {
+      for (int z = fqt_ptr[b * 9 + ub]; z < fqt_ptr[b * 9 + ub + 1]; ++z) acc += fqt_coef[z] * src[(size_t)fqt_col[z] * plane];
+    }
     dst[ub] = acc;
   }
 }
@@ -511,10 +627,11 @@ bool p4_bwd_weight_supported(const rotconv_plan* p) {
   return p4_fwd_pool_mode(p) != kOutUnpooled;
 }
 
-P4BwdWGeom p4_bwd_weight_geom(const rotconv_plan* p) {
+P4BwdWGeom p4_bwd_weight_geom(const rotconv_plan* p, bool lut) {
   const rotconv_desc& d = p->d;
   P4BwdWGeom g{};
-  g.N = d.N; g.Cin = d.Cin; g.H = d.H; g.W = d.W; g.Cout = d.Cout; g.Q = p->host.Q; g.ng = p->ng;
+  g.N = d.N; g.Cin = d.Cin; g.H = d.H; g.W = d.W; g.Cout = d.Cout; g.Q = lut ? 1 : p->host.Q; g.ng = p->ng;
+  g.lut = lut ? 1 : 0; g.R = d.R;
   g.ncb = d.Cin <= 16 ? 1 : 4;
   const int NCB = g.ncb;
   g.CinPad = (d.Cin + 16 * NCB - 1) / (16 * NCB) * (16 * NCB);
@@ -556,15 +673,18 @@ static void finish_dw(const rotconv_plan* p, const P4BwdWGeom& g, float* partial
   }
   const int total = p->B * g.Cout * g.Cin;
   hipLaunchKernelGGL(k_p4_reduce_w, dim3((total + 255) / 256), dim3(256), 0, st, dF, dw, p->dev.fqt_ptr,
-                     p->dev.fqt_col, p->dev.fqt_coef, p->B, g.Cout, g.Cin, g.CoutPad, g.CinPad);
+                     p->dev.fqt_col, p->dev.fqt_coef, p->B, g.Cout, g.Cin, g.CoutPad, g.CinPad, g.lut);
 }
 
 void launch_p4_bwd_weight(const rotconv_plan* p, const float* x, const float* gpool, const uint8_t* idx,
                           float* partial, float* dw, hipStream_t st) {
-  const P4BwdWGeom g = p4_bwd_weight_geom(p);
+  const P4BwdWGeom g = p4_bwd_weight_geom(p, p4_bwd_lut(p));
   const int grid = g.splits * g.ncig * g.ncog;
-  if (g.ncb == 1) hipLaunchKernelGGL(k_p4_bwd_weight<1>, dim3(grid), dim3(NT), 0, st, x, gpool, idx, p->dev.rot_of, partial, g);
-  else hipLaunchKernelGGL(k_p4_bwd_weight<4>, dim3(grid), dim3(NT), 0, st, x, gpool, idx, p->dev.rot_of, partial, g);
+  auto go = [&](auto kern) {
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(NT), 0, st, x, gpool, idx, p->dev.rot_of, p->dev.lut_bwd, partial, g);
+  };
+  if (g.ncb == 1) { if (g.lut) go(k_p4_bwd_weight<1, true>); else go(k_p4_bwd_weight<1, false>); }
+  else { if (g.lut) go(k_p4_bwd_weight<4, true>); else go(k_p4_bwd_weight<4, false>); }
   finish_dw(p, g, partial, dw, st);
 }
 
