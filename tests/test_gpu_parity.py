@@ -196,6 +196,32 @@ def test_gemm_scatter_family_is_the_default_for_larger_layers():
     assert [L.plan.kernel_name(i) for i in range(3)] == ["mfma_gemm_scatter"] * 3
 
 
+LUT_CASES = ["t_r8bil", "t_r16bil", "t_r3irr", "t_cin288_r16", "t_p4m", "t_p4m_c40", "t_ksplit_q2", "t_padw_r16", "t_csplit_r16"]
+
+
+@pytest.mark.parametrize("name", LUT_CASES)
+def test_gradients_per_bank_kernels(name, monkeypatch):
+    """Plans with several banks and one pool group per filter take the routed-gradient table by default (the cases
+    above run it); here the same layers on the per-bank gradient kernels."""
+    monkeypatch.setenv("ROTCONV_BWD_LUT", "0")
+    cfg = next(c for c in TINY if c.name == name)
+    say(f"[case] per-bank gradient kernels {name}")
+    pu.run_fused_parity(cfg)
+
+
+def test_config3_reduced_with_and_without_table(monkeypatch):
+    """Configuration 3's structure (R = 16 bilinear, one pool group) at reduced extent, both gradient variants, and
+    the two must agree with each other far inside the oracle tolerance."""
+    cfg = dataclasses.replace(synth.C3, name="C3r_lut", N=2, Cin=72, Cout=40, H=24, W=40)
+    say(f"[case] {cfg.name}")
+    a = pu.run_fused_parity(cfg)
+    monkeypatch.setenv("ROTCONV_BWD_LUT", "0")
+    b = pu.run_fused_parity(cfg)
+    for k in ("dx", "dw"):
+        scale = float(np.abs(a[k]).max())
+        assert float(np.abs(a[k].astype(np.float64) - b[k]).max()) <= 2e-5 * scale, k
+
+
 def test_config1_fused_and_unfused():
     """Benchmark configuration 1 (N=1, 3->8, 64x64, R=4): both call chains, continuous and dyadic."""
     cfg = synth.C1
