@@ -41,12 +41,14 @@
  *     call on a device uploads its tables (the only allocation and host-to-device
  *     copy the library makes); every later call launches kernels only, so it can
  *     be recorded into a HIP graph and replayed.
- *   - Three environment variables are read when a plan is created and tune its
+ *   - Four environment variables are read when a plan is created and tune its
  *     kernel choice: ROTCONV_FWD_CSPLIT (0 / unset: automatic; 1: never split the
  *     forward's channel contraction; n: n parts) and ROTCONV_GS (0 / 1: never /
  *     always run shapes outside the 3x3 kernels on the GEMM + scatter family;
  *     ROTCONV_GS_CHUNK_MB: MiB of products that family keeps in the workspace at
- *     once, default 512, at least one image's worth is always taken).
+ *     once, default 512, at least one image's worth is always taken;
+ *     ROTCONV_BWD_LUT=0: fp32 gradients of multi-bank layers contract per bank
+ *     instead of folding the routed gradients into the base taps first).
  *   - `ws` is a DEVICE scratch buffer of at least rotconv_workspace_bytes(plan)
  *     bytes, 256-byte aligned; its contents are undefined between calls, and
  *     two calls sharing one ws must not overlap in time.

@@ -149,6 +149,7 @@ int rotconv_plan_create(const rotconv_desc* desc, rotconv_plan** out) {
     p->fwd_csplit[1] = p4_fwd_csplit(p, true);
   }
   if (p->fast[0]) p->ws_bytes = std::max(p->ws_bytes, fwd_fast_ws_bytes(p));
+  p->bwd_lut = p4_bwd_lut_choice(p) ? 1 : 0;
   p->fast[1] = p4_bwd_data_supported(p) ? 1 : 0;
   if (p->fast[1])
     p->ws_bytes = std::max(p->ws_bytes, align256(p4_bwd_data_pack_floats(p) * sizeof(float)) +

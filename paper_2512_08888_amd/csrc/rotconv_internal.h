@@ -78,6 +78,7 @@ struct rotconv_plan {
   int bwdw_splits = 1;          // pixel splits of the generic weight-gradient kernel
   size_t gs_chunk_bytes = (size_t)512 << 20;   // that family holds the products of as many images as fit this
   int gs = 0;                   // passes without a register-resident kernel run the matrix-multiply + scatter family
+  int bwd_lut = 0;              // fast fp32 gradients: routed-gradient table, contraction over the base bank only
   int fwd_csplit[2] = {1, 1};   // fast forward: channel splits for the unpooled / the pooled output (1: none)
   // Average pooling (Eq. 9 / Eq. 11): the fused calls run one ordinary convolution (this R = 1 plan with
   // Cout * R/G filters) on the group-averaged bank.  Owned by the parent.

@@ -69,7 +69,8 @@ struct P4BwdGeom {
   int units;   // workgroups with work (includes the split)
   int lut;     // routed-gradient table: the contraction runs over the base bank only (Q is 1 then)
 };
-bool p4_bwd_lut(const rotconv_plan* p);   // the fp32 gradients use the routed-gradient table (contraction over the base bank)
+bool p4_bwd_lut_choice(const rotconv_plan* p);   // whether the fp32 gradients should use the routed-gradient table
+bool p4_bwd_lut(const rotconv_plan* p);          // the plan's setting (contraction over the base bank)
 bool p4_bwd_data_supported(const rotconv_plan* p);
 P4BwdGeom p4_bwd_data_geom(const rotconv_plan* p);
 size_t p4_bwd_data_pack_floats(const rotconv_plan* p);

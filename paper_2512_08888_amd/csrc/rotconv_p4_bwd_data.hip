@@ -441,12 +441,14 @@ __global__ __launch_bounds__(256) void k_p4_pack_bwd(const float* __restrict__ w
 }  // namespace
 
 // The fp32 gradients run over the base bank through the routed-gradient table: one pool group per filter, one base
-// bank, several banks to save (ROTCONV_BWD_LUT=0, read at every call, keeps the per-bank kernels).
-bool p4_bwd_lut(const rotconv_plan* p) {
+// bank, several banks to save (ROTCONV_BWD_LUT=0 keeps the per-bank kernels).  Decided once, when the plan is created
+// (the two variants need different amounts of scratch).
+bool p4_bwd_lut_choice(const rotconv_plan* p) {
   if (p->host.lut_bwd.empty() || p->host.Q < 2 || p->ng != 1 || p->d.R > 32 || p->d.dtype == ROTCONV_BF16) return false;
   if (const char* e = std::getenv("ROTCONV_BWD_LUT")) return std::atoi(e) != 0;
   return true;
 }
+bool p4_bwd_lut(const rotconv_plan* p) { return p->bwd_lut != 0; }
 
 bool p4_bwd_data_supported(const rotconv_plan* p) {
   const rotconv_desc& d = p->d;

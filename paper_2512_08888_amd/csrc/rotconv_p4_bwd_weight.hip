@@ -19,6 +19,8 @@
 // transposed first-quadrant expansion, so the result is deterministic.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+
 #include "rotconv_bf16.h"
 #include "rotconv_kernels.h"
 #include "rotconv_p4.h"
@@ -656,8 +658,13 @@ P4BwdWGeom p4_bwd_weight_geom(const rotconv_plan* p, bool lut) {
 bool p4_bwd_weight_bf16_supported(const rotconv_plan* p) { return p4_bwd_weight_supported(p) && (p->d.W & 7) == 0; }
 
 size_t p4_bwd_weight_ws_floats(const rotconv_plan* p) {
-  const P4BwdWGeom g = p4_bwd_weight_geom(p);
-  return (size_t)(g.splits + 1) * g.Q * 9 * g.CoutPad * g.CinPad;  // partial sums + their total
+  size_t need = 0;
+  for (int lut = 0; lut < 2; ++lut) {     // the per-bank kernels (also the bf16 one) and the table variant
+    if (lut && !p4_bwd_lut(p)) break;
+    const P4BwdWGeom g = p4_bwd_weight_geom(p, lut != 0);
+    need = std::max(need, (size_t)(g.splits + 1) * g.Q * 9 * g.CoutPad * g.CinPad);  // partial sums + their total
+  }
+  return need;
 }
 
 // partial sums of the splits -> dF (fixed order) -> dw through the transposed expansion
