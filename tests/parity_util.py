@@ -51,12 +51,15 @@ def assert_close(got, ref, what, rtol=RTOL):
         assert float(np.linalg.norm(got - ref)) <= rtol * nref, f"{what}: relative L2 error too large"
 
 
-def check_idx(idx_gpu, y_ref, abs_terms, G, what):
-    """Arg-max protocol on continuous inputs.  y_ref, abs_terms: [N,Cout,R,Ho,Wo] (fp64)."""
+def check_idx(idx_gpu, y_ref, abs_terms, G, what, extra_band=None):
+    """Arg-max protocol on continuous inputs.  y_ref, abs_terms: [N,Cout,R,Ho,Wo] (fp64).  extra_band (same shape or
+    broadcastable): an additional absolute uncertainty of the candidates, added to the near-tie band."""
     N, Cout, R, Ho, Wo = y_ref.shape
     ng = R // G
     yg = y_ref.reshape(N, Cout, G, ng, Ho, Wo)
     tau = 64.0 * EPS32 * abs_terms.reshape(N, Cout, G, ng, Ho, Wo).max(axis=2)  # per pooled element
+    if extra_band is not None:
+        tau = tau + np.broadcast_to(extra_band, y_ref.shape).reshape(N, Cout, G, ng, Ho, Wo).max(axis=2)
     best = yg.max(axis=2)
     ig = idx_gpu.reshape(N, Cout, ng, Ho, Wo).astype(np.int64)
     grp = np.arange(ng).reshape(1, 1, ng, 1, 1)

@@ -43,6 +43,9 @@ CASES = [
     # orientation sets without all four quarter turns per bank: the dense input-gradient instances
     LC("b_p4m", N=1, Cin=24, H=9, W=32, Cout=40, R=8, mode="p4m", seed=73),
     LC("b_r2", N=1, Cin=16, H=8, W=32, Cout=80, R=2, seed=74),
+    # a layer on which one arg-max sits just outside the fp32 near-tie band because a rotated weight rounds to the
+    # neighbouring bf16 value (fp32 against fp64 combination): covered by the bank-rounding band
+    LC("b_r16_bank_rounding", N=2, Cin=32, H=19, W=160, Cout=136, R=16, mode="bilinear", x_dist="absnormal", seed=9148),
 ]
 
 
@@ -69,6 +72,18 @@ def reference(cfg, x, w, ang):
     return w_rot, y, yp, idx
 
 
+def bank_rounding_band(cfg, x, w_rot):
+    """Interpolated banks (bilinear, steerable): the library forms a rotated weight in fp32 and rounds it to bf16 once,
+    the reference forms it in fp64; where the two land on different sides of a rounding boundary the weight differs by
+    one bf16 step (2^-8 relative), which moves a response by at most 2^-8 |w| |x| of the one term it multiplies (two
+    such weights in one response are allowed for).  Exact quarter turns and mirror images copy weights: no band."""
+    if cfg.mode in ("exact90", "p4m"):
+        return None
+    wmax = np.abs(w_rot).max(axis=(2, 3, 4))                        # [R, Cout]
+    xmax = np.abs(x).reshape(cfg.N, -1).max(axis=1)                   # per image
+    return 2.0 * 2.0 ** -8 * wmax.T[None, :, :, None, None] * xmax[:, None, None, None, None]
+
+
 def reference_bwd(cfg, x, w_rot, g, idx, ang):
     dy = orc.orient_maxpool_bwd(g, idx, cfg.R, cfg.G)
     dx = orc.rotconv_bwd_data(dy, w_rot, cfg.H, cfg.W, cfg.stride, cfg.pad)
@@ -91,7 +106,7 @@ def test_bf16_fused_calls(cfg):
     assert_close(f64(yp), yp_ref, f"{cfg.name} ypool", rtol=BF_RTOL)
     abs_terms = orc.rotconv_fwd(np.abs(x), np.abs(w_rot), cfg.stride, cfg.pad)
     idx_h = idx.cpu().numpy()
-    check_idx(idx_h, y_ref, abs_terms, cfg.G, f"{cfg.name} idx")
+    check_idx(idx_h, y_ref, abs_terms, cfg.G, f"{cfg.name} idx", bank_rounding_band(cfg, x, w_rot))
     # backward on the GPU's own idx, both sides
     dx_ref, dw_ref = reference_bwd(cfg, x, w_rot, g, idx_h, ang)
     dx = nan16(*xd.shape)
