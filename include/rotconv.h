@@ -149,6 +149,12 @@ int rotconv_out_shape(const rotconv_plan* plan, int32_t* Ho, int32_t* Wo, int32_
  *   W^(r)[t] = sum_{b,u} E[r][t][b][u] * w[b][u]   (Eq. 5 / Sec. III-D / Eq. 17). */
 int rotconv_plan_orientations(const rotconv_plan* plan, int32_t* Q, int32_t* bank_of_r, int32_t* quarter_of_r);
 int rotconv_plan_expansion(const rotconv_plan* plan, float* E);
+/* The routed-gradient table of 3x3 plans with one base bank (B = 1), HOST array T[9][R + 1][9] of floats: with
+ * Delta_r = G [idx == r] (Eq. 12), the gradient that reaches base tap u of a filter at pixel p (the D of
+ * dX = sum_co,u w[co,ci,u] D[u], dw[co,ci,u] = sum_p D[u][p] x[ci,p]; Eq. 13-16 with the expansion folded in) is
+ * D[u][p] = sum over dy, dx in {-1,0,1} of G[p + (dy,dx)] * T[(dy+1)*3 + (dx+1)][idx[p + (dy,dx)]][u]; row R (no
+ * orientation) is zero.  ROTCONV_ERR_UNSUPPORTED for other plans. */
+int rotconv_plan_routed_table(const rotconv_plan* plan, float* T);
 
 /* ---- the five calls of the unfused chain ------------------------------------- */
 

@@ -21,7 +21,7 @@ POOL_OPS = {"max": 0, "avg": 1}
 
 EXPORTS = [
     "rotconv_plan_create", "rotconv_plan_destroy", "rotconv_workspace_bytes", "rotconv_out_shape",
-    "rotconv_plan_orientations", "rotconv_plan_expansion",
+    "rotconv_plan_orientations", "rotconv_plan_expansion", "rotconv_plan_routed_table",
     "rotconv_fwd", "rotconv_bwd_data", "rotconv_bwd_weight", "orient_maxpool_fwd", "orient_maxpool_bwd",
     "rotconv_pool_fwd", "rotconv_pool_bwd_data", "rotconv_pool_bwd_weight",
     "rotconv_status_string", "rotconv_plan_kernel_name", "rotconv_steerable_reg",
@@ -76,6 +76,7 @@ def lib():
         L.rotconv_out_shape.argtypes = [vp, i32p, i32p, i32p, i32p]
         L.rotconv_plan_orientations.argtypes = [vp, i32p, i32p, i32p]
         L.rotconv_plan_expansion.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
+        L.rotconv_plan_routed_table.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
         L.rotconv_fwd.argtypes = [vp, vp, vp, vp, vp, sz, vp]
         L.rotconv_bwd_data.argtypes = [vp, vp, vp, vp, vp, sz, vp]
         L.rotconv_bwd_weight.argtypes = [vp, vp, vp, vp, vp, sz, vp]
@@ -199,6 +200,14 @@ class Plan:
         _check(lib().rotconv_plan_expansion(self._h, E.ctypes.data_as(ctypes.POINTER(ctypes.c_float))),
                "rotconv_plan_expansion")
         return E
+
+    def routed_table(self):
+        import numpy as np
+
+        T = np.zeros((9, self.R + 1, 9), dtype=np.float32)
+        _check(lib().rotconv_plan_routed_table(self._h, T.ctypes.data_as(ctypes.POINTER(ctypes.c_float))),
+               "rotconv_plan_routed_table")
+        return T
 
     def kernel_name(self, which: int) -> str:
         return lib().rotconv_plan_kernel_name(self._h, which).decode()

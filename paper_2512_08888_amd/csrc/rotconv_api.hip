@@ -265,6 +265,16 @@ int rotconv_plan_expansion(const rotconv_plan* plan, float* E) {
   return ROTCONV_OK;
 }
 
+int rotconv_plan_routed_table(const rotconv_plan* plan, float* T) {
+  if (!plan || !T) return ROTCONV_ERR_NULL;
+  if (plan->host.lut_bwd.empty()) return ROTCONV_ERR_UNSUPPORTED;
+  const int R1 = plan->d.R + 1;
+  for (int rel = 0; rel < 9; ++rel)
+    for (int r = 0; r < R1; ++r)
+      for (int u = 0; u < 9; ++u) T[((size_t)rel * R1 + r) * 9 + u] = plan->host.lut_bwd[((size_t)rel * R1 + r) * 12 + u];
+  return ROTCONV_OK;
+}
+
 }  // extern "C" (the fp32 implementations below have internal linkage)
 
 static int f32_rotconv_fwd(const rotconv_plan* plan, const void* x, const void* w, void* y, void* ws, size_t ws_bytes,

@@ -142,6 +142,41 @@ def test_expansion_table_reproduces_oracle_banks(R, mode, k, angles):
         assert np.count_nonzero(E) == R * k * k
 
 
+@pytest.mark.parametrize("R,mode,angles", [
+    (4, "exact90", None), (16, "bilinear", None), (8, "bilinear", None), (8, "p4m", None),
+    (5, "bilinear", [0.0, 30.0, 120.0, 200.0, 359.0]), (2, "exact90", [90.0, 270.0]),
+])
+def test_routed_gradient_table_against_the_oracle_gradients(R, mode, angles):
+    """The table of the fast fp32 gradients: a single routed gradient value (one pixel, every orientation in turn)
+    pushed through the table and the BASE bank must give the oracle's input gradient and weight gradient
+    (Eq. 12-16 with the expansion folded in)."""
+    p = rc.Plan(1, 1, 5, 5, 1, k=3, R=R, mode=mode, angles_deg=angles)
+    T = p.routed_table().astype(np.float64)            # [9][R + 1][9]
+    assert np.all(T[:, R] == 0)
+    w = RNG.standard_normal((1, 1, 1, 3, 3))
+    x = RNG.standard_normal((1, 1, 5, 5))
+    w_rot = orc.expand_bank(w, R, angles, mode)
+    for r in range(R):
+        g = np.zeros((1, 1, 5, 5))
+        g[0, 0, 2, 3] = 1.7
+        idx = np.full((1, 1, 5, 5), r, dtype=np.uint8)
+        dy = orc.orient_maxpool_bwd(g, idx, R, R)
+        dx_ref = orc.rotconv_bwd_data(dy, w_rot, 5, 5, 1, 1)[0, 0]
+        dw_ref = orc.reduce_bank_grad(orc.rotconv_bwd_weight(x, dy, 3, 1, 1), angles, mode)[0, 0, 0].reshape(9)
+        # D[u][p] = G[p + delta] T[delta][r][u]: the value at (2, 3) reaches pixel (2, 3) - delta
+        D = np.zeros((9, 5, 5))
+        for dyy in (-1, 0, 1):
+            for dxx in (-1, 0, 1):
+                D[:, 2 - dyy, 3 - dxx] = 1.7 * T[(dyy + 1) * 3 + (dxx + 1), r]
+        dx = np.einsum("u,uhw->hw", w.reshape(9), D)
+        dw = np.einsum("uhw,hw->u", D, x[0, 0])
+        np.testing.assert_allclose(dx, dx_ref, rtol=0, atol=1e-6)
+        np.testing.assert_allclose(dw, dw_ref, rtol=0, atol=1e-6)
+    with pytest.raises(rc.RotconvError) as e:
+        rc.Plan(1, 1, 5, 5, 1, k=3, R=8, mode="steerable").routed_table()      # two base banks: no table
+    assert e.value.status == rc.ERR_UNSUPPORTED
+
+
 def test_p4m_tables_reproduce_the_oracle_banks():
     """Host-built expansion of the p4m mode (two banks: the filter and its mirror image, four quarter turns each)
     against the oracle's materialised filters; and the descriptor checks of that mode."""
