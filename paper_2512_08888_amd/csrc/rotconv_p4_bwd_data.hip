@@ -38,6 +38,7 @@ constexpr int WROW = 9 * CIG + 16;     // LDS floats per filter row (padded: con
 constexpr int CHUNK = 16;              // filters per LDS chunk
 constexpr int NWAVE = 8;
 constexpr int NT = 64 * NWAVE;
+constexpr int kLutRows = 33;           // table rows per neighbour offset in LDS: R + 1 <= 33
 
 __device__ __host__ constexpr int tap_i(int s, int u) {
   return s == 0 ? u / 3 : s == 1 ? 2 - u % 3 : s == 2 ? 2 - u / 3 : u % 3;
@@ -66,11 +67,12 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gp
                                                     const float* __restrict__ wd,
                                                     const int32_t* __restrict__ rot_of, const float* __restrict__ lut,
                                                     float* __restrict__ dx, P4BwdGeom g) {
-  extern __shared__ float smem[];      // [2][CHUNK][WROW], then the table [9][R + 1][12] (LUT)
+  extern __shared__ float smem[];      // [2][CHUNK][WROW], then the table [9][kLutRows][12] (LUT)
   float* Tl = smem + 2 * CHUNK * WROW;
-  const int R1 = g.R + 1;
-  if (LUT)
-    for (int i = threadIdx.x; i < 9 * R1 * 12; i += NT) Tl[i] = lut[i];
+  if (LUT) {     // a fixed row count per offset: the offset part of a row address is an instruction immediate
+    const int R1 = g.R + 1;
+    for (int i = threadIdx.x; i < 9 * R1 * 12; i += NT) Tl[(i / (R1 * 12)) * (kLutRows * 12) + i % (R1 * 12)] = lut[i];
+  }
 
   const int per_xcd = (g.units + 7) / 8;
   int v = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
@@ -247,7 +249,7 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gp
   };
   auto lut_read = [&](const LutVals& v, int blk) -> LutRow {
     const int dr = blk / (3 * PX), bb = (blk % (3 * PX)) / 3, dc = blk % 3;
-    const float* t = Tl + (dr * 3 + dc) * R1 * 12 + v.off[dr][bb + dc];   // neighbour at column offset dc - 1 of pixel bb
+    const float* t = Tl + (dr * 3 + dc) * (kLutRows * 12) + v.off[dr][bb + dc];   // neighbour at column offset dc - 1 of pixel bb
     LutRow row;
     row.t0 = *reinterpret_cast<const f4*>(t);
     row.t1 = *reinterpret_cast<const f4*>(t + 4);
@@ -518,7 +520,7 @@ void launch_p4_bwd_data(const rotconv_plan* p, const float* gpool, const uint8_t
                         float* part, hipStream_t st) {
   const P4BwdGeom g = p4_bwd_data_geom(p);
   float* dx = g.ksplit > 1 ? part : dx_out;
-  const size_t lds = ((size_t)2 * CHUNK * WROW + (g.lut ? 9 * (g.R + 1) * 12 : 0)) * sizeof(float);
+  const size_t lds = ((size_t)2 * CHUNK * WROW + (g.lut ? 9 * kLutRows * 12 : 0)) * sizeof(float);
   const int grid = (g.units + 7) / 8 * 8;
   auto go = [&](auto kern) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);

@@ -58,10 +58,11 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_weight(const float* __restrict__ 
                                                       const uint8_t* __restrict__ idx,
                                                       const int32_t* __restrict__ rot_of, const float* __restrict__ lut,
                                                       float* __restrict__ partial, P4BwdWGeom g) {
-  __shared__ float Tl[LUT ? 9 * 33 * 12 : 4];
-  const int R1 = g.R + 1;
+  constexpr int kLutRows = 33;     // table rows per neighbour offset in LDS (R + 1 <= 33): row addresses = immediate + lane offset
+  __shared__ float Tl[LUT ? 9 * kLutRows * 12 : 4];
   if (LUT) {
-    for (int i = threadIdx.x; i < 9 * R1 * 12; i += NT) Tl[i] = lut[i];
+    const int R1 = g.R + 1;
+    for (int i = threadIdx.x; i < 9 * R1 * 12; i += NT) Tl[(i / (R1 * 12)) * (kLutRows * 12) + i % (R1 * 12)] = lut[i];
     __syncthreads();
   }
   // Consecutive indices go to one XCD: the (bank, filter group, channel group) combinations of one work
@@ -166,7 +167,7 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_weight(const float* __restrict__ 
   struct LutT { f4 t0, t1; float t8; };
   // block (dr, dc) of pixel column pc (1..8): the neighbour in row dr at column pc + dc - 1
   auto lut_read = [&](const LutRowW& row, int dr, int dc, int pc) -> LutT {
-    const float* t = Tl + (dr * 3 + dc) * R1 * 12 + row.off[pc + dc - 1];
+    const float* t = Tl + (dr * 3 + dc) * (kLutRows * 12) + row.off[pc + dc - 1];
     LutT v;
     v.t0 = *reinterpret_cast<const f4*>(t);
     v.t1 = *reinterpret_cast<const f4*>(t + 4);
