@@ -65,7 +65,7 @@ def cpu_baseline(cfg, Q):
     }
 
 
-def bench_unet(name, steps, warmup, dtype="f32"):
+def bench_unet(name, steps, warmup, dtype="f32", graph=False):
     """ms per training step of the UNet-shaped stack (benchmark configurations 4 and 5; P4 / P8 / P16: the
     paper's own block, rotation convolution then standard convolution, at 4 / 8 / 16 orientations; fp32), whole
     step timed between synchronisations; then one more step with an event pair around every library
@@ -84,6 +84,16 @@ def bench_unet(name, steps, warmup, dtype="f32"):
         net.step()
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) * 1e3 / steps
+    ms_graph = None
+    if graph:       # the same step recorded once into a HIP graph and replayed
+        net.capture()
+        net.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            net.replay()
+        torch.cuda.synchronize()
+        ms_graph = (time.perf_counter() - t0) * 1e3 / steps
     net.trace = []
     net.step()
     torch.cuda.synchronize()
@@ -102,7 +112,7 @@ def bench_unet(name, steps, warmup, dtype="f32"):
                     f"classes={cfg.classes} R={cfg.R} {cfg.mode} block={cfg.block}, one training step (fwd+bwd), "
                     + ("fp32" if dtype == "f32" else "bf16 parameters / activations, fp32 accumulation, fp32 dW and loss"),
         "dtype": dtype,
-        "ms_per_step": ms, "steps": steps, "warmup": warmup, "loss": loss,
+        "ms_per_step": ms, "ms_per_step_graph_replay": ms_graph, "steps": steps, "warmup": warmup, "loss": loss,
         "rotconv_flops_algorithmic": alg, "rotconv_flops_dense_equivalent": dense,
         "rotconv_ms": rot_ms, "glue_ms": sum(by_call.values()) - rot_ms,
         "rotconv_tflops_algorithmic": alg / (rot_ms * 1e-3) / 1e12,
@@ -188,7 +198,7 @@ def main_unet(args):
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    r = bench_unet(args.workload, args.steps, args.warmup, args.dtype)
+    r = bench_unet(args.workload, args.steps, args.warmup, args.dtype, args.graph)
     out = {
         "metric": "unet_train_step_ms", "value": r["ms_per_step"], "unit": "ms", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": r["ms_per_step"], "higher_is_better": False, "scaling": "weak",
@@ -222,6 +232,8 @@ def main():
     ap.add_argument("--ksize", type=int, default=None,
                     help="single-layer workloads: run the layer's shape with k x k filters (pad k // 2) instead of 3 x 3")
     ap.add_argument("--stride", type=int, default=None, help="single-layer workloads: convolution stride")
+    ap.add_argument("--graph", action="store_true",
+                    help="UNet workloads: also time the step replayed from a HIP graph (ms_per_step_graph_replay)")
     ap.add_argument("--no-unet", action="store_true", help="skip the UNet-shaped steps appended to the default line")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",

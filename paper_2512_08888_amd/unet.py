@@ -322,3 +322,20 @@ class UNet:
         self.forward()
         self.backward()
         return self.loss
+
+    def capture(self):
+        """Records one step (after at least one eager step: the plans upload their tables on first use) into a HIP
+        graph on the current device; `replay()` then runs the whole step with one launch from the host.  Every
+        library call enqueues kernels only and every buffer of the step is preallocated, so the recorded step is
+        the eager step."""
+        assert self.trace is None
+        self.step()
+        self.torch.cuda.synchronize()
+        self._graph = self.torch.cuda.CUDAGraph()
+        with self.torch.cuda.graph(self._graph):
+            self.step()
+        return self._graph
+
+    def replay(self):
+        self._graph.replay()
+        return self.loss

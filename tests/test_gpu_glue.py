@@ -1,5 +1,7 @@
 """GPU parity of the network glue (include/unetglue.h) and of the UNet-shaped training step
 against the CPU oracle (oracle/unet_oracle.py), called through the C-ABI binding."""
+import dataclasses
+
 import numpy as np
 import pytest
 import torch
@@ -423,6 +425,31 @@ def test_unet_step_is_deterministic():
     assert float(net.loss.cpu()[0]) == l0
     for k, v in net.grads.items():
         assert np.array_equal(first[k], v.cpu().numpy()), k
+
+
+@pytest.mark.parametrize("cfg,dtype", [(SMALL[1], "f32"), (SMALL[2], "f32"), (SMALL[2], "bf16")],
+                         ids=lambda v: v if isinstance(v, str) else v.name)
+def test_unet_step_replays_from_a_graph(cfg, dtype):
+    """The whole training step recorded into a HIP graph: replays (with the program's own eager work and
+    synchronisations between them, and a new batch in the captured buffers) give bit for bit the eager step."""
+    net, *_ = _run_stack(cfg, dtype)
+    net.capture()
+    for rep in range(3):
+        cfg2 = dataclasses.replace(cfg, seed=cfg.seed + 10 * rep) if hasattr(cfg, "seed") else cfg
+        net.load_batch(*un.make_batch(cfg2))
+        net.step()
+        torch.cuda.synchronize()
+        loss = float(net.loss.cpu()[0])
+        grads = {k: v.cpu().numpy().copy() for k, v in net.grads.items()}
+        for v in net.grads.values():
+            v.zero_()
+        net.loss.zero_()
+        torch.cuda.synchronize()
+        net.replay()
+        torch.cuda.synchronize()
+        assert float(net.loss.cpu()[0]) == loss, rep
+        for k, v in net.grads.items():
+            assert np.array_equal(grads[k], v.cpu().numpy()), (rep, k)
 
 
 # ---- the benchmark's stacks at full size ------------------------------------------------------------
