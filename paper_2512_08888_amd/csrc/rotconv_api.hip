@@ -267,7 +267,7 @@ int rotconv_plan_expansion(const rotconv_plan* plan, float* E) {
 
 int rotconv_plan_routed_table(const rotconv_plan* plan, float* T) {
   if (!plan || !T) return ROTCONV_ERR_NULL;
-  if (plan->host.lut_bwd.empty()) return ROTCONV_ERR_UNSUPPORTED;
+  if (plan->host.lut_bwd.empty() || plan->B != 1) return ROTCONV_ERR_UNSUPPORTED;
   const int R1 = plan->d.R + 1;
   for (int rel = 0; rel < 9; ++rel)
     for (int r = 0; r < R1; ++r)

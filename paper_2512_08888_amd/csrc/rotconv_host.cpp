@@ -192,18 +192,20 @@ int validate_and_build(const rotconv_desc* desc, rotconv_plan** out) {
         t.exp_coef[(r * kk + dst) * kMaxNnz + e] = t.fq_coef[(t.bank_of_r[r] * kk + u) * kMaxNnz + e];
       }
     }
-  // 3x3, one base bank: the routed-gradient table of the input / weight gradients.  With Delta_r = G [idx == r]
+  // 3x3: the routed-gradient table of the input / weight gradients.  With Delta_r = G [idx == r]
   // (Eq. 12) the gradient that reaches base tap u' from the neighbour at offset (dy, dx) of a pixel is
   // G * lut[(dy+1)*3 + (dx+1)][idx][u'], lut[.][r][u'] = coefficient of base tap u' in tap (1-dy, 1-dx) of the
   // rotated bank r (Eq. 13-16 with the expansion of Eq. 5 / Sec. III-D folded in); row R (no orientation) is zero.
-  if (kk == 9 && B == 1) {
-    t.lut_bwd.assign((size_t)9 * (d.R + 1) * 12, 0.f);
+  // One such table per base bank (the steerable pair has two: [B][9][R + 1][12]).
+  if (kk == 9) {
+    t.lut_bwd.assign((size_t)B * 9 * (d.R + 1) * 12, 0.f);
     for (int r = 0; r < d.R; ++r)
       for (int tp = 0; tp < 9; ++tp) {
         const int rel = (2 - tp / 3) * 3 + (2 - tp % 3);
         for (int e = 0; e < kMaxNnz; ++e) {
-          const int src = t.exp_src[(r * kk + tp) * kMaxNnz + e];
-          if (src >= 0) t.lut_bwd[((size_t)rel * (d.R + 1) + r) * 12 + src] += t.exp_coef[(r * kk + tp) * kMaxNnz + e];
+          const int src = t.exp_src[(r * kk + tp) * kMaxNnz + e];      // base bank * 9 + base tap
+          if (src >= 0)
+            t.lut_bwd[(((size_t)(src / 9) * 9 + rel) * (d.R + 1) + r) * 12 + src % 9] += t.exp_coef[(r * kk + tp) * kMaxNnz + e];
         }
       }
   }

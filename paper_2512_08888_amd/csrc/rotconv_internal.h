@@ -36,7 +36,7 @@ struct HostTables {
   // Quarter-turn tap permutation: turn_tap[s*kk + u] = index of the tap where base tap u
   // sits after s quarter turns (Eq. 8: (m',n') = R_s(m,n)).
   std::vector<int32_t> turn_tap;  // [4*kk]
-  // 3x3 plans with one base bank: [9 neighbour offsets][R + 1][12] routed-gradient coefficients (see rotconv_host.cpp)
+  // 3x3 plans: [B base banks][9 neighbour offsets][R + 1][12] routed-gradient coefficients (see rotconv_host.cpp)
   std::vector<float> lut_bwd;
 };
 

@@ -67,11 +67,11 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gp
                                                     const float* __restrict__ wd,
                                                     const int32_t* __restrict__ rot_of, const float* __restrict__ lut,
                                                     float* __restrict__ dx, P4BwdGeom g) {
-  extern __shared__ float smem[];      // [2][CHUNK][WROW], then the table [9][kLutRows][12] (LUT)
+  extern __shared__ float smem[];      // [2][CHUNK][WROW], then the tables [base bank][9][kLutRows][12] (LUT)
   float* Tl = smem + 2 * CHUNK * WROW;
   if (LUT) {     // a fixed row count per offset: the offset part of a row address is an instruction immediate
     const int R1 = g.R + 1;
-    for (int i = threadIdx.x; i < 9 * R1 * 12; i += NT) Tl[(i / (R1 * 12)) * (kLutRows * 12) + i % (R1 * 12)] = lut[i];
+    for (int i = threadIdx.x; i < g.Q * 9 * R1 * 12; i += NT) Tl[(i / (R1 * 12)) * (kLutRows * 12) + i % (R1 * 12)] = lut[i];
   }
 
   const int per_xcd = (g.units + 7) / 8;
@@ -233,7 +233,8 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gp
   // lut_fma consumes them behind those.
   struct LutVals { float gv[3][PX + 2]; uint32_t off[3][PX + 2]; };
   struct LutRow { f4 t0, t1; float t8; };
-  auto lut_prepare = [&](const Raw<PX>& r, LutVals& v) {
+  auto lut_prepare = [&](const Raw<PX>& r, int bank, LutVals& v) {      // bank: the K-step's base bank (its table)
+    const uint32_t tbase = (uint32_t)bank * (9 * kLutRows * 12);
 #pragma unroll
     for (int dr = 0; dr < 3; ++dr) {
       const uint32_t iwc = r.ic[dr] | invc[dr] | r.finv | (PX == 2 ? 0xffff0000u : 0u);
@@ -243,7 +244,7 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gp
         const uint32_t byte = c == 0 ? (iwe & 0xffu) : c == PX + 1 ? ((iwe >> 8) & 0xffu) : ((iwc >> (8 * (c - 1))) & 0xffu);
         const float gval = c == 0 ? r.gl[dr] : c == PX + 1 ? r.gr[dr] : r.gc[dr][c - 1];
         v.gv[dr][c] = byte < (uint32_t)g.R ? gval : 0.f;
-        v.off[dr][c] = min(byte, (uint32_t)g.R) * 12u;
+        v.off[dr][c] = min(byte, (uint32_t)g.R) * 12u + tbase;
       }
     }
   };
@@ -297,7 +298,7 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gp
     // LUT: PX blocks of the next K-step's sums per tap, their table rows read one tap ahead
     LutVals lv;
     LutRow lrow[PX];
-    if (LUT) lut_prepare(raw_use, lv);
+    if (LUT) lut_prepare(raw_use, bd_q, lv);
 #pragma unroll
     for (int u = 0; u < 9; ++u) {
       if (u < 8) bw[(u + 1) & 1] = *reinterpret_cast<const f4*>(wl + (ks * 4) * WROW + (u + 1) * CIG);
@@ -331,7 +332,7 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gp
   if (LUT) __syncthreads();            // the table is in LDS
   if (LUT) {
     LutVals lv;
-    lut_prepare(rawB, lv);
+    lut_prepare(rawB, q0, lv);
 #pragma unroll
     for (int blk = 0; blk < 9 * PX; ++blk) {
       lut_fma(lv, blk, lut_read(lv, blk), aA);
@@ -427,8 +428,8 @@ __global__ __launch_bounds__(256) void k_p4_pack_bwd(const float* __restrict__ w
 #pragma unroll
   for (int u = 0; u < 9; ++u) {
     float acc = 0.f;
-    if (base) {
-      acc = in ? src[u] : 0.f;
+    if (base) {       // q counts the base banks
+      acc = in ? src[(size_t)q * slices * 9 + u] : 0.f;
     } else {
 #pragma unroll
       for (int z = 0; z < kMaxNnz; ++z) {
@@ -442,11 +443,11 @@ __global__ __launch_bounds__(256) void k_p4_pack_bwd(const float* __restrict__ w
 
 }  // namespace
 
-// The fp32 gradients run over the base bank through the routed-gradient table: one pool group per filter, one base
-// bank, several banks to save (ROTCONV_BWD_LUT=0 keeps the per-bank kernels).  Decided once, when the plan is created
+// The fp32 gradients run over the base bank(s) through the routed-gradient table: one pool group per filter, more
+// banks than base banks (ROTCONV_BWD_LUT=0 keeps the per-bank kernels).  Decided once, when the plan is created
 // (the two variants need different amounts of scratch).
 bool p4_bwd_lut_choice(const rotconv_plan* p) {
-  if (p->host.lut_bwd.empty() || p->host.Q < 2 || p->ng != 1 || p->d.R > 32 || p->d.dtype == ROTCONV_BF16) return false;
+  if (p->host.lut_bwd.empty() || p->host.Q <= p->B || p->ng != 1 || p->d.R > 32 || p->d.dtype == ROTCONV_BF16) return false;
   if (const char* e = std::getenv("ROTCONV_BWD_LUT")) return std::atoi(e) != 0;
   return true;
 }
@@ -466,7 +467,7 @@ P4BwdGeom p4_bwd_data_geom(const rotconv_plan* p) {
   g.CoutPad = (d.Cout + 15) / 16 * 16; g.R = d.R; g.Q = p->host.Q; g.ng = p->ng;
   // routed-gradient table instead of per-bank sums
   g.lut = p4_bwd_lut(p) ? 1 : 0;
-  if (g.lut) g.Q = 1;
+  if (g.lut) g.Q = p->B;        // the "banks" of the contraction are the base banks
   g.ncig = g.CinPad / CIG; g.nrb = (d.H + NWAVE - 1) / NWAVE;
   // pixels per lane: four when the rows are long enough and that still leaves a workgroup per CU
   g.px = ((d.W & 3) == 0 && d.W > 32 && d.N * g.ncig * g.nrb * ((d.W + 63) / 64) >= 256) ? 4 : 2;
@@ -520,7 +521,7 @@ void launch_p4_bwd_data(const rotconv_plan* p, const float* gpool, const uint8_t
                         float* part, hipStream_t st) {
   const P4BwdGeom g = p4_bwd_data_geom(p);
   float* dx = g.ksplit > 1 ? part : dx_out;
-  const size_t lds = ((size_t)2 * CHUNK * WROW + (g.lut ? 9 * kLutRows * 12 : 0)) * sizeof(float);
+  const size_t lds = ((size_t)2 * CHUNK * WROW + (g.lut ? g.Q * 9 * kLutRows * 12 : 0)) * sizeof(float);
   const int grid = (g.units + 7) / 8 * 8;
   auto go = [&](auto kern) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);

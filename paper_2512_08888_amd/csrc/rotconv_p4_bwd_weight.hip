@@ -59,10 +59,10 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_weight(const float* __restrict__ 
                                                       const int32_t* __restrict__ rot_of, const float* __restrict__ lut,
                                                       float* __restrict__ partial, P4BwdWGeom g) {
   constexpr int kLutRows = 33;     // table rows per neighbour offset in LDS (R + 1 <= 33): row addresses = immediate + lane offset
-  __shared__ float Tl[LUT ? 9 * kLutRows * 12 : 4];
+  __shared__ float Tl[LUT ? 2 * 9 * kLutRows * 12 : 4];      // one table per base bank (at most two)
   if (LUT) {
     const int R1 = g.R + 1;
-    for (int i = threadIdx.x; i < 9 * R1 * 12; i += NT) Tl[(i / (R1 * 12)) * (kLutRows * 12) + i % (R1 * 12)] = lut[i];
+    for (int i = threadIdx.x; i < g.Q * 9 * R1 * 12; i += NT) Tl[(i / (R1 * 12)) * (kLutRows * 12) + i % (R1 * 12)] = lut[i];
     __syncthreads();
   }
   // Consecutive indices go to one XCD: the (bank, filter group, channel group) combinations of one work
@@ -161,7 +161,7 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_weight(const float* __restrict__ 
       const uint32_t byte = c == 0 ? il : c == 9 ? ir : c < 5 ? ((ic0 >> (8 * (c - 1))) & 0xffu) : ((ic1 >> (8 * (c - 5))) & 0xffu);
       const float gval = c == 0 ? r.gl : c == 9 ? r.gr : gc[c - 1];
       m.gv[c] = byte < (uint32_t)g.R ? gval : 0.f;
-      m.off[c] = min(byte, (uint32_t)g.R) * 12u;
+      m.off[c] = min(byte, (uint32_t)g.R) * 12u + (uint32_t)q * (9 * kLutRows * 12);     // q: the wave's base bank
     }
   };
   struct LutT { f4 t0, t1; float t8; };
@@ -612,8 +612,8 @@ __global__ __launch_bounds__(256) void k_p4_reduce_w(const float* __restrict__ d
 #pragma unroll
   for (int ub = 0; ub < 9; ++ub) {
     float acc = 0.f;
-    if (base) {       // dF already is the base bank's gradient: only the layout changes
-      acc = src[(size_t)ub * plane];
+    if (base) {       // dF already is the base banks' gradient: only the layout changes
+      acc = src[(size_t)(b * 9 + ub) * plane];
     } else {
       for (int z = fqt_ptr[b * 9 + ub]; z < fqt_ptr[b * 9 + ub + 1]; ++z) acc += fqt_coef[z] * src[(size_t)fqt_col[z] * plane];
     }
@@ -633,7 +633,7 @@ bool p4_bwd_weight_supported(const rotconv_plan* p) {
 P4BwdWGeom p4_bwd_weight_geom(const rotconv_plan* p, bool lut) {
   const rotconv_desc& d = p->d;
   P4BwdWGeom g{};
-  g.N = d.N; g.Cin = d.Cin; g.H = d.H; g.W = d.W; g.Cout = d.Cout; g.Q = lut ? 1 : p->host.Q; g.ng = p->ng;
+  g.N = d.N; g.Cin = d.Cin; g.H = d.H; g.W = d.W; g.Cout = d.Cout; g.Q = lut ? p->B : p->host.Q; g.ng = p->ng;
   g.lut = lut ? 1 : 0; g.R = d.R;
   g.ncb = d.Cin <= 16 ? 1 : 4;
   const int NCB = g.ncb;
