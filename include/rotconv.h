@@ -49,6 +49,10 @@
  *     once, default 512, at least one image's worth is always taken;
  *     ROTCONV_BWD_LUT=0: fp32 gradients of multi-bank layers contract per bank
  *     instead of folding the routed gradients into the base taps first).
+ *   - Host threads: a plan is immutable except for the table upload of its first
+ *     call on a device, and is bound to that device afterwards (a call on another
+ *     device returns ROTCONV_ERR_UNSUPPORTED).  Make that first call from one
+ *     thread; later calls may come from any thread, each with its own workspace.
  *   - `ws` is a DEVICE scratch buffer of at least rotconv_workspace_bytes(plan)
  *     bytes, 256-byte aligned; its contents are undefined between calls, and
  *     two calls sharing one ws must not overlap in time.
