@@ -142,6 +142,10 @@ int rotconv_plan_destroy(rotconv_plan* plan);
 
 /* Bytes of scratch the largest call on this plan needs (may be 0). */
 size_t rotconv_workspace_bytes(const rotconv_plan* plan);
+/* Bytes of scratch with which rotconv_bwd_data and rotconv_bwd_weight (the unfused gradient calls, dense dy) run on
+ * the matrix cores as well: the routed products of a few images at a time, k*k*Q*Cout*H*W floats per image.  With the
+ * smaller rotconv_workspace_bytes they run slower general kernels (same result); never less than that value. */
+size_t rotconv_workspace_bytes_unfused(const rotconv_plan* plan);
 /* Output extents; any pointer may be NULL. Cunpooled = Cout*R, Cpooled = Cout*R/G. */
 int rotconv_out_shape(const rotconv_plan* plan, int32_t* Ho, int32_t* Wo, int32_t* Cunpooled, int32_t* Cpooled);
 

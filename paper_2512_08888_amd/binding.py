@@ -22,6 +22,7 @@ POOL_OPS = {"max": 0, "avg": 1}
 EXPORTS = [
     "rotconv_plan_create", "rotconv_plan_destroy", "rotconv_workspace_bytes", "rotconv_out_shape",
     "rotconv_plan_orientations", "rotconv_plan_expansion", "rotconv_plan_routed_table",
+    "rotconv_workspace_bytes_unfused",
     "rotconv_fwd", "rotconv_bwd_data", "rotconv_bwd_weight", "orient_maxpool_fwd", "orient_maxpool_bwd",
     "rotconv_pool_fwd", "rotconv_pool_bwd_data", "rotconv_pool_bwd_weight",
     "rotconv_status_string", "rotconv_plan_kernel_name", "rotconv_steerable_reg",
@@ -73,6 +74,8 @@ def lib():
         L.rotconv_plan_destroy.argtypes = [vp]
         L.rotconv_workspace_bytes.argtypes = [vp]
         L.rotconv_workspace_bytes.restype = sz
+        L.rotconv_workspace_bytes_unfused.argtypes = [vp]
+        L.rotconv_workspace_bytes_unfused.restype = sz
         L.rotconv_out_shape.argtypes = [vp, i32p, i32p, i32p, i32p]
         L.rotconv_plan_orientations.argtypes = [vp, i32p, i32p, i32p]
         L.rotconv_plan_expansion.argtypes = [vp, ctypes.POINTER(ctypes.c_float)]
@@ -161,6 +164,7 @@ class Plan:
         self.N, self.Cin, self.H, self.W, self.Cout, self.k, self.R = N, Cin, H, W, Cout, k, R
         self.B = 2 if m == MODES["steerable"] else 1
         self.workspace_bytes = int(lib().rotconv_workspace_bytes(self._h))
+        self.workspace_bytes_unfused = int(lib().rotconv_workspace_bytes_unfused(self._h))
         self._ws = None
 
     @classmethod

@@ -123,6 +123,13 @@ PadLayout pad_layout(const rotconv_plan* p) {
   return L;
 }
 
+// Scratch with which the unfused gradient calls (dense dy) of an fp32 plan leave the generic kernels for the matrix
+// multiply + scatter family; equals the plan's own need where that family is used anyway or does not apply.
+size_t unfused_ws_inner(const rotconv_plan* p) {
+  if (p->gs || p->d.pool_op == ROTCONV_POOL_AVG || !gs_wanted(p)) return p->ws_inner;
+  return std::max(p->ws_inner, align256(gs_ws_bytes(p)));
+}
+
 // how a pass runs: 2 bf16 matrix-core kernel, 1 fp32 matrix-core kernel, 0 generic
 int pass_level(const rotconv_plan* p, int pass) {
   if (p->d.dtype == ROTCONV_BF16 && p->native16[pass]) return 2;
@@ -234,6 +241,12 @@ int rotconv_plan_destroy(rotconv_plan* plan) {
 
 size_t rotconv_workspace_bytes(const rotconv_plan* plan) { return plan ? plan->ws_bytes : 0; }
 
+size_t rotconv_workspace_bytes_unfused(const rotconv_plan* plan) {
+  if (!plan) return 0;
+  if (plan->d.dtype == ROTCONV_BF16) return plan->ws_bytes - plan->ws_inner + unfused_ws_inner(plan);   // staging areas in front
+  return std::max(plan->ws_bytes, unfused_ws_inner(plan));
+}
+
 int rotconv_out_shape(const rotconv_plan* plan, int32_t* Ho, int32_t* Wo, int32_t* Cunpooled, int32_t* Cpooled) {
   if (!plan) return ROTCONV_ERR_NULL;
   if (Ho) *Ho = plan->Ho;
@@ -316,7 +329,9 @@ static int f32_rotconv_bwd_data(const rotconv_plan* plan, const void* dy, const 
   rotconv_plan* p = const_cast<rotconv_plan*>(plan);
   if ((rc = ensure_device_tables(p))) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if (p->gs) {
+  // the unfused gradients of a plan whose fused calls run the register-resident kernels: matrix multiply + scatter
+  // if the caller brought the larger workspace that family needs (rotconv_workspace_bytes_unfused), else generic
+  if (p->gs || (ws && ws_bytes >= unfused_ws_inner(p) && unfused_ws_inner(p) > p->ws_inner)) {
     launch_gs_bwd_data(p, static_cast<const float*>(dy), static_cast<const float*>(w), static_cast<float*>(dx), ws, st);
     return finish();
   }
@@ -334,7 +349,7 @@ static int f32_rotconv_bwd_weight(const rotconv_plan* plan, const void* x, const
   rotconv_plan* p = const_cast<rotconv_plan*>(plan);
   if ((rc = ensure_device_tables(p))) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if (p->gs) {
+  if (p->gs || (ws && ws_bytes >= unfused_ws_inner(p) && unfused_ws_inner(p) > p->ws_inner)) {
     launch_gs_bwd_weight(p, static_cast<const float*>(x), static_cast<const float*>(dy), dw, ws, st);
     return finish();
   }

@@ -222,6 +222,32 @@ def test_config3_reduced_with_and_without_table(monkeypatch):
         assert float(np.abs(a[k].astype(np.float64) - b[k]).max()) <= 2e-5 * scale, k
 
 
+@pytest.mark.parametrize("name", ["t_r4", "t_w96", "t_r16bil", "t_p4m_c40", "t_cin256", "t_padw_g2"])
+def test_unfused_gradients_with_the_larger_workspace(name):
+    """rotconv_bwd_data / rotconv_bwd_weight (dense dy) of plans whose fused calls run the register-resident kernels:
+    with rotconv_workspace_bytes_unfused of scratch they run matrix multiply + scatter instead of the generic kernels;
+    both against the oracle."""
+    cfg = next(c for c in TINY if c.name == name)
+    say(f"[case] unfused gradients, larger workspace {name}")
+    x, w = synth.make_x(cfg), synth.make_w(cfg)
+    L = pu.GpuLayer(cfg, x, w)
+    assert L.plan.workspace_bytes_unfused >= L.plan.workspace_bytes
+    dyd = synth.make_dy(cfg)
+    ang = None if cfg.angles_deg is None else list(cfg.angles_deg)
+    w_rot = orc.expand_bank(w, cfg.R, ang, cfg.mode)
+    dyd5 = dyd.reshape(cfg.N, cfg.Cout, cfg.R, cfg.Ho, cfg.Wo)
+    dx_ref = orc.rotconv_bwd_data(dyd5, w_rot, cfg.H, cfg.W, cfg.stride, cfg.pad)
+    dw_ref = orc.reduce_bank_grad(orc.rotconv_bwd_weight(x, dyd5, cfg.k, cfg.stride, cfg.pad), ang, cfg.mode)
+    dy_d = pu.dev(dyd, torch.float32)
+    ws = torch.empty(max(L.plan.workspace_bytes_unfused, 256), dtype=torch.uint8, device="cuda")
+    dx, dw = L.nan(tuple(L.x.shape)), L.nan(tuple(L.w.shape))
+    rc.rotconv_bwd_data(L.plan, dy_d, L.w, dx, ws=ws)
+    rc.rotconv_bwd_weight(L.plan, L.x, dy_d, dw, ws=ws)
+    torch.cuda.synchronize()
+    pu.assert_close(dx.cpu().numpy(), dx_ref, f"{name} dx (dense dy, larger workspace)")
+    pu.assert_close(dw.cpu().numpy(), dw_ref, f"{name} dw (dense dy, larger workspace)")
+
+
 def test_config1_fused_and_unfused():
     """Benchmark configuration 1 (N=1, 3->8, 64x64, R=4): both call chains, continuous and dyadic."""
     cfg = synth.C1
