@@ -241,8 +241,8 @@ def main():
                          "FETCH_SIZE / WRITE_SIZE readings can be scaled to bytes")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build measures one GPU only (the path shards over the batch; "
-              "see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build measures one GPU only (the path would shard over the batch, one process per "
+              "GPU, weight gradients all-reduced); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     if args.workload in ("C4", "C5", "P4", "P8", "P16"):
