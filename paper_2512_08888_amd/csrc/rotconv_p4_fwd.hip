@@ -532,12 +532,15 @@ template <int NWX, int NWY>
 void launch_t(const P4Geom& g, bool fastw, bool stream, const float* x, const float* wt, const int32_t* rot_of,
               float* ov, uint8_t* oi, hipStream_t st) {
   const bool unp = g.out_mode == kOutUnpooled;
-  if (g.nq > 1) {           // banks folded into the columns: resident filter block, pooled output, whole K chunks
+  if (g.nq > 1) {           // banks folded into the columns: pooled output, whole K chunks; a streamed block only
+                            // for rows without overhang (p4_fwd_fold sees to that)
     if (g.nq == 4) {
-      if (fastw) launch_i<NWX, NWY, false, true, false, 8, 4>(g, x, wt, rot_of, ov, oi, st);
+      if (stream) launch_i<NWX, NWY, false, true, true, 8, 4>(g, x, wt, rot_of, ov, oi, st);
+      else if (fastw) launch_i<NWX, NWY, false, true, false, 8, 4>(g, x, wt, rot_of, ov, oi, st);
       else launch_i<NWX, NWY, false, false, false, 8, 4>(g, x, wt, rot_of, ov, oi, st);
     } else {
-      if (fastw) launch_i<NWX, NWY, false, true, false, 8, 2>(g, x, wt, rot_of, ov, oi, st);
+      if (stream) launch_i<NWX, NWY, false, true, true, 8, 2>(g, x, wt, rot_of, ov, oi, st);
+      else if (fastw) launch_i<NWX, NWY, false, true, false, 8, 2>(g, x, wt, rot_of, ov, oi, st);
       else launch_i<NWX, NWY, false, false, false, 8, 2>(g, x, wt, rot_of, ov, oi, st);
     }
     return;
@@ -708,11 +711,14 @@ int p4_fwd_geoms(const rotconv_plan* p, int out_mode, P4Geom* out, int max_out, 
 }
 
 // Banks folded into a wave's 16 columns for the pooled forward: the plan pools all R = 4 Q orientations of a filter
-// together, Q is 2 or 4, every bank has its four quarter turns, the filter block stays LDS-resident and the channels
-// fill whole 32-channel chunks (1: no folding).
+// together, Q is 2 or 4, every bank has its four quarter turns, the channels fill whole 32-channel chunks, and the
+// filter block stays LDS-resident or is streamed under rows the wave chains cover exactly (1: no folding).
 int p4_fwd_fold(const rotconv_plan* p) {
   const int Q = p->host.Q;
-  if ((Q != 2 && Q != 4) || p->ng != 1 || needs_stream(p->d.Cin) || cin_pad_f32(p->d.Cin) == 4) return 1;
+  if ((Q != 2 && Q != 4) || p->ng != 1 || cin_pad_f32(p->d.Cin) == 4) return 1;
+  // a streamed filter block: only rows that the wave chains cover exactly (the instances without load masks)
+  const int W = p->d.W;
+  if (needs_stream(p->d.Cin) && ((W & 31) || (W <= 256 && (W & (W - 1))))) return 1;
   for (int i = 0; i < Q * 4; ++i)
     if (p->rot_of[i] < 0) return 1;
   return Q;
