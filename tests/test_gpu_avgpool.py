@@ -14,7 +14,7 @@ pytestmark = pytest.mark.gpu
 LC = synth.LayerConfig
 
 CASES = [
-    LC("a_r4", N=2, Cin=3, H=9, W=7, Cout=5, R=4, seed=81),                                        # generic kernels
+    LC("a_r4", N=2, Cin=3, H=9, W=7, Cout=5, R=4, seed=81),                                        # odd rows: padded-row plan
     LC("a_fast", N=2, Cin=20, H=12, W=32, Cout=18, R=4, seed=82),                                  # MFMA kernels
     LC("a_r16", N=1, Cin=8, H=10, W=64, Cout=6, R=16, mode="bilinear", seed=83),
     LC("a_ste_g4", N=1, Cin=4, H=8, W=16, Cout=4, R=8, mode="steerable", pool_group=4, seed=84),
