@@ -122,7 +122,9 @@ typedef struct {
   int32_t pool_op;          /* rotconv_pool_op.  ROTCONV_POOL_MAX (0): Eq. 10 / Eq. 12.
                                ROTCONV_POOL_AVG: ypool = mean over the pool group (Eq. 9),
                                every member receives gpool / G (Eq. 11); `idx` arguments are
-                               ignored and may be NULL.  fp32 plans only. */
+                               ignored and may be NULL.  bf16 plans: the fused calls run on fp32 copies
+                               in the workspace (the rotated banks rounded to bf16 first, as for every bf16
+                               plan), results rounded once. */
   int32_t activation;       /* rotconv_activation, applied by rotconv_pool_fwd only (max-pooling plans).
                                ROTCONV_ACT_RELU: ypool = max(pooled value, 0), and idx = 255 (no
                                orientation) wherever the pooled value is not positive.  Because an idx

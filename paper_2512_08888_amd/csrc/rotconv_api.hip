@@ -192,13 +192,17 @@ int rotconv_plan_create(const rotconv_desc* desc, rotconv_plan** out) {
     rotconv_desc cd = p->d;
     cd.Cout = p->d.Cout * p->ng; cd.R = 1; cd.angles_deg = nullptr; cd.mode = ROTCONV_EXACT90; cd.pool_group = 0;
     cd.pool_op = ROTCONV_POOL_MAX;
+    cd.dtype = ROTCONV_F32;       // a bf16 plan runs it on widened copies
     const int crc = rotconv_plan_create(&cd, &p->avg_child);
     if (crc != ROTCONV_OK) {
       delete p;
       return crc;
     }
     const AvgLayout L = avg_layout(p);
-    p->ws_inner = p->ws_bytes = std::max(p->ws_bytes, L.total);
+    const size_t staging = p->ws_bytes - p->ws_inner;       // a bf16 plan's fp32 copies in front (0 for fp32 plans)
+    p->ws_inner = std::max(p->ws_inner, L.total);
+    p->ws_bytes = staging + p->ws_inner;
+    p->native16[0] = p->native16[1] = p->native16[2] = 0;   // the fused calls go through the averaged bank in fp32
   }
   // 3x3 / stride 1 / pad 1 layers whose row width keeps a pass off the matrix-core kernels: the same layer on rows
   // padded to a multiple of 8 (32 beyond 256 pixels)
@@ -628,6 +632,10 @@ int rotconv_bwd_weight(const rotconv_plan* plan, const void* x, const void* dy, 
 int orient_maxpool_fwd(const rotconv_plan* plan, const void* y, void* ypool, uint8_t* idx, void* stream) {
   if (!plan || !y || !ypool || (!idx && !plan->avg_child)) return ROTCONV_ERR_NULL;
   if (!is_bf16(plan)) return f32_orient_maxpool_fwd(plan, y, ypool, idx, stream);
+  if (plan->avg_child) {
+    launch_avgpool_fwd_bf16(plan, h16(y), static_cast<uint16_t*>(ypool), static_cast<hipStream_t>(stream));
+    return finish();
+  }
   launch_maxpool_fwd_bf16(plan, h16(y), static_cast<uint16_t*>(ypool), idx, static_cast<hipStream_t>(stream));
   return finish();
 }
@@ -635,6 +643,10 @@ int orient_maxpool_fwd(const rotconv_plan* plan, const void* y, void* ypool, uin
 int orient_maxpool_bwd(const rotconv_plan* plan, const void* gpool, const uint8_t* idx, void* dy, void* stream) {
   if (!plan || !gpool || (!idx && !plan->avg_child) || !dy) return ROTCONV_ERR_NULL;
   if (!is_bf16(plan)) return f32_orient_maxpool_bwd(plan, gpool, idx, dy, stream);
+  if (plan->avg_child) {
+    launch_avgpool_bwd_bf16(plan, h16(gpool), static_cast<uint16_t*>(dy), static_cast<hipStream_t>(stream));
+    return finish();
+  }
   launch_maxpool_bwd_bf16(plan, h16(gpool), idx, static_cast<uint16_t*>(dy), static_cast<hipStream_t>(stream));
   return finish();
 }

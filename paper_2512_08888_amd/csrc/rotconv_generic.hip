@@ -150,28 +150,34 @@ __global__ __launch_bounds__(256) void k_maxpool_bwd(const T* __restrict__ gpool
   dy[((size_t)n * g.Cout * g.R + chan) * P + p] = (idx[q] == r) ? gpool[q] : T(0);
 }
 
-// Eq. 9: mean over each pool group.
-__global__ __launch_bounds__(256) void k_avgpool_fwd(const float* __restrict__ y, float* __restrict__ ypool, Geom g) {
+template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ uint16_t from_f32<uint16_t>(float v) { return f32_to_bf16(v); }
+
+// Eq. 9: mean over each pool group (T = float, or uint16_t holding bfloat16: summed in fp32, rounded once).
+template <typename T>
+__global__ __launch_bounds__(256) void k_avgpool_fwd(const T* __restrict__ y, T* __restrict__ ypool, Geom g) {
   const int P = g.Ho * g.Wo;
   const int p = blockIdx.x * 256 + threadIdx.x;
   if (p >= P) return;
   const int chan = blockIdx.y, n = blockIdx.z;
   const int co = chan / g.ng, grp = chan % g.ng;
-  const float* yb = y + ((size_t)n * g.Cout + co) * g.R * P + p;
+  const T* yb = y + ((size_t)n * g.Cout + co) * g.R * P + p;
   float s = 0.f;
-  for (int r = grp; r < g.R; r += g.ng) s += yb[(size_t)r * P];
-  ypool[((size_t)n * g.Cout * g.ng + chan) * P + p] = s * (1.0f / (float)g.G);
+  for (int r = grp; r < g.R; r += g.ng) s += as_f32<T>(yb[(size_t)r * P]);
+  ypool[((size_t)n * g.Cout * g.ng + chan) * P + p] = from_f32<T>(s * (1.0f / (float)g.G));
 }
 
 // Eq. 11: every member of the group receives gpool / G.
-__global__ __launch_bounds__(256) void k_avgpool_bwd(const float* __restrict__ gpool, float* __restrict__ dy, Geom g) {
+template <typename T>
+__global__ __launch_bounds__(256) void k_avgpool_bwd(const T* __restrict__ gpool, T* __restrict__ dy, Geom g) {
   const int P = g.Ho * g.Wo;
   const int p = blockIdx.x * 256 + threadIdx.x;
   if (p >= P) return;
   const int chan = blockIdx.y, n = blockIdx.z;   // chan = co*R + r
   const int co = chan / g.R, r = chan % g.R;
   const size_t q = (((size_t)n * g.Cout + co) * g.ng + r % g.ng) * P + p;
-  dy[((size_t)n * g.Cout * g.R + chan) * P + p] = gpool[q] * (1.0f / (float)g.G);
+  dy[((size_t)n * g.Cout * g.R + chan) * P + p] = from_f32<T>(as_f32<T>(gpool[q]) * (1.0f / (float)g.G));
 }
 
 // Group-averaged bank: wavg[(co*ng+grp)][ci][t] = (1/G) sum_{r mod ng == grp} wexp[r][co][ci][t].
@@ -383,12 +389,22 @@ void launch_maxpool_fwd(const rotconv_plan* p, const float* y, float* ypool, uin
 void launch_avgpool_fwd(const rotconv_plan* p, const float* y, float* ypool, hipStream_t st) {
   const Geom g = make_geom(p);
   dim3 grid((g.Ho * g.Wo + 255) / 256, g.Cout * g.ng, g.N);
-  hipLaunchKernelGGL(k_avgpool_fwd, grid, dim3(256), 0, st, y, ypool, g);
+  hipLaunchKernelGGL(k_avgpool_fwd<float>, grid, dim3(256), 0, st, y, ypool, g);
+}
+void launch_avgpool_fwd_bf16(const rotconv_plan* p, const uint16_t* y, uint16_t* ypool, hipStream_t st) {
+  const Geom g = make_geom(p);
+  dim3 grid((g.Ho * g.Wo + 255) / 256, g.Cout * g.ng, g.N);
+  hipLaunchKernelGGL(k_avgpool_fwd<uint16_t>, grid, dim3(256), 0, st, y, ypool, g);
+}
+void launch_avgpool_bwd_bf16(const rotconv_plan* p, const uint16_t* gpool, uint16_t* dy, hipStream_t st) {
+  const Geom g = make_geom(p);
+  dim3 grid((g.Ho * g.Wo + 255) / 256, g.Cout * g.R, g.N);
+  hipLaunchKernelGGL(k_avgpool_bwd<uint16_t>, grid, dim3(256), 0, st, gpool, dy, g);
 }
 void launch_avgpool_bwd(const rotconv_plan* p, const float* gpool, float* dy, hipStream_t st) {
   const Geom g = make_geom(p);
   dim3 grid((g.Ho * g.Wo + 255) / 256, g.Cout * g.R, g.N);
-  hipLaunchKernelGGL(k_avgpool_bwd, grid, dim3(256), 0, st, gpool, dy, g);
+  hipLaunchKernelGGL(k_avgpool_bwd<float>, grid, dim3(256), 0, st, gpool, dy, g);
 }
 void launch_avg_bank(const rotconv_plan* p, const float* wexp, float* wavg, hipStream_t st) {
   const int per = p->d.Cin * p->kk, total = p->d.Cout * p->ng * per;

@@ -110,7 +110,6 @@ int validate_and_build(const rotconv_desc* desc, rotconv_plan** out) {
   if (p4m && (d.angles_deg || (d.R != 2 && d.R != 4 && d.R != 8))) return ROTCONV_ERR_ANGLES;
   if (d.dtype != ROTCONV_F32 && d.dtype != ROTCONV_BF16) return ROTCONV_ERR_UNSUPPORTED;
   if (d.pool_op != ROTCONV_POOL_MAX && d.pool_op != ROTCONV_POOL_AVG) return ROTCONV_ERR_UNSUPPORTED;
-  if (d.pool_op == ROTCONV_POOL_AVG && d.dtype != ROTCONV_F32) return ROTCONV_ERR_UNSUPPORTED;
   if (d.activation != ROTCONV_ACT_NONE && d.activation != ROTCONV_ACT_RELU) return ROTCONV_ERR_UNSUPPORTED;
   if (d.activation == ROTCONV_ACT_RELU && d.pool_op != ROTCONV_POOL_MAX) return ROTCONV_ERR_UNSUPPORTED;
   if (d.k > 15) return ROTCONV_ERR_UNSUPPORTED;

@@ -38,6 +38,8 @@ void launch_maxpool_bwd(const rotconv_plan* p, const float* gpool, const uint8_t
 // average pooling (Eq. 9 / Eq. 11) and the pieces of its fused path
 void launch_avgpool_fwd(const rotconv_plan* p, const float* y, float* ypool, hipStream_t st);
 void launch_avgpool_bwd(const rotconv_plan* p, const float* gpool, float* dy, hipStream_t st);
+void launch_avgpool_fwd_bf16(const rotconv_plan* p, const uint16_t* y, uint16_t* ypool, hipStream_t st);
+void launch_avgpool_bwd_bf16(const rotconv_plan* p, const uint16_t* gpool, uint16_t* dy, hipStream_t st);
 // wavg[(co*ng+g)][ci][t] = (1/G) sum_{r mod ng == g} wexp[r][co][ci][t]
 void launch_avg_bank(const rotconv_plan* p, const float* wexp, float* wavg, hipStream_t st);
 // its adjoint: rep[r][co][ci][t] = dwavg[(co*ng + r mod ng)][ci][t] / G, then the transposed expansion into dw

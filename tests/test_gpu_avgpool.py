@@ -63,7 +63,42 @@ def test_avg_fused_calls(cfg):
     assert_close(host(dy).reshape(y_ref.shape), orc.orient_avgpool_bwd(g, cfg.R, cfg.G), f"{cfg.name} unfused Eq. 11")
 
 
-def test_avg_plan_rejects_bf16():
-    with pytest.raises(rc.RotconvError) as e:
-        rc.Plan(1, 4, 8, 8, 4, dtype=rc.BF16, pool_op="avg")
-    assert e.value.status == rc.ERR_UNSUPPORTED
+@pytest.mark.parametrize("cfg", [CASES[1], CASES[2], CASES[0]], ids=lambda c: c.name)
+def test_avg_bf16_plans(cfg):
+    """Average pooling on bf16 tensors: fused calls and the pooling pair against the oracle fed the bf16 values (the
+    rotated banks rounded to bf16 before they are averaged, as every bf16 plan multiplies with bf16 banks)."""
+    from parity_util import round_bf16
+    plan = rc.Plan.from_config(cfg, dtype=rc.BF16, pool_op="avg")
+    print(f"[case] average pooling bf16 {cfg.name}", flush=True)
+    ang = None if cfg.angles_deg is None else list(cfg.angles_deg)
+    b16 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(torch.bfloat16)
+    xt, wt, gt = b16(synth.make_x(cfg)), b16(synth.make_w(cfg)), b16(synth.make_g(cfg))
+    x, w, g = (t.to(torch.float64).numpy() for t in (xt, wt, gt))
+    xd, wd, gd = xt.cuda(), wt.cuda(), gt.cuda()
+    w_rot = round_bf16(orc.expand_bank(w, cfg.R, ang, cfg.mode))
+    y_ref = orc.rotconv_fwd(x, w_rot, cfg.stride, cfg.pad)
+    yp_ref = orc.orient_avgpool_fwd(y_ref, cfg.G)
+    dy_ref = orc.orient_avgpool_bwd(g, cfg.R, cfg.G)
+    dx_ref = orc.rotconv_bwd_data(dy_ref, w_rot, cfg.H, cfg.W, cfg.stride, cfg.pad)
+    dw_ref = orc.reduce_bank_grad(orc.rotconv_bwd_weight(x, dy_ref, cfg.k, cfg.stride, cfg.pad), ang, cfg.mode)
+    P = (cfg.N, plan.Cpooled, plan.Ho, plan.Wo)
+    nan16 = lambda *s_: torch.full(s_, float("nan"), dtype=torch.bfloat16, device="cuda")
+    yp = nan16(*P)
+    rc.rotconv_pool_fwd(plan, xd, wd, yp, None)
+    assert_close(host(yp.float()), yp_ref, f"{cfg.name} ypool (mean, bf16)", rtol=1e-2)
+    dx = nan16(*xd.shape)
+    rc.rotconv_pool_bwd_data(plan, gd, None, wd, dx)
+    assert_close(host(dx.float()), dx_ref, f"{cfg.name} dx (bf16)", rtol=1e-2)
+    dw = nan(*wd.shape)
+    rc.rotconv_pool_bwd_weight(plan, xd, gd, None, dw)
+    assert_close(host(dw), dw_ref, f"{cfg.name} dw (fp32)")
+    U = (cfg.N, plan.Cunpooled, plan.Ho, plan.Wo)
+    y = nan16(*U)
+    rc.rotconv_fwd(plan, xd, wd, y)
+    yp2 = nan16(*P)
+    rc.orient_maxpool_fwd(plan, y, yp2, None)
+    assert_close(host(yp2.float()), orc.orient_avgpool_fwd(host(y.float()).reshape(y_ref.shape), cfg.G),
+                 f"{cfg.name} unfused mean (bf16)", rtol=1e-2)
+    dy = nan16(*U)
+    rc.orient_maxpool_bwd(plan, gd, None, dy)
+    assert_close(host(dy.float()).reshape(y_ref.shape), dy_ref, f"{cfg.name} unfused Eq. 11 (bf16)", rtol=1e-2)
