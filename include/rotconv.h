@@ -193,6 +193,22 @@ int orient_maxpool_bwd(const rotconv_plan* plan, const void* gpool, const uint8_
  * run ONE ordinary convolution with the group-averaged bank (1/G) sum_r W^(r) (and its adjoints). */
 int rotconv_pool_fwd(const rotconv_plan* plan, const void* x, const void* w, void* ypool, uint8_t* idx, void* ws,
                      size_t ws_bytes, void* stream);
+/* rotconv_pool_fwd for callers that cannot allocate device memory or bring a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and kernels as
+ * rotconv_pool_fwd, but the scratch (the re-laid banks and, for some plans, per-bank candidates or channel-split
+ * parts) lives in a file-scope device array of ROTCONV_STATIC_SCRATCH_BYTES that each GPU the library runs on
+ * holds until the process ends.  The call makes no hipMalloc / hipFree and uploads nothing:
+ *   - ROTCONV_ERR_UNSUPPORTED if the plan's tables are not on the current device yet (run any ordinary call
+ *     of the plan there first; that first call is the one that allocates);
+ *   - ROTCONV_ERR_WORKSPACE if this call's scratch need exceeds ROTCONV_STATIC_SCRATCH_BYTES (e.g. layers deeper
+ *     than about 512 x 512 channels at R = 4, plans that stage padded rows or widened copies of large tensors);
+ *   - the first call on a device resolves the array's device address (no allocation; make it outside a capture).
+ * All calls on one GPU share that GPU's array, which keeps the last call's contents; every region a call reads
+ * it has written first, so nothing needs clearing.  Two calls that overlap in time on one GPU (two streams, two
+ * host threads) race on it: serialise them. */
+#define ROTCONV_STATIC_SCRATCH_BYTES ((size_t)16 << 20)
+int rotconv_pool_fwd_static(const rotconv_plan* plan, const void* x, const void* w, void* ypool, uint8_t* idx,
+                            void* stream);
 /* Eq. 12 + Eq. 13 + Eq. 15. */
 int rotconv_pool_bwd_data(const rotconv_plan* plan, const void* gpool, const uint8_t* idx, const void* w, void* dx,
                           void* ws, size_t ws_bytes, void* stream);

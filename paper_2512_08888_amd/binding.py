@@ -24,7 +24,7 @@ EXPORTS = [
     "rotconv_plan_orientations", "rotconv_plan_expansion", "rotconv_plan_routed_table",
     "rotconv_workspace_bytes_unfused",
     "rotconv_fwd", "rotconv_bwd_data", "rotconv_bwd_weight", "orient_maxpool_fwd", "orient_maxpool_bwd",
-    "rotconv_pool_fwd", "rotconv_pool_bwd_data", "rotconv_pool_bwd_weight",
+    "rotconv_pool_fwd", "rotconv_pool_bwd_data", "rotconv_pool_bwd_weight", "rotconv_pool_fwd_static",
     "rotconv_status_string", "rotconv_plan_kernel_name", "rotconv_steerable_reg",
 ]
 
@@ -86,6 +86,7 @@ def lib():
         L.orient_maxpool_fwd.argtypes = [vp, vp, vp, vp, vp]
         L.orient_maxpool_bwd.argtypes = [vp, vp, vp, vp, vp]
         L.rotconv_pool_fwd.argtypes = [vp, vp, vp, vp, vp, vp, sz, vp]
+        L.rotconv_pool_fwd_static.argtypes = [vp, vp, vp, vp, vp, vp]
         L.rotconv_pool_bwd_data.argtypes = [vp, vp, vp, vp, vp, vp, sz, vp]
         L.rotconv_pool_bwd_weight.argtypes = [vp, vp, vp, vp, vp, vp, sz, vp]
         L.rotconv_status_string.argtypes = [ctypes.c_int]
@@ -258,6 +259,12 @@ def rotconv_pool_fwd(plan: Plan, x, w, ypool, idx, ws=None):
     p, n = _ws_args(plan, ws)
     _check(lib().rotconv_pool_fwd(plan.handle, _ptr(x), _ptr(w), _ptr(ypool), _ptr(idx), p, n, _stream()),
            "rotconv_pool_fwd")
+
+
+def rotconv_pool_fwd_static(plan: Plan, x, w, ypool, idx):
+    """rotconv_pool_fwd on the library's own per-GPU scratch array: no workspace, no allocation."""
+    _check(lib().rotconv_pool_fwd_static(plan.handle, _ptr(x), _ptr(w), _ptr(ypool), _ptr(idx), _stream()),
+           "rotconv_pool_fwd_static")
 
 
 def rotconv_pool_bwd_data(plan: Plan, gpool, idx, w, dx, ws=None):

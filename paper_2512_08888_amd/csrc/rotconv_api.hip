@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cstring>
 
 #include "rotconv_kernels.h"
@@ -45,6 +46,13 @@ int ensure_device_tables(rotconv_plan* p) {
     return ROTCONV_ERR_LAUNCH;
   }
   d.device = dev;
+  // the plans this one runs some passes through: their tables go up with the parent's, so that no pass of the
+  // parent allocates after the parent's first call
+  for (rotconv_plan* ch : {p->avg_child, p->pad_child})
+    if (ch) {
+      const int rc = ensure_device_tables(ch);
+      if (rc != ROTCONV_OK) return rc;
+    }
   return ROTCONV_OK;
 }
 
@@ -55,6 +63,15 @@ void free_device_tables(rotconv_plan* p) {
   for (void* q : ptrs)
     if (q) (void)hipFree(q);
   d = DeviceTables();
+}
+
+// Are the plan's tables (and those of the plans it runs passes through) on the current device already?
+bool tables_on_current_device(const rotconv_plan* p) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || p->dev.device != dev) return false;
+  for (const rotconv_plan* ch : {p->avg_child, p->pad_child})
+    if (ch && !tables_on_current_device(ch)) return false;
+  return true;
 }
 
 namespace {
@@ -386,12 +403,29 @@ static int f32_orient_maxpool_bwd(const rotconv_plan* plan, const void* gpool, c
   return finish();
 }
 
+// Does the pooled forward of an fp32 plan run the register-resident kernel for these pointers?
+static bool f32_pool_fwd_is_fast(const rotconv_plan* p, const void* x, const void* ypool, const uint8_t* idx,
+                                 const void* ws) {
+  return !p->avg_child && p->fast[0] && aligned(x, 8) && aligned(ws, 256) && aligned(ypool, 16) && aligned(idx, 8);
+}
+
+// Scratch the pooled forward of an fp32 plan touches: the packed banks (+ candidates / parts) of the register-resident
+// kernel; every other route is sized by the plan's largest call.
+static size_t f32_pool_fwd_need(const rotconv_plan* p, const void* x, const void* ypool, const uint8_t* idx,
+                                const void* ws) {
+  return f32_pool_fwd_is_fast(p, x, ypool, idx, ws) ? std::min(p->ws_inner, fwd_fast_ws_bytes(p)) : p->ws_inner;
+}
+
+// no_upload: the caller may not allocate, so a plan whose tables are not on this device yet is refused
 static int f32_rotconv_pool_fwd(const rotconv_plan* plan, const void* x, const void* w, void* ypool, uint8_t* idx, void* ws,
-                     size_t ws_bytes, void* stream) {
+                     size_t ws_bytes, void* stream, bool own_need = false, bool no_upload = false) {
   if (!plan || !x || !w || !ypool || (!idx && !plan->avg_child)) return ROTCONV_ERR_NULL;
-  int rc = check_ws_inner(plan, ws, ws_bytes);
-  if (rc) return rc;
+  // own_need: the buffer only has to hold what THIS call touches, not the plan's largest call
+  const size_t need = own_need ? f32_pool_fwd_need(plan, x, ypool, idx, ws) : plan->ws_inner;
+  if (need && (!ws || ws_bytes < need)) return ROTCONV_ERR_WORKSPACE;
+  int rc;
   rotconv_plan* p = const_cast<rotconv_plan*>(plan);
+  if (no_upload && !tables_on_current_device(p)) return ROTCONV_ERR_UNSUPPORTED;
   if ((rc = ensure_device_tables(p))) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (p->avg_child) {     // Eq. 9: the mean over a group = one convolution with the group-averaged bank
@@ -403,7 +437,7 @@ static int f32_rotconv_pool_fwd(const rotconv_plan* plan, const void* x, const v
     launch_avg_bank(p, wexp, wavg, st);
     return rotconv_fwd(p->avg_child, x, wavg, ypool, c + L.child, p->avg_child->ws_bytes, stream);
   }
-  if (p->fast[0] && aligned(x, 8) && aligned(ws, 256) && aligned(ypool, 16) && aligned(idx, 8)) {
+  if (f32_pool_fwd_is_fast(p, x, ypool, idx, ws)) {
     float* wt = static_cast<float*>(ws);
     char* extra = static_cast<char*>(ws) + fwd_pack_region(p);
     const int mode = p4_fwd_pool_mode(p);
@@ -651,27 +685,52 @@ int orient_maxpool_bwd(const rotconv_plan* plan, const void* gpool, const uint8_
   return finish();
 }
 
-int rotconv_pool_fwd(const rotconv_plan* plan, const void* x, const void* w, void* ypool, uint8_t* idx, void* ws,
-                     size_t ws_bytes, void* stream) {
+namespace {
+
+// Does the pooled forward of a bf16 plan run the bf16 matrix-core kernel for these pointers?
+bool bf16_pool_fwd_is_native(const rotconv_plan* plan, const void* x, const void* w, const void* ypool,
+                             const uint8_t* idx, const void* ws) {
+  const int pmode = plan->native16[0] ? p4_fwd_pool_mode(plan) : kOutUnpooled;
+  return pmode != kOutUnpooled && aligned(x, 4) && aligned(w, 2) && aligned(ws, 256) && aligned(ypool, 16) &&
+         aligned(idx, 8);
+}
+
+// Bytes of `ws` one call of the pooled forward touches, by the route it takes for these pointers (never more than
+// rotconv_workspace_bytes, which is the largest need of any call on the plan).
+size_t pool_fwd_need(const rotconv_plan* plan, const void* x, const void* w, const void* ypool, const uint8_t* idx,
+                     const void* ws) {
+  if (plan->pad_child && plan->pad_use[0]) return plan->ws_bytes;             // staging copies + the padded plan
+  if (!is_bf16(plan)) return f32_pool_fwd_need(plan, x, ypool, idx, ws);
+  if (bf16_pool_fwd_is_native(plan, x, w, ypool, idx, ws)) return std::min(plan->ws_bytes, fwd_fast_ws_bytes(plan));
+  return plan->ws_bytes;                                                      // fp32 staging areas in front
+}
+
+// own_need: `ws` has to hold what this call touches (pool_fwd_need), not the plan's largest call.
+// no_upload: no allocation allowed: a plan whose tables are not on the current device yet is refused.
+int pool_fwd_impl(const rotconv_plan* plan, const void* x, const void* w, void* ypool, uint8_t* idx, void* ws,
+                  size_t ws_bytes, void* stream, bool own_need, bool no_upload) {
   if (!plan || !x || !w || !ypool || (!idx && !plan->avg_child)) return ROTCONV_ERR_NULL;
   if (plan->pad_child && plan->pad_use[0]) {
+    if (no_upload && !tables_on_current_device(plan->pad_child)) return ROTCONV_ERR_UNSUPPORTED;
     PadCtx c;
     int rc = pad_ctx(plan, ws, ws_bytes, stream, &c);
     if (rc) return rc;
     launch_repitch(x, c.in, c.rows_x, c.W, c.Wp, c.es, 0, c.st);
-    if ((rc = rotconv_pool_fwd(c.ch, c.in, w, c.out, reinterpret_cast<uint8_t*>(c.idx), c.cws, c.ch->ws_bytes, stream)))
+    if ((rc = pool_fwd_impl(c.ch, c.in, w, c.out, reinterpret_cast<uint8_t*>(c.idx), c.cws, c.ch->ws_bytes, stream, false,
+                            no_upload)))
       return rc;
     launch_repitch(c.out, ypool, c.rows_p, c.Wp, c.W, c.es, 0, c.st);
     launch_repitch(c.idx, idx, c.rows_p, c.Wp, c.W, 1, 0, c.st);
     return finish();
   }
-  if (!is_bf16(plan)) return f32_rotconv_pool_fwd(plan, x, w, ypool, idx, ws, ws_bytes, stream);
-  if (!ws || ws_bytes < plan->ws_bytes) return ROTCONV_ERR_WORKSPACE;
+  if (!is_bf16(plan)) return f32_rotconv_pool_fwd(plan, x, w, ypool, idx, ws, ws_bytes, stream, own_need, no_upload);
+  const size_t need = own_need ? pool_fwd_need(plan, x, w, ypool, idx, ws) : plan->ws_bytes;
+  if (!ws || ws_bytes < need) return ROTCONV_ERR_WORKSPACE;
+  if (no_upload && !tables_on_current_device(plan)) return ROTCONV_ERR_UNSUPPORTED;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  const int pmode = plan->native16[0] ? p4_fwd_pool_mode(plan) : kOutUnpooled;
-  if (pmode != kOutUnpooled && aligned(x, 4) && aligned(w, 2) && aligned(ws, 256) && aligned(ypool, 16) &&
-      aligned(idx, 8)) {
+  if (bf16_pool_fwd_is_native(plan, x, w, ypool, idx, ws)) {
     // bf16 tensors straight into the bf16 matrix-core kernel; scratch laid out as in the fp32 path
+    const int pmode = p4_fwd_pool_mode(plan);
     rotconv_plan* p = const_cast<rotconv_plan*>(plan);
     const int rc = ensure_device_tables(p);
     if (rc) return rc;
@@ -695,10 +754,55 @@ int rotconv_pool_fwd(const rotconv_plan* plan, const void* x, const void* w, voi
   const Stage s = carve(plan, ws, ws_bytes);
   launch_widen(h16(x), s.x, plan->n_x, st);
   launch_widen(h16(w), s.w, plan->n_w, st);
-  const int rc = f32_rotconv_pool_fwd(plan, s.x, s.w, s.y, idx, s.inner, s.inner_bytes, stream);
+  const int rc = f32_rotconv_pool_fwd(plan, s.x, s.w, s.y, idx, s.inner, s.inner_bytes, stream, false, no_upload);
   if (rc) return rc;
   launch_narrow(s.y, static_cast<uint16_t*>(ypool), plan->n_yp, st);
   return finish();
+}
+
+// ---- scratch of the entry point that allocates nothing ------------------------------------------------------
+// One array per GPU (each device that loads this code object holds its own copy at its own address, until the
+// process ends).  Host code never uses the array's name as an address: static_scratch() resolves the device
+// address once per device with hipGetSymbolAddress and hands that pointer to the kernels.
+constexpr size_t kStaticScratchBytes = ROTCONV_STATIC_SCRATCH_BYTES;
+constexpr int kMaxDevices = 64;
+
+}  // namespace
+
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+
+static std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+// Device address of `scratch` on the current device (nullptr on failure).
+static void* static_scratch() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (ptr) return ptr;
+  if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+    (void)hipGetLastError();
+    return nullptr;
+  }
+  g_scratch_ptr[dev].store(ptr, std::memory_order_release);     // every thread resolves the same address
+  return ptr;
+}
+
+}  // namespace
+
+int rotconv_pool_fwd(const rotconv_plan* plan, const void* x, const void* w, void* ypool, uint8_t* idx, void* ws,
+                     size_t ws_bytes, void* stream) {
+  return pool_fwd_impl(plan, x, w, ypool, idx, ws, ws_bytes, stream, false, false);
+}
+
+int rotconv_pool_fwd_static(const rotconv_plan* plan, const void* x, const void* w, void* ypool, uint8_t* idx,
+                            void* stream) {
+  if (!plan || !x || !w || !ypool || (!idx && !plan->avg_child)) return ROTCONV_ERR_NULL;
+  void* ws = static_scratch();
+  if (!ws) return ROTCONV_ERR_LAUNCH;
+  if (pool_fwd_need(plan, x, w, ypool, idx, ws) > kStaticScratchBytes) return ROTCONV_ERR_WORKSPACE;
+  return pool_fwd_impl(plan, x, w, ypool, idx, ws, kStaticScratchBytes, stream, true, true);
 }
 
 int rotconv_pool_bwd_data(const rotconv_plan* plan, const void* gpool, const uint8_t* idx, const void* w, void* dx,
