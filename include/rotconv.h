@@ -41,14 +41,8 @@
  *     call on a device uploads its tables (the only allocation and host-to-device
  *     copy the library makes); every later call launches kernels only, so it can
  *     be recorded into a HIP graph and replayed.
- *   - Four environment variables are read when a plan is created and tune its
- *     kernel choice: ROTCONV_FWD_CSPLIT (0 / unset: automatic; 1: never split the
- *     forward's channel contraction; n: n parts) and ROTCONV_GS (0 / 1: never /
- *     always run shapes outside the 3x3 kernels on the GEMM + scatter family;
- *     ROTCONV_GS_CHUNK_MB: MiB of products that family keeps in the workspace at
- *     once, default 512, at least one image's worth is always taken;
- *     ROTCONV_BWD_LUT=0: fp32 gradients of multi-bank layers contract per bank
- *     instead of folding the routed gradients into the base taps first).
+ *   - Kernel choices are made when a plan is created, from the descriptor and the
+ *     optional rotconv_plan_options (below); the process environment is never read.
  *   - Host threads: a plan is immutable except for the table upload of its first
  *     call on a device, and is bound to that device afterwards (a call on another
  *     device returns ROTCONV_ERR_UNSUPPORTED).  Make that first call from one
@@ -89,7 +83,8 @@ typedef enum { ROTCONV_ACT_NONE = 0, ROTCONV_ACT_RELU = 1 } rotconv_activation;
 typedef struct {
   int32_t N, Cin, H, W;
   int32_t Cout, k;          /* square kernels only: quarter turns need them            */
-  int32_t R;                /* number of orientations, 1..255                          */
+  int32_t R;                /* number of orientations, 1..255; Cout * R, Cin and N at most 65535 each
+                               (ROTCONV_ERR_UNSUPPORTED beyond)                         */
   const double* angles_deg; /* HOST, R strictly ascending angles in [0,360); NULL means
                                r*360/R (evenly spaced, Sec. III-D).  Copied by plan_create. */
   int32_t mode;             /* rotconv_mode: how first-quadrant filters are built.
@@ -115,7 +110,8 @@ typedef struct {
                                values before y / ypool are rounded (nearest even) to
                                bf16; dw stays fp32; idx stays uint8.  The rotated banks a
                                bf16 plan multiplies with are bf16 too (the first-quadrant
-                               combination is formed in fp32 and rounded once).  3x3 /
+                               combination is formed in fp64 from fp64 coefficients and
+                               rounded to fp32, then to bf16, nearest even).  3x3 /
                                stride 1 / pad 1 layers run on the bf16 matrix cores; other
                                shapes are widened to fp32 in the workspace and run the
                                fp32 kernels. */
@@ -136,9 +132,29 @@ typedef struct {
 
 typedef struct rotconv_plan rotconv_plan; /* opaque */
 
+/* Tuning switches of a plan's kernel choice (results are the same for every setting, up to summation order).
+ * All zero = automatic, which is what rotconv_plan_create uses. */
+typedef struct {
+  int32_t fwd_csplit;   /* channel split of the 3x3 forward on small maps with deep inputs: 0 automatic,
+                           1 never (where an unsplit kernel exists), n >= 2: n parts                        */
+  int32_t gs;           /* shapes outside the 3x3 / stride 1 / pad 1 kernels on the matrix multiply + scatter
+                           family: 0 automatic (from about a megaflop), 1 always, -1 never (generic kernels)   */
+  int32_t gs_chunk_mb;  /* MiB of products that family keeps in the workspace at once: 0 = 512, n > 0 = n,
+                           -1 = one image at a time (at least one image's worth is always taken)               */
+  int32_t bwd_lut;      /* fp32 gradients of layers whose pool group spans several first-quadrant banks:
+                           0 automatic (routed gradients folded into the base taps, one contraction),
+                           -1 never (one contraction per bank)                                                 */
+  int32_t fwd_base;     /* fp32 forward of such layers: 0 automatic (products of the base bank only, combined
+                           into the banks' products on the vector ALU), -1 never (one contraction per bank)    */
+  int32_t reserved[3];  /* must be 0 */
+} rotconv_plan_options;
+
 /* Validates the descriptor, builds the orientation tables on the host and
  * returns a plan.  Touches no GPU.  `*out` is set only on ROTCONV_OK. */
 int rotconv_plan_create(const rotconv_desc* desc, rotconv_plan** out);
+/* The same with tuning switches; `opts` HOST, copied, NULL = all automatic.  ROTCONV_ERR_UNSUPPORTED for a
+ * non-zero reserved field. */
+int rotconv_plan_create_opt(const rotconv_desc* desc, const rotconv_plan_options* opts, rotconv_plan** out);
 /* Frees the plan and its device tables (if any were uploaded). NULL is allowed. */
 int rotconv_plan_destroy(rotconv_plan* plan);
 
@@ -231,8 +247,10 @@ int rotconv_steerable_reg(const float* w, int32_t Cout, int32_t per, float lambd
 
 /* Static, never NULL. */
 const char* rotconv_status_string(int status);
-/* Name of the kernel family the last successful call of the given kind on this
- * plan would use ("generic", "mfma_p4", ...).  pass: 0 fwd, 1 bwd_data, 2 bwd_weight. */
+/* Name of the kernel family a call of the given kind on this plan uses ("generic", "mfma_p4", "mfma_p4_bf16",
+ * "mfma_gemm_scatter").  pass: 0 / 1 / 2 = the fused calls rotconv_pool_fwd / _bwd_data / _bwd_weight (and
+ * rotconv_fwd); 3 / 4 = the unfused gradient calls rotconv_bwd_data / rotconv_bwd_weight when given
+ * rotconv_workspace_bytes_unfused of scratch (with less they run "generic"). */
 const char* rotconv_plan_kernel_name(const rotconv_plan* plan, int pass);
 
 #ifdef __cplusplus

@@ -20,7 +20,7 @@ MODES = {"exact90": 0, "steerable": 1, "bilinear": 2, "p4m": 3}
 POOL_OPS = {"max": 0, "avg": 1}
 
 EXPORTS = [
-    "rotconv_plan_create", "rotconv_plan_destroy", "rotconv_workspace_bytes", "rotconv_out_shape",
+    "rotconv_plan_create", "rotconv_plan_create_opt", "rotconv_plan_destroy", "rotconv_workspace_bytes", "rotconv_out_shape",
     "rotconv_plan_orientations", "rotconv_plan_expansion", "rotconv_plan_routed_table",
     "rotconv_workspace_bytes_unfused",
     "rotconv_fwd", "rotconv_bwd_data", "rotconv_bwd_weight", "orient_maxpool_fwd", "orient_maxpool_bwd",
@@ -51,6 +51,14 @@ class Desc(ctypes.Structure):
     ]
 
 
+class PlanOptions(ctypes.Structure):
+    """rotconv_plan_options: tuning switches of a plan's kernel choice (all zero: automatic)."""
+    _fields_ = [
+        ("fwd_csplit", ctypes.c_int32), ("gs", ctypes.c_int32), ("gs_chunk_mb", ctypes.c_int32),
+        ("bwd_lut", ctypes.c_int32), ("fwd_base", ctypes.c_int32), ("reserved", ctypes.c_int32 * 3),
+    ]
+
+
 class RotconvError(RuntimeError):
     def __init__(self, status: int, what: str):
         self.status = status
@@ -71,6 +79,7 @@ def lib():
         L = ctypes.CDLL(LIB_PATH)
         vp, sz, i32p = ctypes.c_void_p, ctypes.c_size_t, ctypes.POINTER(ctypes.c_int32)
         L.rotconv_plan_create.argtypes = [ctypes.POINTER(Desc), ctypes.POINTER(vp)]
+        L.rotconv_plan_create_opt.argtypes = [ctypes.POINTER(Desc), ctypes.POINTER(PlanOptions), ctypes.POINTER(vp)]
         L.rotconv_plan_destroy.argtypes = [vp]
         L.rotconv_workspace_bytes.argtypes = [vp]
         L.rotconv_workspace_bytes.restype = sz
@@ -148,7 +157,8 @@ class Plan:
     """Owns a rotconv_plan*.  Mirrors rotconv_plan_create / destroy and the host-side queries."""
 
     def __init__(self, N, Cin, H, W, Cout, k=3, R=4, angles_deg: Optional[Sequence[float]] = None, mode="exact90",
-                 stride=1, pad=1, pool_group=0, dtype=F32, pool_op="max", relu=False):
+                 stride=1, pad=1, pool_group=0, dtype=F32, pool_op="max", relu=False, options=None):
+        """options: dict of rotconv_plan_options fields (fwd_csplit, gs, gs_chunk_mb, bwd_lut, fwd_base) or None."""
         self._h = ctypes.c_void_p()
         self._angles = None
         ang = None
@@ -158,7 +168,13 @@ class Plan:
         m = MODES[mode] if isinstance(mode, str) else int(mode)
         po = POOL_OPS[pool_op] if isinstance(pool_op, str) else int(pool_op)
         self.desc = Desc(N, Cin, H, W, Cout, k, R, ang, m, stride, pad, pool_group or 0, dtype, po, 1 if relu else 0)
-        _check(lib().rotconv_plan_create(ctypes.byref(self.desc), ctypes.byref(self._h)), "rotconv_plan_create")
+        if options:
+            self.options = PlanOptions(**{k: int(v) for k, v in options.items()})
+            _check(lib().rotconv_plan_create_opt(ctypes.byref(self.desc), ctypes.byref(self.options),
+                                                 ctypes.byref(self._h)), "rotconv_plan_create_opt")
+        else:
+            self.options = None
+            _check(lib().rotconv_plan_create(ctypes.byref(self.desc), ctypes.byref(self._h)), "rotconv_plan_create")
         ho, wo, cu, cp = (ctypes.c_int32() for _ in range(4))
         lib().rotconv_out_shape(self._h, ctypes.byref(ho), ctypes.byref(wo), ctypes.byref(cu), ctypes.byref(cp))
         self.Ho, self.Wo, self.Cunpooled, self.Cpooled = ho.value, wo.value, cu.value, cp.value

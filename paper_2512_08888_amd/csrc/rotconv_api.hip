@@ -35,11 +35,14 @@ int ensure_device_tables(rotconv_plan* p) {
   DeviceTables& d = p->dev;
   std::vector<int32_t> rq(p->d.R);
   for (int r = 0; r < p->d.R; ++r) rq[r] = t.bank_of_r[r] * 4 + t.quarter_of_r[r];
+  const bool bf = p->d.dtype == ROTCONV_BF16;      // only bf16 plans read the fp64 coefficients
+  const std::vector<double> none64;
   const bool ok = upload(t.exp_src, &d.exp_src) && upload(t.exp_coef, &d.exp_coef) && upload(t.tr_ptr, &d.tr_ptr) &&
                   upload(t.tr_col, &d.tr_col) && upload(t.tr_coef, &d.tr_coef) && upload(t.fq_src, &d.fq_src) &&
                   upload(t.fq_coef, &d.fq_coef) && upload(t.fqt_ptr, &d.fqt_ptr) && upload(t.fqt_col, &d.fqt_col) &&
                   upload(t.fqt_coef, &d.fqt_coef) && upload(p->rot_of, &d.rot_of) && upload(rq, &d.rq_of_r) &&
-                  upload(t.turn_tap, &d.turn_tap) && upload(t.lut_bwd, &d.lut_bwd);
+                  upload(t.turn_tap, &d.turn_tap) && upload(t.lut_bwd, &d.lut_bwd) &&
+                  upload(bf ? t.exp_coef64 : none64, &d.exp_coef64) && upload(bf ? t.fq_coef64 : none64, &d.fq_coef64);
   if (!ok) {
     (void)hipGetLastError();
     free_device_tables(p);
@@ -59,7 +62,8 @@ int ensure_device_tables(rotconv_plan* p) {
 void free_device_tables(rotconv_plan* p) {
   DeviceTables& d = p->dev;
   void* ptrs[] = {d.exp_src, d.exp_coef, d.tr_ptr, d.tr_col, d.tr_coef, d.fq_src,
-                  d.fq_coef, d.fqt_ptr, d.fqt_col, d.fqt_coef, d.rot_of, d.rq_of_r, d.turn_tap, d.lut_bwd};
+                  d.fq_coef, d.fqt_ptr, d.fqt_col, d.fqt_coef, d.rot_of, d.rq_of_r, d.turn_tap, d.lut_bwd,
+                  d.exp_coef64, d.fq_coef64};
   for (void* q : ptrs)
     if (q) (void)hipFree(q);
   d = DeviceTables();
@@ -147,6 +151,15 @@ size_t unfused_ws_inner(const rotconv_plan* p) {
   return std::max(p->ws_inner, align256(gs_ws_bytes(p)));
 }
 
+// Do the unfused gradient calls (dense dy) run matrix multiply + scatter with this much scratch?  Plans whose fused
+// calls run that family anyway: always; plans on the register-resident kernels: when the family is wanted for the
+// layer and the caller brought rotconv_workspace_bytes_unfused.
+bool unfused_on_gs(const rotconv_plan* p, const void* ws, size_t ws_bytes) {
+  if (p->gs) return true;
+  if (p->d.pool_op == ROTCONV_POOL_AVG || !gs_wanted(p)) return false;
+  return ws && ws_bytes >= unfused_ws_inner(p);
+}
+
 // how a pass runs: 2 bf16 matrix-core kernel, 1 fp32 matrix-core kernel, 0 generic
 int pass_level(const rotconv_plan* p, int pass) {
   if (p->d.dtype == ROTCONV_BF16 && p->native16[pass]) return 2;
@@ -161,10 +174,16 @@ using namespace rotconv;
 extern "C" {
 
 int rotconv_plan_create(const rotconv_desc* desc, rotconv_plan** out) {
+  return rotconv_plan_create_opt(desc, nullptr, out);
+}
+
+int rotconv_plan_create_opt(const rotconv_desc* desc, const rotconv_plan_options* opts, rotconv_plan** out) {
   if (!desc || !out) return ROTCONV_ERR_NULL;
+  if (opts && (opts->reserved[0] || opts->reserved[1] || opts->reserved[2])) return ROTCONV_ERR_UNSUPPORTED;
   rotconv_plan* p = nullptr;
   const int rc = validate_and_build(desc, &p);
   if (rc != ROTCONV_OK) return rc;
+  if (opts) p->opt = *opts;
   p->bwdw_splits = generic_bwdw_splits(p);
   p->ws_bytes = generic_ws_bytes(p);
   p->fast[0] = p4_fwd_supported(p) ? 1 : 0;
@@ -189,7 +208,7 @@ int rotconv_plan_create(const rotconv_desc* desc, rotconv_plan** out) {
   const bool is3x3 = p->d.k == 3 && p->d.stride == 1 && p->d.pad == 1;
   if (!(p->fast[0] && p->fast[1] && p->fast[2]) && !(is3x3 && p4_fwd_pool_mode(p) != kOutUnpooled) && gs_wanted(p)) {
     p->gs = 1;
-    p->gs_chunk_bytes = gs_chunk_budget();
+    p->gs_chunk_bytes = gs_chunk_budget(p);
     p->ws_bytes = std::max(p->ws_bytes, gs_ws_bytes(p));
   }
   p->ws_inner = p->ws_bytes = align256(p->ws_bytes);
@@ -210,7 +229,7 @@ int rotconv_plan_create(const rotconv_desc* desc, rotconv_plan** out) {
     cd.Cout = p->d.Cout * p->ng; cd.R = 1; cd.angles_deg = nullptr; cd.mode = ROTCONV_EXACT90; cd.pool_group = 0;
     cd.pool_op = ROTCONV_POOL_MAX;
     cd.dtype = ROTCONV_F32;       // a bf16 plan runs it on widened copies
-    const int crc = rotconv_plan_create(&cd, &p->avg_child);
+    const int crc = rotconv_plan_create_opt(&cd, &p->opt, &p->avg_child);
     if (crc != ROTCONV_OK) {
       delete p;
       return crc;
@@ -232,7 +251,7 @@ int rotconv_plan_create(const rotconv_desc* desc, rotconv_plan** out) {
       cd.W = Wp;
       if (cd.mode == ROTCONV_P4M) cd.angles_deg = nullptr;   // that mode takes no explicit angles
       rotconv_plan* ch = nullptr;
-      const int crc = rotconv_plan_create(&cd, &ch);
+      const int crc = rotconv_plan_create_opt(&cd, &p->opt, &ch);
       if (crc != ROTCONV_OK) {
         delete p;
         return crc;
@@ -352,7 +371,7 @@ static int f32_rotconv_bwd_data(const rotconv_plan* plan, const void* dy, const 
   hipStream_t st = static_cast<hipStream_t>(stream);
   // the unfused gradients of a plan whose fused calls run the register-resident kernels: matrix multiply + scatter
   // if the caller brought the larger workspace that family needs (rotconv_workspace_bytes_unfused), else generic
-  if (p->gs || (ws && ws_bytes >= unfused_ws_inner(p) && unfused_ws_inner(p) > p->ws_inner)) {
+  if (unfused_on_gs(p, ws, ws_bytes)) {
     launch_gs_bwd_data(p, static_cast<const float*>(dy), static_cast<const float*>(w), static_cast<float*>(dx), ws, st);
     return finish();
   }
@@ -370,7 +389,7 @@ static int f32_rotconv_bwd_weight(const rotconv_plan* plan, const void* x, const
   rotconv_plan* p = const_cast<rotconv_plan*>(plan);
   if ((rc = ensure_device_tables(p))) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if (p->gs || (ws && ws_bytes >= unfused_ws_inner(p) && unfused_ws_inner(p) > p->ws_inner)) {
+  if (unfused_on_gs(p, ws, ws_bytes)) {
     launch_gs_bwd_weight(p, static_cast<const float*>(x), static_cast<const float*>(dy), dw, ws, st);
     return finish();
   }
@@ -885,7 +904,9 @@ const char* rotconv_status_string(int status) {
 }
 
 const char* rotconv_plan_kernel_name(const rotconv_plan* plan, int pass) {
-  if (!plan || pass < 0 || pass > 2) return "none";
+  if (!plan || pass < 0 || pass > 4) return "none";
+  if (pass >= 3)      // the unfused gradient calls, given rotconv_workspace_bytes_unfused of scratch
+    return plan->gs || (plan->d.pool_op != ROTCONV_POOL_AVG && gs_wanted(plan)) ? "mfma_gemm_scatter" : "generic";
   if (plan->pad_child && plan->pad_use[pass]) return rotconv_plan_kernel_name(plan->pad_child, pass);
   if (plan->d.dtype == ROTCONV_BF16 && plan->native16[pass]) return "mfma_p4_bf16";
   return plan->fast[pass] ? "mfma_p4" : plan->gs ? "mfma_gemm_scatter" : "generic";

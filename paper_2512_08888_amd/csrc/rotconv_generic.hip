@@ -28,13 +28,23 @@ constexpr int kBwdwTile = 16;
 // Eq. 5 / Sec. III-D / Eq. 17: W^(r)[co,ci,t] = sum_e coef[r,t,e] * w[src[r,t,e]] (src = b*kk + u).
 __global__ __launch_bounds__(256) void k_expand_bank(const float* __restrict__ w, float* __restrict__ wexp,
                                                      const int32_t* __restrict__ src, const float* __restrict__ coef,
-                                                     int R, int slices, int kk, int round16) {
+                                                     const double* __restrict__ coef64, int R, int slices, int kk,
+                                                     int round16) {
   const int total = R * slices * kk;
   const int e = blockIdx.x * 256 + threadIdx.x;
   if (e >= total) return;
   const int t = e % kk;
   const int sl = (e / kk) % slices;
   const int r = e / (kk * slices);
+  if (round16) {      // bf16 plans: the combination in fp64, rounded to fp32 and to bf16 once each
+    double a64 = 0.0;
+    for (int z = 0; z < kMaxNnz; ++z) {
+      const int s = src[(r * kk + t) * kMaxNnz + z];
+      if (s >= 0) a64 += coef64[(r * kk + t) * kMaxNnz + z] * (double)w[((s / kk) * slices + sl) * kk + s % kk];
+    }
+    wexp[e] = bf16_to_f32(f32_to_bf16((float)a64));
+    return;
+  }
   float acc = 0.f;
 #pragma unroll
   for (int z = 0; z < kMaxNnz; ++z) {
@@ -44,7 +54,7 @@ __global__ __launch_bounds__(256) void k_expand_bank(const float* __restrict__ w
       acc += coef[(r * kk + t) * kMaxNnz + z] * w[(b * slices + sl) * kk + u];
     }
   }
-  wexp[e] = round16 ? bf16_to_f32(f32_to_bf16(acc)) : acc;   // bf16 plans keep the rotated banks in bf16 precision
+  wexp[e] = acc;
 }
 
 // Eq. 7 (and Eq. 10 when FUSED).  One thread = one output pixel of one filter
@@ -362,7 +372,7 @@ void launch_expand_bank(const rotconv_plan* p, const float* w, float* wexp, hipS
   const int slices = p->d.Cout * p->d.Cin;
   const int total = p->d.R * slices * p->kk;
   hipLaunchKernelGGL(k_expand_bank, dim3((total + 255) / 256), dim3(256), 0, st, w, wexp, p->dev.exp_src,
-                     p->dev.exp_coef, p->d.R, slices, p->kk, p->d.dtype == ROTCONV_BF16 ? 1 : 0);
+                     p->dev.exp_coef, p->dev.exp_coef64, p->d.R, slices, p->kk, p->d.dtype == ROTCONV_BF16 ? 1 : 0);
 }
 
 void launch_fwd_generic(const rotconv_plan* p, const float* x, const float* wexp, float* y, hipStream_t st) {

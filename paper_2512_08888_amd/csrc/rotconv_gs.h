@@ -8,7 +8,7 @@
 namespace rotconv {
 
 bool gs_wanted(const rotconv_plan* p);       // the family pays off for this plan's shape
-size_t gs_chunk_budget();                    // bytes of products held at once (default 512 MiB)
+size_t gs_chunk_budget(const rotconv_plan* p);                    // bytes of products held at once (default 512 MiB)
 size_t gs_ws_bytes(const rotconv_plan* p);   // packed banks, products / routed gradients of a few images, partial sums
 void launch_gs_fwd(const rotconv_plan* p, const float* x, const float* w, float* y, void* ws, hipStream_t st);
 void launch_gs_pool_fwd(const rotconv_plan* p, const float* x, const float* w, float* ypool, uint8_t* idx, void* ws,

@@ -42,7 +42,8 @@ size_t align256(size_t v) { return (v + 255) / 256 * 256; }
 // (q, co, ci), its k^2 taps read the same base filter.
 __global__ __launch_bounds__(256) void k_gs_pack(const float* __restrict__ w, float* __restrict__ a,
                                                  const int32_t* __restrict__ fq_src, const float* __restrict__ fq_coef,
-                                                 int Q, int Cout, int Cin, int kk, int round16) {
+                                                 const double* __restrict__ fq_coef64, int Q, int Cout, int Cin, int kk,
+                                                 int round16) {
   const int total = Q * Cout * Cin;
   const int e = blockIdx.x * 256 + threadIdx.x;
   if (e >= total) return;
@@ -51,12 +52,21 @@ __global__ __launch_bounds__(256) void k_gs_pack(const float* __restrict__ w, fl
   const float* src = w + ((size_t)co * Cin + ci) * kk;
   for (int u = 0; u < kk; ++u) {
     float acc = 0.f;
+    if (round16) {    // bf16 plans: the combination in fp64, rounded to fp32 and to bf16 once each
+      double a64 = 0.0;
+      for (int z = 0; z < kMaxNnz; ++z) {
+        const int s = fq_src[(q * kk + u) * kMaxNnz + z];
+        if (s >= 0) a64 += fq_coef64[(q * kk + u) * kMaxNnz + z] * (double)src[(size_t)(s / kk) * slices * kk + s % kk];
+      }
+      acc = bf16_to_f32(f32_to_bf16((float)a64));
+    } else {
 #pragma unroll
-    for (int z = 0; z < kMaxNnz; ++z) {
-      const int s = fq_src[(q * kk + u) * kMaxNnz + z];
-      if (s >= 0) acc += fq_coef[(q * kk + u) * kMaxNnz + z] * src[(size_t)(s / kk) * slices * kk + s % kk];
+      for (int z = 0; z < kMaxNnz; ++z) {
+        const int s = fq_src[(q * kk + u) * kMaxNnz + z];
+        if (s >= 0) acc += fq_coef[(q * kk + u) * kMaxNnz + z] * src[(size_t)(s / kk) * slices * kk + s % kk];
+      }
     }
-    a[((size_t)(q * Cout + co) * kk + u) * Cin + ci] = round16 ? bf16_to_f32(f32_to_bf16(acc)) : acc;
+    a[((size_t)(q * Cout + co) * kk + u) * Cin + ci] = acc;
   }
 }
 
@@ -238,6 +248,7 @@ GsLayout gs_layout(const rotconv_plan* p) {
 void pack(const rotconv_plan* p, const float* w, float* a, hipStream_t st) {
   const int total = p->host.Q * p->d.Cout * p->d.Cin;
   hipLaunchKernelGGL(k_gs_pack, dim3((total + 255) / 256), dim3(256), 0, st, w, a, p->dev.fq_src, p->dev.fq_coef,
+                     p->dev.fq_coef64,
                      p->host.Q, p->d.Cout, p->d.Cin, p->kk, p->d.dtype == ROTCONV_BF16 ? 1 : 0);
 }
 
@@ -336,17 +347,15 @@ void backward_weight(const rotconv_plan* p, bool routed, const float* x, const f
 bool gs_wanted(const rotconv_plan* p) {
   if (p->d.pool_op == ROTCONV_POOL_AVG) return false;
   if ((double)p->host.Q * p->d.Cout * p->kk * p->d.H * p->d.W * 4.0 > 3.0e9) return false;   // one image's products
-  if (const char* e = std::getenv("ROTCONV_GS")) return std::atoi(e) != 0;
+  if (p->opt.gs) return p->opt.gs > 0;
   const double flops = 2.0 * p->d.N * p->d.H * p->d.W * p->d.Cin * p->d.Cout * p->kk * p->host.Q;
   return flops >= 1.0e6;
 }
 
-// ROTCONV_GS_CHUNK_MB (read when the plan is created): the budget for the images held at once, in MiB.
-size_t gs_chunk_budget() {
-  if (const char* e = std::getenv("ROTCONV_GS_CHUNK_MB")) {
-    const long mb = std::atol(e);
-    if (mb >= 0) return (size_t)mb << 20;
-  }
+// The budget for the products of the images held at once (plan option gs_chunk_mb).
+size_t gs_chunk_budget(const rotconv_plan* p) {
+  if (p->opt.gs_chunk_mb > 0) return (size_t)p->opt.gs_chunk_mb << 20;
+  if (p->opt.gs_chunk_mb < 0) return 0;       // one image at a time
   return (size_t)512 << 20;
 }
 

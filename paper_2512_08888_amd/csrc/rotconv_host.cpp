@@ -1,6 +1,7 @@
 // Host logic of the rotation-convolution library: descriptor validation and the
-// orientation tables ("the index of the output location ... can be pre-computed
-// for each filter", paper Sec. III-B).  No GPU calls in this file.
+// orientation tables: per (rotation, tap) the output position of every product and the
+// expansion coefficients, computed once per plan (paper Sec. III-B, Eq. 8; Sec. III-D).
+// No GPU calls in this file.
 #include <cmath>
 #include <cstring>
 #include <new>
@@ -113,6 +114,8 @@ int validate_and_build(const rotconv_desc* desc, rotconv_plan** out) {
   if (d.activation != ROTCONV_ACT_NONE && d.activation != ROTCONV_ACT_RELU) return ROTCONV_ERR_UNSUPPORTED;
   if (d.activation == ROTCONV_ACT_RELU && d.pool_op != ROTCONV_POOL_MAX) return ROTCONV_ERR_UNSUPPORTED;
   if (d.k > 15) return ROTCONV_ERR_UNSUPPORTED;
+  // the general kernels put a channel extent into the grid's y dimension and the batch into z (65535 each)
+  if ((long long)d.Cout * d.R > 65535 || d.Cin > 65535 || d.N > 65535) return ROTCONV_ERR_UNSUPPORTED;
   const int Ho = (d.H + 2 * d.pad - d.k) / d.stride + 1, Wo = (d.W + 2 * d.pad - d.k) / d.stride + 1;
   const int kk = d.k * d.k, B = d.mode == ROTCONV_STEERABLE ? 2 : 1;
   // Kernels index every tensor with 32-bit element offsets.
@@ -171,6 +174,7 @@ int validate_and_build(const rotconv_desc* desc, rotconv_plan** out) {
 
   t.fq_src.assign(t.Q * kk * kMaxNnz, -1);
   t.fq_coef.assign(t.Q * kk * kMaxNnz, 0.f);
+  t.fq_coef64.assign(t.Q * kk * kMaxNnz, 0.0);
   for (int q = 0; q < t.Q; ++q)
     for (int u = 0; u < kk; ++u) {
       Nz nz[kMaxNnz];
@@ -178,17 +182,20 @@ int validate_and_build(const rotconv_desc* desc, rotconv_plan** out) {
       for (int e = 0; e < n; ++e) {
         t.fq_src[(q * kk + u) * kMaxNnz + e] = nz[e].src;
         t.fq_coef[(q * kk + u) * kMaxNnz + e] = static_cast<float>(nz[e].coef);
+        t.fq_coef64[(q * kk + u) * kMaxNnz + e] = nz[e].coef;
       }
     }
   // W^(r)[R_s(u)] = F_phi[u]: the row of first-quadrant tap u becomes the row of its turned tap.
   t.exp_src.assign(d.R * kk * kMaxNnz, -1);
   t.exp_coef.assign(d.R * kk * kMaxNnz, 0.f);
+  t.exp_coef64.assign(d.R * kk * kMaxNnz, 0.0);
   for (int r = 0; r < d.R; ++r)
     for (int u = 0; u < kk; ++u) {
       const int dst = t.turn_tap[t.quarter_of_r[r] * kk + u];
       for (int e = 0; e < kMaxNnz; ++e) {
         t.exp_src[(r * kk + dst) * kMaxNnz + e] = t.fq_src[(t.bank_of_r[r] * kk + u) * kMaxNnz + e];
         t.exp_coef[(r * kk + dst) * kMaxNnz + e] = t.fq_coef[(t.bank_of_r[r] * kk + u) * kMaxNnz + e];
+        t.exp_coef64[(r * kk + dst) * kMaxNnz + e] = t.fq_coef64[(t.bank_of_r[r] * kk + u) * kMaxNnz + e];
       }
     }
   // 3x3: the routed-gradient table of the input / weight gradients.  With Delta_r = G [idx == r]

@@ -22,6 +22,9 @@ struct HostTables {
   // Forward expansion, one row per (r, dst tap): up to kMaxNnz (src, coef) pairs, src = -1 unused.
   std::vector<int32_t> exp_src;  // [R*kk*kMaxNnz]
   std::vector<float> exp_coef;   // [R*kk*kMaxNnz]
+  // The same coefficients as computed (fp64): bf16 plans form the banks they multiply with in fp64 and round the
+  // result once, so that the rounding does not depend on fp32 intermediate error.
+  std::vector<double> exp_coef64, fq_coef64;
   // Transposed expansion in CSR form, one row per base element (b, u):
   // dw[b][u] = sum over entries e in row: coef[e] * dW^(r_e)[t_e], col = r*kk + t.
   std::vector<int32_t> tr_ptr;   // [B*kk + 1]
@@ -44,6 +47,8 @@ struct DeviceTables {
   int device = -1;
   int32_t* exp_src = nullptr;
   float* exp_coef = nullptr;
+  double* exp_coef64 = nullptr;  // bf16 plans only (one element otherwise)
+  double* fq_coef64 = nullptr;
   int32_t* tr_ptr = nullptr;
   int32_t* tr_col = nullptr;
   float* tr_coef = nullptr;
@@ -62,6 +67,7 @@ struct DeviceTables {
 
 struct rotconv_plan {
   rotconv_desc d;               // angles_deg is redirected to `angles`
+  rotconv_plan_options opt{};   // tuning switches (all zero: automatic); the plans a plan owns inherit them
   std::vector<double> angles;
   int B = 1, G = 1, ng = 1, Ho = 0, Wo = 0, kk = 0;
   rotconv::HostTables host;

@@ -408,7 +408,8 @@ __global__ __launch_bounds__(256) void k_p4_sum_dx(const float* __restrict__ par
 // base bank(s) -> Q first-quadrant banks laid out [Q][CoutPad][9][CinPad] (zero padded).
 __global__ __launch_bounds__(256) void k_p4_pack_bwd(const float* __restrict__ w, float* __restrict__ wd,
                                                      const int32_t* __restrict__ fq_src,
-                                                     const float* __restrict__ fq_coef, int Q, int CoutPad,
+                                                     const float* __restrict__ fq_coef,
+                                                     const double* __restrict__ fq_coef64, int Q, int CoutPad,
                                                      int CinPad, int Cin, int Cout, int round16, int base) {
   // base: the base bank itself (Q = 1, no expansion)
   // One thread per (bank, filter, channel position): its nine taps read the same 36 bytes of w.
@@ -430,6 +431,13 @@ __global__ __launch_bounds__(256) void k_p4_pack_bwd(const float* __restrict__ w
     float acc = 0.f;
     if (base) {       // q counts the base banks
       acc = in ? src[(size_t)q * slices * 9 + u] : 0.f;
+    } else if (round16) {     // bf16 plans: the combination in fp64, rounded to fp32 and to bf16 once each
+      double a64 = 0.0;
+      for (int z = 0; z < kMaxNnz; ++z) {
+        const int s = fq_src[(q * 9 + u) * kMaxNnz + z];
+        if (in && s >= 0) a64 += fq_coef64[(q * 9 + u) * kMaxNnz + z] * (double)src[(size_t)(s / 9) * slices * 9 + s % 9];
+      }
+      acc = bf16_to_f32(f32_to_bf16((float)a64));
     } else {
 #pragma unroll
       for (int z = 0; z < kMaxNnz; ++z) {
@@ -437,7 +445,7 @@ __global__ __launch_bounds__(256) void k_p4_pack_bwd(const float* __restrict__ w
         if (in && s >= 0) acc += fq_coef[(q * 9 + u) * kMaxNnz + z] * src[(size_t)(s / 9) * slices * 9 + s % 9];
       }
     }
-    dst[(size_t)u * CinPad] = round16 ? bf16_to_f32(f32_to_bf16(acc)) : acc;   // bf16 plans keep the expanded banks in bf16 precision
+    dst[(size_t)u * CinPad] = acc;
   }
 }
 
@@ -448,7 +456,7 @@ __global__ __launch_bounds__(256) void k_p4_pack_bwd(const float* __restrict__ w
 // (the two variants need different amounts of scratch).
 bool p4_bwd_lut_choice(const rotconv_plan* p) {
   if (p->host.lut_bwd.empty() || p->host.Q <= p->B || p->ng != 1 || p->d.R > 32 || p->d.dtype == ROTCONV_BF16) return false;
-  if (const char* e = std::getenv("ROTCONV_BWD_LUT")) return std::atoi(e) != 0;
+  if (p->opt.bwd_lut < 0) return false;
   return true;
 }
 bool p4_bwd_lut(const rotconv_plan* p) { return p->bwd_lut != 0; }
@@ -514,6 +522,7 @@ void launch_p4_pack_bwd(const rotconv_plan* p, const float* w, float* wd, hipStr
   const P4BwdGeom g = p4_bwd_data_geom(p);
   const int total = g.Q * g.CoutPad * g.CinPad;
   hipLaunchKernelGGL(k_p4_pack_bwd, dim3((total + 255) / 256), dim3(256), 0, st, w, wd, p->dev.fq_src, p->dev.fq_coef,
+                     p->dev.fq_coef64,
                      g.Q, g.CoutPad, g.CinPad, g.Cin, g.Cout, p->d.dtype == ROTCONV_BF16 ? 1 : 0, g.lut);
 }
 

@@ -437,7 +437,7 @@ __global__ __launch_bounds__(256) void k_p4_sum_dx_parts(const float* __restrict
 // of the input-gradient kernel: [16-channel block][Q][K-step of 32 filters][9 taps][4 k-groups][16 channels][8 filters].
 __global__ __launch_bounds__(256) void k_p4_pack_bwd_bf16(const uint16_t* __restrict__ w, uint16_t* __restrict__ wt,
                                                           const int32_t* __restrict__ fq_src,
-                                                          const float* __restrict__ fq_coef, int Q, int CIB,
+                                                          const double* __restrict__ fq_coef, int Q, int CIB,
                                                           int CoutPad, int Cin, int Cout) {
   // One thread per (bank, filter, channel): its nine taps read the same 18 bytes of w.
   const int total = CIB * Q * CoutPad * 16;
@@ -456,14 +456,14 @@ __global__ __launch_bounds__(256) void k_p4_pack_bwd_bf16(const uint16_t* __rest
   uint16_t* dst = wt + (size_t)(e / 512) * 4608 + e % 512;      // + u * 512
 #pragma unroll
   for (int u = 0; u < 9; ++u) {
-    float acc = 0.f;
+    double acc = 0.0;     // the combination in fp64, rounded to fp32 and to bf16 once each
 #pragma unroll
     for (int z = 0; z < kMaxNnz; ++z) {
       const int s = fq_src[(q * 9 + u) * kMaxNnz + z];
       if (in && s >= 0)
-        acc += fq_coef[(q * 9 + u) * kMaxNnz + z] * bf16_to_f32(src[(size_t)(s / 9) * slices * 9 + s % 9]);
+        acc += fq_coef[(q * 9 + u) * kMaxNnz + z] * (double)bf16_to_f32(src[(size_t)(s / 9) * slices * 9 + s % 9]);
     }
-    dst[u * 512] = f32_to_bf16(acc);
+    dst[u * 512] = f32_to_bf16((float)acc);
   }
 }
 
@@ -472,7 +472,7 @@ __global__ __launch_bounds__(256) void k_p4_pack_bwd_bf16(const uint16_t* __rest
 // the filter that the A lane (lgA = 2 (jg / 2) + lgB / 2) holds as pair p = 2 (lgB % 2) + jg % 2 of half h.
 __global__ __launch_bounds__(256) void k_p4_pack_bwd_bf16s(const uint16_t* __restrict__ w, uint16_t* __restrict__ wt,
                                                            const int32_t* __restrict__ fq_src,
-                                                           const float* __restrict__ fq_coef, int Q, int CIB,
+                                                           const double* __restrict__ fq_coef, int Q, int CIB,
                                                            int CoutPad, int Cin, int Cout) {
   // One thread per (bank, filter, channel): the nine taps go to three orbits x four positions (the centre four times).
   const int per_step = CHBS / 2;                      // elements of one K-step
@@ -492,14 +492,14 @@ __global__ __launch_bounds__(256) void k_p4_pack_bwd_bf16s(const uint16_t* __res
   float val[9];
 #pragma unroll
   for (int u = 0; u < 9; ++u) {
-    float acc = 0.f;
+    double acc = 0.0;     // the combination in fp64, rounded to fp32 and to bf16 once each
 #pragma unroll
     for (int z = 0; z < kMaxNnz; ++z) {
       const int s = fq_src[(q * 9 + u) * kMaxNnz + z];
       if (in && s >= 0)
-        acc += fq_coef[(q * 9 + u) * kMaxNnz + z] * bf16_to_f32(src[(size_t)(s / 9) * slices * 9 + s % 9]);
+        acc += fq_coef[(q * 9 + u) * kMaxNnz + z] * (double)bf16_to_f32(src[(size_t)(s / 9) * slices * 9 + s % 9]);
     }
-    val[u] = acc;
+    val[u] = (float)acc;
   }
   uint16_t* dst = wt + (size_t)step * per_step + h * 3072 + lgB * 256 + n16 * 16 + jg * 4;    // + o * 1024 + t
 #pragma unroll
@@ -651,12 +651,12 @@ void launch_p4_pack_bwd_bf16(const rotconv_plan* p, const uint16_t* w, uint16_t*
   if (use_sparse(p)) {
     const int total = CIB * p->host.Q * (CoutPad / 32) * 512;
     hipLaunchKernelGGL(k_p4_pack_bwd_bf16s, dim3((total + 255) / 256), dim3(256), 0, st, w, wt, p->dev.fq_src,
-                       p->dev.fq_coef, p->host.Q, CIB, CoutPad, p->d.Cin, p->d.Cout);
+                       p->dev.fq_coef64, p->host.Q, CIB, CoutPad, p->d.Cin, p->d.Cout);
     return;
   }
   const int total = CIB * p->host.Q * CoutPad * 16;
   hipLaunchKernelGGL(k_p4_pack_bwd_bf16, dim3((total + 255) / 256), dim3(256), 0, st, w, wt, p->dev.fq_src,
-                     p->dev.fq_coef, p->host.Q, CIB, CoutPad, p->d.Cin, p->d.Cout);
+                     p->dev.fq_coef64, p->host.Q, CIB, CoutPad, p->d.Cin, p->d.Cout);
 }
 
 // part: scratch of p4_bwd_data_bf16_part_bytes() bytes (unused when that is 0)

@@ -488,7 +488,8 @@ __global__ __launch_bounds__(256) void k_p4_sum_pool(const float* __restrict__ p
 // (zero for padded filters / channels).
 __global__ __launch_bounds__(256) void k_p4_pack_fwd(const float* __restrict__ w, float* __restrict__ wt,
                                                      const int32_t* __restrict__ fq_src,
-                                                     const float* __restrict__ fq_coef, int Q, int CB, int CinPad,
+                                                     const float* __restrict__ fq_coef,
+                                                     const double* __restrict__ fq_coef64, int Q, int CB, int CinPad,
                                                      int Cin, int Cout, int round16, int nq) {
   // nq > 1: the banks are folded into the 16 columns (column n = bank n / (16/nq), filter n % (16/nq)): [CB'][CinPad]...
   // One thread per (bank, filter, channel): its nine taps read the same 36 bytes of w.
@@ -508,12 +509,21 @@ __global__ __launch_bounds__(256) void k_p4_pack_fwd(const float* __restrict__ w
 #pragma unroll
   for (int u = 0; u < 9; ++u) {
     float acc = 0.f;
+    if (round16) {    // bf16 plans: the combination in fp64, rounded to fp32 and to bf16 once each
+      double a64 = 0.0;
+      for (int z = 0; z < kMaxNnz; ++z) {
+        const int s = fq_src[(q * 9 + u) * kMaxNnz + z];
+        if (in && s >= 0) a64 += fq_coef64[(q * 9 + u) * kMaxNnz + z] * (double)src[(size_t)(s / 9) * slices * 9 + s % 9];
+      }
+      acc = bf16_to_f32(f32_to_bf16((float)a64));
+    } else {
 #pragma unroll
-    for (int z = 0; z < kMaxNnz; ++z) {
-      const int s = fq_src[(q * 9 + u) * kMaxNnz + z];
-      if (in && s >= 0) acc += fq_coef[(q * 9 + u) * kMaxNnz + z] * src[(size_t)(s / 9) * slices * 9 + s % 9];
+      for (int z = 0; z < kMaxNnz; ++z) {
+        const int s = fq_src[(q * 9 + u) * kMaxNnz + z];
+        if (in && s >= 0) acc += fq_coef[(q * 9 + u) * kMaxNnz + z] * src[(size_t)(s / 9) * slices * 9 + s % 9];
+      }
     }
-    dst[u * 16] = round16 ? bf16_to_f32(f32_to_bf16(acc)) : acc;   // bf16 plans keep the expanded banks in bf16 precision
+    dst[u * 16] = acc;
   }
 }
 
@@ -608,10 +618,9 @@ int p4_fwd_csplit(const rotconv_plan* p, bool pooled) {
   const int nchunk = CinPad / 32;
   if (nchunk < 2) return 1;
   const bool must = needs_stream(d.Cin) && (d.W & 31);          // no unsplit instance for this shape
-  // Tuning knob, read when the plan is created: ROTCONV_FWD_CSPLIT=1 keeps the contraction whole where an unsplit
-  // instance exists, n >= 2 asks for n parts (rounded so that a part holds at most 7 chunks); unset or 0: the model.
-  int forced = 0;
-  if (const char* e = std::getenv("ROTCONV_FWD_CSPLIT")) forced = std::atoi(e);
+  // Plan option fwd_csplit: 1 keeps the contraction whole where an unsplit instance exists, n >= 2 asks for n parts
+  // (rounded so that a part holds at most 7 chunks); 0: the model.
+  const int forced = p->opt.fwd_csplit;
   if (forced == 1 && !must) return 1;
   if (forced >= 2) {
     const int cper = std::max((nchunk + forced - 1) / forced, (nchunk + 31) / 32);
@@ -748,6 +757,7 @@ void launch_p4_pack_fwd(const rotconv_plan* p, const float* w, float* wt, hipStr
   const int CinPad = cin_pad_f32(p->d.Cin), CB = nq > 1 ? (p->d.Cout * nq + 15) / 16 : (p->d.Cout + 15) / 16;
   const int total = (nq > 1 ? 1 : p->host.Q) * CB * CinPad * 16;
   hipLaunchKernelGGL(k_p4_pack_fwd, dim3((total + 255) / 256), dim3(256), 0, st, w, wt, p->dev.fq_src, p->dev.fq_coef,
+                     p->dev.fq_coef64,
                      p->host.Q, CB, CinPad, p->d.Cin, p->d.Cout, p->d.dtype == ROTCONV_BF16 ? 1 : 0, nq);
 }
 

@@ -476,7 +476,7 @@ __global__ __launch_bounds__(256) void k_p4_combine_bf16(const float* __restrict
 // nq > 1: the banks are folded into the 16 columns (column n = bank n / (16/nq), filter n % (16/nq)): [CB'][chunk]...
 __global__ __launch_bounds__(256) void k_p4_pack_fwd_bf16(const uint16_t* __restrict__ w, uint16_t* __restrict__ wt,
                                                           const int32_t* __restrict__ fq_src,
-                                                          const float* __restrict__ fq_coef, int Q, int CB, int CinPad,
+                                                          const double* __restrict__ fq_coef, int Q, int CB, int CinPad,
                                                           int Cin, int Cout, int nq) {
   // One thread per (bank, filter, channel): its nine taps read the same 18 bytes of w.
   const int total = (nq > 1 ? 1 : Q) * CB * CinPad * 16;
@@ -496,14 +496,14 @@ __global__ __launch_bounds__(256) void k_p4_pack_fwd_bf16(const uint16_t* __rest
   uint16_t* dst = wt + (size_t)(e / 512) * 4608 + e % 512;      // + u * 512
 #pragma unroll
   for (int u = 0; u < 9; ++u) {
-    float acc = 0.f;
+    double acc = 0.0;     // the combination in fp64, rounded to fp32 and to bf16 once each
 #pragma unroll
     for (int z = 0; z < kMaxNnz; ++z) {
       const int s = fq_src[(q * 9 + u) * kMaxNnz + z];
       if (in && s >= 0)
-        acc += fq_coef[(q * 9 + u) * kMaxNnz + z] * bf16_to_f32(src[(size_t)(s / 9) * slices * 9 + s % 9]);
+        acc += fq_coef[(q * 9 + u) * kMaxNnz + z] * (double)bf16_to_f32(src[(size_t)(s / 9) * slices * 9 + s % 9]);
     }
-    dst[u * 512] = f32_to_bf16(acc);
+    dst[u * 512] = f32_to_bf16((float)acc);
   }
 }
 
@@ -588,7 +588,7 @@ void launch_p4_pack_fwd_bf16(const rotconv_plan* p, int nq, const uint16_t* w, u
   const int CinPad = cin_pad(p->d.Cin), CB = nq > 1 ? (p->d.Cout * nq + 15) / 16 : (p->d.Cout + 15) / 16;
   const int total = (nq > 1 ? 1 : p->host.Q) * CB * CinPad * 16;
   hipLaunchKernelGGL(k_p4_pack_fwd_bf16, dim3((total + 255) / 256), dim3(256), 0, st, w, wt, p->dev.fq_src,
-                     p->dev.fq_coef, p->host.Q, CB, CinPad, p->d.Cin, p->d.Cout, nq);
+                     p->dev.fq_coef64, p->host.Q, CB, CinPad, p->d.Cin, p->d.Cout, nq);
 }
 
 // out_val: bf16 [N][C'][H][W] (kOutPooled), bf16 [N][Cout*R][H][W] (kOutUnpooled) or fp32 per-bank

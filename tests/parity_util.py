@@ -51,15 +51,12 @@ def assert_close(got, ref, what, rtol=RTOL):
         assert float(np.linalg.norm(got - ref)) <= rtol * nref, f"{what}: relative L2 error too large"
 
 
-def check_idx(idx_gpu, y_ref, abs_terms, G, what, extra_band=None):
-    """Arg-max protocol on continuous inputs.  y_ref, abs_terms: [N,Cout,R,Ho,Wo] (fp64).  extra_band (same shape or
-    broadcastable): an additional absolute uncertainty of the candidates, added to the near-tie band."""
+def check_idx(idx_gpu, y_ref, abs_terms, G, what):
+    """Arg-max protocol on continuous inputs.  y_ref, abs_terms: [N,Cout,R,Ho,Wo] (fp64)."""
     N, Cout, R, Ho, Wo = y_ref.shape
     ng = R // G
     yg = y_ref.reshape(N, Cout, G, ng, Ho, Wo)
     tau = 64.0 * EPS32 * abs_terms.reshape(N, Cout, G, ng, Ho, Wo).max(axis=2)  # per pooled element
-    if extra_band is not None:
-        tau = tau + np.broadcast_to(extra_band, y_ref.shape).reshape(N, Cout, G, ng, Ho, Wo).max(axis=2)
     best = yg.max(axis=2)
     ig = idx_gpu.reshape(N, Cout, ng, Ho, Wo).astype(np.int64)
     grp = np.arange(ng).reshape(1, 1, ng, 1, 1)
@@ -174,15 +171,16 @@ def oracle_layer(cfg: synth.LayerConfig, x, w, g):
     return dict(y=y, ypool=yp, idx=idx, abs_terms=abs_terms, dx=dx, dw=dw, w_rot=w_rot)
 
 
-def run_fused_parity(cfg: synth.LayerConfig, dyadic: bool = False, label: str = ""):
-    """Fused hot path (pool_fwd, pool_bwd_data, pool_bwd_weight) against the oracle."""
+def run_fused_parity(cfg: synth.LayerConfig, dyadic: bool = False, label: str = "", **plan_over):
+    """Fused hot path (pool_fwd, pool_bwd_data, pool_bwd_weight) against the oracle.  plan_over: keyword arguments of
+    the plan beyond the configuration (e.g. options=dict(gs=1), the tuning switches)."""
     what = label or cfg.name
     if dyadic:
         x, w, g = synth.make_x_dyadic(cfg), synth.make_w_dyadic(cfg), synth.make_g_dyadic(cfg)
     else:
         x, w, g = synth.make_x(cfg), synth.make_w(cfg), synth.make_g(cfg)
     ref = oracle_layer(cfg, x, w, g)
-    L = GpuLayer(cfg, x, w)
+    L = GpuLayer(cfg, x, w, **plan_over)
     yp, idx = L.pool_fwd()
     dx = L.pool_bwd_data(g, ref["idx"])
     dw = L.pool_bwd_weight(g, ref["idx"])

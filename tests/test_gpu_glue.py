@@ -545,18 +545,14 @@ def test_unet_full_size_sampled(cfg, dtype):
         u = A[f"up{lvl}"]
         C = cfg.widths[lvl]
         xin, wu, yu = H(u["x"]).astype(np.float64), params[f"up{lvl}"].astype(np.float64), H(u["y"])
-        pts = _pts(4000 + lvl, 512, (cfg.N, C, yu.shape[2], yu.shape[3]))
-        ref = np.array([xin[n, :, oy // 2, ox // 2] @ wu[:, c, oy % 2, ox % 2] for n, c, oy, ox in pts])
-        act_close(yu[pts[:, 0], pts[:, 1], pts[:, 2], pts[:, 3]], ref, f"up{lvl} fwd samples")
+        # the whole up-convolution and its weight gradient against the glue oracle, every element
+        act_close(yu, uo.upconv2_fwd(xin, wu), f"up{lvl} fwd")
         cat = H(u["cat"])
         assert np.array_equal(cat[:, :C], H(e["y"])) and np.array_equal(cat[:, C:], yu)
         gu = H(u["g"]).astype(np.float64)
-        # dW of the up-convolution: sampled (ci, co) slices summed over all pixels
-        prs = _pts(5000 + lvl, 4, (xin.shape[1], C))
-        dwu = H(net.grads[f"up{lvl}"])
-        ref = np.array([[[np.sum(xin[:, i] * gu[:, o, aa::2, bb::2]) for bb in range(2)] for aa in range(2)]
-                        for i, o in prs])
-        assert_close(np.array([dwu[i, o] for i, o in prs]), ref, f"up{lvl} dW samples")
+        _, dwu_ref = uo.upconv2_bwd(xin, wu, gu)
+        assert_close(H(net.grads[f"up{lvl}"]), dwu_ref, f"up{lvl} dW")
+        del dwu_ref
         _say(f"  {cfg.name} pool{lvl}/up{lvl} ok")
     hd = A["head"]
     logits = H(hd["y"])

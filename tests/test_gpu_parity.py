@@ -135,13 +135,12 @@ def test_unfused_chain_tiny(cfg):
 
 @pytest.mark.parametrize("parts", ["1", "2", "5"])
 @pytest.mark.parametrize("name", ["t_cin256", "t_cin288_r16", "t_csplit_r4", "t_csplit_r16"])
-def test_forward_channel_split_settings(name, parts, monkeypatch):
+def test_forward_channel_split_settings(name, parts):
     """The forward with its channel contraction kept whole (where such an instance exists) and split into a given
     number of parts: fused pooled call and the unpooled call, both against the oracle."""
     cfg = next(c for c in TINY if c.name == name)
-    monkeypatch.setenv("ROTCONV_FWD_CSPLIT", parts)      # read when the plan is created
     say(f"[case] forward channel split {name} parts={parts}")
-    out = pu.run_fused_parity(cfg)
+    out = pu.run_fused_parity(cfg, options=dict(fwd_csplit=int(parts)))
     L, ref = out["layer"], out["ref"]
     y = L.fwd()
     pu.assert_close(y.cpu().numpy().reshape(ref["y"].shape), ref["y"], f"{name} y parts={parts}")
@@ -155,12 +154,11 @@ GS_CASES = [c for c in TINY if c.k != 3 or c.stride != 1 or c.pad != 1 or c.name
 
 
 @pytest.mark.parametrize("cfg", GS_CASES, ids=lambda c: c.name)
-def test_gemm_scatter_family(cfg, monkeypatch):
+def test_gemm_scatter_family(cfg):
     """Layers outside the register-resident kernels (k, stride, pad, pool groups that cut through a bank) on the
     matrix-multiply + scatter family, forced on for every size: fused calls, then the unfused chain with a dense dy."""
-    monkeypatch.setenv("ROTCONV_GS", "1")      # read when the plan is created
     say(f"[case] gemm + scatter {cfg.name}")
-    out = pu.run_fused_parity(cfg)
+    out = pu.run_fused_parity(cfg, options=dict(gs=1))
     L, ref = out["layer"], out["ref"]
     names = [L.plan.kernel_name(i) for i in range(3)]
     assert "mfma_gemm_scatter" in names, names
@@ -176,18 +174,17 @@ def test_gemm_scatter_family(cfg, monkeypatch):
     pu.assert_close(L.bwd_data(dyd_d), dx_ref, f"{cfg.name} dx (dense dy)")
     pu.assert_close(L.bwd_weight(dyd_d), dw_ref, f"{cfg.name} dw (dense dy)")
     if cfg.mode == "exact90":
-        pu.run_fused_parity(cfg, dyadic=True, label=f"{cfg.name} dyadic")
+        pu.run_fused_parity(cfg, dyadic=True, label=f"{cfg.name} dyadic", options=dict(gs=1))
 
 
-def test_gemm_scatter_family_one_image_at_a_time(monkeypatch):
+def test_gemm_scatter_family_one_image_at_a_time():
     """With no room for more than one image's products the family walks the batch image by image (the weight
     gradient accumulates its per-image sums in order)."""
-    monkeypatch.setenv("ROTCONV_GS", "1")
-    monkeypatch.setenv("ROTCONV_GS_CHUNK_MB", "0")
     cfg = next(c for c in GS_CASES if c.name == "t_gs_s2_k7")
     say(f"[case] gemm + scatter, one image per chunk {cfg.name}")
-    pu.run_fused_parity(cfg)
-    pu.run_fused_parity(cfg, dyadic=True, label=f"{cfg.name} dyadic")
+    opts = dict(gs=1, gs_chunk_mb=-1)
+    pu.run_fused_parity(cfg, options=opts)
+    pu.run_fused_parity(cfg, dyadic=True, label=f"{cfg.name} dyadic", options=opts)
 
 
 def test_gemm_scatter_family_is_the_default_for_larger_layers():
@@ -200,23 +197,21 @@ LUT_CASES = ["t_r8bil", "t_r16bil", "t_r3irr", "t_cin288_r16", "t_p4m", "t_p4m_c
 
 
 @pytest.mark.parametrize("name", LUT_CASES)
-def test_gradients_per_bank_kernels(name, monkeypatch):
+def test_gradients_per_bank_kernels(name):
     """Plans with several banks and one pool group per filter take the routed-gradient table by default (the cases
     above run it); here the same layers on the per-bank gradient kernels."""
-    monkeypatch.setenv("ROTCONV_BWD_LUT", "0")
     cfg = next(c for c in TINY if c.name == name)
     say(f"[case] per-bank gradient kernels {name}")
-    pu.run_fused_parity(cfg)
+    pu.run_fused_parity(cfg, options=dict(bwd_lut=-1))
 
 
-def test_config3_reduced_with_and_without_table(monkeypatch):
+def test_config3_reduced_with_and_without_table():
     """Configuration 3's structure (R = 16 bilinear, one pool group) at reduced extent, both gradient variants, and
     the two must agree with each other far inside the oracle tolerance."""
     cfg = dataclasses.replace(synth.C3, name="C3r_lut", N=2, Cin=72, Cout=40, H=24, W=40)
     say(f"[case] {cfg.name}")
     a = pu.run_fused_parity(cfg)
-    monkeypatch.setenv("ROTCONV_BWD_LUT", "0")
-    b = pu.run_fused_parity(cfg)
+    b = pu.run_fused_parity(cfg, options=dict(bwd_lut=-1))
     for k in ("dx", "dw"):
         scale = float(np.abs(a[k]).max())
         assert float(np.abs(a[k].astype(np.float64) - b[k]).max()) <= 2e-5 * scale, k
@@ -230,8 +225,10 @@ def test_unfused_gradients_with_the_larger_workspace(name):
     cfg = next(c for c in TINY if c.name == name)
     say(f"[case] unfused gradients, larger workspace {name}")
     x, w = synth.make_x(cfg), synth.make_w(cfg)
-    L = pu.GpuLayer(cfg, x, w)
-    assert L.plan.workspace_bytes_unfused >= L.plan.workspace_bytes
+    # gs=1: the family is wanted whatever the layer's size (several of these cases lie below the automatic threshold,
+    # and would run the generic kernels with either workspace)
+    L = pu.GpuLayer(cfg, x, w, options=dict(gs=1))
+    assert [L.plan.kernel_name(i) for i in range(5)] == ["mfma_p4"] * 3 + ["mfma_gemm_scatter"] * 2
     dyd = synth.make_dy(cfg)
     ang = None if cfg.angles_deg is None else list(cfg.angles_deg)
     w_rot = orc.expand_bank(w, cfg.R, ang, cfg.mode)
@@ -388,6 +385,24 @@ def full_size_sampled_parity(cfg, n_samples=4096, n_pairs=24):
     assert abs(a - b) <= 1e-5 * scale and abs(a - c) <= 1e-5 * scale, (a, b, c, scale)
     say(f"  homogeneity identities ok: {a:.6e} {b:.6e} {c:.6e}")
     return L
+
+
+@pytest.mark.parametrize("name", ["C2", "C3"])
+def test_full_size_element_by_element(name):
+    """Benchmark configurations 2 and 3 at full size, in the launch configuration bench.py times, every element of
+    the pooled output, the arg-max, dX and dW against the whole oracle (continuous inputs, near-tie protocol)."""
+    cfg = synth.CONFIGS[name]
+    say(f"[case] full-size element by element {cfg}")
+    out = pu.run_fused_parity(cfg)
+    say(f"  kernels: {[out['layer'].plan.kernel_name(i) for i in range(3)]}, {out['near_ties']} accepted near-ties of "
+        f"{out['idx'].size}")
+
+
+def test_config2_full_size_dyadic_bit_exact():
+    """Benchmark configuration 2 at full size on the exact-arithmetic grid: pooled output, arg-max and dX bit for
+    bit (dW within the tolerance: its 2^19-term sums are not exact in fp32)."""
+    say("[case] C2 full size, dyadic")
+    pu.run_fused_parity(synth.C2, dyadic=True, label="C2 dyadic full size")
 
 
 def test_config2_full_size_sampled():

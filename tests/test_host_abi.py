@@ -177,12 +177,20 @@ def test_routed_gradient_table_against_the_oracle_gradients(R, mode, angles):
     assert e.value.status == rc.ERR_UNSUPPORTED
 
 
-def test_kernel_family_selection(monkeypatch):
+def test_extents_the_general_kernels_cannot_launch_are_refused():
+    """Cout * R, Cin or N beyond a grid dimension (65535): refused when the plan is created, not at launch."""
+    for kw in (dict(N=1, Cin=2, Cout=512, R=128), dict(N=1, Cin=65536, Cout=1, R=1), dict(N=65536, Cin=1, Cout=1, R=1)):
+        kw = dict(dict(H=4, W=4, k=3, mode="bilinear"), **kw)
+        with pytest.raises(rc.RotconvError) as e:
+            rc.Plan(**kw)
+        assert e.value.status == rc.ERR_UNSUPPORTED, kw
+    rc.Plan(N=1, Cin=2, H=4, W=4, Cout=512, R=127, mode="bilinear", k=3).close()      # 65024 rows: accepted
+
+
+def test_kernel_family_selection():
     """Which family a plan's fused calls run (host logic only): the register-resident kernels for every 3x3 / stride 1 /
     pad 1 layer whatever its row width, matrix multiply + scatter for other filter sizes and strides once the layer is
-    large enough, the generic kernels for tiny ones; and the tuning variables read at plan creation."""
-    for v in ("ROTCONV_GS", "ROTCONV_FWD_CSPLIT", "ROTCONV_BWD_LUT", "ROTCONV_GS_CHUNK_MB"):
-        monkeypatch.delenv(v, raising=False)
+    large enough, the generic kernels for tiny ones; and the tuning switches of rotconv_plan_create_opt."""
     names = lambda p: [p.kernel_name(i) for i in range(3)]
     assert names(rc.Plan(8, 64, 256, 256, 64, k=3, R=4)) == ["mfma_p4"] * 3
     assert names(rc.Plan(2, 16, 33, 255, 8, k=3, R=4)) == ["mfma_p4"] * 3          # odd rows: padded-row plan
@@ -194,24 +202,24 @@ def test_kernel_family_selection(monkeypatch):
     # a pool group that cuts through a bank: the forward pools an unpooled map, the gradients take the other family
     p = rc.Plan(4, 32, 64, 64, 32, k=3, R=4, pool_group=2)
     assert names(p) == ["mfma_p4", "mfma_gemm_scatter", "mfma_gemm_scatter"]
-    monkeypatch.setenv("ROTCONV_GS", "0")
-    assert names(rc.Plan(4, 32, 64, 64, 32, k=5, pad=2, R=8, mode="steerable")) == ["generic"] * 3
-    monkeypatch.setenv("ROTCONV_GS", "1")
-    assert names(rc.Plan(1, 2, 9, 8, 3, k=5, pad=2, R=4)) == ["mfma_gemm_scatter"] * 3
-    monkeypatch.delenv("ROTCONV_GS")
+    assert names(rc.Plan(4, 32, 64, 64, 32, k=5, pad=2, R=8, mode="steerable", options=dict(gs=-1))) == ["generic"] * 3
+    assert names(rc.Plan(1, 2, 9, 8, 3, k=5, pad=2, R=4, options=dict(gs=1))) == ["mfma_gemm_scatter"] * 3
     # the per-bank gradient kernels need more scratch than the table variant; both fit what the plan asks for
     big = dict(k=3, R=16, mode="bilinear")
     ws_lut = rc.Plan(2, 256, 64, 64, 256, **big).workspace_bytes
-    monkeypatch.setenv("ROTCONV_BWD_LUT", "0")
-    ws_bank = rc.Plan(2, 256, 64, 64, 256, **big).workspace_bytes
+    ws_bank = rc.Plan(2, 256, 64, 64, 256, options=dict(bwd_lut=-1), **big).workspace_bytes
     assert 0 < ws_lut <= ws_bank
     # a forced channel split needs one unpooled part per split
-    monkeypatch.delenv("ROTCONV_BWD_LUT")
-    monkeypatch.setenv("ROTCONV_FWD_CSPLIT", "1")
-    ws1 = rc.Plan(1, 256, 32, 32, 64, k=3, R=4).workspace_bytes
-    monkeypatch.setenv("ROTCONV_FWD_CSPLIT", "8")
-    ws8 = rc.Plan(1, 256, 32, 32, 64, k=3, R=4).workspace_bytes
+    ws1 = rc.Plan(1, 256, 32, 32, 64, k=3, R=4, options=dict(fwd_csplit=1)).workspace_bytes
+    ws8 = rc.Plan(1, 256, 32, 32, 64, k=3, R=4, options=dict(fwd_csplit=8)).workspace_bytes
     assert ws8 >= ws1 >= 8 * 64 * 4 * 32 * 32 * 4      # eight parts of N * Cout * R * H * W floats fit either way
+    # a non-zero reserved field is refused
+    import ctypes
+    bad = rc.PlanOptions()
+    bad.reserved[1] = 7
+    h = ctypes.c_void_p()
+    d = rc.Plan(1, 2, 9, 8, 3).desc
+    assert rc.lib().rotconv_plan_create_opt(ctypes.byref(d), ctypes.byref(bad), ctypes.byref(h)) == rc.ERR_UNSUPPORTED
 
 
 def test_p4m_tables_reproduce_the_oracle_banks():

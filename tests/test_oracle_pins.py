@@ -395,6 +395,43 @@ def test_sampled_backward_helpers_match_full():
         np.testing.assert_allclose(got[t], dwr[:, co, ci], rtol=1e-13, atol=1e-13)
 
 
+def test_sampled_weight_gradient_routes_nothing_for_indices_outside_the_group():
+    """Eq. 12's indicator: an idx that names no member of its pool group (255 = the fused ReLU's "no orientation",
+    an index >= R, or an index of another group) contributes nothing.  Pinned against the two-step definition
+    orient_maxpool_bwd -> rotconv_bwd_weight, whose Delta is built by the plain comparison idx == r, and against the
+    same gradient with those positions' upstream gradient set to zero."""
+    x = rnd(2, 3, 6, 5)
+    w = rnd(1, 4, 3, 3, 3)
+    R, G = 8, 4
+    ng = R // G
+    _, yp, idx, _ = orc.layer_fwd(x, w, R, None, "bilinear", 1, 1, G)
+    g = rnd(*yp.shape)
+    bad = idx.copy()
+    flat = bad.reshape(-1)
+    pos = RNG.permutation(flat.size)[: flat.size // 2]
+    third = len(pos) // 3
+    flat[pos[:third]] = 255                                   # no orientation at all
+    flat[pos[third:2 * third]] = R + 3                        # beyond the orientation set
+    chan_grp = (np.arange(yp.shape[1]) % ng).reshape(1, -1, 1, 1) * np.ones(idx.shape, dtype=np.int64)
+    wrong = (idx.astype(np.int64) + 1) % R                    # a valid orientation, but of the other group
+    assert np.all(wrong % ng != chan_grp)
+    flat[pos[2 * third:]] = wrong.reshape(-1)[pos[2 * third:]]
+    routed = np.zeros(idx.shape, dtype=bool)
+    routed.reshape(-1)[pos] = True
+    assert np.all((bad[routed] >= R) | (bad[routed] % ng != chan_grp[routed]))
+    pairs = np.array([[0, 0], [3, 2], [1, 1], [2, 0]], dtype=np.int32)
+    got = orc.rotconv_pool_bwd_weight_at(x, g, bad, pairs, R, 3, G, 1, 1)
+    dwr = orc.rotconv_bwd_weight(x, orc.orient_maxpool_bwd(g, bad, R, G), 3, 1, 1)
+    g0 = np.where(routed, 0.0, g)
+    dwr0 = orc.rotconv_bwd_weight(x, orc.orient_maxpool_bwd(g0, idx, R, G), 3, 1, 1)
+    for t, (co, ci) in enumerate(pairs):
+        np.testing.assert_allclose(got[t], dwr[:, co, ci], rtol=1e-13, atol=1e-13)
+        np.testing.assert_allclose(got[t], dwr0[:, co, ci], rtol=1e-13, atol=1e-13)
+    # and the branch matters: with the valid idx the result is a different one
+    full = orc.rotconv_pool_bwd_weight_at(x, g, idx, pairs, R, 3, G, 1, 1)
+    assert np.abs(full - got).max() > 1e-3
+
+
 # ---------------------------------------------------------------- average orientation pooling (Eq. 9, Eq. 11)
 
 @pytest.mark.parametrize("R,mode,G,stride,pad,k", [
