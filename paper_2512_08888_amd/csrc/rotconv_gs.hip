@@ -343,7 +343,7 @@ void backward_weight(const rotconv_plan* p, bool routed, const float* x, const f
 
 // Worth it from about a megaflop of products per call (measured: 16 x 16 maps with 8 -> 8 channels and 5 x 5 filters
 // already break even); below that the single generic kernel wins on launches.
-// ROTCONV_GS=0 / 1 (read when the plan is created) switches the family off / on for every shape it can run.
+// Plan option gs = -1 / 1 switches the family off / on for every shape it can run.
 bool gs_wanted(const rotconv_plan* p) {
   if (p->d.pool_op == ROTCONV_POOL_AVG) return false;
   if ((double)p->host.Q * p->d.Cout * p->kk * p->d.H * p->d.W * 4.0 > 3.0e9) return false;   // one image's products

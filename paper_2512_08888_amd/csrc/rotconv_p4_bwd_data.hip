@@ -452,7 +452,7 @@ __global__ __launch_bounds__(256) void k_p4_pack_bwd(const float* __restrict__ w
 }  // namespace
 
 // The fp32 gradients run over the base bank(s) through the routed-gradient table: one pool group per filter, more
-// banks than base banks (ROTCONV_BWD_LUT=0 keeps the per-bank kernels).  Decided once, when the plan is created
+// banks than base banks (plan option bwd_lut = -1 keeps the per-bank kernels).  Decided once, when the plan is created
 // (the two variants need different amounts of scratch).
 bool p4_bwd_lut_choice(const rotconv_plan* p) {
   if (p->host.lut_bwd.empty() || p->host.Q <= p->B || p->ng != 1 || p->d.R > 32 || p->d.dtype == ROTCONV_BF16) return false;
