@@ -247,8 +247,8 @@ int rotconv_steerable_reg(const float* w, int32_t Cout, int32_t per, float lambd
 
 /* Static, never NULL. */
 const char* rotconv_status_string(int status);
-/* Name of the kernel family a call of the given kind on this plan uses ("generic", "mfma_p4", "mfma_p4_bf16",
- * "mfma_gemm_scatter").  pass: 0 / 1 / 2 = the fused calls rotconv_pool_fwd / _bwd_data / _bwd_weight (and
+/* Name of the kernel family a call of the given kind on this plan uses ("generic", "mfma_p4", "mfma_p4_base" (the
+ * pooled forward on products of the base bank), "mfma_p4_bf16", "mfma_gemm_scatter").  pass: 0 / 1 / 2 = the fused calls rotconv_pool_fwd / _bwd_data / _bwd_weight (and
  * rotconv_fwd); 3 / 4 = the unfused gradient calls rotconv_bwd_data / rotconv_bwd_weight when given
  * rotconv_workspace_bytes_unfused of scratch (with less they run "generic"). */
 const char* rotconv_plan_kernel_name(const rotconv_plan* plan, int pass);

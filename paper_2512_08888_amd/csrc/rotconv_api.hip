@@ -42,7 +42,8 @@ int ensure_device_tables(rotconv_plan* p) {
                   upload(t.fq_coef, &d.fq_coef) && upload(t.fqt_ptr, &d.fqt_ptr) && upload(t.fqt_col, &d.fqt_col) &&
                   upload(t.fqt_coef, &d.fqt_coef) && upload(p->rot_of, &d.rot_of) && upload(rq, &d.rq_of_r) &&
                   upload(t.turn_tap, &d.turn_tap) && upload(t.lut_bwd, &d.lut_bwd) &&
-                  upload(bf ? t.exp_coef64 : none64, &d.exp_coef64) && upload(bf ? t.fq_coef64 : none64, &d.fq_coef64);
+                  upload(bf ? t.exp_coef64 : none64, &d.exp_coef64) && upload(bf ? t.fq_coef64 : none64, &d.fq_coef64) &&
+                  upload(t.fwd_base_coef, &d.fwd_base_coef);
   if (!ok) {
     (void)hipGetLastError();
     free_device_tables(p);
@@ -63,7 +64,7 @@ void free_device_tables(rotconv_plan* p) {
   DeviceTables& d = p->dev;
   void* ptrs[] = {d.exp_src, d.exp_coef, d.tr_ptr, d.tr_col, d.tr_coef, d.fq_src,
                   d.fq_coef, d.fqt_ptr, d.fqt_col, d.fqt_coef, d.rot_of, d.rq_of_r, d.turn_tap, d.lut_bwd,
-                  d.exp_coef64, d.fq_coef64};
+                  d.exp_coef64, d.fq_coef64, d.fwd_base_coef};
   for (void* q : ptrs)
     if (q) (void)hipFree(q);
   d = DeviceTables();
@@ -192,6 +193,13 @@ int rotconv_plan_create_opt(const rotconv_desc* desc, const rotconv_plan_options
     p->fwd_csplit[1] = p4_fwd_csplit(p, true);
   }
   if (p->fast[0]) p->ws_bytes = std::max(p->ws_bytes, fwd_fast_ws_bytes(p));
+  // one pool group over several banks: products of the base bank only.  Maps below 32 x 32 pixels with deep inputs
+  // keep the channel split of the per-bank kernel where its cost model chose one (few workgroups either way).
+  if (p->fast[0] && p4_fwd_base_supported(p) && (p->fwd_csplit[1] == 1 || (long)p->d.H * p->d.W >= 1024)) {
+    p->fwd_base = 1;
+    p->fwd_csplit[1] = 1;
+    p->fwd_base_cls = p4_fwd_base_classify(p, &p->host.fwd_base_coef);
+  }
   p->bwd_lut = p4_bwd_lut_choice(p) ? 1 : 0;
   p->fast[1] = p4_bwd_data_supported(p) ? 1 : 0;
   if (p->fast[1])
@@ -467,6 +475,11 @@ static int f32_rotconv_pool_fwd(const rotconv_plan* plan, const void* x, const v
       launch_p4_pack_fwd(p, static_cast<const float*>(w), wt, st);
       launch_p4_fwd(p, kOutUnpooled, static_cast<const float*>(x), wt, part, nullptr, st, 1, cs);
       launch_p4_sum_pool(p, part, cs, static_cast<float*>(ypool), idx, st);
+      return finish();
+    }
+    if (p->fwd_base) {     // the pool group spans all banks: products of the base bank, banks combined in the kernel
+      launch_p4_pack_base(p, static_cast<const float*>(w), wt, st);
+      launch_p4_fwd_base(p, static_cast<const float*>(x), wt, static_cast<float*>(ypool), idx, st);
       return finish();
     }
     const int nq = mode == kOutPartial ? p4_fwd_fold(p) : 1;
@@ -909,6 +922,7 @@ const char* rotconv_plan_kernel_name(const rotconv_plan* plan, int pass) {
     return plan->gs || (plan->d.pool_op != ROTCONV_POOL_AVG && gs_wanted(plan)) ? "mfma_gemm_scatter" : "generic";
   if (plan->pad_child && plan->pad_use[pass]) return rotconv_plan_kernel_name(plan->pad_child, pass);
   if (plan->d.dtype == ROTCONV_BF16 && plan->native16[pass]) return "mfma_p4_bf16";
+  if (pass == 0 && plan->fast[0] && plan->fwd_base) return "mfma_p4_base";   // the pooled forward; rotconv_fwd: mfma_p4
   return plan->fast[pass] ? "mfma_p4" : plan->gs ? "mfma_gemm_scatter" : "generic";
 }
 

@@ -41,6 +41,9 @@ struct HostTables {
   std::vector<int32_t> turn_tap;  // [4*kk]
   // 3x3 plans: [B base banks][9 neighbour offsets][R + 1][12] routed-gradient coefficients (see rotconv_host.cpp)
   std::vector<float> lut_bwd;
+  // forward on base products: [Q][9 taps][4] coefficients of a bank's products in terms of the base products, in
+  // the order of the compiled source pattern (empty unless the plan uses that kernel)
+  std::vector<float> fwd_base_coef;
 };
 
 struct DeviceTables {
@@ -61,6 +64,7 @@ struct DeviceTables {
   int32_t* rq_of_r = nullptr;   // [R] bank * 4 + quarter turn of orientation r
   int32_t* turn_tap = nullptr;  // [4*kk] tap position of base tap u after s quarter turns
   float* lut_bwd = nullptr;     // HostTables::lut_bwd (one element if the plan has none)
+  float* fwd_base_coef = nullptr;   // HostTables::fwd_base_coef (one element if the plan has none)
 };
 
 }  // namespace rotconv
@@ -85,6 +89,8 @@ struct rotconv_plan {
   size_t gs_chunk_bytes = (size_t)512 << 20;   // that family holds the products of as many images as fit this
   int gs = 0;                   // passes without a register-resident kernel run the matrix-multiply + scatter family
   int bwd_lut = 0;              // fast fp32 gradients: routed-gradient table, contraction over the base bank only
+  int fwd_base = 0;             // fast fp32 pooled forward: products of the base bank only, banks combined on the vector ALU
+  int fwd_base_cls = 0;         // its banks' classes (two bits per bank)
   int fwd_csplit[2] = {1, 1};   // fast forward: channel splits for the unpooled / the pooled output (1: none)
   // Average pooling (Eq. 9 / Eq. 11): the fused calls run one ordinary convolution (this R = 1 plan with
   // Cout * R/G filters) on the group-averaged bank.  Owned by the parent.

@@ -46,6 +46,14 @@ void launch_p4_fwd(const rotconv_plan* p, int out_mode, const float* x, const fl
 void launch_p4_combine(const rotconv_plan* p, const float* pv, const uint8_t* pi, float* ypool, uint8_t* idx,
                        hipStream_t st);   // applies the plan's fused activation
 
+// pooled forward on base products (pool group spanning several banks): one conv-equivalent on the matrix cores
+int p4_fwd_base_classify(const rotconv_plan* p, std::vector<float>* coef);   // bank classes (-1: none) and coefficients
+bool p4_fwd_base_supported(const rotconv_plan* p);
+size_t p4_fwd_base_pack_floats(const rotconv_plan* p);
+void launch_p4_pack_base(const rotconv_plan* p, const float* w, float* wt, hipStream_t st);
+void launch_p4_fwd_base(const rotconv_plan* p, const float* x, const float* wt, float* ypool, uint8_t* idx,
+                        hipStream_t st);
+
 // forward on bfloat16 tensors (bf16 matrix cores, fp32 accumulation); out_val is bf16 for the pooled and
 // unpooled modes and fp32 for the per-bank candidates
 bool p4_fwd_bf16_supported(const rotconv_plan* p);

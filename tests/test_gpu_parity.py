@@ -217,6 +217,72 @@ def test_config3_reduced_with_and_without_table():
         assert float(np.abs(a[k].astype(np.float64) - b[k]).max()) <= 2e-5 * scale, k
 
 
+# Layers whose pool group spans several banks: the pooled forward multiplies with the base bank only and forms the
+# banks' products on the vector ALU ("mfma_p4_base"); the TINY cases of that kind run it by default.  More of its
+# branches: three row segments, a streamed filter block, a first layer (at most four channels), rows that are not
+# a multiple of four or end inside a wave, several bands per workgroup, fused ReLU.
+BASE_CASES = [
+    LC("t_base_w288", N=1, Cin=8, H=7, W=288, Cout=20, R=16, mode="bilinear", seed=71),
+    LC("t_base_w544_p4m", N=1, Cin=8, H=5, W=544, Cout=16, R=8, mode="p4m", seed=72),
+    LC("t_base_stream", N=2, Cin=288, H=40, W=64, Cout=64, R=16, mode="bilinear", x_dist="absnormal", seed=73),
+    LC("t_base_stream_r8", N=4, Cin=320, H=34, W=32, Cout=64, R=8, mode="bilinear", x_dist="absnormal", seed=74),
+    LC("t_base_cin3", N=2, Cin=3, H=33, W=64, Cout=24, R=16, mode="bilinear", seed=75),
+    LC("t_base_cin3_w46", N=1, Cin=3, H=9, W=46, Cout=8, R=8, mode="bilinear", seed=76),
+    LC("t_base_w18", N=2, Cin=40, H=21, W=18, Cout=17, R=16, mode="bilinear", seed=77),
+    LC("t_base_w32_bands", N=1, Cin=64, H=70, W=32, Cout=32, R=16, mode="bilinear", x_dist="absnormal", seed=78),
+    LC("t_base_w100", N=1, Cin=33, H=12, W=100, Cout=16, R=8, mode="p4m", seed=79),
+]
+
+
+@pytest.mark.parametrize("cfg", BASE_CASES, ids=lambda c: c.name)
+def test_forward_on_base_products(cfg):
+    say(f"[case] forward on base products {cfg.name}")
+    out = pu.run_fused_parity(cfg)
+    assert out["layer"].plan.kernel_name(0) == "mfma_p4_base"
+    if cfg.mode == "p4m":       # the mirror image is a tap permutation: exact arithmetic, ties across the two banks
+        pu.run_fused_parity(cfg, dyadic=True, label=f"{cfg.name} dyadic")
+
+
+def test_forward_on_base_products_with_fused_relu():
+    """The fused ReLU of that kernel: pooled values clamped at 0, idx 255 where the pooled value is not positive."""
+    cfg = LC("t_base_relu", N=1, Cin=16, H=20, W=48, Cout=16, R=16, mode="bilinear", x_dist="normal", seed=80)
+    say(f"[case] forward on base products, fused ReLU {cfg.name}")
+    x, w = synth.make_x(cfg), synth.make_w(cfg)
+    plain = pu.GpuLayer(cfg, x, w)
+    relu = pu.GpuLayer(cfg, x, w, relu=True)
+    assert relu.plan.kernel_name(0) == "mfma_p4_base"
+    yp, idx = plain.pool_fwd()
+    yr, ir = relu.pool_fwd()
+    dead = ~(yp > 0)
+    assert dead.any() and (~dead).any()
+    assert np.array_equal(yr, np.where(dead, np.float32(0), yp))
+    assert np.array_equal(ir, np.where(dead, np.uint8(255), idx))
+
+
+@pytest.mark.parametrize("name", ["t_r8bil", "t_r16bil", "t_p4m", "t_p4m_c40", "t_ksplit_q2", "t_padw_r16",
+                                  "t_ksplit_small_q2"])
+def test_forward_per_bank_kernels(name):
+    """The same layers with the forward kept on the per-bank kernels (plan option fwd_base = -1: the banks folded
+    into a wave's filter columns, or per-bank candidates through memory)."""
+    cfg = next(c for c in TINY if c.name == name)
+    say(f"[case] forward per bank {name}")
+    out = pu.run_fused_parity(cfg, options=dict(fwd_base=-1))
+    assert out["layer"].plan.kernel_name(0) == "mfma_p4"
+
+
+def test_config3_reduced_forward_both_ways():
+    """Configuration 3's structure at reduced extent: the forward on base products and on the per-bank kernel must
+    agree with each other far inside the oracle tolerance (and each with the oracle)."""
+    cfg = dataclasses.replace(synth.C3, name="C3r_fwd", N=2, Cin=72, Cout=40, H=32, W=48)
+    say(f"[case] {cfg.name}")
+    a = pu.run_fused_parity(cfg)
+    b = pu.run_fused_parity(cfg, options=dict(fwd_base=-1))
+    assert a["layer"].plan.kernel_name(0) == "mfma_p4_base" and b["layer"].plan.kernel_name(0) == "mfma_p4"
+    scale = float(np.abs(a["yp"]).max())
+    diff = float(np.abs(a["yp"].astype(np.float64) - b["yp"]).max())
+    assert diff <= 1e-4 * scale, (diff, scale)
+
+
 @pytest.mark.parametrize("name", ["t_r4", "t_w96", "t_r16bil", "t_p4m_c40", "t_cin256", "t_padw_g2"])
 def test_unfused_gradients_with_the_larger_workspace(name):
     """rotconv_bwd_data / rotconv_bwd_weight (dense dy) of plans whose fused calls run the register-resident kernels:
@@ -228,7 +294,8 @@ def test_unfused_gradients_with_the_larger_workspace(name):
     # gs=1: the family is wanted whatever the layer's size (several of these cases lie below the automatic threshold,
     # and would run the generic kernels with either workspace)
     L = pu.GpuLayer(cfg, x, w, options=dict(gs=1))
-    assert [L.plan.kernel_name(i) for i in range(5)] == ["mfma_p4"] * 3 + ["mfma_gemm_scatter"] * 2
+    names = [L.plan.kernel_name(i) for i in range(5)]
+    assert names[0] in ("mfma_p4", "mfma_p4_base") and names[1:] == ["mfma_p4"] * 2 + ["mfma_gemm_scatter"] * 2, names
     dyd = synth.make_dy(cfg)
     ang = None if cfg.angles_deg is None else list(cfg.angles_deg)
     w_rot = orc.expand_bank(w, cfg.R, ang, cfg.mode)

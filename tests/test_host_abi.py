@@ -194,7 +194,9 @@ def test_kernel_family_selection():
     names = lambda p: [p.kernel_name(i) for i in range(3)]
     assert names(rc.Plan(8, 64, 256, 256, 64, k=3, R=4)) == ["mfma_p4"] * 3
     assert names(rc.Plan(2, 16, 33, 255, 8, k=3, R=4)) == ["mfma_p4"] * 3          # odd rows: padded-row plan
-    assert names(rc.Plan(2, 16, 33, 270, 8, k=3, R=16, mode="bilinear")) == ["mfma_p4"] * 3
+    # one pool group over several banks: the pooled forward multiplies with the base bank only
+    assert names(rc.Plan(2, 16, 33, 270, 8, k=3, R=16, mode="bilinear")) == ["mfma_p4_base", "mfma_p4", "mfma_p4"]
+    assert names(rc.Plan(2, 16, 33, 270, 8, k=3, R=16, mode="bilinear", options=dict(fwd_base=-1))) == ["mfma_p4"] * 3
     assert names(rc.Plan(1, 1024, 4, 4, 256, k=3, R=1)) == ["mfma_p4"] * 3           # small map, deep input
     assert names(rc.Plan(4, 32, 64, 64, 32, k=5, pad=2, R=8, mode="steerable")) == ["mfma_gemm_scatter"] * 3
     assert names(rc.Plan(4, 32, 64, 64, 32, k=3, stride=2, R=4)) == ["mfma_gemm_scatter"] * 3
