@@ -245,8 +245,26 @@ int rotconv_pool_bwd_weight(const rotconv_plan* plan, const void* x, const void*
 int rotconv_steerable_reg(const float* w, int32_t Cout, int32_t per, float lambda_mag, float lambda_orth, float eps,
                           float* losses, float* dw, int32_t accumulate, void* ws, size_t ws_bytes, void* stream);
 
+/* ---- measuring kernels (for the benchmark's measured-peak figures; not on the hot path) ------------------
+ * rotconv_diag_mfma: 2048 workgroups of four waves, each wave n_iter rounds of eight independent matrix
+ *   instructions on registers only (dtype ROTCONV_F32: 16x16x4 fp32; ROTCONV_BF16: 16x16x32 bf16 with fp32
+ *   accumulation).  sink DEVICE, rotconv_diag_mfma_sink_bytes() bytes, receives one float per lane.  *flops (HOST,
+ *   may be NULL) receives the floating-point operations the launch executes; time it with events on `stream`.
+ * rotconv_diag_copy: dst[i] = src[i] for bytes / 16 float4 elements (dst, src DEVICE, 16-byte aligned, bytes a
+ *   multiple of 16): 2 * bytes of HBM traffic. */
+size_t rotconv_diag_mfma_sink_bytes(void);
+int rotconv_diag_mfma(int dtype, int n_iter, float* sink, void* stream, double* flops);
+int rotconv_diag_copy(void* dst, const void* src, size_t bytes, void* stream);
+
 /* Static, never NULL. */
 const char* rotconv_status_string(int status);
+/* Matrix work a fused call executes, in conv-equivalents (one conv-equivalent = N*Ho*Wo*Cin*Cout*k*k multiply-adds,
+ * an ordinary convolution of the layer's shape): pass 0 rotconv_pool_fwd, 1 rotconv_pool_bwd_data, 2
+ * rotconv_pool_bwd_weight.  The method's count (Eq. 8) is Q, the number of first-quadrant banks; kernels that fold
+ * the banks into the base bank execute fewer (1 per base bank), kernels that multiply every quarter turn on its own
+ * execute more (up to R); the structured-sparse bf16 instances count at the dense rate they issue at (R / 2).
+ * For reporting (the benchmark's executed-work roofline). */
+double rotconv_plan_conv_equivalents(const rotconv_plan* plan, int pass);
 /* Name of the kernel family a call of the given kind on this plan uses ("generic", "mfma_p4", "mfma_p4_base" (the
  * pooled forward on products of the base bank), "mfma_p4_bf16", "mfma_gemm_scatter").  pass: 0 / 1 / 2 = the fused calls rotconv_pool_fwd / _bwd_data / _bwd_weight (and
  * rotconv_fwd); 3 / 4 = the unfused gradient calls rotconv_bwd_data / rotconv_bwd_weight when given

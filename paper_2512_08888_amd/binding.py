@@ -25,7 +25,8 @@ EXPORTS = [
     "rotconv_workspace_bytes_unfused",
     "rotconv_fwd", "rotconv_bwd_data", "rotconv_bwd_weight", "orient_maxpool_fwd", "orient_maxpool_bwd",
     "rotconv_pool_fwd", "rotconv_pool_bwd_data", "rotconv_pool_bwd_weight", "rotconv_pool_fwd_static",
-    "rotconv_status_string", "rotconv_plan_kernel_name", "rotconv_steerable_reg",
+    "rotconv_status_string", "rotconv_plan_kernel_name", "rotconv_steerable_reg", "rotconv_plan_conv_equivalents",
+    "rotconv_diag_mfma_sink_bytes", "rotconv_diag_mfma", "rotconv_diag_copy",
 ]
 
 # include/unetglue.h
@@ -102,6 +103,11 @@ def lib():
         L.rotconv_status_string.restype = ctypes.c_char_p
         L.rotconv_plan_kernel_name.argtypes = [vp, ctypes.c_int]
         L.rotconv_plan_kernel_name.restype = ctypes.c_char_p
+        L.rotconv_diag_mfma_sink_bytes.restype = sz
+        L.rotconv_diag_mfma.argtypes = [ctypes.c_int, ctypes.c_int, vp, vp, ctypes.POINTER(ctypes.c_double)]
+        L.rotconv_diag_copy.argtypes = [vp, vp, sz, vp]
+        L.rotconv_plan_conv_equivalents.argtypes = [vp, ctypes.c_int]
+        L.rotconv_plan_conv_equivalents.restype = ctypes.c_double
         L.rotconv_steerable_reg.argtypes = [vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_float, ctypes.c_float,
                                             ctypes.c_float, vp, vp, ctypes.c_int32, vp, sz, vp]
         ci = ctypes.c_int
@@ -230,6 +236,10 @@ class Plan:
                "rotconv_plan_routed_table")
         return T
 
+    def conv_equivalents(self, which: int) -> float:
+        """Conv-equivalents of matrix work fused call `which` (0 fwd, 1 bwd_data, 2 bwd_weight) executes."""
+        return float(lib().rotconv_plan_conv_equivalents(self._h, which))
+
     def kernel_name(self, which: int) -> str:
         return lib().rotconv_plan_kernel_name(self._h, which).decode()
 
@@ -293,6 +303,21 @@ def rotconv_pool_bwd_weight(plan: Plan, x, gpool, idx, dw, ws=None):
     p, n = _ws_args(plan, ws)
     _check(lib().rotconv_pool_bwd_weight(plan.handle, _ptr(x), _ptr(gpool), _ptr(idx), _ptr(dw), p, n, _stream()),
            "rotconv_pool_bwd_weight")
+
+
+def rotconv_diag_mfma(dtype: int, n_iter: int, sink) -> float:
+    """Enqueues the matrix-instruction loop; returns the floating-point operations it executes."""
+    fl = ctypes.c_double()
+    _check(lib().rotconv_diag_mfma(int(dtype), int(n_iter), _ptr(sink), _stream(), ctypes.byref(fl)), "rotconv_diag_mfma")
+    return fl.value
+
+
+def rotconv_diag_mfma_sink_bytes() -> int:
+    return int(lib().rotconv_diag_mfma_sink_bytes())
+
+
+def rotconv_diag_copy(dst, src):
+    _check(lib().rotconv_diag_copy(_ptr(dst), _ptr(src), src.numel() * src.element_size(), _stream()), "rotconv_diag_copy")
 
 
 def rotconv_steerable_reg(w, lambda_mag, lambda_orth, eps, losses, dw=None, accumulate=False, ws=None):

@@ -916,6 +916,26 @@ const char* rotconv_status_string(int status) {
   }
 }
 
+double rotconv_plan_conv_equivalents(const rotconv_plan* plan, int pass) {
+  if (!plan || pass < 0 || pass > 2) return 0.0;
+  if (plan->pad_child && plan->pad_use[pass]) return rotconv_plan_conv_equivalents(plan->pad_child, pass);
+  const int Q = plan->host.Q, B = plan->B;
+  if (plan->avg_child) return (double)plan->ng * rotconv_plan_conv_equivalents(plan->avg_child, pass);
+  if (plan->d.dtype == ROTCONV_BF16 && plan->native16[pass]) {
+    int present = 0;      // orientations in the set: the bf16 gradient kernels multiply every quarter turn on its own
+    for (int i = 0; i < Q * 4; ++i) present += plan->rot_of[i] >= 0 ? 1 : 0;
+    if (pass == 0) return Q;
+    if (pass == 1) return p4_bwd_data_bf16_sparse(plan) ? 0.5 * present : present;   // 2-of-4 sparse operand: half the instructions
+    return present;
+  }
+  if (plan->fast[pass]) {
+    if (pass == 0) return plan->fwd_base ? B : Q;
+    return plan->bwd_lut ? B : Q;
+  }
+  if (plan->gs) return Q;
+  return plan->d.R;
+}
+
 const char* rotconv_plan_kernel_name(const rotconv_plan* plan, int pass) {
   if (!plan || pass < 0 || pass > 4) return "none";
   if (pass >= 3)      // the unfused gradient calls, given rotconv_workspace_bytes_unfused of scratch

@@ -98,6 +98,7 @@ struct P4BwdBfGeom {
   int seg_xorg[4], seg_lo[4], seg_hi[4];
 };
 bool p4_bwd_data_bf16_supported(const rotconv_plan* p);
+bool p4_bwd_data_bf16_sparse(const rotconv_plan* p);   // runs the structured-sparse instances (half the matrix instructions)
 size_t p4_bwd_data_bf16_pack_bytes(const rotconv_plan* p);
 void launch_p4_pack_bwd_bf16(const rotconv_plan* p, const uint16_t* w, uint16_t* wt, hipStream_t st);
 size_t p4_bwd_data_bf16_part_bytes(const rotconv_plan* p);

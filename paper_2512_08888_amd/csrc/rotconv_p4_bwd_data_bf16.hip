@@ -622,6 +622,8 @@ bool use_sparse(const rotconv_plan* p) {
 
 }  // namespace
 
+bool p4_bwd_data_bf16_sparse(const rotconv_plan* p) { return use_sparse(p); }
+
 // Shapes of the forward kernel (even W, segmented rows need W % 32 == 0); every bank inside one pool group;
 // after the K split a workgroup's share of the filter block must fit LDS.
 bool p4_bwd_data_bf16_supported(const rotconv_plan* p) {
