@@ -230,6 +230,7 @@ int rotconv_plan_create_opt(const rotconv_desc* desc, const rotconv_plan_options
     p->native16[0] = p->fast[0] && p4_fwd_bf16_supported(p) ? 1 : 0;
     p->native16[1] = p->fast[1] && p4_bwd_data_bf16_supported(p) ? 1 : 0;
     p->native16[2] = p->fast[2] && p4_bwd_weight_bf16_supported(p) ? 1 : 0;
+    if (p->native16[2] && p4_bwd_lut16_choice(p)) p->bwd_lut16[2] = 1;
   }
   if (p->d.pool_op == ROTCONV_POOL_AVG) {
     // the fused calls of an average-pooling plan run an ordinary convolution (R = 1) with Cout * R/G filters
@@ -925,6 +926,7 @@ double rotconv_plan_conv_equivalents(const rotconv_plan* plan, int pass) {
     int present = 0;      // orientations in the set: the bf16 gradient kernels multiply every quarter turn on its own
     for (int i = 0; i < Q * 4; ++i) present += plan->rot_of[i] >= 0 ? 1 : 0;
     if (pass == 0) return Q;
+    if (plan->bwd_lut16[pass]) return B;       // routed gradients folded into the base taps
     if (pass == 1) return p4_bwd_data_bf16_sparse(plan) ? 0.5 * present : present;   // 2-of-4 sparse operand: half the instructions
     return present;
   }
@@ -941,7 +943,7 @@ const char* rotconv_plan_kernel_name(const rotconv_plan* plan, int pass) {
   if (pass >= 3)      // the unfused gradient calls, given rotconv_workspace_bytes_unfused of scratch
     return plan->gs || (plan->d.pool_op != ROTCONV_POOL_AVG && gs_wanted(plan)) ? "mfma_gemm_scatter" : "generic";
   if (plan->pad_child && plan->pad_use[pass]) return rotconv_plan_kernel_name(plan->pad_child, pass);
-  if (plan->d.dtype == ROTCONV_BF16 && plan->native16[pass]) return "mfma_p4_bf16";
+  if (plan->d.dtype == ROTCONV_BF16 && plan->native16[pass]) return plan->bwd_lut16[pass] ? "mfma_p4_bf16_lut" : "mfma_p4_bf16";
   if (pass == 0 && plan->fast[0] && plan->fwd_base) return "mfma_p4_base";   // the pooled forward; rotconv_fwd: mfma_p4
   return plan->fast[pass] ? "mfma_p4" : plan->gs ? "mfma_gemm_scatter" : "generic";
 }

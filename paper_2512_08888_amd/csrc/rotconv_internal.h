@@ -89,6 +89,7 @@ struct rotconv_plan {
   size_t gs_chunk_bytes = (size_t)512 << 20;   // that family holds the products of as many images as fit this
   int gs = 0;                   // passes without a register-resident kernel run the matrix-multiply + scatter family
   int bwd_lut = 0;              // fast fp32 gradients: routed-gradient table, contraction over the base bank only
+  int bwd_lut16[3] = {0, 0, 0}; // bf16 gradient kernels ([1] input, [2] weight gradient): the same table, D rounded to bf16 once
   int fwd_base = 0;             // fast fp32 pooled forward: products of the base bank only, banks combined on the vector ALU
   int fwd_base_cls = 0;         // its banks' classes (two bits per bank)
   int fwd_csplit[2] = {1, 1};   // fast forward: channel splits for the unpooled / the pooled output (1: none)

@@ -79,6 +79,7 @@ struct P4BwdGeom {
 };
 bool p4_bwd_lut_choice(const rotconv_plan* p);   // whether the fp32 gradients should use the routed-gradient table
 bool p4_bwd_lut(const rotconv_plan* p);          // the plan's setting (contraction over the base bank)
+bool p4_bwd_lut16_choice(const rotconv_plan* p); // the same question for the kernels that take bf16 tensors
 bool p4_bwd_data_supported(const rotconv_plan* p);
 P4BwdGeom p4_bwd_data_geom(const rotconv_plan* p);
 size_t p4_bwd_data_pack_floats(const rotconv_plan* p);

@@ -460,6 +460,10 @@ bool p4_bwd_lut_choice(const rotconv_plan* p) {
   return true;
 }
 bool p4_bwd_lut(const rotconv_plan* p) { return p->bwd_lut != 0; }
+bool p4_bwd_lut16_choice(const rotconv_plan* p) {
+  if (p->host.lut_bwd.empty() || p->host.Q <= p->B || p->ng != 1 || p->d.R > 32 || p->d.dtype != ROTCONV_BF16) return false;
+  return p->opt.bwd_lut >= 0;
+}
 
 bool p4_bwd_data_supported(const rotconv_plan* p) {
   const rotconv_desc& d = p->d;

@@ -561,6 +561,237 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_weight_bf16(const uint16_t* __res
   }
 }
 
+// bfloat16 tensors, routed-gradient table (one pool group holds all R orientations of a filter, more banks than base
+// banks): the gradient that reaches BASE tap u' of a filter at a pixel,
+//     D[u'][p] = sum over the 3 x 3 neighbours of G * lut[offset][idx][u'],
+// is formed in fp32 from its at most nine terms (vector ALU, table rows from LDS), rounded to bf16 once and used as
+// the A operand: ONE matrix instruction per (base tap, channel block) and row instead of one per quarter turn and
+// bank (R = 16: 36 instead of 576 per row of 16 filters x 64 channels x 32 pixels), and the result is the base
+// bank's gradient itself.  Same units, strips, row ranges and splits as the kernels above.  The D of row h + 1 is
+// built, pixel by pixel, between the matrix instructions of row h.
+template <int NCB>
+__global__ __launch_bounds__(NT) void k_p4_bwd_weight_bf16_lut(const uint16_t* __restrict__ x,
+                                                               const uint16_t* __restrict__ gpool,
+                                                               const uint8_t* __restrict__ idx,
+                                                               const float* __restrict__ lut,
+                                                               float* __restrict__ partial, P4BwdWGeom g) {
+  constexpr int kLutRows = 33;     // table rows per neighbour offset in LDS (R + 1 <= 33)
+  __shared__ float Tl[2 * 9 * kLutRows * 12];      // one table per base bank (at most two)
+  {
+    const int R1 = g.R + 1;
+    for (int i = threadIdx.x; i < g.Q * 9 * R1 * 12; i += NT) Tl[(i / (R1 * 12)) * (kLutRows * 12) + i % (R1 * 12)] = lut[i];
+    __syncthreads();
+  }
+  const int per_xcd = gridDim.x / 8;
+  int v = gridDim.x % 8 == 0 ? (blockIdx.x % 8) * per_xcd + blockIdx.x / 8 : blockIdx.x;
+  const int cig = v % g.ncig; v /= g.ncig;
+  const int fbg = v % g.ncog;
+  const int split = v / g.ncog;
+
+  const int tid = threadIdx.x;
+  const int wave = tid / 64, lane = tid % 64;
+  const int lg = lane / 16, lc = lane % 16;
+  const int HW = g.H * g.W;
+  const int nfb = g.CoutPad / 16;
+  const int fb_flat = min(fbg * NWAVE + wave, g.Q * nfb - 1);       // an idle wave redoes the last pair
+  const bool wave_on = fbg * NWAVE + wave < g.Q * nfb;
+  const int q = __builtin_amdgcn_readfirstlane(fb_flat / nfb);      // the wave's base bank
+  const int cobase = (fb_flat % nfb) * 16;
+  const int co = cobase + lc;                        // this lane's filter (A role)
+  const int ci0 = cig * 16 * NCB + lc;               // this lane's channel in block 0 (B role)
+  const bool cok = co < g.Cout;
+  const size_t gplane0 = (size_t)(cok ? co : 0) * HW;          // one pooled plane per filter
+  const size_t gimg = (size_t)g.Cout * HW;
+  const size_t ximg = (size_t)g.Cin * HW;
+
+  uint32_t xplane[NCB];
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb) {
+    const int ci = ci0 + cb * 16;
+    xplane[cb] = (uint32_t)(ci < g.Cin ? ci : 0) * (uint32_t)HW;
+  }
+
+  f4 acc[9][NCB];
+#pragma unroll
+  for (int u = 0; u < 9; ++u)
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) acc[u][cb] = f4{0.f, 0.f, 0.f, 0.f};
+
+  // A row as kept for the three rows it serves: per column (0 left neighbour, 1..8 the lane's pixels, 9 right
+  // neighbour) the gradient (zero where the position or its idx is not valid) and the table-row offset of its idx.
+  struct LutRowW { float gv[10]; uint32_t off[10]; };
+  auto lut_route = [&](const RowB& r, bool rok, bool pok, bool lok, bool rok2, LutRowW& m) {
+    const uint32_t ic0 = (rok && pok) ? r.i0 : 0xffffffffu, ic1 = (rok && pok) ? r.i1 : 0xffffffffu;
+    const uint32_t il = (rok && lok) ? (uint32_t)r.il : 0xffu, ir = (rok && rok2) ? (uint32_t)r.ir : 0xffu;
+#pragma unroll
+    for (int c = 0; c < 10; ++c) {
+      const uint32_t byte = c == 0 ? il : c == 9 ? ir : c < 5 ? ((ic0 >> (8 * (c - 1))) & 0xffu) : ((ic1 >> (8 * (c - 5))) & 0xffu);
+      // bf16 -> fp32: the pair word's low half is the even pixel
+      const uint32_t bits = c == 0 ? ((uint32_t)r.gl << 16) : c == 9 ? ((uint32_t)r.gr << 16)
+                            : ((c - 1) & 1) ? (r.g[(c - 1) / 2] & 0xffff0000u) : (r.g[(c - 1) / 2] << 16);
+      m.gv[c] = byte < (uint32_t)g.R ? __uint_as_float(bits) : 0.f;
+      m.off[c] = min(byte, (uint32_t)g.R) * 12u + (uint32_t)q * (9 * kLutRows * 12);
+    }
+  };
+  struct LutT { f4 t0, t1; float t8; };
+  auto lut_read = [&](const LutRowW& row, int dr, int dc, int pc) -> LutT {
+    const float* t = Tl + (dr * 3 + dc) * (kLutRows * 12) + row.off[pc + dc - 1];
+    LutT tv;
+    tv.t0 = *reinterpret_cast<const f4*>(t);
+    tv.t1 = *reinterpret_cast<const f4*>(t + 4);
+    tv.t8 = t[8];
+    return tv;
+  };
+  auto lut_fma = [&](const LutRowW& row, int dr, int dc, int pc, const LutT& tv, float (&d)[9]) {
+    const float gvc = row.gv[pc + dc - 1];
+    const float t9[9] = {tv.t0[0], tv.t0[1], tv.t0[2], tv.t0[3], tv.t1[0], tv.t1[1], tv.t1[2], tv.t1[3], tv.t8};
+#pragma unroll
+    for (int u = 0; u < 9; ++u) d[u] = (dr == 0 && dc == 0) ? gvc * t9[u] : d[u] + gvc * t9[u];
+  };
+
+  for (int unit = split; unit < g.units; unit += g.splits) {
+    int uu = unit;
+    const int strip = uu % g.nstrip; uu /= g.nstrip;
+    const int rng = uu % g.nrange;
+    const int n = uu / g.nrange;
+    const int h0 = rng * g.rows_per, h1 = min(g.H, h0 + g.rows_per);
+    const int px0 = strip * 32 + 8 * lg;
+    const bool pok = px0 < g.W;                              // W % 8 == 0: a lane's 8 pixels are in or out together
+    const bool lok = pok && px0 >= 1, rok2 = px0 + 8 < g.W;
+    const int pc = pok ? px0 : 0, pl = lok ? px0 - 1 : 0, pr = rok2 ? px0 + 8 : 0;
+    const uint16_t* gb = gpool + (size_t)n * gimg + gplane0;
+    const uint8_t* ib = idx + (size_t)n * gimg + gplane0;
+    const uint16_t* xb = x + (size_t)n * ximg;
+    const bool tail = strip * 32 + 32 > g.W;       // wave-uniform
+
+    auto row_ok = [&](int h) { return cok && h >= 0 && h < g.H; };
+    auto load_row = [&](int h, RowB& r) {
+      const uint32_t ro = (uint32_t)min(max(h, 0), g.H - 1) * (uint32_t)g.W;
+      r.g = *reinterpret_cast<const u4*>(gb + ro + pc);
+      const uint2 iv = *reinterpret_cast<const uint2*>(ib + ro + pc);
+      r.i0 = iv.x; r.i1 = iv.y;
+      r.gl = gb[ro + pl];
+      r.gr = gb[ro + pr];
+      r.il = ib[ro + pl];
+      r.ir = ib[ro + pr];
+    };
+    auto lroute = [&](const RowB& r, int h, LutRowW& m) { lut_route(r, row_ok(h), pok, lok, rok2, m); };
+    auto load_x = [&](int h, u4 (&b)[NCB]) {
+      const uint32_t off = (uint32_t)min(h, g.H - 1) * (uint32_t)g.W + (uint32_t)pc;
+#pragma unroll
+      for (int cb = 0; cb < NCB; ++cb) b[cb] = *reinterpret_cast<const u4*>(xb + xplane[cb] + off);
+    };
+    // D of pixel column pcol (1..8) from the rows (above, at, below), nine base taps: three groups (one per row) of
+    // three table-row reads and 27 multiply-adds.  `between(group)` is issued between a group's reads and its
+    // multiply-adds (the matrix instructions of the current row go there); the fences keep the reads of one group
+    // at a time in flight and the opaque uses keep the multiply-adds where they are written (the sums are first
+    // needed when the row is packed: left alone the compiler gathers all table reads of a row up front).
+    auto build_pixel = [&](const LutRowW& ra, const LutRowW& rb, const LutRowW& rc, int pcol, float (&d)[9],
+                           auto&& between) {
+#pragma unroll
+      for (int dr = 0; dr < 3; ++dr) {
+        const LutRowW& row = dr == 0 ? ra : dr == 1 ? rb : rc;
+        LutT tv[3];
+#pragma unroll
+        for (int dc = 0; dc < 3; ++dc) tv[dc] = lut_read(row, dr, dc, pcol);
+        __builtin_amdgcn_sched_barrier(0);
+        between((pcol - 1) * 3 + dr);
+#pragma unroll
+        for (int dc = 0; dc < 3; ++dc) lut_fma(row, dr, dc, pcol, tv[dc], d);
+#pragma unroll
+        for (int u = 0; u < 9; ++u) asm volatile("" : "+v"(d[u]));
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    };
+    auto pack = [&](const float (&d0)[9], const float (&d1)[9], int pair, u4 (&a)[9]) {
+#pragma unroll
+      for (int u = 0; u < 9; ++u) {
+        typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
+        bf2 pr2;
+        pr2[0] = (__bf16)d0[u];
+        pr2[1] = (__bf16)d1[u];
+        a[u][pair] = __builtin_bit_cast(uint32_t, pr2);
+      }
+    };
+
+    RowB rn;                                          // the row being loaded
+    LutRowW l0, l1, l2;                               // routed rows; the roles rotate
+    u4 bX[NCB], bN[NCB];                              // X of row h, and of row h + 1 in flight
+    u4 aC[9], aN[9];                                  // D of row h (A operands), and of row h + 1 being built
+    // One image row h: (ra, rb, rc) = routed rows (h, h+1, h+2), aC = D(h).  Row h + 3 and X(h + 1) are loaded ahead;
+    // the D of row h + 1 is built two pixels at a time between the matrix instructions of row h.
+    auto step = [&](int h, LutRowW& ra, LutRowW& rb, LutRowW& rc) {
+      load_row(h + 3, rn);
+      load_x(h + 1, bN);
+      __builtin_amdgcn_sched_barrier(0);
+      if (tail) {    // X of pixels beyond the row end must be zero: D there gathers in-range neighbours
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb) bX[cb] = pok ? bX[cb] : u4{0u, 0u, 0u, 0u};
+      }
+      // the 9 NCB matrix instructions of row h, spread over the 24 groups of the D build of row h + 1
+      auto mfmas = [&](int grp) {
+        constexpr int TOT = 9 * NCB;
+#pragma unroll
+        for (int i = grp * TOT / 24; i < (grp + 1) * TOT / 24; ++i)
+          acc[i / NCB][i % NCB] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf8, aC[i / NCB]),
+                                                                          __builtin_bit_cast(bf8, bX[i % NCB]),
+                                                                          acc[i / NCB][i % NCB], 0, 0, 0);
+      };
+#pragma unroll
+      for (int pr2 = 0; pr2 < 4; ++pr2) {
+        float d0[9], d1[9];
+        build_pixel(ra, rb, rc, 2 * pr2 + 1, d0, mfmas);
+        build_pixel(ra, rb, rc, 2 * pr2 + 2, d1, mfmas);
+        pack(d0, d1, pr2, aN);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      lroute(rn, h + 3, ra);                          // row h + 3 replaces row h
+#pragma unroll
+      for (int cb = 0; cb < NCB; ++cb) bX[cb] = bN[cb];
+#pragma unroll
+      for (int u = 0; u < 9; ++u) aC[u] = aN[u];
+    };
+    // prologue: rows h0 - 1, h0, h0 + 1 -> D(h0); then row h0 + 2 takes the place of row h0 - 1
+    load_row(h0 - 1, rn);
+    lroute(rn, h0 - 1, l0);
+    load_row(h0, rn);
+    lroute(rn, h0, l1);
+    load_row(h0 + 1, rn);
+    lroute(rn, h0 + 1, l2);
+    load_x(h0, bX);
+#pragma unroll
+    for (int pr2 = 0; pr2 < 4; ++pr2) {
+      float d0[9], d1[9];
+      auto nothing = [](int) {};
+      build_pixel(l0, l1, l2, 2 * pr2 + 1, d0, nothing);
+      build_pixel(l0, l1, l2, 2 * pr2 + 2, d1, nothing);
+      pack(d0, d1, pr2, aC);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    load_row(h0 + 2, rn);
+    lroute(rn, h0 + 2, l0);
+    // step(h, rows h, h+1, h+2): the D of row h + 1 is built from exactly those rows
+    for (int h = h0; h < h1; h += 3) {
+      step(h, l1, l2, l0);
+      if (h + 1 >= h1) break;
+      step(h + 1, l2, l0, l1);
+      if (h + 2 >= h1) break;
+      step(h + 2, l0, l1, l2);
+    }
+  }
+
+  if (wave_on) {
+    float* out = partial + ((size_t)(split * g.Q + q) * 9) * g.CoutPad * g.CinPad;
+#pragma unroll
+    for (int u = 0; u < 9; ++u)
+#pragma unroll
+      for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          out[((size_t)u * g.CoutPad + cobase + 4 * lg + i) * g.CinPad + cig * 16 * NCB + cb * 16 + lc] = acc[u][cb][i];
+  }
+}
+
 // Stage 1: sum the splits.  A block covers 32 consecutive elements x 8 interleaved split groups;
 // each thread adds its splits in ascending order, the groups are combined in a fixed tree, so
 // the result does not depend on scheduling.  out[e] = sum_split partial[split][e].
@@ -661,7 +892,7 @@ bool p4_bwd_weight_bf16_supported(const rotconv_plan* p) { return p4_bwd_weight_
 size_t p4_bwd_weight_ws_floats(const rotconv_plan* p) {
   size_t need = 0;
   for (int lut = 0; lut < 2; ++lut) {     // the per-bank kernels (also the bf16 one) and the table variant
-    if (lut && !p4_bwd_lut(p)) break;
+    if (lut && !p4_bwd_lut(p) && !p->bwd_lut16[2]) break;
     const P4BwdWGeom g = p4_bwd_weight_geom(p, lut != 0);
     need = std::max(need, (size_t)(g.splits + 1) * g.Q * 9 * g.CoutPad * g.CinPad);  // partial sums + their total
   }
@@ -698,6 +929,14 @@ void launch_p4_bwd_weight(const rotconv_plan* p, const float* x, const float* gp
 
 void launch_p4_bwd_weight_bf16(const rotconv_plan* p, const uint16_t* x, const uint16_t* gpool, const uint8_t* idx,
                                float* partial, float* dw, hipStream_t st) {
+  if (p->bwd_lut16[2]) {      // routed-gradient table: one contraction with the base bank
+    const P4BwdWGeom g = p4_bwd_weight_geom(p, true);
+    const int grid = g.splits * g.ncig * g.ncog;
+    if (g.ncb == 1) hipLaunchKernelGGL(k_p4_bwd_weight_bf16_lut<1>, dim3(grid), dim3(NT), 0, st, x, gpool, idx, p->dev.lut_bwd, partial, g);
+    else hipLaunchKernelGGL(k_p4_bwd_weight_bf16_lut<4>, dim3(grid), dim3(NT), 0, st, x, gpool, idx, p->dev.lut_bwd, partial, g);
+    finish_dw(p, g, partial, dw, st);
+    return;
+  }
   const P4BwdWGeom g = p4_bwd_weight_geom(p);
   const int grid = g.splits * g.ncig * g.ncog;
   if (g.ncb == 1) hipLaunchKernelGGL(k_p4_bwd_weight_bf16<1>, dim3(grid), dim3(NT), 0, st, x, gpool, idx, p->dev.rot_of, partial, g);

@@ -72,6 +72,14 @@ def reference(cfg, x, w, ang):
     return w_rot, y, yp, idx
 
 
+def dw_rtol(plan):
+    """Bar of the fp32 weight gradient of a bf16 plan.  The per-bank kernels multiply exact bf16 operands and
+    accumulate in fp32: the fp32 bar.  The table kernels ("..._lut") fold the routed gradients of all orientations
+    into the base taps in fp32 and round that sum to bf16 once, because it is the matrix-core operand: one bf16
+    rounding (2^-9) per operand, the bar of every bf16-typed quantity."""
+    return BF_RTOL if plan.kernel_name(2).endswith("_lut") else RTOL
+
+
 def reference_bwd(cfg, x, w_rot, g, idx, ang):
     dy = orc.orient_maxpool_bwd(g, idx, cfg.R, cfg.G)
     dx = orc.rotconv_bwd_data(dy, w_rot, cfg.H, cfg.W, cfg.stride, cfg.pad)
@@ -104,7 +112,7 @@ def test_bf16_fused_calls(cfg):
     assert_close(f64(dx), dx_ref, f"{cfg.name} dx", rtol=BF_RTOL)
     dw = torch.full(tuple(wd.shape), float("nan"), dtype=torch.float32, device="cuda")
     rc.rotconv_pool_bwd_weight(plan, xd, gd, idx, dw)
-    assert_close(f64(dw), dw_ref, f"{cfg.name} dw (fp32)", rtol=RTOL)
+    assert_close(f64(dw), dw_ref, f"{cfg.name} dw (fp32)", rtol=dw_rtol(plan))
 
 
 DYADIC = [CASES[1], CASES[5], CASES[7], LC("b_dy_stream", N=1, Cin=512, H=6, W=64, Cout=16, R=4, seed=63),
@@ -235,7 +243,7 @@ def test_bf16_config_full_size_sampled(cfg, ns, npairs):
         full[:, 0, 0] = dwr[t]
         ref_dw.append(orc.reduce_bank_grad(full, ang, cfg.mode)[:, 0, 0])
         got_dw.append(dw[:, co, ci])
-    assert_close(np.array(got_dw), np.array(ref_dw), f"{cfg.name} dw samples (fp32)", rtol=RTOL)
+    assert_close(np.array(got_dw), np.array(ref_dw), f"{cfg.name} dw samples (fp32)", rtol=dw_rtol(plan))
     # homogeneity through the max: <w, dW> = <x, dX> = <ypool, g>; ypool and dX carry one bf16 rounding each
     a, b, c = float((yp * g).sum()), float((x * dx).sum()), float((w * dw).sum())
     scale = float(np.abs(yp * g).sum())

@@ -357,7 +357,9 @@ def test_unet_step_teacher_forced(cfg, dtype):
         assert np.all(g[H(a["y"]) <= 0] == 0), f"{name}: ReLU backward"
         dx_ref, dw_ref = layer_bwd(H(a["x"]), p64[name], g, H(a["idx"]).astype(np.uint8), sp["R"], None,
                                        sp["mode"], 1, 1, sp["pool_group"])
-        assert_close(H(net.grads[name]), dw_ref, f"{name} dW")
+        # (a bf16 plan on the table kernels rounds the folded routed gradient to bf16 once: the bf16 bar)
+        assert_close(H(net.grads[name]), dw_ref, f"{name} dW",
+                     rtol=BF_RTOL if net.plans[name].kernel_name(2).endswith("_lut") else RTOL)
         if i == 0:
             continue
         if name.endswith("b"):              # lands in the block's first layer's slot
@@ -519,7 +521,8 @@ def test_unet_full_size_sampled(cfg, dtype):
             full[:, 0, 0] = dwr[t]
             ref_dw.append(orc.reduce_bank_grad(full, None, mode)[:, 0, 0])
             got_dw.append(dw[:, o, c])
-        assert_close(np.array(got_dw), np.array(ref_dw), f"{name} dW samples")
+        assert_close(np.array(got_dw), np.array(ref_dw), f"{name} dW samples",
+                     rtol=BF_RTOL if net.plans[name].kernel_name(2).endswith("_lut") else RTOL)
         # homogeneity through max-pool and ReLU: <w, dW> = <y, g>
         lhs = float((params[name].astype(np.float64) * dw).sum())
         rhs = float((y.astype(np.float64) * g).sum())
