@@ -211,6 +211,8 @@ int rotconv_plan_create_opt(const rotconv_desc* desc, const rotconv_plan_options
     if (p->fast[0] && p4_fwd_bf16_supported(p)) p->ws_bytes = std::max(p->ws_bytes, p4_fwd_bf16_pack_bytes(p));
     if (p->fast[1] && p4_bwd_data_bf16_supported(p))
       p->ws_bytes = std::max(p->ws_bytes, align256(p4_bwd_data_bf16_pack_bytes(p)) + p4_bwd_data_bf16_part_bytes(p));
+    if (p->fast[1] && p4_bwd_data_bf16_lut_supported(p))
+      p->ws_bytes = std::max(p->ws_bytes, align256(p4_bwd_data_bf16_lut_pack_bytes(p)) + p4_bwd_data_bf16_lut_part_bytes(p));
   }
   // other layers (k, stride, pad, or a pool group that cuts through a bank): matrix multiply + scatter
   const bool is3x3 = p->d.k == 3 && p->d.stride == 1 && p->d.pad == 1;
@@ -229,6 +231,7 @@ int rotconv_plan_create_opt(const rotconv_desc* desc, const rotconv_plan_options
     p->ws_bytes = align256(p->n_x * 4) + align256(p->n_w * 4) + align256(p->n_yu * 4) + p->ws_inner;
     p->native16[0] = p->fast[0] && p4_fwd_bf16_supported(p) ? 1 : 0;
     p->native16[1] = p->fast[1] && p4_bwd_data_bf16_supported(p) ? 1 : 0;
+    if (p->fast[1] && p4_bwd_data_bf16_lut_supported(p)) p->native16[1] = p->bwd_lut16[1] = 1;
     p->native16[2] = p->fast[2] && p4_bwd_weight_bf16_supported(p) ? 1 : 0;
     if (p->native16[2] && p4_bwd_lut16_choice(p)) p->bwd_lut16[2] = 1;
   }
@@ -861,6 +864,12 @@ int rotconv_pool_bwd_data(const rotconv_plan* plan, const void* gpool, const uin
     const int rc = ensure_device_tables(p);
     if (rc) return rc;
     uint16_t* wt = static_cast<uint16_t*>(ws);
+    if (p->bwd_lut16[1]) {     // routed-gradient table: one contraction with the base bank
+      launch_p4_pack_bwd_bf16_lut(p, h16(w), wt, st);
+      float* lpart = reinterpret_cast<float*>(static_cast<char*>(ws) + align256(p4_bwd_data_bf16_lut_pack_bytes(p)));
+      launch_p4_bwd_data_bf16_lut(p, h16(gpool), idx, wt, static_cast<uint16_t*>(dx), lpart, st);
+      return finish();
+    }
     launch_p4_pack_bwd_bf16(p, h16(w), wt, st);
     float* part = reinterpret_cast<float*>(static_cast<char*>(ws) + align256(p4_bwd_data_bf16_pack_bytes(p)));
     launch_p4_bwd_data_bf16(p, h16(gpool), idx, wt, static_cast<uint16_t*>(dx), part, st);

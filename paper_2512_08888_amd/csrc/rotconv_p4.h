@@ -106,6 +106,14 @@ size_t p4_bwd_data_bf16_part_bytes(const rotconv_plan* p);
 void launch_p4_bwd_data_bf16(const rotconv_plan* p, const uint16_t* gpool, const uint8_t* idx, const uint16_t* wt,
                              uint16_t* dx, float* part, hipStream_t st);
 
+// input gradient on bfloat16 tensors through the routed-gradient table (one contraction with the base bank)
+bool p4_bwd_data_bf16_lut_supported(const rotconv_plan* p);
+size_t p4_bwd_data_bf16_lut_pack_bytes(const rotconv_plan* p);
+size_t p4_bwd_data_bf16_lut_part_bytes(const rotconv_plan* p);
+void launch_p4_pack_bwd_bf16_lut(const rotconv_plan* p, const uint16_t* w, uint16_t* wt, hipStream_t st);
+void launch_p4_bwd_data_bf16_lut(const rotconv_plan* p, const uint16_t* gpool, const uint8_t* idx, const uint16_t* wt,
+                                 uint16_t* dx, float* part, hipStream_t st);
+
 // weight gradient
 struct P4BwdWGeom {
   int N, Cin, CinPad, H, W, Cout, CoutPad, Q, ng;

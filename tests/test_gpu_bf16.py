@@ -43,8 +43,11 @@ CASES = [
     # orientation sets without all four quarter turns per bank: the dense input-gradient instances
     LC("b_p4m", N=1, Cin=24, H=9, W=32, Cout=40, R=8, mode="p4m", seed=73),
     LC("b_r2", N=1, Cin=16, H=8, W=32, Cout=80, R=2, seed=74),
-    # a layer on which one arg-max sits just outside the fp32 near-tie band because a rotated weight rounds to the
-    # neighbouring bf16 value (fp32 against fp64 combination): covered by the bank-rounding band
+    # the table gradient kernels: two channel groups of 128, filters padded to a K-step, rows that end inside a lane
+    # group (the weight gradient of this width runs on widened copies)
+    LC("b_lut_w44", N=1, Cin=136, H=6, W=44, Cout=40, R=16, mode="bilinear", x_dist="absnormal", seed=75),
+    # a layer on which one arg-max sat just outside the fp32 near-tie band when the rotated weights were formed in fp32
+    # (one of them rounded to the neighbouring bf16 value); they are formed in fp64 now: the regression case
     LC("b_r16_bank_rounding", N=2, Cin=32, H=19, W=160, Cout=136, R=16, mode="bilinear", x_dist="absnormal", seed=9148),
 ]
 
@@ -113,6 +116,30 @@ def test_bf16_fused_calls(cfg):
     dw = torch.full(tuple(wd.shape), float("nan"), dtype=torch.float32, device="cuda")
     rc.rotconv_pool_bwd_weight(plan, xd, gd, idx, dw)
     assert_close(f64(dw), dw_ref, f"{cfg.name} dw (fp32)", rtol=dw_rtol(plan))
+
+
+@pytest.mark.parametrize("name", ["b_r16", "b_c160_r16", "b_co192_r16", "b_r8_fold2", "b_r16_fold4_w40", "b_p4m"])
+def test_bf16_gradients_per_bank_kernels(name):
+    """Layers whose gradients take the routed-gradient table by default, on the per-bank bf16 gradient kernels
+    (plan option bwd_lut = -1): exact bf16 operands, the fp32 bar for dW."""
+    cfg = next(c for c in CASES if c.name == name)
+    plan = rc.Plan.from_config(cfg, dtype=rc.BF16, options=dict(bwd_lut=-1))
+    print(f"[case] bf16 per-bank gradients {cfg.name} kernels {[plan.kernel_name(i) for i in range(3)]}", flush=True)
+    assert not plan.kernel_name(1).endswith("_lut") and not plan.kernel_name(2).endswith("_lut")
+    ang = None if cfg.angles_deg is None else list(cfg.angles_deg)
+    xd, x = bf(synth.make_x(cfg))
+    wd, w = bf(synth.make_w(cfg))
+    gd, g = bf(synth.make_g(cfg))
+    w_rot = round_bf16(orc.expand_bank(w, cfg.R, ang, cfg.mode))
+    idx_h = synth.make_idx(cfg)
+    idx = torch.from_numpy(idx_h).cuda()
+    dx_ref, dw_ref = reference_bwd(cfg, x, w_rot, g, idx_h, ang)
+    dx = nan16(*xd.shape)
+    rc.rotconv_pool_bwd_data(plan, gd, idx, wd, dx)
+    assert_close(f64(dx), dx_ref, f"{cfg.name} dx", rtol=BF_RTOL)
+    dw = torch.full(tuple(wd.shape), float("nan"), dtype=torch.float32, device="cuda")
+    rc.rotconv_pool_bwd_weight(plan, xd, gd, idx, dw)
+    assert_close(f64(dw), dw_ref, f"{cfg.name} dw (fp32)", rtol=RTOL)
 
 
 DYADIC = [CASES[1], CASES[5], CASES[7], LC("b_dy_stream", N=1, Cin=512, H=6, W=64, Cout=16, R=4, seed=63),
