@@ -51,6 +51,8 @@ def source_digest():
     import hashlib
     h = hashlib.sha256()
     for f in sorted(glob.glob(os.path.join(ROOT, "paper_2512_08888_amd", "csrc", "*"))):
+        if not f.endswith((".hip", ".h", ".cpp")):
+            continue
         h.update(os.path.basename(f).encode())
         h.update(open(f, "rb").read())
     return h.hexdigest()[:16]
