@@ -71,7 +71,8 @@ struct P4BwdGeom {
   int ncig;    // groups of 64 input channels
   int px;      // pixels per lane (2 or 4)
   int nstrip;  // strips of 16 * px pixels per row
-  int nrb;     // blocks of 8 rows
+  int nw;      // waves (= rows) per workgroup
+  int nrb;     // blocks of nw rows
   int ksplit;  // workgroups that share a unit's contraction (each writes an fp32 partial dX); 1 = no split
   int kper;    // weight chunks (16 filters of a bank) per such workgroup
   int units;   // workgroups with work (includes the split)

@@ -14,10 +14,13 @@
 // A wave owns one image row x 16 PX pixels x 64 input channels (PX = 2 or 4 pixels
 // per lane, four 16x16 accumulator tiles per 16-pixel block).  Per K-step of 4
 // filters a lane reads the 3 x (PX + 2) pixel neighbourhood of (G, idx) of its
-// filter straight from global memory (L1/L2 resident: the eight waves of a
-// workgroup take eight consecutive rows), builds its 9 PX A values and feeds
+// filter straight from global memory (L1/L2 resident: the waves of a
+// workgroup take consecutive rows), builds its 9 PX A values and feeds
 // 36 PX MFMAs.  The weights stream through LDS in chunks of 16 filters,
 // double-buffered, a quarter chunk per pipeline stage, one barrier per chunk.
+// A workgroup is NW waves = NW consecutive rows.  The per-bank variant runs four-wave workgroups, two per CU:
+// the waves of one workgroup meet at the chunk barrier in step (the two waves of a SIMD would otherwise reach it
+// one after the other, each running alone for a while), the other workgroup's waves fill the gap.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -36,8 +39,6 @@ constexpr int NCB = 4;                 // 16-channel blocks per wave
 constexpr int CIG = 16 * NCB;          // input channels per workgroup
 constexpr int WROW = 9 * CIG + 16;     // LDS floats per filter row (padded: conflict-free B reads)
 constexpr int CHUNK = 16;              // filters per LDS chunk
-constexpr int NWAVE = 8;
-constexpr int NT = 64 * NWAVE;
 constexpr int kLutRows = 33;           // table rows per neighbour offset in LDS: R + 1 <= 33
 
 __device__ __host__ constexpr int tap_i(int s, int u) {
@@ -49,11 +50,33 @@ __device__ __host__ constexpr int tap_j(int s, int u) {
 
 template <int PX>
 struct Raw {           // (G, idx) of one filter on a 3 x (PX + 2) pixel neighbourhood, as loaded
-  float gl[3], gr[3];  // left / right neighbour of the lane's PX pixels
-  float gc[3][PX];     // the PX pixels
-  uint32_t il[3], ic[3], ir[3];   // idx of the same positions (ic: PX bytes)
+  float gc[3][PX];     // the lane's PX pixels
+  float ge[3];         // first lane of a 16-lane row: the pixel left of its pixels; last lane: the pixel right of them
+  uint32_t ic[3], ie[3];   // idx of the same positions (ic: PX bytes)
   uint32_t finv;       // all ones if the lane's filter of this K-step is beyond Cout
 };
+
+// Left / right neighbour values of a lane's pixels: the adjacent lane of the 16-lane row holds them (its last / first
+// pixel); only the row's first and last lane take the value they loaded themselves (a shift inside the row leaves the
+// lane without a source untouched).
+__device__ __forceinline__ uint32_t from_left_lane(uint32_t own_edge, uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp((int)own_edge, (int)v, 0x111, 0xf, 0xf, false);   // row_shr:1
+}
+__device__ __forceinline__ uint32_t from_right_lane(uint32_t own_edge, uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp((int)own_edge, (int)v, 0x101, 0xf, 0xf, false);   // row_shl:1
+}
+template <int PX>
+struct Edges { float gl, gr; uint32_t iwe; };   // iwe: idx byte of the left neighbour in bits 7:0, of the right one in 15:8
+template <int PX>
+__device__ __forceinline__ Edges<PX> edges_of(const Raw<PX>& r, int dr) {
+  Edges<PX> e;
+  e.gl = __builtin_bit_cast(float, from_left_lane(__builtin_bit_cast(uint32_t, r.ge[dr]), __builtin_bit_cast(uint32_t, r.gc[dr][PX - 1])));
+  e.gr = __builtin_bit_cast(float, from_right_lane(__builtin_bit_cast(uint32_t, r.ge[dr]), __builtin_bit_cast(uint32_t, r.gc[dr][0])));
+  const uint32_t il = from_left_lane(r.ie[dr], r.ic[dr] >> (8 * (PX - 1)));
+  const uint32_t ir = from_right_lane(r.ie[dr], r.ic[dr]);
+  e.iwe = (il & 0xffu) | ((ir & 0xffu) << 8);
+  return e;
+}
 
 // PX = pixels per lane (2 or 4): a wave owns one image row x 16 PX pixels x 64 input channels.  More pixels
 // per lane means fewer selects and loads per pixel (the 3 x (PX + 2) neighbourhood is shared by PX pixels).
@@ -62,11 +85,13 @@ struct Raw {           // (G, idx) of one filter on a 3 x (PX + 2) pixel neighbo
 // G * lut[offset][idx][u'] (the rotated banks' coefficients, looked up per value): the routed gradients of all banks
 // are summed into the base taps before the contraction, which then runs over the base bank alone, one
 // conv-equivalent of matrix work instead of Q, and the neighbourhood is loaded once instead of once per bank.
-template <int PX, bool LUT>
-__global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gpool, const uint8_t* __restrict__ idx,
+template <int PX, bool LUT, int NW>
+__global__ __launch_bounds__(64 * NW, 2) void k_p4_bwd_data(const float* __restrict__ gpool, const uint8_t* __restrict__ idx,
                                                     const float* __restrict__ wd,
                                                     const int32_t* __restrict__ rot_of, const float* __restrict__ lut,
                                                     float* __restrict__ dx, P4BwdGeom g) {
+  constexpr int NT = 64 * NW;
+  constexpr int WREG = (4 * 9 * (CIG / 4) + NT - 1) / NT;     // staging registers (float4) per quarter chunk and thread
   extern __shared__ float smem[];      // [2][CHUNK][WROW], then the tables [base bank][9][kLutRows][12] (LUT)
   float* Tl = smem + 2 * CHUNK * WROW;
   if (LUT) {     // a fixed row count per offset: the offset part of a row address is an instruction immediate
@@ -93,7 +118,7 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gp
   const int tid = threadIdx.x;
   const int wave = tid / 64, lane = tid % 64;
   const int lg = lane / 16, lc = lane % 16;
-  const int h = rb * NWAVE + wave;
+  const int h = rb * NW + wave;
   const int x0 = strip * 16 * PX;
   const bool active = h < g.H;
   const int HW = g.H * g.W;
@@ -106,10 +131,10 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gp
   // (four filters) per pipeline stage into the buffer the current chunk does not use, so that only two
   // staging registers are live at any time.
   constexpr int Q4 = 4 * 9 * (CIG / 4);        // float4 per quarter chunk (576)
-  f4 wreg[2];
+  f4 wreg[WREG];
   auto wload = [&](int cc, int part) {
 #pragma unroll
-    for (int k = 0; k < 2; ++k) {
+    for (int k = 0; k < WREG; ++k) {
       const int e = tid + k * NT;
       if (e < Q4) {
         const int c4 = e % (CIG / 4), u = (e / (CIG / 4)) % 9, r = part * 4 + e / (9 * (CIG / 4));
@@ -120,7 +145,7 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gp
   auto wstore = [&](int buf, int part) {
     float* dst = smem + buf * CHUNK * WROW;
 #pragma unroll
-    for (int k = 0; k < 2; ++k) {
+    for (int k = 0; k < WREG; ++k) {
       const int e = tid + k * NT;
       if (e < Q4) {
         const int c4 = e % (CIG / 4), u = (e / (CIG / 4)) % 9, r = part * 4 + e / (9 * (CIG / 4));
@@ -137,7 +162,7 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gp
   // read filter 0).  Nothing is computed from a loaded value before the K-step that uses it, so the
   // loads stay in flight for two K-steps.
   const int xa = x0 + PX * lc;                 // first of this lane's PX pixels (W % PX == 0: in or out together)
-  uint32_t offc[3], offl[3], offr[3], invc[3], inve[3];   // invc: centre bytes, inve: byte 0 left, byte 1 right
+  uint32_t offc[3], offe[3], invc[3], inve[3];   // invc: centre bytes, inve: byte 0 left, byte 1 right
 #pragma unroll
   for (int dr = 0; dr < 3; ++dr) {
     const int row = h - 1 + dr;
@@ -145,8 +170,10 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gp
     const bool okc = rok && xa < g.W, okl = rok && xa >= 1 && xa - 1 < g.W, okr = rok && xa + PX < g.W;
     const uint32_t rowoff = (uint32_t)(rok ? row : 0) * (uint32_t)g.W;
     offc[dr] = rowoff + (uint32_t)(okc ? xa : 0);
-    offl[dr] = rowoff + (uint32_t)(okl ? xa - 1 : 0);
-    offr[dr] = rowoff + (uint32_t)(okr ? xa + PX : 0);
+    // the edge load: the row's first lane fetches its left neighbour, the last lane its right neighbour; the lanes
+    // between them read the first lane's address too (one cache line for the fifteen; their value is not used)
+    const bool okl0 = rok && x0 >= 1 && x0 - 1 < g.W;
+    offe[dr] = lc == 15 ? rowoff + (uint32_t)(okr ? xa + PX : 0) : rowoff + (uint32_t)(okl0 ? x0 - 1 : 0);
     invc[dr] = okc ? 0u : 0xffffffffu;
     inve[dr] = (okl ? 0u : 0xffu) | (okr ? 0u : 0xff00u);
   }
@@ -188,10 +215,8 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gp
         for (int p = 0; p < PX; ++p) r.gc[dr][p] = v[p];
         r.ic[dr] = *reinterpret_cast<const uint32_t*>(ib + (fl + offc[dr]));
       }
-      r.gl[dr] = gb[fl + offl[dr]];
-      r.gr[dr] = gb[fl + offr[dr]];
-      r.il[dr] = ib[fl + offl[dr]];
-      r.ir[dr] = ib[fl + offr[dr]];
+      r.ge[dr] = gb[fl + offe[dr]];
+      r.ie[dr] = ib[fl + offe[dr]];
     }
     if (ld_co + 4 < g.CoutPad) {
       ld_co += 4;
@@ -210,10 +235,11 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gp
     float d[3][PX + 2];
 #pragma unroll
     for (int dr = 0; dr < 3; ++dr) {
+      const Edges<PX> e = edges_of(r, dr);
       const uint32_t iwc = r.ic[dr] | invc[dr] | r.finv | (PX == 2 ? 0xffff0000u : 0u);
-      const uint32_t iwe = (r.il[dr] | (r.ir[dr] << 8)) | inve[dr] | r.finv;
-      d[dr][0] = ((iwe & 0xffu) == (uint32_t)rs) ? r.gl[dr] : 0.f;
-      d[dr][PX + 1] = (((iwe >> 8) & 0xffu) == (uint32_t)rs) ? r.gr[dr] : 0.f;
+      const uint32_t iwe = e.iwe | inve[dr] | r.finv;
+      d[dr][0] = ((iwe & 0xffu) == (uint32_t)rs) ? e.gl : 0.f;
+      d[dr][PX + 1] = (((iwe >> 8) & 0xffu) == (uint32_t)rs) ? e.gr : 0.f;
 #pragma unroll
       for (int p = 0; p < PX; ++p) d[dr][1 + p] = (((iwc >> (8 * p)) & 0xffu) == (uint32_t)rs) ? r.gc[dr][p] : 0.f;
     }
@@ -237,12 +263,13 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_data(const float* __restrict__ gp
     const uint32_t tbase = (uint32_t)bank * (9 * kLutRows * 12);
 #pragma unroll
     for (int dr = 0; dr < 3; ++dr) {
+      const Edges<PX> e = edges_of(r, dr);
       const uint32_t iwc = r.ic[dr] | invc[dr] | r.finv | (PX == 2 ? 0xffff0000u : 0u);
-      const uint32_t iwe = (r.il[dr] | (r.ir[dr] << 8)) | inve[dr] | r.finv;
+      const uint32_t iwe = e.iwe | inve[dr] | r.finv;
 #pragma unroll
       for (int c = 0; c < PX + 2; ++c) {
         const uint32_t byte = c == 0 ? (iwe & 0xffu) : c == PX + 1 ? ((iwe >> 8) & 0xffu) : ((iwc >> (8 * (c - 1))) & 0xffu);
-        const float gval = c == 0 ? r.gl[dr] : c == PX + 1 ? r.gr[dr] : r.gc[dr][c - 1];
+        const float gval = c == 0 ? e.gl : c == PX + 1 ? e.gr : r.gc[dr][c - 1];
         v.gv[dr][c] = byte < (uint32_t)g.R ? gval : 0.f;
         v.off[dr][c] = min(byte, (uint32_t)g.R) * 12u + tbase;
       }
@@ -480,27 +507,30 @@ P4BwdGeom p4_bwd_data_geom(const rotconv_plan* p) {
   // routed-gradient table instead of per-bank sums
   g.lut = p4_bwd_lut(p) ? 1 : 0;
   if (g.lut) g.Q = p->B;        // the "banks" of the contraction are the base banks
-  g.ncig = g.CinPad / CIG; g.nrb = (d.H + NWAVE - 1) / NWAVE;
+  g.ncig = g.CinPad / CIG;
+  g.nw = g.lut ? 8 : 4;     // two workgroups of the table variant would not fit LDS
+  g.nrb = (d.H + g.nw - 1) / g.nw;
   // pixels per lane: four when the rows are long enough and that still leaves a workgroup per CU
-  g.px = ((d.W & 3) == 0 && d.W > 32 && d.N * g.ncig * g.nrb * ((d.W + 63) / 64) >= 256) ? 4 : 2;
+  g.px = ((d.W & 3) == 0 && d.W > 32 && d.N * g.ncig * ((d.H + 7) / 8) * ((d.W + 63) / 64) >= 256) ? 4 : 2;
   if (g.lut) g.px = 2;      // the table build is made for two pixels per lane (four would spill)
   g.nstrip = (d.W + 16 * g.px - 1) / (16 * g.px);
   g.units = d.N * g.ncig * g.nstrip * g.nrb;
   // Few units and a long contraction: share its weight chunks (16 filters of a bank) out so that the chip is filled
   // about twice; at least 8 chunks per workgroup, at most 256 MiB of partial sums.
   const int chunks = g.Q * (g.CoutPad / CHUNK);
+  const int full = 256 * 8 / g.nw;      // workgroups that occupy every CU's eight wave slots
   g.ksplit = 1;
-  if (g.units < 256 && chunks >= 16) {
+  if (g.units < full && chunks >= 16) {
     const double dx_bytes = 4.0 * d.N * d.Cin * d.H * d.W;
-    const int want = std::min({chunks / 8, (512 + g.units - 1) / g.units, std::max(1, (int)(268435456.0 / dx_bytes))});
+    const int want = std::min({chunks / 8, (2 * full + g.units - 1) / g.units, std::max(1, (int)(268435456.0 / dx_bytes))});
     g.kper = (chunks + want - 1) / want;
     g.ksplit = (chunks + g.kper - 1) / g.kper;
   }
   // Still far from filling the chip (small maps): go down to two chunks per workgroup, one when dX is tiny, as long
   // as the partial sums stay within 64 MB.
-  if (g.units * g.ksplit < 256 && chunks >= 2) {
+  if (g.units * g.ksplit < full && chunks >= 2) {
     const double dx_bytes = 4.0 * d.N * d.Cin * d.H * d.W;
-    const int want = std::min({chunks / (dx_bytes < 2.0e6 ? 1 : 2), (512 + g.units - 1) / g.units,
+    const int want = std::min({chunks / (dx_bytes < 2.0e6 ? 1 : 2), (2 * full + g.units - 1) / g.units,
                                std::max(1, (int)(67108864.0 / dx_bytes))});
     if (want > g.ksplit) {
       g.kper = (chunks + want - 1) / want;
@@ -538,11 +568,11 @@ void launch_p4_bwd_data(const rotconv_plan* p, const float* gpool, const uint8_t
   const int grid = (g.units + 7) / 8 * 8;
   auto go = [&](auto kern) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(NT), lds, st, gpool, idx, wd, p->dev.rot_of, p->dev.lut_bwd, dx, g);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * g.nw), lds, st, gpool, idx, wd, p->dev.rot_of, p->dev.lut_bwd, dx, g);
   };
-  if (g.px == 4) go(k_p4_bwd_data<4, false>);
-  else if (g.lut) go(k_p4_bwd_data<2, true>);
-  else go(k_p4_bwd_data<2, false>);
+  if (g.px == 4) go(k_p4_bwd_data<4, false, 4>);
+  else if (g.lut) go(k_p4_bwd_data<2, true, 8>);
+  else go(k_p4_bwd_data<2, false, 4>);
   if (g.ksplit > 1) {
     const size_t n_elem = (size_t)p->d.N * p->d.Cin * p->d.H * p->d.W;
     const unsigned blocks = (unsigned)std::max<size_t>(1, std::min<size_t>((n_elem / 4 + 255) / 256, 1u << 16));
