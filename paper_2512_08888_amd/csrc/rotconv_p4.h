@@ -120,7 +120,9 @@ struct P4BwdWGeom {
   int N, Cin, CinPad, H, W, Cout, CoutPad, Q, ng;
   int ncb;     // 16-channel blocks per wave: 4, or 1 for at most 16 input channels
   int ncig;    // groups of 16 * ncb input channels
-  int ncog;    // groups of four (bank, 16-filter block) pairs (one workgroup of 4 waves)
+  int ncg;     // channel groups per workgroup (their waves build a filter block's D together): 1, 2 or 4
+  int ncigw;   // sets of ncg channel groups
+  int ncog;    // groups of 4 / ncg (bank, 16-filter block) pairs (one workgroup of 4 waves)
   int nstrip;    // 32-pixel strips per row
   int rows_per;  // rows per range
   int nrange;    // row ranges per image
@@ -129,7 +131,7 @@ struct P4BwdWGeom {
   int lut, R;    // routed-gradient table: the sums are those of the base bank (Q is 1 then); orientations
 };
 bool p4_bwd_weight_supported(const rotconv_plan* p);
-P4BwdWGeom p4_bwd_weight_geom(const rotconv_plan* p, bool lut = false);
+P4BwdWGeom p4_bwd_weight_geom(const rotconv_plan* p, bool lut = false, bool share = false);
 size_t p4_bwd_weight_ws_floats(const rotconv_plan* p);
 void launch_p4_bwd_weight(const rotconv_plan* p, const float* x, const float* gpool, const uint8_t* idx,
                           float* partial, float* dw, hipStream_t st);

@@ -366,6 +366,271 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_weight(const float* __restrict__ 
   }
 }
 
+// The table variant for layers with more than 64 input channels.  The D of a filter block does not depend on the
+// input channel, and building it (nine table rows from LDS and 81 multiply-adds per pixel and filter) costs about as
+// much as the matrix instructions of one 64-channel group, so the NCG waves that take the NCG channel groups of ONE
+// filter block build each row's D together -- wave cg the pixels [cg 32/NCG, (cg+1) 32/NCG) of the strip, a lane
+// 8/NCG pixels of one filter -- and hand it to each other through LDS ([tap][filter][pixel], fp32, rows of 36 floats;
+// a lane reads its eight pixels of a tap with two 16-byte reads).  A workgroup is 4/NCG filter blocks x NCG channel
+// groups; one barrier per image row (D of row h + 1 goes into the buffer that row h - 1 was read from before the
+// previous barrier), one more between work units.  A row's 288 matrix instructions per wave are spread over the
+// 3 * 8/NCG table-read groups of the build of the next row.
+template <int NCG>
+__global__ __launch_bounds__(NT) void k_p4_bwd_weight_lut_shared(const float* __restrict__ x, const float* __restrict__ gpool,
+                                                                 const uint8_t* __restrict__ idx,
+                                                                 const float* __restrict__ lut,
+                                                                 float* __restrict__ partial, P4BwdWGeom g) {
+  constexpr int NCB = 4;
+  constexpr int NFB = NWAVE / NCG;     // filter blocks per workgroup
+  constexpr int PPL = 8 / NCG;         // pixels of D a lane builds per row
+  constexpr int NGRP = 3 * PPL;        // table-read groups per row and lane
+  constexpr int kLutRows = 33;         // table rows per neighbour offset in LDS (R + 1 <= 33)
+  constexpr int DPITCH = 36;           // floats per (tap, filter) row of D in LDS (32 pixels + padding)
+  extern __shared__ float smem_s[];
+  float* Tl = smem_s;                                      // [2 * 9 * kLutRows * 12]: one table per base bank (at most two)
+  typedef float DBuf[NFB][9][16][DPITCH];                  // [filter block][tap][filter][pixel]
+  DBuf* Dl = reinterpret_cast<DBuf*>(smem_s + 2 * 9 * kLutRows * 12);     // two buffers
+  {
+    const int R1 = g.R + 1;
+    for (int i = threadIdx.x; i < g.Q * 9 * R1 * 12; i += NT) Tl[(i / (R1 * 12)) * (kLutRows * 12) + i % (R1 * 12)] = lut[i];
+    __syncthreads();
+  }
+  const int per_xcd = gridDim.x / 8;
+  int v = gridDim.x % 8 == 0 ? (blockIdx.x % 8) * per_xcd + blockIdx.x / 8 : blockIdx.x;
+  const int cigw = v % g.ncigw; v /= g.ncigw;       // set of NCG channel groups
+  const int fbg = v % g.ncog;                       // group of NFB (bank, 16-filter block) pairs
+  const int split = v / g.ncog;
+
+  const int tid = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid / 64), lane = tid % 64;
+  const int lg = lane / 16, lc = lane % 16;
+  const int cg = wave % NCG, fbw = wave / NCG;      // the wave's channel group and filter block inside the workgroup
+  const int HW = g.H * g.W;
+  const int nfb = g.CoutPad / 16;
+  const int fb_flat = min(fbg * NFB + fbw, g.Q * nfb - 1);          // idle waves redo the last pair
+  const int cig = cigw * NCG + cg;
+  const bool wave_on = fbg * NFB + fbw < g.Q * nfb && cig < g.ncig;
+  const int q = fb_flat / nfb;                       // the wave's base bank
+  const int cobase = (fb_flat % nfb) * 16;
+  const int co = cobase + lc;                        // this lane's filter (D builder and A role)
+  const int ci0 = cig * 16 * NCB + lc;               // this lane's channel in block 0 (B role)
+  const bool cok = co < g.Cout;
+  const size_t gplane0 = (size_t)(cok ? co : 0) * HW;          // one pooled plane per filter
+  const size_t gimg = (size_t)g.Cout * HW;
+  const size_t ximg = (size_t)g.Cin * HW;
+
+  uint32_t xplane[NCB];
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb) {
+    const int ci = ci0 + cb * 16;
+    xplane[cb] = (uint32_t)(ci < g.Cin ? ci : 0) * (uint32_t)HW;
+  }
+
+  f4 acc[9][NCB];
+#pragma unroll
+  for (int u = 0; u < 9; ++u)
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) acc[u][cb] = f4{0.f, 0.f, 0.f, 0.f};
+
+  // (G, idx) of the lane's PPL build pixels and one neighbour per side on one image row, as loaded; and as kept for
+  // the three rows it serves: per column (0 left neighbour, 1..PPL the pixels, PPL + 1 right neighbour) the gradient
+  // (zero where the position or its idx is not valid) and the table-row offset of its idx
+  struct RowS { float gc[PPL]; float gl, gr; uint32_t iw; uint32_t il, ir; };
+  struct LutRowS { float gv[PPL + 2]; uint32_t off[PPL + 2]; };
+  auto lut_route = [&](const RowS& r, bool rok, bool pok, bool lok, bool rok2, LutRowS& m) {
+    const uint32_t ic = (rok && pok) ? r.iw : 0xffffffffu;
+    const uint32_t il = (rok && lok) ? r.il : 0xffu, ir = (rok && rok2) ? r.ir : 0xffu;
+#pragma unroll
+    for (int c = 0; c < PPL + 2; ++c) {
+      const uint32_t byte = c == 0 ? il : c == PPL + 1 ? ir : ((ic >> (8 * (c - 1))) & 0xffu);
+      const float gval = c == 0 ? r.gl : c == PPL + 1 ? r.gr : r.gc[c - 1];
+      m.gv[c] = byte < (uint32_t)g.R ? gval : 0.f;
+      m.off[c] = min(byte, (uint32_t)g.R) * 12u + (uint32_t)q * (9 * kLutRows * 12);
+    }
+  };
+  struct LutT { f4 t0, t1; float t8; };
+  auto lut_read = [&](const LutRowS& row, int dr, int dc, int pc) -> LutT {
+    const float* t = Tl + (dr * 3 + dc) * (kLutRows * 12) + row.off[pc + dc - 1];
+    LutT tv;
+    tv.t0 = *reinterpret_cast<const f4*>(t);
+    tv.t1 = *reinterpret_cast<const f4*>(t + 4);
+    tv.t8 = t[8];
+    return tv;
+  };
+  auto lut_fma = [&](const LutRowS& row, int dr, int dc, int pc, const LutT& tv, float (&d)[9]) {
+    const float gvc = row.gv[pc + dc - 1];
+    const float t9[9] = {tv.t0[0], tv.t0[1], tv.t0[2], tv.t0[3], tv.t1[0], tv.t1[1], tv.t1[2], tv.t1[3], tv.t8};
+#pragma unroll
+    for (int u = 0; u < 9; ++u) d[u] = (dr == 0 && dc == 0) ? gvc * t9[u] : d[u] + gvc * t9[u];
+  };
+
+  for (int unit = split; unit < g.units; unit += g.splits) {
+    int uu = unit;
+    const int strip = uu % g.nstrip; uu /= g.nstrip;
+    const int rng = uu % g.nrange;
+    const int n = uu / g.nrange;
+    const int h0 = rng * g.rows_per, h1 = min(g.H, h0 + g.rows_per);
+    // builder role: PPL pixels of the wave's share of the strip (W % 4 == 0: in or out of the row together)
+    const int bx = cg * (32 / NCG) + lg * PPL;               // first build pixel inside the strip
+    const int bx0 = strip * 32 + bx;
+    const bool bok = bx0 < g.W;
+    const bool lok = bok && bx0 >= 1, rok2 = bx0 + PPL < g.W;
+    const int bc = bok ? bx0 : 0, bl = lok ? bx0 - 1 : 0, br = rok2 ? bx0 + PPL : 0;
+    // operand role: 8 consecutive pixels of the strip, in two halves
+    const int px0 = strip * 32 + 8 * lg;
+    const bool pok0 = px0 < g.W, pok1 = px0 + 4 < g.W;
+    const int pc0 = pok0 ? px0 : 0, pc1 = pok1 ? px0 + 4 : 0;
+    const float* gb = gpool + (size_t)n * gimg + gplane0;
+    const uint8_t* ib = idx + (size_t)n * gimg + gplane0;
+    const float* xb = x + (size_t)n * ximg;
+    const bool tail = strip * 32 + 32 > g.W;       // wave-uniform
+
+    auto row_ok = [&](int h) { return cok && h >= 0 && h < g.H; };
+    auto load_row = [&](int h, RowS& r) {
+      const uint32_t ro = (uint32_t)min(max(h, 0), g.H - 1) * (uint32_t)g.W;
+      if (PPL == 2) {
+        const float2 gv2 = *reinterpret_cast<const float2*>(gb + ro + bc);
+        r.gc[0] = gv2.x; r.gc[1] = gv2.y;
+        r.iw = *reinterpret_cast<const uint16_t*>(ib + ro + bc);
+      } else {
+        const f4 gv4 = *reinterpret_cast<const f4*>(gb + ro + bc);
+#pragma unroll
+        for (int i = 0; i < PPL; ++i) r.gc[i] = gv4[i & 3];
+        r.iw = *reinterpret_cast<const uint32_t*>(ib + ro + bc);
+      }
+      r.gl = gb[ro + bl];
+      r.gr = gb[ro + br];
+      r.il = ib[ro + bl];
+      r.ir = ib[ro + br];
+    };
+    auto lroute = [&](const RowS& r, int h, LutRowS& m) { lut_route(r, row_ok(h), bok, lok, rok2, m); };
+    auto load_x = [&](int h, f4 (&b)[2][NCB]) {
+      const uint32_t ro = (uint32_t)min(h, g.H - 1) * (uint32_t)g.W;
+#pragma unroll
+      for (int cb = 0; cb < NCB; ++cb) {
+        b[0][cb] = *reinterpret_cast<const f4*>(xb + xplane[cb] + ro + pc0);
+        b[1][cb] = *reinterpret_cast<const f4*>(xb + xplane[cb] + ro + pc1);
+      }
+    };
+    auto build_pixel = [&](const LutRowS& ra, const LutRowS& rb, const LutRowS& rc, int pcol, float (&d)[9],
+                           auto&& between) {
+#pragma unroll
+      for (int dr = 0; dr < 3; ++dr) {
+        const LutRowS& row = dr == 0 ? ra : dr == 1 ? rb : rc;
+        LutT tv[3];
+#pragma unroll
+        for (int dc = 0; dc < 3; ++dc) tv[dc] = lut_read(row, dr, dc, pcol);
+        __builtin_amdgcn_sched_barrier(0);
+        between((pcol - 1) * 3 + dr);
+#pragma unroll
+        for (int dc = 0; dc < 3; ++dc) lut_fma(row, dr, dc, pcol, tv[dc], d);
+#pragma unroll
+        for (int u = 0; u < 9; ++u) asm volatile("" : "+v"(d[u]));
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    };
+    // two neighbouring pixels' D -> LDS
+    auto put = [&](int buf, const float (&d0)[9], const float (&d1)[9], int pair) {
+#pragma unroll
+      for (int u = 0; u < 9; ++u)
+        *reinterpret_cast<float2*>(&Dl[buf][fbw][u][lc][bx + 2 * pair]) = make_float2(d0[u], d1[u]);
+    };
+    // the lane's eight pixels of every tap: a[u][j][t] = D of pixel 4 j + t
+    auto get = [&](int buf, f4 (&a)[9][2]) {
+#pragma unroll
+      for (int u = 0; u < 9; ++u) {
+        a[u][0] = *reinterpret_cast<const f4*>(&Dl[buf][fbw][u][lc][8 * lg]);
+        a[u][1] = *reinterpret_cast<const f4*>(&Dl[buf][fbw][u][lc][8 * lg + 4]);
+      }
+    };
+
+    RowS rn;                                          // the row being loaded
+    LutRowS l0, l1, l2;                               // routed rows; the roles rotate
+    f4 bX[2][NCB], bN[2][NCB];                        // X of row h, and of row h + 1 in flight
+    f4 aC[9][2];                                      // D of row h (A operands)
+    int par = 0;                                      // buffer that holds D of the current row
+    // One image row h: (ra, rb, rc) = routed rows (h, h+1, h+2), aC = D(h).  Row h + 3 and X(h + 1) are loaded ahead;
+    // the lane's share of D(h + 1) is built between the matrix instructions of row h and written to the other buffer.
+    auto step = [&](int h, LutRowS& ra, LutRowS& rb, LutRowS& rc) {
+      load_row(h + 3, rn);
+      load_x(h + 1, bN);
+      __builtin_amdgcn_sched_barrier(0);
+      if (tail) {    // X of pixels beyond the row end must be zero: D there gathers in-range neighbours
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb) {
+          bX[0][cb] = pok0 ? bX[0][cb] : f4{0.f, 0.f, 0.f, 0.f};
+          bX[1][cb] = pok1 ? bX[1][cb] : f4{0.f, 0.f, 0.f, 0.f};
+        }
+      }
+      // the 8 x 9 x NCB matrix instructions of row h (K-step = pixel t of half j, K = the four lane groups)
+      auto mfmas = [&](int grp) {
+        constexpr int TOT = 8 * 9 * NCB;
+#pragma unroll
+        for (int i = grp * TOT / NGRP; i < (grp + 1) * TOT / NGRP; ++i) {
+          const int ks = i / (9 * NCB), u = (i / NCB) % 9, cb = i % NCB;
+          acc[u][cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(aC[u][ks / 4][ks % 4], bX[ks / 4][cb][ks % 4], acc[u][cb], 0, 0, 0);
+        }
+      };
+#pragma unroll
+      for (int pr2 = 0; pr2 < PPL / 2; ++pr2) {
+        float d0[9], d1[9];
+        build_pixel(ra, rb, rc, 2 * pr2 + 1, d0, mfmas);
+        build_pixel(ra, rb, rc, 2 * pr2 + 2, d1, mfmas);
+        put(par ^ 1, d0, d1, pr2);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      lroute(rn, h + 3, ra);                          // row h + 3 replaces row h
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb) bX[j][cb] = bN[j][cb];
+      __syncthreads();
+      par ^= 1;
+      get(par, aC);
+    };
+    // prologue: rows h0 - 1, h0, h0 + 1 -> D(h0); then row h0 + 2 takes the place of row h0 - 1
+    load_row(h0 - 1, rn);
+    lroute(rn, h0 - 1, l0);
+    load_row(h0, rn);
+    lroute(rn, h0, l1);
+    load_row(h0 + 1, rn);
+    lroute(rn, h0 + 1, l2);
+    load_x(h0, bX);
+    __syncthreads();          // every wave is done with the buffers of the previous unit
+#pragma unroll
+    for (int pr2 = 0; pr2 < PPL / 2; ++pr2) {
+      float d0[9], d1[9];
+      auto nothing = [](int) {};
+      build_pixel(l0, l1, l2, 2 * pr2 + 1, d0, nothing);
+      build_pixel(l0, l1, l2, 2 * pr2 + 2, d1, nothing);
+      put(0, d0, d1, pr2);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    load_row(h0 + 2, rn);
+    lroute(rn, h0 + 2, l0);
+    __syncthreads();
+    get(0, aC);
+    for (int h = h0; h < h1; h += 3) {
+      step(h, l1, l2, l0);
+      if (h + 1 >= h1) break;
+      step(h + 1, l2, l0, l1);
+      if (h + 2 >= h1) break;
+      step(h + 2, l0, l1, l2);
+    }
+  }
+
+  if (wave_on) {
+    float* out = partial + ((size_t)(split * g.Q + q) * 9) * g.CoutPad * g.CinPad;
+#pragma unroll
+    for (int u = 0; u < 9; ++u)
+#pragma unroll
+      for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          out[((size_t)u * g.CoutPad + cobase + 4 * lg + i) * g.CinPad + cig * 16 * NCB + cb * 16 + lc] = acc[u][cb][i];
+  }
+}
+
 // ---- bfloat16 tensors -------------------------------------------------------------------------------
 // Same work decomposition (units, strips, row ranges, splits, one wave = 16 filters x 64 channels, nine
 // taps x four channel blocks of accumulators) on v_mfma_f32_16x16x32_bf16: M = 16 filters, N = 16
@@ -792,6 +1057,264 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_weight_bf16_lut(const uint16_t* _
   }
 }
 
+// The same kernel for layers with more than 64 input channels: the D of a filter block does not depend on the input
+// channel, and building it (nine table rows from LDS per pixel and filter) is what bounds the kernel above, so the
+// NCG waves that take the NCG channel groups of ONE filter block build each row's D together -- wave cg the pixels
+// [cg 32/NCG, (cg+1) 32/NCG) of the strip, a lane 8/NCG pixels of one filter -- and hand it to each other through
+// LDS as packed bf16 pairs in the A-operand layout ([tap][filter][pixel pair], one 16-byte read per tap and lane).
+// A workgroup is 4/NCG filter blocks x NCG channel groups; one barrier per image row (D of row h + 1 is written into
+// the buffer that row h - 1 was read from before the previous barrier), one more between work units.
+template <int NCB, int NCG, int NW>
+__global__ __launch_bounds__(64 * NW) void k_p4_bwd_weight_bf16_lut_shared(const uint16_t* __restrict__ x,
+                                                                      const uint16_t* __restrict__ gpool,
+                                                                      const uint8_t* __restrict__ idx,
+                                                                      const float* __restrict__ lut,
+                                                                      float* __restrict__ partial, P4BwdWGeom g) {
+  constexpr int NTW = 64 * NW;         // threads per workgroup
+  constexpr int NFB = NW / NCG;        // filter blocks per workgroup
+  constexpr int PPL = 8 / NCG;         // pixels of D a lane builds per row
+  constexpr int NGRP = 3 * PPL;        // table-read groups per row and lane
+  constexpr int kLutRows = 33;         // table rows per neighbour offset in LDS (R + 1 <= 33)
+  extern __shared__ float smem_w[];
+  float* Tl = smem_w;                                      // [2 * 9 * kLutRows * 12]: one table per base bank (at most two)
+  typedef uint32_t DBuf[NFB][9][16][16];                   // [filter block][tap][filter][pixel pair]
+  DBuf* Dl = reinterpret_cast<DBuf*>(smem_w + 2 * 9 * kLutRows * 12);     // two buffers
+  {
+    const int R1 = g.R + 1;
+    for (int i = threadIdx.x; i < g.Q * 9 * R1 * 12; i += NTW) Tl[(i / (R1 * 12)) * (kLutRows * 12) + i % (R1 * 12)] = lut[i];
+    __syncthreads();
+  }
+  const int per_xcd = gridDim.x / 8;
+  int v = gridDim.x % 8 == 0 ? (blockIdx.x % 8) * per_xcd + blockIdx.x / 8 : blockIdx.x;
+  const int cigw = v % g.ncigw; v /= g.ncigw;       // group of NCG channel groups
+  const int fbg = v % g.ncog;                       // group of NFB (bank, 16-filter block) pairs
+  const int split = v / g.ncog;
+
+  const int tid = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid / 64), lane = tid % 64;
+  const int lg = lane / 16, lc = lane % 16;
+  const int cg = wave % NCG, fbw = wave / NCG;      // the wave's channel group and filter block inside the workgroup
+  const int HW = g.H * g.W;
+  const int nfb = g.CoutPad / 16;
+  const int fb_flat = min(fbg * NFB + fbw, g.Q * nfb - 1);          // idle waves redo the last pair
+  const int cig = cigw * NCG + cg;
+  const bool wave_on = fbg * NFB + fbw < g.Q * nfb && cig < g.ncig;
+  const int q = fb_flat / nfb;                       // the wave's base bank
+  const int cobase = (fb_flat % nfb) * 16;
+  const int co = cobase + lc;                        // this lane's filter (D builder and A role)
+  const int ci0 = cig * 16 * NCB + lc;               // this lane's channel in block 0 (B role)
+  const bool cok = co < g.Cout;
+  const size_t gplane0 = (size_t)(cok ? co : 0) * HW;          // one pooled plane per filter
+  const size_t gimg = (size_t)g.Cout * HW;
+  const size_t ximg = (size_t)g.Cin * HW;
+
+  uint32_t xplane[NCB];
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb) {
+    const int ci = ci0 + cb * 16;
+    xplane[cb] = (uint32_t)(ci < g.Cin ? ci : 0) * (uint32_t)HW;
+  }
+
+  f4 acc[9][NCB];
+#pragma unroll
+  for (int u = 0; u < 9; ++u)
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) acc[u][cb] = f4{0.f, 0.f, 0.f, 0.f};
+
+  // (G, idx) of the lane's PPL build pixels and one neighbour per side on one image row, as loaded; and as kept for
+  // the three rows it serves: per column (0 left neighbour, 1..PPL the pixels, PPL + 1 right neighbour) the gradient
+  // (zero where the position or its idx is not valid) and the table-row offset of its idx
+  struct RowS { uint32_t gw[PPL / 2]; uint16_t gl, gr; uint32_t iw; uint8_t il, ir; };
+  struct LutRowS { float gv[PPL + 2]; uint32_t off[PPL + 2]; };
+  auto lut_route = [&](const RowS& r, bool rok, bool pok, bool lok, bool rok2, LutRowS& m) {
+    const uint32_t ic = (rok && pok) ? r.iw : 0xffffffffu;
+    const uint32_t il = (rok && lok) ? (uint32_t)r.il : 0xffu, ir = (rok && rok2) ? (uint32_t)r.ir : 0xffu;
+#pragma unroll
+    for (int c = 0; c < PPL + 2; ++c) {
+      const uint32_t byte = c == 0 ? il : c == PPL + 1 ? ir : ((ic >> (8 * (c - 1))) & 0xffu);
+      // bf16 -> fp32: the pair word's low half is the even pixel
+      const uint32_t bits = c == 0 ? ((uint32_t)r.gl << 16) : c == PPL + 1 ? ((uint32_t)r.gr << 16)
+                            : ((c - 1) & 1) ? (r.gw[(c - 1) / 2] & 0xffff0000u) : (r.gw[(c - 1) / 2] << 16);
+      m.gv[c] = byte < (uint32_t)g.R ? __uint_as_float(bits) : 0.f;
+      m.off[c] = min(byte, (uint32_t)g.R) * 12u + (uint32_t)q * (9 * kLutRows * 12);
+    }
+  };
+  struct LutT { f4 t0, t1; float t8; };
+  auto lut_read = [&](const LutRowS& row, int dr, int dc, int pc) -> LutT {
+    const float* t = Tl + (dr * 3 + dc) * (kLutRows * 12) + row.off[pc + dc - 1];
+    LutT tv;
+    tv.t0 = *reinterpret_cast<const f4*>(t);
+    tv.t1 = *reinterpret_cast<const f4*>(t + 4);
+    tv.t8 = t[8];
+    return tv;
+  };
+  auto lut_fma = [&](const LutRowS& row, int dr, int dc, int pc, const LutT& tv, float (&d)[9]) {
+    const float gvc = row.gv[pc + dc - 1];
+    const float t9[9] = {tv.t0[0], tv.t0[1], tv.t0[2], tv.t0[3], tv.t1[0], tv.t1[1], tv.t1[2], tv.t1[3], tv.t8};
+#pragma unroll
+    for (int u = 0; u < 9; ++u) d[u] = (dr == 0 && dc == 0) ? gvc * t9[u] : d[u] + gvc * t9[u];
+  };
+
+  for (int unit = split; unit < g.units; unit += g.splits) {
+    int uu = unit;
+    const int strip = uu % g.nstrip; uu /= g.nstrip;
+    const int rng = uu % g.nrange;
+    const int n = uu / g.nrange;
+    const int h0 = rng * g.rows_per, h1 = min(g.H, h0 + g.rows_per);
+    // builder role: PPL pixels of the wave's share of the strip
+    const int bpair = cg * (16 / NCG) + lg * (PPL / 2);      // first pixel pair of the lane inside the strip
+    const int bx0 = strip * 32 + 2 * bpair;
+    const bool bok = bx0 < g.W;                               // W % 8 == 0: the lane's pixels are in or out together
+    const bool lok = bok && bx0 >= 1, rok2 = bx0 + PPL < g.W;
+    const int bc = bok ? bx0 : 0, bl = lok ? bx0 - 1 : 0, br = rok2 ? bx0 + PPL : 0;
+    // operand role: 8 consecutive pixels of the strip
+    const int px0 = strip * 32 + 8 * lg;
+    const bool pok = px0 < g.W;
+    const int pc = pok ? px0 : 0;
+    const uint16_t* gb = gpool + (size_t)n * gimg + gplane0;
+    const uint8_t* ib = idx + (size_t)n * gimg + gplane0;
+    const uint16_t* xb = x + (size_t)n * ximg;
+    const bool tail = strip * 32 + 32 > g.W;       // wave-uniform
+
+    auto row_ok = [&](int h) { return cok && h >= 0 && h < g.H; };
+    auto load_row = [&](int h, RowS& r) {
+      const uint32_t ro = (uint32_t)min(max(h, 0), g.H - 1) * (uint32_t)g.W;
+      if (PPL == 2) {
+        r.gw[0] = *reinterpret_cast<const uint32_t*>(gb + ro + bc);
+        r.iw = *reinterpret_cast<const uint16_t*>(ib + ro + bc);
+      } else {
+        const uint2 gv2 = *reinterpret_cast<const uint2*>(gb + ro + bc);
+        r.gw[0] = gv2.x; r.gw[PPL / 2 - 1] = gv2.y;
+        r.iw = *reinterpret_cast<const uint32_t*>(ib + ro + bc);
+      }
+      r.gl = gb[ro + bl];
+      r.gr = gb[ro + br];
+      r.il = ib[ro + bl];
+      r.ir = ib[ro + br];
+    };
+    auto lroute = [&](const RowS& r, int h, LutRowS& m) { lut_route(r, row_ok(h), bok, lok, rok2, m); };
+    auto load_x = [&](int h, u4 (&b)[NCB]) {
+      const uint32_t off = (uint32_t)min(h, g.H - 1) * (uint32_t)g.W + (uint32_t)pc;
+#pragma unroll
+      for (int cb = 0; cb < NCB; ++cb) b[cb] = *reinterpret_cast<const u4*>(xb + xplane[cb] + off);
+    };
+    // D of pixel column pcol (1..PPL) from the rows (above, at, below): three groups (one per row) of three table-row
+    // reads and 27 multiply-adds, `between(group)` issued between a group's reads and its multiply-adds; fences and
+    // opaque uses as in the kernel above
+    auto build_pixel = [&](const LutRowS& ra, const LutRowS& rb, const LutRowS& rc, int pcol, float (&d)[9],
+                           auto&& between) {
+#pragma unroll
+      for (int dr = 0; dr < 3; ++dr) {
+        const LutRowS& row = dr == 0 ? ra : dr == 1 ? rb : rc;
+        LutT tv[3];
+#pragma unroll
+        for (int dc = 0; dc < 3; ++dc) tv[dc] = lut_read(row, dr, dc, pcol);
+        __builtin_amdgcn_sched_barrier(0);
+        between((pcol - 1) * 3 + dr);
+#pragma unroll
+        for (int dc = 0; dc < 3; ++dc) lut_fma(row, dr, dc, pcol, tv[dc], d);
+#pragma unroll
+        for (int u = 0; u < 9; ++u) asm volatile("" : "+v"(d[u]));
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    };
+    // a pixel pair's D -> LDS (bf16 pairs), A-operand layout
+    auto put = [&](int buf, const float (&d0)[9], const float (&d1)[9], int pair) {
+#pragma unroll
+      for (int u = 0; u < 9; ++u) {
+        typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
+        bf2 pr2;
+        pr2[0] = (__bf16)d0[u];
+        pr2[1] = (__bf16)d1[u];
+        Dl[buf][fbw][u][lc][bpair + pair] = __builtin_bit_cast(uint32_t, pr2);
+      }
+    };
+    auto get = [&](int buf, u4 (&a)[9]) {
+#pragma unroll
+      for (int u = 0; u < 9; ++u) a[u] = *reinterpret_cast<const u4*>(&Dl[buf][fbw][u][lc][4 * lg]);
+    };
+
+    RowS rn;                                          // the row being loaded
+    LutRowS l0, l1, l2;                               // routed rows; the roles rotate
+    u4 bX[NCB], bN[NCB];                              // X of row h, and of row h + 1 in flight
+    u4 aC[9];                                         // D of row h (A operands)
+    int par = 0;                                      // buffer that holds D of the current row
+    // One image row h: (ra, rb, rc) = routed rows (h, h+1, h+2), aC = D(h).  Row h + 3 and X(h + 1) are loaded ahead;
+    // the lane's share of D(h + 1) is built between the matrix instructions of row h and written to the other buffer.
+    auto step = [&](int h, LutRowS& ra, LutRowS& rb, LutRowS& rc) {
+      load_row(h + 3, rn);
+      load_x(h + 1, bN);
+      __builtin_amdgcn_sched_barrier(0);
+      if (tail) {    // X of pixels beyond the row end must be zero: D there gathers in-range neighbours
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb) bX[cb] = pok ? bX[cb] : u4{0u, 0u, 0u, 0u};
+      }
+      auto mfmas = [&](int grp) {
+        constexpr int TOT = 9 * NCB;
+#pragma unroll
+        for (int i = grp * TOT / NGRP; i < (grp + 1) * TOT / NGRP; ++i)
+          acc[i / NCB][i % NCB] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf8, aC[i / NCB]),
+                                                                          __builtin_bit_cast(bf8, bX[i % NCB]),
+                                                                          acc[i / NCB][i % NCB], 0, 0, 0);
+      };
+#pragma unroll
+      for (int pr2 = 0; pr2 < PPL / 2; ++pr2) {
+        float d0[9], d1[9];
+        build_pixel(ra, rb, rc, 2 * pr2 + 1, d0, mfmas);
+        build_pixel(ra, rb, rc, 2 * pr2 + 2, d1, mfmas);
+        put(par ^ 1, d0, d1, pr2);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      lroute(rn, h + 3, ra);                          // row h + 3 replaces row h
+#pragma unroll
+      for (int cb = 0; cb < NCB; ++cb) bX[cb] = bN[cb];
+      __syncthreads();
+      par ^= 1;
+      get(par, aC);
+    };
+    // prologue: rows h0 - 1, h0, h0 + 1 -> D(h0); then row h0 + 2 takes the place of row h0 - 1
+    load_row(h0 - 1, rn);
+    lroute(rn, h0 - 1, l0);
+    load_row(h0, rn);
+    lroute(rn, h0, l1);
+    load_row(h0 + 1, rn);
+    lroute(rn, h0 + 1, l2);
+    load_x(h0, bX);
+    __syncthreads();          // every wave is done with the buffers of the previous unit
+#pragma unroll
+    for (int pr2 = 0; pr2 < PPL / 2; ++pr2) {
+      float d0[9], d1[9];
+      auto nothing = [](int) {};
+      build_pixel(l0, l1, l2, 2 * pr2 + 1, d0, nothing);
+      build_pixel(l0, l1, l2, 2 * pr2 + 2, d1, nothing);
+      put(0, d0, d1, pr2);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    load_row(h0 + 2, rn);
+    lroute(rn, h0 + 2, l0);
+    __syncthreads();
+    get(0, aC);
+    for (int h = h0; h < h1; h += 3) {
+      step(h, l1, l2, l0);
+      if (h + 1 >= h1) break;
+      step(h + 1, l2, l0, l1);
+      if (h + 2 >= h1) break;
+      step(h + 2, l0, l1, l2);
+    }
+  }
+
+  if (wave_on) {
+    float* out = partial + ((size_t)(split * g.Q + q) * 9) * g.CoutPad * g.CinPad;
+#pragma unroll
+    for (int u = 0; u < 9; ++u)
+#pragma unroll
+      for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          out[((size_t)u * g.CoutPad + cobase + 4 * lg + i) * g.CinPad + cig * 16 * NCB + cb * 16 + lc] = acc[u][cb][i];
+  }
+}
+
 // Stage 1: sum the splits.  A block covers 32 consecutive elements x 8 interleaved split groups;
 // each thread adds its splits in ascending order, the groups are combined in a fixed tree, so
 // the result does not depend on scheduling.  out[e] = sum_split partial[split][e].
@@ -861,7 +1384,7 @@ bool p4_bwd_weight_supported(const rotconv_plan* p) {
   return p4_fwd_pool_mode(p) != kOutUnpooled;
 }
 
-P4BwdWGeom p4_bwd_weight_geom(const rotconv_plan* p, bool lut) {
+P4BwdWGeom p4_bwd_weight_geom(const rotconv_plan* p, bool lut, bool share) {
   const rotconv_desc& d = p->d;
   P4BwdWGeom g{};
   g.N = d.N; g.Cin = d.Cin; g.H = d.H; g.W = d.W; g.Cout = d.Cout; g.Q = lut ? p->B : p->host.Q; g.ng = p->ng;
@@ -871,9 +1394,15 @@ P4BwdWGeom p4_bwd_weight_geom(const rotconv_plan* p, bool lut) {
   g.CinPad = (d.Cin + 16 * NCB - 1) / (16 * NCB) * (16 * NCB);
   g.CoutPad = (d.Cout + 15) / 16 * 16;
   g.ncig = g.CinPad / (16 * NCB);
-  g.ncog = (g.Q * (g.CoutPad / 16) + NWAVE - 1) / NWAVE;   // workgroups per channel group and split
+  // channel groups whose waves build a filter block's D together (the bf16 table kernel; elsewhere one).  Measured
+  // on the 512 x 512 stack: four groups of 64 channels 0.145 ms against 0.21 ms unshared; groups of 32 channels with
+  // eight waves (two per SIMD) 0.19 ms: the sharing factor outweighs the occupancy
+  g.ncg = share && lut ? (g.ncig >= 3 ? 4 : g.ncig == 2 ? 2 : 1) : 1;
+  g.ncigw = (g.ncig + g.ncg - 1) / g.ncg;
+  const int nfb_wg = NWAVE / g.ncg;                          // (bank, 16-filter block) pairs per workgroup
+  g.ncog = (g.Q * (g.CoutPad / 16) + nfb_wg - 1) / nfb_wg;   // workgroups per channel-group set and split
   // work units: (image, row range, 32-pixel strip); a range never crosses an image
-  const int combos = g.ncig * g.ncog;
+  const int combos = g.ncigw * g.ncog;
   g.nstrip = (d.W + 31) / 32;
   const int want = (256 + combos - 1) / combos;                       // units wanted to fill the chip
   int per_image = std::max(1, std::min(d.H, (want + d.N * g.nstrip - 1) / (d.N * g.nstrip)));
@@ -891,9 +1420,9 @@ bool p4_bwd_weight_bf16_supported(const rotconv_plan* p) { return p4_bwd_weight_
 
 size_t p4_bwd_weight_ws_floats(const rotconv_plan* p) {
   size_t need = 0;
-  for (int lut = 0; lut < 2; ++lut) {     // the per-bank kernels (also the bf16 one) and the table variant
+  for (int lut = 0; lut < 3; ++lut) {     // the per-bank kernels (also the bf16 one), the table variant, its shared-D form
     if (lut && !p4_bwd_lut(p) && !p->bwd_lut16[2]) break;
-    const P4BwdWGeom g = p4_bwd_weight_geom(p, lut != 0);
+    const P4BwdWGeom g = p4_bwd_weight_geom(p, lut != 0, lut == 2);
     need = std::max(need, (size_t)(g.splits + 1) * g.Q * 9 * g.CoutPad * g.CinPad);  // partial sums + their total
   }
   return need;
@@ -917,8 +1446,19 @@ static void finish_dw(const rotconv_plan* p, const P4BwdWGeom& g, float* partial
 
 void launch_p4_bwd_weight(const rotconv_plan* p, const float* x, const float* gpool, const uint8_t* idx,
                           float* partial, float* dw, hipStream_t st) {
-  const P4BwdWGeom g = p4_bwd_weight_geom(p, p4_bwd_lut(p));
-  const int grid = g.splits * g.ncig * g.ncog;
+  const P4BwdWGeom g = p4_bwd_weight_geom(p, p4_bwd_lut(p), true);
+  const int grid = g.splits * g.ncigw * g.ncog;
+  if (g.ncg > 1) {          // table variant, the channel groups of a filter block build its D together
+    auto gos = [&](auto kern) {
+      const size_t lds = ((size_t)2 * 9 * 33 * 12 + (size_t)2 * (NWAVE / g.ncg) * 9 * 16 * 36) * sizeof(float);
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      hipLaunchKernelGGL(kern, dim3(grid), dim3(NT), lds, st, x, gpool, idx, p->dev.lut_bwd, partial, g);
+    };
+    if (g.ncg == 4) gos(k_p4_bwd_weight_lut_shared<4>);
+    else gos(k_p4_bwd_weight_lut_shared<2>);
+    finish_dw(p, g, partial, dw, st);
+    return;
+  }
   auto go = [&](auto kern) {
     hipLaunchKernelGGL(kern, dim3(grid), dim3(NT), 0, st, x, gpool, idx, p->dev.rot_of, p->dev.lut_bwd, partial, g);
   };
@@ -930,8 +1470,19 @@ void launch_p4_bwd_weight(const rotconv_plan* p, const float* x, const float* gp
 void launch_p4_bwd_weight_bf16(const rotconv_plan* p, const uint16_t* x, const uint16_t* gpool, const uint8_t* idx,
                                float* partial, float* dw, hipStream_t st) {
   if (p->bwd_lut16[2]) {      // routed-gradient table: one contraction with the base bank
-    const P4BwdWGeom g = p4_bwd_weight_geom(p, true);
-    const int grid = g.splits * g.ncig * g.ncog;
+    const P4BwdWGeom g = p4_bwd_weight_geom(p, true, true);
+    const int grid = g.splits * g.ncigw * g.ncog;
+    if (g.ncg > 1) {          // the channel groups of a filter block build its D together
+      auto go = [&](auto kern, int nw) {
+        const size_t lds = (size_t)2 * 9 * 33 * 12 * 4 + (size_t)2 * (nw / g.ncg) * 9 * 16 * 16 * 4;
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * nw), lds, st, x, gpool, idx, p->dev.lut_bwd, partial, g);
+      };
+      if (g.ncg == 4) go(k_p4_bwd_weight_bf16_lut_shared<4, 4, 4>, 4);
+      else go(k_p4_bwd_weight_bf16_lut_shared<4, 2, 4>, 4);
+      finish_dw(p, g, partial, dw, st);
+      return;
+    }
     if (g.ncb == 1) hipLaunchKernelGGL(k_p4_bwd_weight_bf16_lut<1>, dim3(grid), dim3(NT), 0, st, x, gpool, idx, p->dev.lut_bwd, partial, g);
     else hipLaunchKernelGGL(k_p4_bwd_weight_bf16_lut<4>, dim3(grid), dim3(NT), 0, st, x, gpool, idx, p->dev.lut_bwd, partial, g);
     finish_dw(p, g, partial, dw, st);

@@ -46,6 +46,11 @@ CASES = [
     # the table gradient kernels: two channel groups of 128, filters padded to a K-step, rows that end inside a lane
     # group (the weight gradient of this width runs on widened copies)
     LC("b_lut_w44", N=1, Cin=136, H=6, W=44, Cout=40, R=16, mode="bilinear", x_dist="absnormal", seed=75),
+    # the weight gradient whose channel groups build a filter block's D together: two groups; five groups (two sets
+    # of four, the second mostly empty) over several units; two base banks
+    LC("b_lut_c128", N=1, Cin=128, H=7, W=40, Cout=24, R=16, mode="bilinear", x_dist="absnormal", seed=76),
+    LC("b_lut_c320", N=2, Cin=320, H=9, W=72, Cout=40, R=16, mode="bilinear", x_dist="absnormal", seed=77),
+    LC("b_lut_ste_c192", N=1, Cin=192, H=6, W=32, Cout=20, R=16, mode="steerable", x_dist="absnormal", seed=78),
     # a layer on which one arg-max sat just outside the fp32 near-tie band when the rotated weights were formed in fp32
     # (one of them rounded to the neighbouring bf16 value); they are formed in fp64 now: the regression case
     LC("b_r16_bank_rounding", N=2, Cin=32, H=19, W=160, Cout=136, R=16, mode="bilinear", x_dist="absnormal", seed=9148),

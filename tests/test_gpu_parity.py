@@ -54,6 +54,10 @@ TINY = [
     LC("t_cin256", N=1, Cin=256, H=10, W=32, Cout=18, R=4, seed=36),
     LC("t_cin288_r16", N=1, Cin=288, H=9, W=64, Cout=16, R=16, mode="bilinear", seed=37),
     LC("t_cin288_w96", N=1, Cin=288, H=6, W=96, Cout=8, R=4, seed=42),     # streamed block, chain beyond the row
+    # table weight gradient with a filter block's D built by its channel groups together: two groups and a row tail;
+    # three groups and two base banks
+    LC("t_lut_c136_w44", N=2, Cin=136, H=7, W=44, Cout=20, R=16, mode="bilinear", seed=43),
+    LC("t_lut_ste_c192", N=1, Cin=192, H=6, W=32, Cout=20, R=16, mode="steerable", seed=46),
     LC("t_w544_cin6", N=1, Cin=6, H=6, W=544, Cout=16, R=8, mode="steerable", pool_group=4, seed=38),
     # the p4m group (rotations and reflection): the mirrored filter is a second bank of the same kernels
     LC("t_p4m", N=2, Cin=5, H=10, W=12, Cout=6, R=8, mode="p4m", seed=44),
@@ -193,7 +197,7 @@ def test_gemm_scatter_family_is_the_default_for_larger_layers():
     assert [L.plan.kernel_name(i) for i in range(3)] == ["mfma_gemm_scatter"] * 3
 
 
-LUT_CASES = ["t_r8bil", "t_r16bil", "t_r3irr", "t_cin288_r16", "t_p4m", "t_p4m_c40", "t_ksplit_q2", "t_padw_r16", "t_csplit_r16"]
+LUT_CASES = ["t_r8bil", "t_r16bil", "t_r3irr", "t_cin288_r16", "t_lut_c136_w44", "t_lut_ste_c192", "t_p4m", "t_p4m_c40", "t_ksplit_q2", "t_padw_r16", "t_csplit_r16"]
 
 
 @pytest.mark.parametrize("name", LUT_CASES)
