@@ -27,42 +27,57 @@ __global__ __launch_bounds__(256) void k_p4_pack_base(const float* __restrict__ 
   for (int u = 0; u < 9; ++u) dst[u * 16] = in ? src[u] : 0.f;
 }
 
-bool needs_stream_base(int Cin) { return (size_t)cin_pad_base(Cin) * 576 + 2 * 2 * 8 * 144 * 4 > 160 * 1024; }
+// LDS beside the filter block: the edge arrays, and with `park` banks' second rolling sums parked there 16 bytes per
+// bank, quarter turn and thread (eight waves)
+size_t base_lds_extra(int park) { return (size_t)2 * 2 * 8 * 144 * 4 + (size_t)park * 4 * 512 * 16; }
+bool needs_stream_base(int Cin, int park = 0) { return (size_t)cin_pad_base(Cin) * 576 + base_lds_extra(park) > 160 * 1024; }
+// rows a streamed filter block takes: only those the wave chains cover exactly
+bool stream_rows_ok(int W) { return (W & 15) == 0 && (W > 128 || (W & (W - 1)) == 0); }
+// Banks whose second rolling sum is parked in LDS: three of the four of an R = 16 layer (the benchmark instance then
+// keeps 80 instead of 128 sums in registers across the channel loop and no longer spills), when the filter block
+// still fits beside them or may be streamed.
+int base_park(const rotconv_plan* p) {
+  if (p->host.Q != 4) return 0;
+  if (!needs_stream_base(p->d.Cin, 3)) return 3;
+  if (!needs_stream_base(p->d.Cin, 2)) return 2;      // two banks parked, the filter block still resident
+  if (!stream_rows_ok(p->d.W)) return 0;
+  return 3;
+}
 
-template <int NWX, int NWY, bool FASTW, bool STREAM, int KC, int NQ, int CLS>
+template <int NWX, int NWY, bool FASTW, bool STREAM, int KC, int NQ, int CLS, int PARK>
 void launch_i(const P4Geom& g, const float* x, const float* wt, const float* coef, const int32_t* rot_of, float* ov,
               uint8_t* oi, hipStream_t st) {
   const size_t wfl = STREAM ? (size_t)2 * KC * 4 * 144 : (size_t)g.cper * KC * 4 * 144;
-  const size_t lds = (wfl + 4 * NWX * NWY * 144) * sizeof(float);
+  const size_t lds = (wfl + 4 * NWX * NWY * 144) * sizeof(float) + (size_t)PARK * 4 * 64 * NWX * NWY * 16;
   const int grid = (g.units + 7) / 8 * 8;
-  auto kern = k_p4_fwd_base<NWX, NWY, FASTW, STREAM, KC, NQ, CLS>;
+  auto kern = k_p4_fwd_base<NWX, NWY, FASTW, STREAM, KC, NQ, CLS, PARK>;
   (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * NWX * NWY), lds, st, x, wt, coef, rot_of, ov, oi, g);
 }
 
-template <int NWX, int NWY, int NQ, int CLS>
+template <int NWX, int NWY, int NQ, int CLS, int PARK>
 void launch_t(const P4Geom& g, bool fastw, bool stream, const float* x, const float* wt, const float* coef,
               const int32_t* rot_of, float* ov, uint8_t* oi, hipStream_t st) {
   if (g.CinPad == 4) {
-    if (fastw) launch_i<NWX, NWY, true, false, 1, NQ, CLS>(g, x, wt, coef, rot_of, ov, oi, st);
-    else launch_i<NWX, NWY, false, false, 1, NQ, CLS>(g, x, wt, coef, rot_of, ov, oi, st);
+    if (fastw) launch_i<NWX, NWY, true, false, 1, NQ, CLS, PARK>(g, x, wt, coef, rot_of, ov, oi, st);
+    else launch_i<NWX, NWY, false, false, 1, NQ, CLS, PARK>(g, x, wt, coef, rot_of, ov, oi, st);
   } else if (stream) {
-    if (fastw) launch_i<NWX, NWY, true, true, 8, NQ, CLS>(g, x, wt, coef, rot_of, ov, oi, st);
-    else launch_i<NWX, NWY, false, true, 8, NQ, CLS>(g, x, wt, coef, rot_of, ov, oi, st);
+    if (fastw) launch_i<NWX, NWY, true, true, 8, NQ, CLS, PARK>(g, x, wt, coef, rot_of, ov, oi, st);
+    else launch_i<NWX, NWY, false, true, 8, NQ, CLS, PARK>(g, x, wt, coef, rot_of, ov, oi, st);
   } else {
-    if (fastw) launch_i<NWX, NWY, true, false, 8, NQ, CLS>(g, x, wt, coef, rot_of, ov, oi, st);
-    else launch_i<NWX, NWY, false, false, 8, NQ, CLS>(g, x, wt, coef, rot_of, ov, oi, st);
+    if (fastw) launch_i<NWX, NWY, true, false, 8, NQ, CLS, PARK>(g, x, wt, coef, rot_of, ov, oi, st);
+    else launch_i<NWX, NWY, false, false, 8, NQ, CLS, PARK>(g, x, wt, coef, rot_of, ov, oi, st);
   }
 }
 
-template <int NQ, int CLS>
+template <int NQ, int CLS, int PARK>
 void launch_c(const P4Geom& g, bool fastw, bool stream, const float* x, const float* wt, const float* coef,
               const int32_t* rot_of, float* ov, uint8_t* oi, hipStream_t st) {
   switch (g.nwx) {
-    case 1: launch_t<1, 8, NQ, CLS>(g, fastw, stream, x, wt, coef, rot_of, ov, oi, st); break;
-    case 2: launch_t<2, 4, NQ, CLS>(g, fastw, stream, x, wt, coef, rot_of, ov, oi, st); break;
-    case 4: launch_t<4, 2, NQ, CLS>(g, fastw, stream, x, wt, coef, rot_of, ov, oi, st); break;
-    default: launch_t<8, 1, NQ, CLS>(g, fastw, stream, x, wt, coef, rot_of, ov, oi, st); break;
+    case 1: launch_t<1, 8, NQ, CLS, PARK>(g, fastw, stream, x, wt, coef, rot_of, ov, oi, st); break;
+    case 2: launch_t<2, 4, NQ, CLS, PARK>(g, fastw, stream, x, wt, coef, rot_of, ov, oi, st); break;
+    case 4: launch_t<4, 2, NQ, CLS, PARK>(g, fastw, stream, x, wt, coef, rot_of, ov, oi, st); break;
+    default: launch_t<8, 1, NQ, CLS, PARK>(g, fastw, stream, x, wt, coef, rot_of, ov, oi, st); break;
   }
 }
 
@@ -190,8 +205,9 @@ bool p4_fwd_base_supported(const rotconv_plan* p) {
   if (d.k != 3 || d.stride != 1 || d.pad != 1 || d.dtype != ROTCONV_F32 || d.pool_op != ROTCONV_POOL_MAX) return false;
   if (p->ng != 1 || p->opt.fwd_base < 0) return false;
   if ((d.W & 1) || (d.W > 128 && (d.W & 15))) return false;
+  if ((double)d.Cin * d.H * d.W >= 1073741824.0) return false;     // 32-bit element offsets inside an image
   // a streamed filter block: only rows that the wave chains cover exactly
-  if (needs_stream_base(d.Cin) && ((d.W & 15) || (d.W <= 128 && (d.W & (d.W - 1))))) return false;
+  if (needs_stream_base(d.Cin) && !stream_rows_ok(d.W)) return false;
   const int Q = p->host.Q;
   for (int i = 0; i < Q * 4; ++i)
     if (p->rot_of[i] < 0) return false;
@@ -214,16 +230,19 @@ void launch_p4_fwd_base(const rotconv_plan* p, const float* x, const float* wt, 
                         hipStream_t st) {
   P4Geom gs[8];
   const int ng = base_geoms(p, gs, 8);
-  const bool stream = needs_stream_base(p->d.Cin);
+  const int park = base_park(p);
+  const bool stream = needs_stream_base(p->d.Cin, park);
   const int cls = p->fwd_base_cls;
   const float* coef = p->dev.fwd_base_coef;
   const int32_t* rot_of = p->dev.rot_of;
   for (int i = 0; i < ng; ++i) {
     const P4Geom& g = gs[i];
     const bool fastw = (p->d.W & 3) == 0 && g.inside;
-    if (cls == kCls16) launch_c<4, kCls16>(g, fastw, stream, x, wt, coef, rot_of, ypool, idx, st);
-    else if (cls == kCls8) launch_c<2, kCls8>(g, fastw, stream, x, wt, coef, rot_of, ypool, idx, st);
-    else launch_c<2, kClsP4m>(g, fastw, stream, x, wt, coef, rot_of, ypool, idx, st);
+    if (cls == kCls16 && park == 3) launch_c<4, kCls16, 3>(g, fastw, stream, x, wt, coef, rot_of, ypool, idx, st);
+    else if (cls == kCls16 && park == 2) launch_c<4, kCls16, 2>(g, fastw, stream, x, wt, coef, rot_of, ypool, idx, st);
+    else if (cls == kCls16) launch_c<4, kCls16, 0>(g, fastw, stream, x, wt, coef, rot_of, ypool, idx, st);
+    else if (cls == kCls8) launch_c<2, kCls8, 0>(g, fastw, stream, x, wt, coef, rot_of, ypool, idx, st);
+    else launch_c<2, kClsP4m, 0>(g, fastw, stream, x, wt, coef, rot_of, ypool, idx, st);
   }
 }
 

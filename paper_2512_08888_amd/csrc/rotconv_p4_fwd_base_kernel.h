@@ -61,7 +61,10 @@ int cin_pad_base(int Cin) { return Cin <= 4 ? 4 : (Cin + 31) / 32 * 32; }
 // STREAM: the filter block does not fit LDS: streamed in 32-channel chunks (double buffered).
 // KC:     K-steps (of 4 channels) per prefetch chunk: 8, or 1 for layers with at most 4 input channels.
 // NQ:     banks; CLS: their classes, two bits each.
-template <int NWX, int NWY, bool FASTW, bool STREAM, int KC, int NQ, int CLS>
+// PARK:   banks (the last PARK of them) whose second rolling sum lives in LDS between the row that starts it and the
+//         row that continues it, a lane's own slots ([bank][quarter turn][thread] x four pixels): 16 PARK registers
+//         less to keep across the channel loop.
+template <int NWX, int NWY, bool FASTW, bool STREAM, int KC, int NQ, int CLS, int PARK>
 __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd_base(const float* __restrict__ x,
                                                                 const float* __restrict__ wt,
                                                                 const float* __restrict__ coef,
@@ -75,6 +78,7 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd_base(const float* __r
   float* Wl = smem;                      // resident: [CinPad][9][16]; streamed: [2][32][9][16]
   float* EL = smem + (STREAM ? 2 * CHF : g.cper * CHF);    // [2][NW][9][16] left-edge products of every wave
   float* ER = EL + 2 * NW * 144;         // [2][NW][9][16] right-edge products
+  f4* PK = reinterpret_cast<f4*>(ER + 2 * NW * 144) + threadIdx.x;   // [PARK][4][NT] parked sums, this thread's column
 
   // XCD-aware unit decode: consecutive units (same image rows, different filter blocks) share an XCD's L2.
   const int per_xcd = (g.units + 7) / 8;
@@ -132,33 +136,43 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd_base(const float* __r
   // A-operand loads: lane (lc, lg) reads X[ci = 4*kstep + lg][h][x0 + lc].  Rows outside the image are loaded from
   // the clamped row and their products discarded; channels beyond Cin meet zero filter taps; pixels beyond W read
   // as zero (only possible without FASTW).
+  // The address is the image's base (wave-uniform) plus a 32-bit element offset: row (uniform) + channel + lane pixel
+  // (an image has fewer than 2^30 elements: checked when the plan takes this kernel).
   const int pxa = x0 + lc;
   const bool px_ok = pxa < g.W;
-  const float* xn = x + (size_t)n * g.Cin * HW + (px_ok ? pxa : 0);
+  const float* xn = x + (size_t)n * g.Cin * HW;
+  const uint32_t lane_px = (uint32_t)(px_ok ? pxa : 0);
   uint32_t lgoff = (uint32_t)lg * (uint32_t)HW;
   asm volatile("" : "+v"(lgoff));   // opaque: keeps the K-step part of the offset scalar
   const uint32_t off_last = (uint32_t)(g.Cin - 1) * (uint32_t)HW;
-  auto row_ptr = [&](int t) -> const float* {
+  auto row_ptr = [&](int t) -> uint32_t {          // element offset of the (clamped) row
     const int h = min(max(y0 - 1 + t, 0), g.H - 1);
-    return xn + (size_t)h * g.W;
+    return (uint32_t)h * (uint32_t)g.W;
   };
-  auto load_a = [&](const float* rp, int kstep) -> float {
-    const uint32_t off = min((uint32_t)(kstep * 4) * (uint32_t)HW + lgoff, off_last);
-    const float v1 = rp[off];
+  auto load_a = [&](uint32_t rp, int kstep) -> float {
+    const uint32_t off = min((uint32_t)(kstep * 4) * (uint32_t)HW + lgoff, off_last) + lane_px;
+    const float v1 = xn[off + rp];
     if (FASTW) return v1;
     return px_ok ? v1 : 0.f;
   };
 
   // two rolling partial sums per orientation and pixel
-  float accA[NQ * 4][4], accB[NQ * 4][4];
+  constexpr int NKEEP = NQ - PARK;       // banks whose second sum stays in registers
+  float accA[NQ * 4][4], accB[(NKEEP > 0 ? NKEEP : 1) * 4][4];
 #pragma unroll
   for (int r = 0; r < NQ * 4; ++r)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) { accA[r][j] = 0.f; accB[r][j] = 0.f; }
+    for (int j = 0; j < 4; ++j) accA[r][j] = 0.f;
+#pragma unroll
+  for (int r = 0; r < NKEEP * 4; ++r)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) accB[r][j] = 0.f;
+#pragma unroll
+  for (int r = 0; r < PARK * 4; ++r) PK[r * NT] = f4{0.f, 0.f, 0.f, 0.f};    // read back by this thread only
 
   float a_cur[KC];
   {
-    const float* rp = row_ptr(0);
+    const uint32_t rp = row_ptr(0);
 #pragma unroll
     for (int ks = 0; ks < KC; ++ks) a_cur[ks] = load_a(rp, ks);
     __builtin_amdgcn_s_waitcnt(0x0F70);
@@ -169,15 +183,15 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd_base(const float* __r
   for (int t = 0; t < nsteps; ++t) {
     const int h = y0 - 1 + t;
     const bool row_ok = h >= 0 && h < g.H;
-    const float* rp_cur = row_ptr(t);
-    const float* rp_nxt = row_ptr(t + 1);
+    const uint32_t rp_cur = row_ptr(t);
+    const uint32_t rp_nxt = row_ptr(t + 1);
     f4 P[9];
 
     // One chunk: the MFMAs of its K-steps, each A slot refilled for the next chunk right after its MFMAs, B read
     // from LDS one K-step ahead, behind scheduling fences (the compiler would sink loads to their first use).
     auto chunk = [&](int c, bool first) {
       const bool last = c + 1 == nchunk;
-      const float* rp = last ? rp_nxt : rp_cur;
+      const uint32_t rp = last ? rp_nxt : rp_cur;
       const int kn = (last ? 0 : c + 1) * KC;
       if (STREAM) wload(last ? 0 : c + 1);
       const float* wc = STREAM ? wl_lane + (seq & 1) * CHF : wl_lane + (size_t)c * CHF;
@@ -282,6 +296,14 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd_base(const float* __r
       constexpr int q = decltype(qc)::value;
       constexpr int c = cls_of(CLS, q);
       constexpr bool turned = c == kClsLo || c == kClsHi;
+      constexpr bool parked = q >= NKEEP;
+      // a parked bank's second sums of the previous row: read at the head of the bank's section, used pixel by pixel
+      f4 pB[4];
+      f4 nB[4];
+      if constexpr (parked) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) pB[s] = PK[((q - NKEEP) * 4 + s) * NT];
+      }
       // the bank's products of one pixel column jj in -1 .. 4 (a turned bank: up to four multiply-adds per tap)
       auto column = [&](int jj, float (&Cc)[9]) {
         const float* cf = coef + q * 36;
@@ -332,8 +354,13 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd_base(const float* __r
             begun[ti] = true;
           }
           const float yfin = accA[r][j] + tr[2];   // rows h-2, h-1, h are in: output row h-1 done
-          accA[r][j] = accB[r][j] + tr[1];         // output row h has rows h-1, h
-          accB[r][j] = tr[0];                      // output row h+1 has row h
+          if constexpr (parked) {
+            accA[r][j] = pB[s][j] + tr[1];
+            nB[s][j] = tr[0];
+          } else {
+            accA[r][j] = accB[r][j] + tr[1];       // output row h has rows h-1, h
+            accB[r][j] = tr[0];                    // output row h+1 has row h
+          }
           if (s == 0) {
             bv = yfin;
             bi = rot[r];
@@ -353,6 +380,10 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd_base(const float* __r
           best[j] = take ? bv : best[j];
           besti[j] = take ? bi : besti[j];
         }
+      }
+      if constexpr (parked) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) PK[((q - NKEEP) * 4 + s) * NT] = nB[s];
       }
     };
     bank(std::integral_constant<int, 0>{});
