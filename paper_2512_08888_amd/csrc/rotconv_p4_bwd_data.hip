@@ -37,9 +37,11 @@ typedef float f4 __attribute__((ext_vector_type(4)));
 
 constexpr int NCB = 4;                 // 16-channel blocks per wave
 constexpr int CIG = 16 * NCB;          // input channels per workgroup
-constexpr int WROW = 9 * CIG + 16;     // LDS floats per filter row (padded: conflict-free B reads)
+constexpr int WROW = 9 * CIG + 16;     // LDS floats per filter row (padded)
+constexpr int WROW_TIGHT = 9 * CIG + 4; // the same for the four-wave table variant (two workgroups must fit 160 KB)
 constexpr int CHUNK = 16;              // filters per LDS chunk
 constexpr int kLutRows = 33;           // table rows per neighbour offset in LDS: R + 1 <= 33
+constexpr int kLutRowsTight = 17;      // the four-wave table variant: R <= 16
 
 __device__ __host__ constexpr int tap_i(int s, int u) {
   return s == 0 ? u / 3 : s == 1 ? 2 - u % 3 : s == 2 ? 2 - u / 3 : u % 3;
@@ -91,12 +93,14 @@ __global__ __launch_bounds__(64 * NW, 2) void k_p4_bwd_data(const float* __restr
                                                     const int32_t* __restrict__ rot_of, const float* __restrict__ lut,
                                                     float* __restrict__ dx, P4BwdGeom g) {
   constexpr int NT = 64 * NW;
+  constexpr int WR = (LUT && NW == 4) ? WROW_TIGHT : WROW;          // LDS floats per filter row
+  constexpr int LR = (LUT && NW == 4) ? kLutRowsTight : kLutRows;   // table rows per neighbour offset
   constexpr int WREG = (4 * 9 * (CIG / 4) + NT - 1) / NT;     // staging registers (float4) per quarter chunk and thread
-  extern __shared__ float smem[];      // [2][CHUNK][WROW], then the tables [base bank][9][kLutRows][12] (LUT)
-  float* Tl = smem + 2 * CHUNK * WROW;
+  extern __shared__ float smem[];      // [2][CHUNK][WR], then the tables [base bank][9][LR][12] (LUT)
+  float* Tl = smem + 2 * CHUNK * WR;
   if (LUT) {     // a fixed row count per offset: the offset part of a row address is an instruction immediate
     const int R1 = g.R + 1;
-    for (int i = threadIdx.x; i < g.Q * 9 * R1 * 12; i += NT) Tl[(i / (R1 * 12)) * (kLutRows * 12) + i % (R1 * 12)] = lut[i];
+    for (int i = threadIdx.x; i < g.Q * 9 * R1 * 12; i += NT) Tl[(i / (R1 * 12)) * (LR * 12) + i % (R1 * 12)] = lut[i];
   }
 
   const int per_xcd = (g.units + 7) / 8;
@@ -143,13 +147,13 @@ __global__ __launch_bounds__(64 * NW, 2) void k_p4_bwd_data(const float* __restr
     }
   };
   auto wstore = [&](int buf, int part) {
-    float* dst = smem + buf * CHUNK * WROW;
+    float* dst = smem + buf * CHUNK * WR;
 #pragma unroll
     for (int k = 0; k < WREG; ++k) {
       const int e = tid + k * NT;
       if (e < Q4) {
         const int c4 = e % (CIG / 4), u = (e / (CIG / 4)) % 9, r = part * 4 + e / (9 * (CIG / 4));
-        *reinterpret_cast<f4*>(dst + r * WROW + u * CIG + c4 * 4) = wreg[k];
+        *reinterpret_cast<f4*>(dst + r * WR + u * CIG + c4 * 4) = wreg[k];
       }
     }
   };
@@ -260,7 +264,7 @@ __global__ __launch_bounds__(64 * NW, 2) void k_p4_bwd_data(const float* __restr
   struct LutVals { float gv[3][PX + 2]; uint32_t off[3][PX + 2]; };
   struct LutRow { f4 t0, t1; float t8; };
   auto lut_prepare = [&](const Raw<PX>& r, int bank, LutVals& v) {      // bank: the K-step's base bank (its table)
-    const uint32_t tbase = (uint32_t)bank * (9 * kLutRows * 12);
+    const uint32_t tbase = (uint32_t)bank * (9 * LR * 12);
 #pragma unroll
     for (int dr = 0; dr < 3; ++dr) {
       const Edges<PX> e = edges_of(r, dr);
@@ -277,7 +281,7 @@ __global__ __launch_bounds__(64 * NW, 2) void k_p4_bwd_data(const float* __restr
   };
   auto lut_read = [&](const LutVals& v, int blk) -> LutRow {
     const int dr = blk / (3 * PX), bb = (blk % (3 * PX)) / 3, dc = blk % 3;
-    const float* t = Tl + (dr * 3 + dc) * (kLutRows * 12) + v.off[dr][bb + dc];   // neighbour at column offset dc - 1 of pixel bb
+    const float* t = Tl + (dr * 3 + dc) * (LR * 12) + v.off[dr][bb + dc];   // neighbour at column offset dc - 1 of pixel bb
     LutRow row;
     row.t0 = *reinterpret_cast<const f4*>(t);
     row.t1 = *reinterpret_cast<const f4*>(t + 4);
@@ -321,14 +325,14 @@ __global__ __launch_bounds__(64 * NW, 2) void k_p4_bwd_data(const float* __restr
     // B operand: one 16-byte LDS read per tap (the lane's channel in the four 16-channel blocks), issued
     // one tap ahead; the fences keep it there.
     f4 bw[2];
-    bw[0] = *reinterpret_cast<const f4*>(wl + (ks * 4) * WROW);
+    bw[0] = *reinterpret_cast<const f4*>(wl + (ks * 4) * WR);
     // LUT: PX blocks of the next K-step's sums per tap, their table rows read one tap ahead
     LutVals lv;
     LutRow lrow[PX];
     if (LUT) lut_prepare(raw_use, bd_q, lv);
 #pragma unroll
     for (int u = 0; u < 9; ++u) {
-      if (u < 8) bw[(u + 1) & 1] = *reinterpret_cast<const f4*>(wl + (ks * 4) * WROW + (u + 1) * CIG);
+      if (u < 8) bw[(u + 1) & 1] = *reinterpret_cast<const f4*>(wl + (ks * 4) * WR + (u + 1) * CIG);
       if (LUT) {      // read ahead of the tap's matrix instructions, used behind them
 #pragma unroll
         for (int i = 0; i < PX; ++i) lrow[i] = lut_read(lv, u * PX + i);
@@ -379,7 +383,7 @@ __global__ __launch_bounds__(64 * NW, 2) void k_p4_bwd_data(const float* __restr
 
   for (int cc = 0; cc < nchunks; ++cc) {
     const bool more = cc + 1 < nchunks;
-    const float* wl = smem + (cc & 1) * CHUNK * WROW + lg * WROW + lc * 4;
+    const float* wl = smem + (cc & 1) * CHUNK * WR + lg * WR + lc * 4;
     if (more) wload(cc + 1, 0);
     stage(0, wl, rawA, rawB, aA, aB);
     if (more) { wstore((cc + 1) & 1, 0); wload(cc + 1, 1); }
@@ -508,7 +512,9 @@ P4BwdGeom p4_bwd_data_geom(const rotconv_plan* p) {
   g.lut = p4_bwd_lut(p) ? 1 : 0;
   if (g.lut) g.Q = p->B;        // the "banks" of the contraction are the base banks
   g.ncig = g.CinPad / CIG;
-  g.nw = g.lut ? 8 : 4;     // two workgroups of the table variant would not fit LDS
+  // four-wave workgroups, two per CU; the table variant only with one table of at most 17 rows per offset (two
+  // workgroups' weight chunks and tables then fill the 160 KB of LDS exactly)
+  g.nw = (g.lut && (p->B != 1 || d.R > 16)) ? 8 : 4;
   g.nrb = (d.H + g.nw - 1) / g.nw;
   // pixels per lane: four when the rows are long enough and that still leaves a workgroup per CU
   g.px = ((d.W & 3) == 0 && d.W > 32 && d.N * g.ncig * ((d.H + 7) / 8) * ((d.W + 63) / 64) >= 256) ? 4 : 2;
@@ -564,13 +570,15 @@ void launch_p4_bwd_data(const rotconv_plan* p, const float* gpool, const uint8_t
                         float* part, hipStream_t st) {
   const P4BwdGeom g = p4_bwd_data_geom(p);
   float* dx = g.ksplit > 1 ? part : dx_out;
-  const size_t lds = ((size_t)2 * CHUNK * WROW + (g.lut ? g.Q * 9 * kLutRows * 12 : 0)) * sizeof(float);
+  const bool tight = g.lut && g.nw == 4;
+  const size_t lds = ((size_t)2 * CHUNK * (tight ? WROW_TIGHT : WROW) + (g.lut ? g.Q * 9 * (tight ? kLutRowsTight : kLutRows) * 12 : 0)) * sizeof(float);
   const int grid = (g.units + 7) / 8 * 8;
   auto go = [&](auto kern) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * g.nw), lds, st, gpool, idx, wd, p->dev.rot_of, p->dev.lut_bwd, dx, g);
   };
   if (g.px == 4) go(k_p4_bwd_data<4, false, 4>);
+  else if (g.lut && g.nw == 4) go(k_p4_bwd_data<2, true, 4>);
   else if (g.lut) go(k_p4_bwd_data<2, true, 8>);
   else go(k_p4_bwd_data<2, false, 4>);
   if (g.ksplit > 1) {
