@@ -43,7 +43,7 @@ int ensure_device_tables(rotconv_plan* p) {
                   upload(t.fqt_coef, &d.fqt_coef) && upload(p->rot_of, &d.rot_of) && upload(rq, &d.rq_of_r) &&
                   upload(t.turn_tap, &d.turn_tap) && upload(t.lut_bwd, &d.lut_bwd) &&
                   upload(bf ? t.exp_coef64 : none64, &d.exp_coef64) && upload(bf ? t.fq_coef64 : none64, &d.fq_coef64) &&
-                  upload(t.fwd_base_coef, &d.fwd_base_coef);
+                  upload(t.fwd_base_coef, &d.fwd_base_coef) && upload(bf ? t.fq_dense64 : none64, &d.fq_dense64);
   if (!ok) {
     (void)hipGetLastError();
     free_device_tables(p);
@@ -64,7 +64,7 @@ void free_device_tables(rotconv_plan* p) {
   DeviceTables& d = p->dev;
   void* ptrs[] = {d.exp_src, d.exp_coef, d.tr_ptr, d.tr_col, d.tr_coef, d.fq_src,
                   d.fq_coef, d.fqt_ptr, d.fqt_col, d.fqt_coef, d.rot_of, d.rq_of_r, d.turn_tap, d.lut_bwd,
-                  d.exp_coef64, d.fq_coef64, d.fwd_base_coef};
+                  d.exp_coef64, d.fq_coef64, d.fwd_base_coef, d.fq_dense64};
   for (void* q : ptrs)
     if (q) (void)hipFree(q);
   d = DeviceTables();

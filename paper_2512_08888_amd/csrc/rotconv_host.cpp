@@ -198,6 +198,15 @@ int validate_and_build(const rotconv_desc* desc, rotconv_plan** out) {
         t.exp_coef64[(r * kk + dst) * kMaxNnz + e] = t.fq_coef64[(t.bank_of_r[r] * kk + u) * kMaxNnz + e];
       }
     }
+  if (kk == 9) {
+    t.fq_dense64.assign((size_t)t.Q * 9 * B * 9, 0.0);
+    for (int q = 0; q < t.Q; ++q)
+      for (int u = 0; u < 9; ++u)
+        for (int e = 0; e < kMaxNnz; ++e) {
+          const int src = t.fq_src[(q * 9 + u) * kMaxNnz + e];
+          if (src >= 0) t.fq_dense64[((size_t)q * 9 + u) * (B * 9) + src] += t.fq_coef64[(q * 9 + u) * kMaxNnz + e];
+        }
+  }
   // 3x3: the routed-gradient table of the input / weight gradients.  With Delta_r = G [idx == r]
   // (Eq. 12) the gradient that reaches base tap u' from the neighbour at offset (dy, dx) of a pixel is
   // G * lut[(dy+1)*3 + (dx+1)][idx][u'], lut[.][r][u'] = coefficient of base tap u' in tap (1-dy, 1-dx) of the

@@ -25,6 +25,9 @@ struct HostTables {
   // The same coefficients as computed (fp64): bf16 plans form the banks they multiply with in fp64 and round the
   // result once, so that the rounding does not depend on fp32 intermediate error.
   std::vector<double> exp_coef64, fq_coef64;
+  // 3x3 plans: the first-quadrant expansion as dense fp64 matrices [Q][9 taps][B * 9 source taps] (the bf16 bank
+  // packing multiplies with wave-uniform coefficients)
+  std::vector<double> fq_dense64;
   // Transposed expansion in CSR form, one row per base element (b, u):
   // dw[b][u] = sum over entries e in row: coef[e] * dW^(r_e)[t_e], col = r*kk + t.
   std::vector<int32_t> tr_ptr;   // [B*kk + 1]
@@ -52,6 +55,7 @@ struct DeviceTables {
   float* exp_coef = nullptr;
   double* exp_coef64 = nullptr;  // bf16 plans only (one element otherwise)
   double* fq_coef64 = nullptr;
+  double* fq_dense64 = nullptr;  // bf16 plans only (one element otherwise)
   int32_t* tr_ptr = nullptr;
   int32_t* tr_col = nullptr;
   float* tr_coef = nullptr;

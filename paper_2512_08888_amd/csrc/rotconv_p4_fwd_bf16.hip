@@ -470,40 +470,44 @@ __global__ __launch_bounds__(256) void k_p4_combine_bf16(const float* __restrict
   idx[o] = dead ? (uint8_t)255 : (uint8_t)bi;
 }
 
-// bf16 base bank(s) -> Q first-quadrant banks (Sec. III-D / Eq. 17 combination in fp32, rounded to bf16
-// once) in the LDS image layout [Q][CB][chunk][9 taps][4 k-groups][16 filters][8 channels]; zero for
+// bf16 base bank(s) -> Q first-quadrant banks (Sec. III-D / Eq. 17 combination in fp64, rounded to fp32 and
+// to bf16 once each) in the LDS image layout [Q][CB][chunk][9 taps][4 k-groups][16 filters][8 channels]; zero for
 // padded filters / channels.
 // nq > 1: the banks are folded into the 16 columns (column n = bank n / (16/nq), filter n % (16/nq)): [CB'][chunk]...
+// One thread per (filter, channel): it reads the 9 NB taps of its base filter(s) once and forms all Q banks with
+// wave-uniform fp64 coefficients (dense [Q][9][NS] matrices, NS = 9 source taps per base bank).
+template <int NS>
 __global__ __launch_bounds__(256) void k_p4_pack_fwd_bf16(const uint16_t* __restrict__ w, uint16_t* __restrict__ wt,
-                                                          const int32_t* __restrict__ fq_src,
-                                                          const double* __restrict__ fq_coef, int Q, int CB, int CinPad,
+                                                          const double* __restrict__ dense, int Q, int CB, int CinPad,
                                                           int Cin, int Cout, int nq) {
-  // One thread per (bank, filter, channel): its nine taps read the same 18 bytes of w.
-  const int total = (nq > 1 ? 1 : Q) * CB * CinPad * 16;
+  const int fpb = nq > 1 ? 16 / nq : 16;                 // filters of a block that are distinct filters
+  const int total = CB * CinPad * fpb;
   const int e = blockIdx.x * 256 + threadIdx.x;
   if (e >= total) return;
   const int c8 = e % 8;
-  const int f16 = (e / 8) % 16;
-  const int kg = (e / 128) % 4;
-  const int chunk = (e / 512) % (CinPad / 32);
-  const int cb = (e / (16 * CinPad)) % CB;
-  const int fpb = 16 / nq;
-  const int q = nq > 1 ? f16 / fpb : e / (16 * CinPad * CB);
-  const int co = nq > 1 ? cb * fpb + f16 % fpb : cb * 16 + f16, ci = chunk * 32 + kg * 8 + c8;
+  const int fs = (e / 8) % fpb;
+  const int kg = (e / (8 * fpb)) % 4;
+  const int chunk = (e / (32 * fpb)) % (CinPad / 32);
+  const int cb = e / (fpb * CinPad);
+  const int co = cb * fpb + fs, ci = chunk * 32 + kg * 8 + c8;
   const bool in = co < Cout && ci < Cin;
-  const int slices = Cout * Cin;
+  const size_t slices = (size_t)Cout * Cin;
   const uint16_t* src = w + (size_t)(in ? co * Cin + ci : 0) * 9;
-  uint16_t* dst = wt + (size_t)(e / 512) * 4608 + e % 512;      // + u * 512
+  double wv[NS];
 #pragma unroll
-  for (int u = 0; u < 9; ++u) {
-    double acc = 0.0;     // the combination in fp64, rounded to fp32 and to bf16 once each
+  for (int s = 0; s < NS; ++s) wv[s] = in ? (double)bf16_to_f32(src[(size_t)(s / 9) * slices * 9 + s % 9]) : 0.0;
+  for (int q = 0; q < Q; ++q) {
+    const int f16 = nq > 1 ? q * fpb + fs : fs;
+    const int blk = nq > 1 ? cb : q * CB + cb;
+    uint16_t* dst = wt + ((size_t)blk * (CinPad / 32) + chunk) * 4608 + (kg * 16 + f16) * 8 + c8;      // + u * 512
+    const double* dq = dense + (size_t)q * 9 * NS;
 #pragma unroll
-    for (int z = 0; z < kMaxNnz; ++z) {
-      const int s = fq_src[(q * 9 + u) * kMaxNnz + z];
-      if (in && s >= 0)
-        acc += fq_coef[(q * 9 + u) * kMaxNnz + z] * (double)bf16_to_f32(src[(size_t)(s / 9) * slices * 9 + s % 9]);
+    for (int u = 0; u < 9; ++u) {
+      double acc = 0.0;     // the combination in fp64, rounded to fp32 and to bf16 once each
+#pragma unroll
+      for (int s = 0; s < NS; ++s) acc += dq[u * NS + s] * wv[s];
+      dst[u * 512] = f32_to_bf16((float)acc);
     }
-    dst[u * 512] = f32_to_bf16((float)acc);
   }
 }
 
@@ -586,9 +590,13 @@ size_t p4_fwd_bf16_pack_bytes(const rotconv_plan* p) {
 // nq: 1 = one bank per wave ([Q][CB] blocks); p4_fwd_bf16_fold(p) = banks folded into the columns ([CB'] blocks)
 void launch_p4_pack_fwd_bf16(const rotconv_plan* p, int nq, const uint16_t* w, uint16_t* wt, hipStream_t st) {
   const int CinPad = cin_pad(p->d.Cin), CB = nq > 1 ? (p->d.Cout * nq + 15) / 16 : (p->d.Cout + 15) / 16;
-  const int total = (nq > 1 ? 1 : p->host.Q) * CB * CinPad * 16;
-  hipLaunchKernelGGL(k_p4_pack_fwd_bf16, dim3((total + 255) / 256), dim3(256), 0, st, w, wt, p->dev.fq_src,
-                     p->dev.fq_coef64, p->host.Q, CB, CinPad, p->d.Cin, p->d.Cout, nq);
+  const int total = CB * CinPad * (nq > 1 ? 16 / nq : 16);
+  if (p->B == 1)
+    hipLaunchKernelGGL(k_p4_pack_fwd_bf16<9>, dim3((total + 255) / 256), dim3(256), 0, st, w, wt, p->dev.fq_dense64,
+                       p->host.Q, CB, CinPad, p->d.Cin, p->d.Cout, nq);
+  else
+    hipLaunchKernelGGL(k_p4_pack_fwd_bf16<18>, dim3((total + 255) / 256), dim3(256), 0, st, w, wt, p->dev.fq_dense64,
+                       p->host.Q, CB, CinPad, p->d.Cin, p->d.Cout, nq);
 }
 
 // out_val: bf16 [N][C'][H][W] (kOutPooled), bf16 [N][Cout*R][H][W] (kOutUnpooled) or fp32 per-bank
