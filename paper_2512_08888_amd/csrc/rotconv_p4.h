@@ -77,6 +77,8 @@ struct P4BwdGeom {
   int kper;    // weight chunks (16 filters of a bank) per such workgroup
   int units;   // workgroups with work (includes the split)
   int lut;     // routed-gradient table: the contraction runs over the base bank only (Q is 1 then)
+  int ncg;     // bf16 table kernel: channel groups of 128 per workgroup (their waves build a K-step's D together)
+  int ncigw;   // sets of ncg channel groups
 };
 bool p4_bwd_lut_choice(const rotconv_plan* p);   // whether the fp32 gradients should use the routed-gradient table
 bool p4_bwd_lut(const rotconv_plan* p);          // the plan's setting (contraction over the base bank)

@@ -51,6 +51,8 @@ CASES = [
     LC("b_lut_c128", N=1, Cin=128, H=7, W=40, Cout=24, R=16, mode="bilinear", x_dist="absnormal", seed=76),
     LC("b_lut_c320", N=2, Cin=320, H=9, W=72, Cout=40, R=16, mode="bilinear", x_dist="absnormal", seed=77),
     LC("b_lut_ste_c192", N=1, Cin=192, H=6, W=32, Cout=20, R=16, mode="steerable", x_dist="absnormal", seed=78),
+    # the input gradient with shared D and its K-steps split over workgroups
+    LC("b_lut_ks_c384", N=1, Cin=384, H=5, W=32, Cout=192, R=16, mode="bilinear", x_dist="absnormal", seed=79),
     # a layer on which one arg-max sat just outside the fp32 near-tie band when the rotated weights were formed in fp32
     # (one of them rounded to the neighbouring bf16 value); they are formed in fp64 now: the regression case
     LC("b_r16_bank_rounding", N=2, Cin=32, H=19, W=160, Cout=136, R=16, mode="bilinear", x_dist="absnormal", seed=9148),
