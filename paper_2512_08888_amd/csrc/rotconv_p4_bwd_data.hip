@@ -420,6 +420,241 @@ __global__ __launch_bounds__(64 * NW, 2) void k_p4_bwd_data(const float* __restr
   }
 }
 
+// Table variant for layers with more than 64 input channels.  The D of a (filter, pixel) does not depend on the input
+// channel, and building it (nine table rows from LDS and 81 multiply-adds) costs as much as the matrix instructions of
+// one 64-channel group, so a workgroup's four waves are NCG channel groups x 4 / NCG rows, and the NCG waves of a row build the D of a
+// chunk of 16 filters together: wave cg the K-steps [cg 4/NCG, (cg+1) 4/NCG) of the chunk, every lane the operand
+// values of its own (pixel pair, filter) -- exactly the A-operand layout, so the exchange through LDS is
+// [row][K-step][tap][pixel tile][lane], written and read without conflicts.  One buffer, two barriers per chunk of
+// 288 matrix instructions per wave; two or three workgroups share a CU and fill each other's build phases.  The base
+// bank is re-laid so that the B operand of (K-step, tap) is one contiguous kilobyte ([group][bank][K-step][tap][lane]
+// x four channel blocks) and is read straight from global memory (L2; the two rows' waves of a group read the same
+// kilobytes), one K-step ahead; (G, idx) of the next chunk are loaded at the head of a chunk's matrix instructions.
+template <int NCG>
+__global__ __launch_bounds__(256, 2) void k_p4_bwd_data_lut_shared(const float* __restrict__ gpool,
+                                                                         const uint8_t* __restrict__ idx,
+                                                                         const f4* __restrict__ wt,
+                                                                         const float* __restrict__ lut,
+                                                                         float* __restrict__ dx, P4BwdGeom g) {
+  constexpr int PX = 2;
+  constexpr int NT = 256;              // 4 / NCG rows x NCG channel groups
+  constexpr int NR = 4 / NCG;          // rows per workgroup
+  constexpr int NKS = 4 / NCG;         // K-steps of a chunk that a wave builds
+  extern __shared__ float smem[];      // the tables [base bank][9][kLutRows][12], then D [NR rows][4][9][2][64]
+  float* Tl = smem;
+  typedef float DBuf[4][9][2][64];     // [K-step][tap][pixel tile][lane]
+  DBuf* Dl = reinterpret_cast<DBuf*>(smem + g.Q * 9 * kLutRows * 12);
+  {
+    const int R1 = g.R + 1;
+    for (int i = threadIdx.x; i < g.Q * 9 * R1 * 12; i += NT) Tl[(i / (R1 * 12)) * (kLutRows * 12) + i % (R1 * 12)] = lut[i];
+  }
+  __syncthreads();
+
+  const int per_xcd = (g.units + 7) / 8;
+  int v = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  if (v >= g.units) return;
+  const int cpb = g.CoutPad / CHUNK;           // chunks per base bank
+  const int ksp = v % g.ksplit; v /= g.ksplit;
+  const int c0 = ksp * g.kper, c1 = min(g.Q * cpb, c0 + g.kper);
+  const int cigw = v % g.ncigw; v /= g.ncigw;
+  const int strip = v % g.nstrip; v /= g.nstrip;
+  const int rb = v % g.nrb;
+  const int n = v / g.nrb;
+
+  const int tid = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid / 64), lane = tid % 64;
+  const int lg = lane / 16, lc = lane % 16;
+  const int cg = wave % NCG, rw = wave / NCG;       // the wave's channel group and row inside the workgroup
+  const int cig = min(cigw * NCG + cg, g.ncig - 1); // a wave beyond the last group redoes it (and stores nothing)
+  const bool cg_on = cigw * NCG + cg < g.ncig;
+  const int h = rb * NR + rw;
+  const int x0 = strip * 16 * PX;
+  const bool active = h < g.H;
+  const int HW = g.H * g.W;
+
+  // ---- (G, idx) neighbourhood loads (as in the kernel above) ----
+  const int xa = x0 + PX * lc;
+  uint32_t offc[3], offe[3], invc[3], inve[3];
+#pragma unroll
+  for (int dr = 0; dr < 3; ++dr) {
+    const int row = h - 1 + dr;
+    const bool rok = active && row >= 0 && row < g.H;
+    const bool okc = rok && xa < g.W, okl = rok && xa >= 1 && xa - 1 < g.W, okr = rok && xa + PX < g.W;
+    const uint32_t rowoff = (uint32_t)(rok ? row : 0) * (uint32_t)g.W;
+    offc[dr] = rowoff + (uint32_t)(okc ? xa : 0);
+    const bool okl0 = rok && x0 >= 1 && x0 - 1 < g.W;
+    offe[dr] = lc == 15 ? rowoff + (uint32_t)(okr ? xa + PX : 0) : rowoff + (uint32_t)(okl0 ? x0 - 1 : 0);
+    invc[dr] = okc ? 0u : 0xffffffffu;
+    inve[dr] = (okl ? 0u : 0xffu) | (okr ? 0u : 0xff00u);
+  }
+  const float* gimg = gpool + (size_t)n * g.Cout * HW;
+  const uint8_t* iimg = idx + (size_t)n * g.Cout * HW;
+  auto raw_load = [&](int co, Raw<PX>& r) {      // filter co of the layer (beyond Cout: filter 0, nothing routed)
+    const bool fok = co < g.Cout;
+    const uint32_t fl = (uint32_t)(fok ? co : 0) * (uint32_t)HW;
+    r.finv = fok ? 0u : 0xffffffffu;
+#pragma unroll
+    for (int dr = 0; dr < 3; ++dr) {
+      const float2 v2 = *reinterpret_cast<const float2*>(gimg + (fl + offc[dr]));
+      r.gc[dr][0] = v2.x; r.gc[dr][1] = v2.y;
+      r.ic[dr] = *reinterpret_cast<const uint16_t*>(iimg + (fl + offc[dr]));
+      r.ge[dr] = gimg[fl + offe[dr]];
+      r.ie[dr] = iimg[fl + offe[dr]];
+    }
+  };
+  struct LutVals { float gv[3][PX + 2]; uint32_t off[3][PX + 2]; };
+  auto lut_prepare = [&](const Raw<PX>& r, int bank, LutVals& lv) {
+    const uint32_t tbase = (uint32_t)bank * (9 * kLutRows * 12);
+#pragma unroll
+    for (int dr = 0; dr < 3; ++dr) {
+      const Edges<PX> e = edges_of(r, dr);
+      const uint32_t iwc = r.ic[dr] | invc[dr] | r.finv | 0xffff0000u;
+      const uint32_t iwe = e.iwe | inve[dr] | r.finv;
+#pragma unroll
+      for (int c = 0; c < PX + 2; ++c) {
+        const uint32_t byte = c == 0 ? (iwe & 0xffu) : c == PX + 1 ? ((iwe >> 8) & 0xffu) : ((iwc >> (8 * (c - 1))) & 0xffu);
+        const float gval = c == 0 ? e.gl : c == PX + 1 ? e.gr : r.gc[dr][c - 1];
+        lv.gv[dr][c] = byte < (uint32_t)g.R ? gval : 0.f;
+        lv.off[dr][c] = min(byte, (uint32_t)g.R) * 12u + tbase;
+      }
+    }
+  };
+  // D of pixel b of the lane's filter, nine base taps: three groups (one per neighbour row) of three table-row reads
+  // and 27 multiply-adds, one group's reads in flight at a time
+  auto build_pixel = [&](const LutVals& lv, int b, float (&d)[9]) {
+#pragma unroll
+    for (int dr = 0; dr < 3; ++dr) {
+      f4 t0[3], t1[3];
+      float t8[3];
+#pragma unroll
+      for (int dc = 0; dc < 3; ++dc) {
+        const float* t = Tl + (dr * 3 + dc) * (kLutRows * 12) + lv.off[dr][b + dc];
+        t0[dc] = *reinterpret_cast<const f4*>(t);
+        t1[dc] = *reinterpret_cast<const f4*>(t + 4);
+        t8[dc] = t[8];
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int dc = 0; dc < 3; ++dc) {
+        const float gvc = lv.gv[dr][b + dc];
+        const float tv[9] = {t0[dc][0], t0[dc][1], t0[dc][2], t0[dc][3], t1[dc][0], t1[dc][1], t1[dc][2], t1[dc][3], t8[dc]};
+#pragma unroll
+        for (int u = 0; u < 9; ++u) d[u] = (dr == 0 && dc == 0) ? gvc * tv[u] : d[u] + gvc * tv[u];
+      }
+#pragma unroll
+      for (int u = 0; u < 9; ++u) asm volatile("" : "+v"(d[u]));
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+
+  f4 acc[NCB][PX];
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+    for (int b = 0; b < PX; ++b) acc[cb][b] = f4{0.f, 0.f, 0.f, 0.f};
+
+  // this lane's 16 bytes of B operand of (K-step ks of the workgroup's range, tap u): wl[(ks * 9 + u) * 64]
+  const f4* wl = wt + ((size_t)cig * g.Q * cpb + c0) * (4 * 9 * 64) + lane;
+  // filter of this lane in K-step ks (0..3) of chunk c
+  auto filt = [&](int c, int ks) { return (c % cpb) * CHUNK + 4 * ks + lg; };
+
+  Raw<PX> raw[NKS];
+#pragma unroll
+  for (int i = 0; i < NKS; ++i) raw_load(filt(c0, cg * NKS + i), raw[i]);
+  f4 bw[2][9];
+#pragma unroll
+  for (int u = 0; u < 9; ++u) bw[0][u] = wl[u * 64];
+
+  for (int c = c0; c < c1; ++c) {
+    const int bank = c / cpb;
+    // ---- the wave's K-steps of the chunk's D -> LDS ----
+#pragma unroll
+    for (int i = 0; i < NKS; ++i) {
+      LutVals lv;
+      lut_prepare(raw[i], bank, lv);
+      float d0[9], d1[9];
+      build_pixel(lv, 0, d0);
+      build_pixel(lv, 1, d1);
+#pragma unroll
+      for (int u = 0; u < 9; ++u) {
+        Dl[rw][cg * NKS + i][u][0][lane] = d0[u];
+        Dl[rw][cg * NKS + i][u][1][lane] = d1[u];
+      }
+    }
+    // (G, idx) of the next chunk: in flight during this chunk's matrix instructions (the last chunk reloads itself)
+    const int cn = min(c + 1, c1 - 1);
+#pragma unroll
+    for (int i = 0; i < NKS; ++i) raw_load(filt(cn, cg * NKS + i), raw[i]);
+    __syncthreads();
+    // ---- the contraction of the chunk: four K-steps of 9 x NCB x 2 matrix instructions ----
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      float a[9][PX];
+#pragma unroll
+      for (int u = 0; u < 9; ++u) {
+        a[u][0] = Dl[rw][ks][u][0][lane];
+        a[u][1] = Dl[rw][ks][u][1][lane];
+      }
+      // B of the next K-step (the workgroup's last one reloads itself)
+      const int kn = min((c - c0) * 4 + ks + 1, (c1 - c0) * 4 - 1);
+#pragma unroll
+      for (int u = 0; u < 9; ++u) bw[(ks + 1) & 1][u] = wl[(size_t)(kn * 9 + u) * 64];
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int u = 0; u < 9; ++u)
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+          for (int b = 0; b < PX; ++b)
+            acc[cb][b] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[u][b], bw[ks & 1][u][cb], acc[cb][b], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    __syncthreads();          // every wave has read the chunk's D
+  }
+
+  // ---- store: lane (lg, lc) holds channel cb*16+lc, pixels x0 + 8 lg + 2 i + b ----
+  if (!active || !cg_on) return;
+#pragma unroll
+  for (int cb = 0; cb < NCB; ++cb) {
+    const int ci = cig * CIG + cb * 16 + lc;
+    if (ci >= g.Cin) continue;
+    const int px = x0 + 4 * PX * lg;
+    float* o = dx + (((size_t)ksp * g.N + n) * g.Cin + ci) * HW + (size_t)h * g.W + px;   // ksp > 0 only in the partial buffer
+    float vals[4 * PX];
+#pragma unroll
+    for (int j = 0; j < 4 * PX; ++j) vals[j] = acc[cb][j % PX][j / PX];
+    if ((g.W & 3) == 0) {
+#pragma unroll
+      for (int v4 = 0; v4 < PX; ++v4)
+        if (px + 4 * v4 < g.W)
+          reinterpret_cast<f4*>(o)[v4] = f4{vals[4 * v4], vals[4 * v4 + 1], vals[4 * v4 + 2], vals[4 * v4 + 3]};
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4 * PX; ++j)
+        if (px + j < g.W) o[j] = vals[j];
+    }
+  }
+}
+
+// base bank(s) -> [channel group of 64][base bank][K-step of 4 filters][tap][lane = (filter, channel)][4 channel blocks]
+__global__ __launch_bounds__(256) void k_p4_pack_bwd_shared(const float* __restrict__ w, float* __restrict__ wd, int B,
+                                                            int ncig, int CoutPad, int Cin, int Cout) {
+  const size_t total = (size_t)ncig * B * CoutPad * 64;     // one thread per (group, bank, filter, channel, block)
+  const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (e >= total) return;
+  const int cb = (int)(e % 4), lc = (int)((e / 4) % 16), lg = (int)((e / 64) % 4);
+  size_t r = e / 256;
+  const int kstep = (int)(r % (CoutPad / 4)); r /= (CoutPad / 4);
+  const int b = (int)(r % B);
+  const int cig = (int)(r / B);
+  const int co = kstep * 4 + lg, ci = cig * CIG + cb * 16 + lc;
+  const bool in = co < Cout && ci < Cin;
+  const float* src = w + ((size_t)b * Cout * Cin + (size_t)(in ? co * Cin + ci : 0)) * 9;
+  float* dst = wd + ((((size_t)cig * B + b) * (CoutPad / 4) + kstep) * 9 * 64 + lg * 16 + lc) * 4 + cb;
+#pragma unroll
+  for (int u = 0; u < 9; ++u) dst[(size_t)u * 64 * 4] = in ? src[u] : 0.f;
+}
+
 // dx[e] = sum over the bank splits, ascending, of part[s][e] (four elements per thread, scalar tail).
 __global__ __launch_bounds__(256) void k_p4_sum_dx(const float* __restrict__ part, float* __restrict__ dx, size_t n_elem,
                                                    int nparts) {
@@ -512,15 +747,20 @@ P4BwdGeom p4_bwd_data_geom(const rotconv_plan* p) {
   g.lut = p4_bwd_lut(p) ? 1 : 0;
   if (g.lut) g.Q = p->B;        // the "banks" of the contraction are the base banks
   g.ncig = g.CinPad / CIG;
-  // four-wave workgroups, two per CU; the table variant only with one table of at most 17 rows per offset (two
-  // workgroups' weight chunks and tables then fill the 160 KB of LDS exactly)
-  g.nw = (g.lut && (p->B != 1 || d.R > 16)) ? 8 : 4;
-  g.nrb = (d.H + g.nw - 1) / g.nw;
+  // table variant with several channel groups: the groups of a row build D together (k_p4_bwd_data_lut_shared):
+  // workgroups of 4 / ncg rows x ncg channel groups
+  g.ncg = g.lut && g.ncig >= 2 ? (g.ncig >= 3 ? 4 : 2) : 1;
+  g.ncigw = (g.ncig + g.ncg - 1) / g.ncg;
+  // otherwise four-wave workgroups, two per CU; the table variant only with one table of at most 17 rows per offset
+  // (two workgroups' weight chunks and tables then fill the 160 KB of LDS exactly)
+  g.nw = g.ncg > 1 ? 4 : (g.lut && (p->B != 1 || d.R > 16)) ? 8 : 4;
+  const int rows_wg = g.ncg > 1 ? 4 / g.ncg : g.nw;
+  g.nrb = (d.H + rows_wg - 1) / rows_wg;
   // pixels per lane: four when the rows are long enough and that still leaves a workgroup per CU
   g.px = ((d.W & 3) == 0 && d.W > 32 && d.N * g.ncig * ((d.H + 7) / 8) * ((d.W + 63) / 64) >= 256) ? 4 : 2;
   if (g.lut) g.px = 2;      // the table build is made for two pixels per lane (four would spill)
   g.nstrip = (d.W + 16 * g.px - 1) / (16 * g.px);
-  g.units = d.N * g.ncig * g.nstrip * g.nrb;
+  g.units = d.N * g.ncigw * g.nstrip * g.nrb;
   // Few units and a long contraction: share its weight chunks (16 filters of a bank) out so that the chip is filled
   // about twice; at least 8 chunks per workgroup, at most 256 MiB of partial sums.
   const int chunks = g.Q * (g.CoutPad / CHUNK);
@@ -560,6 +800,12 @@ size_t p4_bwd_data_pack_floats(const rotconv_plan* p) {
 
 void launch_p4_pack_bwd(const rotconv_plan* p, const float* w, float* wd, hipStream_t st) {
   const P4BwdGeom g = p4_bwd_data_geom(p);
+  if (g.ncg > 1) {
+    const size_t total = (size_t)g.ncig * g.Q * g.CoutPad * 64;
+    hipLaunchKernelGGL(k_p4_pack_bwd_shared, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, w, wd, g.Q, g.ncig,
+                       g.CoutPad, g.Cin, g.Cout);
+    return;
+  }
   const int total = g.Q * g.CoutPad * g.CinPad;
   hipLaunchKernelGGL(k_p4_pack_bwd, dim3((total + 255) / 256), dim3(256), 0, st, w, wd, p->dev.fq_src, p->dev.fq_coef,
                      p->dev.fq_coef64,
@@ -570,6 +816,23 @@ void launch_p4_bwd_data(const rotconv_plan* p, const float* gpool, const uint8_t
                         float* part, hipStream_t st) {
   const P4BwdGeom g = p4_bwd_data_geom(p);
   float* dx = g.ksplit > 1 ? part : dx_out;
+  if (g.ncg > 1) {
+    const size_t lds_s = ((size_t)g.Q * 9 * kLutRows * 12 + (size_t)(4 / g.ncg) * 4 * 9 * 2 * 64) * sizeof(float);
+    const int grid_s = (g.units + 7) / 8 * 8;
+    auto gos = [&](auto kern) {
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_s);
+      hipLaunchKernelGGL(kern, dim3(grid_s), dim3(64 * g.nw), lds_s, st, gpool, idx, reinterpret_cast<const f4*>(wd),
+                         p->dev.lut_bwd, dx, g);
+    };
+    if (g.ncg == 4) gos(k_p4_bwd_data_lut_shared<4>);
+    else gos(k_p4_bwd_data_lut_shared<2>);
+    if (g.ksplit > 1) {
+      const size_t n_elem = (size_t)p->d.N * p->d.Cin * p->d.H * p->d.W;
+      const unsigned blocks = (unsigned)std::max<size_t>(1, std::min<size_t>((n_elem / 4 + 255) / 256, 1u << 16));
+      hipLaunchKernelGGL(k_p4_sum_dx, dim3(blocks), dim3(256), 0, st, part, dx_out, n_elem, g.ksplit);
+    }
+    return;
+  }
   const bool tight = g.lut && g.nw == 4;
   const size_t lds = ((size_t)2 * CHUNK * (tight ? WROW_TIGHT : WROW) + (g.lut ? g.Q * 9 * (tight ? kLutRowsTight : kLutRows) * 12 : 0)) * sizeof(float);
   const int grid = (g.units + 7) / 8 * 8;
