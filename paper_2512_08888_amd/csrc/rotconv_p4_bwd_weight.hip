@@ -54,7 +54,7 @@ struct RowW {            // (G, idx) of one filter on one image row as loaded: t
 // table row holds the rotated bank's coefficients of the base taps), so the contraction runs once instead of once
 // per bank and its result is the base-bank gradient itself.
 template <int NCB, bool LUT>
-__global__ __launch_bounds__(NT) void k_p4_bwd_weight(const float* __restrict__ x, const float* __restrict__ gpool,
+__global__ __launch_bounds__(NT, (NCB == 1 && !LUT) ? 2 : 1) void k_p4_bwd_weight(const float* __restrict__ x, const float* __restrict__ gpool,
                                                       const uint8_t* __restrict__ idx,
                                                       const int32_t* __restrict__ rot_of, const float* __restrict__ lut,
                                                       float* __restrict__ partial, P4BwdWGeom g) {
@@ -654,7 +654,7 @@ struct RowB {            // (G, idx) of one filter on one image row as loaded
 };
 
 template <int NCB>
-__global__ __launch_bounds__(NT) void k_p4_bwd_weight_bf16(const uint16_t* __restrict__ x,
+__global__ __launch_bounds__(NT, NCB == 1 ? 2 : 1) void k_p4_bwd_weight_bf16(const uint16_t* __restrict__ x,
                                                            const uint16_t* __restrict__ gpool,
                                                            const uint8_t* __restrict__ idx,
                                                            const int32_t* __restrict__ rot_of,
@@ -835,7 +835,7 @@ __global__ __launch_bounds__(NT) void k_p4_bwd_weight_bf16(const uint16_t* __res
 // bank's gradient itself.  Same units, strips, row ranges and splits as the kernels above.  The D of row h + 1 is
 // built, pixel by pixel, between the matrix instructions of row h.
 template <int NCB>
-__global__ __launch_bounds__(NT) void k_p4_bwd_weight_bf16_lut(const uint16_t* __restrict__ x,
+__global__ __launch_bounds__(NT, NCB == 1 ? 2 : 1) void k_p4_bwd_weight_bf16_lut(const uint16_t* __restrict__ x,
                                                                const uint16_t* __restrict__ gpool,
                                                                const uint8_t* __restrict__ idx,
                                                                const float* __restrict__ lut,
@@ -1404,7 +1404,10 @@ P4BwdWGeom p4_bwd_weight_geom(const rotconv_plan* p, bool lut, bool share) {
   // work units: (image, row range, 32-pixel strip); a range never crosses an image
   const int combos = g.ncigw * g.ncog;
   g.nstrip = (d.W + 31) / 32;
-  const int want = (256 + combos - 1) / combos;                       // units wanted to fill the chip
+  // units wanted to fill the chip: one workgroup per CU; two where the instance leaves room for two waves per SIMD
+  // (one channel block per wave: the first layer)
+  const int fill = (NCB == 1 && !(lut && p->d.dtype != ROTCONV_BF16)) ? 512 : 256;
+  const int want = (fill + combos - 1) / combos;
   int per_image = std::max(1, std::min(d.H, (want + d.N * g.nstrip - 1) / (d.N * g.nstrip)));
   g.rows_per = (d.H + per_image - 1) / per_image;
   g.nrange = (d.H + g.rows_per - 1) / g.rows_per;
