@@ -420,40 +420,41 @@ __global__ __launch_bounds__(64 * NW, 2) void k_p4_bwd_data(const float* __restr
   }
 }
 
-// Table variant for layers with more than 64 input channels.  The D of a (filter, pixel) does not depend on the input
-// channel, and building it (nine table rows from LDS and 81 multiply-adds) costs as much as the matrix instructions of
-// one 64-channel group, so a workgroup's four waves are NCG channel groups x 4 / NCG rows, and the NCG waves of a row build the D of a
-// chunk of 16 filters together: wave cg the K-steps [cg 4/NCG, (cg+1) 4/NCG) of the chunk, every lane the operand
-// values of its own (pixel pair, filter) -- exactly the A-operand layout, so the exchange through LDS is
+// Layers with more than 64 input channels (one pool group per filter; the table variant or a single bank).  The D of
+// a (filter, pixel) does not depend on the input channel, and building it costs as much as the matrix instructions of
+// one 64-channel group (table: nine table rows from LDS and 81 multiply-adds; per-bank: 72 selects and 108 adds per
+// four pixels), so a workgroup's four waves are NCG channel groups x 4 / NCG rows, and the NCG waves of a row build
+// the D of a chunk of 16 filters together: wave cg the K-steps [cg 4/NCG, (cg+1) 4/NCG) of the chunk, every lane the
+// operand values of its own (pixels, filter) -- exactly the A-operand layout, so the exchange through LDS is
 // [row][K-step][tap][pixel tile][lane], written and read without conflicts.  One buffer, two barriers per chunk of
-// 288 matrix instructions per wave; two or three workgroups share a CU and fill each other's build phases.  The base
+// 144 PX matrix instructions per wave; two or three workgroups share a CU and fill each other's build phases.  The
 // bank is re-laid so that the B operand of (K-step, tap) is one contiguous kilobyte ([group][bank][K-step][tap][lane]
-// x four channel blocks) and is read straight from global memory (L2; the two rows' waves of a group read the same
-// kilobytes), one K-step ahead; (G, idx) of the next chunk are loaded at the head of a chunk's matrix instructions.
-template <int NCG>
-__global__ __launch_bounds__(256, 2) void k_p4_bwd_data_lut_shared(const float* __restrict__ gpool,
-                                                                         const uint8_t* __restrict__ idx,
-                                                                         const f4* __restrict__ wt,
-                                                                         const float* __restrict__ lut,
-                                                                         float* __restrict__ dx, P4BwdGeom g) {
-  constexpr int PX = 2;
+// x four channel blocks) and is read straight from global memory (L2; the waves of a group read the same kilobytes),
+// one K-step ahead; (G, idx) of the next chunk are loaded at the head of a chunk's matrix instructions.
+template <int PX, bool LUT, int NCG>
+__global__ __launch_bounds__(256, 2) void k_p4_bwd_data_shared(const float* __restrict__ gpool,
+                                                               const uint8_t* __restrict__ idx,
+                                                               const f4* __restrict__ wt,
+                                                               const int32_t* __restrict__ rot_of,
+                                                               const float* __restrict__ lut,
+                                                               float* __restrict__ dx, P4BwdGeom g) {
   constexpr int NT = 256;              // 4 / NCG rows x NCG channel groups
   constexpr int NR = 4 / NCG;          // rows per workgroup
   constexpr int NKS = 4 / NCG;         // K-steps of a chunk that a wave builds
-  extern __shared__ float smem[];      // the tables [base bank][9][kLutRows][12], then D [NR rows][4][9][2][64]
+  extern __shared__ float smem[];      // the tables [base bank][9][kLutRows][12] (LUT), then D [NR rows][4][9][PX][64]
   float* Tl = smem;
-  typedef float DBuf[4][9][2][64];     // [K-step][tap][pixel tile][lane]
-  DBuf* Dl = reinterpret_cast<DBuf*>(smem + g.Q * 9 * kLutRows * 12);
-  {
+  typedef float DBuf[4][9][PX][64];    // [K-step][tap][pixel tile][lane]
+  DBuf* Dl = reinterpret_cast<DBuf*>(smem + (LUT ? g.Q * 9 * kLutRows * 12 : 0));
+  if (LUT) {
     const int R1 = g.R + 1;
     for (int i = threadIdx.x; i < g.Q * 9 * R1 * 12; i += NT) Tl[(i / (R1 * 12)) * (kLutRows * 12) + i % (R1 * 12)] = lut[i];
+    __syncthreads();
   }
-  __syncthreads();
 
   const int per_xcd = (g.units + 7) / 8;
   int v = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
   if (v >= g.units) return;
-  const int cpb = g.CoutPad / CHUNK;           // chunks per base bank
+  const int cpb = g.CoutPad / CHUNK;           // chunks per bank
   const int ksp = v % g.ksplit; v /= g.ksplit;
   const int c0 = ksp * g.kper, c1 = min(g.Q * cpb, c0 + g.kper);
   const int cigw = v % g.ncigw; v /= g.ncigw;
@@ -471,6 +472,10 @@ __global__ __launch_bounds__(256, 2) void k_p4_bwd_data_lut_shared(const float* 
   const int x0 = strip * 16 * PX;
   const bool active = h < g.H;
   const int HW = g.H * g.W;
+
+  int rot[4];                                       // per-bank variant: orientation of each quarter turn (-1: absent)
+#pragma unroll
+  for (int s = 0; s < 4; ++s) rot[s] = LUT ? 0 : rot_of[s];
 
   // ---- (G, idx) neighbourhood loads (as in the kernel above) ----
   const int xa = x0 + PX * lc;
@@ -495,20 +500,59 @@ __global__ __launch_bounds__(256, 2) void k_p4_bwd_data_lut_shared(const float* 
     r.finv = fok ? 0u : 0xffffffffu;
 #pragma unroll
     for (int dr = 0; dr < 3; ++dr) {
-      const float2 v2 = *reinterpret_cast<const float2*>(gimg + (fl + offc[dr]));
-      r.gc[dr][0] = v2.x; r.gc[dr][1] = v2.y;
-      r.ic[dr] = *reinterpret_cast<const uint16_t*>(iimg + (fl + offc[dr]));
+      if (PX == 2) {
+        const float2 v2 = *reinterpret_cast<const float2*>(gimg + (fl + offc[dr]));
+        r.gc[dr][0] = v2.x; r.gc[dr][1] = v2.y;
+        r.ic[dr] = *reinterpret_cast<const uint16_t*>(iimg + (fl + offc[dr]));
+      } else {
+        const f4 v4 = *reinterpret_cast<const f4*>(gimg + (fl + offc[dr]));
+#pragma unroll
+        for (int p = 0; p < PX; ++p) r.gc[dr][p] = v4[p & 3];
+        r.ic[dr] = *reinterpret_cast<const uint32_t*>(iimg + (fl + offc[dr]));
+      }
       r.ge[dr] = gimg[fl + offe[dr]];
       r.ie[dr] = iimg[fl + offe[dr]];
     }
   };
+  // per-bank variant: the nine tap sums of the lane's PX pixels (Eq. 12 + the rotated tap positions of Eq. 8)
+  auto build_taps = [&](const Raw<PX>& r, float (&a)[9][PX]) {
+    float gl[3], gr[3];
+    uint32_t iwc[3], iwe[3];
+#pragma unroll
+    for (int dr = 0; dr < 3; ++dr) {
+      const Edges<PX> e = edges_of(r, dr);
+      gl[dr] = e.gl; gr[dr] = e.gr;
+      iwc[dr] = r.ic[dr] | invc[dr] | r.finv | (PX == 2 ? 0xffff0000u : 0u);
+      iwe[dr] = e.iwe | inve[dr] | r.finv;
+    }
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const uint32_t rs = (uint32_t)rot[s];
+      float d[3][PX + 2];
+#pragma unroll
+      for (int dr = 0; dr < 3; ++dr) {
+        d[dr][0] = ((iwe[dr] & 0xffu) == rs) ? gl[dr] : 0.f;
+        d[dr][PX + 1] = (((iwe[dr] >> 8) & 0xffu) == rs) ? gr[dr] : 0.f;
+#pragma unroll
+        for (int p = 0; p < PX; ++p) d[dr][1 + p] = (((iwc[dr] >> (8 * p)) & 0xffu) == rs) ? r.gc[dr][p] : 0.f;
+      }
+#pragma unroll
+      for (int u = 0; u < 9; ++u)
+#pragma unroll
+        for (int b = 0; b < PX; ++b) {
+          const float t = d[2 - tap_i(s, u)][b + 2 - tap_j(s, u)];
+          a[u][b] = s == 0 ? t : a[u][b] + t;
+        }
+    }
+  };
+  // table variant
   struct LutVals { float gv[3][PX + 2]; uint32_t off[3][PX + 2]; };
   auto lut_prepare = [&](const Raw<PX>& r, int bank, LutVals& lv) {
     const uint32_t tbase = (uint32_t)bank * (9 * kLutRows * 12);
 #pragma unroll
     for (int dr = 0; dr < 3; ++dr) {
       const Edges<PX> e = edges_of(r, dr);
-      const uint32_t iwc = r.ic[dr] | invc[dr] | r.finv | 0xffff0000u;
+      const uint32_t iwc = r.ic[dr] | invc[dr] | r.finv | (PX == 2 ? 0xffff0000u : 0u);
       const uint32_t iwe = e.iwe | inve[dr] | r.finv;
 #pragma unroll
       for (int c = 0; c < PX + 2; ++c) {
@@ -570,15 +614,23 @@ __global__ __launch_bounds__(256, 2) void k_p4_bwd_data_lut_shared(const float* 
     // ---- the wave's K-steps of the chunk's D -> LDS ----
 #pragma unroll
     for (int i = 0; i < NKS; ++i) {
-      LutVals lv;
-      lut_prepare(raw[i], bank, lv);
-      float d0[9], d1[9];
-      build_pixel(lv, 0, d0);
-      build_pixel(lv, 1, d1);
+      if (LUT) {
+        LutVals lv;
+        lut_prepare(raw[i], bank, lv);
 #pragma unroll
-      for (int u = 0; u < 9; ++u) {
-        Dl[rw][cg * NKS + i][u][0][lane] = d0[u];
-        Dl[rw][cg * NKS + i][u][1][lane] = d1[u];
+        for (int b = 0; b < PX; ++b) {
+          float d[9];
+          build_pixel(lv, b, d);
+#pragma unroll
+          for (int u = 0; u < 9; ++u) Dl[rw][cg * NKS + i][u][b][lane] = d[u];
+        }
+      } else {
+        float a[9][PX];
+        build_taps(raw[i], a);
+#pragma unroll
+        for (int u = 0; u < 9; ++u)
+#pragma unroll
+          for (int b = 0; b < PX; ++b) Dl[rw][cg * NKS + i][u][b][lane] = a[u][b];
       }
     }
     // (G, idx) of the next chunk: in flight during this chunk's matrix instructions (the last chunk reloads itself)
@@ -586,15 +638,14 @@ __global__ __launch_bounds__(256, 2) void k_p4_bwd_data_lut_shared(const float* 
 #pragma unroll
     for (int i = 0; i < NKS; ++i) raw_load(filt(cn, cg * NKS + i), raw[i]);
     __syncthreads();
-    // ---- the contraction of the chunk: four K-steps of 9 x NCB x 2 matrix instructions ----
+    // ---- the contraction of the chunk: four K-steps of 9 x NCB x PX matrix instructions ----
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
       float a[9][PX];
 #pragma unroll
-      for (int u = 0; u < 9; ++u) {
-        a[u][0] = Dl[rw][ks][u][0][lane];
-        a[u][1] = Dl[rw][ks][u][1][lane];
-      }
+      for (int u = 0; u < 9; ++u)
+#pragma unroll
+        for (int b = 0; b < PX; ++b) a[u][b] = Dl[rw][ks][u][b][lane];
       // B of the next K-step (the workgroup's last one reloads itself)
       const int kn = min((c - c0) * 4 + ks + 1, (c1 - c0) * 4 - 1);
 #pragma unroll
@@ -612,7 +663,7 @@ __global__ __launch_bounds__(256, 2) void k_p4_bwd_data_lut_shared(const float* 
     __syncthreads();          // every wave has read the chunk's D
   }
 
-  // ---- store: lane (lg, lc) holds channel cb*16+lc, pixels x0 + 8 lg + 2 i + b ----
+  // ---- store: lane (lg, lc) holds channel cb*16+lc, pixels x0 + 4 PX lg + j, j = PX i + b ----
   if (!active || !cg_on) return;
 #pragma unroll
   for (int cb = 0; cb < NCB; ++cb) {
@@ -747,9 +798,16 @@ P4BwdGeom p4_bwd_data_geom(const rotconv_plan* p) {
   g.lut = p4_bwd_lut(p) ? 1 : 0;
   if (g.lut) g.Q = p->B;        // the "banks" of the contraction are the base banks
   g.ncig = g.CinPad / CIG;
-  // table variant with several channel groups: the groups of a row build D together (k_p4_bwd_data_lut_shared):
-  // workgroups of 4 / ncg rows x ncg channel groups
-  g.ncg = g.lut && g.ncig >= 2 ? (g.ncig >= 3 ? 4 : 2) : 1;
+  // several channel groups, and one pool group per filter with one bank per base bank (the table variant, or a
+  // single bank): the groups of a row build D together (k_p4_bwd_data_shared): workgroups of 4 / ncg rows x ncg
+  // channel groups
+  bool one_bank = !g.lut && g.Q == 1 && g.ng == 1 && p->B == 1;     // ... whose bank is the base bank itself
+  for (int u = 0; u < 9 && one_bank; ++u)
+    for (int z = 0; z < kMaxNnz; ++z) {
+      const int src = p->host.fq_src[u * kMaxNnz + z];
+      if (z == 0 ? (src != u || p->host.fq_coef[u * kMaxNnz] != 1.0f) : src >= 0) one_bank = false;
+    }
+  g.ncg = (g.lut || one_bank) && g.ncig >= 2 ? (g.ncig >= 3 ? 4 : 2) : 1;
   g.ncigw = (g.ncig + g.ncg - 1) / g.ncg;
   // otherwise four-wave workgroups, two per CU; the table variant only with one table of at most 17 rows per offset
   // (two workgroups' weight chunks and tables then fill the 160 KB of LDS exactly)
@@ -758,7 +816,11 @@ P4BwdGeom p4_bwd_data_geom(const rotconv_plan* p) {
   g.nrb = (d.H + rows_wg - 1) / rows_wg;
   // pixels per lane: four when the rows are long enough and that still leaves a workgroup per CU
   g.px = ((d.W & 3) == 0 && d.W > 32 && d.N * g.ncig * ((d.H + 7) / 8) * ((d.W + 63) / 64) >= 256) ? 4 : 2;
-  if (g.lut) g.px = 2;      // the table build is made for two pixels per lane (four would spill)
+  // the unshared table build is made for two pixels per lane (four would spill); two groups sharing with four pixels
+  // per lane would leave room for one workgroup's D buffer and table per CU only
+  if (g.lut && g.ncg <= 2) g.px = 2;
+  // sharing workgroups are four waves: four pixels per lane only while that leaves two waves per SIMD
+  if (g.ncg > 1 && d.N * g.ncigw * g.nrb * ((d.W + 63) / 64) < 512) g.px = 2;
   g.nstrip = (d.W + 16 * g.px - 1) / (16 * g.px);
   g.units = d.N * g.ncigw * g.nstrip * g.nrb;
   // Few units and a long contraction: share its weight chunks (16 filters of a bank) out so that the chip is filled
@@ -817,15 +879,20 @@ void launch_p4_bwd_data(const rotconv_plan* p, const float* gpool, const uint8_t
   const P4BwdGeom g = p4_bwd_data_geom(p);
   float* dx = g.ksplit > 1 ? part : dx_out;
   if (g.ncg > 1) {
-    const size_t lds_s = ((size_t)g.Q * 9 * kLutRows * 12 + (size_t)(4 / g.ncg) * 4 * 9 * 2 * 64) * sizeof(float);
+    const size_t lds_s = ((size_t)(g.lut ? g.Q * 9 * kLutRows * 12 : 0) + (size_t)(4 / g.ncg) * 4 * 9 * g.px * 64) * sizeof(float);
     const int grid_s = (g.units + 7) / 8 * 8;
     auto gos = [&](auto kern) {
       (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_s);
       hipLaunchKernelGGL(kern, dim3(grid_s), dim3(64 * g.nw), lds_s, st, gpool, idx, reinterpret_cast<const f4*>(wd),
-                         p->dev.lut_bwd, dx, g);
+                         p->dev.rot_of, p->dev.lut_bwd, dx, g);
     };
-    if (g.ncg == 4) gos(k_p4_bwd_data_lut_shared<4>);
-    else gos(k_p4_bwd_data_lut_shared<2>);
+    if (g.lut) {
+      if (g.px == 4) { if (g.ncg == 4) gos(k_p4_bwd_data_shared<4, true, 4>); else gos(k_p4_bwd_data_shared<4, true, 2>); }
+      else { if (g.ncg == 4) gos(k_p4_bwd_data_shared<2, true, 4>); else gos(k_p4_bwd_data_shared<2, true, 2>); }
+    } else {
+      if (g.px == 4) { if (g.ncg == 4) gos(k_p4_bwd_data_shared<4, false, 4>); else gos(k_p4_bwd_data_shared<4, false, 2>); }
+      else { if (g.ncg == 4) gos(k_p4_bwd_data_shared<2, false, 4>); else gos(k_p4_bwd_data_shared<2, false, 2>); }
+    }
     if (g.ksplit > 1) {
       const size_t n_elem = (size_t)p->d.N * p->d.Cin * p->d.H * p->d.W;
       const unsigned blocks = (unsigned)std::max<size_t>(1, std::min<size_t>((n_elem / 4 + 255) / 256, 1u << 16));
