@@ -247,6 +247,21 @@ def test_forward_on_base_products(cfg):
         pu.run_fused_parity(cfg, dyadic=True, label=f"{cfg.name} dyadic")
 
 
+# Input gradient with the D of a row built by its channel groups together, four pixels per lane (launches that still
+# give every SIMD two waves): the per-bank build (R = 4, two groups) and the table build (R = 16, three groups).
+SHARED_PX4 = [
+    LC("t_shared_r4_px4", N=4, Cin=128, H=128, W=128, Cout=16, R=4, x_dist="absnormal", seed=81),
+    LC("t_shared_r16_px4", N=2, Cin=192, H=128, W=128, Cout=16, R=16, mode="bilinear", x_dist="absnormal", seed=82),
+]
+
+
+@pytest.mark.parametrize("cfg", SHARED_PX4, ids=lambda c: c.name)
+def test_input_gradient_shared_four_pixels_per_lane(cfg):
+    say(f"[case] shared input gradient, four pixels per lane {cfg.name}")
+    pu.run_fused_parity(cfg)
+    pu.run_fused_parity(cfg, dyadic=True, label=f"{cfg.name} dyadic") if cfg.R == 4 else None
+
+
 def test_forward_on_base_products_with_fused_relu():
     """The fused ReLU of that kernel: pooled values clamped at 0, idx 255 where the pooled value is not positive."""
     cfg = LC("t_base_relu", N=1, Cin=16, H=20, W=48, Cout=16, R=16, mode="bilinear", x_dist="normal", seed=80)
