@@ -32,6 +32,11 @@ sys.path.insert(0, ROOT)
 PEAK_FP32_TFLOPS = 157.3  # MI355X fp32 matrix (and vector) peak
 PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
 PEAK_HBM_GBS = 8000.0
+# Vector ALU: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz = 39.3e12 lane-instructions/s; the published 157.3 TFLOP/s fp32
+# vector peak is that rate with packed two-wide multiply-adds (x 2 x 2).  A kernel on the vector ALU is priced at the
+# published peak: a multiply-add counts 2 flop, an addition 1 flop at half of it (78.6e12 additions/s).  This build
+# keeps the packed fp32 forms off, so what it can reach is half of that roof (`frac_of_unpacked_alu_roof`).
+PEAK_VALU_LANE_OPS = 256 * 4 * 16 * 2.4e9
 PASSES = ["rotconv_pool_fwd", "rotconv_pool_bwd_data", "rotconv_pool_bwd_weight"]
 
 
@@ -91,7 +96,14 @@ def pass_accounting(N, Cin, Cout, H, W, R, q_paper, c_pooled, k, plan, pass_ms, 
         ms = pass_ms[name]
         f_exec = ce * plan.conv_equivalents(i) + adds
         f_alg = ce * q_paper + adds
-        roof_ms = max(f_exec / peak, nbytes[i] / (PEAK_HBM_GBS * 1e9)) * 1e3
+        t_hbm = nbytes[i] / (PEAK_HBM_GBS * 1e9)
+        valu = plan.kernel_name(i) == "valu_direct"
+        if valu:       # multiply-adds and placement additions as vector instructions, two per lane and clock at the peak
+            lane_ops = ce * plan.conv_equivalents(i) / 2.0 + adds
+            t_cmp = lane_ops / (2.0 * PEAK_VALU_LANE_OPS)
+        else:
+            t_cmp = f_exec / peak
+        roof_ms = max(t_cmp, t_hbm) * 1e3
         out[name] = {
             "ms": round(ms, 4), "kernel": plan.kernel_name(i),
             "flops_algorithmic": f_alg, "flops_executed": f_exec,
@@ -99,9 +111,11 @@ def pass_accounting(N, Cin, Cout, H, W, R, q_paper, c_pooled, k, plan, pass_ms, 
             "bytes_algorithmic": nbytes[i],
             "tflops_paper_count": round(f_alg / (ms * 1e-3) / 1e12, 2),
             "tflops_executed": round(f_exec / (ms * 1e-3) / 1e12, 2),
-            "bound": "mfma" if f_exec / peak >= nbytes[i] / (PEAK_HBM_GBS * 1e9) else "hbm",
+            "bound": "hbm" if t_hbm > t_cmp else "alu" if valu else "mfma",
             "roof_ms": round(roof_ms, 4), "frac_of_roof": round(roof_ms / ms, 4),
         }
+        if valu:
+            out[name]["frac_of_unpacked_alu_roof"] = round(max(2.0 * t_cmp, t_hbm) * 1e3 / ms, 4)
     return out
 
 

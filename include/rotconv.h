@@ -146,7 +146,10 @@ typedef struct {
                            -1 never (one contraction per bank)                                                 */
   int32_t fwd_base;     /* fp32 forward of such layers: 0 automatic (products of the base bank only, combined
                            into the banks' products on the vector ALU), -1 never (one contraction per bank)    */
-  int32_t reserved[3];  /* must be 0 */
+  int32_t direct;       /* layers with at most four input channels (a network's first layer): 0 automatic (the
+                           pooled forward on the vector-ALU kernel, no matrix instructions), -1 never             */
+  int32_t direct_ty;    /* rows per band of that kernel: 0 automatic, n > 0 = n                                   */
+  int32_t reserved[1];  /* must be 0 */
 } rotconv_plan_options;
 
 /* Validates the descriptor, builds the orientation tables on the host and

@@ -11,6 +11,7 @@
 #include "rotconv_bf16.h"
 #include "rotconv_p4.h"
 #include "rotconv_gs.h"
+#include "rotconv_direct.h"
 
 namespace rotconv {
 
@@ -163,6 +164,7 @@ bool unfused_on_gs(const rotconv_plan* p, const void* ws, size_t ws_bytes) {
 
 // how a pass runs: 2 bf16 matrix-core kernel, 1 fp32 matrix-core kernel, 0 generic
 int pass_level(const rotconv_plan* p, int pass) {
+  if (p->direct[pass]) return 2;
   if (p->d.dtype == ROTCONV_BF16 && p->native16[pass]) return 2;
   return p->fast[pass] ? 1 : 0;
 }
@@ -180,7 +182,7 @@ int rotconv_plan_create(const rotconv_desc* desc, rotconv_plan** out) {
 
 int rotconv_plan_create_opt(const rotconv_desc* desc, const rotconv_plan_options* opts, rotconv_plan** out) {
   if (!desc || !out) return ROTCONV_ERR_NULL;
-  if (opts && (opts->reserved[0] || opts->reserved[1] || opts->reserved[2])) return ROTCONV_ERR_UNSUPPORTED;
+  if (opts && (opts->reserved[0])) return ROTCONV_ERR_UNSUPPORTED;
   rotconv_plan* p = nullptr;
   const int rc = validate_and_build(desc, &p);
   if (rc != ROTCONV_OK) return rc;
@@ -199,6 +201,10 @@ int rotconv_plan_create_opt(const rotconv_desc* desc, const rotconv_plan_options
     p->fwd_base = 1;
     p->fwd_csplit[1] = 1;
     p->fwd_base_cls = p4_fwd_base_classify(p, &p->host.fwd_base_coef);
+  }
+  if (direct_fwd_supported(p)) {     // first layers: the pooled forward on the vector ALU
+    p->direct[0] = 1;
+    p->ws_bytes = std::max(p->ws_bytes, direct_fwd_pack_floats(p) * sizeof(float));
   }
   p->bwd_lut = p4_bwd_lut_choice(p) ? 1 : 0;
   p->fast[1] = p4_bwd_data_supported(p) ? 1 : 0;
@@ -733,9 +739,16 @@ bool bf16_pool_fwd_is_native(const rotconv_plan* plan, const void* x, const void
 
 // Bytes of `ws` one call of the pooled forward touches, by the route it takes for these pointers (never more than
 // rotconv_workspace_bytes, which is the largest need of any call on the plan).
+// Does the pooled forward run the vector-ALU kernel of layers with at most four input channels for these pointers?
+bool pool_fwd_is_direct(const rotconv_plan* p, const void* x, const void* ypool, const void* ws) {
+  const size_t es = is_bf16(p) ? 2 : 4;
+  return p->direct[0] && aligned(x, es) && aligned(ypool, es) && aligned(ws, 16);
+}
+
 size_t pool_fwd_need(const rotconv_plan* plan, const void* x, const void* w, const void* ypool, const uint8_t* idx,
                      const void* ws) {
   if (plan->pad_child && plan->pad_use[0]) return plan->ws_bytes;             // staging copies + the padded plan
+  if (pool_fwd_is_direct(plan, x, ypool, ws)) return align256(direct_fwd_pack_floats(plan) * sizeof(float));
   if (!is_bf16(plan)) return f32_pool_fwd_need(plan, x, ypool, idx, ws);
   if (bf16_pool_fwd_is_native(plan, x, w, ypool, idx, ws)) return std::min(plan->ws_bytes, fwd_fast_ws_bytes(plan));
   return plan->ws_bytes;                                                      // fp32 staging areas in front
@@ -757,6 +770,16 @@ int pool_fwd_impl(const rotconv_plan* plan, const void* x, const void* w, void* 
       return rc;
     launch_repitch(c.out, ypool, c.rows_p, c.Wp, c.W, c.es, 0, c.st);
     launch_repitch(c.idx, idx, c.rows_p, c.Wp, c.W, 1, 0, c.st);
+    return finish();
+  }
+  if (pool_fwd_is_direct(plan, x, ypool, ws)) {     // at most four input channels: the vector-ALU kernel
+    const size_t dneed = own_need ? pool_fwd_need(plan, x, w, ypool, idx, ws) : plan->ws_bytes;
+    if (!ws || ws_bytes < dneed) return ROTCONV_ERR_WORKSPACE;
+    if (no_upload && !tables_on_current_device(plan)) return ROTCONV_ERR_UNSUPPORTED;
+    rotconv_plan* p = const_cast<rotconv_plan*>(plan);
+    const int rc = ensure_device_tables(p);
+    if (rc) return rc;
+    launch_direct_fwd(p, x, w, ypool, idx, static_cast<float*>(ws), static_cast<hipStream_t>(stream));
     return finish();
   }
   if (!is_bf16(plan)) return f32_rotconv_pool_fwd(plan, x, w, ypool, idx, ws, ws_bytes, stream, own_need, no_upload);
@@ -931,6 +954,7 @@ double rotconv_plan_conv_equivalents(const rotconv_plan* plan, int pass) {
   if (plan->pad_child && plan->pad_use[pass]) return rotconv_plan_conv_equivalents(plan->pad_child, pass);
   const int Q = plan->host.Q, B = plan->B;
   if (plan->avg_child) return (double)plan->ng * rotconv_plan_conv_equivalents(plan->avg_child, pass);
+  if (plan->direct[pass]) return Q;     // one product set per first-quadrant bank, on the vector ALU
   if (plan->d.dtype == ROTCONV_BF16 && plan->native16[pass]) {
     int present = 0;      // orientations in the set: the bf16 gradient kernels multiply every quarter turn on its own
     for (int i = 0; i < Q * 4; ++i) present += plan->rot_of[i] >= 0 ? 1 : 0;
@@ -952,6 +976,7 @@ const char* rotconv_plan_kernel_name(const rotconv_plan* plan, int pass) {
   if (pass >= 3)      // the unfused gradient calls, given rotconv_workspace_bytes_unfused of scratch
     return plan->gs || (plan->d.pool_op != ROTCONV_POOL_AVG && gs_wanted(plan)) ? "mfma_gemm_scatter" : "generic";
   if (plan->pad_child && plan->pad_use[pass]) return rotconv_plan_kernel_name(plan->pad_child, pass);
+  if (plan->direct[pass]) return "valu_direct";
   if (plan->d.dtype == ROTCONV_BF16 && plan->native16[pass]) return plan->bwd_lut16[pass] ? "mfma_p4_bf16_lut" : "mfma_p4_bf16";
   if (pass == 0 && plan->fast[0] && plan->fwd_base) return "mfma_p4_base";   // the pooled forward; rotconv_fwd: mfma_p4
   return plan->fast[pass] ? "mfma_p4" : plan->gs ? "mfma_gemm_scatter" : "generic";

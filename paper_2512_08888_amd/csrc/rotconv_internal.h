@@ -96,6 +96,7 @@ struct rotconv_plan {
   int bwd_lut16[3] = {0, 0, 0}; // bf16 gradient kernels ([1] input, [2] weight gradient): the same table, D rounded to bf16 once
   int fwd_base = 0;             // fast fp32 pooled forward: products of the base bank only, banks combined on the vector ALU
   int fwd_base_cls = 0;         // its banks' classes (two bits per bank)
+  int direct[3] = {0, 0, 0};    // the pass runs the vector-ALU kernel of layers with at most four input channels
   int fwd_csplit[2] = {1, 1};   // fast forward: channel splits for the unpooled / the pooled output (1: none)
   // Average pooling (Eq. 9 / Eq. 11): the fused calls run one ordinary convolution (this R = 1 plan with
   // Cout * R/G filters) on the group-averaged bank.  Owned by the parent.

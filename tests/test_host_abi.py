@@ -201,6 +201,13 @@ def test_kernel_family_selection():
     assert names(rc.Plan(4, 32, 64, 64, 32, k=5, pad=2, R=8, mode="steerable")) == ["mfma_gemm_scatter"] * 3
     assert names(rc.Plan(4, 32, 64, 64, 32, k=3, stride=2, R=4)) == ["mfma_gemm_scatter"] * 3
     assert names(rc.Plan(1, 2, 9, 8, 3, k=5, pad=2, R=4)) == ["generic"] * 3       # tiny: one generic kernel
+    # at most four input channels (a first layer): the pooled forward on the vector-ALU kernel, whatever the row width
+    assert names(rc.Plan(4, 3, 512, 512, 64, k=3, R=4)) == ["valu_direct", "mfma_p4", "mfma_p4"]
+    assert names(rc.Plan(1, 3, 33, 37, 5, k=3, R=16, mode="bilinear"))[0] == "valu_direct"
+    assert names(rc.Plan(1, 3, 64, 64, 8, k=3, R=4, dtype=rc.BF16))[0] == "valu_direct"
+    assert names(rc.Plan(4, 3, 512, 512, 64, k=3, R=4, options=dict(direct=-1))) == ["mfma_p4"] * 3
+    assert names(rc.Plan(1, 3, 64, 64, 8, k=3, R=8, pool_group=4, mode="bilinear"))[0] != "valu_direct"   # sub-group pooling
+    assert names(rc.Plan(1, 3, 64, 64, 8, k=3, R=1))[0] != "valu_direct"            # no quarter turns to share
     # a pool group that cuts through a bank: the forward pools an unpooled map, the gradients take the other family
     p = rc.Plan(4, 32, 64, 64, 32, k=3, R=4, pool_group=2)
     assert names(p) == ["mfma_p4", "mfma_gemm_scatter", "mfma_gemm_scatter"]
@@ -218,7 +225,7 @@ def test_kernel_family_selection():
     # a non-zero reserved field is refused
     import ctypes
     bad = rc.PlanOptions()
-    bad.reserved[1] = 7
+    bad.reserved[0] = 7
     h = ctypes.c_void_p()
     d = rc.Plan(1, 2, 9, 8, 3).desc
     assert rc.lib().rotconv_plan_create_opt(ctypes.byref(d), ctypes.byref(bad), ctypes.byref(h)) == rc.ERR_UNSUPPORTED
