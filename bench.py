@@ -447,7 +447,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4", "C5", "P4", "P8", "P16", "sweep"])
+    ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4", "C5", "P4", "P8", "P16", "sweep", "C4_enc0a", "C5_enc0a"],
+                    help="C1-C3: the single layers; C4 / C5: the UNet-shaped training step; P4 / P8 / P16: the paper's own "
+                         "block; C4_enc0a / C5_enc0a: the first layer (3 -> 64 channels, 512 x 512) of those stacks alone")
     ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"],
                     help="storage type of activations and weights (accumulation is fp32 either way)")
     ap.add_argument("--pool-op", default="max", choices=["max", "avg"],
@@ -505,6 +507,11 @@ def main():
     dom = max(PASSES, key=lambda n: pass_ms[n])
     a = acc[dom]
     achieved = a["flops_executed"] / (a["ms"] * 1e-3) / 1e12
+    roof_unit = "TFLOP/s"
+    if a["bound"] == "alu":      # vector-ALU kernel: against the published fp32 vector peak (see PEAK_VALU_LANE_OPS)
+        peak, achieved = PEAK_FP32_TFLOPS, a["frac_of_roof"] * PEAK_FP32_TFLOPS
+    elif a["bound"] == "hbm":
+        peak, achieved, roof_unit = PEAK_HBM_GBS, a["bytes_algorithmic"] / (a["ms"] * 1e-3) / 1e9, "GB/s"
     std = args.workload in ("C2", "C3") and not args.group and not args.ksize and not args.stride and not avg
     out = {
         "metric": "rotconv_fwd_bwd_tflops", "value": 3.0 * fa / (ms_step * 1e-3) / 1e12, "unit": "TFLOP/s",
@@ -520,7 +527,7 @@ def main():
         },
         "roofline": {
             "bound": a["bound"], "kernel": f"{dom} ({a['kernel']})", "achieved": achieved,
-            "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
+            "peak": peak, "unit": roof_unit, "frac": achieved / peak,
             "flops_counted": "executed by the kernel (equal to the paper's count for this pass)"
             if a["flops_executed"] == a["flops_algorithmic"] else "executed by the kernel; the paper's count is in config.passes",
             "traffic": stored_traffic(f"{args.workload}:{dom}:{a['kernel']}") if std else None,

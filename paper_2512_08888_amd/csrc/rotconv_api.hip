@@ -206,6 +206,10 @@ int rotconv_plan_create_opt(const rotconv_desc* desc, const rotconv_plan_options
     p->direct[0] = 1;
     p->ws_bytes = std::max(p->ws_bytes, direct_fwd_pack_floats(p) * sizeof(float));
   }
+  if (direct_bwd_weight_supported(p)) {     // ... and, with a single bank, the weight gradient
+    p->direct[2] = 1;
+    p->ws_bytes = std::max(p->ws_bytes, direct_bwd_weight_ws_floats(p) * sizeof(float));
+  }
   p->bwd_lut = p4_bwd_lut_choice(p) ? 1 : 0;
   p->fast[1] = p4_bwd_data_supported(p) ? 1 : 0;
   if (p->fast[1])
@@ -919,6 +923,14 @@ int rotconv_pool_bwd_weight(const rotconv_plan* plan, const void* x, const void*
     launch_repitch(idx, c.idx, c.rows_p, c.W, c.Wp, 1, 0xff, c.st);
     return rotconv_pool_bwd_weight(c.ch, c.in, c.out, reinterpret_cast<const uint8_t*>(c.idx), dw, c.cws,
                                    c.ch->ws_bytes, stream);
+  }
+  if (plan->direct[2] && aligned(x, is_bf16(plan) ? 2 : 4) && aligned(gpool, is_bf16(plan) ? 2 : 4) && aligned(ws, 16)) {
+    if (!ws || ws_bytes < plan->ws_bytes) return ROTCONV_ERR_WORKSPACE;
+    rotconv_plan* p = const_cast<rotconv_plan*>(plan);
+    const int rc = ensure_device_tables(p);
+    if (rc) return rc;
+    launch_direct_bwd_weight(p, x, gpool, idx, static_cast<float*>(ws), dw, static_cast<hipStream_t>(stream));
+    return finish();
   }
   if (!is_bf16(plan)) return f32_rotconv_pool_bwd_weight(plan, x, gpool, idx, dw, ws, ws_bytes, stream);
   if (!ws || ws_bytes < plan->ws_bytes) return ROTCONV_ERR_WORKSPACE;

@@ -13,4 +13,10 @@ size_t direct_fwd_pack_floats(const rotconv_plan* p);
 void launch_direct_fwd(const rotconv_plan* p, const void* x, const void* w, void* ypool, uint8_t* idx, float* wb,
                        hipStream_t st);
 
+// weight gradient (single-bank layers): `part` holds direct_bwd_weight_ws_floats(p) floats of partial sums
+bool direct_bwd_weight_supported(const rotconv_plan* p);
+size_t direct_bwd_weight_ws_floats(const rotconv_plan* p);
+void launch_direct_bwd_weight(const rotconv_plan* p, const void* x, const void* gpool, const uint8_t* idx, float* part,
+                              float* dw, hipStream_t st);
+
 }  // namespace rotconv

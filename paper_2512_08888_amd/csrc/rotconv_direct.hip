@@ -278,6 +278,240 @@ __global__ __launch_bounds__(256) void k_direct_pack(const void* __restrict__ w,
   }
 }
 
+// ---- weight gradient of such layers with a single bank (R = 4 exact quarter turns) -------------------------------
+// dF[co,ci,u] = sum_pixels D_u[co,p] * X[ci,p],  D_u[co,p] = sum_s Delta_s[co, p - off_s(u)],  Delta_s = G * 1[idx == s]
+// (Eq. 12, 14, and Eq. 16's inverse rotation moved in front of the contraction: the routed gradients of the four
+// quarter turns are summed at the rotated tap positions first).  Same decomposition as the forward: a lane owns one
+// pixel column of the padded band-row sequence and walks down a band; a (G, idx) row is routed once into four values
+// that stay in registers while the row serves as h-1, h and h+1 (the row loop is unrolled three deep, the roles rotate
+// by renaming); the column neighbours are the adjacent lanes' registers, read by the additions through a wave shift.
+// 27 accumulators per filter and lane, added across the wave's lanes at the end of the band in a fixed order, one
+// partial sum per wave; k_direct_dw_finish adds the partial sums in ascending order and applies the transposed
+// first-quadrant table.  No atomics: bitwise reproducible.
+constexpr int kDwFB = 2;       // filters per wave
+
+struct DirWGeom {
+  int N, H, W, Cout, CoutPad, TY, nbr, nfb, nchunk;
+  long nb;
+};
+
+// the value the lane to the left (x - 1) / to the right (x + 1) holds; the wave's first / last lane gets 0.  Each use
+// below is the only use of its shifted value, so the compiler folds the shift into the addition.
+__device__ __forceinline__ float from_left(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x138, 0xf, 0xf, true));
+}
+__device__ __forceinline__ float from_right(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x130, 0xf, 0xf, true));
+}
+
+template <int CTRL, int ROWMASK>
+__device__ __forceinline__ float add_dpp(float acc, float v) {
+  return acc + __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROWMASK, 0xf, true));
+}
+// sum over the 64 lanes, in lanes 48..63 (fixed order)
+__device__ __forceinline__ float wave_sum(float v) {
+  v = add_dpp<0xb1, 0xf>(v, v);      // quad_perm [1,0,3,2]
+  v = add_dpp<0x4e, 0xf>(v, v);      // quad_perm [2,3,0,1]
+  v = add_dpp<0x141, 0xf>(v, v);     // row_half_mirror
+  v = add_dpp<0x140, 0xf>(v, v);     // row_mirror: every lane holds its row's sum
+  v = add_dpp<0x142, 0xa>(v, v);     // row_bcast:15 into rows 1 and 3
+  v = add_dpp<0x143, 0xc>(v, v);     // row_bcast:31 into rows 2 and 3
+  return v;
+}
+
+template <typename T, int CIN>
+__global__ __launch_bounds__(256) void k_direct_bwd_weight(const T* __restrict__ x, const T* __restrict__ gpool,
+                                                           const uint8_t* __restrict__ idx, float* __restrict__ part,
+                                                           const DirWGeom g) {
+  constexpr int FB = kDwFB, NA = CIN * 9;
+  const int lane = threadIdx.x & 63;
+  const int gw = __builtin_amdgcn_readfirstlane(blockIdx.x * 4 + (threadIdx.x >> 6));
+  const int fb = gw % g.nfb, chunk = gw / g.nfb;
+  if (chunk >= g.nchunk) return;
+  const int Wp = g.W + 2;
+  const long slot = (long)chunk * kSeg + lane;
+  const long b = slot / Wp;
+  const int xs = (int)(slot - b * Wp) - 1;
+  const int n = (int)(b / g.nbr);
+  const int y0 = (int)(b - (long)n * g.nbr) * g.TY;
+  const bool xin = b < g.nb && xs >= 0 && xs < g.W;
+  const bool own = xin && lane >= 1 && lane <= kSeg;      // the lanes whose D is complete: only they accumulate
+  const int HW = g.H * g.W;
+  const int co0 = fb * FB;
+  const unsigned xoff = xin ? (unsigned)(n * CIN * HW + xs) : 0u;
+  unsigned goff[FB];
+#pragma unroll
+  for (int f = 0; f < FB; ++f) goff[f] = xin ? (unsigned)((n * g.Cout + min(co0 + f, g.Cout - 1)) * HW + xs) : 0u;
+
+  float acc[FB][NA];
+#pragma unroll
+  for (int f = 0; f < FB; ++f)
+#pragma unroll
+    for (int i = 0; i < NA; ++i) acc[f][i] = 0.f;
+
+  struct Routed { float m[FB][4]; };
+  // (G, idx) of row y, routed: m[f][s] = G where idx == s, else 0 (rows outside the image, columns outside it and
+  // filters beyond Cout give zeros)
+  auto load_route = [&](int y, Routed& r) {
+    const bool in = xin && y >= 0 && y < g.H;
+    float gv[FB];
+    int iv[FB];
+#pragma unroll
+    for (int f = 0; f < FB; ++f) {
+      const unsigned o = in ? goff[f] + (unsigned)(y * g.W) : 0u;
+      gv[f] = ld(gpool + o);
+      iv[f] = idx[o];
+    }
+#pragma unroll
+    for (int f = 0; f < FB; ++f) {
+      const bool ok = in && co0 + f < g.Cout;
+#pragma unroll
+      for (int s = 0; s < 4; ++s) r.m[f][s] = (ok && iv[f] == s) ? gv[f] : 0.f;
+    }
+  };
+  auto load_x = [&](int y, float (&dst)[CIN]) {
+    const bool in = own && y >= 0 && y < g.H;
+    const unsigned o = in ? xoff + (unsigned)(y * g.W) : 0u;
+#pragma unroll
+    for (int ci = 0; ci < CIN; ++ci) dst[ci] = ld(x + (o + (in ? (unsigned)(ci * HW) : 0u)));
+#pragma unroll
+    for (int ci = 0; ci < CIN; ++ci) dst[ci] = in ? dst[ci] : 0.f;
+  };
+  // D of row h from the routed rows h-1 (up), h (mid), h+1 (dn), times X of row h
+  auto accumulate = [&](const Routed& up, const Routed& mid, const Routed& dn, const float (&xv)[CIN]) {
+#pragma unroll
+    for (int f = 0; f < FB; ++f) {
+#pragma unroll
+      for (int u = 0; u < 9; ++u) {
+        float d = 0.f;
+        bool first = true;
+        // plain terms first, so that a lane-shifted term always meets a plain register in its addition
+#pragma unroll
+        for (int pass = 0; pass < 2; ++pass)
+#pragma unroll
+          for (int s = 0; s < 4; ++s) {
+            const int i = tap_i(s, u), j = tap_j(s, u);
+            if ((j == 1) != (pass == 0)) continue;
+            const float mv = i == 0 ? dn.m[f][s] : i == 1 ? mid.m[f][s] : up.m[f][s];     // row h - (i - 1)
+            const float t = j == 0 ? from_right(mv) : j == 2 ? from_left(mv) : mv;        // column x - (j - 1)
+            d = first ? t : d + t;
+            first = false;
+          }
+#pragma unroll
+        for (int ci = 0; ci < CIN; ++ci) acc[f][ci * 9 + u] = fmaf(d, xv[ci], acc[f][ci * 9 + u]);
+      }
+    }
+  };
+
+  Routed ra, rb, rc;
+  float xa[CIN], xb[CIN], xc[CIN];
+  // rows y0-1 and y0 are routed before the loop; iteration t brings row y0 + t + 1 and finishes D row y0 + t
+  load_route(y0 - 1, ra);
+  load_route(y0, rb);
+  load_x(y0, xa);
+  const int rows = min(g.TY, g.H - y0);
+  for (int t = 0; t < rows; t += 3) {
+    load_route(y0 + t + 1, rc);
+    load_x(y0 + t + 1, xb);
+    accumulate(ra, rb, rc, xa);
+    if (t + 1 < rows) {
+      load_route(y0 + t + 2, ra);
+      load_x(y0 + t + 2, xc);
+      accumulate(rb, rc, ra, xb);
+    }
+    if (t + 2 < rows) {
+      load_route(y0 + t + 3, rb);
+      load_x(y0 + t + 3, xa);
+      accumulate(rc, ra, rb, xc);
+    }
+  }
+  float* dst = part + ((size_t)chunk * g.CoutPad + co0) * NA;
+#pragma unroll
+  for (int f = 0; f < FB; ++f)
+#pragma unroll
+    for (int i = 0; i < NA; ++i) {
+      const float sum = wave_sum(acc[f][i]);
+      if (lane == 63) dst[f * NA + i] = sum;
+    }
+}
+
+// dw[b][co][ci][ub] = sum_z coef_z * (sum over the waves' partial sums, ascending, of dF[co][ci][t_z]): the partial
+// sums of eight interleaved groups are added by eight threads and combined in a fixed tree, then the transposed
+// first-quadrant table (Eq. 16 / the adjoint of Eq. 17) is applied.  One workgroup per (filter, channel).
+__global__ __launch_bounds__(256) void k_direct_dw_finish(const float* __restrict__ part, float* __restrict__ dw,
+                                                          const int32_t* __restrict__ fqt_ptr,
+                                                          const int32_t* __restrict__ fqt_col,
+                                                          const float* __restrict__ fqt_coef, int B, int Cout, int Cin,
+                                                          int CoutPad, int nchunk) {
+  __shared__ float red[16][9];
+  __shared__ float tot[9];
+  const int co = blockIdx.x / Cin, ci = blockIdx.x % Cin;
+  const int t = threadIdx.x % 16, grp = threadIdx.x / 16;      // 16 groups x (9 taps used of 16)
+  const int NA = Cin * 9;
+  if (t < 9) {
+    float s = 0.f;
+    for (int c = grp; c < nchunk; c += 16) s += part[((size_t)c * CoutPad + co) * NA + ci * 9 + t];
+    red[grp][t] = s;
+  }
+  __syncthreads();
+  if (threadIdx.x < 9) {
+    const int u = threadIdx.x;
+    float a[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) a[i] = red[i][u];
+#pragma unroll
+    for (int n = 8; n >= 1; n /= 2)
+#pragma unroll
+      for (int i = 0; i < n; ++i) a[i] = a[i] + a[i + n];
+    tot[u] = a[0];
+  }
+  __syncthreads();
+  if (threadIdx.x < B * 9) {
+    const int b = threadIdx.x / 9, ub = threadIdx.x % 9;
+    float v = 0.f;
+    for (int z = fqt_ptr[b * 9 + ub]; z < fqt_ptr[b * 9 + ub + 1]; ++z) v += fqt_coef[z] * tot[fqt_col[z]];     // col = tap (one bank)
+    dw[((size_t)(b * Cout + co) * Cin + ci) * 9 + ub] = v;
+  }
+}
+
+DirWGeom direct_wgeom(const rotconv_plan* p) {
+  const rotconv_desc& d = p->d;
+  DirWGeom g{};
+  g.N = d.N; g.H = d.H; g.W = d.W; g.Cout = d.Cout;
+  g.nfb = (d.Cout + kDwFB - 1) / kDwFB;
+  g.CoutPad = g.nfb * kDwFB;
+  // band height: as for the forward (measured: 32 rows on 512 x 512 x 64 filters, where this picks 32)
+  int ty = std::min(std::max(p->opt.direct_ty, 1), d.H);
+  if (p->opt.direct_ty <= 0) {
+    long best = -1;
+    for (int t = std::min(8, d.H); t <= std::min(128, d.H); ++t) {
+      const long nb = (long)d.N * ((d.H + t - 1) / t);
+      const long waves = ((nb * (d.W + 2) - 1 + kSeg - 1) / kSeg) * g.nfb;
+      const long cost = ((waves + 1023) / 1024) * (t + 2);
+      if (best < 0 || cost < best) { best = cost; ty = t; }
+    }
+  }
+  g.TY = ty;
+  g.nbr = (d.H + ty - 1) / ty;
+  g.nb = (long)d.N * g.nbr;
+  g.nchunk = (int)((g.nb * (d.W + 2) - 1 + kSeg - 1) / kSeg);
+  return g;
+}
+
+template <typename T>
+void launch_w(int Cin, const DirWGeom& g, const void* x, const void* gpool, const uint8_t* idx, float* part,
+              hipStream_t st) {
+  const dim3 grid((unsigned)(((long)g.nchunk * g.nfb + 3) / 4));
+  const T* xp = static_cast<const T*>(x);
+  const T* gp = static_cast<const T*>(gpool);
+  switch (Cin) {
+    case 1: hipLaunchKernelGGL((k_direct_bwd_weight<T, 1>), grid, dim3(256), 0, st, xp, gp, idx, part, g); break;
+    case 2: hipLaunchKernelGGL((k_direct_bwd_weight<T, 2>), grid, dim3(256), 0, st, xp, gp, idx, part, g); break;
+    case 3: hipLaunchKernelGGL((k_direct_bwd_weight<T, 3>), grid, dim3(256), 0, st, xp, gp, idx, part, g); break;
+    default: hipLaunchKernelGGL((k_direct_bwd_weight<T, 4>), grid, dim3(256), 0, st, xp, gp, idx, part, g); break;
+  }
+}
+
 int direct_fb(int Q) { return 8 / Q; }            // filters per wave: eight (filter, bank) pairs
 
 int direct_pitch(int Cin) { return (Cin * 9 + 3) / 4 * 4; }
@@ -379,6 +613,32 @@ void launch_direct_fwd(const rotconv_plan* p, const void* x, const void* w, void
   const bool relu = d.activation == ROTCONV_ACT_RELU;
   if (is16) launch_t<uint16_t>(d.Cin, Q, g, relu, x, wb, ypool, idx, st);
   else launch_t<float>(d.Cin, Q, g, relu, x, wb, ypool, idx, st);
+}
+
+}  // namespace rotconv
+
+namespace rotconv {
+
+// The weight gradient on the vector ALU: the forward's conditions with a single first-quadrant bank (R = 4), fp32
+// plans.  With several banks the table kernels on the matrix cores execute fewer instructions, and on bf16 tensors
+// the bf16 matrix-core kernel is the faster one (measured on 4 x 3 x 512 x 512 -> 64: 0.139 against 0.173 ms).
+bool direct_bwd_weight_supported(const rotconv_plan* p) {
+  return direct_fwd_supported(p) && p->host.Q == 1 && p->d.dtype == ROTCONV_F32;
+}
+
+size_t direct_bwd_weight_ws_floats(const rotconv_plan* p) {
+  const DirWGeom g = direct_wgeom(p);
+  return (size_t)g.nchunk * g.CoutPad * p->d.Cin * 9;
+}
+
+void launch_direct_bwd_weight(const rotconv_plan* p, const void* x, const void* gpool, const uint8_t* idx, float* part,
+                              float* dw, hipStream_t st) {
+  const rotconv_desc& d = p->d;
+  const DirWGeom g = direct_wgeom(p);
+  if (d.dtype == ROTCONV_BF16) launch_w<uint16_t>(d.Cin, g, x, gpool, idx, part, st);
+  else launch_w<float>(d.Cin, g, x, gpool, idx, part, st);
+  hipLaunchKernelGGL(k_direct_dw_finish, dim3(d.Cout * d.Cin), dim3(256), 0, st, part, dw, p->dev.fqt_ptr,
+                     p->dev.fqt_col, p->dev.fqt_coef, p->B, d.Cout, d.Cin, g.CoutPad, g.nchunk);
 }
 
 }  // namespace rotconv

@@ -122,7 +122,11 @@ C1 = LayerConfig("C1", N=1, Cin=3, H=64, W=64, Cout=8, R=4, x_dist="uniform", se
 C2 = LayerConfig("C2", N=8, Cin=64, H=256, W=256, Cout=64, R=4, x_dist="absnormal", seed=2000)
 C3 = LayerConfig("C3", N=4, Cin=128, H=128, W=128, Cout=128, R=16, mode="bilinear", x_dist="absnormal", seed=3000)
 
-CONFIGS = {"C1": C1, "C2": C2, "C3": C3}
+# The first layer (RGB image -> 64 filters) of the UNet-shaped stacks of configurations 4 and 5, as a layer of its own.
+C4_ENC0A = LayerConfig("C4_enc0a", N=4, Cin=3, H=512, W=512, Cout=64, R=4, x_dist="uniform", seed=4100)
+C5_ENC0A = LayerConfig("C5_enc0a", N=2, Cin=3, H=512, W=512, Cout=64, R=16, mode="bilinear", x_dist="uniform", seed=5100)
+
+CONFIGS = {"C1": C1, "C2": C2, "C3": C3, "C4_enc0a": C4_ENC0A, "C5_enc0a": C5_ENC0A}
 
 
 def make_x(cfg: LayerConfig) -> np.ndarray:

@@ -44,6 +44,8 @@ CASES = [
 
 def direct_plan_check(plan):
     assert plan.kernel_name(0) == "valu_direct", plan.kernel_name(0)
+    # the weight gradient of fp32 plans runs the vector-ALU kernel too when the layer has a single bank (R = 4)
+    assert (plan.kernel_name(2) == "valu_direct") == (plan.R == 4 and plan.desc.dtype == rc.F32), plan.kernel_name(2)
 
 
 @pytest.mark.parametrize("cfg", CASES, ids=lambda c: c.name)
@@ -163,3 +165,43 @@ def test_first_layer_full_size_forward_element_by_element(cfg):
     abs_terms = orc.rotconv_fwd(np.abs(x), np.abs(w_rot), cfg.stride, cfg.pad)
     ties = pu.check_idx(idx, y, abs_terms, cfg.G, f"{cfg.name} idx")
     say(f"  {idx.size} outputs ok, {ties} accepted near-ties")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_direct_weight_gradient_through_fused_relu(dtype):
+    """The weight gradient fed the idx of a fused-ReLU forward (255 where the pooled value was not positive) equals
+    the weight gradient of the plain plan fed the masked upstream gradient, bit for bit; two runs agree bit for bit."""
+    cfg = dataclasses.replace(next(c for c in CASES if c.name == "d_w130"), x_dist="normal")
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    dt = rc.BF16 if dtype == "bf16" else rc.F32
+    plain, fused = rc.Plan.from_config(cfg, dtype=dt), rc.Plan.from_config(cfg, dtype=dt, relu=True)
+    assert (plain.kernel_name(2) == "valu_direct") == (dtype == "f32")
+    x, w, g = (pu.dev(a, tdt) for a in (synth.make_x(cfg), synth.make_w(cfg), synth.make_g(cfg)))
+    P = (cfg.N, plain.Cpooled, plain.Ho, plain.Wo)
+    y0, i0 = torch.empty(P, dtype=tdt, device="cuda"), torch.empty(P, dtype=torch.uint8, device="cuda")
+    y1, i1 = torch.empty_like(y0), torch.empty_like(i0)
+    rc.rotconv_pool_fwd(plain, x, w, y0, i0)
+    rc.rotconv_pool_fwd(fused, x, w, y1, i1)
+    gm = torch.where(y0 > 0, g, torch.zeros_like(g))
+    dws = [torch.full(w.shape, float("nan"), device="cuda") for _ in range(3)]
+    rc.rotconv_pool_bwd_weight(plain, x, gm, i0, dws[0])
+    rc.rotconv_pool_bwd_weight(fused, x, g, i1, dws[1])
+    rc.rotconv_pool_bwd_weight(fused, x, g, i1, dws[2])
+    torch.cuda.synchronize()
+    assert torch.equal(dws[0], dws[1]) and torch.equal(dws[1], dws[2])
+    assert float(dws[0].abs().max()) > 0
+
+
+def test_first_layer_full_size_weight_gradient():
+    """The weight gradient of configuration 4's first layer at full size, in the launch configuration bench.py times:
+    every (filter, channel) slice against the oracle's gradient of the rotated banks, reduced through Eq. 16."""
+    cfg = FIRST_LAYERS[0]
+    say(f"[case] first layer full size dW {cfg}")
+    x, w, g = synth.make_x(cfg), synth.make_w(cfg), synth.make_g(cfg)
+    L = pu.GpuLayer(cfg, x, w)
+    assert L.plan.kernel_name(2) == "valu_direct"
+    yp, idx = L.pool_fwd()
+    dw = L.pool_bwd_weight(g, idx)
+    dy = orc.orient_maxpool_bwd(g, idx, cfg.R, cfg.G)
+    dw_ref = orc.reduce_bank_grad(orc.rotconv_bwd_weight(x, dy, cfg.k, cfg.stride, cfg.pad), None, cfg.mode)
+    pu.assert_close(dw, dw_ref, f"{cfg.name} dw")

@@ -288,7 +288,8 @@ def test_forward_per_bank_kernels(name):
     into a wave's filter columns, or per-bank candidates through memory)."""
     cfg = next(c for c in TINY if c.name == name)
     say(f"[case] forward per bank {name}")
-    out = pu.run_fused_parity(cfg, options=dict(fwd_base=-1))
+    # (layers with at most four input channels: the vector-ALU kernel switched off as well)
+    out = pu.run_fused_parity(cfg, options=dict(fwd_base=-1, direct=-1))
     assert out["layer"].plan.kernel_name(0) == "mfma_p4"
 
 
@@ -317,7 +318,8 @@ def test_unfused_gradients_with_the_larger_workspace(name):
     # and would run the generic kernels with either workspace)
     L = pu.GpuLayer(cfg, x, w, options=dict(gs=1))
     names = [L.plan.kernel_name(i) for i in range(5)]
-    assert names[0] in ("mfma_p4", "mfma_p4_base") and names[1:] == ["mfma_p4"] * 2 + ["mfma_gemm_scatter"] * 2, names
+    assert names[0] in ("mfma_p4", "mfma_p4_base", "valu_direct") and names[1] == "mfma_p4", names
+    assert names[2] in ("mfma_p4", "valu_direct") and names[3:] == ["mfma_gemm_scatter"] * 2, names
     dyd = synth.make_dy(cfg)
     ang = None if cfg.angles_deg is None else list(cfg.angles_deg)
     w_rot = orc.expand_bank(w, cfg.R, ang, cfg.mode)

@@ -202,7 +202,8 @@ def test_kernel_family_selection():
     assert names(rc.Plan(4, 32, 64, 64, 32, k=3, stride=2, R=4)) == ["mfma_gemm_scatter"] * 3
     assert names(rc.Plan(1, 2, 9, 8, 3, k=5, pad=2, R=4)) == ["generic"] * 3       # tiny: one generic kernel
     # at most four input channels (a first layer): the pooled forward on the vector-ALU kernel, whatever the row width
-    assert names(rc.Plan(4, 3, 512, 512, 64, k=3, R=4)) == ["valu_direct", "mfma_p4", "mfma_p4"]
+    assert names(rc.Plan(4, 3, 512, 512, 64, k=3, R=4)) == ["valu_direct", "mfma_p4", "valu_direct"]
+    assert names(rc.Plan(2, 3, 512, 512, 64, k=3, R=16, mode="bilinear"))[2] == "mfma_p4"      # several banks: the table kernel
     assert names(rc.Plan(1, 3, 33, 37, 5, k=3, R=16, mode="bilinear"))[0] == "valu_direct"
     assert names(rc.Plan(1, 3, 64, 64, 8, k=3, R=4, dtype=rc.BF16))[0] == "valu_direct"
     assert names(rc.Plan(4, 3, 512, 512, 64, k=3, R=4, options=dict(direct=-1))) == ["mfma_p4"] * 3
