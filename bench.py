@@ -512,7 +512,7 @@ def main():
         peak, achieved = PEAK_FP32_TFLOPS, a["frac_of_roof"] * PEAK_FP32_TFLOPS
     elif a["bound"] == "hbm":
         peak, achieved, roof_unit = PEAK_HBM_GBS, a["bytes_algorithmic"] / (a["ms"] * 1e-3) / 1e9, "GB/s"
-    std = args.workload in ("C2", "C3") and not args.group and not args.ksize and not args.stride and not avg
+    std = args.workload in ("C2", "C3", "C4_enc0a", "C5_enc0a") and not args.group and not args.ksize and not args.stride and not avg
     out = {
         "metric": "rotconv_fwd_bwd_tflops", "value": 3.0 * fa / (ms_step * 1e-3) / 1e12, "unit": "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
