@@ -149,7 +149,11 @@ typedef struct {
   int32_t direct;       /* layers with at most four input channels (a network's first layer): 0 automatic (the
                            pooled forward on the vector-ALU kernel, no matrix instructions), -1 never             */
   int32_t direct_ty;    /* rows per band of that kernel: 0 automatic, n > 0 = n                                   */
-  int32_t reserved[1];  /* must be 0 */
+  int32_t px_fwd;       /* bf16 pooled forward of layers with 8 to 128 input channels pooled over all orientations:
+                           0 automatic (filters on the matrix instruction's M side, a lane per pixel column, for
+                           layers with four banks and at most 64 input channels), 1 wherever that kernel can run,
+                           -1 never (pixels on the M side, eight pixels per lane)                                   */
+  int32_t reserved[4];  /* must be 0 */
 } rotconv_plan_options;
 
 /* Validates the descriptor, builds the orientation tables on the host and

@@ -57,7 +57,7 @@ class PlanOptions(ctypes.Structure):
     _fields_ = [
         ("fwd_csplit", ctypes.c_int32), ("gs", ctypes.c_int32), ("gs_chunk_mb", ctypes.c_int32),
         ("bwd_lut", ctypes.c_int32), ("fwd_base", ctypes.c_int32), ("direct", ctypes.c_int32),
-        ("direct_ty", ctypes.c_int32), ("reserved", ctypes.c_int32 * 1),
+        ("direct_ty", ctypes.c_int32), ("px_fwd", ctypes.c_int32), ("reserved", ctypes.c_int32 * 4),
     ]
 
 
@@ -166,7 +166,7 @@ class Plan:
     def __init__(self, N, Cin, H, W, Cout, k=3, R=4, angles_deg: Optional[Sequence[float]] = None, mode="exact90",
                  stride=1, pad=1, pool_group=0, dtype=F32, pool_op="max", relu=False, options=None):
         """options: dict of rotconv_plan_options fields (fwd_csplit, gs, gs_chunk_mb, bwd_lut, fwd_base, direct,
-        direct_ty) or None."""
+        direct_ty, px_fwd) or None."""
         self._h = ctypes.c_void_p()
         self._angles = None
         ang = None

@@ -12,6 +12,7 @@
 #include "rotconv_p4.h"
 #include "rotconv_gs.h"
 #include "rotconv_direct.h"
+#include "rotconv_px_fwd_bf16.h"
 
 namespace rotconv {
 
@@ -164,7 +165,7 @@ bool unfused_on_gs(const rotconv_plan* p, const void* ws, size_t ws_bytes) {
 
 // how a pass runs: 2 bf16 matrix-core kernel, 1 fp32 matrix-core kernel, 0 generic
 int pass_level(const rotconv_plan* p, int pass) {
-  if (p->direct[pass]) return 2;
+  if (p->direct[pass] || (pass == 0 && p->px16)) return 2;
   if (p->d.dtype == ROTCONV_BF16 && p->native16[pass]) return 2;
   return p->fast[pass] ? 1 : 0;
 }
@@ -182,7 +183,7 @@ int rotconv_plan_create(const rotconv_desc* desc, rotconv_plan** out) {
 
 int rotconv_plan_create_opt(const rotconv_desc* desc, const rotconv_plan_options* opts, rotconv_plan** out) {
   if (!desc || !out) return ROTCONV_ERR_NULL;
-  if (opts && (opts->reserved[0])) return ROTCONV_ERR_UNSUPPORTED;
+  if (opts && (opts->reserved[0] || opts->reserved[1] || opts->reserved[2] || opts->reserved[3])) return ROTCONV_ERR_UNSUPPORTED;
   rotconv_plan* p = nullptr;
   const int rc = validate_and_build(desc, &p);
   if (rc != ROTCONV_OK) return rc;
@@ -205,6 +206,10 @@ int rotconv_plan_create_opt(const rotconv_desc* desc, const rotconv_plan_options
   if (direct_fwd_supported(p)) {     // first layers: the pooled forward on the vector ALU
     p->direct[0] = 1;
     p->ws_bytes = std::max(p->ws_bytes, direct_fwd_pack_floats(p) * sizeof(float));
+  }
+  if (!p->direct[0] && px_fwd_bf16_supported(p)) {     // bf16, shallow layers: a lane per pixel column
+    p->px16 = 1;
+    p->ws_bytes = std::max(p->ws_bytes, px_fwd_bf16_pack_bytes(p));
   }
   if (direct_bwd_weight_supported(p)) {     // ... and, with a single bank, the weight gradient
     p->direct[2] = 1;
@@ -749,9 +754,14 @@ bool pool_fwd_is_direct(const rotconv_plan* p, const void* x, const void* ypool,
   return p->direct[0] && aligned(x, es) && aligned(ypool, es) && aligned(ws, 16);
 }
 
+bool pool_fwd_is_px16(const rotconv_plan* p, const void* x, const void* ypool, const void* ws) {
+  return p->px16 && aligned(x, 2) && aligned(ypool, 2) && aligned(ws, 16);
+}
+
 size_t pool_fwd_need(const rotconv_plan* plan, const void* x, const void* w, const void* ypool, const uint8_t* idx,
                      const void* ws) {
   if (plan->pad_child && plan->pad_use[0]) return plan->ws_bytes;             // staging copies + the padded plan
+  if (pool_fwd_is_px16(plan, x, ypool, ws)) return align256(px_fwd_bf16_pack_bytes(plan));
   if (pool_fwd_is_direct(plan, x, ypool, ws)) return align256(direct_fwd_pack_floats(plan) * sizeof(float));
   if (!is_bf16(plan)) return f32_pool_fwd_need(plan, x, ypool, idx, ws);
   if (bf16_pool_fwd_is_native(plan, x, w, ypool, idx, ws)) return std::min(plan->ws_bytes, fwd_fast_ws_bytes(plan));
@@ -784,6 +794,17 @@ int pool_fwd_impl(const rotconv_plan* plan, const void* x, const void* w, void* 
     const int rc = ensure_device_tables(p);
     if (rc) return rc;
     launch_direct_fwd(p, x, w, ypool, idx, static_cast<float*>(ws), static_cast<hipStream_t>(stream));
+    return finish();
+  }
+  if (pool_fwd_is_px16(plan, x, ypool, ws)) {
+    const size_t pneed = own_need ? pool_fwd_need(plan, x, w, ypool, idx, ws) : plan->ws_bytes;
+    if (!ws || ws_bytes < pneed) return ROTCONV_ERR_WORKSPACE;
+    if (no_upload && !tables_on_current_device(plan)) return ROTCONV_ERR_UNSUPPORTED;
+    rotconv_plan* p = const_cast<rotconv_plan*>(plan);
+    const int rc = ensure_device_tables(p);
+    if (rc) return rc;
+    launch_px_fwd_bf16(p, h16(x), h16(w), static_cast<uint16_t*>(ypool), idx, static_cast<uint16_t*>(ws),
+                       static_cast<hipStream_t>(stream));
     return finish();
   }
   if (!is_bf16(plan)) return f32_rotconv_pool_fwd(plan, x, w, ypool, idx, ws, ws_bytes, stream, own_need, no_upload);
@@ -989,6 +1010,7 @@ const char* rotconv_plan_kernel_name(const rotconv_plan* plan, int pass) {
     return plan->gs || (plan->d.pool_op != ROTCONV_POOL_AVG && gs_wanted(plan)) ? "mfma_gemm_scatter" : "generic";
   if (plan->pad_child && plan->pad_use[pass]) return rotconv_plan_kernel_name(plan->pad_child, pass);
   if (plan->direct[pass]) return "valu_direct";
+  if (pass == 0 && plan->px16) return "mfma_px_bf16";
   if (plan->d.dtype == ROTCONV_BF16 && plan->native16[pass]) return plan->bwd_lut16[pass] ? "mfma_p4_bf16_lut" : "mfma_p4_bf16";
   if (pass == 0 && plan->fast[0] && plan->fwd_base) return "mfma_p4_base";   // the pooled forward; rotconv_fwd: mfma_p4
   return plan->fast[pass] ? "mfma_p4" : plan->gs ? "mfma_gemm_scatter" : "generic";

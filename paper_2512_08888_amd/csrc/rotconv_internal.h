@@ -97,6 +97,7 @@ struct rotconv_plan {
   int fwd_base = 0;             // fast fp32 pooled forward: products of the base bank only, banks combined on the vector ALU
   int fwd_base_cls = 0;         // its banks' classes (two bits per bank)
   int direct[3] = {0, 0, 0};    // the pass runs the vector-ALU kernel of layers with at most four input channels
+  int px16 = 0;                 // bf16 pooled forward: the kernel with a lane per pixel column (filters on M)
   int fwd_csplit[2] = {1, 1};   // fast forward: channel splits for the unpooled / the pooled output (1: none)
   // Average pooling (Eq. 9 / Eq. 11): the fused calls run one ordinary convolution (this R = 1 plan with
   // Cout * R/G filters) on the group-averaged bank.  Owned by the parent.

@@ -53,6 +53,13 @@ CASES = [
     LC("b_lut_ste_c192", N=1, Cin=192, H=6, W=32, Cout=20, R=16, mode="steerable", x_dist="absnormal", seed=78),
     # the input gradient with shared D and its K-steps split over workgroups
     LC("b_lut_ks_c384", N=1, Cin=384, H=5, W=32, Cout=192, R=16, mode="bilinear", x_dist="absnormal", seed=79),
+    # the forward with a lane per pixel column: one to four K-steps, a last K-step with idle channel groups, padded rows
+    # that end inside / at a wave's 14 outputs, ragged filter blocks, several images and bands, all three modes
+    LC("b_px_c8", N=2, Cin=8, H=9, W=12, Cout=5, R=4, seed=81),
+    LC("b_px_c40_w26", N=1, Cin=40, H=35, W=26, Cout=20, R=8, mode="bilinear", seed=82),
+    LC("b_px_c72_w27", N=2, Cin=72, H=7, W=27, Cout=33, R=16, mode="bilinear", x_dist="absnormal", seed=83),
+    LC("b_px_c128_ste", N=1, Cin=128, H=40, W=70, Cout=16, R=16, mode="steerable", x_dist="absnormal", seed=84),
+    LC("b_px_c104_r4", N=3, Cin=104, H=6, W=13, Cout=48, R=4, seed=85),
     # a layer on which one arg-max sat just outside the fp32 near-tie band when the rotated weights were formed in fp32
     # (one of them rounded to the neighbouring bf16 value); they are formed in fp64 now: the regression case
     LC("b_r16_bank_rounding", N=2, Cin=32, H=19, W=160, Cout=136, R=16, mode="bilinear", x_dist="absnormal", seed=9148),
@@ -99,7 +106,34 @@ def reference_bwd(cfg, x, w_rot, g, idx, ang):
 
 @pytest.mark.parametrize("cfg", CASES, ids=[c.name for c in CASES])
 def test_bf16_fused_calls(cfg):
-    plan = rc.Plan.from_config(cfg, dtype=rc.BF16)
+    run_bf16_fused(cfg)
+
+
+def px_plan(cfg):
+    """Can the pooled forward of this layer's bf16 plan take the kernel with a lane per pixel column?  (3 x 3 / stride 1
+    / pad 1, 8 to 128 input channels in eights, one pool group over an evenly spaced set of 4, 8 or 16 orientations; it
+    is the default for R = 16 up to 64 channels, plan option px_fwd = 1 takes it wherever it can run.)"""
+    return (cfg.k == 3 and cfg.stride == 1 and cfg.pad == 1 and 8 <= cfg.Cin <= 128 and cfg.Cin % 8 == 0 and cfg.G == cfg.R
+            and cfg.R in (4, 8, 16) and cfg.mode != "p4m" and cfg.angles_deg is None)
+
+
+PX_CASES = [c for c in CASES if px_plan(c)]
+
+
+@pytest.mark.parametrize("cfg", PX_CASES, ids=[c.name for c in PX_CASES])
+def test_bf16_fused_calls_on_both_forward_kernels(cfg):
+    """The layers whose forward can take the pixel-column kernel, on that kernel (plan option px_fwd = 1) and on the
+    kernel with eight pixels per lane (px_fwd = -1), whichever of the two the default plan picks."""
+    assert rc.Plan.from_config(cfg, dtype=rc.BF16, options=dict(px_fwd=1)).kernel_name(0) == "mfma_px_bf16"
+    assert rc.Plan.from_config(cfg, dtype=rc.BF16, options=dict(px_fwd=-1)).kernel_name(0) == "mfma_p4_bf16"
+    default = rc.Plan.from_config(cfg, dtype=rc.BF16).kernel_name(0)
+    assert (default == "mfma_px_bf16") == (cfg.R == 16 and cfg.Cin <= 64)
+    run_bf16_fused(cfg, options=dict(px_fwd=1))
+    run_bf16_fused(cfg, options=dict(px_fwd=-1))
+
+
+def run_bf16_fused(cfg, options=None):
+    plan = rc.Plan.from_config(cfg, dtype=rc.BF16, options=options)
     print(f"[case] bf16 fused {cfg.name} kernels {[plan.kernel_name(i) for i in range(3)]}", flush=True)
     ang = None if cfg.angles_deg is None else list(cfg.angles_deg)
     xd, x = bf(synth.make_x(cfg))
@@ -149,16 +183,23 @@ def test_bf16_gradients_per_bank_kernels(name):
     assert_close(f64(dw), dw_ref, f"{cfg.name} dw (fp32)", rtol=RTOL)
 
 
-DYADIC = [CASES[1], CASES[5], CASES[7], LC("b_dy_stream", N=1, Cin=512, H=6, W=64, Cout=16, R=4, seed=63),
+DYADIC = [CASES[1], CASES[5], CASES[7], next(c for c in CASES if c.name == "b_px_c8"), next(c for c in CASES if c.name == "b_px_c104_r4"), LC("b_dy_stream", N=1, Cin=512, H=6, W=64, Cout=16, R=4, seed=63),
           LC("b_dy_co64", N=1, Cin=40, H=20, W=64, Cout=64, R=4, seed=69),
           LC("b_dy_co576", N=1, Cin=8, H=5, W=64, Cout=576, R=4, seed=70)]
 
 
 @pytest.mark.parametrize("cfg", DYADIC, ids=[c.name for c in DYADIC])
 def test_bf16_dyadic_bit_exact(cfg):
+    run_bf16_dyadic(cfg)
+    if px_plan(cfg):
+        run_bf16_dyadic(cfg, options=dict(px_fwd=1))
+        run_bf16_dyadic(cfg, options=dict(px_fwd=-1))
+
+
+def run_bf16_dyadic(cfg, options=None):
     """Inputs on the exact-arithmetic grid (all representable in bf16; every fp32 partial sum exact in any
     order): pooled output = the oracle's rounded once to bf16, arg-max and dX (rounded once) bit for bit."""
-    plan = rc.Plan.from_config(cfg, dtype=rc.BF16)
+    plan = rc.Plan.from_config(cfg, dtype=rc.BF16, options=options)
     print(f"[case] bf16 dyadic {cfg.name}", flush=True)
     xd, x = bf(synth.make_x_dyadic(cfg))
     wd, w = bf(synth.make_w_dyadic(cfg))

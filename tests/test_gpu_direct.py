@@ -90,14 +90,14 @@ def test_direct_forward_against_the_matrix_core_kernel(name):
 def test_direct_forward_bf16(cfg):
     plan = rc.Plan.from_config(cfg, dtype=rc.BF16)
     direct_plan_check(plan)
-    tb.test_bf16_fused_calls(cfg)
+    tb.run_bf16_fused(cfg)
 
 
 @pytest.mark.parametrize("cfg", [CASES[0], CASES[5], CASES[6]], ids=lambda c: c.name)
 def test_direct_forward_bf16_dyadic_bit_exact(cfg):
     plan = rc.Plan.from_config(cfg, dtype=rc.BF16)
     direct_plan_check(plan)
-    tb.test_bf16_dyadic_bit_exact(cfg)
+    tb.run_bf16_dyadic(cfg)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
