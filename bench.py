@@ -447,9 +447,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4", "C5", "P4", "P8", "P16", "sweep", "C4_enc0a", "C5_enc0a"],
+    ap.add_argument("--workload", default="C2", choices=["C1", "C2", "C3", "C4", "C5", "P4", "P8", "P16", "sweep", "C4_enc0a", "C5_enc0a", "C5_enc0b"],
                     help="C1-C3: the single layers; C4 / C5: the UNet-shaped training step; P4 / P8 / P16: the paper's own "
-                         "block; C4_enc0a / C5_enc0a: the first layer (3 -> 64 channels, 512 x 512) of those stacks alone")
+                         "block; C4_enc0a / C5_enc0a: the first layer (3 -> 64 channels, 512 x 512) of those stacks alone; C5_enc0b: the second one (64 -> 64)")
     ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"],
                     help="storage type of activations and weights (accumulation is fp32 either way)")
     ap.add_argument("--pool-op", default="max", choices=["max", "avg"],
@@ -512,7 +512,7 @@ def main():
         peak, achieved = PEAK_FP32_TFLOPS, a["frac_of_roof"] * PEAK_FP32_TFLOPS
     elif a["bound"] == "hbm":
         peak, achieved, roof_unit = PEAK_HBM_GBS, a["bytes_algorithmic"] / (a["ms"] * 1e-3) / 1e9, "GB/s"
-    std = args.workload in ("C2", "C3", "C4_enc0a", "C5_enc0a") and not args.group and not args.ksize and not args.stride and not avg
+    std = args.workload in ("C2", "C3", "C4_enc0a", "C5_enc0a", "C5_enc0b") and not args.group and not args.ksize and not args.stride and not avg
     out = {
         "metric": "rotconv_fwd_bwd_tflops", "value": 3.0 * fa / (ms_step * 1e-3) / 1e12, "unit": "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,

@@ -51,7 +51,12 @@ __global__ __launch_bounds__(64 * NWV, NWV == 4 ? 2 : 1) void k_px_fwd_bf16(cons
   constexpr int NOP = Q * NKS * 9;          // matrix operands of a filter block
   extern __shared__ u4 Wl[];                // [Q][NKS][9][64]
   const int tid = threadIdx.x;
-  const int fb = blockIdx.x % g.nfb, grp = blockIdx.x / g.nfb;
+  // XCD-aware order (workgroup i runs on XCD i % 8): the filter blocks of one group of pixel chunks follow one another
+  // on the same XCD and share its L2 copy of the input rows
+  const int nwg = g.ngrp * g.nfb, per_xcd = (nwg + 7) / 8;
+  const int v = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  if (v >= nwg) return;
+  const int fb = v % g.nfb, grp = v / g.nfb;
   {
     const u4* src = wt + (size_t)fb * NOP * 64;
     for (int i = tid; i < NOP * 64; i += 64 * NWV) Wl[i] = src[i];
@@ -252,7 +257,7 @@ template <int Q, int NKS>
 void launch_k(const PxGeom& g, int nwv, bool relu, const uint16_t* x, const uint16_t* wt, uint16_t* ypool, uint8_t* idx,
               hipStream_t st) {
   const size_t lds = (size_t)Q * NKS * 9 * 1024;
-  const dim3 grid((unsigned)(g.ngrp * g.nfb));
+  const dim3 grid((unsigned)((g.ngrp * g.nfb + 7) / 8 * 8));
   auto go = [&](auto kern, int nw) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     hipLaunchKernelGGL(kern, grid, dim3(64 * nw), lds, st, x, reinterpret_cast<const u4*>(wt), ypool, idx, g);

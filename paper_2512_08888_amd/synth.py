@@ -126,7 +126,10 @@ C3 = LayerConfig("C3", N=4, Cin=128, H=128, W=128, Cout=128, R=16, mode="bilinea
 C4_ENC0A = LayerConfig("C4_enc0a", N=4, Cin=3, H=512, W=512, Cout=64, R=4, x_dist="uniform", seed=4100)
 C5_ENC0A = LayerConfig("C5_enc0a", N=2, Cin=3, H=512, W=512, Cout=64, R=16, mode="bilinear", x_dist="uniform", seed=5100)
 
-CONFIGS = {"C1": C1, "C2": C2, "C3": C3, "C4_enc0a": C4_ENC0A, "C5_enc0a": C5_ENC0A}
+# ... and the second one (64 -> 64 channels at full resolution), the shallow R = 16 layer of configuration 5.
+C5_ENC0B = LayerConfig("C5_enc0b", N=2, Cin=64, H=512, W=512, Cout=64, R=16, mode="bilinear", x_dist="absnormal", seed=5200)
+
+CONFIGS = {"C1": C1, "C2": C2, "C3": C3, "C4_enc0a": C4_ENC0A, "C5_enc0a": C5_ENC0A, "C5_enc0b": C5_ENC0B}
 
 
 def make_x(cfg: LayerConfig) -> np.ndarray:

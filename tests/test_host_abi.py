@@ -209,6 +209,14 @@ def test_kernel_family_selection():
     assert names(rc.Plan(4, 3, 512, 512, 64, k=3, R=4, options=dict(direct=-1))) == ["mfma_p4"] * 3
     assert names(rc.Plan(1, 3, 64, 64, 8, k=3, R=8, pool_group=4, mode="bilinear"))[0] != "valu_direct"   # sub-group pooling
     assert names(rc.Plan(1, 3, 64, 64, 8, k=3, R=1))[0] != "valu_direct"            # no quarter turns to share
+    # bf16 forward with a lane per pixel column: R = 16 up to 64 input channels by default, px_fwd = 1 wherever it can run
+    b16 = dict(k=3, R=16, mode="bilinear", dtype=rc.BF16)
+    assert names(rc.Plan(2, 64, 64, 64, 64, **b16))[0] == "mfma_px_bf16"
+    assert names(rc.Plan(2, 64, 64, 64, 64, options=dict(px_fwd=-1), **b16))[0] == "mfma_p4_bf16"
+    assert names(rc.Plan(2, 128, 64, 64, 64, **b16))[0] == "mfma_p4_bf16"
+    assert names(rc.Plan(2, 128, 64, 64, 64, options=dict(px_fwd=1), **b16))[0] == "mfma_px_bf16"
+    assert names(rc.Plan(2, 136, 64, 64, 64, options=dict(px_fwd=1), **b16))[0] == "mfma_p4_bf16"     # beyond 128 channels
+    assert names(rc.Plan(2, 64, 64, 64, 64, k=3, R=4, dtype=rc.BF16))[0] == "mfma_p4_bf16"
     # a pool group that cuts through a bank: the forward pools an unpooled map, the gradients take the other family
     p = rc.Plan(4, 32, 64, 64, 32, k=3, R=4, pool_group=2)
     assert names(p) == ["mfma_p4", "mfma_gemm_scatter", "mfma_gemm_scatter"]
