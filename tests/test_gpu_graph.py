@@ -18,6 +18,8 @@ CASES = [
     LC("g_csplit", N=1, Cin=160, H=6, W=8, Cout=18, R=8, mode="bilinear", seed=72),   # channel split + ordered sums
     LC("g_padw", N=1, Cin=8, H=9, W=13, Cout=6, R=4, seed=73),                         # staged on padded rows
     LC("g_gs", N=2, Cin=32, H=24, W=24, Cout=32, k=5, pad=2, R=8, mode="steerable", seed=74),   # GEMM + scatter
+    LC("g_first", N=2, Cin=3, H=20, W=70, Cout=12, R=4, seed=75),                      # first layer: vector-ALU kernels
+    LC("g_px", N=1, Cin=64, H=12, W=40, Cout=24, R=16, mode="bilinear", seed=76),      # bf16: a lane per pixel column
 ]
 
 
