@@ -24,7 +24,8 @@ def _cases():
         (L("na_csplit", N=1, Cin=512, H=8, W=8, Cout=32, R=4, x_dist="absnormal", seed=702), rc.F32),   # channel-split parts
         (L("na_r16_fold", N=1, Cin=32, H=32, W=32, Cout=16, R=16, mode="bilinear", x_dist="absnormal", seed=703),
          rc.F32),                                                                                        # banks folded
-        (L("na_r16_cand", N=1, Cin=3, H=32, W=32, Cout=8, R=16, mode="bilinear", seed=704), rc.F32),    # per-bank candidates
+        (L("na_r16_first", N=1, Cin=3, H=32, W=32, Cout=8, R=16, mode="bilinear", seed=704), rc.F32),   # first layer: vector ALU
+        (L("na_px", N=1, Cin=64, H=20, W=32, Cout=16, R=16, mode="bilinear", x_dist="absnormal", seed=707), rc.BF16),   # bf16, a lane per pixel column
         (L("na_bf16", N=1, Cin=32, H=16, W=32, Cout=16, R=4, x_dist="absnormal", seed=705), rc.BF16),   # bf16 kernel
         (L("na_generic", N=1, Cin=2, H=7, W=5, Cout=3, R=3, mode="bilinear", pad=0, seed=706), rc.F32), # generic family
     ]
