@@ -274,7 +274,9 @@ const char* rotconv_status_string(int status);
 double rotconv_plan_conv_equivalents(const rotconv_plan* plan, int pass);
 /* Name of the kernel family a call of the given kind on this plan uses ("generic", "mfma_p4", "mfma_p4_base" (the
  * pooled forward on products of the base bank), "mfma_p4_bf16", "mfma_p4_bf16_lut" (a bf16 gradient whose routed
- * gradients are folded into the base taps in fp32 and rounded to bf16 once, the matrix operand), "mfma_gemm_scatter").  pass: 0 / 1 / 2 = the fused calls rotconv_pool_fwd / _bwd_data / _bwd_weight (and
+ * gradients are folded into the base taps in fp32 and rounded to bf16 once, the matrix operand), "mfma_gemm_scatter",
+ * "valu_direct" (layers with at most four input channels: vector ALU only), "mfma_px_bf16" (the bf16 pooled forward with
+ * a lane per pixel column)).  pass: 0 / 1 / 2 = the fused calls rotconv_pool_fwd / _bwd_data / _bwd_weight (and
  * rotconv_fwd); 3 / 4 = the unfused gradient calls rotconv_bwd_data / rotconv_bwd_weight when given
  * rotconv_workspace_bytes_unfused of scratch (with less they run "generic"). */
 const char* rotconv_plan_kernel_name(const rotconv_plan* plan, int pass);
