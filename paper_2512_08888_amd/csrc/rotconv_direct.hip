@@ -51,7 +51,8 @@ __device__ __forceinline__ float ld(const uint16_t* p) { return bf16_to_f32(*p);
 template <int CIN>
 constexpr int wpitch() { return (CIN * 9 + 3) / 4 * 4; }
 
-template <typename T, int CIN, int Q, int FB, bool RELU>
+// PB: every bank is pooled on its own (pool groups of the four quarter turns, Sec. V-A): Q pooled channels per filter.
+template <typename T, int CIN, int Q, int FB, bool RELU, bool PB = false>
 __global__ __launch_bounds__(256) void k_direct_fwd(const T* __restrict__ x, const float* __restrict__ wb,
                                                     T* __restrict__ ypool, uint8_t* __restrict__ idx, const DirGeom g) {
   constexpr int R = 4 * Q, K = FB * Q, NW = CIN * 9;
@@ -69,7 +70,7 @@ __global__ __launch_bounds__(256) void k_direct_fwd(const T* __restrict__ x, con
   const bool outl = xin && lane >= 1 && lane <= kSeg;
   const int HW = g.H * g.W;
   const unsigned xoff = xin ? (unsigned)(n * CIN * HW + xs) : 0u;   // + ci * HW + y * W
-  const unsigned ooff = (unsigned)(n * g.Cout * HW + xs);           // + co * HW + y * W
+  const unsigned ooff = (unsigned)(n * g.Cout * (PB ? Q : 1) * HW + xs);      // + pooled channel * HW + y * W
   const int co0 = fb * FB;
   cfloat* wbase = (cfloat*)wb + (size_t)co0 * Q * wpitch<CIN>();
 
@@ -121,26 +122,27 @@ __global__ __launch_bounds__(256) void k_direct_fwd(const T* __restrict__ x, con
       place_row(P, A[k], B[k], o);
 #pragma unroll
       for (int s = 0; s < 4; ++s) out[s * Q + q] = o[s];
-      if (q == Q - 1) {
+      if (PB || q == Q - 1) {
         // Eq. 10: the maximum first (a tree of three-input maxima), then the smallest orientation that attains it:
-        // the R - 1 equality tests do not depend on one another
-        float m[R];
+        // the equality tests do not depend on one another.  PB: the group is this bank's four quarter turns.
+        constexpr int NC = PB ? 4 : R;             // candidates; candidate j is orientation (PB ? j * Q + q : j)
+        float m[NC], cand[NC];
 #pragma unroll
-        for (int r = 0; r < R; ++r) m[r] = out[r];
-        int n = R;
+        for (int j = 0; j < NC; ++j) m[j] = cand[j] = PB ? o[j] : out[j];
+        int n = NC;
 #pragma unroll
         for (; n >= 3; n -= 2) m[n - 3] = max3(m[n - 3], m[n - 2], m[n - 1]);
         float best = n == 2 ? max2(m[0], m[1]) : m[0];
-        int bi = R - 1;
+        int bi = PB ? (NC - 1) * Q + q : NC - 1;
 #pragma unroll
-        for (int r = R - 2; r >= 0; --r) bi = out[r] == best ? r : bi;
+        for (int j = NC - 2; j >= 0; --j) bi = cand[j] == best ? (PB ? j * Q + q : j) : bi;
         if (RELU) {     // fused ReLU: dead elements get idx 255 (no orientation)
           const bool dead = !(best > 0.f);
           best = dead ? 0.f : best;
           bi = dead ? 255 : bi;
         }
         if (store && co0 + f < g.Cout) {     // a wave-uniform channel base plus the lane's 32-bit byte offset
-          const size_t cbase = (size_t)(co0 + f + zero) * HW;     // scalar arithmetic here, not 2 x FB live bases
+          const size_t cbase = (size_t)((co0 + f + zero) * (PB ? Q : 1) + (PB ? q : 0)) * HW;     // scalar arithmetic, in the loop
           st_at(ypool + cbase, orow * (unsigned)sizeof(T), best);
           st_at(idx + cbase, orow, bi);
         }
@@ -455,55 +457,56 @@ DirGeom direct_geom(const rotconv_plan* p) {
 }
 
 template <typename T, int CIN, int Q>
-void launch_q(const DirGeom& g, bool relu, const void* x, const float* wb, void* ypool, uint8_t* idx, hipStream_t st) {
+void launch_q(const DirGeom& g, bool relu, bool pb, const void* x, const float* wb, void* ypool, uint8_t* idx,
+              hipStream_t st) {
   constexpr int FB = 8 / Q;
   const long waves = (long)g.nchunk * g.nfb;
   const dim3 grid((unsigned)((waves + 3) / 4));
-  if (relu)
-    hipLaunchKernelGGL((k_direct_fwd<T, CIN, Q, FB, true>), grid, dim3(256), 0, st, static_cast<const T*>(x), wb,
-                       static_cast<T*>(ypool), idx, g);
-  else
-    hipLaunchKernelGGL((k_direct_fwd<T, CIN, Q, FB, false>), grid, dim3(256), 0, st, static_cast<const T*>(x), wb,
-                       static_cast<T*>(ypool), idx, g);
+  auto go = [&](auto kern) {
+    hipLaunchKernelGGL(kern, grid, dim3(256), 0, st, static_cast<const T*>(x), wb, static_cast<T*>(ypool), idx, g);
+  };
+  if (Q > 1 && pb) { if (relu) go(k_direct_fwd<T, CIN, Q, FB, true, (Q > 1)>); else go(k_direct_fwd<T, CIN, Q, FB, false, (Q > 1)>); }
+  else { if (relu) go(k_direct_fwd<T, CIN, Q, FB, true, false>); else go(k_direct_fwd<T, CIN, Q, FB, false, false>); }
 }
 
 template <typename T, int CIN>
-void launch_c(int Q, const DirGeom& g, bool relu, const void* x, const float* wb, void* ypool, uint8_t* idx,
+void launch_c(int Q, const DirGeom& g, bool relu, bool pb, const void* x, const float* wb, void* ypool, uint8_t* idx,
               hipStream_t st) {
   switch (Q) {
-    case 1: launch_q<T, CIN, 1>(g, relu, x, wb, ypool, idx, st); break;
-    case 2: launch_q<T, CIN, 2>(g, relu, x, wb, ypool, idx, st); break;
-    default: launch_q<T, CIN, 4>(g, relu, x, wb, ypool, idx, st); break;
+    case 1: launch_q<T, CIN, 1>(g, relu, pb, x, wb, ypool, idx, st); break;
+    case 2: launch_q<T, CIN, 2>(g, relu, pb, x, wb, ypool, idx, st); break;
+    default: launch_q<T, CIN, 4>(g, relu, pb, x, wb, ypool, idx, st); break;
   }
 }
 
 template <typename T>
-void launch_t(int Cin, int Q, const DirGeom& g, bool relu, const void* x, const float* wb, void* ypool, uint8_t* idx,
-              hipStream_t st) {
+void launch_t(int Cin, int Q, const DirGeom& g, bool relu, bool pb, const void* x, const float* wb, void* ypool,
+              uint8_t* idx, hipStream_t st) {
   switch (Cin) {
-    case 1: launch_c<T, 1>(Q, g, relu, x, wb, ypool, idx, st); break;
-    case 2: launch_c<T, 2>(Q, g, relu, x, wb, ypool, idx, st); break;
-    case 3: launch_c<T, 3>(Q, g, relu, x, wb, ypool, idx, st); break;
-    default: launch_c<T, 4>(Q, g, relu, x, wb, ypool, idx, st); break;
+    case 1: launch_c<T, 1>(Q, g, relu, pb, x, wb, ypool, idx, st); break;
+    case 2: launch_c<T, 2>(Q, g, relu, pb, x, wb, ypool, idx, st); break;
+    case 3: launch_c<T, 3>(Q, g, relu, pb, x, wb, ypool, idx, st); break;
+    default: launch_c<T, 4>(Q, g, relu, pb, x, wb, ypool, idx, st); break;
   }
 }
 
 }  // namespace
 
 // The kernel takes: 3 x 3, stride 1, pad 1, at most four input channels, max-pooling over ALL R orientations of a
-// filter, an orientation set closed under quarter turns and numbered r = s * Q + q (evenly spaced sets) with one, two
-// or four first-quadrant banks; tensors whose byte offsets fit 32 bits.  Any N, H, W, Cout, any mode.
+// filter or over the four quarter turns of each bank (pool groups of four), an orientation set closed under quarter
+// turns and numbered r = s * Q + q (evenly spaced sets) with one, two or four first-quadrant banks; tensors whose byte
+// offsets fit 32 bits.  Any N, H, W, Cout, any mode.
 bool direct_fwd_supported(const rotconv_plan* p) {
   const rotconv_desc& d = p->d;
   if (p->opt.direct < 0) return false;
   if (d.k != 3 || d.stride != 1 || d.pad != 1 || d.Cin > 4 || d.pool_op != ROTCONV_POOL_MAX) return false;
   const int Q = p->host.Q;
-  if (p->ng != 1 || d.R != 4 * Q || (Q != 1 && Q != 2 && Q != 4)) return false;
+  if ((p->ng != 1 && p->ng != Q) || d.R != 4 * Q || (Q != 1 && Q != 2 && Q != 4)) return false;
   for (int q = 0; q < Q; ++q)
     for (int s = 0; s < 4; ++s)
       if (p->rot_of[q * 4 + s] != s * Q + q) return false;
   const size_t lim = (size_t)1 << 31;
-  if ((size_t)d.N * d.Cout * d.H * d.W * 4 >= lim || (size_t)d.N * d.Cin * d.H * d.W * 4 >= lim) return false;
+  if ((size_t)d.N * d.Cout * p->ng * d.H * d.W * 4 >= lim || (size_t)d.N * d.Cin * d.H * d.W * 4 >= lim) return false;
   return true;
 }
 
@@ -524,8 +527,9 @@ void launch_direct_fwd(const rotconv_plan* p, const void* x, const void* w, void
                      p->dev.fq_coef64, Q, d.Cin, d.Cout, CoutPad, pitch, is16 ? 1 : 0);
   const DirGeom g = direct_geom(p);
   const bool relu = d.activation == ROTCONV_ACT_RELU;
-  if (is16) launch_t<uint16_t>(d.Cin, Q, g, relu, x, wb, ypool, idx, st);
-  else launch_t<float>(d.Cin, Q, g, relu, x, wb, ypool, idx, st);
+  const bool pb = p->ng > 1;       // pool groups of four quarter turns: every bank pooled on its own
+  if (is16) launch_t<uint16_t>(d.Cin, Q, g, relu, pb, x, wb, ypool, idx, st);
+  else launch_t<float>(d.Cin, Q, g, relu, pb, x, wb, ypool, idx, st);
 }
 
 }  // namespace rotconv

@@ -39,6 +39,9 @@ CASES = [
     LC("d_r16_bil", N=1, Cin=3, H=33, W=37, Cout=5, R=16, mode="bilinear", seed=309),
     LC("d_r16_ste", N=2, Cin=2, H=9, W=66, Cout=3, R=16, mode="steerable", seed=310),
     LC("d_h1", N=1, Cin=3, H=1, W=1, Cout=2, R=4, seed=311),
+    # pool groups of four quarter turns (the paper's own block): every bank pooled on its own, Q pooled channels per filter
+    LC("d_r8_g4", N=2, Cin=3, H=13, W=70, Cout=7, R=8, mode="bilinear", pool_group=4, seed=312),
+    LC("d_r16_g4", N=1, Cin=4, H=9, W=33, Cout=5, R=16, mode="steerable", pool_group=4, seed=313),
 ]
 
 
@@ -86,7 +89,7 @@ def test_direct_forward_against_the_matrix_core_kernel(name):
     assert out["layer"].plan.kernel_name(0) != "valu_direct"
 
 
-@pytest.mark.parametrize("cfg", CASES[:3] + CASES[6:8] + CASES[9:11], ids=lambda c: c.name)
+@pytest.mark.parametrize("cfg", CASES[:3] + CASES[6:8] + CASES[9:11] + CASES[12:], ids=lambda c: c.name)
 def test_direct_forward_bf16(cfg):
     plan = rc.Plan.from_config(cfg, dtype=rc.BF16)
     direct_plan_check(plan)

@@ -207,7 +207,8 @@ def test_kernel_family_selection():
     assert names(rc.Plan(1, 3, 33, 37, 5, k=3, R=16, mode="bilinear"))[0] == "valu_direct"
     assert names(rc.Plan(1, 3, 64, 64, 8, k=3, R=4, dtype=rc.BF16))[0] == "valu_direct"
     assert names(rc.Plan(4, 3, 512, 512, 64, k=3, R=4, options=dict(direct=-1))) == ["mfma_p4"] * 3
-    assert names(rc.Plan(1, 3, 64, 64, 8, k=3, R=8, pool_group=4, mode="bilinear"))[0] != "valu_direct"   # sub-group pooling
+    assert names(rc.Plan(1, 3, 64, 64, 8, k=3, R=8, pool_group=4, mode="bilinear"))[0] == "valu_direct"   # every bank pooled on its own
+    assert names(rc.Plan(1, 3, 64, 64, 8, k=3, R=8, pool_group=2, mode="bilinear"))[0] != "valu_direct"   # groups that cut through a bank
     assert names(rc.Plan(1, 3, 64, 64, 8, k=3, R=1))[0] != "valu_direct"            # no quarter turns to share
     # bf16 forward with a lane per pixel column: R = 16 up to 64 input channels by default, px_fwd = 1 wherever it can run
     b16 = dict(k=3, R=16, mode="bilinear", dtype=rc.BF16)
