@@ -120,7 +120,7 @@ __global__ __launch_bounds__(64 * NW, 2) void k_p4_bwd_data(const float* __restr
   const int n = v / g.nrb;
 
   const int tid = threadIdx.x;
-  const int wave = tid / 64, lane = tid % 64;
+  const int wave = __builtin_amdgcn_readfirstlane(tid / 64), lane = tid % 64;
   const int lg = lane / 16, lc = lane % 16;
   const int h = rb * NW + wave;
   const int x0 = strip * 16 * PX;
@@ -136,14 +136,22 @@ __global__ __launch_bounds__(64 * NW, 2) void k_p4_bwd_data(const float* __restr
   // staging registers are live at any time.
   constexpr int Q4 = 4 * 9 * (CIG / 4);        // float4 per quarter chunk (576)
   f4 wreg[WREG];
+  // A thread's slots sit at the same byte offsets inside every quarter chunk: computed once, so that a load is a
+  // wave-uniform base (chunk, quarter: scalar arithmetic) plus a 32-bit lane offset and costs no vector instruction.
+  uint32_t woff[WREG];
+#pragma unroll
+  for (int k = 0; k < WREG; ++k) {
+    const int e = min(tid + k * NT, Q4 - 1);
+    const int c4 = e % (CIG / 4), u = (e / (CIG / 4)) % 9, r = e / (9 * (CIG / 4));
+    woff[k] = (uint32_t)(((r * 9 + u) * g.CinPad + c4 * 4) * (int)sizeof(float));
+  }
+  const float* wgrp = wd + cig * CIG;
   auto wload = [&](int cc, int part) {
+    const char* wq = reinterpret_cast<const char*>(wgrp + ((size_t)(cbase + cc) * CHUNK + part * 4) * 9 * g.CinPad);
 #pragma unroll
     for (int k = 0; k < WREG; ++k) {
       const int e = tid + k * NT;
-      if (e < Q4) {
-        const int c4 = e % (CIG / 4), u = (e / (CIG / 4)) % 9, r = part * 4 + e / (9 * (CIG / 4));
-        wreg[k] = *reinterpret_cast<const f4*>(wd + ((size_t)((cbase + cc) * CHUNK + r) * 9 + u) * g.CinPad + cig * CIG + c4 * 4);
-      }
+      if (e < Q4) wreg[k] = *reinterpret_cast<const f4*>(wq + woff[k]);
     }
   };
   auto wstore = [&](int buf, int part) {
@@ -163,25 +171,30 @@ __global__ __launch_bounds__(64 * NW, 2) void k_p4_bwd_data(const float* __restr
   // is computed once; per K-step the address is a wave-uniform base plus 32-bit lane offsets.
   // Out-of-range positions read a clamped (valid) address and get the idx byte 0xff, which matches no
   // orientation (R <= 255), so they contribute nothing; so do lanes whose filter is beyond Cout (they
-  // read filter 0).  Nothing is computed from a loaded value before the K-step that uses it, so the
+  // read the last filter).  Nothing is computed from a loaded value before the K-step that uses it, so the
   // loads stay in flight for two K-steps.
+  // A load address is a wave-uniform part -- image, pool group, first filter of the K-step, row (a wave owns one row):
+  // scalar arithmetic -- plus a lane part that is the same in every K-step: the lane's filter among the four and its
+  // column.  (One image of the pooled gradient has fewer than 2^30 elements: checked when the plan takes this kernel.)
   const int xa = x0 + PX * lc;                 // first of this lane's PX pixels (W % PX == 0: in or out together)
-  uint32_t offc[3], offe[3], invc[3], inve[3];   // invc: centre bytes, inve: byte 0 left, byte 1 right
+  const uint32_t plane = (uint32_t)g.ng * (uint32_t)HW;          // floats between consecutive filters
+  uint32_t rowoff[3], invc[3], inve[3];        // invc: centre bytes, inve: byte 0 left, byte 1 right
 #pragma unroll
   for (int dr = 0; dr < 3; ++dr) {
     const int row = h - 1 + dr;
     const bool rok = active && row >= 0 && row < g.H;
     const bool okc = rok && xa < g.W, okl = rok && xa >= 1 && xa - 1 < g.W, okr = rok && xa + PX < g.W;
-    const uint32_t rowoff = (uint32_t)(rok ? row : 0) * (uint32_t)g.W;
-    offc[dr] = rowoff + (uint32_t)(okc ? xa : 0);
-    // the edge load: the row's first lane fetches its left neighbour, the last lane its right neighbour; the lanes
-    // between them read the first lane's address too (one cache line for the fifteen; their value is not used)
-    const bool okl0 = rok && x0 >= 1 && x0 - 1 < g.W;
-    offe[dr] = lc == 15 ? rowoff + (uint32_t)(okr ? xa + PX : 0) : rowoff + (uint32_t)(okl0 ? x0 - 1 : 0);
+    rowoff[dr] = (uint32_t)(rok ? row : 0) * (uint32_t)g.W;
     invc[dr] = okc ? 0u : 0xffffffffu;
     inve[dr] = (okl ? 0u : 0xffu) | (okr ? 0u : 0xff00u);
   }
-  const uint32_t plane = (uint32_t)g.ng * (uint32_t)HW;          // floats between consecutive filters
+  // the edge load: the row's first lane fetches its left neighbour, the last lane its right neighbour; the lanes
+  // between them read the first lane's address too (one cache line for the fifteen; their value is not used)
+  const uint32_t colc = (uint32_t)(xa < g.W ? xa : 0);
+  const uint32_t cole = lc == 15 ? (uint32_t)(xa + PX < g.W ? xa + PX : 0) : (uint32_t)(x0 >= 1 && x0 - 1 < g.W ? x0 - 1 : 0);
+  const uint32_t lgplane = (uint32_t)lg * plane;
+  const uint32_t ec = lgplane + colc, ee = lgplane + cole;       // element offsets (the idx bytes), and in bytes of G:
+  const uint32_t ec4 = ec * 4u, ee4 = ee * 4u;
   const float* gimg = gpool + (size_t)n * g.Cout * plane;
   const uint8_t* iimg = idx + (size_t)n * g.Cout * plane;
   auto bank_rot = [&](int q, int (&rot)[4]) {                     // orientation index of each quarter turn (-1: absent)
@@ -202,25 +215,34 @@ __global__ __launch_bounds__(64 * NW, 2) void k_p4_bwd_data(const float* __restr
     ld_pg = group_of(r);
   }
   auto raw_load = [&](Raw<PX>& r) {
-    const bool fok = ld_co + lg < g.Cout;
-    const uint32_t fl = (uint32_t)(fok ? ld_co + lg : 0) * plane;   // lane's filter plane
-    const float* gb = gimg + (size_t)ld_pg * HW;
-    const uint8_t* ib = iimg + (size_t)ld_pg * HW;
-    r.finv = fok ? 0u : 0xffffffffu;
+    const int fco = min(ld_co, g.Cout - 1);      // first filter of the K-step (clamped: a K-step of the padding)
+    const int lim = g.Cout - 1 - fco;            // lanes with lg > lim hold no filter: they read filter fco + lim
+    const size_t kbase = (size_t)ld_pg * HW + (size_t)fco * plane;
+    const float* gb = gimg + kbase;
+    const uint8_t* ib = iimg + kbase;
+    uint32_t oc = ec, oe = ee, oc4 = ec4, oe4 = ee4;
+    r.finv = 0u;
+    if (lim < 3 || ld_co >= g.Cout) {            // wave-uniform: the K-step reaches beyond Cout
+      const uint32_t back = (uint32_t)(lg - min(lg, lim)) * plane;
+      oc -= back; oe -= back; oc4 -= back * 4u; oe4 -= back * 4u;
+      r.finv = ld_co + lg < g.Cout ? 0u : 0xffffffffu;
+    }
 #pragma unroll
     for (int dr = 0; dr < 3; ++dr) {
+      const char* gr = reinterpret_cast<const char*>(gb + rowoff[dr]);
+      const uint8_t* ir = ib + rowoff[dr];
       if (PX == 2) {
-        const float2 v = *reinterpret_cast<const float2*>(gb + (fl + offc[dr]));
+        const float2 v = *reinterpret_cast<const float2*>(gr + oc4);
         r.gc[dr][0] = v.x; r.gc[dr][1] = v.y;
-        r.ic[dr] = *reinterpret_cast<const uint16_t*>(ib + (fl + offc[dr]));
+        r.ic[dr] = *reinterpret_cast<const uint16_t*>(ir + oc);
       } else {
-        const f4 v = *reinterpret_cast<const f4*>(gb + (fl + offc[dr]));
+        const f4 v = *reinterpret_cast<const f4*>(gr + oc4);
 #pragma unroll
         for (int p = 0; p < PX; ++p) r.gc[dr][p] = v[p];
-        r.ic[dr] = *reinterpret_cast<const uint32_t*>(ib + (fl + offc[dr]));
+        r.ic[dr] = *reinterpret_cast<const uint32_t*>(ir + oc);
       }
-      r.ge[dr] = gb[fl + offe[dr]];
-      r.ie[dr] = ib[fl + offe[dr]];
+      r.ge[dr] = *reinterpret_cast<const float*>(gr + oe4);
+      r.ie[dr] = ir[oe];
     }
     if (ld_co + 4 < g.CoutPad) {
       ld_co += 4;
@@ -233,19 +255,29 @@ __global__ __launch_bounds__(64 * NW, 2) void k_p4_bwd_data(const float* __restr
     }
   };
 
-  // One quarter turn's share of the nine tap sums for the lane's two pixels (Eq. 12 + the rotated
-  // tap positions of Eq. 8): Delta_s on the neighbourhood, added where R_s puts each base tap.
-  auto build_slice = [&](const Raw<PX>& r, int s, int rs, float (&a)[9][PX]) {
-    float d[3][PX + 2];
+  // What the four quarter turns of a K-step share: the neighbour lanes' edge values and the idx words with the bytes of
+  // invalid positions forced to 0xff (pinned: formed once per K-step, not once per quarter turn).
+  struct Pre { float gl[3], gr[3]; uint32_t iwc[3], iwe[3]; };
+  auto prepare = [&](const Raw<PX>& r, Pre& p) {
 #pragma unroll
     for (int dr = 0; dr < 3; ++dr) {
       const Edges<PX> e = edges_of(r, dr);
-      const uint32_t iwc = r.ic[dr] | invc[dr] | r.finv | (PX == 2 ? 0xffff0000u : 0u);
-      const uint32_t iwe = e.iwe | inve[dr] | r.finv;
-      d[dr][0] = ((iwe & 0xffu) == (uint32_t)rs) ? e.gl : 0.f;
-      d[dr][PX + 1] = (((iwe >> 8) & 0xffu) == (uint32_t)rs) ? e.gr : 0.f;
+      p.gl[dr] = e.gl; p.gr[dr] = e.gr;
+      p.iwc[dr] = r.ic[dr] | invc[dr] | r.finv | (PX == 2 ? 0xffff0000u : 0u);
+      p.iwe[dr] = e.iwe | inve[dr] | r.finv;
+      asm volatile("" : "+v"(p.gl[dr]), "+v"(p.gr[dr]), "+v"(p.iwc[dr]), "+v"(p.iwe[dr]));
+    }
+  };
+  // One quarter turn's share of the nine tap sums for the lane's pixels (Eq. 12 + the rotated
+  // tap positions of Eq. 8): Delta_s on the neighbourhood, added where R_s puts each base tap.
+  auto build_slice = [&](const Raw<PX>& r, const Pre& p, int s, int rs, float (&a)[9][PX]) {
+    float d[3][PX + 2];
 #pragma unroll
-      for (int p = 0; p < PX; ++p) d[dr][1 + p] = (((iwc >> (8 * p)) & 0xffu) == (uint32_t)rs) ? r.gc[dr][p] : 0.f;
+    for (int dr = 0; dr < 3; ++dr) {
+      d[dr][0] = ((p.iwe[dr] & 0xffu) == (uint32_t)rs) ? p.gl[dr] : 0.f;
+      d[dr][PX + 1] = (((p.iwe[dr] >> 8) & 0xffu) == (uint32_t)rs) ? p.gr[dr] : 0.f;
+#pragma unroll
+      for (int q = 0; q < PX; ++q) d[dr][1 + q] = (((p.iwc[dr] >> (8 * q)) & 0xffu) == (uint32_t)rs) ? r.gc[dr][q] : 0.f;
     }
 #pragma unroll
     for (int u = 0; u < 9; ++u)
@@ -329,7 +361,9 @@ __global__ __launch_bounds__(64 * NW, 2) void k_p4_bwd_data(const float* __restr
     // LUT: PX blocks of the next K-step's sums per tap, their table rows read one tap ahead
     LutVals lv;
     LutRow lrow[PX];
+    Pre pre;
     if (LUT) lut_prepare(raw_use, bd_q, lv);
+    else prepare(raw_use, pre);
 #pragma unroll
     for (int u = 0; u < 9; ++u) {
       if (u < 8) bw[(u + 1) & 1] = *reinterpret_cast<const f4*>(wl + (ks * 4) * WR + (u + 1) * CIG);
@@ -353,7 +387,7 @@ __global__ __launch_bounds__(64 * NW, 2) void k_p4_bwd_data(const float* __restr
 #pragma unroll
           for (int t = 0; t < 9; ++t) asm volatile("" : "+v"(a_nxt[t][(u * PX + i) % (3 * PX) / 3]));
       } else if ((u & 1) == 0 && u < 8) {
-        build_slice(raw_use, u / 2, rotb[u / 2], a_nxt);
+        build_slice(raw_use, pre, u / 2, rotb[u / 2], a_nxt);
       }
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -370,8 +404,10 @@ __global__ __launch_bounds__(64 * NW, 2) void k_p4_bwd_data(const float* __restr
       __builtin_amdgcn_sched_barrier(0);      // one block's rows at a time (all at once would spill)
     }
   } else {
+    Pre pre;
+    prepare(rawB, pre);
 #pragma unroll
-    for (int s = 0; s < 4; ++s) build_slice(rawB, s, rotb[s], aA);
+    for (int s = 0; s < 4; ++s) build_slice(rawB, pre, s, rotb[s], aA);
   }
   raw_load(rawA);
 #pragma unroll
@@ -786,6 +822,8 @@ bool p4_bwd_data_supported(const rotconv_plan* p) {
   const rotconv_desc& d = p->d;
   if (d.k != 3 || d.stride != 1 || d.pad != 1) return false;   // bf16 plans run these kernels on widened copies
   if (d.W & 1) return false;
+  // the kernels address one image of the pooled gradient with 32-bit byte offsets
+  if ((size_t)d.Cout * p->ng * d.H * d.W >= ((size_t)1 << 30)) return false;
   return p4_fwd_pool_mode(p) != kOutUnpooled;  // every bank inside one pool group
 }
 

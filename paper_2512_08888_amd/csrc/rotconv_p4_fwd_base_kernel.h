@@ -94,11 +94,16 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd_base(const float* __r
   const float* wsrc = wt + ((size_t)cb * g.CinPad) * 144;
   constexpr int WPT = (CHF / 4 + NT - 1) / NT;   // float4 per thread and chunk when streaming
   f4 wreg[STREAM ? WPT : 1];
+  // a staging load = wave-uniform base (filter block, chunk, slot: scalar arithmetic) + the thread's 32-bit byte offset
+  const uint32_t tid16 = (uint32_t)tid * 16u;
   auto wload = [&](int c) {
+    c = __builtin_amdgcn_readfirstlane(c);
+    asm volatile("" : "+s"(c));      // opaque: no per-thread 64-bit addresses kept (and spilled) for a known chunk
 #pragma unroll
     for (int k = 0; k < WPT; ++k) {
       const int e = tid + k * NT;
-      if (e < CHF / 4) wreg[k] = reinterpret_cast<const f4*>(wsrc + (size_t)c * CHF)[e];
+      const char* wk = reinterpret_cast<const char*>(wsrc + (size_t)c * CHF + (size_t)k * NT * 4);
+      if (e < CHF / 4) wreg[k] = *reinterpret_cast<const f4*>(wk + tid16);
     }
   };
   auto wstore = [&](int buf) {
@@ -192,7 +197,9 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd_base(const float* __r
     auto chunk = [&](int c, bool first) {
       const bool last = c + 1 == nchunk;
       const uint32_t rp = last ? rp_nxt : rp_cur;
-      const int kn = (last ? 0 : c + 1) * KC;
+      int kn = (last ? 0 : c + 1) * KC;
+      if (KC > 1) asm volatile("" : "+s"(kn));   // opaque: the per-K-step offsets are formed where they are used (a
+                                                 // precomputed set per chunk position would be spilled)
       if (STREAM) wload(last ? 0 : c + 1);
       const float* wc = STREAM ? wl_lane + (seq & 1) * CHF : wl_lane + (size_t)c * CHF;
       float bw[2][9];
