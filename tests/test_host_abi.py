@@ -232,6 +232,10 @@ def test_kernel_family_selection():
     ws1 = rc.Plan(1, 256, 32, 32, 64, k=3, R=4, options=dict(fwd_csplit=1)).workspace_bytes
     ws8 = rc.Plan(1, 256, 32, 32, 64, k=3, R=4, options=dict(fwd_csplit=8)).workspace_bytes
     assert ws8 >= ws1 >= 8 * 64 * 4 * 32 * 32 * 4      # eight parts of N * Cout * R * H * W floats fit either way
+    # the matrix-core input gradient addresses an image of the pooled gradient with 32-bit byte offsets: 2^30 elements and
+    # more per image go to the general kernel
+    assert names(rc.Plan(1, 8, 4096, 4096, 63, k=3, R=1))[1] == "mfma_p4"
+    assert names(rc.Plan(1, 8, 4096, 4096, 64, k=3, R=1))[1] == "generic"
     # a non-zero reserved field is refused
     import ctypes
     bad = rc.PlanOptions()
