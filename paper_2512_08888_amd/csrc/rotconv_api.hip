@@ -367,8 +367,11 @@ static int f32_rotconv_fwd(const rotconv_plan* plan, const void* x, const void* 
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int cs = p->fwd_csplit[0];
   if (p->fast[0] && aligned(x, 8) && aligned(ws, cs > 1 ? 256 : 16) && aligned(y, 16)) {
-    float* wt = static_cast<float*>(ws);
-    launch_p4_pack_fwd(p, static_cast<const float*>(w), wt, st);
+    const float* wt = static_cast<const float*>(w);      // the kernel takes w itself, or the bank packed into ws
+    if (!p4_fwd_raw_weights(p, 1, cs)) {
+      launch_p4_pack_fwd(p, static_cast<const float*>(w), static_cast<float*>(ws), st);
+      wt = static_cast<const float*>(ws);
+    }
     if (cs > 1) {     // small map, deep input: the channels are split over workgroups
       float* part = reinterpret_cast<float*>(static_cast<char*>(ws) + fwd_pack_region(p));
       launch_p4_fwd(p, kOutUnpooled, static_cast<const float*>(x), wt, part, nullptr, st, 1, cs);
@@ -489,10 +492,15 @@ static int f32_rotconv_pool_fwd(const rotconv_plan* plan, const void* x, const v
     const int mode = p4_fwd_pool_mode(p);
     const size_t hw = (size_t)p->d.H * p->d.W;
     const int cs = p->fwd_csplit[1];
+    // the bank the kernel multiplies with: w itself where the kernel can re-lay its block on its own, else packed into ws
+    auto bank = [&](int nq_, int cs_) -> const float* {
+      if (p4_fwd_raw_weights(p, nq_, cs_)) return static_cast<const float*>(w);
+      launch_p4_pack_fwd(p, static_cast<const float*>(w), wt, st, nq_);
+      return wt;
+    };
     if (cs > 1) {     // small map, deep input: the channels are split over workgroups, summed and pooled afterwards
       float* part = reinterpret_cast<float*>(extra);
-      launch_p4_pack_fwd(p, static_cast<const float*>(w), wt, st);
-      launch_p4_fwd(p, kOutUnpooled, static_cast<const float*>(x), wt, part, nullptr, st, 1, cs);
+      launch_p4_fwd(p, kOutUnpooled, static_cast<const float*>(x), bank(1, cs), part, nullptr, st, 1, cs);
       launch_p4_sum_pool(p, part, cs, static_cast<float*>(ypool), idx, st);
       return finish();
     }
@@ -502,19 +510,19 @@ static int f32_rotconv_pool_fwd(const rotconv_plan* plan, const void* x, const v
       return finish();
     }
     const int nq = mode == kOutPartial ? p4_fwd_fold(p) : 1;
-    launch_p4_pack_fwd(p, static_cast<const float*>(w), wt, st, nq);
+    const float* wb = bank(nq, 1);
     if (mode == kOutPooled) {
-      launch_p4_fwd(p, mode, static_cast<const float*>(x), wt, static_cast<float*>(ypool), idx, st);
+      launch_p4_fwd(p, mode, static_cast<const float*>(x), wb, static_cast<float*>(ypool), idx, st);
     } else if (nq > 1) {     // the pool group spans all banks: pooled across them inside the kernel
-      launch_p4_fwd(p, kOutPooled, static_cast<const float*>(x), wt, static_cast<float*>(ypool), idx, st, nq);
+      launch_p4_fwd(p, kOutPooled, static_cast<const float*>(x), wb, static_cast<float*>(ypool), idx, st, nq);
     } else if (mode == kOutPartial) {
       float* pv = reinterpret_cast<float*>(extra);
       uint8_t* pi = reinterpret_cast<uint8_t*>(extra + align256((size_t)p->host.Q * p->d.N * p->d.Cout * hw * 4));
-      launch_p4_fwd(p, mode, static_cast<const float*>(x), wt, pv, pi, st);
+      launch_p4_fwd(p, mode, static_cast<const float*>(x), wb, pv, pi, st);
       launch_p4_combine(p, pv, pi, static_cast<float*>(ypool), idx, st);
     } else {
       float* yu = reinterpret_cast<float*>(extra);
-      launch_p4_fwd(p, mode, static_cast<const float*>(x), wt, yu, nullptr, st);
+      launch_p4_fwd(p, mode, static_cast<const float*>(x), wb, yu, nullptr, st);
       launch_maxpool_fwd(p, yu, static_cast<float*>(ypool), idx, st, true);
     }
     return finish();

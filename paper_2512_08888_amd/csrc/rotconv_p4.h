@@ -23,6 +23,7 @@ struct P4Geom {
   int csplit;    // parts the channel contraction is split into (1: none); a part is an unpooled fp32 map
   int cper;      // 32-channel chunks per part (all of them without a split)
   int cost;      // modelled cost of the launch (host side only)
+  int raw_w;     // the weight argument is the caller's w[Cout][Cin][9] itself (see p4_fwd_raw_weights)
   int seg_xorg[4];  // first product column of a segment's wave chain
   int seg_lo[4], seg_hi[4];  // output pixels [lo, hi) the segment stores (multiples of 8, or W)
 };
@@ -41,6 +42,10 @@ int p4_fwd_pool_mode(const rotconv_plan* p);
 int p4_fwd_fold(const rotconv_plan* p);   // banks a wave can fold into its columns for the pooled forward (1: none)
 // nq = 1: one bank per wave; nq = p4_fwd_fold(p) > 1 (with kOutPooled): folded blocks, pooled across banks in-kernel
 void launch_p4_pack_fwd(const rotconv_plan* p, const float* w, float* wt, hipStream_t st, int nq = 1);
+// A plan whose one bank is its base bank (exact quarter turns, or a single orientation) and whose filter block stays in
+// LDS: the forward kernel re-lays its block out of the caller's weights itself, launch_p4_fwd takes w in place of the
+// packed bank and launch_p4_pack_fwd is not called (one small dependent launch less per call).
+bool p4_fwd_raw_weights(const rotconv_plan* p, int nq = 1, int csplit = 1);
 void launch_p4_fwd(const rotconv_plan* p, int out_mode, const float* x, const float* wt, float* out_val,
                    uint8_t* out_idx, hipStream_t st, int nq = 1, int csplit = 1);
 void launch_p4_combine(const rotconv_plan* p, const float* pv, const uint8_t* pi, float* ypool, uint8_t* idx,

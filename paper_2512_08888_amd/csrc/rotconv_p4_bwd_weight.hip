@@ -1315,11 +1315,23 @@ __global__ __launch_bounds__(64 * NW) void k_p4_bwd_weight_bf16_lut_shared(const
   }
 }
 
+// Where the summed dF goes.  RELAYOUT: the transposed expansion is the identity (the table variant, whose dF already is
+// the base banks' gradient, or a plan whose one bank is its base bank): element ((b*9 + u) * CoutPad + co) * CinPad + ci of
+// dF is dw[b][co][ci][u], written directly -- one launch instead of two, the same sums in the same order.
+struct DwLayout { int Cout, Cin, CoutPad, CinPad; };
+template <bool RELAYOUT>
+__device__ __forceinline__ void put_sum(float* __restrict__ out, int e, float v, const DwLayout& L) {
+  if (!RELAYOUT) { out[e] = v; return; }
+  const int ci = e % L.CinPad, co = (e / L.CinPad) % L.CoutPad, bu = e / (L.CinPad * L.CoutPad);
+  if (ci < L.Cin && co < L.Cout) out[(((size_t)(bu / 9) * L.Cout + co) * L.Cin + ci) * 9 + bu % 9] = v;
+}
+
 // Stage 1: sum the splits.  A block covers 32 consecutive elements x 8 interleaved split groups;
 // each thread adds its splits in ascending order, the groups are combined in a fixed tree, so
 // the result does not depend on scheduling.  out[e] = sum_split partial[split][e].
+template <bool RELAYOUT>
 __global__ __launch_bounds__(256) void k_p4_sum_splits(const float* __restrict__ partial, float* __restrict__ out,
-                                                       int n_elem, int splits) {
+                                                       int n_elem, int splits, DwLayout L) {
   __shared__ float red[8][32];
   const int e = blockIdx.x * 32 + (threadIdx.x % 32);
   const int grp = threadIdx.x / 32;
@@ -1330,20 +1342,26 @@ __global__ __launch_bounds__(256) void k_p4_sum_splits(const float* __restrict__
   __syncthreads();
   if (grp == 0 && e < n_elem) {
     const int l = threadIdx.x;
-    out[e] = ((red[0][l] + red[1][l]) + (red[2][l] + red[3][l])) + ((red[4][l] + red[5][l]) + (red[6][l] + red[7][l]));
+    put_sum<RELAYOUT>(out, e, ((red[0][l] + red[1][l]) + (red[2][l] + red[3][l])) + ((red[4][l] + red[5][l]) + (red[6][l] + red[7][l])), L);
   }
 }
 
 // The same sum for large images (many elements, few splits): one thread per four elements adds the splits in
 // ascending order, every access a full 16-byte lane access.
+template <bool RELAYOUT>
 __global__ __launch_bounds__(256) void k_p4_sum_splits_wide(const float* __restrict__ partial, float* __restrict__ out,
-                                                            int n4, int splits) {
+                                                            int n4, int splits, DwLayout L) {
   const int e = blockIdx.x * 256 + threadIdx.x;
   if (e >= n4) return;
   const f4* src = reinterpret_cast<const f4*>(partial);
   f4 s = src[e];
   for (int sp = 1; sp < splits; ++sp) s += src[(size_t)sp * n4 + e];
-  reinterpret_cast<f4*>(out)[e] = s;
+  if (!RELAYOUT) {
+    reinterpret_cast<f4*>(out)[e] = s;
+  } else {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) put_sum<true>(out, 4 * e + i, s[i], L);
+  }
 }
 
 // Stage 2: the transposed first-quadrant expansion (Eq. 16 / adjoint of Eq. 17):
@@ -1431,16 +1449,33 @@ size_t p4_bwd_weight_ws_floats(const rotconv_plan* p) {
   return need;
 }
 
-// partial sums of the splits -> dF (fixed order) -> dw through the transposed expansion
+// partial sums of the splits -> dF (fixed order) -> dw through the transposed expansion; one launch where that
+// expansion is the identity
+static bool dw_is_relayout(const rotconv_plan* p, const P4BwdWGeom& g) {
+  if (g.lut) return true;
+  if (g.Q != 1 || p->B != 1) return false;
+  for (int u = 0; u < 9; ++u)
+    for (int z = 0; z < kMaxNnz; ++z) {
+      const int src = p->host.fq_src[u * kMaxNnz + z];
+      if (z == 0 ? (src != u || p->host.fq_coef[u * kMaxNnz] != 1.0f) : src >= 0) return false;
+    }
+  return true;
+}
 static void finish_dw(const rotconv_plan* p, const P4BwdWGeom& g, float* partial, float* dw, hipStream_t st) {
   const int n_elem = g.Q * 9 * g.CoutPad * g.CinPad;      // a multiple of 16
+  const DwLayout L{g.Cout, g.Cin, g.CoutPad, g.CinPad};
+  const bool relayout = g.splits > 1 && dw_is_relayout(p, g);
   float* dF = partial;                                     // a single split is the sum
   if (g.splits > 1) {
-    dF = partial + (size_t)g.splits * n_elem;
-    if (n_elem >= (1 << 18))
-      hipLaunchKernelGGL(k_p4_sum_splits_wide, dim3((n_elem / 4 + 255) / 256), dim3(256), 0, st, partial, dF, n_elem / 4, g.splits);
-    else
-      hipLaunchKernelGGL(k_p4_sum_splits, dim3((n_elem + 31) / 32), dim3(256), 0, st, partial, dF, n_elem, g.splits);
+    dF = relayout ? dw : partial + (size_t)g.splits * n_elem;
+    if (n_elem >= (1 << 18)) {
+      if (relayout) hipLaunchKernelGGL(k_p4_sum_splits_wide<true>, dim3((n_elem / 4 + 255) / 256), dim3(256), 0, st, partial, dF, n_elem / 4, g.splits, L);
+      else hipLaunchKernelGGL(k_p4_sum_splits_wide<false>, dim3((n_elem / 4 + 255) / 256), dim3(256), 0, st, partial, dF, n_elem / 4, g.splits, L);
+    } else {
+      if (relayout) hipLaunchKernelGGL(k_p4_sum_splits<true>, dim3((n_elem + 31) / 32), dim3(256), 0, st, partial, dF, n_elem, g.splits, L);
+      else hipLaunchKernelGGL(k_p4_sum_splits<false>, dim3((n_elem + 31) / 32), dim3(256), 0, st, partial, dF, n_elem, g.splits, L);
+    }
+    if (relayout) return;
   }
   const int total = p->B * g.Cout * g.Cin;
   hipLaunchKernelGGL(k_p4_reduce_w, dim3((total + 255) / 256), dim3(256), 0, st, dF, dw, p->dev.fqt_ptr,

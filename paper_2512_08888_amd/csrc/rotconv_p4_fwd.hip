@@ -103,6 +103,20 @@ __global__ __launch_bounds__(64 * NWX * NWY) void k_p4_fwd(const float* __restri
   if (STREAM) {
     wload(0);
     wstore(0);
+  } else if (g.raw_w) {
+    // wt is the caller's w[Cout][Cin][9]: the block's sixteen filters at one (channel, tap) are sixteen loads 9 Cin
+    // floats apart (consecutive lanes: consecutive addresses) and one 64-byte row of the block; zeros beyond Cout / Cin
+    const int pairs = (c_hi - c_lo) * (CHF / 16), e_lo = c_lo * (CHF / 16), e_end = g.Cin * 9;
+    const float* wrow = wt + (size_t)cb * 16 * e_end;
+    for (int i = tid; i < pairs; i += NT) {
+      const int e = e_lo + i;                    // ci * 9 + u
+      f4 v[4];
+#pragma unroll
+      for (int f = 0; f < 16; ++f)
+        v[f / 4][f % 4] = (e < e_end && cb * 16 + f < g.Cout) ? wrow[(size_t)f * e_end + e] : 0.f;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) reinterpret_cast<f4*>(Wl)[i * 4 + k] = v[k];
+    }
   } else {
     const f4* src = reinterpret_cast<const f4*>(wsrc + (size_t)c_lo * CHF);
     f4* dst = reinterpret_cast<f4*>(Wl);
@@ -761,13 +775,26 @@ void launch_p4_pack_fwd(const rotconv_plan* p, const float* w, float* wt, hipStr
                      p->host.Q, CB, CinPad, p->d.Cin, p->d.Cout, p->d.dtype == ROTCONV_BF16 ? 1 : 0, nq);
 }
 
+bool p4_fwd_raw_weights(const rotconv_plan* p, int nq, int csplit) {
+  if (p->d.dtype != ROTCONV_F32 || p->host.Q != 1 || p->B != 1 || nq > 1) return false;
+  if (csplit < 2 && needs_stream(p->d.Cin)) return false;
+  for (int u = 0; u < 9; ++u)
+    for (int z = 0; z < kMaxNnz; ++z) {
+      const int src = p->host.fq_src[u * kMaxNnz + z];
+      if (z == 0 ? (src != u || p->host.fq_coef[u * kMaxNnz] != 1.0f) : src >= 0) return false;
+    }
+  return true;
+}
+
 void launch_p4_fwd(const rotconv_plan* p, int out_mode, const float* x, const float* wt, float* out_val,
                    uint8_t* out_idx, hipStream_t st, int nq, int csplit) {
   P4Geom gs[4];
   const int ng = p4_fwd_geoms(p, out_mode, gs, 4, csplit, nq);
   const bool stream = csplit < 2 && needs_stream(p->d.Cin);
+  const int raw = p4_fwd_raw_weights(p, nq, csplit) ? 1 : 0;
   for (int i = 0; i < ng; ++i) {
     P4Geom& g = gs[i];
+    g.raw_w = raw;
     const bool fastw = (p->d.W & 7) == 0 && g.inside;   // no lane reaches beyond the row: no masks, vector stores
     switch (g.nwx) {
       case 1: launch_t<1, 8>(g, fastw, stream, x, wt, p->dev.rot_of, out_val, out_idx, st); break;
