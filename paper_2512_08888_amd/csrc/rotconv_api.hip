@@ -558,10 +558,14 @@ static int f32_rotconv_pool_bwd_data(const rotconv_plan* plan, const void* gpool
     return rotconv_pool_bwd_data(p->avg_child, gpool, idx0, wavg, dx, c + L.child, p->avg_child->ws_bytes, stream);
   }
   if (p->fast[1] && aligned(gpool, 8) && aligned(idx, 2) && aligned(dx, 16) && aligned(ws, 16)) {
-    float* wd = static_cast<float*>(ws);
-    launch_p4_pack_bwd(p, static_cast<const float*>(w), wd, st);
+    const bool raw = p4_bwd_data_raw_weights(p) && aligned(w, 16);   // the kernel takes w itself, 16 bytes at a time
+    const float* wd = static_cast<const float*>(w);
+    if (!raw) {                                                       // ... or the banks packed into ws
+      launch_p4_pack_bwd(p, static_cast<const float*>(w), static_cast<float*>(ws), st);
+      wd = static_cast<const float*>(ws);
+    }
     float* part = reinterpret_cast<float*>(static_cast<char*>(ws) + align256(p4_bwd_data_pack_floats(p) * sizeof(float)));
-    launch_p4_bwd_data(p, static_cast<const float*>(gpool), idx, wd, static_cast<float*>(dx), part, st);
+    launch_p4_bwd_data(p, static_cast<const float*>(gpool), idx, wd, static_cast<float*>(dx), part, st, raw);
     return finish();
   }
   if (p->gs) {

@@ -89,13 +89,15 @@ bool p4_bwd_lut_choice(const rotconv_plan* p);   // whether the fp32 gradients s
 bool p4_bwd_lut(const rotconv_plan* p);          // the plan's setting (contraction over the base bank)
 bool p4_bwd_lut16_choice(const rotconv_plan* p); // the same question for the kernels that take bf16 tensors
 bool p4_bwd_data_supported(const rotconv_plan* p);
+// launch_p4_bwd_data takes the caller's w in place of the packed banks and launch_p4_pack_bwd is not called
+bool p4_bwd_data_raw_weights(const rotconv_plan* p);
 P4BwdGeom p4_bwd_data_geom(const rotconv_plan* p);
 size_t p4_bwd_data_pack_floats(const rotconv_plan* p);
 void launch_p4_pack_bwd(const rotconv_plan* p, const float* w, float* wd, hipStream_t st);
 // scratch behind the packed bank: the fp32 partial dX of a bank split (0 floats without one)
 size_t p4_bwd_data_part_floats(const rotconv_plan* p);
 void launch_p4_bwd_data(const rotconv_plan* p, const float* gpool, const uint8_t* idx, const float* wd, float* dx,
-                        float* part, hipStream_t st);
+                        float* part, hipStream_t st, bool raw_w = false);
 
 // input gradient on bfloat16 tensors (bf16 matrix cores): the forward kernel's row segments and bands with
 // the roles of filters and channels swapped

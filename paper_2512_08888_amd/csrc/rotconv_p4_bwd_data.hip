@@ -87,7 +87,10 @@ __device__ __forceinline__ Edges<PX> edges_of(const Raw<PX>& r, int dr) {
 // G * lut[offset][idx][u'] (the rotated banks' coefficients, looked up per value): the routed gradients of all banks
 // are summed into the base taps before the contraction, which then runs over the base bank alone, one
 // conv-equivalent of matrix work instead of Q, and the neighbourhood is loaded once instead of once per bank.
-template <int PX, bool LUT, int NW>
+// RAW: wd is the caller's w[Cout][Cin][9] itself (a plan whose one bank is its base bank, Cin a multiple of 64, Cout of
+// 16): a quarter chunk is four filters' 576 contiguous floats of this channel group, loaded 16 bytes per thread as before
+// and put into the [tap][channel position] order of the LDS rows by four 4-byte writes at offsets computed once.
+template <int PX, bool LUT, int NW, bool RAW = false>
 __global__ __launch_bounds__(64 * NW, 2) void k_p4_bwd_data(const float* __restrict__ gpool, const uint8_t* __restrict__ idx,
                                                     const float* __restrict__ wd,
                                                     const int32_t* __restrict__ rot_of, const float* __restrict__ lut,
@@ -139,15 +142,28 @@ __global__ __launch_bounds__(64 * NW, 2) void k_p4_bwd_data(const float* __restr
   // A thread's slots sit at the same byte offsets inside every quarter chunk: computed once, so that a load is a
   // wave-uniform base (chunk, quarter: scalar arithmetic) plus a 32-bit lane offset and costs no vector instruction.
   uint32_t woff[WREG];
+  uint32_t wlds[RAW ? WREG : 1][4];      // RAW: LDS byte offsets of a slot's four values inside a quarter's four rows
+  const int rowf = g.Cin * 9;            // RAW: floats per filter in w
 #pragma unroll
   for (int k = 0; k < WREG; ++k) {
     const int e = min(tid + k * NT, Q4 - 1);
-    const int c4 = e % (CIG / 4), u = (e / (CIG / 4)) % 9, r = e / (9 * (CIG / 4));
-    woff[k] = (uint32_t)(((r * 9 + u) * g.CinPad + c4 * 4) * (int)sizeof(float));
+    if (RAW) {
+      const int r = e / (9 * (CIG / 4)), j = e % (9 * (CIG / 4));     // filter of the quarter, 16-byte piece of its row
+      woff[k] = (uint32_t)((r * rowf + 4 * j) * (int)sizeof(float));
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int m = 4 * j + i, cl = m / 9, u = m % 9;               // channel of the group, tap
+        wlds[k][i] = (uint32_t)((r * WR + u * CIG + (cl % 16) * 4 + cl / 16) * (int)sizeof(float));
+      }
+    } else {
+      const int c4 = e % (CIG / 4), u = (e / (CIG / 4)) % 9, r = e / (9 * (CIG / 4));
+      woff[k] = (uint32_t)(((r * 9 + u) * g.CinPad + c4 * 4) * (int)sizeof(float));
+    }
   }
-  const float* wgrp = wd + cig * CIG;
+  const float* wgrp = RAW ? wd + cig * CIG * 9 : wd + cig * CIG;
   auto wload = [&](int cc, int part) {
-    const char* wq = reinterpret_cast<const char*>(wgrp + ((size_t)(cbase + cc) * CHUNK + part * 4) * 9 * g.CinPad);
+    const size_t row0 = (size_t)(cbase + cc) * CHUNK + part * 4;      // first filter row of the quarter
+    const char* wq = reinterpret_cast<const char*>(wgrp + (RAW ? row0 * rowf : row0 * 9 * g.CinPad));
 #pragma unroll
     for (int k = 0; k < WREG; ++k) {
       const int e = tid + k * NT;
@@ -160,8 +176,14 @@ __global__ __launch_bounds__(64 * NW, 2) void k_p4_bwd_data(const float* __restr
     for (int k = 0; k < WREG; ++k) {
       const int e = tid + k * NT;
       if (e < Q4) {
-        const int c4 = e % (CIG / 4), u = (e / (CIG / 4)) % 9, r = part * 4 + e / (9 * (CIG / 4));
-        *reinterpret_cast<f4*>(dst + r * WR + u * CIG + c4 * 4) = wreg[k];
+        if (RAW) {
+          char* q4 = reinterpret_cast<char*>(dst + part * 4 * WR);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) *reinterpret_cast<float*>(q4 + wlds[k][i]) = wreg[k][i];
+        } else {
+          const int c4 = e % (CIG / 4), u = (e / (CIG / 4)) % 9, r = part * 4 + e / (9 * (CIG / 4));
+          *reinterpret_cast<f4*>(dst + r * WR + u * CIG + c4 * 4) = wreg[k];
+        }
       }
     }
   };
@@ -898,6 +920,20 @@ size_t p4_bwd_data_pack_floats(const rotconv_plan* p) {
   return (size_t)g.Q * g.CoutPad * 9 * g.CinPad;
 }
 
+// The input gradient reads the caller's w itself (no packed copy, one dependent launch less): the unshared per-bank
+// kernel of a plan whose one bank is its base bank, with whole 64-channel groups and whole 16-filter chunks.
+bool p4_bwd_data_raw_weights(const rotconv_plan* p) {
+  const P4BwdGeom g = p4_bwd_data_geom(p);
+  if (p->d.dtype != ROTCONV_F32 || g.lut || g.ncg > 1 || g.Q != 1 || p->B != 1) return false;
+  if (p->d.Cin % CIG || p->d.Cout % CHUNK) return false;
+  for (int u = 0; u < 9; ++u)
+    for (int z = 0; z < kMaxNnz; ++z) {
+      const int src = p->host.fq_src[u * kMaxNnz + z];
+      if (z == 0 ? (src != u || p->host.fq_coef[u * kMaxNnz] != 1.0f) : src >= 0) return false;
+    }
+  return true;
+}
+
 void launch_p4_pack_bwd(const rotconv_plan* p, const float* w, float* wd, hipStream_t st) {
   const P4BwdGeom g = p4_bwd_data_geom(p);
   if (g.ncg > 1) {
@@ -913,7 +949,7 @@ void launch_p4_pack_bwd(const rotconv_plan* p, const float* w, float* wd, hipStr
 }
 
 void launch_p4_bwd_data(const rotconv_plan* p, const float* gpool, const uint8_t* idx, const float* wd, float* dx_out,
-                        float* part, hipStream_t st) {
+                        float* part, hipStream_t st, bool raw_w) {
   const P4BwdGeom g = p4_bwd_data_geom(p);
   float* dx = g.ksplit > 1 ? part : dx_out;
   if (g.ncg > 1) {
@@ -945,9 +981,11 @@ void launch_p4_bwd_data(const rotconv_plan* p, const float* gpool, const uint8_t
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * g.nw), lds, st, gpool, idx, wd, p->dev.rot_of, p->dev.lut_bwd, dx, g);
   };
-  if (g.px == 4) go(k_p4_bwd_data<4, false, 4>);
+  const bool raw = raw_w && p4_bwd_data_raw_weights(p);      // wd is the caller's w
+  if (g.px == 4) { if (raw) go(k_p4_bwd_data<4, false, 4, true>); else go(k_p4_bwd_data<4, false, 4>); }
   else if (g.lut && g.nw == 4) go(k_p4_bwd_data<2, true, 4>);
   else if (g.lut) go(k_p4_bwd_data<2, true, 8>);
+  else if (raw) go(k_p4_bwd_data<2, false, 4, true>);
   else go(k_p4_bwd_data<2, false, 4>);
   if (g.ksplit > 1) {
     const size_t n_elem = (size_t)p->d.N * p->d.Cin * p->d.H * p->d.W;

@@ -87,6 +87,11 @@ TINY = [
     LC("t_csplit_r4", N=2, Cin=96, H=6, W=32, Cout=18, R=4, seed=51),
     LC("t_csplit_r8_g4", N=1, Cin=72, H=5, W=16, Cout=9, R=8, mode="bilinear", pool_group=4, seed=52),
     LC("t_csplit_r16", N=1, Cin=160, H=4, W=4, Cout=17, R=16, mode="bilinear", seed=53),
+    # whole 64-channel groups and 16-filter chunks, one bank: the input gradient reads w itself (no packed copy): four
+    # and two pixels per lane, a contraction shared out over workgroups, a single orientation
+    LC("t_raw_w_px4", N=1, Cin=64, H=6, W=68, Cout=16, R=4, seed=56),
+    LC("t_raw_w_px2", N=2, Cin=64, H=9, W=10, Cout=48, R=4, seed=57),
+    LC("t_raw_w_r1", N=1, Cin=64, H=5, W=36, Cout=32, R=1, seed=58),
 ]
 
 
